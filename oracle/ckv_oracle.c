@@ -1,0 +1,199 @@
+/*
+ * CollectiveKV decode-stage oracle: TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, fp64 CPU statement of what the decode stage of CollectiveKV computes
+ * (paper section 4.2 "In the decode stage", equations labelled "eq: Kc" and "eq: K",
+ * and the appendix "Discussion of the sharing mechanism" for the column order).
+ * It exists so that tests, the smoke check and the benchmark's cpu_baseline leg have
+ * something independent to compare the GPU library with.  Nothing in the product
+ * path may call it, and it shares no code, header or table with the HIP library.
+ *
+ * Data as the paper states the problem, one record per user, users back to back:
+ *   lengths[B]                 n of each user (history length), n >= 0
+ *   idx_k, idx_v  [T][H]       I_k, I_v: 0-based pool row of position t, head h;  T = sum(lengths)
+ *   user_k, user_v [T][H][d_u] K_u, V_u: the user-specific slices
+ *   pool_k, pool_v [H][P][pool_ld]   P_k, P_v: one pool per head, d_g valid columns per row
+ *   q   [B][H][Nq][d_a]        candidate queries, d_a = d_u + d_g
+ *   out [B][H][Nq][d_a]        fp64
+ * Stored values are fp32 (dtype 0) or bfloat16 bit patterns in uint16 (dtype 1).  Both
+ * widen to fp64 exactly; no intermediate is ever rounded below fp64.
+ *
+ * The paper fixes gather and concat but not the attention form; the two forms below are
+ * the ones the workloads name: softmax(scale * q.K^T) V and SiLU(scale * q.K^T) V / n,
+ * non-causal over the user's whole history.  A user with n = 0 gets out = 0.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+enum { ORACLE_SOFTMAX = 0, ORACLE_SILU_OVER_N = 1 };
+
+static double widen(const void *base, int64_t i, int dtype)
+{
+    if (dtype == ORACLE_F32)
+        return (double)((const float *)base)[i];
+    /* bfloat16 is the upper half of an IEEE binary32 */
+    uint32_t bits = (uint32_t)((const uint16_t *)base)[i] << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+static size_t elem_size(int dtype) { return dtype == ORACLE_F32 ? 4u : 2u; }
+
+/*
+ * Final K row (or V row) of one position and head, widened to fp64:
+ *   row[0 : d_u]     = user slice          (user-specific dimensions come first)
+ *   row[d_u : d_a]   = pool[h][index]      (collective part, gathered by the stored index)
+ * Section 4.2, eq. "eq: Kc" (gather) then eq. "eq: K" (concat).
+ */
+static void final_row(double *row, const void *user, const void *pool, const int32_t *idx,
+                      int64_t t, int h, int H, int d_u, int d_g, int P, int64_t pool_ld, int dtype)
+{
+    for (int c = 0; c < d_u; ++c)
+        row[c] = widen(user, (t * H + h) * (int64_t)d_u + c, dtype);
+    if (d_g > 0) {
+        int64_t r = idx[t * H + h];
+        for (int c = 0; c < d_g; ++c)
+            row[d_u + c] = widen(pool, ((int64_t)h * P + r) * pool_ld + c, dtype);
+    }
+}
+
+/*
+ * Attention outputs of the listed users.  users[] holds n_users user numbers (or NULL for
+ * all B users in order); rows of out that belong to other users are not touched.
+ * Returns 0, or -1 on a bad argument (index outside [0,P), negative length, unknown mode).
+ */
+int ckv_oracle_attend(int B, int H, int d_g, int d_u, int P, int Nq, int dtype, int mode,
+                      double scale, int64_t pool_ld,
+                      const int32_t *lengths, const int32_t *idx_k, const int32_t *idx_v,
+                      const void *user_k, const void *user_v,
+                      const void *pool_k, const void *pool_v, const void *q,
+                      double *out, const int32_t *users, int n_users)
+{
+    const int d_a = d_u + d_g;
+    if (B < 0 || H < 1 || d_g < 0 || d_u < 0 || d_a < 1 || Nq < 1 || pool_ld < d_g)
+        return -1;
+    if (mode != ORACLE_SOFTMAX && mode != ORACLE_SILU_OVER_N)
+        return -1;
+    int64_t *offset = (int64_t *)malloc(sizeof(int64_t) * (size_t)(B + 1));
+    offset[0] = 0;
+    for (int b = 0; b < B; ++b) {
+        if (lengths[b] < 0) { free(offset); return -1; }
+        offset[b + 1] = offset[b] + lengths[b];
+    }
+    if (d_g > 0)
+        for (int64_t i = 0; i < offset[B] * H; ++i)
+            if (idx_k[i] < 0 || idx_k[i] >= P || idx_v[i] < 0 || idx_v[i] >= P) { free(offset); return -1; }
+    if (!users) n_users = B;
+
+    int bad = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int u = 0; u < n_users; ++u) {
+        for (int h = 0; h < H; ++h) {
+            const int b = users ? users[u] : u;
+            if (b < 0 || b >= B) { bad = 1; continue; }
+            const int n = lengths[b];
+            const int64_t o = offset[b];
+            double *K = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1) * d_a);
+            double *V = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1) * d_a);
+            double *w = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
+            double *qv = (double *)malloc(sizeof(double) * (size_t)d_a);
+            /* gather + concat: the user's final K and V, n x d_a */
+            for (int i = 0; i < n; ++i) {
+                final_row(K + (int64_t)i * d_a, user_k, pool_k, idx_k, o + i, h, H, d_u, d_g, P, pool_ld, dtype);
+                final_row(V + (int64_t)i * d_a, user_v, pool_v, idx_v, o + i, h, H, d_u, d_g, P, pool_ld, dtype);
+            }
+            for (int j = 0; j < Nq; ++j) {
+                const int64_t qo = (((int64_t)b * H + h) * Nq + j) * d_a;
+                for (int c = 0; c < d_a; ++c) qv[c] = widen(q, qo + c, dtype);
+                /* scores s_i = scale * q . K_i */
+                for (int i = 0; i < n; ++i) {
+                    double s = 0.0;
+                    for (int c = 0; c < d_a; ++c) s += qv[c] * K[(int64_t)i * d_a + c];
+                    w[i] = scale * s;
+                }
+                /* weights */
+                if (mode == ORACLE_SOFTMAX) {
+                    double m = -INFINITY, z = 0.0;
+                    for (int i = 0; i < n; ++i) if (w[i] > m) m = w[i];
+                    for (int i = 0; i < n; ++i) { w[i] = exp(w[i] - m); z += w[i]; }
+                    for (int i = 0; i < n; ++i) w[i] /= z;
+                } else {
+                    for (int i = 0; i < n; ++i) w[i] = w[i] / (1.0 + exp(-w[i])) / (double)n;
+                }
+                /* out_j = sum_i w_i V_i */
+                for (int c = 0; c < d_a; ++c) {
+                    double a = 0.0;
+                    for (int i = 0; i < n; ++i) a += w[i] * V[(int64_t)i * d_a + c];
+                    out[qo + c] = a;
+                }
+            }
+            free(K); free(V); free(w); free(qv);
+        }
+    }
+    free(offset);
+    return bad ? -1 : 0;
+}
+
+/*
+ * The final K and V rows themselves, in the storage dtype, [T][H][d_a]: a byte-for-byte
+ * copy of the user slice followed by the gathered pool row (no arithmetic).
+ */
+int ckv_oracle_reconstruct(int H, int d_g, int d_u, int P, int dtype, int64_t pool_ld, int64_t T,
+                           const int32_t *idx_k, const int32_t *idx_v,
+                           const void *user_k, const void *user_v,
+                           const void *pool_k, const void *pool_v,
+                           void *k_full, void *v_full)
+{
+    const size_t e = elem_size(dtype);
+    const int d_a = d_u + d_g;
+    for (int64_t t = 0; t < T; ++t)
+        for (int h = 0; h < H; ++h) {
+            const int64_t ph = t * H + h;
+            if (d_g > 0 && (idx_k[ph] < 0 || idx_k[ph] >= P || idx_v[ph] < 0 || idx_v[ph] >= P))
+                return -1;
+            char *kd = (char *)k_full + (size_t)ph * d_a * e;
+            char *vd = (char *)v_full + (size_t)ph * d_a * e;
+            memcpy(kd, (const char *)user_k + (size_t)ph * d_u * e, (size_t)d_u * e);
+            memcpy(vd, (const char *)user_v + (size_t)ph * d_u * e, (size_t)d_u * e);
+            if (d_g > 0) {
+                memcpy(kd + (size_t)d_u * e,
+                       (const char *)pool_k + (((size_t)h * P + idx_k[ph]) * pool_ld) * e, (size_t)d_g * e);
+                memcpy(vd + (size_t)d_u * e,
+                       (const char *)pool_v + (((size_t)h * P + idx_v[ph]) * pool_ld) * e, (size_t)d_g * e);
+            }
+        }
+    return 0;
+}
+
+/*
+ * Cache-size accounting (section 5.1 "Metrics": the CollectiveKV cache is the global KV
+ * indices plus the user-specific KV; section 4.4 counts one index as one element:
+ * the load is s*d_u + s).  Counts are per K and V together, over T positions and H heads.
+ *   stored_elems = T*H*2*(d_u + 1)       full_elems = T*H*2*d_a
+ *   stored_bytes = T*H*2*(d_u*e + index_bytes)   full_bytes = T*H*2*d_a*e
+ */
+void ckv_oracle_cache_size(int64_t T, int H, int d_g, int d_u, int dtype, int index_bytes,
+                           int64_t *stored_elems, int64_t *full_elems,
+                           int64_t *stored_bytes, int64_t *full_bytes)
+{
+    const int64_t e = (int64_t)elem_size(dtype);
+    const int64_t ph = T * H;
+    *stored_elems = ph * 2 * ((int64_t)d_u + 1);
+    *full_elems = ph * 2 * ((int64_t)d_u + d_g);
+    *stored_bytes = ph * 2 * ((int64_t)d_u * e + index_bytes);
+    *full_bytes = ph * 2 * ((int64_t)d_u + d_g) * e;
+}
+
+int ckv_oracle_threads(void)
+{
+#ifdef _OPENMP
+    extern int omp_get_max_threads(void);
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

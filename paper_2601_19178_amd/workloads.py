@@ -1,0 +1,141 @@
+"""Seeded synthetic workloads (inputs only; none of the method's arithmetic lives here).
+
+The five workloads stand in for the recommendation datasets and trained weights the paper
+evaluates on, which are not available: same shapes, value distributions and index
+distributions, drawn from a counter-based generator (Philox) keyed by `seed`.
+
+A workload is a plain dict:
+  B, H, d_g, d_u, P, Nq, pool_ld : ints          dtype : 0 fp32 | 1 bf16     mode : 0 softmax | 1 SiLU/n
+  scale : float
+  lengths [B] int32                               history length n of every user
+  idx_k, idx_v   [T][H] int32                     pool row per position and head (user-major, ragged)
+  user_k, user_v [T][H][d_u]                      user-specific slices
+  pool_k, pool_v [H][P][pool_ld]                  global pools; columns >= d_g are padding (NaN)
+  q              [B][H][Nq][d_a]                  candidate queries
+Stored values are float32 arrays (dtype 0) or bfloat16 bit patterns in uint16 (dtype 1),
+rounded to nearest-even once, here.
+"""
+import numpy as np
+
+F32, BF16 = 0, 1
+SOFTMAX, SILU_OVER_N = 0, 1
+
+# name -> recipe.  L = (lo, hi) inclusive, uniform per user.  sigma_* are standard deviations.
+CONFIGS = {
+    "cfg1": dict(B=4, L=(50, 50), H=1, d_a=64, d_u=8, P=256, idx="uniform", Nq=1,
+                 mode=SOFTMAX, dtype=F32, sigma_pool=1.0 / 8.0, seed=1001),
+    "cfg2_f32": dict(B=1024, L=(200, 200), H=2, d_a=64, d_u=8, P=4096, idx="uniform", Nq=1,
+                     mode=SOFTMAX, dtype=F32, sigma_pool=1.0 / 8.0, seed=1002),
+    "cfg2_bf16": dict(B=1024, L=(200, 200), H=2, d_a=64, d_u=8, P=4096, idx="uniform", Nq=1,
+                      mode=SOFTMAX, dtype=BF16, sigma_pool=1.0 / 8.0, seed=1002),
+    "cfg3": dict(B=512, L=(1024, 1024), H=4, d_a=64, d_u=4, P=16384, idx=("zipf", 1.1), Nq=64,
+                 mode=SILU_OVER_N, dtype=BF16, sigma_pool=1.0 / 8.0, seed=1003),
+    "cfg4": dict(B=128, L=(2048, 8192), H=8, d_a=128, d_u=8, P=65536, idx="uniform", Nq=128,
+                 mode=SOFTMAX, dtype=BF16, sigma_pool=128.0 ** -0.5, seed=1004),
+    "cfg5": dict(B=8192, L=(512, 2048), H=4, d_a=64, d_u=2, P=1048576, idx=("zipf", 1.05), Nq=16,
+                 mode=SOFTMAX, dtype=BF16, sigma_pool=1.0 / 8.0, seed=1005),
+}
+
+
+def f32_to_bf16_bits(x):
+    """float32 array -> bfloat16 bit patterns (uint16), round to nearest, ties to even."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    r = ((u >> np.uint32(16)) & np.uint32(1)) + np.uint32(0x7FFF)
+    return ((u + r) >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_bits_to_f32(b):
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def to_f64(a, dtype):
+    """Stored array -> float64 (exact)."""
+    return (a if dtype == F32 else bf16_bits_to_f32(a)).astype(np.float64)
+
+
+def _rng(seed, stream):
+    return np.random.Generator(np.random.Philox(key=[seed, stream]))
+
+
+def _normal(rng, shape, sigma, dtype):
+    x = rng.standard_normal(size=shape, dtype=np.float32)
+    x *= np.float32(sigma)
+    return x if dtype == F32 else f32_to_bf16_bits(x)
+
+
+def _draw_idx(rng, kind, P, shape, perm_rng):
+    """Pool rows for every (position, head).  'uniform', or ('zipf', s): bounded Zipf over
+    ranks 1..P with p(r) ~ r^-s, inverse CDF in fp64, ranks mapped to rows by a seeded
+    permutation per head so that hot rows are not neighbours."""
+    T, H = shape
+    if kind == "uniform":
+        return rng.integers(0, P, size=shape, dtype=np.int32)
+    _, s = kind
+    cdf = np.cumsum(np.arange(1, P + 1, dtype=np.float64) ** (-float(s)))
+    cdf /= cdf[-1]
+    out = np.empty(shape, dtype=np.int32)
+    for h in range(H):
+        perm = perm_rng.permutation(P).astype(np.int32)
+        step = 1 << 22
+        for lo in range(0, T, step):
+            u = rng.random(size=min(step, T - lo))
+            rank = np.minimum(np.searchsorted(cdf, u, side="left"), P - 1)
+            out[lo:lo + len(u), h] = perm[rank]
+    return out
+
+
+def make(B, L, H, d_a, d_u, P, idx, Nq, mode, dtype, sigma_pool, seed,
+         sigma_user=0.1, sigma_q=1.0, pool_ld=None, scale=None, lengths=None, pad_nan=True):
+    """Build one workload dict from a recipe (see CONFIGS)."""
+    d_g = d_a - d_u
+    if pool_ld is None:
+        pool_ld = d_a if d_g > 0 else 0
+    if lengths is None:
+        lo, hi = L
+        lengths = _rng(seed, 0).integers(lo, hi + 1, size=B, dtype=np.int32)
+    lengths = np.ascontiguousarray(lengths, dtype=np.int32)
+    assert lengths.shape == (B,)
+    T = int(lengths.sum())
+    P_eff = max(P, 1)
+    if d_g > 0:
+        perm_rng = _rng(seed, 9)
+        idx_k = _draw_idx(_rng(seed, 1), idx, P_eff, (T, H), perm_rng)
+        idx_v = _draw_idx(_rng(seed, 2), idx, P_eff, (T, H), perm_rng)
+    else:
+        idx_k = np.zeros((T, H), dtype=np.int32)
+        idx_v = np.zeros((T, H), dtype=np.int32)
+    user_k = _normal(_rng(seed, 3), (T, H, d_u), sigma_user, dtype)
+    user_v = _normal(_rng(seed, 4), (T, H, d_u), sigma_user, dtype)
+    pool_k = _normal(_rng(seed, 5), (H, P_eff, pool_ld), sigma_pool, dtype)
+    pool_v = _normal(_rng(seed, 6), (H, P_eff, pool_ld), sigma_pool, dtype)
+    if pad_nan and pool_ld > d_g:
+        nan = np.float32(np.nan) if dtype == F32 else np.uint16(0x7FC0)
+        pool_k[:, :, d_g:] = nan
+        pool_v[:, :, d_g:] = nan
+    q = _normal(_rng(seed, 7), (B, H, Nq, d_a), sigma_q, dtype)
+    if scale is None:
+        scale = d_a ** -0.5 if mode == SOFTMAX else 1.0
+    return dict(B=B, H=H, d_g=d_g, d_u=d_u, P=P_eff, Nq=Nq, pool_ld=int(pool_ld), dtype=dtype,
+                mode=mode, scale=float(scale), lengths=lengths, idx_k=idx_k, idx_v=idx_v,
+                user_k=user_k, user_v=user_v, pool_k=pool_k, pool_v=pool_v, q=q)
+
+
+def config(name, **override):
+    """One of the named workloads, optionally with recipe fields overridden (smaller B, ...)."""
+    recipe = dict(CONFIGS[name])
+    recipe.update(override)
+    return make(**recipe)
+
+
+def algorithmic_bytes(w):
+    """Bytes the method must move for one pass (latency analysis, section 4.4:
+    load of s*d_u + s per K and per V, plus the index operation over s*d_g), plus q in and
+    out out.  Returns dict(compressed, gathered, q_out, E, position_heads)."""
+    e = 4 if w["dtype"] == F32 else 2
+    ph = int(np.sum(w["lengths"], dtype=np.int64)) * w["H"]
+    d_a = w["d_g"] + w["d_u"]
+    compressed = ph * (8 + 2 * w["d_u"] * e)
+    gathered = ph * 2 * w["d_g"] * e
+    q_out = 2 * w["B"] * w["H"] * w["Nq"] * d_a * e
+    return dict(position_heads=ph, compressed=compressed, gathered=gathered, q_out=q_out,
+                E=compressed + gathered + q_out)
