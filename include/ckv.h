@@ -1,0 +1,165 @@
+/*
+ * ckv.h - C ABI of the CollectiveKV decode hot path on AMD MI355X (gfx950).
+ *
+ * CollectiveKV (paper section 4.2) stores, for every position of a user's history and
+ * every head, two pool indices I_k, I_v and two low-dimensional user-specific slices
+ * K_u, V_u (d_u columns).  At decode time the collective part is gathered from the global
+ * pools, K_c[i] = P_k[I_k[i]], V_c[i] = P_v[I_v[i]] (eq. "eq: Kc"), concatenated behind the
+ * user slice, K = concat(K_u, K_c), V = concat(V_u, V_c) with d_a = d_u + d_g (eq. "eq: K";
+ * the first d_u columns are the user-specific ones, appendix "Discussion of the sharing
+ * mechanism"), and the user's queries attend over the final K, V.
+ *
+ * This library does gather + concat + attention in one fused pass that never writes a
+ * full-width K or V to memory.  Notation: B users, n_b = lengths[b] positions of user b,
+ * T = sum n_b, H heads, P pool rows per head, Nq queries per user and head.
+ *
+ * Conventions
+ *  - Every entry point returns 0 (CKV_OK) or a negative CKV_ERR_* code; the text of the
+ *    last error of the calling thread is available from ckv_last_error().  No C++
+ *    exception crosses this boundary.
+ *  - "device" pointers are HIP device memory on the current device, allocated and owned by
+ *    the caller and only borrowed for the duration of the enqueued work; "host" pointers
+ *    are ordinary host memory.  `stream` is a hipStream_t passed as void* (NULL = the
+ *    default stream).
+ *  - dtype selects the storage type of pools, user slices, q and out: CKV_F32 (float) or
+ *    CKV_BF16 (bfloat16, upper half of a binary32).  Accumulation is always fp32.
+ *  - The library needs a gfx950 device; there is no CPU fallback.
+ */
+#ifndef CKV_H
+#define CKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { CKV_F32 = 0, CKV_BF16 = 1 };
+enum { CKV_SOFTMAX = 0, CKV_SILU_OVER_N = 1 };
+
+enum {
+    CKV_OK = 0,
+    CKV_ERR_NULL = -1,        /* a required pointer is NULL                              */
+    CKV_ERR_SHAPE = -2,       /* a field of ckv_shape is out of range                    */
+    CKV_ERR_INDEX = -3,       /* a pool index lies outside [0, P)                        */
+    CKV_ERR_LENGTH = -4,      /* a history length is negative or T*H overflows           */
+    CKV_ERR_UNSUPPORTED = -5, /* valid but not implemented (alignment, size)             */
+    CKV_ERR_HIP = -6          /* a HIP runtime call failed                               */
+};
+
+/*
+ * Problem shape (section 4.2 notation: n -> lengths, m -> P, d_u, d_g, d_a = d_u + d_g).
+ * mode:  CKV_SOFTMAX      out_j = sum_i softmax_i(scale * q_j . K_i) V_i
+ *        CKV_SILU_OVER_N  out_j = sum_i SiLU(scale * q_j . K_i) V_i / n_b   (HSTU-style pointwise)
+ * Attention is non-causal over the user's n_b positions.  A user with n_b = 0 gets out = 0.
+ * pool_ld is the row stride of both pools in elements, pool_ld >= d_g; columns
+ * [d_g, pool_ld) of a pool row are padding and are never interpreted.
+ */
+typedef struct ckv_shape {
+    int32_t B, H, d_g, d_u, P, Nq;
+    int32_t dtype;   /* CKV_F32 | CKV_BF16 */
+    int32_t mode;    /* CKV_SOFTMAX | CKV_SILU_OVER_N */
+    float scale;
+    int32_t reserved; /* must be 0 */
+    int64_t pool_ld;
+} ckv_shape;
+
+/* Opaque handle: the packed compressed cache of B users plus launch metadata. Owned by the
+ * library from ckv_build_cache until ckv_free. */
+typedef struct ckv_cache ckv_cache;
+
+/*
+ * Pack the compressed cache of B users ("both the global K/V indices and the user-specific
+ * K/V will be cached", section 4.2, prefill stage) into the device layout the attention
+ * kernels stream, and precompute launch metadata (per-user offsets, the work list).
+ *
+ *   shape     host.  Copied.
+ *   lengths   host int32 [B], each >= 0.
+ *   idx_k,
+ *   idx_v     host int32 [T][H]: pool row of flattened position t (users back to back) and
+ *             head h, 0-based, each in [0, P).  Ignored (may be NULL) when d_g == 0.
+ *   user_k,
+ *   user_v    host [T][H][d_u] in shape->dtype.  Ignored (may be NULL) when d_u == 0.
+ *   out       receives the handle.
+ *   stream    uploads and the packing kernel run on this stream; the call synchronises it
+ *             before returning (it has to read back the index check).
+ *
+ * Device layout produced (see the accessors): indices as two planes [2][H][T] (plane 0 =
+ * I_k, plane 1 = I_v), user slices [H][T][d_u], so that one head's positions are one
+ * contiguous, coalesced stream.  Packing and the range check of every index run on the GPU.
+ * Errors: CKV_ERR_NULL, _SHAPE, _LENGTH, _INDEX (message names the first offending
+ * position and head; nothing is clamped), _HIP.  On error *out is NULL and nothing leaks.
+ */
+int ckv_build_cache(const ckv_shape* shape, const int32_t* lengths,
+                    const int32_t* idx_k, const int32_t* idx_v,
+                    const void* user_k, const void* user_v,
+                    ckv_cache** out, void* stream);
+
+/* Borrowed device views of the packed cache; valid until ckv_free. */
+const int32_t* ckv_cache_idx(const ckv_cache* c);     /* device int32 [2][H][T]        */
+const void* ckv_cache_user_k(const ckv_cache* c);     /* device [H][T][d_u]            */
+const void* ckv_cache_user_v(const ckv_cache* c);     /* device [H][T][d_u]            */
+const int32_t* ckv_cache_lengths(const ckv_cache* c); /* device int32 [B]              */
+int64_t ckv_cache_positions(const ckv_cache* c);      /* T                             */
+/* Bytes of the stored cache (indices + user slices; the quantity whose ratio to the full
+ * K/V size 2*T*H*d_a*e is the compression rate of section 5.1). */
+int64_t ckv_cache_stored_bytes(const ckv_cache* c);
+
+/*
+ * Fused gather + concat + attend (section 4.2, decode stage), enqueued on `stream`.
+ *
+ *   cache     handle from ckv_build_cache: shape, offsets, work list, split workspace.
+ *   pool_k,
+ *   pool_v    device [H][P][pool_ld]: the global K/V pools P_k, P_v.
+ *   idx       device int32 [2][H][T]            } normally the handle's own views; any
+ *   user_k,
+ *   user_v    device [H][T][d_u]                } buffers of the same layout and contents
+ *   lengths   device int32 [B]                  } class (same lengths) are accepted.
+ *   q         device [B][H][Nq][d_a]: queries, columns in final-K order (user columns first).
+ *   out       device [B][H][Nq][d_a]: written completely (zeros for users with n_b = 0).
+ *
+ * No allocation, no synchronisation, no validation pass over the data: indices were checked
+ * when the cache was built; passing other index buffers with out-of-range entries is
+ * undefined.  Calls on the same handle share its split workspace, so two calls on one handle
+ * must not overlap in time (serialise them on one stream).
+ * Errors: CKV_ERR_NULL, CKV_ERR_HIP (launch failure).
+ */
+int ckv_attend(const ckv_cache* cache, const void* pool_k, const void* pool_v,
+               const int32_t* idx, const void* user_k, const void* user_v,
+               const void* q, const int32_t* lengths, void* out, void* stream);
+
+/*
+ * Materialise the final K and V rows, k_full, v_full device [H][T][d_a], each row the
+ * user slice followed by the gathered pool row (eq. "eq: Kc", "eq: K").  A pure copy,
+ * bit-exact.  Exists for verification of the gather and the layouts; the attention path
+ * never calls it.  Either output may be NULL to skip it.
+ */
+int ckv_reconstruct(const ckv_cache* cache, const void* pool_k, const void* pool_v,
+                    void* k_full, void* v_full, void* stream);
+
+/* Release the handle and the device memory it owns.  NULL is allowed. */
+void ckv_free(ckv_cache* cache);
+
+/* Message of the last error on this thread ("" if none). Never NULL. */
+const char* ckv_last_error(void);
+
+/*
+ * Measurement helpers.
+ * ckv_set_timing(cache, 1) makes every following ckv_attend on this handle bracket its main
+ * attention kernel with HIP events on the launch stream; ckv_kernel_ms then synchronises the
+ * last pair and returns the elapsed milliseconds of that one kernel launch (negative if
+ * none was recorded).  ckv_variant names the kernel family the handle dispatches to.
+ * ckv_copy enqueues a plain device-to-device copy kernel of nbytes (16-byte aligned device
+ * pointers), used to calibrate hardware byte counters against a transfer of known size and
+ * to read the packed cache back in tests.
+ */
+int ckv_set_timing(ckv_cache* cache, int enable);
+float ckv_kernel_ms(ckv_cache* cache);
+const char* ckv_variant(const ckv_cache* cache);
+int ckv_copy(void* dst, const void* src, size_t nbytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CKV_H */

@@ -1,0 +1,158 @@
+"""Thin ctypes binding of libckv.so: same names as include/ckv.h, argument marshalling only.
+
+Device arguments may be torch tensors (their data_ptr() is passed), ints (raw device
+addresses) or None.  Host arguments are numpy arrays.  There is no fallback: if the library
+is missing, import fails with the build command to run.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIBPATH = os.path.join(_HERE, "libckv.so")
+
+CKV_F32, CKV_BF16 = 0, 1
+CKV_SOFTMAX, CKV_SILU_OVER_N = 0, 1
+CKV_OK, CKV_ERR_NULL, CKV_ERR_SHAPE, CKV_ERR_INDEX, CKV_ERR_LENGTH, CKV_ERR_UNSUPPORTED, CKV_ERR_HIP = 0, -1, -2, -3, -4, -5, -6
+
+EXPORTS = [
+    "ckv_build_cache", "ckv_cache_idx", "ckv_cache_user_k", "ckv_cache_user_v", "ckv_cache_lengths",
+    "ckv_cache_positions", "ckv_cache_stored_bytes", "ckv_attend", "ckv_reconstruct", "ckv_free",
+    "ckv_last_error", "ckv_set_timing", "ckv_kernel_ms", "ckv_variant", "ckv_copy",
+]
+
+
+class ckv_shape(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("d_g", ctypes.c_int32), ("d_u", ctypes.c_int32),
+                ("P", ctypes.c_int32), ("Nq", ctypes.c_int32), ("dtype", ctypes.c_int32), ("mode", ctypes.c_int32),
+                ("scale", ctypes.c_float), ("reserved", ctypes.c_int32), ("pool_ld", ctypes.c_int64)]
+
+
+class CkvError(RuntimeError):
+    def __init__(self, code, message):
+        super().__init__(f"ckv error {code}: {message}")
+        self.code = code
+
+
+if not os.path.exists(_LIBPATH):
+    raise ImportError(f"{_LIBPATH} is not built; run `python -m paper_2601_19178_amd.build` "
+                      "(hipcc, gfx950). There is no CPU fallback.")
+_lib = ctypes.CDLL(_LIBPATH)
+
+_vp, _i32, _i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+_lib.ckv_build_cache.restype = ctypes.c_int
+_lib.ckv_build_cache.argtypes = [ctypes.POINTER(ckv_shape), _vp, _vp, _vp, _vp, _vp, ctypes.POINTER(_vp), _vp]
+for _n in ("ckv_cache_idx", "ckv_cache_user_k", "ckv_cache_user_v", "ckv_cache_lengths"):
+    getattr(_lib, _n).restype = _vp
+    getattr(_lib, _n).argtypes = [_vp]
+_lib.ckv_cache_positions.restype = _i64
+_lib.ckv_cache_positions.argtypes = [_vp]
+_lib.ckv_cache_stored_bytes.restype = _i64
+_lib.ckv_cache_stored_bytes.argtypes = [_vp]
+_lib.ckv_attend.restype = ctypes.c_int
+_lib.ckv_attend.argtypes = [_vp] * 10
+_lib.ckv_reconstruct.restype = ctypes.c_int
+_lib.ckv_reconstruct.argtypes = [_vp] * 6
+_lib.ckv_free.restype = None
+_lib.ckv_free.argtypes = [_vp]
+_lib.ckv_last_error.restype = ctypes.c_char_p
+_lib.ckv_last_error.argtypes = []
+_lib.ckv_set_timing.restype = ctypes.c_int
+_lib.ckv_set_timing.argtypes = [_vp, ctypes.c_int]
+_lib.ckv_kernel_ms.restype = ctypes.c_float
+_lib.ckv_kernel_ms.argtypes = [_vp]
+_lib.ckv_variant.restype = ctypes.c_char_p
+_lib.ckv_variant.argtypes = [_vp]
+_lib.ckv_copy.restype = ctypes.c_int
+_lib.ckv_copy.argtypes = [_vp, _vp, ctypes.c_size_t, _vp]
+
+
+def _dev(x):
+    """torch tensor | int | None -> c_void_p of a device address."""
+    if x is None:
+        return _vp(0)
+    if isinstance(x, int):
+        return _vp(x)
+    return _vp(x.data_ptr())
+
+
+def _host(a, dtype=None):
+    if a is None:
+        return None, _vp(0)
+    a = np.ascontiguousarray(a) if dtype is None else np.ascontiguousarray(a, dtype=dtype)
+    return a, _vp(a.ctypes.data)
+
+
+def _check(rc):
+    if rc != CKV_OK:
+        raise CkvError(rc, ckv_last_error())
+
+
+def ckv_last_error():
+    return _lib.ckv_last_error().decode()
+
+
+def make_shape(B, H, d_g, d_u, P, Nq, dtype, mode, scale, pool_ld):
+    return ckv_shape(B, H, d_g, d_u, P, Nq, dtype, mode, scale, 0, pool_ld)
+
+
+def ckv_build_cache(shape, lengths, idx_k, idx_v, user_k, user_v, stream=0):
+    """Host arrays in, opaque handle (int address) out."""
+    keep = [_host(lengths, np.int32), _host(idx_k, np.int32), _host(idx_v, np.int32), _host(user_k), _host(user_v)]
+    out = _vp(0)
+    _check(_lib.ckv_build_cache(ctypes.byref(shape), *[p for _, p in keep], ctypes.byref(out), _vp(stream)))
+    return out.value
+
+
+def ckv_cache_idx(cache):
+    return _lib.ckv_cache_idx(cache) or 0
+
+
+def ckv_cache_user_k(cache):
+    return _lib.ckv_cache_user_k(cache) or 0
+
+
+def ckv_cache_user_v(cache):
+    return _lib.ckv_cache_user_v(cache) or 0
+
+
+def ckv_cache_lengths(cache):
+    return _lib.ckv_cache_lengths(cache) or 0
+
+
+def ckv_cache_positions(cache):
+    return int(_lib.ckv_cache_positions(cache))
+
+
+def ckv_cache_stored_bytes(cache):
+    return int(_lib.ckv_cache_stored_bytes(cache))
+
+
+def ckv_attend(cache, pool_k, pool_v, idx, user_k, user_v, q, lengths, out, stream=0):
+    _check(_lib.ckv_attend(cache, _dev(pool_k), _dev(pool_v), _dev(idx), _dev(user_k), _dev(user_v), _dev(q),
+                           _dev(lengths), _dev(out), _vp(stream)))
+
+
+def ckv_reconstruct(cache, pool_k, pool_v, k_full, v_full, stream=0):
+    _check(_lib.ckv_reconstruct(cache, _dev(pool_k), _dev(pool_v), _dev(k_full), _dev(v_full), _vp(stream)))
+
+
+def ckv_free(cache):
+    _lib.ckv_free(cache)
+
+
+def ckv_set_timing(cache, enable):
+    _check(_lib.ckv_set_timing(cache, int(enable)))
+
+
+def ckv_kernel_ms(cache):
+    return float(_lib.ckv_kernel_ms(cache))
+
+
+def ckv_variant(cache):
+    return _lib.ckv_variant(cache).decode()
+
+
+def ckv_copy(dst, src, nbytes, stream=0):
+    _check(_lib.ckv_copy(_dev(dst), _dev(src), nbytes, _vp(stream)))

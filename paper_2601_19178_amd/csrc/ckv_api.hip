@@ -1,0 +1,542 @@
+// C ABI of libckv.so: cache packing, work-list construction, dispatch, verification helpers.
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <numeric>
+#include <vector>
+
+#include "ckv_internal.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define CKV_HIP(call)                                                                         \
+    do {                                                                                      \
+        hipError_t e_ = (call);                                                               \
+        if (e_ != hipSuccess) {                                                               \
+            rc = fail(CKV_ERR_HIP, "%s failed: %s", #call, hipGetErrorString(e_));            \
+            goto done;                                                                        \
+        }                                                                                     \
+    } while (0)
+
+size_t esize(int dtype) { return dtype == CKV_F32 ? 4 : 2; }
+
+// ---------------------------------------------------------------------------------------
+// Packing: user-major [T][H] records -> head-major planes, with the range check of every
+// index done in the same pass.  `bad` receives the smallest offending t*H + h.
+template <typename U>
+__global__ void ckv_pack_kernel(const int32_t* __restrict__ in_k, const int32_t* __restrict__ in_v,
+                                const U* __restrict__ in_uk, const U* __restrict__ in_uv,
+                                int32_t* __restrict__ idx, U* __restrict__ uk, U* __restrict__ uv,
+                                int64_t T, int H, int d_u, int P, int has_pool,
+                                unsigned long long* __restrict__ bad) {
+    const int64_t total = T * H;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t t = i / H;
+        const int h = (int)(i - t * H);
+        const int64_t o = (int64_t)h * T + t;
+        if (has_pool) {
+            const int32_t a = in_k[i], b = in_v[i];
+            if (a < 0 || a >= P || b < 0 || b >= P) atomicMin(bad, (unsigned long long)i);
+            idx[o] = a;
+            idx[(int64_t)H * T + o] = b;
+        }
+        for (int c = 0; c < d_u; ++c) {
+            uk[o * d_u + c] = in_uk[i * d_u + c];
+            uv[o * d_u + c] = in_uv[i * d_u + c];
+        }
+    }
+}
+
+// Final K and V rows [H][T][d_a]: user slice then pool row.  Pure copy.
+template <typename U>
+__global__ void ckv_reconstruct_kernel(const int32_t* __restrict__ idx, const U* __restrict__ user,
+                                       const U* __restrict__ pool, U* __restrict__ full,
+                                       int64_t T, int H, int d_u, int d_g, int P, int64_t pool_ld) {
+    const int d_a = d_u + d_g;
+    const int64_t total = (int64_t)H * T * d_a;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t ht = i / d_a;
+        const int c = (int)(i - ht * d_a);
+        if (c < d_u) {
+            full[i] = user[ht * d_u + c];
+        } else {
+            const int h = (int)(ht / T);
+            full[i] = pool[((int64_t)h * P + idx[ht]) * pool_ld + (c - d_u)];
+        }
+    }
+}
+
+// Merge of the pieces of a split history.  Softmax pieces carry (acc, m, l) with acc and l
+// relative to the piece maximum m; SiLU pieces carry only acc.
+template <typename U, int MODE>
+__global__ void ckv_merge_kernel(const ckv_merge* __restrict__ list, const float* __restrict__ partial,
+                                 U* __restrict__ out, int H, int Nq, int d_a, int QB) {
+    const ckv_merge mg = list[blockIdx.x];
+    const int64_t stride = (int64_t)QB * (d_a + 2);
+    for (int j = 0; j < QB; ++j) {
+        if (mg.q0 + j >= Nq) break;
+        float M = -INFINITY;
+        if (MODE == CKV_SOFTMAX)
+            for (int p = 0; p < mg.nparts; ++p)
+                M = fmaxf(M, partial[(mg.part0 + p) * stride + (int64_t)QB * d_a + j]);
+        float denom = 0.f;
+        if (MODE == CKV_SOFTMAX) {
+            for (int p = 0; p < mg.nparts; ++p) {
+                const float* ws = partial + (mg.part0 + p) * stride;
+                const float mp = ws[(int64_t)QB * d_a + j];
+                denom += (mp == -INFINITY ? 0.f : __expf(mp - M)) * ws[(int64_t)QB * d_a + QB + j];
+            }
+        } else {
+            denom = (float)mg.n_total;
+        }
+        const float inv = denom > 0.f ? 1.f / denom : 0.f;
+        for (int c = threadIdx.x; c < d_a; c += blockDim.x) {
+            float acc = 0.f;
+            for (int p = 0; p < mg.nparts; ++p) {
+                const float* ws = partial + (mg.part0 + p) * stride;
+                float w = 1.f;
+                if (MODE == CKV_SOFTMAX) {
+                    const float mp = ws[(int64_t)QB * d_a + j];
+                    w = mp == -INFINITY ? 0.f : __expf(mp - M);
+                }
+                acc += w * ws[(int64_t)j * d_a + c];
+            }
+            const float r = acc * inv;
+            const int64_t o = (((int64_t)mg.b * H + mg.h) * Nq + mg.q0 + j) * d_a + c;
+            if (sizeof(U) == 4) {
+                ((float*)out)[o] = r;
+            } else {
+                uint32_t u = __float_as_uint(r);
+                if ((u & 0x7FFFFFFFu) > 0x7F800000u) u |= 0x400000u;
+                else u += 0x7FFFu + ((u >> 16) & 1u);
+                ((uint16_t*)out)[o] = (uint16_t)(u >> 16);
+            }
+        }
+    }
+}
+
+__global__ void ckv_copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n16, int tail) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
+        dst[i] = src[i];
+    if (blockIdx.x == 0 && (int)threadIdx.x < tail)
+        ((unsigned char*)(dst + n16))[threadIdx.x] = ((const unsigned char*)(src + n16))[threadIdx.x];
+}
+
+// ---------------------------------------------------------------------------------------
+// Work list.  Units are (user, head, query block); long histories are cut into pieces when
+// there are too few units to fill and balance the chip.  Pieces are ordered longest first
+// (the hardware dispatcher hands out workgroups in grid order, which makes this longest-
+// processing-time-first scheduling), interleaved so that workgroup i, which lands on XCD
+// i mod 8, keeps to one head class: each XCD's L2 then caches one head's pool rows.
+struct Unit {
+    int32_t b, h, q0, n;
+    int64_t t0;
+};
+
+int pick_stream_vec(const ckv_shape& s) {
+    const int d_a = s.d_g + s.d_u;
+    const int maxvec = s.dtype == CKV_F32 ? 4 : 8;
+    for (int v = maxvec; v > 1; v >>= 1) {
+        if (v == 2) continue;  // not instantiated
+        if (s.d_u % v || s.d_g % v || (s.d_g > 0 && s.pool_ld % v)) continue;
+        if ((d_a + 16 * v - 1) / (16 * v) <= 8) return v;
+    }
+    return 1;
+}
+
+void build_work(ckv_cache* c, const int32_t* lengths, const std::vector<int64_t>& offs, int cus,
+                std::vector<ckv_item>& items, std::vector<ckv_merge>& merges) {
+    const ckv_shape& s = c->shape;
+    const int nqb = (s.Nq + c->QB - 1) / c->QB;
+    int wg_per_cu = 8;
+    if (c->family == CKV_K_MFMA) wg_per_cu = std::max(1, ckv_mfma_occupancy(s.d_g + s.d_u, c->nw, c->tp, s.mode));
+    const int64_t slots = (int64_t)cus * wg_per_cu;
+    const int64_t n_units = (int64_t)s.B * s.H * nqb;
+    const int64_t total_ph = c->T * s.H * nqb;
+    int64_t piece = INT64_MAX;
+    if (n_units < 8 * slots) {
+        piece = std::max<int64_t>(1024, total_ph / (slots * 4));
+        piece = (piece + 63) / 64 * 64;
+    }
+    std::vector<Unit> units;
+    units.reserve((size_t)n_units);
+    for (int b = 0; b < s.B; ++b)
+        for (int h = 0; h < s.H; ++h)
+            for (int qb = 0; qb < nqb; ++qb) units.push_back({b, h, qb * c->QB, lengths[b], offs[b]});
+
+    int n_parts = 0;
+    for (const Unit& u : units) {
+        const int np = u.n > piece ? (int)((u.n + piece - 1) / piece) : 1;
+        if (np == 1) {
+            items.push_back({u.b, u.h, u.q0, u.n, u.t0, -1, u.n});
+            continue;
+        }
+        int64_t len = (u.n + np - 1) / np;
+        len = (len + 63) / 64 * 64;
+        const int real_np = (int)((u.n + len - 1) / len);
+        merges.push_back({u.b, u.h, u.q0, n_parts, real_np, u.n});
+        for (int p = 0; p < real_np; ++p) {
+            const int64_t lo = (int64_t)p * len;
+            const int nn = (int)std::min<int64_t>(len, u.n - lo);
+            items.push_back({u.b, u.h, u.q0, nn, u.t0 + lo, n_parts++, u.n});
+        }
+    }
+    c->n_parts = n_parts;
+
+    // head classes for the XCD-aware order
+    int ncls = 1;
+    if (s.H >= 8 && s.H % 8 == 0) ncls = 8;
+    else if (s.H < 8 && 8 % s.H == 0) ncls = s.H;
+    std::vector<std::vector<ckv_item>> cls((size_t)ncls);
+    for (const ckv_item& it : items) cls[(size_t)(it.h % ncls)].push_back(it);
+    for (auto& v : cls)
+        std::stable_sort(v.begin(), v.end(), [](const ckv_item& x, const ckv_item& y) { return x.n > y.n; });
+    std::vector<ckv_item> ordered;
+    ordered.reserve(items.size());
+    std::vector<size_t> cur((size_t)ncls, 0);
+    size_t remaining = items.size();
+    for (size_t i = 0; remaining > 0; ++i) {
+        size_t k = i % (size_t)ncls;
+        if (cur[k] >= cls[k].size()) {  // this class ran dry: take from the fullest one
+            size_t best = 0, left = 0;
+            for (size_t j = 0; j < (size_t)ncls; ++j)
+                if (cls[j].size() - cur[j] > left) { left = cls[j].size() - cur[j]; best = j; }
+            k = best;
+        }
+        ordered.push_back(cls[k][cur[k]++]);
+        --remaining;
+    }
+    items.swap(ordered);
+}
+
+void choose_variant(ckv_cache* c) {
+    const ckv_shape& s = c->shape;
+    const int d_a = s.d_g + s.d_u;
+    c->family = CKV_K_STREAM;
+    if (s.dtype == CKV_BF16 && (d_a == 64 || d_a == 128) && s.Nq >= 8 && (s.d_g == 0 || s.pool_ld % 8 == 0)) {
+        const int nw = s.Nq <= 32 ? 1 : (s.Nq <= 64 ? 2 : 4);
+        const int tp = 64;
+        if (ckv_mfma_supported(d_a, nw, tp)) {
+            c->family = CKV_K_MFMA;
+            c->nw = nw;
+            c->tp = tp;
+            c->QB = 32 * nw;
+            snprintf(c->variant, sizeof c->variant, "mfma_bf16_d%d_w%d_t%d_%s", d_a, nw, tp,
+                     s.mode == CKV_SOFTMAX ? "softmax" : "silu");
+            return;
+        }
+    }
+    c->vec = pick_stream_vec(s);
+    int ncb = (d_a + 16 * c->vec - 1) / (16 * c->vec);
+    c->ncb = ncb <= 1 ? 1 : (ncb <= 2 ? 2 : (ncb <= 4 ? 4 : 8));
+    c->QB = s.Nq;
+    snprintf(c->variant, sizeof c->variant, "stream_%s_v%d_c%d_%s", s.dtype == CKV_F32 ? "f32" : "bf16", c->vec,
+             c->ncb, s.mode == CKV_SOFTMAX ? "softmax" : "silu");
+}
+
+void destroy(ckv_cache* c) {
+    if (!c) return;
+    (void)hipFree(c->d_idx);
+    (void)hipFree(c->d_user_k);
+    (void)hipFree(c->d_user_v);
+    (void)hipFree(c->d_lengths);
+    (void)hipFree(c->d_items);
+    (void)hipFree(c->d_merge);
+    (void)hipFree(c->d_partial);
+    if (c->ev0) (void)hipEventDestroy(c->ev0);
+    if (c->ev1) (void)hipEventDestroy(c->ev1);
+    delete c;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ckv_last_error(void) { return g_err; }
+
+int ckv_build_cache(const ckv_shape* shape, const int32_t* lengths, const int32_t* idx_k, const int32_t* idx_v,
+                    const void* user_k, const void* user_v, ckv_cache** out, void* stream) {
+    if (out) *out = nullptr;
+    if (!shape || !lengths || !out) return fail(CKV_ERR_NULL, "ckv_build_cache: shape, lengths and out must not be NULL");
+    const ckv_shape s = *shape;
+    const int64_t d_a = (int64_t)s.d_g + s.d_u;
+    if (s.B < 1 || s.H < 1 || s.d_g < 0 || s.d_u < 0 || d_a < 1 || s.Nq < 1 || s.reserved != 0)
+        return fail(CKV_ERR_SHAPE, "ckv_build_cache: need B,H,Nq >= 1, d_g,d_u >= 0, d_g+d_u >= 1 (B=%d H=%d d_g=%d d_u=%d Nq=%d)",
+                    s.B, s.H, s.d_g, s.d_u, s.Nq);
+    if (s.d_g > 0 && (s.P < 1 || s.pool_ld < s.d_g))
+        return fail(CKV_ERR_SHAPE, "ckv_build_cache: need P >= 1 and pool_ld >= d_g (P=%d pool_ld=%lld d_g=%d)", s.P,
+                    (long long)s.pool_ld, s.d_g);
+    if ((s.dtype != CKV_F32 && s.dtype != CKV_BF16) || (s.mode != CKV_SOFTMAX && s.mode != CKV_SILU_OVER_N))
+        return fail(CKV_ERR_SHAPE, "ckv_build_cache: unknown dtype %d or mode %d", s.dtype, s.mode);
+    if (!(s.scale == s.scale) || s.scale - s.scale != 0.f)
+        return fail(CKV_ERR_SHAPE, "ckv_build_cache: scale must be finite");
+    std::vector<int64_t> offs((size_t)s.B + 1, 0);
+    for (int b = 0; b < s.B; ++b) {
+        if (lengths[b] < 0) return fail(CKV_ERR_LENGTH, "ckv_build_cache: lengths[%d] = %d is negative", b, lengths[b]);
+        offs[(size_t)b + 1] = offs[(size_t)b] + lengths[b];
+    }
+    const int64_t T = offs[(size_t)s.B];
+    if (T * s.H > ((int64_t)1 << 40)) return fail(CKV_ERR_LENGTH, "ckv_build_cache: T*H = %lld is too large", (long long)(T * s.H));
+    if (T > 0 && s.d_g > 0 && (!idx_k || !idx_v)) return fail(CKV_ERR_NULL, "ckv_build_cache: idx_k/idx_v are NULL but d_g > 0");
+    if (T > 0 && s.d_u > 0 && (!user_k || !user_v)) return fail(CKV_ERR_NULL, "ckv_build_cache: user_k/user_v are NULL but d_u > 0");
+
+    ckv_cache* c = new (std::nothrow) ckv_cache();
+    if (!c) return fail(CKV_ERR_HIP, "ckv_build_cache: out of host memory");
+    memset(c, 0, sizeof *c);
+    c->shape = s;
+    c->T = T;
+    choose_variant(c);
+    if (c->family == CKV_K_STREAM && (d_a + 16 * c->vec - 1) / (16 * c->vec) > 8) {
+        const int vec = c->vec;
+        delete c;
+        return fail(CKV_ERR_UNSUPPORTED,
+                    "ckv_build_cache: d_a = %lld exceeds the streaming kernel's limit of %d columns at this alignment",
+                    (long long)d_a, 128 * vec);
+    }
+
+    int rc = CKV_OK;
+    hipStream_t st = (hipStream_t)stream;
+    const size_t e = esize(s.dtype);
+    const size_t n_ph = (size_t)T * s.H;
+    int32_t *s_ik = nullptr, *s_iv = nullptr;
+    void *s_uk = nullptr, *s_uv = nullptr;
+    unsigned long long* d_bad = nullptr;
+    unsigned long long h_bad = ~0ull;
+    std::vector<ckv_item> items;
+    std::vector<ckv_merge> merges;
+    hipDeviceProp_t prop;
+
+    CKV_HIP(hipGetDevice(&c->device));
+    CKV_HIP(hipGetDeviceProperties(&prop, c->device));
+    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) {
+        rc = fail(CKV_ERR_UNSUPPORTED, "ckv_build_cache: device is %s, this library is built for gfx950 only", prop.gcnArchName);
+        goto done;
+    }
+    CKV_HIP(hipMalloc((void**)&c->d_lengths, sizeof(int32_t) * (size_t)s.B));
+    CKV_HIP(hipMemcpyAsync(c->d_lengths, lengths, sizeof(int32_t) * (size_t)s.B, hipMemcpyHostToDevice, st));
+    if (n_ph > 0) {
+        if (s.d_g > 0) {
+            CKV_HIP(hipMalloc((void**)&c->d_idx, sizeof(int32_t) * 2 * n_ph));
+            CKV_HIP(hipMalloc((void**)&s_ik, sizeof(int32_t) * n_ph));
+            CKV_HIP(hipMalloc((void**)&s_iv, sizeof(int32_t) * n_ph));
+            CKV_HIP(hipMemcpyAsync(s_ik, idx_k, sizeof(int32_t) * n_ph, hipMemcpyHostToDevice, st));
+            CKV_HIP(hipMemcpyAsync(s_iv, idx_v, sizeof(int32_t) * n_ph, hipMemcpyHostToDevice, st));
+        }
+        if (s.d_u > 0) {
+            const size_t ub = n_ph * (size_t)s.d_u * e;
+            CKV_HIP(hipMalloc(&c->d_user_k, ub));
+            CKV_HIP(hipMalloc(&c->d_user_v, ub));
+            CKV_HIP(hipMalloc(&s_uk, ub));
+            CKV_HIP(hipMalloc(&s_uv, ub));
+            CKV_HIP(hipMemcpyAsync(s_uk, user_k, ub, hipMemcpyHostToDevice, st));
+            CKV_HIP(hipMemcpyAsync(s_uv, user_v, ub, hipMemcpyHostToDevice, st));
+        }
+        CKV_HIP(hipMalloc((void**)&d_bad, sizeof h_bad));
+        CKV_HIP(hipMemcpyAsync(d_bad, &h_bad, sizeof h_bad, hipMemcpyHostToDevice, st));
+        {
+            const int threads = 256;
+            const int blocks = (int)std::min<size_t>((n_ph + threads - 1) / threads, 65536);
+            if (e == 4)
+                hipLaunchKernelGGL(ckv_pack_kernel<uint32_t>, dim3(blocks), dim3(threads), 0, st, s_ik, s_iv,
+                                   (const uint32_t*)s_uk, (const uint32_t*)s_uv, c->d_idx, (uint32_t*)c->d_user_k,
+                                   (uint32_t*)c->d_user_v, T, s.H, s.d_u, s.P, s.d_g > 0 ? 1 : 0, d_bad);
+            else
+                hipLaunchKernelGGL(ckv_pack_kernel<uint16_t>, dim3(blocks), dim3(threads), 0, st, s_ik, s_iv,
+                                   (const uint16_t*)s_uk, (const uint16_t*)s_uv, c->d_idx, (uint16_t*)c->d_user_k,
+                                   (uint16_t*)c->d_user_v, T, s.H, s.d_u, s.P, s.d_g > 0 ? 1 : 0, d_bad);
+            CKV_HIP(hipGetLastError());
+        }
+        CKV_HIP(hipMemcpyAsync(&h_bad, d_bad, sizeof h_bad, hipMemcpyDeviceToHost, st));
+    }
+    CKV_HIP(hipStreamSynchronize(st));
+    if (h_bad != ~0ull) {
+        const long long t = (long long)(h_bad / (unsigned long long)s.H);
+        const int h = (int)(h_bad % (unsigned long long)s.H);
+        rc = fail(CKV_ERR_INDEX, "ckv_build_cache: pool index out of range [0,%d) at position %lld head %d (idx_k=%d idx_v=%d)", s.P,
+                  t, h, idx_k[h_bad], idx_v[h_bad]);
+        goto done;
+    }
+
+    build_work(c, lengths, offs, prop.multiProcessorCount, items, merges);
+    c->n_items = (int)items.size();
+    c->n_merge = (int)merges.size();
+    if (c->n_items > 0) {
+        CKV_HIP(hipMalloc((void**)&c->d_items, sizeof(ckv_item) * items.size()));
+        CKV_HIP(hipMemcpyAsync(c->d_items, items.data(), sizeof(ckv_item) * items.size(), hipMemcpyHostToDevice, st));
+    }
+    if (c->n_merge > 0) {
+        CKV_HIP(hipMalloc((void**)&c->d_merge, sizeof(ckv_merge) * merges.size()));
+        CKV_HIP(hipMemcpyAsync(c->d_merge, merges.data(), sizeof(ckv_merge) * merges.size(), hipMemcpyHostToDevice, st));
+        CKV_HIP(hipMalloc((void**)&c->d_partial, sizeof(float) * (size_t)c->n_parts * c->QB * (size_t)(d_a + 2)));
+    }
+    CKV_HIP(hipEventCreate(&c->ev0));
+    CKV_HIP(hipEventCreate(&c->ev1));
+    CKV_HIP(hipStreamSynchronize(st));
+
+done:
+    (void)hipFree(s_ik);
+    (void)hipFree(s_iv);
+    (void)hipFree(s_uk);
+    (void)hipFree(s_uv);
+    (void)hipFree(d_bad);
+    if (rc != CKV_OK) {
+        destroy(c);
+        return rc;
+    }
+    *out = c;
+    return CKV_OK;
+}
+
+const int32_t* ckv_cache_idx(const ckv_cache* c) { return c ? c->d_idx : nullptr; }
+const void* ckv_cache_user_k(const ckv_cache* c) { return c ? c->d_user_k : nullptr; }
+const void* ckv_cache_user_v(const ckv_cache* c) { return c ? c->d_user_v : nullptr; }
+const int32_t* ckv_cache_lengths(const ckv_cache* c) { return c ? c->d_lengths : nullptr; }
+int64_t ckv_cache_positions(const ckv_cache* c) { return c ? c->T : -1; }
+int64_t ckv_cache_stored_bytes(const ckv_cache* c) {
+    if (!c) return -1;
+    const int64_t ph = c->T * c->shape.H;
+    return ph * 2 * ((c->shape.d_g > 0 ? (int64_t)sizeof(int32_t) : 0) + (int64_t)c->shape.d_u * (int64_t)esize(c->shape.dtype));
+}
+const char* ckv_variant(const ckv_cache* c) { return c ? c->variant : ""; }
+
+int ckv_attend(const ckv_cache* c, const void* pool_k, const void* pool_v, const int32_t* idx, const void* user_k,
+               const void* user_v, const void* q, const int32_t* lengths, void* out, void* stream) {
+    if (!c || !q || !out || !lengths) return fail(CKV_ERR_NULL, "ckv_attend: cache, q, lengths and out must not be NULL");
+    const ckv_shape& s = c->shape;
+    if (c->T > 0 && s.d_g > 0 && (!pool_k || !pool_v || !idx)) return fail(CKV_ERR_NULL, "ckv_attend: pool_k, pool_v or idx is NULL");
+    if (c->T > 0 && s.d_u > 0 && (!user_k || !user_v)) return fail(CKV_ERR_NULL, "ckv_attend: user_k or user_v is NULL");
+    const uintptr_t align = (uintptr_t)pool_k | (uintptr_t)pool_v | (uintptr_t)idx | (uintptr_t)user_k | (uintptr_t)user_v |
+                            (uintptr_t)q | (uintptr_t)out;
+    if (align & 15) return fail(CKV_ERR_UNSUPPORTED, "ckv_attend: every device pointer must be 16-byte aligned");
+    hipStream_t st = (hipStream_t)stream;
+    ckv_args a;
+    a.pool_k = pool_k;
+    a.pool_v = pool_v;
+    a.idx_k = idx;
+    a.idx_v = idx ? idx + (int64_t)s.H * c->T : nullptr;
+    a.user_k = user_k;
+    a.user_v = user_v;
+    a.q = q;
+    a.out = out;
+    a.items = c->d_items;
+    a.partial = c->d_partial;
+    a.T = c->T;
+    a.pool_ld = s.pool_ld;
+    a.H = s.H;
+    a.P = s.P;
+    a.d_g = s.d_g;
+    a.d_u = s.d_u;
+    a.d_a = s.d_g + s.d_u;
+    a.Nq = s.Nq;
+    a.QB = c->QB;
+    a.scale = s.scale;
+    ckv_cache* mc = const_cast<ckv_cache*>(c);
+    hipError_t e;
+    if (c->timing) {
+        e = hipEventRecord(c->ev0, st);
+        if (e != hipSuccess) return fail(CKV_ERR_HIP, "ckv_attend: hipEventRecord: %s", hipGetErrorString(e));
+    }
+    e = c->family == CKV_K_MFMA ? ckv_launch_mfma(c, a, st) : ckv_launch_stream(c, a, st);
+    if (e != hipSuccess) return fail(CKV_ERR_HIP, "ckv_attend: kernel launch (%s): %s", c->variant, hipGetErrorString(e));
+    if (c->timing) {
+        e = hipEventRecord(c->ev1, st);
+        if (e != hipSuccess) return fail(CKV_ERR_HIP, "ckv_attend: hipEventRecord: %s", hipGetErrorString(e));
+        mc->ev_valid = 1;
+    }
+    if (c->n_merge > 0) {
+        const int d_a = a.d_a;
+        const int threads = d_a <= 64 ? 64 : (d_a <= 128 ? 128 : 256);
+        if (s.dtype == CKV_F32) {
+            if (s.mode == CKV_SOFTMAX)
+                hipLaunchKernelGGL((ckv_merge_kernel<float, CKV_SOFTMAX>), dim3(c->n_merge), dim3(threads), 0, st, c->d_merge,
+                                   c->d_partial, (float*)out, s.H, s.Nq, d_a, c->QB);
+            else
+                hipLaunchKernelGGL((ckv_merge_kernel<float, CKV_SILU_OVER_N>), dim3(c->n_merge), dim3(threads), 0, st, c->d_merge,
+                                   c->d_partial, (float*)out, s.H, s.Nq, d_a, c->QB);
+        } else {
+            if (s.mode == CKV_SOFTMAX)
+                hipLaunchKernelGGL((ckv_merge_kernel<uint16_t, CKV_SOFTMAX>), dim3(c->n_merge), dim3(threads), 0, st, c->d_merge,
+                                   c->d_partial, (uint16_t*)out, s.H, s.Nq, d_a, c->QB);
+            else
+                hipLaunchKernelGGL((ckv_merge_kernel<uint16_t, CKV_SILU_OVER_N>), dim3(c->n_merge), dim3(threads), 0, st,
+                                   c->d_merge, c->d_partial, (uint16_t*)out, s.H, s.Nq, d_a, c->QB);
+        }
+        e = hipGetLastError();
+        if (e != hipSuccess) return fail(CKV_ERR_HIP, "ckv_attend: merge launch: %s", hipGetErrorString(e));
+    }
+    return CKV_OK;
+}
+
+int ckv_reconstruct(const ckv_cache* c, const void* pool_k, const void* pool_v, void* k_full, void* v_full, void* stream) {
+    if (!c) return fail(CKV_ERR_NULL, "ckv_reconstruct: cache is NULL");
+    const ckv_shape& s = c->shape;
+    if (s.d_g > 0 && c->T > 0 && ((k_full && !pool_k) || (v_full && !pool_v)))
+        return fail(CKV_ERR_NULL, "ckv_reconstruct: pool pointer is NULL");
+    const int64_t total = (int64_t)s.H * c->T * (s.d_g + s.d_u);
+    if (total == 0) return CKV_OK;
+    const int threads = 256;
+    const int blocks = (int)std::min<int64_t>((total + threads - 1) / threads, 1 << 20);
+    hipStream_t st = (hipStream_t)stream;
+    for (int side = 0; side < 2; ++side) {
+        void* full = side == 0 ? k_full : v_full;
+        if (!full) continue;
+        const void* pool = side == 0 ? pool_k : pool_v;
+        const void* user = side == 0 ? c->d_user_k : c->d_user_v;
+        const int32_t* idx = c->d_idx ? c->d_idx + (int64_t)side * s.H * c->T : nullptr;
+        if (s.dtype == CKV_F32)
+            hipLaunchKernelGGL(ckv_reconstruct_kernel<uint32_t>, dim3(blocks), dim3(threads), 0, st, idx, (const uint32_t*)user,
+                               (const uint32_t*)pool, (uint32_t*)full, c->T, s.H, s.d_u, s.d_g, s.P, s.pool_ld);
+        else
+            hipLaunchKernelGGL(ckv_reconstruct_kernel<uint16_t>, dim3(blocks), dim3(threads), 0, st, idx, (const uint16_t*)user,
+                               (const uint16_t*)pool, (uint16_t*)full, c->T, s.H, s.d_u, s.d_g, s.P, s.pool_ld);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return fail(CKV_ERR_HIP, "ckv_reconstruct: launch: %s", hipGetErrorString(e));
+    }
+    return CKV_OK;
+}
+
+void ckv_free(ckv_cache* c) { destroy(c); }
+
+int ckv_set_timing(ckv_cache* c, int enable) {
+    if (!c) return fail(CKV_ERR_NULL, "ckv_set_timing: cache is NULL");
+    c->timing = enable ? 1 : 0;
+    c->ev_valid = 0;
+    return CKV_OK;
+}
+
+float ckv_kernel_ms(ckv_cache* c) {
+    if (!c || !c->ev_valid) return -1.f;
+    float ms = -1.f;
+    if (hipEventSynchronize(c->ev1) != hipSuccess) return -1.f;
+    if (hipEventElapsedTime(&ms, c->ev0, c->ev1) != hipSuccess) return -1.f;
+    return ms;
+}
+
+int ckv_copy(void* dst, const void* src, size_t nbytes, void* stream) {
+    if (!dst || !src) return fail(CKV_ERR_NULL, "ckv_copy: NULL pointer");
+    if (((uintptr_t)dst | (uintptr_t)src) & 15) return fail(CKV_ERR_UNSUPPORTED, "ckv_copy: pointers must be 16-byte aligned");
+    if (nbytes == 0) return CKV_OK;
+    const size_t n16 = nbytes / 16;
+    const int blocks = (int)std::max<size_t>(1, std::min<size_t>((n16 + 255) / 256, 256 * 32));
+    hipLaunchKernelGGL(ckv_copy_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (uint4*)dst, (const uint4*)src, n16,
+                       (int)(nbytes & 15));
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(CKV_ERR_HIP, "ckv_copy: launch: %s", hipGetErrorString(e));
+    return CKV_OK;
+}
+
+}  // extern "C"

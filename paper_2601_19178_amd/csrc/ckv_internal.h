@@ -1,0 +1,82 @@
+// Internal declarations shared by the translation units of libckv.so (not part of the ABI).
+#ifndef CKV_INTERNAL_H
+#define CKV_INTERNAL_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ckv.h"
+
+// One piece of work for one workgroup: a contiguous run of positions of one user and head,
+// attended by one block of queries.
+struct ckv_item {
+    int32_t b, h;      // user, head
+    int32_t q0;        // first query of the block this item serves
+    int32_t n;         // positions in this piece (0 for an empty history)
+    int64_t t0;        // first flattened position of the piece, in [0, T]
+    int32_t part;      // slot in the split workspace, or -1 if the piece is the whole history
+    int32_t n_total;   // n_b, the user's full history length
+};
+
+// A (user, head, query block) whose history was split into pieces; merged by a second kernel.
+struct ckv_merge {
+    int32_t b, h, q0;
+    int32_t part0, nparts;  // consecutive workspace slots
+    int32_t n_total;
+};
+
+// Kernel arguments common to both attention kernels.
+struct ckv_args {
+    const void* pool_k;
+    const void* pool_v;
+    const int32_t* idx_k;  // plane 0 of idx, [H][T]
+    const int32_t* idx_v;  // plane 1
+    const void* user_k;    // [H][T][d_u]
+    const void* user_v;
+    const void* q;         // [B][H][Nq][d_a]
+    void* out;             // [B][H][Nq][d_a]
+    const ckv_item* items;
+    float* partial;        // split workspace: per slot [QB][d_a] acc, [QB] m, [QB] l
+    int64_t T;
+    int64_t pool_ld;
+    int32_t H, P, d_g, d_u, d_a, Nq;
+    int32_t QB;            // queries per block (rows of a workspace slot)
+    float scale;
+};
+
+enum ckv_kernel_family { CKV_K_STREAM = 0, CKV_K_MFMA = 1 };
+
+struct ckv_cache {
+    ckv_shape shape;
+    int64_t T;
+    int device;
+    // packed cache (device, owned)
+    int32_t* d_idx;      // [2][H][T]
+    void* d_user_k;      // [H][T][d_u]
+    void* d_user_v;
+    int32_t* d_lengths;  // [B]
+    // launch metadata
+    int family;          // ckv_kernel_family
+    int vec, ncb;        // stream kernel: elements per lane per column block, column blocks
+    int nw, tp;          // mfma kernel: waves per workgroup, positions per tile
+    int QB;              // queries per block
+    int n_items, n_merge, n_parts;
+    ckv_item* d_items;
+    ckv_merge* d_merge;
+    float* d_partial;
+    // timing
+    int timing;
+    hipEvent_t ev0, ev1;
+    int ev_valid;
+    char variant[96];
+};
+
+// Launchers (each returns hipGetLastError() of its launch).
+hipError_t ckv_launch_stream(const ckv_cache* c, const ckv_args& a, hipStream_t s);
+hipError_t ckv_launch_mfma(const ckv_cache* c, const ckv_args& a, hipStream_t s);
+// Resident workgroups per CU of the chosen mfma kernel (0 if the shape has no mfma kernel).
+int ckv_mfma_occupancy(int d_a, int nw, int tp, int mode);
+// Whether (d_a, nw, tp) has an instantiated mfma kernel.
+bool ckv_mfma_supported(int d_a, int nw, int tp);
+
+#endif

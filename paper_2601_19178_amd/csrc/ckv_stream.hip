@@ -1,0 +1,236 @@
+// Streaming (vector-ALU) gather-concat-attend kernel: the path for few queries per user
+// (target attention, Q in R^{1 x d}, section 2.1) and the general fallback for any shape.
+//
+// One 64-lane wavefront serves one work item (a run of positions of one user and head) for
+// every query of the block, one query after the other.  A tile is 64 positions.  Sixteen
+// lanes share one final K (or V) row: lane c of the group owns the columns
+// (cb*16 + c)*VEC .. +VEC of every column block cb, taken from the user slice when the
+// column is < d_u and from the gathered pool row otherwise (eq. "eq: Kc", "eq: K": the
+// concat exists only as this column test).  Four rows are processed per step.  The score of
+// position 4*t + r ends up in lane 16*r + t, so softmax maxima and sums are wavefront
+// shuffles, and the weight is shuffled back to the row's sixteen lanes for the V pass.
+#include "ckv_internal.h"
+
+namespace {
+
+constexpr int kLanes = 64;
+constexpr int kGroup = 16;  // lanes per row
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kLanes));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kLanes);
+    return v;
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static __device__ __forceinline__ float up(float x) { return x; }
+    static __device__ __forceinline__ float down(float x) { return x; }
+};
+template <> struct Elem<uint16_t> {  // bfloat16 bit pattern
+    static __device__ __forceinline__ float up(uint16_t x) { return __uint_as_float((uint32_t)x << 16); }
+    static __device__ __forceinline__ uint16_t down(float f) {  // round to nearest even
+        uint32_t u = __float_as_uint(f);
+        if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40);
+        u += 0x7FFFu + ((u >> 16) & 1u);
+        return (uint16_t)(u >> 16);
+    }
+};
+
+template <typename T, int VEC> struct alignas(sizeof(T) * VEC) Pack { T v[VEC]; };
+
+template <typename T, int VEC>
+__device__ __forceinline__ void load_vec(float (&dst)[VEC], const T* src) {
+    Pack<T, VEC> p = *reinterpret_cast<const Pack<T, VEC>*>(src);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) dst[i] = Elem<T>::up(p.v[i]);
+}
+
+template <typename T, int VEC, int NCB, int MODE>
+__global__ __launch_bounds__(kLanes) void ckv_stream_kernel(ckv_args a) {
+    const ckv_item it = a.items[blockIdx.x];
+    const int lane = threadIdx.x;
+    const int r = lane >> 4, c = lane & 15;
+    const int d_u = a.d_u, d_a = a.d_a;
+    const int64_t hT = (int64_t)it.h * a.T + it.t0;
+    const int32_t* ik = a.idx_k + hT;
+    const int32_t* iv = a.idx_v + hT;
+    const T* uk = (const T*)a.user_k + hT * d_u;
+    const T* uv = (const T*)a.user_v + hT * d_u;
+    const T* pk = (const T*)a.pool_k + (int64_t)it.h * a.P * a.pool_ld;
+    const T* pv = (const T*)a.pool_v + (int64_t)it.h * a.P * a.pool_ld;
+    const int n = it.n;
+    const int slot_of_lane = 4 * c + r;  // position (within a tile) whose score this lane keeps
+
+    // column ownership: col[cb] = first final-K column of this lane in block cb (or -1)
+    int col[NCB];
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) {
+        int c0 = (cb * kGroup + c) * VEC;
+        col[cb] = c0 < d_a ? c0 : -1;
+    }
+
+    for (int j = 0; j < a.QB; ++j) {
+        const int qj = it.q0 + j;
+        if (qj >= a.Nq) break;
+        const int64_t qo = (((int64_t)it.b * a.H + it.h) * a.Nq + qj) * d_a;
+        const T* qp = (const T*)a.q + qo;
+        float qreg[NCB][VEC];
+        float acc[NCB][VEC];
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) { qreg[cb][v] = 0.f; acc[cb][v] = 0.f; }
+            if (col[cb] >= 0) load_vec<T, VEC>(qreg[cb], qp + col[cb]);
+        }
+        float m_run = -INFINITY, l_run = 0.f;
+
+        for (int t0 = 0; t0 < n; t0 += kLanes) {
+            const int nt = min(n - t0, kLanes);
+            const int myslot = min(slot_of_lane, nt - 1);
+            const int my_ik = a.d_g > 0 ? ik[t0 + myslot] : 0;
+            const int my_iv = a.d_g > 0 ? iv[t0 + myslot] : 0;
+            // ---- scores
+            float s_mine = 0.f;
+#pragma unroll 4
+            for (int t = 0; t < 16; ++t) {
+                const int pos = min(4 * t + r, nt - 1);
+                const int row = __shfl(my_ik, (lane & 48) | t, kLanes);
+                float part = 0.f;
+#pragma unroll
+                for (int cb = 0; cb < NCB; ++cb) {
+                    if (col[cb] >= 0) {
+                        float kv[VEC];
+                        const T* src = col[cb] < d_u ? uk + (int64_t)(t0 + pos) * d_u + col[cb]
+                                                     : pk + (int64_t)row * a.pool_ld + (col[cb] - d_u);
+                        load_vec<T, VEC>(kv, src);
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) part = fmaf(kv[v], qreg[cb][v], part);
+                    }
+                }
+#pragma unroll
+                for (int o = 8; o > 0; o >>= 1) part += __shfl_xor(part, o, kLanes);
+                if (c == t) s_mine = part;
+            }
+            // ---- weights
+            const bool valid = slot_of_lane < nt;
+            float w;
+            if (MODE == CKV_SOFTMAX) {
+                const float s = valid ? s_mine * a.scale : -INFINITY;
+                const float m_new = fmaxf(m_run, wave_max(s));
+                const float alpha = __expf(m_run - m_new);  // first tile: exp(-inf) = 0
+                w = valid ? __expf(s - m_new) : 0.f;
+                l_run = l_run * alpha + wave_sum(w);
+                m_run = m_new;
+#pragma unroll
+                for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) acc[cb][v] *= alpha;
+            } else {
+                const float s = s_mine * a.scale;
+                w = valid ? s / (1.f + __expf(-s)) : 0.f;
+            }
+            // ---- weighted sum of final V rows
+#pragma unroll 4
+            for (int t = 0; t < 16; ++t) {
+                const int pos = min(4 * t + r, nt - 1);
+                const int src_lane = (lane & 48) | t;
+                const int row = __shfl(my_iv, src_lane, kLanes);
+                const float wr = __shfl(w, src_lane, kLanes);
+#pragma unroll
+                for (int cb = 0; cb < NCB; ++cb) {
+                    if (col[cb] >= 0) {
+                        float vv[VEC];
+                        const T* src = col[cb] < d_u ? uv + (int64_t)(t0 + pos) * d_u + col[cb]
+                                                     : pv + (int64_t)row * a.pool_ld + (col[cb] - d_u);
+                        load_vec<T, VEC>(vv, src);
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) acc[cb][v] = fmaf(wr, vv[v], acc[cb][v]);
+                    }
+                }
+            }
+        }
+        // ---- fold the four row groups, then write
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                float x = acc[cb][v];
+                x += __shfl_xor(x, 16, kLanes);
+                x += __shfl_xor(x, 32, kLanes);
+                acc[cb][v] = x;
+            }
+        if (r == 0) {
+            if (it.part < 0) {
+                float norm;
+                if (MODE == CKV_SOFTMAX) norm = l_run > 0.f ? 1.f / l_run : 0.f;
+                else norm = it.n_total > 0 ? 1.f / (float)it.n_total : 0.f;
+                T* op = (T*)a.out + qo;
+#pragma unroll
+                for (int cb = 0; cb < NCB; ++cb)
+                    if (col[cb] >= 0) {
+                        Pack<T, VEC> p;
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) p.v[v] = Elem<T>::down(acc[cb][v] * norm);
+                        *reinterpret_cast<Pack<T, VEC>*>(op + col[cb]) = p;
+                    }
+            } else {
+                float* ws = a.partial + (int64_t)it.part * a.QB * (d_a + 2);
+#pragma unroll
+                for (int cb = 0; cb < NCB; ++cb)
+                    if (col[cb] >= 0)
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) ws[(int64_t)j * d_a + col[cb] + v] = acc[cb][v];
+                if (c == 0) {
+                    ws[(int64_t)a.QB * d_a + j] = m_run;
+                    ws[(int64_t)a.QB * d_a + a.QB + j] = l_run;
+                }
+            }
+        }
+    }
+}
+
+template <typename T, int VEC, int NCB>
+hipError_t launch_mode(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
+    dim3 grid(c->n_items), block(kLanes);
+    if (c->shape.mode == CKV_SOFTMAX)
+        hipLaunchKernelGGL((ckv_stream_kernel<T, VEC, NCB, CKV_SOFTMAX>), grid, block, 0, s, a);
+    else
+        hipLaunchKernelGGL((ckv_stream_kernel<T, VEC, NCB, CKV_SILU_OVER_N>), grid, block, 0, s, a);
+    return hipGetLastError();
+}
+
+template <typename T, int VEC>
+hipError_t launch_ncb(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
+    switch (c->ncb) {
+        case 1: return launch_mode<T, VEC, 1>(c, a, s);
+        case 2: return launch_mode<T, VEC, 2>(c, a, s);
+        case 4: return launch_mode<T, VEC, 4>(c, a, s);
+        case 8: return launch_mode<T, VEC, 8>(c, a, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace
+
+hipError_t ckv_launch_stream(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
+    if (c->n_items == 0) return hipSuccess;
+    if (c->shape.dtype == CKV_F32) {
+        switch (c->vec) {
+            case 1: return launch_ncb<float, 1>(c, a, s);
+            case 4: return launch_ncb<float, 4>(c, a, s);
+            default: return hipErrorInvalidValue;
+        }
+    }
+    switch (c->vec) {
+        case 1: return launch_ncb<uint16_t, 1>(c, a, s);
+        case 4: return launch_ncb<uint16_t, 4>(c, a, s);
+        case 8: return launch_ncb<uint16_t, 8>(c, a, s);
+        default: return hipErrorInvalidValue;
+    }
+}

@@ -1,0 +1,200 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element."""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import oracle
+from paper_2601_19178_amd import workloads as wl
+from tests.parity import check
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2601_19178_amd import ckv, session
+    return ckv, session
+
+
+def make(lengths, dtype, mode, d_a, d_u, H, P, Nq, seed=11, idx="uniform", **kw):
+    lengths = np.asarray(lengths, dtype=np.int32)
+    return wl.make(B=len(lengths), L=None, H=H, d_a=d_a, d_u=d_u, P=P, idx=idx, Nq=Nq, mode=mode, dtype=dtype,
+                   sigma_pool=d_a ** -0.5, seed=seed, lengths=lengths, **kw)
+
+
+def run_and_check(gpu, w, what, users=None, expect_variant=None):
+    ckv, session = gpu
+    say(f"[case] {what}: B={w['B']} H={w['H']} d_g={w['d_g']} d_u={w['d_u']} P={w['P']} Nq={w['Nq']} "
+        f"dtype={w['dtype']} mode={w['mode']} T={int(w['lengths'].sum())}")
+    with session.Session(w) as s:
+        variant = ckv.ckv_variant(s.cache)
+        say(f"  variant {variant}")
+        if expect_variant:
+            assert variant.startswith(expect_variant), variant
+        s.attend()
+        out = s.output()
+    ref = oracle.attend(w, users=users)
+    norm = check(out, ref, w["dtype"], rows=users, what=what)
+    say(f"  ok, norm-wise error {norm:.3e}")
+    return out
+
+
+RAGGED = (5, 1, 0, 9, 64, 2, 63, 65, 128, 200, 0, 331)
+
+
+# ---------------------------------------------------------------------------------------------
+# packed layout and reconstructed rows: bit exact
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+def test_pack_and_reconstruct_bit_exact(gpu, dtype):
+    ckv, session = gpu
+    w = make(RAGGED, dtype, wl.SOFTMAX, d_a=24, d_u=3, H=3, P=101, Nq=2, pool_ld=29)
+    say(f"[case] reconstruct dtype={dtype}")
+    with session.Session(w) as s:
+        idx, uk, uv = s.packed_views()
+        k_full, v_full = s.reconstruct()
+        stored = ckv.ckv_cache_stored_bytes(s.cache)
+    np.testing.assert_array_equal(idx[0], w["idx_k"].T)
+    np.testing.assert_array_equal(idx[1], w["idx_v"].T)
+    np.testing.assert_array_equal(uk, w["user_k"].transpose(1, 0, 2))
+    np.testing.assert_array_equal(uv, w["user_v"].transpose(1, 0, 2))
+    ok, ov = oracle.reconstruct(w)                       # [T][H][d_a]
+    np.testing.assert_array_equal(k_full, ok.transpose(1, 0, 2))
+    np.testing.assert_array_equal(v_full, ov.transpose(1, 0, 2))
+    T = int(w["lengths"].sum())
+    _, _, sb, _ = oracle.cache_size(T, w["H"], w["d_g"], w["d_u"], dtype)
+    assert stored == sb
+
+
+# ---------------------------------------------------------------------------------------------
+# streaming kernel (few queries, any shape)
+def test_config1(gpu):
+    run_and_check(gpu, wl.config("cfg1"), "cfg1", expect_variant="stream_f32_v4")
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+@pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
+def test_stream_ragged(gpu, dtype, mode):
+    w = make(RAGGED, dtype, mode, d_a=64, d_u=8, H=2, P=300, Nq=1)
+    run_and_check(gpu, w, f"stream ragged dtype={dtype} mode={mode}", expect_variant="stream")
+
+
+@pytest.mark.parametrize("dtype,d_a,d_u,pool_ld,Nq", [
+    (wl.F32, 16, 3, 13, 3),      # unaligned everything: scalar path
+    (wl.BF16, 40, 5, 37, 2),
+    (wl.F32, 200, 8, 192, 1),    # several column blocks
+    (wl.BF16, 96, 16, 80, 5),    # 8-wide bf16 vectors, Nq not a power of two
+    (wl.F32, 12, 0, 12, 2),      # d_u = 0: pure pool attention
+    (wl.F32, 12, 12, 0, 2),      # d_g = 0: ordinary attention over the user K/V
+])
+def test_stream_shapes(gpu, dtype, d_a, d_u, pool_ld, Nq):
+    w = make(RAGGED, dtype, wl.SOFTMAX, d_a=d_a, d_u=d_u, H=2, P=77, Nq=Nq, pool_ld=pool_ld)
+    run_and_check(gpu, w, f"stream shape d_a={d_a} d_u={d_u} ld={pool_ld}", expect_variant="stream")
+
+
+def test_stream_split_history(gpu):
+    # one long history among few users: cut into pieces and merged
+    w = make((5000, 70, 2300), wl.F32, wl.SOFTMAX, d_a=64, d_u=8, H=2, P=500, Nq=2)
+    run_and_check(gpu, w, "stream split softmax")
+    w = make((5000, 70, 2300), wl.BF16, wl.SILU_OVER_N, d_a=64, d_u=8, H=2, P=500, Nq=2)
+    run_and_check(gpu, w, "stream split silu")
+
+
+@pytest.mark.parametrize("name", ["cfg2_f32", "cfg2_bf16"])
+def test_config2_full(gpu, name):
+    run_and_check(gpu, wl.config(name), name, expect_variant="stream")
+
+
+# ---------------------------------------------------------------------------------------------
+# matrix-core kernel (many queries, bf16)
+MFMA_LENGTHS = (1, 31, 32, 33, 64, 65, 0, 127, 200, 1500, 96, 2)
+
+
+@pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
+@pytest.mark.parametrize("d_a,d_u,Nq", [(64, 4, 64), (64, 2, 16), (64, 8, 32), (128, 8, 128), (128, 8, 40),
+                                         (64, 3, 20), (128, 16, 64), (64, 0, 16), (128, 24, 100), (64, 8, 200)])
+def test_mfma_ragged(gpu, mode, d_a, d_u, Nq):
+    w = make(MFMA_LENGTHS, wl.BF16, mode, d_a=d_a, d_u=d_u, H=2, P=700, Nq=Nq)
+    run_and_check(gpu, w, f"mfma ragged d_a={d_a} d_u={d_u} Nq={Nq} mode={mode}", expect_variant="mfma")
+
+
+@pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
+def test_mfma_split_history(gpu, mode):
+    w = make((5000, 70, 2300, 1024, 1025), wl.BF16, mode, d_a=128, d_u=8, H=2, P=5000, Nq=128)
+    run_and_check(gpu, w, f"mfma split mode={mode}", expect_variant="mfma")
+
+
+def test_mfma_all_users_is_ordinary_attention_when_dg_zero(gpu):
+    w = make(MFMA_LENGTHS, wl.BF16, wl.SOFTMAX, d_a=64, d_u=64, H=1, P=1, Nq=16)
+    run_and_check(gpu, w, "mfma d_g=0", expect_variant="mfma")
+
+
+def test_mfma_large_scores_softmax(gpu):
+    # big logits exercise the running-maximum bookkeeping (lazy rescale threshold)
+    w = make((700, 129), wl.BF16, wl.SOFTMAX, d_a=64, d_u=8, H=1, P=300, Nq=32, sigma_q=6.0, scale=1.0)
+    run_and_check(gpu, w, "mfma large scores", expect_variant="mfma")
+
+
+# ---------------------------------------------------------------------------------------------
+# full-size workloads, in the launch configuration the benchmark times; oracle on sampled users
+def sampled_users(B, k, seed):
+    return np.sort(np.random.default_rng(seed).choice(B, size=k, replace=False)).astype(np.int32)
+
+
+def test_config3_full(gpu):
+    w = wl.config("cfg3")
+    run_and_check(gpu, w, "cfg3", users=sampled_users(w["B"], 24, 3), expect_variant="mfma_bf16_d64_w2")
+
+
+def test_config4_full(gpu):
+    w = wl.config("cfg4")
+    users = sampled_users(w["B"], 3, 4)
+    users = np.unique(np.concatenate([users, [int(np.argmax(w["lengths"])), int(np.argmin(w["lengths"]))]])).astype(np.int32)
+    run_and_check(gpu, w, "cfg4", users=users, expect_variant="mfma_bf16_d128_w4")
+
+
+def test_config5_full(gpu):
+    w = wl.config("cfg5")
+    run_and_check(gpu, w, "cfg5", users=sampled_users(w["B"], 48, 5), expect_variant="mfma_bf16_d64_w1")
+
+
+# ---------------------------------------------------------------------------------------------
+# error paths that need the device
+def test_out_of_range_index_is_rejected(gpu):
+    ckv, session = gpu
+    w = make((10, 20), wl.F32, wl.SOFTMAX, d_a=16, d_u=4, H=2, P=50, Nq=1)
+    w["idx_v"][13, 1] = 50
+    with pytest.raises(ckv.CkvError) as e:
+        session.Session(w)
+    assert e.value.code == ckv.CKV_ERR_INDEX and "position 13 head 1" in str(e.value)
+    w["idx_v"][13, 1] = -1
+    with pytest.raises(ckv.CkvError):
+        session.Session(w)
+
+
+def test_all_histories_empty(gpu):
+    w = make((0, 0, 0), wl.BF16, wl.SOFTMAX, d_a=64, d_u=8, H=2, P=10, Nq=16)
+    out = run_and_check(gpu, w, "all empty")
+    assert np.all(out == 0)
+    w = make((0, 0), wl.F32, wl.SOFTMAX, d_a=16, d_u=4, H=1, P=10, Nq=1)
+    out = run_and_check(gpu, w, "all empty stream")
+    assert np.all(out == 0)
+
+
+def test_repeated_calls_are_deterministic(gpu):
+    ckv, session = gpu
+    w = make((5000, 70, 2300), wl.BF16, wl.SOFTMAX, d_a=128, d_u=8, H=2, P=5000, Nq=128)
+    with session.Session(w) as s:
+        s.attend()
+        a = s.output().copy()
+        s.out.fill_(float("nan"))
+        s.attend()
+        b = s.output()
+    np.testing.assert_array_equal(a, b)
