@@ -1,0 +1,168 @@
+#!/usr/bin/env python3
+"""Benchmark of the CollectiveKV decode hot path (fused gather + concat + attend) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4] [--also cfg2_f32,cfg2_bf16,cfg3]
+
+One step = one ckv_attend over the whole batch of the workload (main kernel + merge of split
+histories), inputs resident in HBM.  Prints ONE JSON line:
+  value        users/s = B / step time (events on the launch stream around exactly K steps)
+  roofline     algorithmic bytes E per launch / mean duration of the main attention kernel
+               (event pairs recorded by the library around each of the K timed launches),
+               against the 8 TB/s HBM peak
+  cpu_baseline the CPU oracle on a sample of the same workload's users, on this host's cores
+  also         the same figures for the other workloads (not the headline)
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+METRIC = "users/sec and effective HBM GB/s (% of peak) for fused gather+concat+attend"
+DESCRIBE = {
+    "cfg1": "config 1 tiny: B=4 L=50 H=1 d=56+8 P=256 Nq=1 softmax fp32",
+    "cfg2_f32": "config 2 SASRec-like: B=1024 L=200 H=2 d=56+8 P=4096 Nq=1 softmax fp32",
+    "cfg2_bf16": "config 2 SASRec-like: B=1024 L=200 H=2 d=56+8 P=4096 Nq=1 softmax bf16",
+    "cfg3": "config 3 HSTU-style: B=512 L=1024 H=4 d=60+4 P=16384 Zipf(1.1) Nq=64 SiLU/L bf16",
+    "cfg4": "config 4 long ragged: B=128 L~U[2048,8192] H=8 d=120+8 P=65536 Nq=128 softmax bf16",
+    "cfg5": "config 5 large batch: B=8192 L~U[512,2048] H=4 d=62+2 P=1048576 Zipf(1.05) Nq=16 softmax bf16",
+}
+
+
+def compulsory_bytes(w, ab):
+    """Compressed stream + every distinct touched pool row once + q + out."""
+    e = 4 if w["dtype"] == 0 else 2
+    rows = 0
+    for h in range(w["H"]):
+        rows += len(np.unique(w["idx_k"][:, h])) + len(np.unique(w["idx_v"][:, h]))
+    return ab["compressed"] + rows * w["d_g"] * e + ab["q_out"]
+
+
+def measure(name, steps, warmup, with_compulsory=True):
+    import torch
+    from paper_2601_19178_amd import ckv, session, workloads as wl
+
+    w = wl.config(name)
+    ab = wl.algorithmic_bytes(w)
+    t0 = time.time()
+    s = session.Session(w)
+    torch.cuda.synchronize()
+    build_s = time.time() - t0
+    for _ in range(warmup):
+        s.attend()
+    torch.cuda.synchronize()
+    ckv.ckv_set_timing(s.cache, steps)
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for _ in range(steps):
+        s.attend()
+    stop.record()
+    torch.cuda.synchronize()
+    ms_step = start.elapsed_time(stop) / steps
+    ms_kernel = ckv.ckv_kernel_ms(s.cache)
+    ckv.ckv_set_timing(s.cache, 0)
+    res = {
+        "workload": name,
+        "describe": DESCRIBE[name],
+        "variant": ckv.ckv_variant(s.cache),
+        "B": w["B"], "T": int(w["lengths"].sum()),
+        "ms_per_step": ms_step,
+        "kernel_ms": ms_kernel,
+        "users_per_s": w["B"] / (ms_step * 1e-3),
+        "E_bytes": ab["E"],
+        "E_GBps_step": ab["E"] / (ms_step * 1e-3) / 1e9,
+        "E_GBps_kernel": ab["E"] / (ms_kernel * 1e-3) / 1e9,
+        "frac_of_hbm_peak": ab["E"] / (ms_kernel * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "build_cache_s": build_s,
+    }
+    if with_compulsory:
+        res["C_bytes"] = compulsory_bytes(w, ab)
+        res["C_GBps_kernel"] = res["C_bytes"] / (ms_kernel * 1e-3) / 1e9
+    return res, w, s
+
+
+def cpu_baseline(w, budget_s=15.0):
+    """The oracle as it stands, timed on a bounded sample of users (all heads, all queries)."""
+    from oracle import oracle
+    threads = oracle.threads()
+    order = np.random.default_rng(0).permutation(w["B"]).astype(np.int32)
+    n = min(w["B"], max(1, threads // max(1, w["H"])))
+    t0 = time.time()
+    oracle.attend(w, users=order[:n])
+    dt = time.time() - t0
+    if dt < budget_s / 3 and n < w["B"]:
+        n2 = int(min(w["B"], max(n + 1, n * budget_s / max(dt, 1e-3))))
+        t0 = time.time()
+        oracle.attend(w, users=order[:n2])
+        dt, n = time.time() - t0, n2
+    return {"value": n / dt, "unit": "users/s", "cores": threads, "kind": "oracle",
+            "sample": f"{n} of {w['B']} users (seeded choice), all heads and queries, {dt:.1f} s wall"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg4", choices=sorted(DESCRIBE))
+    ap.add_argument("--also", default="cfg2_f32,cfg2_bf16,cfg3", help="comma list of further workloads ('' for none)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1")
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the hot path has no CPU fallback")
+
+    head, w, sess = measure(args.workload, args.steps, args.warmup)
+    base = None if args.no_cpu_baseline else cpu_baseline(w)
+    sess.close()
+    del w, sess
+    also = []
+    for name in [x for x in args.also.split(",") if x and x != args.workload]:
+        r, w2, s2 = measure(name, args.steps, args.warmup)
+        s2.close()
+        del w2, s2
+        also.append(r)
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get(args.workload, {}).get("bytes_per_launch")
+    line = {
+        "metric": METRIC,
+        "value": head["users_per_s"],
+        "unit": "users/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if "bf16" in head["variant"] else "f32",
+        "data": "synthetic (seeded; shapes and index/value distributions of BASELINE.json's configs)",
+        "config": {"workload": head["describe"], "name": head["workload"], "kernel": head["variant"],
+                   "B": head["B"], "T": head["T"]},
+        "effective_GBps": head["E_GBps_step"],
+        "pct_of_hbm_peak": 100.0 * head["E_GBps_step"] / HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "achieved": head["E_GBps_kernel"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": head["frac_of_hbm_peak"], "traffic": traffic,
+                     "kernel": head["variant"], "kernel_ms": head["kernel_ms"], "E_bytes": head["E_bytes"],
+                     "C_bytes": head.get("C_bytes"), "C_GBps": head.get("C_GBps_kernel")},
+        "cpu_baseline": base,
+        "also": also,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -146,15 +146,16 @@ const char* ckv_last_error(void);
 
 /*
  * Measurement helpers.
- * ckv_set_timing(cache, 1) makes every following ckv_attend on this handle bracket its main
- * attention kernel with HIP events on the launch stream; ckv_kernel_ms then synchronises the
- * last pair and returns the elapsed milliseconds of that one kernel launch (negative if
- * none was recorded).  ckv_variant names the kernel family the handle dispatches to.
+ * ckv_set_timing(cache, n) with n > 0 makes every following ckv_attend on this handle bracket
+ * its main attention kernel (not the merge) with a pair of HIP events on the launch stream,
+ * kept in a ring of n pairs; n = 0 switches it off.  ckv_kernel_ms synchronises the recorded
+ * pairs and returns the mean elapsed milliseconds per launch over the last min(calls, n)
+ * launches (negative if none).  ckv_variant names the kernel family the handle dispatches to.
  * ckv_copy enqueues a plain device-to-device copy kernel of nbytes (16-byte aligned device
  * pointers), used to calibrate hardware byte counters against a transfer of known size and
  * to read the packed cache back in tests.
  */
-int ckv_set_timing(ckv_cache* cache, int enable);
+int ckv_set_timing(ckv_cache* cache, int pairs);
 float ckv_kernel_ms(ckv_cache* cache);
 const char* ckv_variant(const ckv_cache* cache);
 int ckv_copy(void* dst, const void* src, size_t nbytes, void* stream);

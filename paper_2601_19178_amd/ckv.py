@@ -8,6 +8,8 @@ import ctypes
 import os
 
 import numpy as np
+import torch  # noqa: F401  -- must come first: libckv.so has to bind to the HIP runtime torch ships,
+#                              or torch's device pointers and streams would belong to another runtime.
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIBPATH = os.path.join(_HERE, "libckv.so")

@@ -257,8 +257,8 @@ void destroy(ckv_cache* c) {
     (void)hipFree(c->d_items);
     (void)hipFree(c->d_merge);
     (void)hipFree(c->d_partial);
-    if (c->ev0) (void)hipEventDestroy(c->ev0);
-    if (c->ev1) (void)hipEventDestroy(c->ev1);
+    for (int i = 0; i < 2 * c->timing; ++i) (void)hipEventDestroy(c->ev[i]);
+    delete[] c->ev;
     delete c;
 }
 
@@ -383,8 +383,6 @@ int ckv_build_cache(const ckv_shape* shape, const int32_t* lengths, const int32_
         CKV_HIP(hipMemcpyAsync(c->d_merge, merges.data(), sizeof(ckv_merge) * merges.size(), hipMemcpyHostToDevice, st));
         CKV_HIP(hipMalloc((void**)&c->d_partial, sizeof(float) * (size_t)c->n_parts * c->QB * (size_t)(d_a + 2)));
     }
-    CKV_HIP(hipEventCreate(&c->ev0));
-    CKV_HIP(hipEventCreate(&c->ev1));
     CKV_HIP(hipStreamSynchronize(st));
 
 done:
@@ -446,16 +444,17 @@ int ckv_attend(const ckv_cache* c, const void* pool_k, const void* pool_v, const
     a.scale = s.scale;
     ckv_cache* mc = const_cast<ckv_cache*>(c);
     hipError_t e;
+    const int slot = c->timing ? (int)(c->ev_count % c->timing) : 0;
     if (c->timing) {
-        e = hipEventRecord(c->ev0, st);
+        e = hipEventRecord(c->ev[2 * slot], st);
         if (e != hipSuccess) return fail(CKV_ERR_HIP, "ckv_attend: hipEventRecord: %s", hipGetErrorString(e));
     }
     e = c->family == CKV_K_MFMA ? ckv_launch_mfma(c, a, st) : ckv_launch_stream(c, a, st);
     if (e != hipSuccess) return fail(CKV_ERR_HIP, "ckv_attend: kernel launch (%s): %s", c->variant, hipGetErrorString(e));
     if (c->timing) {
-        e = hipEventRecord(c->ev1, st);
+        e = hipEventRecord(c->ev[2 * slot + 1], st);
         if (e != hipSuccess) return fail(CKV_ERR_HIP, "ckv_attend: hipEventRecord: %s", hipGetErrorString(e));
-        mc->ev_valid = 1;
+        mc->ev_count++;
     }
     if (c->n_merge > 0) {
         const int d_a = a.d_a;
@@ -511,19 +510,41 @@ int ckv_reconstruct(const ckv_cache* c, const void* pool_k, const void* pool_v, 
 
 void ckv_free(ckv_cache* c) { destroy(c); }
 
-int ckv_set_timing(ckv_cache* c, int enable) {
+int ckv_set_timing(ckv_cache* c, int pairs) {
     if (!c) return fail(CKV_ERR_NULL, "ckv_set_timing: cache is NULL");
-    c->timing = enable ? 1 : 0;
-    c->ev_valid = 0;
+    if (pairs < 0 || pairs > 4096) return fail(CKV_ERR_SHAPE, "ckv_set_timing: pairs must be in [0, 4096]");
+    for (int i = 0; i < 2 * c->timing; ++i) (void)hipEventDestroy(c->ev[i]);
+    delete[] c->ev;
+    c->ev = nullptr;
+    c->timing = 0;
+    c->ev_count = 0;
+    if (pairs == 0) return CKV_OK;
+    c->ev = new (std::nothrow) hipEvent_t[2 * (size_t)pairs];
+    if (!c->ev) return fail(CKV_ERR_HIP, "ckv_set_timing: out of host memory");
+    for (int i = 0; i < 2 * pairs; ++i) {
+        hipError_t e = hipEventCreate(&c->ev[i]);
+        if (e != hipSuccess) {
+            for (int j = 0; j < i; ++j) (void)hipEventDestroy(c->ev[j]);
+            delete[] c->ev;
+            c->ev = nullptr;
+            return fail(CKV_ERR_HIP, "ckv_set_timing: hipEventCreate: %s", hipGetErrorString(e));
+        }
+    }
+    c->timing = pairs;
     return CKV_OK;
 }
 
 float ckv_kernel_ms(ckv_cache* c) {
-    if (!c || !c->ev_valid) return -1.f;
-    float ms = -1.f;
-    if (hipEventSynchronize(c->ev1) != hipSuccess) return -1.f;
-    if (hipEventElapsedTime(&ms, c->ev0, c->ev1) != hipSuccess) return -1.f;
-    return ms;
+    if (!c || !c->timing || c->ev_count == 0) return -1.f;
+    const int n = (int)std::min<long long>(c->ev_count, c->timing);
+    double sum = 0;
+    for (int i = 0; i < n; ++i) {
+        float ms = 0.f;
+        if (hipEventSynchronize(c->ev[2 * i + 1]) != hipSuccess) return -1.f;
+        if (hipEventElapsedTime(&ms, c->ev[2 * i], c->ev[2 * i + 1]) != hipSuccess) return -1.f;
+        sum += ms;
+    }
+    return (float)(sum / n);
 }
 
 int ckv_copy(void* dst, const void* src, size_t nbytes, void* stream) {

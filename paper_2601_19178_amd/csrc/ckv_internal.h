@@ -64,10 +64,10 @@ struct ckv_cache {
     ckv_item* d_items;
     ckv_merge* d_merge;
     float* d_partial;
-    // timing
-    int timing;
-    hipEvent_t ev0, ev1;
-    int ev_valid;
+    // timing: ring of event pairs around the main kernel, filled while timing > 0
+    int timing;            // number of pairs in the ring (0 = off)
+    long long ev_count;    // launches recorded since timing was switched on
+    hipEvent_t* ev;        // 2 * timing events
     char variant[96];
 };
 
