@@ -2,6 +2,7 @@
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <numeric>
@@ -164,6 +165,7 @@ void build_work(ckv_cache* c, const int32_t* lengths, const std::vector<int64_t>
     const int nqb = (s.Nq + c->QB - 1) / c->QB;
     int wg_per_cu = 8;
     if (c->family == CKV_K_MFMA) wg_per_cu = std::max(1, ckv_mfma_occupancy(s.d_g + s.d_u, c->nw, c->tp, s.mode));
+    if (c->family == CKV_K_DMA) wg_per_cu = std::max(1, ckv_dma_occupancy(s.d_g + s.d_u, c->nw, s.mode));
     const int64_t slots = (int64_t)cus * wg_per_cu;
     const int64_t n_units = (int64_t)s.B * s.H * nqb;
     const int64_t total_ph = c->T * s.H * nqb;
@@ -227,9 +229,22 @@ void choose_variant(ckv_cache* c) {
     const ckv_shape& s = c->shape;
     const int d_a = s.d_g + s.d_u;
     c->family = CKV_K_STREAM;
-    if (s.dtype == CKV_BF16 && (d_a == 64 || d_a == 128) && s.Nq >= 8 && (s.d_g == 0 || s.pool_ld % 8 == 0)) {
+    // the matrix-core kernels take the running maximum before scaling, which needs scale > 0
+    if (s.dtype == CKV_BF16 && (d_a == 64 || d_a == 128) && s.Nq >= 8 && (s.d_g == 0 || s.pool_ld % 8 == 0) &&
+        (s.mode == CKV_SILU_OVER_N || s.scale > 0.f)) {
         const int nw = s.Nq <= 32 ? 1 : (s.Nq <= 64 ? 2 : 4);
-        const int tp = 64;
+        const char* impl = getenv("CKV_MFMA_IMPL");  // tuning knob: "staged" forces the register-staged kernel
+        const int nui = s.d_g > 0 ? ckv_dma_nui(d_a, nw, s.d_u) : -1;
+        if (nui >= 0 && !(impl && strcmp(impl, "staged") == 0)) {
+            c->family = CKV_K_DMA;
+            c->nw = nw;
+            c->tp = 32;
+            c->nui = nui;
+            c->QB = 32 * nw;
+            snprintf(c->variant, sizeof c->variant, "mfma_dma_bf16_d%d_w%d_%s", d_a, nw, s.mode == CKV_SOFTMAX ? "softmax" : "silu");
+            return;
+        }
+        const int tp = (d_a == 128 && nw == 1) ? 32 : 64;
         if (ckv_mfma_supported(d_a, nw, tp)) {
             c->family = CKV_K_MFMA;
             c->nw = nw;
@@ -449,7 +464,7 @@ int ckv_attend(const ckv_cache* c, const void* pool_k, const void* pool_v, const
         e = hipEventRecord(c->ev[2 * slot], st);
         if (e != hipSuccess) return fail(CKV_ERR_HIP, "ckv_attend: hipEventRecord: %s", hipGetErrorString(e));
     }
-    e = c->family == CKV_K_MFMA ? ckv_launch_mfma(c, a, st) : ckv_launch_stream(c, a, st);
+    e = c->family == CKV_K_DMA ? ckv_launch_dma(c, a, st) : (c->family == CKV_K_MFMA ? ckv_launch_mfma(c, a, st) : ckv_launch_stream(c, a, st));
     if (e != hipSuccess) return fail(CKV_ERR_HIP, "ckv_attend: kernel launch (%s): %s", c->variant, hipGetErrorString(e));
     if (c->timing) {
         e = hipEventRecord(c->ev[2 * slot + 1], st);

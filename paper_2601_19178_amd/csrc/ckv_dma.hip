@@ -1,0 +1,407 @@
+// Matrix-core gather-concat-attend kernel with direct global->LDS gathers (bf16 storage, fp32
+// accumulation, d_a = 64 or 128, even d_u <= 8).
+//
+// Same mathematics and MFMA operand layouts as the register-staged kernel next to it
+// (S^T = K Q^T, O^T += V^T P^T, one query per lane), but the final K and V rows of a tile are
+// assembled in LDS without passing through registers:
+//   * pool rows are gathered with global_load_lds_dwordx4 (16 bytes per lane straight into
+//     LDS; the instruction puts lane l at M0 + 16*l, so one wavefront fills 1 KiB of
+//     consecutive rows).  The row layout inside LDS is [pool columns | user columns],
+//     unpadded, with the 16-byte chunks of row p stored at slot (chunk XOR f(p)) so that the
+//     operand reads stay free of bank conflicts; the lane chooses which chunk it fetches,
+//     so the swizzle costs nothing on the way in.
+//   * the pool indices of a tile and its user-specific slices are fetched the same way
+//     (global_load_lds_dword) into small staging areas; the "concat" of the paper
+//     (eq. "eq: K") is an LDS->LDS copy of the user columns into the tail of each row.
+// Tiles are 32 positions; a ring of 4 stages keeps two to three tiles of gathers in flight
+// per workgroup while one tile is computed.  The loads are issued from inline asm and
+// waited for with explicit s_waitcnt vmcnt(N): every wavefront issues the same number of
+// loads per iteration (positions past the end of the history are clamped to the last one),
+// so N is a constant.
+#include "ckv_internal.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((address_space(3))) unsigned char lds_u8;
+typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
+typedef __attribute__((address_space(3))) uint32_t lds_u32;
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kLazy = 8.f;
+constexpr int TP = 32;  // positions per tile
+constexpr int NS = 4;   // stages in the ring
+
+__device__ __forceinline__ float other_half(float x) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return threadIdx.x & 32 ? __uint_as_float(r[0]) : __uint_as_float(r[1]);
+}
+__device__ __forceinline__ uint16_t f2bf(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
+
+// 16 bytes per lane, global -> LDS[lds_base + 16*lane].  lds_base is wavefront-uniform.
+__device__ __forceinline__ void dma16(const void* g, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_base) : "memory");
+}
+// 4 bytes per lane, global -> LDS[lds_base + 4*lane].
+__device__ __forceinline__ void dma4(const void* g, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(g), "s"(lds_base) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// wait until at most `base + nui` vector-memory operations are outstanding (nui in {0,1,2,4})
+template <int BASE>
+__device__ __forceinline__ void wait_vm_plus(int nui) {
+    if (nui == 0) wait_vm<BASE>();
+    else if (nui == 1) wait_vm<BASE + 1>();
+    else if (nui == 2) wait_vm<BASE + 2>();
+    else wait_vm<BASE + 4>();
+}
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+__device__ __forceinline__ int fk(int p) { return p & 7; }         // K rows: 16-byte row reads
+__device__ __forceinline__ int fv(int p) { return (p & 3) << 1; }  // V rows: transpose reads
+
+template <int DA, int NW>
+struct Geo {
+    static constexpr int NT = NW * 64;
+    static constexpr int CH = DA / 8;            // 16-byte chunks per row
+    static constexpr int ROWB = DA * 2;          // bytes per row
+    static constexpr int RPI = 64 / CH;          // rows filled by one wavefront instruction
+    static constexpr int NI = TP / RPI / NW;     // gather instructions per wavefront, K and V each
+    static constexpr int NUI_MAX = 4 / NW;       // user-slice instructions per wavefront (d_u <= 8)
+    static constexpr int KV = TP * ROWB;         // bytes of the K (or V) rows of a stage
+    static constexpr int USER = NW * 64 * 4 * NUI_MAX;  // bytes of the user staging of a stage (1 KiB)
+    static constexpr int STAGE = 2 * KV + USER;
+    static constexpr int IDX = 256;              // bytes of one index slot: 32 x I_k, 32 x I_v
+    static constexpr int LDS = NS * STAGE + NW * 2 * IDX;
+    static constexpr int PE = 256 / NT;          // user dwords copied per lane in the concat step
+    static_assert(NI >= 1, "tile too small for this many wavefronts");
+};
+
+template <int DA, int NW, int MODE>
+__global__ __launch_bounds__(NW * 64, 2) void ckv_dma_kernel(ckv_args a, int nui) {
+    using G = Geo<DA, NW>;
+    constexpr int NKK = DA / 16, NDT = DA / 32;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_u8*)smem;
+
+    const ckv_item it = a.items[blockIdx.x];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int qn = lane & 31, hh = lane >> 5;
+    const int d_g = a.d_g, d_u = a.d_u;
+    const int n = it.n;
+
+    const int64_t hT = (int64_t)it.h * a.T + it.t0;
+    const int32_t* __restrict__ ik = a.idx_k + hT;
+    const int32_t* __restrict__ iv = a.idx_v + hT;
+    const uint32_t* __restrict__ uk32 = (const uint32_t*)((const uint16_t*)a.user_k + hT * d_u);
+    const uint32_t* __restrict__ uv32 = (const uint32_t*)((const uint16_t*)a.user_v + hT * d_u);
+    const unsigned char* __restrict__ pk = (const unsigned char*)a.pool_k + (int64_t)it.h * a.P * a.pool_ld * 2;
+    const unsigned char* __restrict__ pv = (const unsigned char*)a.pool_v + (int64_t)it.h * a.P * a.pool_ld * 2;
+    const uint32_t row_bytes = (uint32_t)a.pool_ld * 2;
+
+    // ---- queries of this lane in kernel column order [pool | user], as B operands
+    const int qj = it.q0 + wave * 32 + qn;
+    const bool qok = qj < a.Nq;
+    const int64_t qo = (((int64_t)it.b * a.H + it.h) * a.Nq + (qok ? qj : 0)) * DA;
+    bf16x8 qreg[NKK];
+    {
+        const uint16_t* qp = (const uint16_t*)a.q + qo;
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int ci = 16 * kk + 8 * hh + e;
+                const int pc = ci < d_g ? ci + d_u : ci - d_g;
+                const uint16_t x = qp[pc];
+                qreg[kk][e] = __builtin_bit_cast(__bf16, qok ? x : (uint16_t)0);
+            }
+        // make the compiler finish these loads here: a wait for them inside the tile loop would
+        // also drain the asynchronous gathers it does not know about
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk) asm volatile("" : "+v"(qreg[kk]));
+    }
+
+    f32x16 oacc[NDT];
+#pragma unroll
+    for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
+    float m_ref = -INFINITY, lsum = 0.f;
+    const float sc = MODE == CKV_SOFTMAX ? a.scale * kLog2e : a.scale;
+
+    const int ntiles = (n + TP - 1) / TP;
+    if (ntiles > 0) {
+        // ---- per-lane constants of the gather: instruction i of this wavefront fills rows
+        //      (i*NW + wave)*RPI .. +RPI; this lane owns row gp[i] and LDS slot gslot of it.
+        const int gslot = lane % G::CH;
+        int gp[G::NI];
+        uint32_t gk_off[G::NI], gv_off[G::NI];  // byte offset of the chunk this lane fetches, within a pool row
+#pragma unroll
+        for (int i = 0; i < G::NI; ++i) {
+            gp[i] = (i * NW + wave) * G::RPI + lane / G::CH;
+            int ck = gslot ^ fk(gp[i]);
+            int cv = gslot ^ fv(gp[i]);
+            if (ck * 8 >= d_g) ck = 0;  // a pure user chunk: fetch something valid, the concat overwrites it
+            if (cv * 8 >= d_g) cv = 0;
+            gk_off[i] = ck * 16;
+            gv_off[i] = cv * 16;
+        }
+        // ---- per-lane constants of the user staging: dword j of the tile's [K_u | V_u] block
+        const int udw = 16 * d_u;  // dwords of one tile's K_u (and of its V_u)
+        int up[G::NUI_MAX], uoff[G::NUI_MAX];
+        bool uisv[G::NUI_MAX];
+#pragma unroll
+        for (int u = 0; u < G::NUI_MAX; ++u) {
+            int j = (u * NW + wave) * 64 + lane;
+            if (j >= 2 * udw) j = 0;
+            uisv[u] = j >= udw;
+            if (uisv[u]) j -= udw;
+            const int hd = d_u > 0 ? d_u >> 1 : 1;
+            up[u] = j / hd;
+            uoff[u] = j - up[u] * hd;
+        }
+        // ---- per-lane constants of the concat step: copy dword e of the staging into its row
+        uint32_t csrc[G::PE], cdst[G::PE];
+        bool cok[G::PE];
+#pragma unroll
+        for (int x = 0; x < G::PE; ++x) {
+            int e = x * G::NT + tid;
+            cok[x] = e < 2 * udw;
+            if (!cok[x]) e = 0;
+            csrc[x] = 2 * G::KV + e * 4;
+            const bool isv = e >= udw;
+            if (isv) e -= udw;
+            const int hd = d_u > 0 ? d_u >> 1 : 1;
+            const int p = e / hd, col = d_g + 2 * (e - p * hd);
+            const int slot = (col >> 3) ^ (isv ? fv(p) : fk(p));
+            cdst[x] = (isv ? G::KV : 0) + p * G::ROWB + slot * 16 + (col & 7) * 2;
+        }
+        // ---- per-lane constants of the operand reads
+        const uint32_t krow = qn * G::ROWB;
+        const int kx = fk(qn);
+        const int g16 = lane >> 4, s16 = lane & 15;
+        const uint32_t vrow = G::KV + (4 * hh + (s16 >> 2)) * G::ROWB + (s16 & 1) * 8;
+        const int vc = 2 * (g16 & 1) + ((s16 & 3) >> 1), vx = fv(s16 >> 2);
+
+        const uint32_t idx_lds = lds0 + NS * G::STAGE + wave * 2 * G::IDX;
+
+        auto issue_idx = [&](int tile) {
+            const int pos = min(tile * TP + qn, n - 1);
+            const int32_t* g = (hh ? iv : ik) + pos;
+            dma4(g, idx_lds + (tile & 1) * G::IDX);
+        };
+        auto issue_gather = [&](int tile) {
+            const uint32_t st = lds0 + (tile & (NS - 1)) * G::STAGE;
+            const lds_u32* islot = (const lds_u32*)(uintptr_t)(idx_lds + (tile & 1) * G::IDX);
+            int rk[G::NI], rv[G::NI];
+#pragma unroll
+            for (int i = 0; i < G::NI; ++i) {
+                rk[i] = islot[gp[i]];
+                rv[i] = islot[32 + gp[i]];
+            }
+#pragma unroll
+            for (int i = 0; i < G::NI; ++i) {
+                const uint32_t dst = (i * NW + wave) * G::RPI * G::ROWB;
+                dma16(pk + (uint64_t)(uint32_t)rk[i] * row_bytes + gk_off[i], st + dst);
+                dma16(pv + (uint64_t)(uint32_t)rv[i] * row_bytes + gv_off[i], st + G::KV + dst);
+            }
+#pragma unroll
+            for (int u = 0; u < G::NUI_MAX; ++u) {
+                if (u < nui) {
+                    const int pos = min(tile * TP + up[u], n - 1);
+                    const uint32_t* g = (uisv[u] ? uv32 : uk32) + (int64_t)pos * (d_u >> 1) + uoff[u];
+                    dma4(g, st + 2 * G::KV + (u * NW + wave) * 256);
+                }
+            }
+        };
+        auto concat = [&](int tile) {
+            const uint32_t st = lds0 + (tile & (NS - 1)) * G::STAGE;
+#pragma unroll
+            for (int x = 0; x < G::PE; ++x)
+                if (cok[x]) *(lds_u32*)(uintptr_t)(st + cdst[x]) = *(const lds_u32*)(uintptr_t)(st + csrc[x]);
+        };
+
+        issue_idx(0);
+        wait_vm<0>();
+        for (int t = -(NS - 1); t < ntiles; ++t) {
+            // indices of tile t+3 have landed once at most the gathers of tile t+2 are outstanding
+            wait_vm_plus<2 * G::NI>(nui);
+            issue_idx(t + NS);
+            issue_gather(t + NS - 1);
+            if (t + 1 >= 0 && t + 1 < ntiles && d_u > 0) concat(t + 1);
+            if (t >= 0) {
+                const uint32_t st = lds0 + (t & (NS - 1)) * G::STAGE;
+                const int nt = min(n - t * TP, TP);
+                // S^T = K Q^T
+                f32x16 sacc;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+#pragma unroll
+                for (int kk = 0; kk < NKK; ++kk) {
+                    const uint32_t ad = st + krow + (((2 * kk + hh) ^ kx) << 4);
+                    const bf16x8 ka = *(const lds_bf16x8*)(uintptr_t)ad;
+                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[kk], sacc, 0, 0, 0);
+                }
+                const bool ragged = nt < TP;
+                bf16x8 pb[2];
+                if (MODE == CKV_SOFTMAX) {
+                    if (ragged) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            if (8 * (r >> 2) + 4 * hh + (r & 3) >= nt) sacc[r] = -INFINITY;
+                    }
+                    float tmax = sacc[0];
+#pragma unroll
+                    for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, sacc[r]);
+                    tmax = fmaxf(tmax, other_half(tmax)) * sc;
+                    if (__any(tmax > m_ref + kLazy)) {
+                        const float m_new = fmaxf(m_ref, tmax);
+                        const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
+                        lsum *= alpha;
+#pragma unroll
+                        for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+                        m_ref = m_new;
+                    }
+                    float psum = 0.f;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float p = __builtin_amdgcn_exp2f(fmaf(sacc[r], sc, -m_ref));
+                        psum += p;
+                        pb[r >> 3][r & 7] = (__bf16)p;
+                    }
+                    lsum += psum;
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float x = sacc[r] * sc;
+                        float p = x * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-kLog2e * x));
+                        if (ragged && 8 * (r >> 2) + 4 * hh + (r & 3) >= nt) p = 0.f;
+                        pb[r >> 3][r & 7] = (__bf16)p;
+                    }
+                }
+                // O^T += V^T P^T
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                    for (int dt = 0; dt < NDT; ++dt) {
+                        const uint32_t ad = st + vrow + (16 * ks) * G::ROWB + (((4 * dt + vc) ^ vx) << 4);
+                        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(uintptr_t)ad);
+                        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(uintptr_t)(ad + 8 * G::ROWB));
+                        const bf16x8 va = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[ks], oacc[dt], 0, 0, 0);
+                    }
+            }
+            // own gathers of tile t+2 have landed once only idx(t+4) and gathers(t+3) are outstanding
+            wait_vm_plus<2 * G::NI + 1>(nui);
+            lds_barrier();
+        }
+        wait_vm<0>();  // the clamped loads past the last tile must not outlive the workgroup's LDS
+    }
+
+    // ---- epilogue
+    float l_tot = 0.f;
+    if (MODE == CKV_SOFTMAX) l_tot = lsum + other_half(lsum);
+    if (it.part < 0) {
+        float inv;
+        if (MODE == CKV_SOFTMAX) inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+        else inv = it.n_total > 0 ? 1.f / (float)it.n_total : 0.f;
+        if (qok) {
+            uint16_t* op = (uint16_t*)a.out + qo;
+#pragma unroll
+            for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int ci = 32 * dt + 8 * (r >> 2) + 4 * hh + (r & 3);
+                    const int pc = ci < d_g ? ci + d_u : ci - d_g;
+                    op[pc] = f2bf(oacc[dt][r] * inv);
+                }
+        }
+    } else {
+        float* ws = a.partial + (int64_t)it.part * a.QB * (DA + 2);
+        const int j = wave * 32 + qn;
+#pragma unroll
+        for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int ci = 32 * dt + 8 * (r >> 2) + 4 * hh + (r & 3);
+                const int pc = ci < d_g ? ci + d_u : ci - d_g;
+                ws[(int64_t)j * DA + pc] = oacc[dt][r];
+            }
+        if (hh == 0) {
+            ws[(int64_t)a.QB * DA + j] = m_ref * kLn2;
+            ws[(int64_t)a.QB * DA + a.QB + j] = l_tot;
+        }
+    }
+}
+
+template <int DA, int NW, int MODE>
+hipError_t prepare() {
+    constexpr int lds = Geo<DA, NW>::LDS;
+    static hipError_t done =
+        hipFuncSetAttribute((const void*)ckv_dma_kernel<DA, NW, MODE>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    return done;
+}
+
+template <int DA, int NW, int MODE>
+hipError_t launch(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
+    hipError_t e = prepare<DA, NW, MODE>();
+    if (e != hipSuccess) return e;
+    constexpr int lds = Geo<DA, NW>::LDS;
+    hipLaunchKernelGGL((ckv_dma_kernel<DA, NW, MODE>), dim3(c->n_items), dim3(NW * 64), lds, s, a, c->nui);
+    return hipGetLastError();
+}
+
+template <int DA, int NW, int MODE>
+int occupancy() {
+    if (prepare<DA, NW, MODE>() != hipSuccess) return 0;
+    int nb = 0;
+    constexpr int lds = Geo<DA, NW>::LDS;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)ckv_dma_kernel<DA, NW, MODE>, NW * 64, lds) != hipSuccess)
+        return 0;
+    return nb;
+}
+
+#define CKV_DMA_SHAPES(X) X(64, 1) X(64, 2) X(64, 4) X(128, 1) X(128, 2) X(128, 4)
+
+}  // namespace
+
+// Number of user-slice load instructions per wavefront and tile, or -1 if the shape is not
+// served by this kernel.
+int ckv_dma_nui(int d_a, int nw, int d_u) {
+    if ((d_a != 64 && d_a != 128) || (nw != 1 && nw != 2 && nw != 4)) return -1;
+    if (d_u < 0 || d_u > 8 || (d_u & 1)) return -1;
+    const int need = (32 * d_u + nw * 64 - 1) / (nw * 64);  // ceil(dwords of K_u and V_u / lanes)
+    return need <= 1 ? need : (need <= 2 ? 2 : 4);
+}
+
+int ckv_dma_occupancy(int d_a, int nw, int mode) {
+#define X(DA, NW) \
+    if (d_a == DA && nw == NW) return mode == CKV_SOFTMAX ? occupancy<DA, NW, CKV_SOFTMAX>() : occupancy<DA, NW, CKV_SILU_OVER_N>();
+    CKV_DMA_SHAPES(X)
+#undef X
+    return 0;
+}
+
+hipError_t ckv_launch_dma(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
+    if (c->n_items == 0) return hipSuccess;
+    const int d_a = a.d_a, nw = c->nw;
+#define X(DA, NW)                                                                                                  \
+    if (d_a == DA && nw == NW)                                                                                     \
+        return c->shape.mode == CKV_SOFTMAX ? launch<DA, NW, CKV_SOFTMAX>(c, a, s) : launch<DA, NW, CKV_SILU_OVER_N>(c, a, s);
+    CKV_DMA_SHAPES(X)
+#undef X
+    return hipErrorInvalidValue;
+}

@@ -44,7 +44,7 @@ struct ckv_args {
     float scale;
 };
 
-enum ckv_kernel_family { CKV_K_STREAM = 0, CKV_K_MFMA = 1 };
+enum ckv_kernel_family { CKV_K_STREAM = 0, CKV_K_MFMA = 1, CKV_K_DMA = 2 };
 
 struct ckv_cache {
     ckv_shape shape;
@@ -58,7 +58,8 @@ struct ckv_cache {
     // launch metadata
     int family;          // ckv_kernel_family
     int vec, ncb;        // stream kernel: elements per lane per column block, column blocks
-    int nw, tp;          // mfma kernel: waves per workgroup, positions per tile
+    int nw, tp;          // mfma kernels: waves per workgroup, positions per tile
+    int nui;             // dma kernel: user-slice load instructions per wavefront and tile
     int QB;              // queries per block
     int n_items, n_merge, n_parts;
     ckv_item* d_items;
@@ -78,5 +79,9 @@ hipError_t ckv_launch_mfma(const ckv_cache* c, const ckv_args& a, hipStream_t s)
 int ckv_mfma_occupancy(int d_a, int nw, int tp, int mode);
 // Whether (d_a, nw, tp) has an instantiated mfma kernel.
 bool ckv_mfma_supported(int d_a, int nw, int tp);
+// Direct-to-LDS variant of the mfma kernel.
+hipError_t ckv_launch_dma(const ckv_cache* c, const ckv_args& a, hipStream_t s);
+int ckv_dma_nui(int d_a, int nw, int d_u);  // -1: shape not served
+int ckv_dma_occupancy(int d_a, int nw, int mode);
 
 #endif

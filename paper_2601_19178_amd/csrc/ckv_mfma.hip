@@ -75,7 +75,7 @@ __device__ __forceinline__ uint4 gather_chunk(const uint16_t* __restrict__ pool_
 }
 
 template <int DA, int NW, int TP, int MODE>
-__global__ __launch_bounds__(NW * 64) void ckv_mfma_kernel(ckv_args a) {
+__global__ __launch_bounds__(NW * 64, (DA == 128 ? 2 : 2)) void ckv_mfma_kernel(ckv_args a) {
     constexpr int NT = NW * 64;        // threads
     constexpr int CH = DA / 8;         // 16-byte chunks per row
     constexpr int RPP = NT / CH;       // rows gathered per pass

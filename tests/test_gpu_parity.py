@@ -30,8 +30,19 @@ def make(lengths, dtype, mode, d_a, d_u, H, P, Nq, seed=11, idx="uniform", **kw)
                    sigma_pool=d_a ** -0.5, seed=seed, lengths=lengths, **kw)
 
 
-def run_and_check(gpu, w, what, users=None, expect_variant=None):
+def run_and_check(gpu, w, what, users=None, expect_variant=None, impl=None):
+    """impl: None (library's choice) or "staged" (force the register-staged matrix-core kernel)."""
+    import os
     ckv, session = gpu
+    if impl:
+        os.environ["CKV_MFMA_IMPL"] = impl
+    try:
+        return _run_and_check(ckv, session, w, what, users, expect_variant)
+    finally:
+        os.environ.pop("CKV_MFMA_IMPL", None)
+
+
+def _run_and_check(ckv, session, w, what, users, expect_variant):
     say(f"[case] {what}: B={w['B']} H={w['H']} d_g={w['d_g']} d_u={w['d_u']} P={w['P']} Nq={w['Nq']} "
         f"dtype={w['dtype']} mode={w['mode']} T={int(w['lengths'].sum())}")
     with session.Session(w) as s:
@@ -117,18 +128,36 @@ def test_config2_full(gpu, name):
 MFMA_LENGTHS = (1, 31, 32, 33, 64, 65, 0, 127, 200, 1500, 96, 2)
 
 
+@pytest.mark.parametrize("impl", [None, "staged"])
 @pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
 @pytest.mark.parametrize("d_a,d_u,Nq", [(64, 4, 64), (64, 2, 16), (64, 8, 32), (128, 8, 128), (128, 8, 40),
-                                         (64, 3, 20), (128, 16, 64), (64, 0, 16), (128, 24, 100), (64, 8, 200)])
-def test_mfma_ragged(gpu, mode, d_a, d_u, Nq):
+                                         (64, 3, 20), (128, 16, 64), (64, 0, 16), (128, 24, 100), (64, 8, 200),
+                                         (128, 2, 16), (128, 4, 64), (64, 6, 128), (128, 0, 32), (64, 8, 8)])
+def test_mfma_ragged(gpu, impl, mode, d_a, d_u, Nq):
     w = make(MFMA_LENGTHS, wl.BF16, mode, d_a=d_a, d_u=d_u, H=2, P=700, Nq=Nq)
-    run_and_check(gpu, w, f"mfma ragged d_a={d_a} d_u={d_u} Nq={Nq} mode={mode}", expect_variant="mfma")
+    dma_ok = d_u % 2 == 0 and d_u <= 8
+    expect = "mfma_dma" if (impl is None and dma_ok) else "mfma_bf16"
+    run_and_check(gpu, w, f"mfma ragged d_a={d_a} d_u={d_u} Nq={Nq} mode={mode} impl={impl}", expect_variant=expect, impl=impl)
 
 
+@pytest.mark.parametrize("impl", [None, "staged"])
 @pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
-def test_mfma_split_history(gpu, mode):
+def test_mfma_split_history(gpu, impl, mode):
     w = make((5000, 70, 2300, 1024, 1025), wl.BF16, mode, d_a=128, d_u=8, H=2, P=5000, Nq=128)
-    run_and_check(gpu, w, f"mfma split mode={mode}", expect_variant="mfma")
+    run_and_check(gpu, w, f"mfma split mode={mode} impl={impl}", expect_variant="mfma", impl=impl)
+
+
+def test_mfma_unpadded_pool_rows(gpu):
+    # pool_ld == d_g (a multiple of 8): the chunk that would be padding does not exist in memory
+    w = make(MFMA_LENGTHS, wl.BF16, wl.SOFTMAX, d_a=64, d_u=8, H=2, P=333, Nq=16, pool_ld=56)
+    run_and_check(gpu, w, "mfma pool_ld=d_g", expect_variant="mfma_dma")
+    w = make(MFMA_LENGTHS, wl.BF16, wl.SOFTMAX, d_a=128, d_u=8, H=1, P=333, Nq=64, pool_ld=120)
+    run_and_check(gpu, w, "mfma pool_ld=d_g staged", expect_variant="mfma_bf16", impl="staged")
+
+
+def test_negative_scale_falls_back_to_streaming(gpu):
+    w = make((70, 33), wl.BF16, wl.SOFTMAX, d_a=64, d_u=8, H=1, P=50, Nq=16, scale=-0.125)
+    run_and_check(gpu, w, "negative scale", expect_variant="stream")
 
 
 def test_mfma_all_users_is_ordinary_attention_when_dg_zero(gpu):
@@ -150,19 +179,19 @@ def sampled_users(B, k, seed):
 
 def test_config3_full(gpu):
     w = wl.config("cfg3")
-    run_and_check(gpu, w, "cfg3", users=sampled_users(w["B"], 24, 3), expect_variant="mfma_bf16_d64_w2")
+    run_and_check(gpu, w, "cfg3", users=sampled_users(w["B"], 24, 3), expect_variant="mfma_dma_bf16_d64_w2")
 
 
 def test_config4_full(gpu):
     w = wl.config("cfg4")
     users = sampled_users(w["B"], 3, 4)
     users = np.unique(np.concatenate([users, [int(np.argmax(w["lengths"])), int(np.argmin(w["lengths"]))]])).astype(np.int32)
-    run_and_check(gpu, w, "cfg4", users=users, expect_variant="mfma_bf16_d128_w4")
+    run_and_check(gpu, w, "cfg4", users=users, expect_variant="mfma_dma_bf16_d128_w4")
 
 
 def test_config5_full(gpu):
     w = wl.config("cfg5")
-    run_and_check(gpu, w, "cfg5", users=sampled_users(w["B"], 48, 5), expect_variant="mfma_bf16_d64_w1")
+    run_and_check(gpu, w, "cfg5", users=sampled_users(w["B"], 48, 5), expect_variant="mfma_dma_bf16_d64_w1")
 
 
 # ---------------------------------------------------------------------------------------------
