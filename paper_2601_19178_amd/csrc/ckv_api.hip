@@ -82,50 +82,47 @@ __global__ void ckv_reconstruct_kernel(const int32_t* __restrict__ idx, const U*
 }
 
 // Merge of the pieces of a split history.  Softmax pieces carry (acc, m, l) with acc and l
-// relative to the piece maximum m; SiLU pieces carry only acc.
+// relative to the piece maximum m; SiLU pieces carry only acc.  Block (x, y) handles merge
+// entry x and queries 16y .. 16y+15, sixteen threads per query.
 template <typename U, int MODE>
-__global__ void ckv_merge_kernel(const ckv_merge* __restrict__ list, const float* __restrict__ partial,
-                                 U* __restrict__ out, int H, int Nq, int d_a, int QB) {
+__global__ __launch_bounds__(256) void ckv_merge_kernel(const ckv_merge* __restrict__ list, const float* __restrict__ partial,
+                                                        U* __restrict__ out, int H, int Nq, int d_a, int QB) {
     const ckv_merge mg = list[blockIdx.x];
     const int64_t stride = (int64_t)QB * (d_a + 2);
-    for (int j = 0; j < QB; ++j) {
-        if (mg.q0 + j >= Nq) break;
-        float M = -INFINITY;
-        if (MODE == CKV_SOFTMAX)
-            for (int p = 0; p < mg.nparts; ++p)
-                M = fmaxf(M, partial[(mg.part0 + p) * stride + (int64_t)QB * d_a + j]);
-        float denom = 0.f;
-        if (MODE == CKV_SOFTMAX) {
-            for (int p = 0; p < mg.nparts; ++p) {
-                const float* ws = partial + (mg.part0 + p) * stride;
-                const float mp = ws[(int64_t)QB * d_a + j];
-                denom += (mp == -INFINITY ? 0.f : __expf(mp - M)) * ws[(int64_t)QB * d_a + QB + j];
-            }
-        } else {
-            denom = (float)mg.n_total;
+    const int j = blockIdx.y * 16 + (threadIdx.x >> 4);
+    const int c0 = threadIdx.x & 15;
+    if (j >= QB || mg.q0 + j >= Nq) return;
+    const float* base = partial + (int64_t)mg.part0 * stride;
+    float M = -INFINITY, denom = 0.f;
+    if (MODE == CKV_SOFTMAX) {
+        for (int p = 0; p < mg.nparts; ++p) M = fmaxf(M, base[p * stride + (int64_t)QB * d_a + j]);
+        for (int p = 0; p < mg.nparts; ++p) {
+            const float mp = base[p * stride + (int64_t)QB * d_a + j];
+            denom += (mp == -INFINITY ? 0.f : __expf(mp - M)) * base[p * stride + (int64_t)QB * d_a + QB + j];
         }
-        const float inv = denom > 0.f ? 1.f / denom : 0.f;
-        for (int c = threadIdx.x; c < d_a; c += blockDim.x) {
-            float acc = 0.f;
-            for (int p = 0; p < mg.nparts; ++p) {
-                const float* ws = partial + (mg.part0 + p) * stride;
-                float w = 1.f;
-                if (MODE == CKV_SOFTMAX) {
-                    const float mp = ws[(int64_t)QB * d_a + j];
-                    w = mp == -INFINITY ? 0.f : __expf(mp - M);
-                }
-                acc += w * ws[(int64_t)j * d_a + c];
+    } else {
+        denom = (float)mg.n_total;
+    }
+    const float inv = denom > 0.f ? 1.f / denom : 0.f;
+    const int64_t o = (((int64_t)mg.b * H + mg.h) * Nq + mg.q0 + j) * d_a;
+    for (int c = c0; c < d_a; c += 16) {
+        float acc = 0.f;
+        for (int p = 0; p < mg.nparts; ++p) {
+            float w = 1.f;
+            if (MODE == CKV_SOFTMAX) {
+                const float mp = base[p * stride + (int64_t)QB * d_a + j];
+                w = mp == -INFINITY ? 0.f : __expf(mp - M);
             }
-            const float r = acc * inv;
-            const int64_t o = (((int64_t)mg.b * H + mg.h) * Nq + mg.q0 + j) * d_a + c;
-            if (sizeof(U) == 4) {
-                ((float*)out)[o] = r;
-            } else {
-                uint32_t u = __float_as_uint(r);
-                if ((u & 0x7FFFFFFFu) > 0x7F800000u) u |= 0x400000u;
-                else u += 0x7FFFu + ((u >> 16) & 1u);
-                ((uint16_t*)out)[o] = (uint16_t)(u >> 16);
-            }
+            acc += w * base[p * stride + (int64_t)j * d_a + c];
+        }
+        const float r = acc * inv;
+        if (sizeof(U) == 4) {
+            ((float*)out)[o + c] = r;
+        } else {
+            uint32_t u = __float_as_uint(r);
+            if ((u & 0x7FFFFFFFu) > 0x7F800000u) u |= 0x400000u;
+            else u += 0x7FFFu + ((u >> 16) & 1u);
+            ((uint16_t*)out)[o + c] = (uint16_t)(u >> 16);
         }
     }
 }
@@ -159,27 +156,12 @@ int pick_stream_vec(const ckv_shape& s) {
     return 1;
 }
 
-void build_work(ckv_cache* c, const int32_t* lengths, const std::vector<int64_t>& offs, int cus,
-                std::vector<ckv_item>& items, std::vector<ckv_merge>& merges) {
+// Cut units into pieces of at most `piece` positions and order them (see above).
+void make_items(const ckv_cache* c, const std::vector<Unit>& units, int64_t piece, std::vector<ckv_item>& items,
+                std::vector<ckv_merge>& merges, int* n_parts_out) {
     const ckv_shape& s = c->shape;
-    const int nqb = (s.Nq + c->QB - 1) / c->QB;
-    int wg_per_cu = 8;
-    if (c->family == CKV_K_MFMA) wg_per_cu = std::max(1, ckv_mfma_occupancy(s.d_g + s.d_u, c->nw, c->tp, s.mode));
-    if (c->family == CKV_K_DMA) wg_per_cu = std::max(1, ckv_dma_occupancy(s.d_g + s.d_u, c->nw, s.mode));
-    const int64_t slots = (int64_t)cus * wg_per_cu;
-    const int64_t n_units = (int64_t)s.B * s.H * nqb;
-    const int64_t total_ph = c->T * s.H * nqb;
-    int64_t piece = INT64_MAX;
-    if (n_units < 8 * slots) {
-        piece = std::max<int64_t>(1024, total_ph / (slots * 4));
-        piece = (piece + 63) / 64 * 64;
-    }
-    std::vector<Unit> units;
-    units.reserve((size_t)n_units);
-    for (int b = 0; b < s.B; ++b)
-        for (int h = 0; h < s.H; ++h)
-            for (int qb = 0; qb < nqb; ++qb) units.push_back({b, h, qb * c->QB, lengths[b], offs[b]});
-
+    items.clear();
+    merges.clear();
     int n_parts = 0;
     for (const Unit& u : units) {
         const int np = u.n > piece ? (int)((u.n + piece - 1) / piece) : 1;
@@ -197,7 +179,7 @@ void build_work(ckv_cache* c, const int32_t* lengths, const std::vector<int64_t>
             items.push_back({u.b, u.h, u.q0, nn, u.t0 + lo, n_parts++, u.n});
         }
     }
-    c->n_parts = n_parts;
+    *n_parts_out = n_parts;
 
     // head classes for the XCD-aware order
     int ncls = 1;
@@ -223,6 +205,81 @@ void build_work(ckv_cache* c, const int32_t* lengths, const std::vector<int64_t>
         --remaining;
     }
     items.swap(ordered);
+}
+
+// Finish time (in positions) of the last workgroup when the items are handed out in order:
+// workgroup i runs on XCD i mod 8, on whichever of that XCD's slots frees up first.
+int64_t simulate_dispatch(const std::vector<ckv_item>& items, int64_t slots, int64_t overhead) {
+    const int nx = 8;
+    const size_t per = (size_t)std::max<int64_t>(1, slots / nx);
+    std::vector<std::vector<int64_t>> heap((size_t)nx);  // min-heaps of slot finish times
+    for (auto& h : heap) h.assign(per, 0);
+    auto cmp = [](int64_t x, int64_t y) { return x > y; };
+    int64_t makespan = 0;
+    for (size_t i = 0; i < items.size(); ++i) {
+        auto& h = heap[i % nx];
+        std::pop_heap(h.begin(), h.end(), cmp);
+        h.back() += items[i].n + overhead;
+        makespan = std::max(makespan, h.back());
+        std::push_heap(h.begin(), h.end(), cmp);
+    }
+    return makespan;
+}
+
+void build_work(ckv_cache* c, const int32_t* lengths, const std::vector<int64_t>& offs, int cus,
+                std::vector<ckv_item>& items, std::vector<ckv_merge>& merges) {
+    const ckv_shape& s = c->shape;
+    const int d_a = s.d_g + s.d_u;
+    const int nqb = (s.Nq + c->QB - 1) / c->QB;
+    int wg_per_cu = 8;
+    if (c->family == CKV_K_MFMA) wg_per_cu = std::max(1, ckv_mfma_occupancy(d_a, c->nw, c->tp, s.mode));
+    if (c->family == CKV_K_DMA) wg_per_cu = std::max(1, ckv_dma_occupancy(d_a, c->nw, s.mode));
+    const int64_t slots = (int64_t)cus * wg_per_cu;
+    std::vector<Unit> units;
+    units.reserve((size_t)s.B * s.H * nqb);
+    int64_t longest = 0;
+    for (int b = 0; b < s.B; ++b)
+        for (int h = 0; h < s.H; ++h)
+            for (int qb = 0; qb < nqb; ++qb) {
+                units.push_back({b, h, qb * c->QB, lengths[b], offs[b]});
+                longest = std::max<int64_t>(longest, lengths[b]);
+            }
+    // Candidate piece lengths: no split, then halvings of the longest history down to 512.
+    // Cost of a candidate, in positions per slot: simulated finish time plus the traffic of the
+    // split workspace (written and read once) expressed in positions of gather traffic.
+    const int64_t overhead = c->family == CKV_K_STREAM ? 16 : 128;  // per-item fill/drain, in positions
+    const double e = (double)esize(s.dtype);
+    const double part_positions = (double)c->QB * (d_a + 2) * 8.0 / (2.0 * d_a * e + 8.0);
+    std::vector<ckv_item> best_items;
+    std::vector<ckv_merge> best_merges;
+    double best_cost = -1.0;
+    int best_parts = 0;
+    int64_t best_piece = 0;
+    for (int64_t piece = INT64_MAX; piece >= 512; piece = (piece == INT64_MAX ? (longest + 1) / 2 : piece / 2)) {
+        if (piece != INT64_MAX) piece = (piece + 63) / 64 * 64;
+        std::vector<ckv_item> it2;
+        std::vector<ckv_merge> mg2;
+        int parts = 0;
+        make_items(c, units, piece, it2, mg2, &parts);
+        double cost = (double)simulate_dispatch(it2, slots, overhead) + parts * part_positions / (double)slots;
+        if (parts > 0) cost *= 1.02;  // the merge is a second launch
+        if (best_cost < 0 || cost < best_cost) {
+            best_cost = cost;
+            best_items.swap(it2);
+            best_merges.swap(mg2);
+            best_parts = parts;
+            best_piece = piece;
+        }
+        if (piece != INT64_MAX && piece <= 512) break;
+        if (units.size() > (size_t)(64 * slots)) break;  // plenty of units: splitting cannot pay
+    }
+    items.swap(best_items);
+    merges.swap(best_merges);
+    c->n_parts = best_parts;
+    if (getenv("CKV_DEBUG"))
+        fprintf(stderr, "ckv: %s: %zu units, %lld slots, piece %lld -> %zu items, %d parts, cost %.0f positions/slot\n", c->variant,
+                units.size(), (long long)slots, (long long)(best_piece == INT64_MAX ? -1 : best_piece), items.size(), best_parts,
+                best_cost);
 }
 
 void choose_variant(ckv_cache* c) {
@@ -473,20 +530,20 @@ int ckv_attend(const ckv_cache* c, const void* pool_k, const void* pool_v, const
     }
     if (c->n_merge > 0) {
         const int d_a = a.d_a;
-        const int threads = d_a <= 64 ? 64 : (d_a <= 128 ? 128 : 256);
+        const dim3 mgrid(c->n_merge, (c->QB + 15) / 16), threads(256);
         if (s.dtype == CKV_F32) {
             if (s.mode == CKV_SOFTMAX)
-                hipLaunchKernelGGL((ckv_merge_kernel<float, CKV_SOFTMAX>), dim3(c->n_merge), dim3(threads), 0, st, c->d_merge,
+                hipLaunchKernelGGL((ckv_merge_kernel<float, CKV_SOFTMAX>), mgrid, threads, 0, st, c->d_merge,
                                    c->d_partial, (float*)out, s.H, s.Nq, d_a, c->QB);
             else
-                hipLaunchKernelGGL((ckv_merge_kernel<float, CKV_SILU_OVER_N>), dim3(c->n_merge), dim3(threads), 0, st, c->d_merge,
+                hipLaunchKernelGGL((ckv_merge_kernel<float, CKV_SILU_OVER_N>), mgrid, threads, 0, st, c->d_merge,
                                    c->d_partial, (float*)out, s.H, s.Nq, d_a, c->QB);
         } else {
             if (s.mode == CKV_SOFTMAX)
-                hipLaunchKernelGGL((ckv_merge_kernel<uint16_t, CKV_SOFTMAX>), dim3(c->n_merge), dim3(threads), 0, st, c->d_merge,
+                hipLaunchKernelGGL((ckv_merge_kernel<uint16_t, CKV_SOFTMAX>), mgrid, threads, 0, st, c->d_merge,
                                    c->d_partial, (uint16_t*)out, s.H, s.Nq, d_a, c->QB);
             else
-                hipLaunchKernelGGL((ckv_merge_kernel<uint16_t, CKV_SILU_OVER_N>), dim3(c->n_merge), dim3(threads), 0, st,
+                hipLaunchKernelGGL((ckv_merge_kernel<uint16_t, CKV_SILU_OVER_N>), mgrid, threads, 0, st,
                                    c->d_merge, c->d_partial, (uint16_t*)out, s.H, s.Nq, d_a, c->QB);
         }
         e = hipGetLastError();

@@ -83,11 +83,15 @@ struct Geo {
     static constexpr int IDX = 256;              // bytes of one index slot: 32 x I_k, 32 x I_v
     static constexpr int LDS = NS * STAGE + NW * 2 * IDX;
     static constexpr int PE = 256 / NT;          // user dwords copied per lane in the concat step
+    // wavefronts per SIMD that LDS lets be resident; the register budget is sized for exactly that
+    static constexpr int WG_PER_CU = 163840 / LDS;
+    static constexpr int WAVES_PER_EU = WG_PER_CU * NW / 4 < 1 ? 1 : (WG_PER_CU * NW / 4 > 8 ? 8 : WG_PER_CU * NW / 4);
     static_assert(NI >= 1, "tile too small for this many wavefronts");
 };
 
 template <int DA, int NW, int MODE>
-__global__ __launch_bounds__(NW * 64, 2) void ckv_dma_kernel(ckv_args a, int nui) {
+__global__ __launch_bounds__(NW * 64)
+__attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES_PER_EU))) void ckv_dma_kernel(ckv_args a, int nui) {
     using G = Geo<DA, NW>;
     constexpr int NKK = DA / 16, NDT = DA / 32;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -247,12 +251,29 @@ __global__ __launch_bounds__(NW * 64, 2) void ckv_dma_kernel(ckv_args a, int nui
                 f32x16 sacc;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+                bf16x8 ka[NKK];  // all operand reads first, so their LDS latencies overlap
 #pragma unroll
-                for (int kk = 0; kk < NKK; ++kk) {
-                    const uint32_t ad = st + krow + (((2 * kk + hh) ^ kx) << 4);
-                    const bf16x8 ka = *(const lds_bf16x8*)(uintptr_t)ad;
-                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[kk], sacc, 0, 0, 0);
-                }
+                for (int kk = 0; kk < NKK; ++kk)
+                    ka[kk] = *(const lds_bf16x8*)(uintptr_t)(st + krow + (((2 * kk + hh) ^ kx) << 4));
+#pragma unroll
+                for (int kk = 0; kk < NKK; ++kk)
+                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk], qreg[kk], sacc, 0, 0, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, NKK, 0);  // all LDS reads ...
+                __builtin_amdgcn_sched_group_barrier(0x008, NKK, 0);  // ... then the MFMAs
+                // V^T operands of the whole tile: issued now, so that their LDS latency is hidden
+                // behind the MFMAs above and the weight arithmetic below
+                bf16x8 va[2][NDT];
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                    for (int dt = 0; dt < NDT; ++dt) {
+                        const uint32_t ad = st + vrow + (16 * ks) * G::ROWB + (((4 * dt + vc) ^ vx) << 4);
+                        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(uintptr_t)ad);
+                        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(uintptr_t)(ad + 8 * G::ROWB));
+                        va[ks][dt] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    }
+                __builtin_amdgcn_sched_group_barrier(0x100, 4 * NDT, 0);
+                __builtin_amdgcn_sched_barrier(0);
                 const bool ragged = nt < TP;
                 bf16x8 pb[2];
                 if (MODE == CKV_SOFTMAX) {
@@ -296,13 +317,8 @@ __global__ __launch_bounds__(NW * 64, 2) void ckv_dma_kernel(ckv_args a, int nui
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-                    for (int dt = 0; dt < NDT; ++dt) {
-                        const uint32_t ad = st + vrow + (16 * ks) * G::ROWB + (((4 * dt + vc) ^ vx) << 4);
-                        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(uintptr_t)ad);
-                        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(uintptr_t)(ad + 8 * G::ROWB));
-                        const bf16x8 va = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[ks], oacc[dt], 0, 0, 0);
-                    }
+                    for (int dt = 0; dt < NDT; ++dt)
+                        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ks][dt], pb[ks], oacc[dt], 0, 0, 0);
             }
             // own gathers of tile t+2 have landed once only idx(t+4) and gathers(t+3) are outstanding
             wait_vm_plus<2 * G::NI + 1>(nui);
