@@ -233,7 +233,7 @@ void build_work(ckv_cache* c, const int32_t* lengths, const std::vector<int64_t>
     const int nqb = (s.Nq + c->QB - 1) / c->QB;
     int wg_per_cu = 8;
     if (c->family == CKV_K_MFMA) wg_per_cu = std::max(1, ckv_mfma_occupancy(d_a, c->nw, c->tp, s.mode));
-    if (c->family == CKV_K_DMA) wg_per_cu = std::max(1, ckv_dma_occupancy(d_a, c->nw, s.mode));
+    if (c->family == CKV_K_DMA) wg_per_cu = std::max(1, ckv_dma_occupancy(d_a, c->nw, c->qg, s.mode));
     const int64_t slots = (int64_t)cus * wg_per_cu;
     std::vector<Unit> units;
     units.reserve((size_t)s.B * s.H * nqb);
@@ -289,18 +289,26 @@ void choose_variant(ckv_cache* c) {
     // the matrix-core kernels take the running maximum before scaling, which needs scale > 0
     if (s.dtype == CKV_BF16 && (d_a == 64 || d_a == 128) && s.Nq >= 8 && (s.d_g == 0 || s.pool_ld % 8 == 0) &&
         (s.mode == CKV_SILU_OVER_N || s.scale > 0.f)) {
-        const int nw = s.Nq <= 32 ? 1 : (s.Nq <= 64 ? 2 : 4);
         const char* impl = getenv("CKV_MFMA_IMPL");  // tuning knob: "staged" forces the register-staged kernel
-        const int nui = s.d_g > 0 ? ckv_dma_nui(d_a, nw, s.d_u) : -1;
-        if (nui >= 0 && !(impl && strcmp(impl, "staged") == 0)) {
-            c->family = CKV_K_DMA;
-            c->nw = nw;
-            c->tp = 32;
-            c->nui = nui;
-            c->QB = 32 * nw;
-            snprintf(c->variant, sizeof c->variant, "mfma_dma_bf16_d%d_w%d_%s", d_a, nw, s.mode == CKV_SOFTMAX ? "softmax" : "silu");
-            return;
+        {
+            // direct-to-LDS kernel: 32 queries per wavefront, up to 4 wavefronts per workgroup (two
+            // wavefronts per SIMD overlap better than one wavefront with two query groups)
+            int nw = s.Nq <= 32 ? 1 : (s.Nq <= 64 ? 2 : 4), qg = 1;
+            if (const char* shp = getenv("CKV_DMA_SHAPE")) sscanf(shp, "%d,%d", &nw, &qg);  // tuning knob "nw,qg"
+            const int nui = s.d_g > 0 && ckv_dma_supported(d_a, nw, qg) ? ckv_dma_nui(d_a, nw, s.d_u) : -1;
+            if (nui >= 0 && !(impl && strcmp(impl, "staged") == 0)) {
+                c->family = CKV_K_DMA;
+                c->nw = nw;
+                c->qg = qg;
+                c->tp = 32;
+                c->nui = nui;
+                c->QB = 32 * nw * qg;
+                snprintf(c->variant, sizeof c->variant, "mfma_dma_bf16_d%d_w%d_g%d_%s", d_a, nw, qg,
+                         s.mode == CKV_SOFTMAX ? "softmax" : "silu");
+                return;
+            }
         }
+        const int nw = s.Nq <= 32 ? 1 : (s.Nq <= 64 ? 2 : 4);
         const int tp = (d_a == 128 && nw == 1) ? 32 : 64;
         if (ckv_mfma_supported(d_a, nw, tp)) {
             c->family = CKV_K_MFMA;

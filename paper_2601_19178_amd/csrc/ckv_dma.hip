@@ -18,6 +18,8 @@
 // waited for with explicit s_waitcnt vmcnt(N): every wavefront issues the same number of
 // loads per iteration (positions past the end of the history are clamped to the last one),
 // so N is a constant.
+#include <cstdlib>
+
 #include "ckv_internal.h"
 
 namespace {
@@ -81,7 +83,8 @@ struct Geo {
     static constexpr int USER = NW * 64 * 4 * NUI_MAX;  // bytes of the user staging of a stage (1 KiB)
     static constexpr int STAGE = 2 * KV + USER;
     static constexpr int IDX = 256;              // bytes of one index slot: 32 x I_k, 32 x I_v
-    static constexpr int LDS = NS * STAGE + NW * 2 * IDX;
+    static constexpr int NIS = 4;                // index slots per wavefront (indices run 2 tiles ahead of the gathers)
+    static constexpr int LDS = NS * STAGE + NW * NIS * IDX;
     static constexpr int PE = 256 / NT;          // user dwords copied per lane in the concat step
     // wavefronts per SIMD that LDS lets be resident; the register budget is sized for exactly that
     static constexpr int WG_PER_CU = 163840 / LDS;
@@ -89,9 +92,12 @@ struct Geo {
     static_assert(NI >= 1, "tile too small for this many wavefronts");
 };
 
-template <int DA, int NW, int MODE>
+// QG = groups of 32 queries owned by one wavefront.  With QG = 2 every K and V operand read
+// from LDS feeds two MFMAs, and the weight arithmetic of one group can run while the matrix
+// core works on the other.
+template <int DA, int NW, int QG, int MODE>
 __global__ __launch_bounds__(NW * 64)
-__attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES_PER_EU))) void ckv_dma_kernel(ckv_args a, int nui) {
+__attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES_PER_EU))) void ckv_dma_kernel(ckv_args a, int nui, int dbg) {
     using G = Geo<DA, NW>;
     constexpr int NKK = DA / 16, NDT = DA / 32;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -115,12 +121,15 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
     const uint32_t row_bytes = (uint32_t)a.pool_ld * 2;
 
     // ---- queries of this lane in kernel column order [pool | user], as B operands
-    const int qj = it.q0 + wave * 32 + qn;
-    const bool qok = qj < a.Nq;
-    const int64_t qo = (((int64_t)it.b * a.H + it.h) * a.Nq + (qok ? qj : 0)) * DA;
-    bf16x8 qreg[NKK];
-    {
-        const uint16_t* qp = (const uint16_t*)a.q + qo;
+    bool qok[QG];
+    int64_t qo[QG];
+    bf16x8 qreg[QG][NKK];
+#pragma unroll
+    for (int g = 0; g < QG; ++g) {
+        const int qj = it.q0 + (wave * QG + g) * 32 + qn;
+        qok[g] = qj < a.Nq;
+        qo[g] = (((int64_t)it.b * a.H + it.h) * a.Nq + (qok[g] ? qj : 0)) * DA;
+        const uint16_t* qp = (const uint16_t*)a.q + qo[g];
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk)
 #pragma unroll
@@ -128,20 +137,25 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
                 const int ci = 16 * kk + 8 * hh + e;
                 const int pc = ci < d_g ? ci + d_u : ci - d_g;
                 const uint16_t x = qp[pc];
-                qreg[kk][e] = __builtin_bit_cast(__bf16, qok ? x : (uint16_t)0);
+                qreg[g][kk][e] = __builtin_bit_cast(__bf16, qok[g] ? x : (uint16_t)0);
             }
         // make the compiler finish these loads here: a wait for them inside the tile loop would
         // also drain the asynchronous gathers it does not know about
 #pragma unroll
-        for (int kk = 0; kk < NKK; ++kk) asm volatile("" : "+v"(qreg[kk]));
+        for (int kk = 0; kk < NKK; ++kk) asm volatile("" : "+v"(qreg[g][kk]));
     }
 
-    f32x16 oacc[NDT];
+    f32x16 oacc[QG][NDT];
+    float m_ref[QG], lsum[QG];
 #pragma unroll
-    for (int dt = 0; dt < NDT; ++dt)
+    for (int g = 0; g < QG; ++g) {
+        m_ref[g] = -INFINITY;
+        lsum[g] = 0.f;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
-    float m_ref = -INFINITY, lsum = 0.f;
+        for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[g][dt][r] = 0.f;
+    }
     const float sc = MODE == CKV_SOFTMAX ? a.scale * kLog2e : a.scale;
 
     const int ntiles = (n + TP - 1) / TP;
@@ -198,16 +212,16 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
         const uint32_t vrow = G::KV + (4 * hh + (s16 >> 2)) * G::ROWB + (s16 & 1) * 8;
         const int vc = 2 * (g16 & 1) + ((s16 & 3) >> 1), vx = fv(s16 >> 2);
 
-        const uint32_t idx_lds = lds0 + NS * G::STAGE + wave * 2 * G::IDX;
+        const uint32_t idx_lds = lds0 + NS * G::STAGE + wave * G::NIS * G::IDX;
 
         auto issue_idx = [&](int tile) {
             const int pos = min(tile * TP + qn, n - 1);
             const int32_t* g = (hh ? iv : ik) + pos;
-            dma4(g, idx_lds + (tile & 1) * G::IDX);
+            dma4(g, idx_lds + (tile & (G::NIS - 1)) * G::IDX);
         };
         auto issue_gather = [&](int tile) {
             const uint32_t st = lds0 + (tile & (NS - 1)) * G::STAGE;
-            const lds_u32* islot = (const lds_u32*)(uintptr_t)(idx_lds + (tile & 1) * G::IDX);
+            const lds_u32* islot = (const lds_u32*)(uintptr_t)(idx_lds + (tile & (G::NIS - 1)) * G::IDX);
             int rk[G::NI], rv[G::NI];
 #pragma unroll
             for (int i = 0; i < G::NI; ++i) {
@@ -236,30 +250,38 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
                 if (cok[x]) *(lds_u32*)(uintptr_t)(st + cdst[x]) = *(const lds_u32*)(uintptr_t)(st + csrc[x]);
         };
 
+        // Order of the asynchronous loads of one wavefront: iteration t issues idx(t+5), then the
+        // gathers of tile t+3 (which read idx(t+3) from LDS).  The wait at the end of iteration t
+        // lets only those two groups stay outstanding, so it completes the gathers of tile t+2
+        // and, being older, idx(t+4): the indices a gather needs have always landed two waits
+        // earlier, and no wait is needed before using them.
         issue_idx(0);
+        issue_idx(1);
         wait_vm<0>();
         for (int t = -(NS - 1); t < ntiles; ++t) {
-            // indices of tile t+3 have landed once at most the gathers of tile t+2 are outstanding
-            wait_vm_plus<2 * G::NI>(nui);
-            issue_idx(t + NS);
-            issue_gather(t + NS - 1);
+            issue_idx(t + NS + 1);
+            if (!(dbg & 2)) issue_gather(t + NS - 1);
             if (t + 1 >= 0 && t + 1 < ntiles && d_u > 0) concat(t + 1);
-            if (t >= 0) {
+            if (t >= 0 && !(dbg & 1)) {
                 const uint32_t st = lds0 + (t & (NS - 1)) * G::STAGE;
                 const int nt = min(n - t * TP, TP);
-                // S^T = K Q^T
-                f32x16 sacc;
+                // S^T = K Q^T for every query group; each K operand is read once
+                f32x16 sacc[QG];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
-                bf16x8 ka[NKK];  // all operand reads first, so their LDS latencies overlap
+                for (int g = 0; g < QG; ++g)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) sacc[g][r] = 0.f;
+                bf16x8 ka[NKK];
 #pragma unroll
                 for (int kk = 0; kk < NKK; ++kk)
                     ka[kk] = *(const lds_bf16x8*)(uintptr_t)(st + krow + (((2 * kk + hh) ^ kx) << 4));
 #pragma unroll
-                for (int kk = 0; kk < NKK; ++kk)
-                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk], qreg[kk], sacc, 0, 0, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, NKK, 0);  // all LDS reads ...
-                __builtin_amdgcn_sched_group_barrier(0x008, NKK, 0);  // ... then the MFMAs
+                for (int g = 0; g < QG; ++g)
+#pragma unroll
+                    for (int kk = 0; kk < NKK; ++kk)
+                        sacc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk], qreg[g][kk], sacc[g], 0, 0, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, NKK, 0);       // all LDS reads ...
+                __builtin_amdgcn_sched_group_barrier(0x008, NKK * QG, 0);  // ... then the MFMAs
                 // V^T operands of the whole tile: issued now, so that their LDS latency is hidden
                 // behind the MFMAs above and the weight arithmetic below
                 bf16x8 va[2][NDT];
@@ -275,50 +297,53 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
                 __builtin_amdgcn_sched_group_barrier(0x100, 4 * NDT, 0);
                 __builtin_amdgcn_sched_barrier(0);
                 const bool ragged = nt < TP;
-                bf16x8 pb[2];
-                if (MODE == CKV_SOFTMAX) {
-                    if (ragged) {
 #pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            if (8 * (r >> 2) + 4 * hh + (r & 3) >= nt) sacc[r] = -INFINITY;
+                for (int g = 0; g < QG; ++g) {
+                    bf16x8 pb[2];
+                    if (MODE == CKV_SOFTMAX) {
+                        if (ragged) {
+#pragma unroll
+                            for (int r = 0; r < 16; ++r)
+                                if (8 * (r >> 2) + 4 * hh + (r & 3) >= nt) sacc[g][r] = -INFINITY;
+                        }
+                        float tmax = sacc[g][0];
+#pragma unroll
+                        for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, sacc[g][r]);
+                        tmax = fmaxf(tmax, other_half(tmax)) * sc;
+                        if (__any(tmax > m_ref[g] + kLazy)) {
+                            const float m_new = fmaxf(m_ref[g], tmax);
+                            const float alpha = __builtin_amdgcn_exp2f(m_ref[g] - m_new);
+                            lsum[g] *= alpha;
+#pragma unroll
+                            for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+                                for (int r = 0; r < 16; ++r) oacc[g][dt][r] *= alpha;
+                            m_ref[g] = m_new;
+                        }
+                        float psum = 0.f;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const float p = __builtin_amdgcn_exp2f(fmaf(sacc[g][r], sc, -m_ref[g]));
+                            psum += p;
+                            pb[r >> 3][r & 7] = (__bf16)p;
+                        }
+                        lsum[g] += psum;
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const float x = sacc[g][r] * sc;
+                            float p = x * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-kLog2e * x));
+                            if (ragged && 8 * (r >> 2) + 4 * hh + (r & 3) >= nt) p = 0.f;
+                            pb[r >> 3][r & 7] = (__bf16)p;
+                        }
                     }
-                    float tmax = sacc[0];
+                    // O^T += V^T P^T
 #pragma unroll
-                    for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, sacc[r]);
-                    tmax = fmaxf(tmax, other_half(tmax)) * sc;
-                    if (__any(tmax > m_ref + kLazy)) {
-                        const float m_new = fmaxf(m_ref, tmax);
-                        const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
-                        lsum *= alpha;
+                    for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
                         for (int dt = 0; dt < NDT; ++dt)
-#pragma unroll
-                            for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
-                        m_ref = m_new;
-                    }
-                    float psum = 0.f;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const float p = __builtin_amdgcn_exp2f(fmaf(sacc[r], sc, -m_ref));
-                        psum += p;
-                        pb[r >> 3][r & 7] = (__bf16)p;
-                    }
-                    lsum += psum;
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const float x = sacc[r] * sc;
-                        float p = x * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-kLog2e * x));
-                        if (ragged && 8 * (r >> 2) + 4 * hh + (r & 3) >= nt) p = 0.f;
-                        pb[r >> 3][r & 7] = (__bf16)p;
-                    }
+                            oacc[g][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ks][dt], pb[ks], oacc[g][dt], 0, 0, 0);
                 }
-                // O^T += V^T P^T
-#pragma unroll
-                for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-                    for (int dt = 0; dt < NDT; ++dt)
-                        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ks][dt], pb[ks], oacc[dt], 0, 0, 0);
             }
             // own gathers of tile t+2 have landed once only idx(t+4) and gathers(t+3) are outstanding
             wait_vm_plus<2 * G::NI + 1>(nui);
@@ -328,71 +353,86 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
     }
 
     // ---- epilogue
-    float l_tot = 0.f;
-    if (MODE == CKV_SOFTMAX) l_tot = lsum + other_half(lsum);
-    if (it.part < 0) {
-        float inv;
-        if (MODE == CKV_SOFTMAX) inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-        else inv = it.n_total > 0 ? 1.f / (float)it.n_total : 0.f;
-        if (qok) {
-            uint16_t* op = (uint16_t*)a.out + qo;
+#pragma unroll
+    for (int g = 0; g < QG; ++g) {
+        float l_tot = 0.f;
+        if (MODE == CKV_SOFTMAX) l_tot = lsum[g] + other_half(lsum[g]);
+        if (it.part < 0) {
+            float inv;
+            if (MODE == CKV_SOFTMAX) inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+            else inv = it.n_total > 0 ? 1.f / (float)it.n_total : 0.f;
+            if (qok[g]) {
+                uint16_t* op = (uint16_t*)a.out + qo[g];
+#pragma unroll
+                for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int ci = 32 * dt + 8 * (r >> 2) + 4 * hh + (r & 3);
+                        const int pc = ci < d_g ? ci + d_u : ci - d_g;
+                        op[pc] = f2bf(oacc[g][dt][r] * inv);
+                    }
+            }
+        } else {
+            float* ws = a.partial + (int64_t)it.part * a.QB * (DA + 2);
+            const int j = (wave * QG + g) * 32 + qn;
 #pragma unroll
             for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int ci = 32 * dt + 8 * (r >> 2) + 4 * hh + (r & 3);
                     const int pc = ci < d_g ? ci + d_u : ci - d_g;
-                    op[pc] = f2bf(oacc[dt][r] * inv);
+                    ws[(int64_t)j * DA + pc] = oacc[g][dt][r];
                 }
-        }
-    } else {
-        float* ws = a.partial + (int64_t)it.part * a.QB * (DA + 2);
-        const int j = wave * 32 + qn;
-#pragma unroll
-        for (int dt = 0; dt < NDT; ++dt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int ci = 32 * dt + 8 * (r >> 2) + 4 * hh + (r & 3);
-                const int pc = ci < d_g ? ci + d_u : ci - d_g;
-                ws[(int64_t)j * DA + pc] = oacc[dt][r];
+            if (hh == 0) {
+                ws[(int64_t)a.QB * DA + j] = m_ref[g] * kLn2;
+                ws[(int64_t)a.QB * DA + a.QB + j] = l_tot;
             }
-        if (hh == 0) {
-            ws[(int64_t)a.QB * DA + j] = m_ref * kLn2;
-            ws[(int64_t)a.QB * DA + a.QB + j] = l_tot;
         }
     }
 }
 
-template <int DA, int NW, int MODE>
+template <int DA, int NW, int QG, int MODE>
 hipError_t prepare() {
     constexpr int lds = Geo<DA, NW>::LDS;
     static hipError_t done =
-        hipFuncSetAttribute((const void*)ckv_dma_kernel<DA, NW, MODE>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        hipFuncSetAttribute((const void*)ckv_dma_kernel<DA, NW, QG, MODE>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     return done;
 }
 
-template <int DA, int NW, int MODE>
+template <int DA, int NW, int QG, int MODE>
 hipError_t launch(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
-    hipError_t e = prepare<DA, NW, MODE>();
+    hipError_t e = prepare<DA, NW, QG, MODE>();
     if (e != hipSuccess) return e;
     constexpr int lds = Geo<DA, NW>::LDS;
-    hipLaunchKernelGGL((ckv_dma_kernel<DA, NW, MODE>), dim3(c->n_items), dim3(NW * 64), lds, s, a, c->nui);
+    static const int dbg = getenv("CKV_DMA_DBG") ? atoi(getenv("CKV_DMA_DBG")) : 0;  // timing experiments only
+    hipLaunchKernelGGL((ckv_dma_kernel<DA, NW, QG, MODE>), dim3(c->n_items), dim3(NW * 64), lds, s, a, c->nui, dbg);
     return hipGetLastError();
 }
 
-template <int DA, int NW, int MODE>
+template <int DA, int NW, int QG, int MODE>
 int occupancy() {
-    if (prepare<DA, NW, MODE>() != hipSuccess) return 0;
+    if (prepare<DA, NW, QG, MODE>() != hipSuccess) return 0;
     int nb = 0;
     constexpr int lds = Geo<DA, NW>::LDS;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)ckv_dma_kernel<DA, NW, MODE>, NW * 64, lds) != hipSuccess)
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)ckv_dma_kernel<DA, NW, QG, MODE>, NW * 64, lds) !=
+        hipSuccess)
         return 0;
     return nb;
 }
 
-#define CKV_DMA_SHAPES(X) X(64, 1) X(64, 2) X(64, 4) X(128, 1) X(128, 2) X(128, 4)
+// (d_a, wavefronts per workgroup, query groups per wavefront)
+#define CKV_DMA_SHAPES(X) \
+    X(64, 1, 1) X(64, 1, 2) X(64, 2, 1) X(64, 2, 2) X(64, 4, 1) X(128, 1, 1) X(128, 1, 2) X(128, 2, 1) X(128, 2, 2) X(128, 4, 1)
 
 }  // namespace
+
+bool ckv_dma_supported(int d_a, int nw, int qg) {
+#define X(DA, NW, QG) \
+    if (d_a == DA && nw == NW && qg == QG) return true;
+    CKV_DMA_SHAPES(X)
+#undef X
+    return false;
+}
 
 // Number of user-slice load instructions per wavefront and tile, or -1 if the shape is not
 // served by this kernel.
@@ -403,9 +443,10 @@ int ckv_dma_nui(int d_a, int nw, int d_u) {
     return need <= 1 ? need : (need <= 2 ? 2 : 4);
 }
 
-int ckv_dma_occupancy(int d_a, int nw, int mode) {
-#define X(DA, NW) \
-    if (d_a == DA && nw == NW) return mode == CKV_SOFTMAX ? occupancy<DA, NW, CKV_SOFTMAX>() : occupancy<DA, NW, CKV_SILU_OVER_N>();
+int ckv_dma_occupancy(int d_a, int nw, int qg, int mode) {
+#define X(DA, NW, QG)                          \
+    if (d_a == DA && nw == NW && qg == QG)     \
+        return mode == CKV_SOFTMAX ? occupancy<DA, NW, QG, CKV_SOFTMAX>() : occupancy<DA, NW, QG, CKV_SILU_OVER_N>();
     CKV_DMA_SHAPES(X)
 #undef X
     return 0;
@@ -413,10 +454,11 @@ int ckv_dma_occupancy(int d_a, int nw, int mode) {
 
 hipError_t ckv_launch_dma(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
     if (c->n_items == 0) return hipSuccess;
-    const int d_a = a.d_a, nw = c->nw;
-#define X(DA, NW)                                                                                                  \
-    if (d_a == DA && nw == NW)                                                                                     \
-        return c->shape.mode == CKV_SOFTMAX ? launch<DA, NW, CKV_SOFTMAX>(c, a, s) : launch<DA, NW, CKV_SILU_OVER_N>(c, a, s);
+    const int d_a = a.d_a, nw = c->nw, qg = c->qg;
+#define X(DA, NW, QG)                                                                    \
+    if (d_a == DA && nw == NW && qg == QG)                                               \
+        return c->shape.mode == CKV_SOFTMAX ? launch<DA, NW, QG, CKV_SOFTMAX>(c, a, s)    \
+                                            : launch<DA, NW, QG, CKV_SILU_OVER_N>(c, a, s);
     CKV_DMA_SHAPES(X)
 #undef X
     return hipErrorInvalidValue;

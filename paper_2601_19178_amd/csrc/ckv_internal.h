@@ -60,6 +60,7 @@ struct ckv_cache {
     int vec, ncb;        // stream kernel: elements per lane per column block, column blocks
     int nw, tp;          // mfma kernels: waves per workgroup, positions per tile
     int nui;             // dma kernel: user-slice load instructions per wavefront and tile
+    int qg;              // dma kernel: groups of 32 queries per wavefront
     int QB;              // queries per block
     int n_items, n_merge, n_parts;
     ckv_item* d_items;
@@ -82,6 +83,7 @@ bool ckv_mfma_supported(int d_a, int nw, int tp);
 // Direct-to-LDS variant of the mfma kernel.
 hipError_t ckv_launch_dma(const ckv_cache* c, const ckv_args& a, hipStream_t s);
 int ckv_dma_nui(int d_a, int nw, int d_u);  // -1: shape not served
-int ckv_dma_occupancy(int d_a, int nw, int mode);
+int ckv_dma_occupancy(int d_a, int nw, int qg, int mode);
+bool ckv_dma_supported(int d_a, int nw, int qg);
 
 #endif

@@ -179,19 +179,19 @@ def sampled_users(B, k, seed):
 
 def test_config3_full(gpu):
     w = wl.config("cfg3")
-    run_and_check(gpu, w, "cfg3", users=sampled_users(w["B"], 24, 3), expect_variant="mfma_dma_bf16_d64_w2")
+    run_and_check(gpu, w, "cfg3", users=sampled_users(w["B"], 24, 3), expect_variant="mfma_dma_bf16_d64_w2_g1")
 
 
 def test_config4_full(gpu):
     w = wl.config("cfg4")
     users = sampled_users(w["B"], 3, 4)
     users = np.unique(np.concatenate([users, [int(np.argmax(w["lengths"])), int(np.argmin(w["lengths"]))]])).astype(np.int32)
-    run_and_check(gpu, w, "cfg4", users=users, expect_variant="mfma_dma_bf16_d128_w4")
+    run_and_check(gpu, w, "cfg4", users=users, expect_variant="mfma_dma_bf16_d128_w4_g1")
 
 
 def test_config5_full(gpu):
     w = wl.config("cfg5")
-    run_and_check(gpu, w, "cfg5", users=sampled_users(w["B"], 48, 5), expect_variant="mfma_dma_bf16_d64_w1")
+    run_and_check(gpu, w, "cfg5", users=sampled_users(w["B"], 48, 5), expect_variant="mfma_dma_bf16_d64_w1_g1")
 
 
 # ---------------------------------------------------------------------------------------------
