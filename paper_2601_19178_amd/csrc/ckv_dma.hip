@@ -31,6 +31,8 @@ typedef __attribute__((address_space(3))) unsigned char lds_u8;
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
 typedef __attribute__((address_space(3))) uint32_t lds_u32;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -64,6 +66,14 @@ __device__ __forceinline__ void wait_vm_plus(int nui) {
     else if (nui == 2) wait_vm<BASE + 2>();
     else wait_vm<BASE + 4>();
 }
+// wait until at most 2 * (base + nui) vector-memory operations are outstanding
+template <int BASE>
+__device__ __forceinline__ void wait_vm_twice(int nui) {
+    if (nui == 0) wait_vm<2 * BASE>();
+    else if (nui == 1) wait_vm<2 * (BASE + 1)>();
+    else if (nui == 2) wait_vm<2 * (BASE + 2)>();
+    else wait_vm<2 * (BASE + 4)>();
+}
 __device__ __forceinline__ void lds_barrier() {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
@@ -83,9 +93,8 @@ struct Geo {
     static constexpr int USER = NW * 64 * 4 * NUI_MAX;  // bytes of the user staging of a stage (1 KiB)
     static constexpr int STAGE = 2 * KV + USER;
     static constexpr int IDX = 256;              // bytes of one index slot: 32 x I_k, 32 x I_v
-    static constexpr int NIS = 4;                // index slots per wavefront (indices run 2 tiles ahead of the gathers)
+    static constexpr int NIS = 4;                // index slots per wavefront (indices run 3 tiles ahead of the gathers)
     static constexpr int LDS = NS * STAGE + NW * NIS * IDX;
-    static constexpr int PE = 256 / NT;          // user dwords copied per lane in the concat step
     // wavefronts per SIMD that LDS lets be resident; the register budget is sized for exactly that
     static constexpr int WG_PER_CU = 163840 / LDS;
     static constexpr int WAVES_PER_EU = WG_PER_CU * NW / 4 < 1 ? 1 : (WG_PER_CU * NW / 4 > 8 ? 8 : WG_PER_CU * NW / 4);
@@ -120,29 +129,45 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
     const unsigned char* __restrict__ pv = (const unsigned char*)a.pool_v + (int64_t)it.h * a.P * a.pool_ld * 2;
     const uint32_t row_bytes = (uint32_t)a.pool_ld * 2;
 
-    // ---- queries of this lane in kernel column order [pool | user], as B operands
-    bool qok[QG];
-    int64_t qo[QG];
+    // ---- queries: the wavefront's 32*QG query rows are copied row-major into LDS with
+    //      coalesced 16-byte loads, then every lane picks its B operands (kernel column order
+    //      [pool | user], i.e. paper column + d_u for pool columns) out of LDS.
+    constexpr int QS = DA * 2 + 16;  // bytes per staged row
+    const int qfirst = it.q0 + wave * QG * 32;
+    const int qrows = min(max(a.Nq - qfirst, 0), QG * 32);
+    const int64_t qbyte0 = (((int64_t)it.b * a.H + it.h) * a.Nq + qfirst) * (DA * 2);
+    const uint32_t qlds = lds0 + wave * (QG * 32 * QS);
     bf16x8 qreg[QG][NKK];
+    {
+        const unsigned char* qsrc = (const unsigned char*)a.q + qbyte0;
 #pragma unroll
-    for (int g = 0; g < QG; ++g) {
-        const int qj = it.q0 + (wave * QG + g) * 32 + qn;
-        qok[g] = qj < a.Nq;
-        qo[g] = (((int64_t)it.b * a.H + it.h) * a.Nq + (qok[g] ? qj : 0)) * DA;
-        const uint16_t* qp = (const uint16_t*)a.q + qo[g];
+        for (int i = 0; i < QG * 32 * G::CH / 64; ++i) {
+            const int e = i * 64 + lane, row = e / G::CH, c = e % G::CH;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (row < qrows) v = *reinterpret_cast<const u32x4*>(qsrc + (int64_t)row * (DA * 2) + c * 16);
+            *(lds_u32x4*)(uintptr_t)(qlds + row * QS + c * 16) = v;
+        }
 #pragma unroll
-        for (int kk = 0; kk < NKK; ++kk)
+        for (int g = 0; g < QG; ++g)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int ci = 16 * kk + 8 * hh + e;
-                const int pc = ci < d_g ? ci + d_u : ci - d_g;
-                const uint16_t x = qp[pc];
-                qreg[g][kk][e] = __builtin_bit_cast(__bf16, qok[g] ? x : (uint16_t)0);
+            for (int kk = 0; kk < NKK; ++kk) {
+                u32x4 w;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int ci = 16 * kk + 8 * hh + 2 * j;
+                    const int pc = ci < d_g ? ci + d_u : ci - d_g;
+                    w[j] = *(const lds_u32*)(uintptr_t)(qlds + (g * 32 + qn) * QS + pc * 2);
+                }
+                qreg[g][kk] = __builtin_bit_cast(bf16x8, w);
             }
-        // make the compiler finish these loads here: a wait for them inside the tile loop would
-        // also drain the asynchronous gathers it does not know about
+        // everything above (global loads included) has to be complete here: a compiler-inserted
+        // wait inside the tile loop would also drain the asynchronous gathers it cannot see, and
+        // the gathers are about to overwrite the staging area
 #pragma unroll
-        for (int kk = 0; kk < NKK; ++kk) asm volatile("" : "+v"(qreg[g][kk]));
+        for (int g = 0; g < QG; ++g)
+#pragma unroll
+            for (int kk = 0; kk < NKK; ++kk) asm volatile("" : "+v"(qreg[g][kk]));
+        lds_barrier();
     }
 
     f32x16 oacc[QG][NDT];
@@ -175,35 +200,29 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
             gk_off[i] = ck * 16;
             gv_off[i] = cv * 16;
         }
-        // ---- per-lane constants of the user staging: dword j of the tile's [K_u | V_u] block
-        const int udw = 16 * d_u;  // dwords of one tile's K_u (and of its V_u)
+        // ---- per-lane constants of the user slices.  A wavefront fetches the user slices of
+        //      exactly the rows it gathers, so that after its own wait it can copy them into the
+        //      row tails (the concat) without depending on any other wavefront.  Dword jj of the
+        //      wavefront's block is ((kv * ROWS_W + o) * hd + off): kv = K or V, o = ordinal of the
+        //      own row, off = dword inside the d_u-wide slice (hd = d_u / 2 dwords).
+        constexpr int ROWS_W = TP / NW;
+        const int hd = d_u > 0 ? d_u >> 1 : 1;
         int up[G::NUI_MAX], uoff[G::NUI_MAX];
-        bool uisv[G::NUI_MAX];
+        bool uisv[G::NUI_MAX], uok[G::NUI_MAX];
+        uint32_t cdst[G::NUI_MAX];
 #pragma unroll
         for (int u = 0; u < G::NUI_MAX; ++u) {
-            int j = (u * NW + wave) * 64 + lane;
-            if (j >= 2 * udw) j = 0;
-            uisv[u] = j >= udw;
-            if (uisv[u]) j -= udw;
-            const int hd = d_u > 0 ? d_u >> 1 : 1;
-            up[u] = j / hd;
-            uoff[u] = j - up[u] * hd;
-        }
-        // ---- per-lane constants of the concat step: copy dword e of the staging into its row
-        uint32_t csrc[G::PE], cdst[G::PE];
-        bool cok[G::PE];
-#pragma unroll
-        for (int x = 0; x < G::PE; ++x) {
-            int e = x * G::NT + tid;
-            cok[x] = e < 2 * udw;
-            if (!cok[x]) e = 0;
-            csrc[x] = 2 * G::KV + e * 4;
-            const bool isv = e >= udw;
-            if (isv) e -= udw;
-            const int hd = d_u > 0 ? d_u >> 1 : 1;
-            const int p = e / hd, col = d_g + 2 * (e - p * hd);
-            const int slot = (col >> 3) ^ (isv ? fv(p) : fk(p));
-            cdst[x] = (isv ? G::KV : 0) + p * G::ROWB + slot * 16 + (col & 7) * 2;
+            int jj = u * 64 + lane;
+            uok[u] = u < nui && jj < 2 * ROWS_W * hd;
+            if (!uok[u]) jj = 0;
+            const int slice = jj / hd;            // kv * ROWS_W + o
+            uoff[u] = jj - slice * hd;
+            uisv[u] = slice >= ROWS_W;
+            const int o = uisv[u] ? slice - ROWS_W : slice;
+            up[u] = ((o / G::RPI) * NW + wave) * G::RPI + (o % G::RPI);
+            const int col = d_g + 2 * uoff[u];
+            const int slot = (col >> 3) ^ (uisv[u] ? fv(up[u]) : fk(up[u]));
+            cdst[u] = (uisv[u] ? G::KV : 0) + up[u] * G::ROWB + slot * 16 + (col & 7) * 2;
         }
         // ---- per-lane constants of the operand reads
         const uint32_t krow = qn * G::ROWB;
@@ -238,30 +257,37 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
             for (int u = 0; u < G::NUI_MAX; ++u) {
                 if (u < nui) {
                     const int pos = min(tile * TP + up[u], n - 1);
-                    const uint32_t* g = (uisv[u] ? uv32 : uk32) + (int64_t)pos * (d_u >> 1) + uoff[u];
-                    dma4(g, st + 2 * G::KV + (u * NW + wave) * 256);
+                    const uint32_t* g = (uisv[u] ? uv32 : uk32) + (int64_t)pos * hd + uoff[u];
+                    dma4(g, st + 2 * G::KV + (wave * G::NUI_MAX + u) * 256);
                 }
             }
         };
+        // the paper's concat: user columns behind the pool columns of the wavefront's own rows
         auto concat = [&](int tile) {
             const uint32_t st = lds0 + (tile & (NS - 1)) * G::STAGE;
+            uint32_t x[G::NUI_MAX];
 #pragma unroll
-            for (int x = 0; x < G::PE; ++x)
-                if (cok[x]) *(lds_u32*)(uintptr_t)(st + cdst[x]) = *(const lds_u32*)(uintptr_t)(st + csrc[x]);
+            for (int u = 0; u < G::NUI_MAX; ++u)
+                if (uok[u]) x[u] = *(const lds_u32*)(uintptr_t)(st + 2 * G::KV + (wave * G::NUI_MAX + u) * 256 + lane * 4);
+#pragma unroll
+            for (int u = 0; u < G::NUI_MAX; ++u)
+                if (uok[u]) *(lds_u32*)(uintptr_t)(st + cdst[u]) = x[u];
         };
 
-        // Order of the asynchronous loads of one wavefront: iteration t issues idx(t+5), then the
+        // Order of the asynchronous loads of one wavefront: iteration t issues idx(t+6), then the
         // gathers of tile t+3 (which read idx(t+3) from LDS).  The wait at the end of iteration t
-        // lets only those two groups stay outstanding, so it completes the gathers of tile t+2
-        // and, being older, idx(t+4): the indices a gather needs have always landed two waits
-        // earlier, and no wait is needed before using them.
+        // lets the last two iterations' loads stay outstanding, so it completes the wavefront's
+        // gathers of tile t+1 and, being older, idx(t+4): three tiles of gathers are in flight
+        // while one is computed, and the indices a gather needs landed at least one wait earlier.
+        // After its wait the wavefront concatenates its own rows of tile t+1; the barrier then
+        // publishes tile t+1 to the workgroup and retires tile t's stage.
         issue_idx(0);
         issue_idx(1);
+        issue_idx(2);
         wait_vm<0>();
         for (int t = -(NS - 1); t < ntiles; ++t) {
-            issue_idx(t + NS + 1);
+            if (!(dbg & 16)) issue_idx(t + NS + 2);
             if (!(dbg & 2)) issue_gather(t + NS - 1);
-            if (t + 1 >= 0 && t + 1 < ntiles && d_u > 0) concat(t + 1);
             if (t >= 0 && !(dbg & 1)) {
                 const uint32_t st = lds0 + (t & (NS - 1)) * G::STAGE;
                 const int nt = min(n - t * TP, TP);
@@ -345,35 +371,51 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
                             oacc[g][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ks][dt], pb[ks], oacc[g][dt], 0, 0, 0);
                 }
             }
-            // own gathers of tile t+2 have landed once only idx(t+4) and gathers(t+3) are outstanding
-            wait_vm_plus<2 * G::NI + 1>(nui);
-            lds_barrier();
+            // own gathers of tile t+1 have landed once only the loads of this and the previous
+            // iteration are outstanding
+            wait_vm_twice<2 * G::NI + 1>(nui);
+            if (t + 1 >= 0 && t + 1 < ntiles && d_u > 0 && !(dbg & 8)) concat(t + 1);
+            if (!(dbg & 4)) lds_barrier();
         }
-        wait_vm<0>();  // the clamped loads past the last tile must not outlive the workgroup's LDS
+        // the clamped loads past the last tile must have landed, for every wavefront, before the
+        // epilogue reuses the stages (and before the workgroup gives its LDS back)
+        wait_vm<0>();
+        lds_barrier();
     }
 
-    // ---- epilogue
+    // ---- epilogue.  Whole histories: normalise, transpose through LDS (the tile loop's last
+    //      barrier has retired every stage) and write complete output rows, 16 bytes per lane.
+    //      Pieces of a split history: unnormalised fp32 accumulators, maximum and sum.
+    float l_tot[QG];
 #pragma unroll
-    for (int g = 0; g < QG; ++g) {
-        float l_tot = 0.f;
-        if (MODE == CKV_SOFTMAX) l_tot = lsum[g] + other_half(lsum[g]);
-        if (it.part < 0) {
+    for (int g = 0; g < QG; ++g) l_tot[g] = MODE == CKV_SOFTMAX ? lsum[g] + other_half(lsum[g]) : 0.f;
+    if (it.part < 0) {
+#pragma unroll
+        for (int g = 0; g < QG; ++g) {
             float inv;
-            if (MODE == CKV_SOFTMAX) inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+            if (MODE == CKV_SOFTMAX) inv = l_tot[g] > 0.f ? 1.f / l_tot[g] : 0.f;
             else inv = it.n_total > 0 ? 1.f / (float)it.n_total : 0.f;
-            if (qok[g]) {
-                uint16_t* op = (uint16_t*)a.out + qo[g];
 #pragma unroll
-                for (int dt = 0; dt < NDT; ++dt)
+            for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int ci = 32 * dt + 8 * (r >> 2) + 4 * hh + (r & 3);
-                        const int pc = ci < d_g ? ci + d_u : ci - d_g;
-                        op[pc] = f2bf(oacc[g][dt][r] * inv);
-                    }
-            }
-        } else {
-            float* ws = a.partial + (int64_t)it.part * a.QB * (DA + 2);
+                for (int r = 0; r < 16; r += 2) {
+                    const int ci = 32 * dt + 8 * (r >> 2) + 4 * hh + (r & 3);
+                    const int pc = ci < d_g ? ci + d_u : ci - d_g;
+                    const uint32_t two = (uint32_t)f2bf(oacc[g][dt][r] * inv) | ((uint32_t)f2bf(oacc[g][dt][r + 1] * inv) << 16);
+                    *(lds_u32*)(uintptr_t)(qlds + (g * 32 + qn) * QS + pc * 2) = two;
+                }
+        }
+        unsigned char* odst = (unsigned char*)a.out + qbyte0;
+#pragma unroll
+        for (int i = 0; i < QG * 32 * G::CH / 64; ++i) {
+            const int e = i * 64 + lane, row = e / G::CH, c = e % G::CH;
+            const u32x4 v = *(const lds_u32x4*)(uintptr_t)(qlds + row * QS + c * 16);
+            if (row < qrows) *reinterpret_cast<u32x4*>(odst + (int64_t)row * (DA * 2) + c * 16) = v;
+        }
+    } else {
+        float* ws = a.partial + (int64_t)it.part * a.QB * (DA + 2);
+#pragma unroll
+        for (int g = 0; g < QG; ++g) {
             const int j = (wave * QG + g) * 32 + qn;
 #pragma unroll
             for (int dt = 0; dt < NDT; ++dt)
@@ -385,7 +427,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
                 }
             if (hh == 0) {
                 ws[(int64_t)a.QB * DA + j] = m_ref[g] * kLn2;
-                ws[(int64_t)a.QB * DA + a.QB + j] = l_tot;
+                ws[(int64_t)a.QB * DA + a.QB + j] = l_tot[g];
             }
         }
     }
