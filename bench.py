@@ -114,12 +114,26 @@ def main():
     ap.add_argument("--workload", default="cfg4", choices=sorted(DESCRIBE))
     ap.add_argument("--also", default="cfg2_f32,cfg2_bf16,cfg3", help="comma list of further workloads ('' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy-mb", type=int, default=0,
+                    help="only run the library's plain copy kernel on this many MiB (counter calibration) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1")
     import torch
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the hot path has no CPU fallback")
+
+    if args.calibrate_copy_mb > 0:
+        from paper_2601_19178_amd import ckv
+        nbytes = args.calibrate_copy_mb << 20
+        src = torch.full((nbytes,), 7, dtype=torch.uint8, device="cuda")
+        dst = torch.zeros_like(src)
+        stream = torch.cuda.current_stream().cuda_stream
+        for _ in range(args.steps):
+            ckv.ckv_copy(dst, src, nbytes, stream)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes": nbytes, "launches": args.steps}))
+        return
 
     head, w, sess = measure(args.workload, args.steps, args.warmup)
     base = None if args.no_cpu_baseline else cpu_baseline(w)
