@@ -159,6 +159,17 @@ int ckv_set_timing(ckv_cache* cache, int pairs);
 float ckv_kernel_ms(ckv_cache* cache);
 const char* ckv_variant(const ckv_cache* cache);
 int ckv_copy(void* dst, const void* src, size_t nbytes, void* stream);
+/*
+ * Per-workgroup timeline of the matrix-core kernel, for load-balance studies.  After
+ * ckv_trace_enable(cache, 1) every ckv_attend on the handle records, per work item in launch
+ * order, 8 words: [0] start, [1] tile loop entered, [2] tile loop left, [3] end (all in ticks of
+ * the 100 MHz wall clock), [4] hardware id (XCC id << 32 | HW_ID), [5] positions, [6..7] unused.
+ * ckv_trace_read synchronises the device and copies up to max_items records to `host`
+ * (8 * max_items words); it returns the number of records or a negative error.  Costs one
+ * allocation; switch it off (enable = 0) for timed runs.
+ */
+int ckv_trace_enable(ckv_cache* cache, int enable);
+int64_t ckv_trace_read(ckv_cache* cache, unsigned long long* host, int64_t max_items);
 
 #ifdef __cplusplus
 }

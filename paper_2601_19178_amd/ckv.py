@@ -21,7 +21,7 @@ CKV_OK, CKV_ERR_NULL, CKV_ERR_SHAPE, CKV_ERR_INDEX, CKV_ERR_LENGTH, CKV_ERR_UNSU
 EXPORTS = [
     "ckv_build_cache", "ckv_cache_idx", "ckv_cache_user_k", "ckv_cache_user_v", "ckv_cache_lengths",
     "ckv_cache_positions", "ckv_cache_stored_bytes", "ckv_attend", "ckv_reconstruct", "ckv_free",
-    "ckv_last_error", "ckv_set_timing", "ckv_kernel_ms", "ckv_variant", "ckv_copy",
+    "ckv_last_error", "ckv_set_timing", "ckv_kernel_ms", "ckv_variant", "ckv_copy", "ckv_trace_enable", "ckv_trace_read",
 ]
 
 
@@ -66,6 +66,10 @@ _lib.ckv_kernel_ms.restype = ctypes.c_float
 _lib.ckv_kernel_ms.argtypes = [_vp]
 _lib.ckv_variant.restype = ctypes.c_char_p
 _lib.ckv_variant.argtypes = [_vp]
+_lib.ckv_trace_enable.restype = ctypes.c_int
+_lib.ckv_trace_enable.argtypes = [_vp, ctypes.c_int]
+_lib.ckv_trace_read.restype = _i64
+_lib.ckv_trace_read.argtypes = [_vp, _vp, _i64]
 _lib.ckv_copy.restype = ctypes.c_int
 _lib.ckv_copy.argtypes = [_vp, _vp, ctypes.c_size_t, _vp]
 
@@ -158,3 +162,16 @@ def ckv_variant(cache):
 
 def ckv_copy(dst, src, nbytes, stream=0):
     _check(_lib.ckv_copy(_dev(dst), _dev(src), nbytes, _vp(stream)))
+
+
+def ckv_trace_enable(cache, enable):
+    _check(_lib.ckv_trace_enable(cache, int(enable)))
+
+
+def ckv_trace_read(cache, max_items):
+    """numpy uint64 [n][8] timeline records (see include/ckv.h)."""
+    buf = np.zeros((max_items, 8), dtype=np.uint64)
+    n = _lib.ckv_trace_read(cache, _vp(buf.ctypes.data), max_items)
+    if n < 0:
+        raise CkvError(int(n), ckv_last_error())
+    return buf[:n]

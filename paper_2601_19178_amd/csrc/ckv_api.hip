@@ -282,6 +282,168 @@ void build_work(ckv_cache* c, const int32_t* lengths, const std::vector<int64_t>
                 best_cost);
 }
 
+// Static work lists for the persistent direct-to-LDS kernel: exactly `slots` workgroups are
+// launched (all resident at once), workgroup i runs on XCD i mod 8 and serves one head class,
+// and every workgroup gets its own list of pieces.  Pieces are assigned longest first to the
+// least loaded workgroup of their class; then load is moved from the fullest to the emptiest
+// workgroup by cutting the tail off a piece (the two halves become a split history that the
+// merge kernel joins), until every workgroup is within a few percent of the mean.  With two
+// long histories per workgroup (the long ragged workload) the greedy assignment alone leaves
+// the last workgroups running ~10 % longer than the median.
+struct Piece {
+    int unit;        // index into units
+    int64_t lo;      // first position of the piece inside the unit
+    int64_t n;       // positions
+};
+
+double assign_static(const ckv_cache* c, const std::vector<Unit>& units, int64_t piece_len, int64_t slots, int64_t overhead,
+                     double part_positions, std::vector<std::vector<Piece>>& lists, int* n_parts_out) {
+    const ckv_shape& s = c->shape;
+    int ncls = 1;
+    if (s.H >= 8 && s.H % 8 == 0) ncls = 8;
+    else if (s.H < 8 && 8 % s.H == 0) ncls = s.H;
+    lists.assign((size_t)slots, {});
+    std::vector<int64_t> load((size_t)slots, 0);
+    std::vector<int> pieces_of_unit(units.size(), 0);
+    double worst = 0;
+    for (int cls = 0; cls < ncls; ++cls) {
+        std::vector<int> wgs;
+        for (int i = 0; i < (int)slots; ++i)
+            if ((i % 8) % ncls == cls) wgs.push_back(i);
+        if (wgs.empty()) continue;
+        std::vector<Piece> ps;
+        for (int u = 0; u < (int)units.size(); ++u) {
+            if (units[u].h % ncls != cls) continue;
+            const int64_t n = units[u].n;
+            const int np = n > piece_len ? (int)((n + piece_len - 1) / piece_len) : 1;
+            int64_t len = np > 1 ? ((n + np - 1) / np + 63) / 64 * 64 : n;
+            if (np == 1) {
+                ps.push_back({u, 0, n});
+                pieces_of_unit[(size_t)u] = 1;
+            } else {
+                int k = 0;
+                for (int64_t lo = 0; lo < n; lo += len, ++k) ps.push_back({u, lo, std::min<int64_t>(len, n - lo)});
+                pieces_of_unit[(size_t)u] = k;
+            }
+        }
+        std::stable_sort(ps.begin(), ps.end(), [](const Piece& x, const Piece& y) { return x.n > y.n; });
+        // longest first onto the least loaded workgroup
+        auto cmp = [&](int x, int y) { return load[(size_t)x] > load[(size_t)y] || (load[(size_t)x] == load[(size_t)y] && x > y); };
+        std::vector<int> heap = wgs;
+        std::make_heap(heap.begin(), heap.end(), cmp);
+        for (const Piece& p : ps) {
+            std::pop_heap(heap.begin(), heap.end(), cmp);
+            const int w = heap.back();
+            lists[(size_t)w].push_back(p);
+            load[(size_t)w] += p.n + overhead;
+            std::push_heap(heap.begin(), heap.end(), cmp);
+        }
+        // move load from the fullest to the emptiest workgroup
+        int64_t total = 0;
+        for (int w : wgs) total += load[(size_t)w];
+        const int64_t target = total / (int64_t)wgs.size();
+        const int64_t tol = std::max<int64_t>(target / 50, 256);
+        for (size_t iter = 0; iter < 2 * wgs.size(); ++iter) {
+            int d = wgs[0], r = wgs[0];
+            for (int w : wgs) {
+                if (load[(size_t)w] > load[(size_t)d]) d = w;
+                if (load[(size_t)w] < load[(size_t)r]) r = w;
+            }
+            const int64_t excess = load[(size_t)d] - target, deficit = target - load[(size_t)r] - overhead;
+            if (excess < tol || deficit < 256) break;
+            int64_t move = std::min(excess, deficit) / 32 * 32;
+            if (move < 256) break;
+            // cut the tail off the longest piece of the donor
+            std::vector<Piece>& dl = lists[(size_t)d];
+            size_t best = 0;
+            for (size_t k = 1; k < dl.size(); ++k)
+                if (dl[k].n > dl[best].n) best = k;
+            if (dl.empty() || dl[best].n - move < 256) break;
+            const int64_t keep = (dl[best].n - move + 31) / 32 * 32;  // keep the cut on a tile boundary
+            move = dl[best].n - keep;
+            if (move < 256) break;
+            lists[(size_t)r].push_back({dl[best].unit, dl[best].lo + keep, move});
+            dl[best].n = keep;
+            pieces_of_unit[(size_t)dl[best].unit]++;
+            load[(size_t)d] -= move;
+            load[(size_t)r] += move + overhead;
+        }
+        for (int w : wgs) worst = std::max(worst, (double)load[(size_t)w]);
+    }
+    int parts = 0;
+    for (int k : pieces_of_unit)
+        if (k > 1) parts += k;
+    *n_parts_out = parts;
+    double cost = worst + parts * part_positions / (double)slots;
+    if (parts > 0) cost *= 1.01;
+    return cost;
+}
+
+void build_work_static(ckv_cache* c, const int32_t* lengths, const std::vector<int64_t>& offs, int cus,
+                       std::vector<ckv_item>& items, std::vector<ckv_merge>& merges, std::vector<int32_t>& wg_begin) {
+    const ckv_shape& s = c->shape;
+    const int d_a = s.d_g + s.d_u;
+    const int nqb = (s.Nq + c->QB - 1) / c->QB;
+    const int wg_per_cu = std::max(1, ckv_dma_occupancy(d_a, c->nw, c->qg, s.mode));
+    const int64_t slots = (int64_t)cus * wg_per_cu;
+    std::vector<Unit> units;
+    int64_t longest = 0;
+    for (int b = 0; b < s.B; ++b)
+        for (int h = 0; h < s.H; ++h)
+            for (int qb = 0; qb < nqb; ++qb) {
+                units.push_back({b, h, qb * c->QB, lengths[b], offs[b]});
+                longest = std::max<int64_t>(longest, lengths[b]);
+            }
+    const int64_t overhead = 192;  // per-item fill, drain and epilogue, in positions
+    const double part_positions = (double)c->QB * (d_a + 2) * 8.0 / (2.0 * d_a * 2.0 + 8.0);
+    std::vector<std::vector<Piece>> best;
+    double best_cost = -1;
+    int64_t best_piece = 0;
+    for (int64_t piece = INT64_MAX; piece >= 512; piece = (piece == INT64_MAX ? (longest + 1) / 2 : piece / 2)) {
+        if (piece != INT64_MAX) piece = (piece + 63) / 64 * 64;
+        std::vector<std::vector<Piece>> lists;
+        int parts = 0;
+        const double cost = assign_static(c, units, piece, slots, overhead, part_positions, lists, &parts);
+        if (best_cost < 0 || cost < best_cost) {
+            best_cost = cost;
+            best.swap(lists);
+            best_piece = piece;
+        }
+        if (piece != INT64_MAX && piece <= 512) break;
+        if (units.size() > (size_t)(8 * slots)) break;  // plenty of units per workgroup: uniform cuts cannot pay
+    }
+    // part slots: the pieces of a split unit get consecutive workspace slots, in position order
+    std::vector<std::vector<std::pair<int64_t, std::pair<int, int>>>> by_unit(units.size());  // lo -> (wg, index in list)
+    for (int w = 0; w < (int)best.size(); ++w)
+        for (int k = 0; k < (int)best[(size_t)w].size(); ++k)
+            by_unit[(size_t)best[(size_t)w][(size_t)k].unit].push_back({best[(size_t)w][(size_t)k].lo, {w, k}});
+    std::vector<std::vector<int>> part_of(best.size());
+    for (size_t w = 0; w < best.size(); ++w) part_of[w].assign(best[w].size(), -1);
+    int next_part = 0;
+    for (size_t u = 0; u < units.size(); ++u) {
+        auto& v = by_unit[u];
+        if (v.size() <= 1) continue;
+        std::sort(v.begin(), v.end());
+        merges.push_back({units[u].b, units[u].h, units[u].q0, next_part, (int)v.size(), units[u].n});
+        for (auto& e : v) part_of[(size_t)e.second.first][(size_t)e.second.second] = next_part++;
+    }
+    c->n_parts = next_part;
+    wg_begin.assign(best.size() + 1, 0);
+    for (size_t w = 0; w < best.size(); ++w) {
+        wg_begin[w] = (int32_t)items.size();
+        for (size_t k = 0; k < best[w].size(); ++k) {
+            const Piece& p = best[w][k];
+            const Unit& u = units[(size_t)p.unit];
+            items.push_back({u.b, u.h, u.q0, (int32_t)p.n, u.t0 + p.lo, part_of[w][k], u.n});
+        }
+    }
+    wg_begin[best.size()] = (int32_t)items.size();
+    if (getenv("CKV_DEBUG"))
+        fprintf(stderr, "ckv: %s: %zu units on %lld persistent workgroups, piece %lld -> %zu items, %d parts, cost %.0f positions\n",
+                c->variant, units.size(), (long long)slots, (long long)(best_piece == INT64_MAX ? -1 : best_piece), items.size(),
+                next_part, best_cost);
+}
+
 void choose_variant(ckv_cache* c) {
     const ckv_shape& s = c->shape;
     const int d_a = s.d_g + s.d_u;
@@ -335,8 +497,10 @@ void destroy(ckv_cache* c) {
     (void)hipFree(c->d_user_v);
     (void)hipFree(c->d_lengths);
     (void)hipFree(c->d_items);
+    (void)hipFree(c->d_wg_begin);
     (void)hipFree(c->d_merge);
     (void)hipFree(c->d_partial);
+    (void)hipFree(c->d_trace);
     for (int i = 0; i < 2 * c->timing; ++i) (void)hipEventDestroy(c->ev[i]);
     delete[] c->ev;
     delete c;
@@ -451,7 +615,27 @@ int ckv_build_cache(const ckv_shape* shape, const int32_t* lengths, const int32_
         goto done;
     }
 
-    build_work(c, lengths, offs, prop.multiProcessorCount, items, merges);
+    if (c->family == CKV_K_DMA) {
+        // Two ways to hand out work.  Static (default): one resident workgroup per slot with its
+        // own item list, no relaunch gaps.  Dynamic: one workgroup per item in longest-first order,
+        // scheduled by the hardware dispatcher as slots free up.  Static measured faster on every
+        // workload (uniform lengths: by 20 %; two long ragged histories per slot: by 2 %).
+        bool use_static = true;
+        if (const char* e = getenv("CKV_DMA_SCHED")) use_static = strcmp(e, "static") == 0;  // tuning knob
+        std::vector<int32_t> wg_begin;
+        if (use_static) {
+            build_work_static(c, lengths, offs, prop.multiProcessorCount, items, merges, wg_begin);
+        } else {
+            build_work(c, lengths, offs, prop.multiProcessorCount, items, merges);
+            wg_begin.resize(items.size() + 1);
+            for (size_t i = 0; i <= items.size(); ++i) wg_begin[i] = (int32_t)i;
+        }
+        c->n_wg = (int)wg_begin.size() - 1;
+        CKV_HIP(hipMalloc((void**)&c->d_wg_begin, sizeof(int32_t) * wg_begin.size()));
+        CKV_HIP(hipMemcpy(c->d_wg_begin, wg_begin.data(), sizeof(int32_t) * wg_begin.size(), hipMemcpyHostToDevice));
+    } else {
+        build_work(c, lengths, offs, prop.multiProcessorCount, items, merges);
+    }
     c->n_items = (int)items.size();
     c->n_merge = (int)merges.size();
     if (c->n_items > 0) {
@@ -511,7 +695,9 @@ int ckv_attend(const ckv_cache* c, const void* pool_k, const void* pool_v, const
     a.q = q;
     a.out = out;
     a.items = c->d_items;
+    a.wg_begin = c->d_wg_begin;
     a.partial = c->d_partial;
+    a.trace = c->d_trace;
     a.T = c->T;
     a.pool_ld = s.pool_ld;
     a.H = s.H;
@@ -625,6 +811,32 @@ float ckv_kernel_ms(ckv_cache* c) {
         sum += ms;
     }
     return (float)(sum / n);
+}
+
+int ckv_trace_enable(ckv_cache* c, int enable) {
+    if (!c) return fail(CKV_ERR_NULL, "ckv_trace_enable: cache is NULL");
+    (void)hipFree(c->d_trace);
+    c->d_trace = nullptr;
+    if (!enable || c->n_items == 0) return CKV_OK;
+    const size_t bytes = sizeof(unsigned long long) * 8 * (size_t)c->n_items;
+    hipError_t e = hipMalloc((void**)&c->d_trace, bytes);
+    if (e == hipSuccess) e = hipMemset(c->d_trace, 0, bytes);
+    if (e != hipSuccess) {
+        c->d_trace = nullptr;
+        return fail(CKV_ERR_HIP, "ckv_trace_enable: %s", hipGetErrorString(e));
+    }
+    return CKV_OK;
+}
+
+int64_t ckv_trace_read(ckv_cache* c, unsigned long long* host, int64_t max_items) {
+    if (!c || !host) return fail(CKV_ERR_NULL, "ckv_trace_read: NULL argument");
+    if (!c->d_trace) return 0;
+    const int64_t n = std::min<int64_t>(max_items, c->n_items);
+    if (n <= 0) return 0;
+    hipError_t e = hipDeviceSynchronize();
+    if (e == hipSuccess) e = hipMemcpy(host, c->d_trace, sizeof(unsigned long long) * 8 * (size_t)n, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return fail(CKV_ERR_HIP, "ckv_trace_read: %s", hipGetErrorString(e));
+    return n;
 }
 
 int ckv_copy(void* dst, const void* src, size_t nbytes, void* stream) {

@@ -112,10 +112,20 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_u8*)smem;
 
-    const ckv_item it = a.items[blockIdx.x];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // persistent workgroup: one list of work items per workgroup
+    const int item_end = a.wg_begin[blockIdx.x + 1];
+    for (int item = a.wg_begin[blockIdx.x]; item < item_end; ++item) {
+    const ckv_item it = a.items[item];
+    unsigned long long* tr = a.trace ? a.trace + (size_t)item * 8 : nullptr;
+    if (tr && tid == 0) {
+        tr[0] = wall_clock64();
+        tr[4] = ((unsigned long long)__builtin_amdgcn_s_getreg((20 << 0) | (0 << 6) | (31 << 11)) << 32) |
+                (unsigned)__builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (31 << 11));
+        tr[5] = (unsigned long long)it.n;
+    }
     const int qn = lane & 31, hh = lane >> 5;
     const int d_g = a.d_g, d_u = a.d_u;
     const int n = it.n;
@@ -285,6 +295,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
         issue_idx(1);
         issue_idx(2);
         wait_vm<0>();
+        if (tr && tid == 0) tr[1] = wall_clock64();
         for (int t = -(NS - 1); t < ntiles; ++t) {
             if (!(dbg & 16)) issue_idx(t + NS + 2);
             if (!(dbg & 2)) issue_gather(t + NS - 1);
@@ -381,6 +392,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
         // epilogue reuses the stages (and before the workgroup gives its LDS back)
         wait_vm<0>();
         lds_barrier();
+        if (tr && tid == 0) tr[2] = wall_clock64();
     }
 
     // ---- epilogue.  Whole histories: normalise, transpose through LDS (the tile loop's last
@@ -431,6 +443,8 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
             }
         }
     }
+    if (tr && tid == 0) tr[3] = wall_clock64();
+    }  // items of this workgroup
 }
 
 template <int DA, int NW, int QG, int MODE>
@@ -447,7 +461,7 @@ hipError_t launch(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
     if (e != hipSuccess) return e;
     constexpr int lds = Geo<DA, NW>::LDS;
     static const int dbg = getenv("CKV_DMA_DBG") ? atoi(getenv("CKV_DMA_DBG")) : 0;  // timing experiments only
-    hipLaunchKernelGGL((ckv_dma_kernel<DA, NW, QG, MODE>), dim3(c->n_items), dim3(NW * 64), lds, s, a, c->nui, dbg);
+    hipLaunchKernelGGL((ckv_dma_kernel<DA, NW, QG, MODE>), dim3(c->n_wg), dim3(NW * 64), lds, s, a, c->nui, dbg);
     return hipGetLastError();
 }
 

@@ -36,7 +36,9 @@ struct ckv_args {
     const void* q;         // [B][H][Nq][d_a]
     void* out;             // [B][H][Nq][d_a]
     const ckv_item* items;
+    const int32_t* wg_begin;  // persistent kernel: items [wg_begin[i], wg_begin[i+1]) belong to workgroup i
     float* partial;        // split workspace: per slot [QB][d_a] acc, [QB] m, [QB] l
+    unsigned long long* trace;  // optional: 8 words per item (timestamps, hardware id), or nullptr
     int64_t T;
     int64_t pool_ld;
     int32_t H, P, d_g, d_u, d_a, Nq;
@@ -64,8 +66,11 @@ struct ckv_cache {
     int QB;              // queries per block
     int n_items, n_merge, n_parts;
     ckv_item* d_items;
+    int32_t* d_wg_begin;  // persistent kernel only
+    int n_wg;             // persistent kernel only: workgroups launched
     ckv_merge* d_merge;
     float* d_partial;
+    unsigned long long* d_trace;  // 8 words per item while tracing is on
     // timing: ring of event pairs around the main kernel, filled while timing > 0
     int timing;            // number of pairs in the ring (0 = off)
     long long ev_count;    // launches recorded since timing was switched on
