@@ -112,12 +112,16 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_u8*)smem;
 
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // persistent workgroup: one list of work items per workgroup
     const int item_end = a.wg_begin[blockIdx.x + 1];
     for (int item = a.wg_begin[blockIdx.x]; item < item_end; ++item) {
+    // The lane id is laundered once per item so that the many per-lane constants derived from it
+    // are recomputed per item (a few dozen ALU operations) instead of being kept alive, and
+    // spilled, across the whole kernel.
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63;
     const ckv_item it = a.items[item];
     unsigned long long* tr = a.trace ? a.trace + (size_t)item * 8 : nullptr;
     if (tr && tid == 0) {
