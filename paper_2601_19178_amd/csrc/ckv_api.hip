@@ -146,14 +146,20 @@ struct Unit {
 };
 
 int pick_stream_vec(const ckv_shape& s) {
+    // widest vector the alignment allows, but no wider than what keeps all sixteen lanes of a row
+    // busy: among the admissible widths take the one with the fewest column blocks, narrowest first
     const int d_a = s.d_g + s.d_u;
-    const int maxvec = s.dtype == CKV_F32 ? 4 : 8;
-    for (int v = maxvec; v > 1; v >>= 1) {
-        if (v == 2) continue;  // not instantiated
+    int best = 1, best_ncb = (d_a + 15) / 16;
+    for (int v : {4, 8}) {
+        if (v == 8 && s.dtype == CKV_F32) continue;
         if (s.d_u % v || s.d_g % v || (s.d_g > 0 && s.pool_ld % v)) continue;
-        if ((d_a + 16 * v - 1) / (16 * v) <= 8) return v;
+        const int ncb = (d_a + 16 * v - 1) / (16 * v);
+        if (ncb < best_ncb) {
+            best = v;
+            best_ncb = ncb;
+        }
     }
-    return 1;
+    return best;
 }
 
 // Cut units into pieces of at most `piece` positions and order them (see above).

@@ -1,8 +1,10 @@
 // Streaming (vector-ALU) gather-concat-attend kernel: the path for few queries per user
 // (target attention, Q in R^{1 x d}, section 2.1) and the general fallback for any shape.
 //
-// One 64-lane wavefront serves one work item (a run of positions of one user and head) for
-// every query of the block, one query after the other.  A tile is 64 positions.  Sixteen
+// A workgroup of four 64-lane wavefronts serves one work item (a run of positions of one user
+// and head) for every query of the block, one query after the other.  A tile is 64 positions;
+// wavefront w takes tiles w, w+4, ... and the four partial results (maximum, sum, weighted sum)
+// are merged through LDS.  Sixteen
 // lanes share one final K (or V) row: lane c of the group owns the columns
 // (cb*16 + c)*VEC .. +VEC of every column block cb, taken from the user slice when the
 // column is < d_u and from the gathered pool row otherwise (eq. "eq: Kc", "eq: K": the
@@ -15,6 +17,7 @@ namespace {
 
 constexpr int kLanes = 64;
 constexpr int kGroup = 16;  // lanes per row
+constexpr int kWaves = 4;   // wavefronts per work item
 
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
@@ -52,9 +55,11 @@ __device__ __forceinline__ void load_vec(float (&dst)[VEC], const T* src) {
 }
 
 template <typename T, int VEC, int NCB, int MODE>
-__global__ __launch_bounds__(kLanes) void ckv_stream_kernel(ckv_args a) {
+__global__ __launch_bounds__(kLanes * kWaves) void ckv_stream_kernel(ckv_args a) {
+    __shared__ float sm_acc[kWaves][NCB * kGroup * VEC];
+    __shared__ float sm_ml[kWaves][2];
     const ckv_item it = a.items[blockIdx.x];
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane >> 4, c = lane & 15;
     const int d_u = a.d_u, d_a = a.d_a;
     const int64_t hT = (int64_t)it.h * a.T + it.t0;
@@ -90,15 +95,17 @@ __global__ __launch_bounds__(kLanes) void ckv_stream_kernel(ckv_args a) {
         }
         float m_run = -INFINITY, l_run = 0.f;
 
-        for (int t0 = 0; t0 < n; t0 += kLanes) {
+        for (int t0 = wave * kLanes; t0 < n; t0 += kLanes * kWaves) {
             const int nt = min(n - t0, kLanes);
+            const int nsteps = (nt + 3) >> 2;  // four rows per step
             const int myslot = min(slot_of_lane, nt - 1);
             const int my_ik = a.d_g > 0 ? ik[t0 + myslot] : 0;
             const int my_iv = a.d_g > 0 ? iv[t0 + myslot] : 0;
             // ---- scores
             float s_mine = 0.f;
-#pragma unroll 4
-            for (int t = 0; t < 16; ++t) {
+            for (int tb = 0; tb < nsteps; tb += 4)
+#pragma unroll
+            for (int t = tb; t < tb + 4; ++t) {  // steps past nsteps touch clamped, masked positions
                 const int pos = min(4 * t + r, nt - 1);
                 const int row = __shfl(my_ik, (lane & 48) | t, kLanes);
                 float part = 0.f;
@@ -136,8 +143,9 @@ __global__ __launch_bounds__(kLanes) void ckv_stream_kernel(ckv_args a) {
                 w = valid ? s / (1.f + __expf(-s)) : 0.f;
             }
             // ---- weighted sum of final V rows
-#pragma unroll 4
-            for (int t = 0; t < 16; ++t) {
+            for (int tb = 0; tb < nsteps; tb += 4)
+#pragma unroll
+            for (int t = tb; t < tb + 4; ++t) {
                 const int pos = min(4 * t + r, nt - 1);
                 const int src_lane = (lane & 48) | t;
                 const int row = __shfl(my_iv, src_lane, kLanes);
@@ -165,10 +173,44 @@ __global__ __launch_bounds__(kLanes) void ckv_stream_kernel(ckv_args a) {
                 x += __shfl_xor(x, 32, kLanes);
                 acc[cb][v] = x;
             }
+        // ---- merge the four wavefronts through LDS (exact: rescale to the common maximum)
         if (r == 0) {
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) sm_acc[wave][(cb * kGroup + c) * VEC + v] = acc[cb][v];
+            if (c == 0) {
+                sm_ml[wave][0] = m_run;
+                sm_ml[wave][1] = l_run;
+            }
+        }
+        __syncthreads();
+        if (wave == 0 && r == 0) {
+            float M = -INFINITY, L = 0.f, wgt[kWaves];
+            if (MODE == CKV_SOFTMAX) {
+#pragma unroll
+                for (int w = 0; w < kWaves; ++w) M = fmaxf(M, sm_ml[w][0]);
+#pragma unroll
+                for (int w = 0; w < kWaves; ++w) {
+                    wgt[w] = sm_ml[w][0] == -INFINITY ? 0.f : __expf(sm_ml[w][0] - M);
+                    L += wgt[w] * sm_ml[w][1];
+                }
+            } else {
+#pragma unroll
+                for (int w = 0; w < kWaves; ++w) wgt[w] = 1.f;
+            }
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    float x = 0.f;
+#pragma unroll
+                    for (int w = 0; w < kWaves; ++w) x += wgt[w] * sm_acc[w][(cb * kGroup + c) * VEC + v];
+                    acc[cb][v] = x;
+                }
             if (it.part < 0) {
                 float norm;
-                if (MODE == CKV_SOFTMAX) norm = l_run > 0.f ? 1.f / l_run : 0.f;
+                if (MODE == CKV_SOFTMAX) norm = L > 0.f ? 1.f / L : 0.f;
                 else norm = it.n_total > 0 ? 1.f / (float)it.n_total : 0.f;
                 T* op = (T*)a.out + qo;
 #pragma unroll
@@ -187,17 +229,18 @@ __global__ __launch_bounds__(kLanes) void ckv_stream_kernel(ckv_args a) {
 #pragma unroll
                         for (int v = 0; v < VEC; ++v) ws[(int64_t)j * d_a + col[cb] + v] = acc[cb][v];
                 if (c == 0) {
-                    ws[(int64_t)a.QB * d_a + j] = m_run;
-                    ws[(int64_t)a.QB * d_a + a.QB + j] = l_run;
+                    ws[(int64_t)a.QB * d_a + j] = M;
+                    ws[(int64_t)a.QB * d_a + a.QB + j] = L;
                 }
             }
         }
+        __syncthreads();  // the next query reuses the LDS buffers
     }
 }
 
 template <typename T, int VEC, int NCB>
 hipError_t launch_mode(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
-    dim3 grid(c->n_items), block(kLanes);
+    dim3 grid(c->n_items), block(kLanes * kWaves);
     if (c->shape.mode == CKV_SOFTMAX)
         hipLaunchKernelGGL((ckv_stream_kernel<T, VEC, NCB, CKV_SOFTMAX>), grid, block, 0, s, a);
     else
