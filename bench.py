@@ -108,6 +108,40 @@ def cpu_baseline(w, budget_s=15.0):
             "sample": f"{n} of {w['B']} users (seeded choice), all heads and queries, {dt:.1f} s wall"}
 
 
+def offloaded_sweep(batches=(1, 8, 32, 64, 128, 256, 512), reps=30):
+    """Decode latency of one request batch (target attention: one query per user, L=200, 2 heads, d=56+8, pool
+    10000, bf16): compressed cache read in place from pinned host memory, compressed cache resident in HBM, and
+    the time to load the same batch's full-width keys from pinned host memory (the standard-KV-cache baseline)."""
+    import torch
+    from paper_2601_19178_amd import ckv, session, workloads as wl
+
+    def median_ms(fn):
+        ts = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(); fn(); b.record(); torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b))
+        return float(np.median(ts[reps // 3:]))
+
+    rows = []
+    for B in batches:
+        w = wl.make(B=B, L=(200, 200), H=2, d_a=64, d_u=8, P=10000, idx="uniform", Nq=1, mode=wl.SOFTMAX, dtype=wl.BF16,
+                    sigma_pool=0.125, seed=2000 + B)
+        ab = wl.algorithmic_bytes(w)
+        full_keys = torch.empty(B * 200 * 2 * 64, dtype=torch.bfloat16).pin_memory()
+        dev_keys = torch.empty_like(full_keys, device="cuda")
+        row = {"batch": B, "compressed_bytes": ab["compressed"], "full_key_bytes": full_keys.numel() * 2}
+        for name, off in (("resident_ms", False), ("offloaded_ms", True)):
+            s = session.Session(w, offloaded=off)
+            for _ in range(5):
+                s.attend()
+            row[name] = median_ms(s.attend)
+            s.close()
+        row["full_key_load_ms"] = median_ms(lambda: dev_keys.copy_(full_keys, non_blocking=True))
+        rows.append(row)
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -117,6 +151,9 @@ def main():
     ap.add_argument("--workload", default="cfg4", choices=sorted(DESCRIBE))
     ap.add_argument("--also", default="cfg2_f32,cfg2_bf16,cfg3", help="comma list of further workloads ('' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--offloaded-sweep", action="store_true",
+                    help="latency of one decode batch with the compressed cache in pinned host memory vs resident vs "
+                         "loading a full-width key cache, batch 1..512 (the paper's latency-table scenario)")
     ap.add_argument("--calibrate-copy-mb", type=int, default=0,
                     help="only run the library's plain copy kernel on this many MiB (counter calibration) and exit")
     args = ap.parse_args()
@@ -136,6 +173,10 @@ def main():
             ckv.ckv_copy(dst, src, nbytes, stream)
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes": nbytes, "launches": args.steps}))
+        return
+
+    if args.offloaded_sweep:
+        print(json.dumps({"offloaded_sweep": offloaded_sweep()}))
         return
 
     head, w, sess = measure(args.workload, args.steps, args.warmup)

@@ -96,6 +96,21 @@ int ckv_build_cache(const ckv_shape* shape, const int32_t* lengths,
                     const void* user_k, const void* user_v,
                     ckv_cache** out, void* stream);
 
+/*
+ * Offloaded cache (latency analysis, section 4.4: the cache of a large user base does not fit
+ * GPU memory and is kept in CPU memory; the load term shrinks from s*d_a to s*d_u + s).  Same
+ * arguments and packing as ckv_build_cache, but the packed indices and user slices are placed
+ * in pinned, GPU-mapped host memory.  The views below then return device-visible addresses of
+ * that host memory, and ckv_attend streams the compressed cache over PCIe while it gathers
+ * from the GPU-resident pools and attends: load, gather, concat and attention are one pass,
+ * with no staging copy.  Everything else about the handle is unchanged.
+ */
+int ckv_build_cache_offloaded(const ckv_shape* shape, const int32_t* lengths,
+                              const int32_t* idx_k, const int32_t* idx_v,
+                              const void* user_k, const void* user_v,
+                              ckv_cache** out, void* stream);
+int ckv_cache_is_offloaded(const ckv_cache* c);
+
 /* Borrowed device views of the packed cache; valid until ckv_free. */
 const int32_t* ckv_cache_idx(const ckv_cache* c);     /* device int32 [2][H][T]        */
 const void* ckv_cache_user_k(const ckv_cache* c);     /* device [H][T][d_u]            */

@@ -19,7 +19,7 @@ CKV_SOFTMAX, CKV_SILU_OVER_N = 0, 1
 CKV_OK, CKV_ERR_NULL, CKV_ERR_SHAPE, CKV_ERR_INDEX, CKV_ERR_LENGTH, CKV_ERR_UNSUPPORTED, CKV_ERR_HIP = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = [
-    "ckv_build_cache", "ckv_cache_idx", "ckv_cache_user_k", "ckv_cache_user_v", "ckv_cache_lengths",
+    "ckv_build_cache", "ckv_build_cache_offloaded", "ckv_cache_is_offloaded", "ckv_cache_idx", "ckv_cache_user_k", "ckv_cache_user_v", "ckv_cache_lengths",
     "ckv_cache_positions", "ckv_cache_stored_bytes", "ckv_attend", "ckv_reconstruct", "ckv_free",
     "ckv_last_error", "ckv_set_timing", "ckv_kernel_ms", "ckv_variant", "ckv_copy", "ckv_trace_enable", "ckv_trace_read",
 ]
@@ -45,6 +45,10 @@ _lib = ctypes.CDLL(_LIBPATH)
 _vp, _i32, _i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
 _lib.ckv_build_cache.restype = ctypes.c_int
 _lib.ckv_build_cache.argtypes = [ctypes.POINTER(ckv_shape), _vp, _vp, _vp, _vp, _vp, ctypes.POINTER(_vp), _vp]
+_lib.ckv_build_cache_offloaded.restype = ctypes.c_int
+_lib.ckv_build_cache_offloaded.argtypes = _lib.ckv_build_cache.argtypes
+_lib.ckv_cache_is_offloaded.restype = ctypes.c_int
+_lib.ckv_cache_is_offloaded.argtypes = [_vp]
 for _n in ("ckv_cache_idx", "ckv_cache_user_k", "ckv_cache_user_v", "ckv_cache_lengths"):
     getattr(_lib, _n).restype = _vp
     getattr(_lib, _n).argtypes = [_vp]
@@ -109,6 +113,18 @@ def ckv_build_cache(shape, lengths, idx_k, idx_v, user_k, user_v, stream=0):
     out = _vp(0)
     _check(_lib.ckv_build_cache(ctypes.byref(shape), *[p for _, p in keep], ctypes.byref(out), _vp(stream)))
     return out.value
+
+
+def ckv_build_cache_offloaded(shape, lengths, idx_k, idx_v, user_k, user_v, stream=0):
+    """As ckv_build_cache, but the packed cache stays in pinned host memory."""
+    keep = [_host(lengths, np.int32), _host(idx_k, np.int32), _host(idx_v, np.int32), _host(user_k), _host(user_v)]
+    out = _vp(0)
+    _check(_lib.ckv_build_cache_offloaded(ctypes.byref(shape), *[p for _, p in keep], ctypes.byref(out), _vp(stream)))
+    return out.value
+
+
+def ckv_cache_is_offloaded(cache):
+    return bool(_lib.ckv_cache_is_offloaded(cache))
 
 
 def ckv_cache_idx(cache):

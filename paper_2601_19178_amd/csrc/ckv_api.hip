@@ -496,11 +496,28 @@ void choose_variant(ckv_cache* c) {
              c->ncb, s.mode == CKV_SOFTMAX ? "softmax" : "silu");
 }
 
+// The packed cache lives in device memory, or (offloaded handle) in pinned host memory that the
+// GPU reads in place.
+hipError_t cache_alloc(const ckv_cache* c, void** p, size_t bytes) {
+    if (!c->offloaded) return hipMalloc(p, bytes);
+    void* h = nullptr;
+    hipError_t e = hipHostMalloc(&h, bytes, hipHostMallocMapped | hipHostMallocPortable);
+    if (e != hipSuccess) return e;
+    e = hipHostGetDevicePointer(p, h, 0);
+    if (e != hipSuccess) (void)hipHostFree(h);
+    return e;
+}
+void cache_free(const ckv_cache* c, void* p) {
+    if (!p) return;
+    if (c->offloaded) (void)hipHostFree(p);
+    else (void)hipFree(p);
+}
+
 void destroy(ckv_cache* c) {
     if (!c) return;
-    (void)hipFree(c->d_idx);
-    (void)hipFree(c->d_user_k);
-    (void)hipFree(c->d_user_v);
+    cache_free(c, c->d_idx);
+    cache_free(c, c->d_user_k);
+    cache_free(c, c->d_user_v);
     (void)hipFree(c->d_lengths);
     (void)hipFree(c->d_items);
     (void)hipFree(c->d_wg_begin);
@@ -518,8 +535,8 @@ extern "C" {
 
 const char* ckv_last_error(void) { return g_err; }
 
-int ckv_build_cache(const ckv_shape* shape, const int32_t* lengths, const int32_t* idx_k, const int32_t* idx_v,
-                    const void* user_k, const void* user_v, ckv_cache** out, void* stream) {
+static int build_cache_impl(const ckv_shape* shape, const int32_t* lengths, const int32_t* idx_k, const int32_t* idx_v,
+                            const void* user_k, const void* user_v, ckv_cache** out, void* stream, bool offloaded) {
     if (out) *out = nullptr;
     if (!shape || !lengths || !out) return fail(CKV_ERR_NULL, "ckv_build_cache: shape, lengths and out must not be NULL");
     const ckv_shape s = *shape;
@@ -549,6 +566,7 @@ int ckv_build_cache(const ckv_shape* shape, const int32_t* lengths, const int32_
     memset(c, 0, sizeof *c);
     c->shape = s;
     c->T = T;
+    c->offloaded = offloaded ? 1 : 0;
     choose_variant(c);
     if (c->family == CKV_K_STREAM && (d_a + 16 * c->vec - 1) / (16 * c->vec) > 8) {
         const int vec = c->vec;
@@ -580,7 +598,7 @@ int ckv_build_cache(const ckv_shape* shape, const int32_t* lengths, const int32_
     CKV_HIP(hipMemcpyAsync(c->d_lengths, lengths, sizeof(int32_t) * (size_t)s.B, hipMemcpyHostToDevice, st));
     if (n_ph > 0) {
         if (s.d_g > 0) {
-            CKV_HIP(hipMalloc((void**)&c->d_idx, sizeof(int32_t) * 2 * n_ph));
+            CKV_HIP(cache_alloc(c, (void**)&c->d_idx, sizeof(int32_t) * 2 * n_ph));
             CKV_HIP(hipMalloc((void**)&s_ik, sizeof(int32_t) * n_ph));
             CKV_HIP(hipMalloc((void**)&s_iv, sizeof(int32_t) * n_ph));
             CKV_HIP(hipMemcpyAsync(s_ik, idx_k, sizeof(int32_t) * n_ph, hipMemcpyHostToDevice, st));
@@ -588,8 +606,8 @@ int ckv_build_cache(const ckv_shape* shape, const int32_t* lengths, const int32_
         }
         if (s.d_u > 0) {
             const size_t ub = n_ph * (size_t)s.d_u * e;
-            CKV_HIP(hipMalloc(&c->d_user_k, ub));
-            CKV_HIP(hipMalloc(&c->d_user_v, ub));
+            CKV_HIP(cache_alloc(c, &c->d_user_k, ub));
+            CKV_HIP(cache_alloc(c, &c->d_user_v, ub));
             CKV_HIP(hipMalloc(&s_uk, ub));
             CKV_HIP(hipMalloc(&s_uv, ub));
             CKV_HIP(hipMemcpyAsync(s_uk, user_k, ub, hipMemcpyHostToDevice, st));
@@ -668,6 +686,18 @@ done:
     *out = c;
     return CKV_OK;
 }
+
+int ckv_build_cache(const ckv_shape* shape, const int32_t* lengths, const int32_t* idx_k, const int32_t* idx_v,
+                    const void* user_k, const void* user_v, ckv_cache** out, void* stream) {
+    return build_cache_impl(shape, lengths, idx_k, idx_v, user_k, user_v, out, stream, false);
+}
+
+int ckv_build_cache_offloaded(const ckv_shape* shape, const int32_t* lengths, const int32_t* idx_k, const int32_t* idx_v,
+                              const void* user_k, const void* user_v, ckv_cache** out, void* stream) {
+    return build_cache_impl(shape, lengths, idx_k, idx_v, user_k, user_v, out, stream, true);
+}
+
+int ckv_cache_is_offloaded(const ckv_cache* c) { return c ? c->offloaded : 0; }
 
 const int32_t* ckv_cache_idx(const ckv_cache* c) { return c ? c->d_idx : nullptr; }
 const void* ckv_cache_user_k(const ckv_cache* c) { return c ? c->d_user_k : nullptr; }

@@ -52,6 +52,7 @@ struct ckv_cache {
     ckv_shape shape;
     int64_t T;
     int device;
+    int offloaded;       // packed cache in pinned host memory, read by the kernels in place
     // packed cache (device, owned)
     int32_t* d_idx;      // [2][H][T]
     void* d_user_k;      // [H][T][d_u]

@@ -26,7 +26,7 @@ def _to_host(t, dtype):
 class Session:
     """Pools and queries on the device, the packed cache handle, an output buffer."""
 
-    def __init__(self, w):
+    def __init__(self, w, offloaded=False):
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU: the CollectiveKV hot path needs an MI355X (there is no CPU fallback)")
         self.w = w
@@ -40,7 +40,8 @@ class Session:
         self.q = _to_device(w["q"], self.dtype)
         tdt = torch.float32 if self.dtype == ckv.CKV_F32 else torch.bfloat16
         self.out = torch.full((w["B"], w["H"], w["Nq"], self.d_a), float("nan"), dtype=tdt, device="cuda")
-        self.cache = ckv.ckv_build_cache(self.shape, w["lengths"], w["idx_k"], w["idx_v"], w["user_k"], w["user_v"],
+        build = ckv.ckv_build_cache_offloaded if offloaded else ckv.ckv_build_cache
+        self.cache = build(self.shape, w["lengths"], w["idx_k"], w["idx_v"], w["user_k"], w["user_v"],
                                          self.stream)
         self.T = ckv.ckv_cache_positions(self.cache)
 

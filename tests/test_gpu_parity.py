@@ -195,6 +195,31 @@ def test_config5_full(gpu):
 
 
 # ---------------------------------------------------------------------------------------------
+# offloaded cache: packed cache in pinned host memory, read in place by the same kernels
+@pytest.mark.parametrize("kind", ["stream", "dma", "staged"])
+def test_offloaded_cache_matches_resident(gpu, kind):
+    ckv, session = gpu
+    if kind == "stream":
+        w = make(RAGGED, wl.BF16, wl.SOFTMAX, d_a=64, d_u=8, H=2, P=300, Nq=1)
+    elif kind == "dma":
+        w = make(MFMA_LENGTHS, wl.BF16, wl.SILU_OVER_N, d_a=64, d_u=4, H=2, P=700, Nq=64)
+    else:
+        w = make(MFMA_LENGTHS, wl.BF16, wl.SOFTMAX, d_a=128, d_u=16, H=2, P=700, Nq=40)
+    say(f"[case] offloaded {kind}")
+    outs = []
+    for off in (False, True):
+        with session.Session(w, offloaded=off) as s:
+            assert ckv.ckv_cache_is_offloaded(s.cache) == off
+            s.attend()
+            outs.append(s.output().copy())
+            idx, uk, uv = s.packed_views()
+            np.testing.assert_array_equal(idx[0], w["idx_k"].T)
+            np.testing.assert_array_equal(uv, w["user_v"].transpose(1, 0, 2))
+    np.testing.assert_array_equal(outs[0], outs[1])
+    check(outs[1], oracle.attend(w), w["dtype"], what=f"offloaded {kind}")
+
+
+# ---------------------------------------------------------------------------------------------
 # error paths that need the device
 def test_out_of_range_index_is_rejected(gpu):
     ckv, session = gpu
