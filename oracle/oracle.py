@@ -10,7 +10,7 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "ckv_oracle.c")
+_SRCS = [os.path.join(_HERE, "ckv_oracle.c"), os.path.join(_HERE, "ckv_prefill_oracle.c")]
 _LIB = os.path.join(_HERE, "libckv_oracle.so")
 
 F32, BF16 = 0, 1
@@ -21,9 +21,9 @@ _lib = None
 
 def build(force=False):
     """Compile the oracle with gcc (plain -O2, OpenMP over (user, head) only)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(s) for s in _SRCS):
         subprocess.check_call(
-            ["gcc", "-O2", "-std=c11", "-fopenmp", "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"])
+            ["gcc", "-O2", "-std=c11", "-fopenmp", "-shared", "-fPIC", "-o", _LIB, *_SRCS, "-lm"])
     return _LIB
 
 
@@ -40,6 +40,10 @@ def _load():
         lib.ckv_oracle_cache_size.restype = None
         lib.ckv_oracle_cache_size.argtypes = [i64, i32, i32, i32, i32, i32] + [vp] * 4
         lib.ckv_oracle_threads.restype = ctypes.c_int
+        lib.ckv_oracle_prefill.restype = ctypes.c_int
+        lib.ckv_oracle_prefill.argtypes = [i32] * 5 + [i64] + [vp] * 13
+        lib.ckv_oracle_router_gap.restype = ctypes.c_int
+        lib.ckv_oracle_router_gap.argtypes = [i32] * 4 + [i64] + [vp] * 6
         _lib = lib
     return _lib
 
@@ -114,3 +118,51 @@ def cache_size(T, H, d_g, d_u, dtype, index_bytes=4):
 
 def threads():
     return int(_load().ckv_oracle_threads())
+
+
+def _prefill_arrays(r):
+    dt = r["dtype"]
+    ws = [_check_store(r[k], dt, k) for k in ("S", "w_rk", "w_rv", "w_k", "w_v")]
+    bs = [np.ascontiguousarray(r[k], dtype=np.float32) for k in ("b_rk", "b_rv", "b_k", "b_v")]
+    return ws, bs
+
+
+def prefill(r):
+    """What the prefill stage caches: (idx_k, idx_v int32 [T][H], user_k, user_v float64 [T][H][d_u]).
+
+    `r` is a prefill workload dict as made by the seeded generators: keys H, d_e, d_u, P, dtype,
+    S [T][d_e], w_rk, w_rv [H][P][d_e], b_rk, b_rv [H][P], w_k, w_v [H][d_u][d_e], b_k, b_v [H][d_u].
+    """
+    lib = _load()
+    (S, w_rk, w_rv, w_k, w_v), (b_rk, b_rv, b_k, b_v) = _prefill_arrays(r)
+    T, H, d_u = S.shape[0], r["H"], r["d_u"]
+    idx_k = np.zeros((T, H), dtype=np.int32)
+    idx_v = np.zeros((T, H), dtype=np.int32)
+    user_k = np.zeros((T, H, d_u), dtype=np.float64)
+    user_v = np.zeros((T, H, d_u), dtype=np.float64)
+    rc = lib.ckv_oracle_prefill(H, r["d_e"], d_u, r["P"], r["dtype"], T, _ptr(S), _ptr(w_rk), _ptr(b_rk), _ptr(w_rv),
+                                _ptr(b_rv), _ptr(w_k), _ptr(b_k), _ptr(w_v), _ptr(b_v), _ptr(idx_k), _ptr(idx_v),
+                                _ptr(user_k), _ptr(user_v))
+    if rc != 0:
+        raise ValueError("ckv_oracle_prefill rejected its arguments")
+    return idx_k, idx_v, user_k, user_v
+
+
+def router_gap(r, side, cand):
+    """(gap, mag) float64 [T][H] of the candidate indices `cand` [T][H] for the key (side "k") or value
+    (side "v") router: distance of the candidate's routing score from the row maximum, and the size of
+    the terms behind the candidate's score."""
+    lib = _load()
+    dt = r["dtype"]
+    S = _check_store(r["S"], dt, "S")
+    w = _check_store(r["w_r" + side], dt, "w_r" + side)
+    b = np.ascontiguousarray(r["b_r" + side], dtype=np.float32)
+    cand = np.ascontiguousarray(cand, dtype=np.int32)
+    T, H = S.shape[0], r["H"]
+    assert cand.shape == (T, H)
+    gap = np.zeros((T, H), dtype=np.float64)
+    mag = np.zeros((T, H), dtype=np.float64)
+    rc = lib.ckv_oracle_router_gap(H, r["d_e"], r["P"], dt, T, _ptr(S), _ptr(w), _ptr(b), _ptr(cand), _ptr(gap), _ptr(mag))
+    if rc != 0:
+        raise ValueError("ckv_oracle_router_gap rejected its arguments")
+    return gap, mag

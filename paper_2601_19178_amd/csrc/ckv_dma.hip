@@ -106,7 +106,7 @@ struct Geo {
 // core works on the other.
 template <int DA, int NW, int QG, int MODE>
 __global__ __launch_bounds__(NW * 64)
-__attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES_PER_EU))) void ckv_dma_kernel(ckv_args a, int nui, int dbg) {
+__attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES_PER_EU))) void ckv_dma_kernel(ckv_args a, int nui) {
     using G = Geo<DA, NW>;
     constexpr int NKK = DA / 16, NDT = DA / 32;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -301,9 +301,9 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
         wait_vm<0>();
         if (tr && tid == 0) tr[1] = wall_clock64();
         for (int t = -(NS - 1); t < ntiles; ++t) {
-            if (!(dbg & 16)) issue_idx(t + NS + 2);
-            if (!(dbg & 2)) issue_gather(t + NS - 1);
-            if (t >= 0 && !(dbg & 1)) {
+            issue_idx(t + NS + 2);
+            issue_gather(t + NS - 1);
+            if (t >= 0) {
                 const uint32_t st = lds0 + (t & (NS - 1)) * G::STAGE;
                 const int nt = min(n - t * TP, TP);
                 // S^T = K Q^T for every query group; each K operand is read once
@@ -389,8 +389,8 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
             // own gathers of tile t+1 have landed once only the loads of this and the previous
             // iteration are outstanding
             wait_vm_twice<2 * G::NI + 1>(nui);
-            if (t + 1 >= 0 && t + 1 < ntiles && d_u > 0 && !(dbg & 8)) concat(t + 1);
-            if (!(dbg & 4)) lds_barrier();
+            if (t + 1 >= 0 && t + 1 < ntiles && d_u > 0) concat(t + 1);
+            lds_barrier();
         }
         // the clamped loads past the last tile must have landed, for every wavefront, before the
         // epilogue reuses the stages (and before the workgroup gives its LDS back)
@@ -464,8 +464,7 @@ hipError_t launch(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
     hipError_t e = prepare<DA, NW, QG, MODE>();
     if (e != hipSuccess) return e;
     constexpr int lds = Geo<DA, NW>::LDS;
-    static const int dbg = getenv("CKV_DMA_DBG") ? atoi(getenv("CKV_DMA_DBG")) : 0;  // timing experiments only
-    hipLaunchKernelGGL((ckv_dma_kernel<DA, NW, QG, MODE>), dim3(c->n_wg), dim3(NW * 64), lds, s, a, c->nui, dbg);
+    hipLaunchKernelGGL((ckv_dma_kernel<DA, NW, QG, MODE>), dim3(c->n_wg), dim3(NW * 64), lds, s, a, c->nui);
     return hipGetLastError();
 }
 

@@ -139,3 +139,28 @@ def algorithmic_bytes(w):
     q_out = 2 * w["B"] * w["H"] * w["Nq"] * d_a * e
     return dict(position_heads=ph, compressed=compressed, gathered=gathered, q_out=q_out,
                 E=compressed + gathered + q_out)
+
+
+def make_prefill(T, H, d_e, d_u, P, dtype, seed, sigma_s=1.0, sigma_b=0.1, integers=None):
+    """Inputs of the prefill stage (section 4.2 / 4.3): history embedding S [T][d_e] shared by the heads,
+    per-head router weights w_rk, w_rv [H][P][d_e] (row j = column j of the paper's W_r) with fp32 bias
+    b_rk, b_rv [H][P], per-head projection weights w_k, w_v [H][d_u][d_e] with fp32 bias b_k, b_v [H][d_u].
+    Weights are N(0, 1/sqrt(d_e)), S is N(0, sigma_s), biases N(0, sigma_b).  With integers=m every value is
+    a uniform integer in [-m, m]: all sums are then exact in fp32, so equal routing scores (ties) are common
+    and every implementation must agree bit for bit.  They stand in for trained embeddings and routers."""
+    P_eff = max(P, 1)
+
+    def draw(stream, shape, sigma, dt):
+        rng = _rng(seed, stream)
+        if integers is not None:
+            x = rng.integers(-integers, integers + 1, size=shape).astype(np.float32)
+            return x if dt == F32 else f32_to_bf16_bits(x)
+        return _normal(rng, shape, sigma, dt)
+
+    sw = d_e ** -0.5
+    return dict(H=H, d_e=d_e, d_u=d_u, P=P_eff, dtype=dtype, T=T,
+                S=draw(20, (T, d_e), sigma_s, dtype),
+                w_rk=draw(21, (H, P_eff, d_e), sw, dtype), w_rv=draw(22, (H, P_eff, d_e), sw, dtype),
+                b_rk=draw(23, (H, P_eff), sigma_b, F32), b_rv=draw(24, (H, P_eff), sigma_b, F32),
+                w_k=draw(25, (H, d_u, d_e), sw, dtype), w_v=draw(26, (H, d_u, d_e), sw, dtype),
+                b_k=draw(27, (H, d_u), sigma_b, F32), b_v=draw(28, (H, d_u), sigma_b, F32))
