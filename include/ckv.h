@@ -111,6 +111,50 @@ int ckv_build_cache_offloaded(const ckv_shape* shape, const int32_t* lengths,
                               ckv_cache** out, void* stream);
 int ckv_cache_is_offloaded(const ckv_cache* c);
 
+/*
+ * Prefill stage (section 4.2 "In the prefill stage" and section 4.3 "CollectiveKV Router"): from the
+ * history embedding S (T x d_e, users back to back, shared by the heads) compute, per head,
+ *   K_u = S W_k + b_k,  V_u = S W_v + b_v                 the d_u user-specific columns, and
+ *   M = S W_r + b_r,  I[i] = argmax_j M[i][j]             one router for keys, one for values,
+ * and write them straight into the packed cache of a new handle; the T x P routing map is never
+ * stored.  Inference form only (the sigmoid weighting and the router losses exist in training).
+ *
+ * ckv_router: device pointers, borrowed for the duration of the enqueued work.  Weights are in
+ * shape->dtype, one row per output: row j of w_rk[h] is column j of that head's W_r, row c of
+ * w_k[h] is column c of W_k.  Biases are always float.
+ *   w_rk, w_rv  [H][P][d_e]    b_rk, b_rv  [H][P]       (ignored when d_g == 0)
+ *   w_k,  w_v   [H][d_u][d_e]  b_k,  b_v   [H][d_u]     (ignored when d_u == 0)
+ * Arithmetic: products of the stored values accumulated in fp32, bias added in fp32; user slices
+ * are rounded to shape->dtype (nearest even).  Of equal routing scores the lowest pool entry
+ * wins.  Scores that differ by less than the fp32 rounding of their sums may resolve either way;
+ * inputs must be finite.  Every index written lies in [0, P).
+ *
+ *   lengths   host int32 [B]; T = sum.       S   device [T][d_e] in shape->dtype.
+ * ckv_prefill allocates the handle (device-resident), enqueues the kernels on `stream`, builds the
+ * launch metadata and synchronises the stream before returning.  ckv_prefill_into recomputes the
+ * packed cache of an existing, device-resident handle (same shape and lengths) from new S or
+ * weights: no allocation, no synchronisation.  ckv_prefill_kernel_name names the kernel the pair
+ * (shape, router) dispatches to: a matrix-core kernel for bf16 with d_e of 64, 128 or 256 and
+ * d_u <= 32, a scalar kernel otherwise.
+ * Errors: CKV_ERR_NULL, _SHAPE, _LENGTH, _UNSUPPORTED (pointer not 16-byte aligned), _HIP.
+ */
+typedef struct ckv_router {
+    int32_t d_e;
+    int32_t reserved; /* must be 0 */
+    const void* w_rk;
+    const float* b_rk;
+    const void* w_rv;
+    const float* b_rv;
+    const void* w_k;
+    const float* b_k;
+    const void* w_v;
+    const float* b_v;
+} ckv_router;
+int ckv_prefill(const ckv_shape* shape, const ckv_router* router, const int32_t* lengths, const void* S,
+                ckv_cache** out, void* stream);
+int ckv_prefill_into(ckv_cache* cache, const ckv_router* router, const void* S, void* stream);
+const char* ckv_prefill_kernel_name(const ckv_shape* shape, const ckv_router* router);
+
 /* Borrowed device views of the packed cache; valid until ckv_free. */
 const int32_t* ckv_cache_idx(const ckv_cache* c);     /* device int32 [2][H][T]        */
 const void* ckv_cache_user_k(const ckv_cache* c);     /* device [H][T][d_u]            */

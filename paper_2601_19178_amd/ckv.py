@@ -19,7 +19,8 @@ CKV_SOFTMAX, CKV_SILU_OVER_N = 0, 1
 CKV_OK, CKV_ERR_NULL, CKV_ERR_SHAPE, CKV_ERR_INDEX, CKV_ERR_LENGTH, CKV_ERR_UNSUPPORTED, CKV_ERR_HIP = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = [
-    "ckv_build_cache", "ckv_build_cache_offloaded", "ckv_cache_is_offloaded", "ckv_cache_idx", "ckv_cache_user_k", "ckv_cache_user_v", "ckv_cache_lengths",
+    "ckv_build_cache", "ckv_build_cache_offloaded", "ckv_cache_is_offloaded", "ckv_prefill", "ckv_prefill_into",
+    "ckv_prefill_kernel_name", "ckv_cache_idx", "ckv_cache_user_k", "ckv_cache_user_v", "ckv_cache_lengths",
     "ckv_cache_positions", "ckv_cache_stored_bytes", "ckv_attend", "ckv_reconstruct", "ckv_free",
     "ckv_last_error", "ckv_set_timing", "ckv_kernel_ms", "ckv_variant", "ckv_copy", "ckv_trace_enable", "ckv_trace_read",
 ]
@@ -29,6 +30,11 @@ class ckv_shape(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("d_g", ctypes.c_int32), ("d_u", ctypes.c_int32),
                 ("P", ctypes.c_int32), ("Nq", ctypes.c_int32), ("dtype", ctypes.c_int32), ("mode", ctypes.c_int32),
                 ("scale", ctypes.c_float), ("reserved", ctypes.c_int32), ("pool_ld", ctypes.c_int64)]
+
+
+class ckv_router(ctypes.Structure):
+    _fields_ = [("d_e", ctypes.c_int32), ("reserved", ctypes.c_int32)] + [
+        (n, ctypes.c_void_p) for n in ("w_rk", "b_rk", "w_rv", "b_rv", "w_k", "b_k", "w_v", "b_v")]
 
 
 class CkvError(RuntimeError):
@@ -47,6 +53,12 @@ _lib.ckv_build_cache.restype = ctypes.c_int
 _lib.ckv_build_cache.argtypes = [ctypes.POINTER(ckv_shape), _vp, _vp, _vp, _vp, _vp, ctypes.POINTER(_vp), _vp]
 _lib.ckv_build_cache_offloaded.restype = ctypes.c_int
 _lib.ckv_build_cache_offloaded.argtypes = _lib.ckv_build_cache.argtypes
+_lib.ckv_prefill.restype = ctypes.c_int
+_lib.ckv_prefill.argtypes = [ctypes.POINTER(ckv_shape), ctypes.POINTER(ckv_router), _vp, _vp, ctypes.POINTER(_vp), _vp]
+_lib.ckv_prefill_into.restype = ctypes.c_int
+_lib.ckv_prefill_into.argtypes = [_vp, ctypes.POINTER(ckv_router), _vp, _vp]
+_lib.ckv_prefill_kernel_name.restype = ctypes.c_char_p
+_lib.ckv_prefill_kernel_name.argtypes = [ctypes.POINTER(ckv_shape), ctypes.POINTER(ckv_router)]
 _lib.ckv_cache_is_offloaded.restype = ctypes.c_int
 _lib.ckv_cache_is_offloaded.argtypes = [_vp]
 for _n in ("ckv_cache_idx", "ckv_cache_user_k", "ckv_cache_user_v", "ckv_cache_lengths"):
@@ -121,6 +133,27 @@ def ckv_build_cache_offloaded(shape, lengths, idx_k, idx_v, user_k, user_v, stre
     out = _vp(0)
     _check(_lib.ckv_build_cache_offloaded(ctypes.byref(shape), *[p for _, p in keep], ctypes.byref(out), _vp(stream)))
     return out.value
+
+
+def make_router(d_e, w_rk, b_rk, w_rv, b_rv, w_k, b_k, w_v, b_v):
+    """Device tensors (or addresses, or None) -> ckv_router."""
+    return ckv_router(d_e, 0, *[_dev(x).value for x in (w_rk, b_rk, w_rv, b_rv, w_k, b_k, w_v, b_v)])
+
+
+def ckv_prefill(shape, router, lengths, S, stream=0):
+    """Router and projection over the device embedding S; returns a new handle (int address)."""
+    keep = _host(lengths, np.int32)
+    out = _vp(0)
+    _check(_lib.ckv_prefill(ctypes.byref(shape), ctypes.byref(router), keep[1], _dev(S), ctypes.byref(out), _vp(stream)))
+    return out.value
+
+
+def ckv_prefill_into(cache, router, S, stream=0):
+    _check(_lib.ckv_prefill_into(cache, ctypes.byref(router), _dev(S), _vp(stream)))
+
+
+def ckv_prefill_kernel_name(shape, router):
+    return _lib.ckv_prefill_kernel_name(ctypes.byref(shape), ctypes.byref(router)).decode()
 
 
 def ckv_cache_is_offloaded(cache):

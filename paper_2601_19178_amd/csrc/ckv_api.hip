@@ -535,34 +535,32 @@ extern "C" {
 
 const char* ckv_last_error(void) { return g_err; }
 
-static int build_cache_impl(const ckv_shape* shape, const int32_t* lengths, const int32_t* idx_k, const int32_t* idx_v,
-                            const void* user_k, const void* user_v, ckv_cache** out, void* stream, bool offloaded) {
-    if (out) *out = nullptr;
-    if (!shape || !lengths || !out) return fail(CKV_ERR_NULL, "ckv_build_cache: shape, lengths and out must not be NULL");
+// Validate the shape and the lengths, choose the kernel, allocate the handle and the buffers of
+// the packed cache (device memory, or pinned host memory for an offloaded handle) and upload the
+// lengths.  offs receives the B+1 prefix sums of the lengths.
+static int cache_new(const char* who, const ckv_shape* shape, const int32_t* lengths, bool offloaded, hipStream_t st,
+                     ckv_cache** out, std::vector<int64_t>& offs, hipDeviceProp_t* prop) {
     const ckv_shape s = *shape;
     const int64_t d_a = (int64_t)s.d_g + s.d_u;
     if (s.B < 1 || s.H < 1 || s.d_g < 0 || s.d_u < 0 || d_a < 1 || s.Nq < 1 || s.reserved != 0)
-        return fail(CKV_ERR_SHAPE, "ckv_build_cache: need B,H,Nq >= 1, d_g,d_u >= 0, d_g+d_u >= 1 (B=%d H=%d d_g=%d d_u=%d Nq=%d)",
+        return fail(CKV_ERR_SHAPE, "%s: need B,H,Nq >= 1, d_g,d_u >= 0, d_g+d_u >= 1 (B=%d H=%d d_g=%d d_u=%d Nq=%d)", who,
                     s.B, s.H, s.d_g, s.d_u, s.Nq);
     if (s.d_g > 0 && (s.P < 1 || s.pool_ld < s.d_g))
-        return fail(CKV_ERR_SHAPE, "ckv_build_cache: need P >= 1 and pool_ld >= d_g (P=%d pool_ld=%lld d_g=%d)", s.P,
+        return fail(CKV_ERR_SHAPE, "%s: need P >= 1 and pool_ld >= d_g (P=%d pool_ld=%lld d_g=%d)", who, s.P,
                     (long long)s.pool_ld, s.d_g);
     if ((s.dtype != CKV_F32 && s.dtype != CKV_BF16) || (s.mode != CKV_SOFTMAX && s.mode != CKV_SILU_OVER_N))
-        return fail(CKV_ERR_SHAPE, "ckv_build_cache: unknown dtype %d or mode %d", s.dtype, s.mode);
-    if (!(s.scale == s.scale) || s.scale - s.scale != 0.f)
-        return fail(CKV_ERR_SHAPE, "ckv_build_cache: scale must be finite");
-    std::vector<int64_t> offs((size_t)s.B + 1, 0);
+        return fail(CKV_ERR_SHAPE, "%s: unknown dtype %d or mode %d", who, s.dtype, s.mode);
+    if (!(s.scale == s.scale) || s.scale - s.scale != 0.f) return fail(CKV_ERR_SHAPE, "%s: scale must be finite", who);
+    offs.assign((size_t)s.B + 1, 0);
     for (int b = 0; b < s.B; ++b) {
-        if (lengths[b] < 0) return fail(CKV_ERR_LENGTH, "ckv_build_cache: lengths[%d] = %d is negative", b, lengths[b]);
+        if (lengths[b] < 0) return fail(CKV_ERR_LENGTH, "%s: lengths[%d] = %d is negative", who, b, lengths[b]);
         offs[(size_t)b + 1] = offs[(size_t)b] + lengths[b];
     }
     const int64_t T = offs[(size_t)s.B];
-    if (T * s.H > ((int64_t)1 << 40)) return fail(CKV_ERR_LENGTH, "ckv_build_cache: T*H = %lld is too large", (long long)(T * s.H));
-    if (T > 0 && s.d_g > 0 && (!idx_k || !idx_v)) return fail(CKV_ERR_NULL, "ckv_build_cache: idx_k/idx_v are NULL but d_g > 0");
-    if (T > 0 && s.d_u > 0 && (!user_k || !user_v)) return fail(CKV_ERR_NULL, "ckv_build_cache: user_k/user_v are NULL but d_u > 0");
+    if (T * s.H > ((int64_t)1 << 40)) return fail(CKV_ERR_LENGTH, "%s: T*H = %lld is too large", who, (long long)(T * s.H));
 
     ckv_cache* c = new (std::nothrow) ckv_cache();
-    if (!c) return fail(CKV_ERR_HIP, "ckv_build_cache: out of host memory");
+    if (!c) return fail(CKV_ERR_HIP, "%s: out of host memory", who);
     memset(c, 0, sizeof *c);
     c->shape = s;
     c->T = T;
@@ -571,74 +569,41 @@ static int build_cache_impl(const ckv_shape* shape, const int32_t* lengths, cons
     if (c->family == CKV_K_STREAM && (d_a + 16 * c->vec - 1) / (16 * c->vec) > 8) {
         const int vec = c->vec;
         delete c;
-        return fail(CKV_ERR_UNSUPPORTED,
-                    "ckv_build_cache: d_a = %lld exceeds the streaming kernel's limit of %d columns at this alignment",
+        return fail(CKV_ERR_UNSUPPORTED, "%s: d_a = %lld exceeds the streaming kernel's limit of %d columns at this alignment", who,
                     (long long)d_a, 128 * vec);
     }
-
     int rc = CKV_OK;
-    hipStream_t st = (hipStream_t)stream;
-    const size_t e = esize(s.dtype);
     const size_t n_ph = (size_t)T * s.H;
-    int32_t *s_ik = nullptr, *s_iv = nullptr;
-    void *s_uk = nullptr, *s_uv = nullptr;
-    unsigned long long* d_bad = nullptr;
-    unsigned long long h_bad = ~0ull;
-    std::vector<ckv_item> items;
-    std::vector<ckv_merge> merges;
-    hipDeviceProp_t prop;
-
     CKV_HIP(hipGetDevice(&c->device));
-    CKV_HIP(hipGetDeviceProperties(&prop, c->device));
-    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) {
-        rc = fail(CKV_ERR_UNSUPPORTED, "ckv_build_cache: device is %s, this library is built for gfx950 only", prop.gcnArchName);
+    CKV_HIP(hipGetDeviceProperties(prop, c->device));
+    if (strncmp(prop->gcnArchName, "gfx950", 6) != 0) {
+        rc = fail(CKV_ERR_UNSUPPORTED, "%s: device is %s, this library is built for gfx950 only", who, prop->gcnArchName);
         goto done;
     }
     CKV_HIP(hipMalloc((void**)&c->d_lengths, sizeof(int32_t) * (size_t)s.B));
     CKV_HIP(hipMemcpyAsync(c->d_lengths, lengths, sizeof(int32_t) * (size_t)s.B, hipMemcpyHostToDevice, st));
-    if (n_ph > 0) {
-        if (s.d_g > 0) {
-            CKV_HIP(cache_alloc(c, (void**)&c->d_idx, sizeof(int32_t) * 2 * n_ph));
-            CKV_HIP(hipMalloc((void**)&s_ik, sizeof(int32_t) * n_ph));
-            CKV_HIP(hipMalloc((void**)&s_iv, sizeof(int32_t) * n_ph));
-            CKV_HIP(hipMemcpyAsync(s_ik, idx_k, sizeof(int32_t) * n_ph, hipMemcpyHostToDevice, st));
-            CKV_HIP(hipMemcpyAsync(s_iv, idx_v, sizeof(int32_t) * n_ph, hipMemcpyHostToDevice, st));
-        }
-        if (s.d_u > 0) {
-            const size_t ub = n_ph * (size_t)s.d_u * e;
-            CKV_HIP(cache_alloc(c, &c->d_user_k, ub));
-            CKV_HIP(cache_alloc(c, &c->d_user_v, ub));
-            CKV_HIP(hipMalloc(&s_uk, ub));
-            CKV_HIP(hipMalloc(&s_uv, ub));
-            CKV_HIP(hipMemcpyAsync(s_uk, user_k, ub, hipMemcpyHostToDevice, st));
-            CKV_HIP(hipMemcpyAsync(s_uv, user_v, ub, hipMemcpyHostToDevice, st));
-        }
-        CKV_HIP(hipMalloc((void**)&d_bad, sizeof h_bad));
-        CKV_HIP(hipMemcpyAsync(d_bad, &h_bad, sizeof h_bad, hipMemcpyHostToDevice, st));
-        {
-            const int threads = 256;
-            const int blocks = (int)std::min<size_t>((n_ph + threads - 1) / threads, 65536);
-            if (e == 4)
-                hipLaunchKernelGGL(ckv_pack_kernel<uint32_t>, dim3(blocks), dim3(threads), 0, st, s_ik, s_iv,
-                                   (const uint32_t*)s_uk, (const uint32_t*)s_uv, c->d_idx, (uint32_t*)c->d_user_k,
-                                   (uint32_t*)c->d_user_v, T, s.H, s.d_u, s.P, s.d_g > 0 ? 1 : 0, d_bad);
-            else
-                hipLaunchKernelGGL(ckv_pack_kernel<uint16_t>, dim3(blocks), dim3(threads), 0, st, s_ik, s_iv,
-                                   (const uint16_t*)s_uk, (const uint16_t*)s_uv, c->d_idx, (uint16_t*)c->d_user_k,
-                                   (uint16_t*)c->d_user_v, T, s.H, s.d_u, s.P, s.d_g > 0 ? 1 : 0, d_bad);
-            CKV_HIP(hipGetLastError());
-        }
-        CKV_HIP(hipMemcpyAsync(&h_bad, d_bad, sizeof h_bad, hipMemcpyDeviceToHost, st));
+    if (n_ph > 0 && s.d_g > 0) CKV_HIP(cache_alloc(c, (void**)&c->d_idx, sizeof(int32_t) * 2 * n_ph));
+    if (n_ph > 0 && s.d_u > 0) {
+        const size_t ub = n_ph * (size_t)s.d_u * esize(s.dtype);
+        CKV_HIP(cache_alloc(c, &c->d_user_k, ub));
+        CKV_HIP(cache_alloc(c, &c->d_user_v, ub));
     }
-    CKV_HIP(hipStreamSynchronize(st));
-    if (h_bad != ~0ull) {
-        const long long t = (long long)(h_bad / (unsigned long long)s.H);
-        const int h = (int)(h_bad % (unsigned long long)s.H);
-        rc = fail(CKV_ERR_INDEX, "ckv_build_cache: pool index out of range [0,%d) at position %lld head %d (idx_k=%d idx_v=%d)", s.P,
-                  t, h, idx_k[h_bad], idx_v[h_bad]);
-        goto done;
+done:
+    if (rc != CKV_OK) {
+        destroy(c);
+        return rc;
     }
+    *out = c;
+    return CKV_OK;
+}
 
+// Build and upload the work lists (and the split workspace) of a handle whose packed cache is in place.
+static int cache_finish(ckv_cache* c, const int32_t* lengths, const std::vector<int64_t>& offs, const hipDeviceProp_t& prop,
+                        hipStream_t st) {
+    int rc = CKV_OK;
+    const int64_t d_a = (int64_t)c->shape.d_g + c->shape.d_u;
+    std::vector<ckv_item> items;
+    std::vector<ckv_merge> merges;
     if (c->family == CKV_K_DMA) {
         // Two ways to hand out work.  Static (default): one resident workgroup per slot with its
         // own item list, no relaunch gaps.  Dynamic: one workgroup per item in longest-first order,
@@ -671,7 +636,76 @@ static int build_cache_impl(const ckv_shape* shape, const int32_t* lengths, cons
         CKV_HIP(hipMemcpyAsync(c->d_merge, merges.data(), sizeof(ckv_merge) * merges.size(), hipMemcpyHostToDevice, st));
         CKV_HIP(hipMalloc((void**)&c->d_partial, sizeof(float) * (size_t)c->n_parts * c->QB * (size_t)(d_a + 2)));
     }
+    CKV_HIP(hipStreamSynchronize(st));  // the host vectors above go out of scope
+done:
+    return rc;
+}
+
+static int build_cache_impl(const ckv_shape* shape, const int32_t* lengths, const int32_t* idx_k, const int32_t* idx_v,
+                            const void* user_k, const void* user_v, ckv_cache** out, void* stream, bool offloaded) {
+    if (out) *out = nullptr;
+    if (!shape || !lengths || !out) return fail(CKV_ERR_NULL, "ckv_build_cache: shape, lengths and out must not be NULL");
+    hipStream_t st = (hipStream_t)stream;
+    ckv_cache* c = nullptr;
+    std::vector<int64_t> offs;
+    hipDeviceProp_t prop;
+    {
+        int64_t T = 0;
+        for (int b = 0; b < shape->B; ++b) T += lengths[b] > 0 ? lengths[b] : 0;
+        if (T > 0 && shape->d_g > 0 && (!idx_k || !idx_v)) return fail(CKV_ERR_NULL, "ckv_build_cache: idx_k/idx_v are NULL but d_g > 0");
+        if (T > 0 && shape->d_u > 0 && (!user_k || !user_v)) return fail(CKV_ERR_NULL, "ckv_build_cache: user_k/user_v are NULL but d_u > 0");
+    }
+    int rc = cache_new("ckv_build_cache", shape, lengths, offloaded, st, &c, offs, &prop);
+    if (rc != CKV_OK) return rc;
+    const ckv_shape& s = c->shape;
+    const int64_t T = c->T;
+    const size_t e = esize(s.dtype);
+    const size_t n_ph = (size_t)T * s.H;
+    int32_t *s_ik = nullptr, *s_iv = nullptr;
+    void *s_uk = nullptr, *s_uv = nullptr;
+    unsigned long long* d_bad = nullptr;
+    unsigned long long h_bad = ~0ull;
+
+    if (n_ph > 0) {
+        if (s.d_g > 0) {
+            CKV_HIP(hipMalloc((void**)&s_ik, sizeof(int32_t) * n_ph));
+            CKV_HIP(hipMalloc((void**)&s_iv, sizeof(int32_t) * n_ph));
+            CKV_HIP(hipMemcpyAsync(s_ik, idx_k, sizeof(int32_t) * n_ph, hipMemcpyHostToDevice, st));
+            CKV_HIP(hipMemcpyAsync(s_iv, idx_v, sizeof(int32_t) * n_ph, hipMemcpyHostToDevice, st));
+        }
+        if (s.d_u > 0) {
+            const size_t ub = n_ph * (size_t)s.d_u * e;
+            CKV_HIP(hipMalloc(&s_uk, ub));
+            CKV_HIP(hipMalloc(&s_uv, ub));
+            CKV_HIP(hipMemcpyAsync(s_uk, user_k, ub, hipMemcpyHostToDevice, st));
+            CKV_HIP(hipMemcpyAsync(s_uv, user_v, ub, hipMemcpyHostToDevice, st));
+        }
+        CKV_HIP(hipMalloc((void**)&d_bad, sizeof h_bad));
+        CKV_HIP(hipMemcpyAsync(d_bad, &h_bad, sizeof h_bad, hipMemcpyHostToDevice, st));
+        {
+            const int threads = 256;
+            const int blocks = (int)std::min<size_t>((n_ph + threads - 1) / threads, 65536);
+            if (e == 4)
+                hipLaunchKernelGGL(ckv_pack_kernel<uint32_t>, dim3(blocks), dim3(threads), 0, st, s_ik, s_iv,
+                                   (const uint32_t*)s_uk, (const uint32_t*)s_uv, c->d_idx, (uint32_t*)c->d_user_k,
+                                   (uint32_t*)c->d_user_v, T, s.H, s.d_u, s.P, s.d_g > 0 ? 1 : 0, d_bad);
+            else
+                hipLaunchKernelGGL(ckv_pack_kernel<uint16_t>, dim3(blocks), dim3(threads), 0, st, s_ik, s_iv,
+                                   (const uint16_t*)s_uk, (const uint16_t*)s_uv, c->d_idx, (uint16_t*)c->d_user_k,
+                                   (uint16_t*)c->d_user_v, T, s.H, s.d_u, s.P, s.d_g > 0 ? 1 : 0, d_bad);
+            CKV_HIP(hipGetLastError());
+        }
+        CKV_HIP(hipMemcpyAsync(&h_bad, d_bad, sizeof h_bad, hipMemcpyDeviceToHost, st));
+    }
     CKV_HIP(hipStreamSynchronize(st));
+    if (h_bad != ~0ull) {
+        const long long t = (long long)(h_bad / (unsigned long long)s.H);
+        const int h = (int)(h_bad % (unsigned long long)s.H);
+        rc = fail(CKV_ERR_INDEX, "ckv_build_cache: pool index out of range [0,%d) at position %lld head %d (idx_k=%d idx_v=%d)", s.P,
+                  t, h, idx_k[h_bad], idx_v[h_bad]);
+        goto done;
+    }
+    rc = cache_finish(c, lengths, offs, prop, st);
 
 done:
     (void)hipFree(s_ik);
@@ -687,6 +721,35 @@ done:
     return CKV_OK;
 }
 
+// Check a router against a shape and fill the kernel arguments that do not depend on the handle.
+static int router_args(const char* who, const ckv_shape& s, const ckv_router* r, const void* S, int64_t T, ckv_prefill_args* a) {
+    if (!r) return fail(CKV_ERR_NULL, "%s: router is NULL", who);
+    if (r->d_e < 1) return fail(CKV_ERR_SHAPE, "%s: d_e = %d must be >= 1", who, r->d_e);
+    if (T > 0 && !S) return fail(CKV_ERR_NULL, "%s: S is NULL", who);
+    if (T > 0 && s.d_g > 0 && (!r->w_rk || !r->b_rk || !r->w_rv || !r->b_rv))
+        return fail(CKV_ERR_NULL, "%s: router weights or biases are NULL but d_g > 0", who);
+    if (T > 0 && s.d_u > 0 && (!r->w_k || !r->b_k || !r->w_v || !r->b_v))
+        return fail(CKV_ERR_NULL, "%s: projection weights or biases are NULL but d_u > 0", who);
+    const uintptr_t align = (uintptr_t)S | (uintptr_t)r->w_rk | (uintptr_t)r->w_rv | (uintptr_t)r->w_k | (uintptr_t)r->w_v |
+                            (uintptr_t)r->b_rk | (uintptr_t)r->b_rv | (uintptr_t)r->b_k | (uintptr_t)r->b_v;
+    if (align & 15) return fail(CKV_ERR_UNSUPPORTED, "%s: every device pointer must be 16-byte aligned", who);
+    a->S = S;
+    a->w_r[0] = r->w_rk;
+    a->w_r[1] = r->w_rv;
+    a->b_r[0] = r->b_rk;
+    a->b_r[1] = r->b_rv;
+    a->w_u[0] = r->w_k;
+    a->w_u[1] = r->w_v;
+    a->b_u[0] = r->b_k;
+    a->b_u[1] = r->b_v;
+    a->T = T;
+    a->H = s.H;
+    a->P = s.d_g > 0 ? s.P : 0;
+    a->d_u = s.d_u;
+    a->d_e = r->d_e;
+    return CKV_OK;
+}
+
 int ckv_build_cache(const ckv_shape* shape, const int32_t* lengths, const int32_t* idx_k, const int32_t* idx_v,
                     const void* user_k, const void* user_v, ckv_cache** out, void* stream) {
     return build_cache_impl(shape, lengths, idx_k, idx_v, user_k, user_v, out, stream, false);
@@ -695,6 +758,45 @@ int ckv_build_cache(const ckv_shape* shape, const int32_t* lengths, const int32_
 int ckv_build_cache_offloaded(const ckv_shape* shape, const int32_t* lengths, const int32_t* idx_k, const int32_t* idx_v,
                               const void* user_k, const void* user_v, ckv_cache** out, void* stream) {
     return build_cache_impl(shape, lengths, idx_k, idx_v, user_k, user_v, out, stream, true);
+}
+
+int ckv_prefill_into(ckv_cache* c, const ckv_router* router, const void* S, void* stream) {
+    if (!c) return fail(CKV_ERR_NULL, "ckv_prefill_into: cache is NULL");
+    ckv_prefill_args a;
+    int rc = router_args("ckv_prefill_into", c->shape, router, S, c->T, &a);
+    if (rc != CKV_OK) return rc;
+    a.idx = c->d_idx;
+    a.user[0] = c->d_user_k;
+    a.user[1] = c->d_user_v;
+    hipError_t e = ckv_launch_prefill(a, c->shape.dtype, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(CKV_ERR_HIP, "ckv_prefill_into: kernel launch (%s): %s",
+                                     ckv_prefill_variant(c->shape.dtype, router->d_e, c->shape.d_u), hipGetErrorString(e));
+    return CKV_OK;
+}
+
+int ckv_prefill(const ckv_shape* shape, const ckv_router* router, const int32_t* lengths, const void* S, ckv_cache** out,
+                void* stream) {
+    if (out) *out = nullptr;
+    if (!shape || !lengths || !out || !router) return fail(CKV_ERR_NULL, "ckv_prefill: shape, router, lengths and out must not be NULL");
+    hipStream_t st = (hipStream_t)stream;
+    ckv_cache* c = nullptr;
+    std::vector<int64_t> offs;
+    hipDeviceProp_t prop;
+    int rc = cache_new("ckv_prefill", shape, lengths, false, st, &c, offs, &prop);
+    if (rc != CKV_OK) return rc;
+    rc = ckv_prefill_into(c, router, S, stream);
+    if (rc == CKV_OK) rc = cache_finish(c, lengths, offs, prop, st);
+    if (rc != CKV_OK) {
+        destroy(c);
+        return rc;
+    }
+    *out = c;
+    return CKV_OK;
+}
+
+const char* ckv_prefill_kernel_name(const ckv_shape* shape, const ckv_router* router) {
+    if (!shape || !router) return "";
+    return ckv_prefill_variant(shape->dtype, router->d_e, shape->d_u);
 }
 
 int ckv_cache_is_offloaded(const ckv_cache* c) { return c ? c->offloaded : 0; }

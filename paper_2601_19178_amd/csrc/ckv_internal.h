@@ -46,6 +46,19 @@ struct ckv_args {
     float scale;
 };
 
+// Kernel arguments of the prefill kernels.  Index 0 of every pair is the key side, 1 the value side.
+struct ckv_prefill_args {
+    const void* S;            // [T][d_e]
+    const void* w_r[2];       // [H][P][d_e]
+    const float* b_r[2];      // [H][P]
+    const void* w_u[2];       // [H][d_u][d_e]
+    const float* b_u[2];      // [H][d_u]
+    int32_t* idx;             // out [2][H][T]
+    void* user[2];            // out [H][T][d_u]
+    int64_t T;
+    int32_t H, P, d_u, d_e;
+};
+
 enum ckv_kernel_family { CKV_K_STREAM = 0, CKV_K_MFMA = 1, CKV_K_DMA = 2 };
 
 struct ckv_cache {
@@ -91,5 +104,10 @@ hipError_t ckv_launch_dma(const ckv_cache* c, const ckv_args& a, hipStream_t s);
 int ckv_dma_nui(int d_a, int nw, int d_u);  // -1: shape not served
 int ckv_dma_occupancy(int d_a, int nw, int qg, int mode);
 bool ckv_dma_supported(int d_a, int nw, int qg);
+
+// Prefill (projection + router argmax into the packed cache layout).
+hipError_t ckv_launch_prefill(const ckv_prefill_args& a, int dtype, hipStream_t s);
+const char* ckv_prefill_variant(int dtype, int d_e, int d_u);
+bool ckv_prefill_mfma_supported(int dtype, int d_e, int d_u);
 
 #endif

@@ -26,7 +26,9 @@ def _to_host(t, dtype):
 class Session:
     """Pools and queries on the device, the packed cache handle, an output buffer."""
 
-    def __init__(self, w, offloaded=False):
+    def __init__(self, w, offloaded=False, prefill=None):
+        """prefill: a prefill workload dict (embedding, router and projection weights); the packed cache is
+        then computed on the device by ckv_prefill instead of being packed from w's host arrays."""
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU: the CollectiveKV hot path needs an MI355X (there is no CPU fallback)")
         self.w = w
@@ -40,9 +42,21 @@ class Session:
         self.q = _to_device(w["q"], self.dtype)
         tdt = torch.float32 if self.dtype == ckv.CKV_F32 else torch.bfloat16
         self.out = torch.full((w["B"], w["H"], w["Nq"], self.d_a), float("nan"), dtype=tdt, device="cuda")
-        build = ckv.ckv_build_cache_offloaded if offloaded else ckv.ckv_build_cache
-        self.cache = build(self.shape, w["lengths"], w["idx_k"], w["idx_v"], w["user_k"], w["user_v"],
-                                         self.stream)
+        self.router = None
+        if prefill is not None:
+            r = prefill
+            assert not offloaded and r["H"] == w["H"] and r["d_u"] == w["d_u"] and r["dtype"] == w["dtype"]
+            assert r["T"] == int(np.sum(w["lengths"])) and (w["d_g"] == 0 or r["P"] == w["P"])
+            self.S = _to_device(r["S"], self.dtype)
+            self.rw = {k: _to_device(r[k], self.dtype) for k in ("w_rk", "w_rv", "w_k", "w_v")}
+            self.rb = {k: torch.from_numpy(np.ascontiguousarray(r[k], dtype=np.float32)).cuda()
+                       for k in ("b_rk", "b_rv", "b_k", "b_v")}
+            self.router = ckv.make_router(r["d_e"], self.rw["w_rk"], self.rb["b_rk"], self.rw["w_rv"], self.rb["b_rv"],
+                                          self.rw["w_k"], self.rb["b_k"], self.rw["w_v"], self.rb["b_v"])
+            self.cache = ckv.ckv_prefill(self.shape, self.router, w["lengths"], self.S, self.stream)
+        else:
+            build = ckv.ckv_build_cache_offloaded if offloaded else ckv.ckv_build_cache
+            self.cache = build(self.shape, w["lengths"], w["idx_k"], w["idx_v"], w["user_k"], w["user_v"], self.stream)
         self.T = ckv.ckv_cache_positions(self.cache)
 
     def attend(self, stream=None):
@@ -51,6 +65,10 @@ class Session:
                        ckv.ckv_cache_user_v(c), self.q, ckv.ckv_cache_lengths(c), self.out,
                        self.stream if stream is None else stream)
         return self.out
+
+    def prefill_again(self, stream=None):
+        """Recompute the packed cache in place from the embedding and the router (no allocation)."""
+        ckv.ckv_prefill_into(self.cache, self.router, self.S, self.stream if stream is None else stream)
 
     def output(self):
         """Output of the last attend() as float64 numpy (exact widening of the stored values)."""

@@ -164,3 +164,22 @@ def make_prefill(T, H, d_e, d_u, P, dtype, seed, sigma_s=1.0, sigma_b=0.1, integ
                 b_rk=draw(23, (H, P_eff), sigma_b, F32), b_rv=draw(24, (H, P_eff), sigma_b, F32),
                 w_k=draw(25, (H, d_u, d_e), sw, dtype), w_v=draw(26, (H, d_u, d_e), sw, dtype),
                 b_k=draw(27, (H, d_u), sigma_b, F32), b_v=draw(28, (H, d_u), sigma_b, F32))
+
+
+# Prefill workloads: the cache shapes of configs 2 and 3 (T positions, heads, d_u, pool size), an embedding
+# width of 128 (the paper does not state d_e for its models).
+PREFILL_CONFIGS = {
+    "prefill_cfg2": dict(T=1024 * 200, H=2, d_e=128, d_u=8, P=4096, dtype=BF16, seed=1102),
+    "prefill_cfg3": dict(T=512 * 1024, H=4, d_e=128, d_u=4, P=16384, dtype=BF16, seed=1103),
+}
+
+
+def prefill_config(name, **override):
+    recipe = dict(PREFILL_CONFIGS[name])
+    recipe.update(override)
+    return make_prefill(**recipe)
+
+
+def prefill_flops(r):
+    """Multiply-adds of the prefill stage counted as 2 flop: two routers and two projections per head."""
+    return 2.0 * r["T"] * r["H"] * 2 * (r["P"] + r["d_u"]) * r["d_e"]

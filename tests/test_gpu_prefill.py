@@ -1,0 +1,198 @@
+"""GPU parity of the prefill stage (projection + router argmax written into the packed cache) through
+the C ABI against the CPU oracle.
+
+Indices are integers decided by floating point: on inputs whose sums are exact in fp32 (small integers)
+both sides must agree bit for bit, ties included; on random inputs the GPU forms the routing map in fp32
+and the oracle in fp64, so an index may differ where two scores are closer than the fp32 rounding of
+their sums: there the GPU's pick must be within that rounding of the row maximum (its validity), and
+nearly all indices must still be identical.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import oracle
+from paper_2601_19178_amd import workloads as wl
+from tests.parity import check
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2601_19178_amd import ckv, session
+    return ckv, session
+
+
+def decode_workload(lengths, r, Nq=2, mode=wl.SOFTMAX, d_g=None, seed=31):
+    """A decode workload whose cache shape matches the prefill workload r."""
+    lengths = np.asarray(lengths, dtype=np.int32)
+    d_g = (56 if r["P"] > 1 else 0) if d_g is None else d_g
+    d_a = d_g + r["d_u"]
+    return wl.make(B=len(lengths), L=None, H=r["H"], d_a=d_a, d_u=r["d_u"], P=r["P"], idx="uniform", Nq=Nq, mode=mode,
+                   dtype=r["dtype"], sigma_pool=max(d_a, 1) ** -0.5, seed=seed, lengths=lengths)
+
+
+def user_tolerance(ref, dtype):
+    # fp32 accumulation of d_e <= 256 products of magnitude ~0.1 (worst case d_e * 2^-24 of their absolute sum,
+    # ~2^-16 of a result of order one), then one rounding to the storage type (2^-9 for bf16)
+    eps = 2.0 ** -8 if dtype == wl.BF16 else 2.0 ** -16
+    return eps * np.abs(ref) + eps
+
+
+def run_prefill(gpu, lengths, r, what, expect_kernel, exact, d_g=None):
+    ckv, session = gpu
+    w = decode_workload(lengths, r, d_g=d_g)
+    say(f"[case] {what}: T={r['T']} H={r['H']} d_e={r['d_e']} d_u={r['d_u']} P={r['P']} dtype={r['dtype']} d_g={w['d_g']}")
+    with session.Session(w, prefill=r) as s:
+        name = ckv.ckv_prefill_kernel_name(s.shape, s.router)
+        say(f"  kernel {name}")
+        assert name.startswith(expect_kernel), name
+        idx, uk, uv = s.packed_views()
+        # the handle works like any other: attend over the cache the prefill wrote
+        s.attend()
+        out = s.output()
+    ik, iv, ruk, ruv = oracle.prefill(r)
+    T, H = r["T"], r["H"]
+    if w["d_g"] > 0:
+        for side, got, ref in (("k", idx[0].T, ik), ("v", idx[1].T, iv)):
+            assert got.size == 0 or (got.min() >= 0 and got.max() < r["P"])
+            same = float((got == ref).mean()) if got.size else 1.0
+            if exact:
+                np.testing.assert_array_equal(got, ref, err_msg=f"{what}: I_{side}")
+            else:
+                gap, mag = oracle.router_gap(r, side, np.ascontiguousarray(got))
+                bound = (r["d_e"] + 2) * 2.0 ** -23 * mag
+                assert (gap <= bound).all(), f"{what}: I_{side}: a pick is {float((gap - bound).max()):.3e} beyond fp32 rounding of the maximum"
+                assert same > 0.995, f"{what}: I_{side}: only {same:.4f} of the indices equal the fp64 argmax"
+            say(f"  I_{side}: {same:.5f} identical to the oracle")
+    sdt = np.float32 if r["dtype"] == wl.F32 else np.uint16
+    guk = wl.to_f64(uk.astype(sdt), r["dtype"]).transpose(1, 0, 2)
+    guv = wl.to_f64(uv.astype(sdt), r["dtype"]).transpose(1, 0, 2)
+    for side, got, ref in (("k", guk, ruk), ("v", guv, ruv)):
+        if exact:
+            want = ref.astype(np.float32)
+            want = want.astype(np.float64) if r["dtype"] == wl.F32 else wl.to_f64(wl.f32_to_bf16_bits(want), wl.BF16)
+            np.testing.assert_array_equal(got, want, err_msg=f"{what}: {side.upper()}_u")
+        else:
+            assert (np.abs(got - ref) <= user_tolerance(ref, r["dtype"])).all(), f"{what}: {side.upper()}_u out of tolerance"
+    # decode over exactly what the prefill cached
+    if T > 0:
+        w2 = dict(w)
+        if w["d_g"] > 0:
+            w2["idx_k"], w2["idx_v"] = np.ascontiguousarray(idx[0].T), np.ascontiguousarray(idx[1].T)
+        w2["user_k"] = np.ascontiguousarray(uk.astype(sdt).transpose(1, 0, 2))
+        w2["user_v"] = np.ascontiguousarray(uv.astype(sdt).transpose(1, 0, 2))
+        check(out, oracle.attend(w2), w["dtype"], what=what + " (decode over the prefilled cache)")
+    say("  ok")
+
+
+LENGTHS = (5, 0, 300, 1, 64, 257, 33)   # T = 660: three position blocks of 256 and a ragged tail
+
+
+@pytest.mark.parametrize("d_e,d_u,P,H", [(64, 8, 1000, 2), (128, 3, 77, 3), (128, 8, 4096, 1), (256, 32, 333, 2),
+                                          (64, 0, 31, 1), (128, 16, 32, 2), (256, 2, 5, 1)])
+def test_mfma_exact_on_integer_inputs(gpu, d_e, d_u, P, H):
+    r = wl.make_prefill(T=sum(LENGTHS), H=H, d_e=d_e, d_u=d_u, P=P, dtype=wl.BF16, seed=40 + d_u, integers=1)
+    run_prefill(gpu, LENGTHS, r, f"prefill mfma exact d_e={d_e} d_u={d_u} P={P}", "prefill_mfma_bf16", exact=True)
+
+
+@pytest.mark.parametrize("d_e,d_u,P,H", [(64, 8, 1000, 2), (128, 4, 4099, 2), (256, 8, 500, 1)])
+def test_mfma_random_inputs(gpu, d_e, d_u, P, H):
+    r = wl.make_prefill(T=sum(LENGTHS), H=H, d_e=d_e, d_u=d_u, P=P, dtype=wl.BF16, seed=50 + d_u)
+    run_prefill(gpu, LENGTHS, r, f"prefill mfma random d_e={d_e} d_u={d_u} P={P}", "prefill_mfma_bf16", exact=False)
+
+
+@pytest.mark.parametrize("dtype,d_e,d_u,P,integers", [(wl.F32, 24, 3, 61, 2), (wl.F32, 100, 8, 300, None),
+                                                       (wl.BF16, 40, 5, 129, 2), (wl.BF16, 72, 2, 50, None)])
+def test_scalar_kernel(gpu, dtype, d_e, d_u, P, integers):
+    lengths = (5, 0, 120, 1, 64)
+    r = wl.make_prefill(T=sum(lengths), H=2, d_e=d_e, d_u=d_u, P=P, dtype=dtype, seed=60 + d_e, integers=integers)
+    run_prefill(gpu, lengths, r, f"prefill scalar dtype={dtype} d_e={d_e}", "prefill_scalar", exact=integers is not None)
+
+
+def test_no_pool_and_no_user_columns(gpu):
+    # d_g = 0: "degenerates into the original KV" (only the projection); d_u = 0: only the router
+    r = wl.make_prefill(T=sum(LENGTHS), H=2, d_e=64, d_u=16, P=1, dtype=wl.BF16, seed=70, integers=1)
+    run_prefill(gpu, LENGTHS, r, "prefill d_g=0", "prefill_mfma_bf16", exact=True, d_g=0)
+    r = wl.make_prefill(T=sum(LENGTHS), H=2, d_e=128, d_u=0, P=200, dtype=wl.BF16, seed=71, integers=1)
+    run_prefill(gpu, LENGTHS, r, "prefill d_u=0", "prefill_mfma_bf16", exact=True, d_g=64)
+
+
+def test_all_histories_empty(gpu):
+    r = wl.make_prefill(T=0, H=2, d_e=64, d_u=8, P=100, dtype=wl.BF16, seed=72)
+    run_prefill(gpu, (0, 0, 0), r, "prefill T=0", "prefill_mfma_bf16", exact=True)
+
+
+def test_prefill_into_recomputes_in_place(gpu):
+    ckv, session = gpu
+    r = wl.make_prefill(T=sum(LENGTHS), H=2, d_e=128, d_u=8, P=1000, dtype=wl.BF16, seed=73)
+    w = decode_workload(LENGTHS, r)
+    say("[case] prefill_into")
+    with session.Session(w, prefill=r) as s:
+        first = [a.copy() for a in s.packed_views()]
+        import torch
+        # overwrite the packed cache, then recompute it
+        n = 2 * r["H"] * r["T"]
+        junk = torch.full((n,), 7, dtype=torch.int32, device="cuda")
+        ckv.ckv_copy(ckv.ckv_cache_idx(s.cache), junk, n * 4, s.stream)
+        torch.cuda.synchronize()
+        assert (s.packed_views()[0] == 7).all()
+        s.prefill_again()
+        again = s.packed_views()
+    for a, b in zip(first, again):
+        np.testing.assert_array_equal(a, b)
+
+
+def test_router_rejects_bad_arguments(gpu):
+    ckv, session = gpu
+    import torch
+    r = wl.make_prefill(T=10, H=1, d_e=64, d_u=8, P=10, dtype=wl.BF16, seed=74)
+    w = decode_workload((10,), r)
+    sh = ckv.make_shape(w["B"], w["H"], w["d_g"], w["d_u"], w["P"], w["Nq"], w["dtype"], w["mode"], w["scale"], w["pool_ld"])
+    S = torch.zeros((10, 64), dtype=torch.bfloat16, device="cuda")
+    z = torch.zeros(64 * 64, dtype=torch.float32, device="cuda")
+    with pytest.raises(ckv.CkvError) as e:
+        ckv.ckv_prefill(sh, ckv.make_router(64, None, z, z, z, z, z, z, z), w["lengths"], S)
+    assert e.value.code == ckv.CKV_ERR_NULL
+    with pytest.raises(ckv.CkvError) as e:
+        ckv.ckv_prefill(sh, ckv.make_router(0, z, z, z, z, z, z, z, z), w["lengths"], S)
+    assert e.value.code == ckv.CKV_ERR_SHAPE
+    with pytest.raises(ckv.CkvError) as e:
+        ckv.ckv_prefill(sh, ckv.make_router(64, z, z, z, z, z, z, z, z), w["lengths"], S.data_ptr() + 2)
+    assert e.value.code == ckv.CKV_ERR_UNSUPPORTED
+
+
+def test_full_size_prefill_sampled(gpu):
+    """The workload the benchmark times (config 2's cache: B=1024, L=200, H=2, d_u=8, P=4096; d_e=128),
+    oracle on sampled positions."""
+    ckv, session = gpu
+    r = wl.prefill_config("prefill_cfg2")
+    w = wl.config("cfg2_bf16")
+    say(f"[case] full-size prefill: T={r['T']} P={r['P']} d_e={r['d_e']}")
+    with session.Session(w, prefill=r) as s:
+        assert ckv.ckv_prefill_kernel_name(s.shape, s.router) == "prefill_mfma_bf16_e128"
+        idx, uk, uv = s.packed_views()
+    sample = np.sort(np.random.default_rng(5).choice(r["T"], size=3000, replace=False))
+    sample = np.unique(np.concatenate([sample, [0, 255, 256, r["T"] - 1]]))
+    rs = dict(r)
+    rs["S"] = np.ascontiguousarray(r["S"][sample])
+    rs["T"] = len(sample)
+    ik, iv, ruk, ruv = oracle.prefill(rs)
+    for side, got, ref in (("k", idx[0].T[sample], ik), ("v", idx[1].T[sample], iv)):
+        gap, mag = oracle.router_gap(rs, side, np.ascontiguousarray(got))
+        assert (gap <= (r["d_e"] + 2) * 2.0 ** -23 * mag).all()
+        same = float((got == ref).mean())
+        say(f"  I_{side}: {same:.5f} identical to the oracle")
+        assert same > 0.995
+    for got, ref in ((uk, ruk), (uv, ruv)):
+        g = wl.to_f64(got.astype(np.uint16), wl.BF16).transpose(1, 0, 2)[sample]
+        assert (np.abs(g - ref) <= user_tolerance(ref, wl.BF16)).all()
