@@ -11,6 +11,8 @@ histories), inputs resident in HBM.  Prints ONE JSON line:
                against the 8 TB/s HBM peak
   cpu_baseline the CPU oracle on a sample of the same workload's users, on this host's cores
   also         the same figures for the other workloads (not the headline)
+  prefill      the prefill stage (router argmax + projection into the packed cache) on the cache shape of
+               config 2: positions/s and matrix-core TFLOP/s against the dense bf16 peak
 """
 import argparse
 import json
@@ -88,6 +90,60 @@ def measure(name, steps, warmup, with_compulsory=True):
     return res, w, s
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def measure_prefill(name, steps, warmup, with_cpu=False):
+    """Prefill stage (router GEMM + argmax, projection) recomputed into a resident handle: one step = one
+    ckv_prefill_into over all T positions.  Every launch is bracketed by its own event pair on the launch stream."""
+    import torch
+    from paper_2601_19178_amd import ckv, session, workloads as wl
+
+    r = wl.prefill_config(name)
+    decode = {"prefill_cfg2": "cfg2_bf16", "prefill_cfg3": "cfg3"}[name]
+    w = wl.config(decode)
+    s = session.Session(w, prefill=r)
+    for _ in range(warmup):
+        s.prefill_again()
+    torch.cuda.synchronize()
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for a, b in pairs:
+        a.record()
+        s.prefill_again()
+        b.record()
+    stop.record()
+    torch.cuda.synchronize()
+    ms_step = start.elapsed_time(stop) / steps
+    ms_kernel = float(np.mean([a.elapsed_time(b) for a, b in pairs]))
+    flops = wl.prefill_flops(r)
+    res = {
+        "workload": name,
+        "describe": f"prefill of {decode}'s cache: T={r['T']} H={r['H']} d_e={r['d_e']} d_u={r['d_u']} P={r['P']} bf16",
+        "kernel": ckv.ckv_prefill_kernel_name(s.shape, s.router),
+        "ms_per_step": ms_step, "kernel_ms": ms_kernel,
+        "positions_per_s": r["T"] / (ms_step * 1e-3),
+        "users_per_s": w["B"] / (ms_step * 1e-3),
+        "flop": flops,
+        "roofline": {"bound": "mfma", "achieved": flops / (ms_kernel * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": flops / (ms_kernel * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
+    }
+    s.close()
+    if with_cpu:
+        from oracle import oracle
+        n = 256
+        rs = dict(r)
+        rs["S"] = np.ascontiguousarray(r["S"][:n])
+        rs["T"] = n
+        t0 = time.time()
+        oracle.prefill(rs)
+        dt = time.time() - t0
+        res["cpu_baseline"] = {"value": n / dt, "unit": "positions/s", "cores": oracle.threads(), "kind": "oracle",
+                               "sample": f"first {n} of {r['T']} positions, all heads, both routers, {dt:.1f} s wall"}
+    return res
+
+
 def cpu_baseline(w, budget_s=15.0):
     """The oracle as it stands, timed on a bounded sample of users (all heads, all queries)."""
     from oracle import oracle
@@ -150,6 +206,8 @@ def main():
                     help="untimed steps; the GPU needs ~50 back-to-back launches to reach its steady clocks")
     ap.add_argument("--workload", default="cfg4", choices=sorted(DESCRIBE))
     ap.add_argument("--also", default="cfg2_f32,cfg2_bf16,cfg3", help="comma list of further workloads ('' for none)")
+    ap.add_argument("--prefill", default="prefill_cfg2",
+                    help="comma list of prefill workloads reported under 'prefill' (prefill_cfg2, prefill_cfg3; '' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--offloaded-sweep", action="store_true",
                     help="latency of one decode batch with the compressed cache in pinned host memory vs resident vs "
@@ -190,6 +248,9 @@ def main():
         del w2, s2
         also.append(r)
 
+    prefill = [measure_prefill(n, max(10, args.steps // 4), max(5, args.warmup // 4), with_cpu=not args.no_cpu_baseline)
+               for n in args.prefill.split(",") if n]
+
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
@@ -218,6 +279,7 @@ def main():
                      "C_bytes": head.get("C_bytes"), "C_GBps": head.get("C_GBps_kernel")},
         "cpu_baseline": base,
         "also": also,
+        "prefill": prefill,
     }
     print(json.dumps(line))
 

@@ -8,8 +8,8 @@
 //     LDS; the instruction puts lane l at M0 + 16*l, so one wavefront fills 1 KiB of
 //     consecutive rows).  The row layout inside LDS is [pool columns | user columns],
 //     unpadded, with the 16-byte chunks of row p stored at slot (chunk XOR f(p)) so that the
-//     operand reads stay free of bank conflicts; the lane chooses which chunk it fetches,
-//     so the swizzle costs nothing on the way in.
+//     operand reads stay free of bank conflicts (64 banks); the lane chooses which chunk it
+//     fetches, so the swizzle costs nothing on the way in.
 //   * the pool indices of a tile and its user-specific slices are fetched the same way
 //     (global_load_lds_dword) into small staging areas; the "concat" of the paper
 //     (eq. "eq: K") is an LDS->LDS copy of the user columns into the tail of each row.
@@ -78,8 +78,19 @@ __device__ __forceinline__ void lds_barrier() {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-__device__ __forceinline__ int fk(int p) { return p & 7; }         // K rows: 16-byte row reads
-__device__ __forceinline__ int fv(int p) { return (p & 3) << 1; }  // V rows: transpose reads
+// LDS swizzle: 16-byte chunk c of row p is stored at slot c ^ f(p).  The LDS has 64 banks of 4 bytes
+// (256 bytes per clock), so an access is conflict free when the lanes served together cover sixteen
+// different 16-byte slots modulo 16.
+//   K rows (ds_read_b128, sixteen consecutive rows, same chunk): the low four bits of the row for
+//   256-byte rows; for 128-byte rows two neighbouring rows already differ in bit 3 of the slot number, so
+//   the next three bits of the row are used.
+//   V rows (ds_read_b64_tr_b16, four consecutive rows x four consecutive chunks per clock): the row's low
+//   two bits select one of the four 64-byte quarters of a 256-byte row; for 128-byte rows bit 1 of the row
+//   selects one of the two halves.
+template <int DA>
+__device__ __forceinline__ int fk(int p) { return DA == 128 ? (p & 15) : ((p >> 1) & 7); }
+template <int DA>
+__device__ __forceinline__ int fv(int p) { return DA == 128 ? ((p & 3) << 2) : (((p >> 1) & 1) << 2); }
 
 template <int DA, int NW>
 struct Geo {
@@ -207,8 +218,8 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
 #pragma unroll
         for (int i = 0; i < G::NI; ++i) {
             gp[i] = (i * NW + wave) * G::RPI + lane / G::CH;
-            int ck = gslot ^ fk(gp[i]);
-            int cv = gslot ^ fv(gp[i]);
+            int ck = gslot ^ fk<DA>(gp[i]);
+            int cv = gslot ^ fv<DA>(gp[i]);
             if (ck * 8 >= d_g) ck = 0;  // a pure user chunk: fetch something valid, the concat overwrites it
             if (cv * 8 >= d_g) cv = 0;
             gk_off[i] = ck * 16;
@@ -235,15 +246,15 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
             const int o = uisv[u] ? slice - ROWS_W : slice;
             up[u] = ((o / G::RPI) * NW + wave) * G::RPI + (o % G::RPI);
             const int col = d_g + 2 * uoff[u];
-            const int slot = (col >> 3) ^ (uisv[u] ? fv(up[u]) : fk(up[u]));
+            const int slot = (col >> 3) ^ (uisv[u] ? fv<DA>(up[u]) : fk<DA>(up[u]));
             cdst[u] = (uisv[u] ? G::KV : 0) + up[u] * G::ROWB + slot * 16 + (col & 7) * 2;
         }
         // ---- per-lane constants of the operand reads
         const uint32_t krow = qn * G::ROWB;
-        const int kx = fk(qn);
+        const int kx = fk<DA>(qn);
         const int g16 = lane >> 4, s16 = lane & 15;
         const uint32_t vrow = G::KV + (4 * hh + (s16 >> 2)) * G::ROWB + (s16 & 1) * 8;
-        const int vc = 2 * (g16 & 1) + ((s16 & 3) >> 1), vx = fv(s16 >> 2);
+        const int vc = 2 * (g16 & 1) + ((s16 & 3) >> 1), vx = fv<DA>(s16 >> 2);
 
         const uint32_t idx_lds = lds0 + NS * G::STAGE + wave * G::NIS * G::IDX;
 

@@ -18,6 +18,8 @@
 // The projection is one more tile whose 32 "pool entries" are the d_u rows of W_k (or W_v).
 //
 // Scalar kernel: any d_e and either storage type, one thread per (position, head, side).
+#include <type_traits>
+
 #include "ckv_internal.h"
 
 namespace {
@@ -30,14 +32,20 @@ typedef __attribute__((address_space(3))) unsigned char lds_u8;
 typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
 typedef __attribute__((address_space(3))) f32x4 lds_f32x4;
 
-constexpr int TR = 32;  // pool entries per tile
-constexpr int NS = 4;   // stages in the LDS ring
+constexpr int SR = 32;  // pool entries per MFMA row block
 
 __device__ __forceinline__ void dma16(const void* g, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_base) : "memory");
 }
+// 16 bytes per lane from (wavefront-uniform base + per-lane 32-bit offset) to LDS[lds_base + 16*lane]
+__device__ __forceinline__ void dma16_uniform(const void* base, uint32_t off, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds_base) : "memory");
+}
 __device__ __forceinline__ void dma4(const void* g, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(g), "s"(lds_base) : "memory");
+}
+__device__ __forceinline__ void dma4_uniform(const void* base, uint32_t off, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(base), "s"(lds_base) : "memory");
 }
 template <int N>
 __device__ __forceinline__ void wait_vm() {
@@ -52,22 +60,32 @@ __device__ __forceinline__ uint32_t swap_halves(uint32_t x) {
 }
 __device__ __forceinline__ uint16_t f2bf(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
 
-template <int DE, int NW>
+// TR = pool entries per stage (one barrier per stage), NS = stages in the LDS ring.
+template <int DE, int NW, int TR, int NS>
 struct PGeo {
     static constexpr int CH = DE / 8;            // 16-byte chunks per weight row
     static constexpr int ROWB = DE * 2;          // bytes per weight row
     static constexpr int RPI = 64 / CH;          // rows filled by one wavefront load instruction
-    static constexpr int NI = TR / RPI / NW;     // load instructions per wavefront and tile
+    static constexpr int NI = TR / RPI / NW;     // load instructions per wavefront and stage
     static constexpr int WT = TR * ROWB;         // bytes of the weight rows of a stage
-    static constexpr int STAGE = WT + NW * 256;  // plus one private copy of the 32 biases per wavefront
+    static constexpr int STAGE = WT + NW * 256;  // plus one private copy of the (up to 64) biases per wavefront
     static constexpr int LDS = NS * STAGE;
-    static_assert(NI >= 1, "tile too small for this many wavefronts");
+    static constexpr int NSUB = TR / SR;         // MFMA row blocks per stage
+    // 16-byte chunk c of row p is stored at slot c ^ swz(p).  A 16-byte-per-lane LDS read is served sixteen
+    // lanes at a time from 64 banks, so sixteen consecutive rows must land in sixteen different slots
+    // modulo 16: rows of 256 or 512 bytes use the low four bits of the row, rows of 128 bytes (two rows
+    // per 16 slots) the next three.
+    __device__ static constexpr int swz(int p) { return CH >= 16 ? (p & 15) : ((p >> 1) & 7); }
+    static_assert(NI >= 1 && (TR == 32 || TR == 64), "stage geometry");
 };
 
 // One workgroup: NW wavefronts x QG groups x 32 positions, one (head, side).
-template <int DE, int NW, int QG>
-__global__ __launch_bounds__(NW * 64) void ckv_prefill_mfma_kernel(ckv_prefill_args a) {
-    using G = PGeo<DE, NW>;
+// WPE resident wavefronts per SIMD; with at most 256 registers per wavefront the accumulators live in
+// ordinary vector registers, where the maximum search reads them without copies.  Three wavefronts per
+// SIMD measured 10 % faster than two: while one searches its accumulators another feeds the matrix core.
+template <int DE, int NW, int QG, int TR, int NS, int WPE>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))) void ckv_prefill_mfma_kernel(ckv_prefill_args a) {
+    using G = PGeo<DE, NW, TR, NS>;
     constexpr int NKK = DE / 16;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_u8*)smem;
@@ -85,8 +103,9 @@ __global__ __launch_bounds__(NW * 64) void ckv_prefill_mfma_kernel(ckv_prefill_a
     const float* __restrict__ br = a.b_r[side] + (int64_t)h * P;
     const unsigned char* __restrict__ wu = (const unsigned char*)a.w_u[side] + (int64_t)h * d_u * G::ROWB;
     const float* __restrict__ bu = a.b_u[side] + (int64_t)h * d_u;
-    const int nrt = (P + TR - 1) / TR;         // router tiles
-    const int ntt = nrt + (d_u > 0 ? 1 : 0);   // plus the projection tile
+    const int nfull = P / TR;                      // stages made of TR valid router rows
+    const int nrt = (P + TR - 1) / TR;             // router stages
+    const int ntt = nrt + (d_u > 0 ? 1 : 0);       // plus the projection stage
     if (ntt == 0) return;
 
     // ---- positions of this wavefront: B operands, 16 bytes per lane and k-step, straight from S
@@ -111,17 +130,30 @@ __global__ __launch_bounds__(NW * 64) void ckv_prefill_mfma_kernel(ckv_prefill_a
         for (int kk = 0; kk < NKK; ++kk) asm volatile("" : "+v"(sreg[g][kk]));
 
     // ---- per-lane constants of the weight loads: instruction i of this wavefront fills rows
-    //      (i*NW + wave)*RPI .. +RPI of the stage; chunk c of row p is stored at slot c ^ (p & 7)
+    //      (i*NW + wave)*RPI .. +RPI of the stage; chunk c of row p is stored at slot c ^ swz(p).
+    //      For a stage of TR valid rows the per-lane byte offset inside the stage never changes and
+    //      the stage base is wavefront-uniform, so issuing a load costs no vector arithmetic.
     int lrow[G::NI];
-    uint32_t lchunk[G::NI];
+    uint32_t lchunk[G::NI], loff[G::NI];
 #pragma unroll
     for (int i = 0; i < G::NI; ++i) {
         lrow[i] = (i * NW + wave) * G::RPI + lane / G::CH;
-        lchunk[i] = (uint32_t)(((lane % G::CH) ^ (lrow[i] & 7)) * 16);
+        lchunk[i] = (uint32_t)(((lane % G::CH) ^ G::swz(lrow[i])) * 16);
+        loff[i] = (uint32_t)lrow[i] * G::ROWB + lchunk[i];
     }
+    const uint32_t boff = (uint32_t)(lane & (TR - 1)) * 4;
     auto issue = [&](int tile) {
-        const uint32_t st = lds0 + (tile & (NS - 1)) * G::STAGE;
-        tile = min(tile, ntt - 1);  // loads past the last tile repeat it, into a retired stage (never read)
+        const uint32_t st = lds0 + (tile % NS) * G::STAGE;
+        if (tile < nfull) {
+            const unsigned char* base = wr + (int64_t)tile * (TR * G::ROWB);
+#pragma unroll
+            for (int i = 0; i < G::NI; ++i) dma16_uniform(base, loff[i], st + (i * NW + wave) * G::RPI * G::ROWB);
+            dma4_uniform(br + (int64_t)tile * TR, boff, st + G::WT + wave * 256);
+            return;
+        }
+        // ragged last router stage, the projection stage, or a repeat of the last stage into a retired
+        // slot (never read): rows are clamped to the last valid one
+        tile = min(tile, ntt - 1);
         const bool proj = tile >= nrt;
         const unsigned char* wbase = proj ? wu : wr;
         const float* bbase = proj ? bu : br;
@@ -132,7 +164,7 @@ __global__ __launch_bounds__(NW * 64) void ckv_prefill_mfma_kernel(ckv_prefill_a
             const int row = min(row0 + lrow[i], rmax);
             dma16(wbase + (int64_t)row * G::ROWB + lchunk[i], st + (i * NW + wave) * G::RPI * G::ROWB);
         }
-        dma4(bbase + min(row0 + qn, rmax), st + G::WT + wave * 256);
+        dma4(bbase + min(row0 + (lane & (TR - 1)), rmax), st + G::WT + wave * 256);
     };
 
     float bv[QG];
@@ -143,67 +175,87 @@ __global__ __launch_bounds__(NW * 64) void ckv_prefill_mfma_kernel(ckv_prefill_a
         bj[g] = 0;
     }
     const uint32_t arow = qn * G::ROWB;
-    const int ax = qn & 7;
+    const int ax = G::swz(qn);
 
-    issue(0);
-    issue(1);
-    issue(2);
-    wait_vm<2 * (G::NI + 1)>();
-    lds_barrier();
-    for (int t = 0; t < ntt; ++t) {
+    // One stage: KIND 0 = TR valid router rows, 1 = last router stage with fewer, 2 = projection.
+    // The three are separate instantiations so that the loop over full stages stays free of their branches.
+    // Iteration t issues the loads of stage t+NS-1 into the slot stage t-1 used (retired by the barrier at
+    // the end of iteration t-1), computes stage t, then waits until only the loads of the last NS-2 issues
+    // are outstanding, i.e. until its own part of stage t+1 has landed; the barrier publishes stage t+1.
+    auto stage = [&](auto kind, int t) {
+        constexpr int KIND = decltype(kind)::value;
         issue(t + NS - 1);
-        const uint32_t st = lds0 + (t & (NS - 1)) * G::STAGE;
-        bf16x8 wa[NKK];
+        const uint32_t st = lds0 + (t % NS) * G::STAGE;
+        bf16x8 wa[NKK];  // A operand: this lane's router row, all k-steps
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk) wa[kk] = *(const lds_bf16x8*)(uintptr_t)(st + arow + (((2 * kk + hh) ^ ax) << 4));
-        f32x16 cinit;
+        f32x16 acc[QG];  // accumulators start from the biases of this lane's sixteen rows
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) {
             const f32x4 b4 = *(const lds_f32x4*)(uintptr_t)(st + G::WT + wave * 256 + (8 * g4 + 4 * hh) * 4);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) cinit[4 * g4 + j] = b4[j];
+            for (int g = 0; g < QG; ++g)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[g][4 * g4 + j] = b4[j];
         }
-        const bool proj = t >= nrt;
 #pragma unroll
-        for (int g = 0; g < QG; ++g) {
-            f32x16 acc = cinit;
+        for (int kk = 0; kk < NKK; ++kk)
 #pragma unroll
-            for (int kk = 0; kk < NKK; ++kk) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[kk], sreg[g][kk], acc, 0, 0, 0);
-            if (!proj) {
-                if (t == nrt - 1 && (P & (TR - 1))) {
+            for (int g = 0; g < QG; ++g) acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[kk], sreg[g][kk], acc[g], 0, 0, 0);
+        if (KIND == 2) {
+            // projection: row c of the block is column c of the user slice
 #pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        if (t * TR + 8 * (r >> 2) + 4 * hh + (r & 3) >= P) acc[r] = -INFINITY;
-                }
-                float tmax = acc[0];
-#pragma unroll
-                for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, acc[r]);
-                if (__any(tmax > bv[g])) {
-                    int rr = 15;
-#pragma unroll
-                    for (int r = 14; r >= 0; --r) rr = acc[r] == tmax ? r : rr;
-                    if (tmax > bv[g]) {
-                        bv[g] = tmax;
-                        bj[g] = t * TR + 8 * (rr >> 2) + 4 * hh + (rr & 3);
-                    }
-                }
-            } else {
-                // projection tile: row c of the tile is column c of the user slice
+            for (int g = 0; g < QG; ++g) {
                 const int64_t pos = pos0 + g * 32 + qn;
                 if (pos < a.T) {
                     uint16_t* dst = (uint16_t*)a.user[side] + ((int64_t)h * a.T + pos) * d_u;
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int c = 8 * (r >> 2) + 4 * hh + (r & 3);
-                        if (c < d_u) dst[c] = f2bf(acc[r]);
+                        if (c < d_u) dst[c] = f2bf(acc[g][r]);
+                    }
+                }
+            }
+        } else {
+            const int j0 = t * TR;
+            float tmax[QG];
+#pragma unroll
+            for (int g = 0; g < QG; ++g) {
+                if (KIND == 1) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (j0 + 8 * (r >> 2) + 4 * hh + (r & 3) >= P) acc[g][r] = -INFINITY;
+                }
+                tmax[g] = acc[g][0];
+#pragma unroll
+                for (int r = 1; r < 16; ++r) tmax[g] = fmaxf(tmax[g], acc[g][r]);
+            }
+            // the entry that attains a new maximum is located only when some lane of the wavefront has one
+#pragma unroll
+            for (int g = 0; g < QG; ++g) {
+                if (__any(tmax[g] > bv[g])) {
+                    int rr = 15;
+#pragma unroll
+                    for (int r = 14; r >= 0; --r) rr = acc[g][r] == tmax[g] ? r : rr;
+                    if (tmax[g] > bv[g]) {
+                        bv[g] = tmax[g];
+                        bj[g] = j0 + 8 * (rr >> 2) + 4 * hh + (rr & 3);
                     }
                 }
             }
         }
-        wait_vm<2 * (G::NI + 1)>();
+        wait_vm<(NS - 2) * (G::NI + 1)>();
         lds_barrier();
-    }
-    wait_vm<0>();  // the repeated loads past the last tile must land before the workgroup gives its LDS back
+    };
+    static_assert(G::NSUB == 1, "one row block per stage");
+#pragma unroll
+    for (int i = 0; i < NS - 1; ++i) issue(i);
+    wait_vm<(NS - 2) * (G::NI + 1)>();
+    lds_barrier();
+    for (int t = 0; t < nfull; ++t) stage(std::integral_constant<int, 0>{}, t);
+    if (nrt > nfull) stage(std::integral_constant<int, 1>{}, nfull);
+    if (d_u > 0) stage(std::integral_constant<int, 2>{}, nrt);
+    wait_vm<0>();  // the repeated loads past the last stage must land before the workgroup gives its LDS back
 
     if (nrt > 0) {
 #pragma unroll
@@ -268,16 +320,16 @@ __global__ __launch_bounds__(256) void ckv_prefill_scalar_kernel(ckv_prefill_arg
     }
 }
 
-template <int DE, int NW, int QG>
+template <int DE, int NW, int QG, int TR, int NS, int WPE>
 hipError_t launch_mfma(const ckv_prefill_args& a, hipStream_t s) {
-    constexpr int lds = PGeo<DE, NW>::LDS;
-    static hipError_t prepared = hipFuncSetAttribute((const void*)ckv_prefill_mfma_kernel<DE, NW, QG>,
+    constexpr int lds = PGeo<DE, NW, TR, NS>::LDS;
+    static hipError_t prepared = hipFuncSetAttribute((const void*)ckv_prefill_mfma_kernel<DE, NW, QG, TR, NS, WPE>,
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (prepared != hipSuccess) return prepared;
     const int64_t per_wg = 32 * QG * NW;
     const int64_t blocks = (a.T + per_wg - 1) / per_wg * 2 * a.H;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((ckv_prefill_mfma_kernel<DE, NW, QG>), dim3((unsigned)blocks), dim3(NW * 64), lds, s, a);
+    hipLaunchKernelGGL((ckv_prefill_mfma_kernel<DE, NW, QG, TR, NS, WPE>), dim3((unsigned)blocks), dim3(NW * 64), lds, s, a);
     return hipGetLastError();
 }
 
@@ -295,9 +347,9 @@ const char* ckv_prefill_variant(int dtype, int d_e, int d_u) {
 hipError_t ckv_launch_prefill(const ckv_prefill_args& a, int dtype, hipStream_t s) {
     if (a.T == 0 || (a.P == 0 && a.d_u == 0)) return hipSuccess;
     if (ckv_prefill_mfma_supported(dtype, a.d_e, a.d_u)) {
-        if (a.d_e == 64) return launch_mfma<64, 4, 2>(a, s);
-        if (a.d_e == 128) return launch_mfma<128, 4, 2>(a, s);
-        return launch_mfma<256, 4, 1>(a, s);
+        if (a.d_e == 64) return launch_mfma<64, 4, 2, 32, 4, 3>(a, s);
+        if (a.d_e == 128) return launch_mfma<128, 4, 2, 32, 4, 3>(a, s);
+        return launch_mfma<256, 4, 1, 32, 4, 3>(a, s);
     }
     const int64_t total = a.T * a.H * 2;
     const int blocks = (int)((total + 255) / 256 < 65536 ? (total + 255) / 256 : 65536);
