@@ -11,7 +11,8 @@
  * Data as the paper states the problem, one record per user, users back to back:
  *   lengths[B]                 n of each user (history length), n >= 0
  *   idx_k, idx_v  [T][H]       I_k, I_v: 0-based pool row of position t, head h;  T = sum(lengths)
- *   user_k, user_v [T][H][d_u] K_u, V_u: the user-specific slices
+ *   user_k, user_v [T][H][d_u] K_u, V_u: the user-specific slices ([T][H][d_a] for a side that is
+ *                              not shared, see side_dims below)
  *   pool_k, pool_v [H][P][pool_ld]   P_k, P_v: one pool per head, d_g valid columns per row
  *   q   [B][H][Nq][d_a]        candidate queries, d_a = d_u + d_g
  *   out [B][H][Nq][d_a]        fp64
@@ -44,6 +45,22 @@ static double widen(const void *base, int64_t i, int dtype)
 static size_t elem_size(int dtype) { return dtype == ORACLE_F32 ? 4u : 2u; }
 
 /*
+ * Sharing only one side (ablation "sharing keys or values": CollectiveK shares only the keys,
+ * CollectiveV only the values).  share = 0: both sides are [user slice | pool row]; 1: only K is,
+ * V is the ordinary cache; 2: only V is.  The ordinary (unshared) side keeps all d_a columns per
+ * position in its user array and has no index and no pool: d_u' = d_a, d_g' = 0.
+ * side: 0 = K, 1 = V.
+ */
+enum { ORACLE_SHARE_KV = 0, ORACLE_SHARE_K = 1, ORACLE_SHARE_V = 2 };
+static void side_dims(int share, int side, int d_u, int d_g, int *du, int *dg)
+{
+    const int shared = share == ORACLE_SHARE_KV || (share == ORACLE_SHARE_K && side == 0) ||
+                       (share == ORACLE_SHARE_V && side == 1);
+    *du = shared ? d_u : d_u + d_g;
+    *dg = shared ? d_g : 0;
+}
+
+/*
  * Final K row (or V row) of one position and head, widened to fp64:
  *   row[0 : d_u]     = user slice          (user-specific dimensions come first)
  *   row[d_u : d_a]   = pool[h][index]      (collective part, gathered by the stored index)
@@ -66,7 +83,7 @@ static void final_row(double *row, const void *user, const void *pool, const int
  * all B users in order); rows of out that belong to other users are not touched.
  * Returns 0, or -1 on a bad argument (index outside [0,P), negative length, unknown mode).
  */
-int ckv_oracle_attend(int B, int H, int d_g, int d_u, int P, int Nq, int dtype, int mode,
+int ckv_oracle_attend(int B, int H, int d_g, int d_u, int P, int Nq, int dtype, int mode, int share,
                       double scale, int64_t pool_ld,
                       const int32_t *lengths, const int32_t *idx_k, const int32_t *idx_v,
                       const void *user_k, const void *user_v,
@@ -78,15 +95,22 @@ int ckv_oracle_attend(int B, int H, int d_g, int d_u, int P, int Nq, int dtype, 
         return -1;
     if (mode != ORACLE_SOFTMAX && mode != ORACLE_SILU_OVER_N)
         return -1;
+    if (share < 0 || share > 2)
+        return -1;
+    int duk, dgk, duv, dgv;
+    side_dims(share, 0, d_u, d_g, &duk, &dgk);
+    side_dims(share, 1, d_u, d_g, &duv, &dgv);
     int64_t *offset = (int64_t *)malloc(sizeof(int64_t) * (size_t)(B + 1));
     offset[0] = 0;
     for (int b = 0; b < B; ++b) {
         if (lengths[b] < 0) { free(offset); return -1; }
         offset[b + 1] = offset[b] + lengths[b];
     }
-    if (d_g > 0)
-        for (int64_t i = 0; i < offset[B] * H; ++i)
-            if (idx_k[i] < 0 || idx_k[i] >= P || idx_v[i] < 0 || idx_v[i] >= P) { free(offset); return -1; }
+    for (int64_t i = 0; i < offset[B] * H; ++i)
+        if ((dgk > 0 && (idx_k[i] < 0 || idx_k[i] >= P)) || (dgv > 0 && (idx_v[i] < 0 || idx_v[i] >= P))) {
+            free(offset);
+            return -1;
+        }
     if (!users) n_users = B;
 
     int bad = 0;
@@ -103,8 +127,8 @@ int ckv_oracle_attend(int B, int H, int d_g, int d_u, int P, int Nq, int dtype, 
             double *qv = (double *)malloc(sizeof(double) * (size_t)d_a);
             /* gather + concat: the user's final K and V, n x d_a */
             for (int i = 0; i < n; ++i) {
-                final_row(K + (int64_t)i * d_a, user_k, pool_k, idx_k, o + i, h, H, d_u, d_g, P, pool_ld, dtype);
-                final_row(V + (int64_t)i * d_a, user_v, pool_v, idx_v, o + i, h, H, d_u, d_g, P, pool_ld, dtype);
+                final_row(K + (int64_t)i * d_a, user_k, pool_k, idx_k, o + i, h, H, duk, dgk, P, pool_ld, dtype);
+                final_row(V + (int64_t)i * d_a, user_v, pool_v, idx_v, o + i, h, H, duv, dgv, P, pool_ld, dtype);
             }
             for (int j = 0; j < Nq; ++j) {
                 const int64_t qo = (((int64_t)b * H + h) * Nq + j) * d_a;
@@ -142,7 +166,7 @@ int ckv_oracle_attend(int B, int H, int d_g, int d_u, int P, int Nq, int dtype, 
  * The final K and V rows themselves, in the storage dtype, [T][H][d_a]: a byte-for-byte
  * copy of the user slice followed by the gathered pool row (no arithmetic).
  */
-int ckv_oracle_reconstruct(int H, int d_g, int d_u, int P, int dtype, int64_t pool_ld, int64_t T,
+int ckv_oracle_reconstruct(int H, int d_g, int d_u, int P, int dtype, int share, int64_t pool_ld, int64_t T,
                            const int32_t *idx_k, const int32_t *idx_v,
                            const void *user_k, const void *user_v,
                            const void *pool_k, const void *pool_v,
@@ -150,22 +174,27 @@ int ckv_oracle_reconstruct(int H, int d_g, int d_u, int P, int dtype, int64_t po
 {
     const size_t e = elem_size(dtype);
     const int d_a = d_u + d_g;
-    for (int64_t t = 0; t < T; ++t)
-        for (int h = 0; h < H; ++h) {
-            const int64_t ph = t * H + h;
-            if (d_g > 0 && (idx_k[ph] < 0 || idx_k[ph] >= P || idx_v[ph] < 0 || idx_v[ph] >= P))
-                return -1;
-            char *kd = (char *)k_full + (size_t)ph * d_a * e;
-            char *vd = (char *)v_full + (size_t)ph * d_a * e;
-            memcpy(kd, (const char *)user_k + (size_t)ph * d_u * e, (size_t)d_u * e);
-            memcpy(vd, (const char *)user_v + (size_t)ph * d_u * e, (size_t)d_u * e);
-            if (d_g > 0) {
-                memcpy(kd + (size_t)d_u * e,
-                       (const char *)pool_k + (((size_t)h * P + idx_k[ph]) * pool_ld) * e, (size_t)d_g * e);
-                memcpy(vd + (size_t)d_u * e,
-                       (const char *)pool_v + (((size_t)h * P + idx_v[ph]) * pool_ld) * e, (size_t)d_g * e);
+    if (share < 0 || share > 2)
+        return -1;
+    for (int side = 0; side < 2; ++side) {
+        int du, dg;
+        side_dims(share, side, d_u, d_g, &du, &dg);
+        const int32_t *idx = side == 0 ? idx_k : idx_v;
+        const char *user = (const char *)(side == 0 ? user_k : user_v);
+        const char *pool = (const char *)(side == 0 ? pool_k : pool_v);
+        char *full = (char *)(side == 0 ? k_full : v_full);
+        for (int64_t t = 0; t < T; ++t)
+            for (int h = 0; h < H; ++h) {
+                const int64_t ph = t * H + h;
+                char *dst = full + (size_t)ph * d_a * e;
+                memcpy(dst, user + (size_t)ph * du * e, (size_t)du * e);
+                if (dg > 0) {
+                    if (idx[ph] < 0 || idx[ph] >= P)
+                        return -1;
+                    memcpy(dst + (size_t)du * e, pool + (((size_t)h * P + idx[ph]) * pool_ld) * e, (size_t)dg * e);
+                }
             }
-        }
+    }
     return 0;
 }
 
@@ -175,16 +204,24 @@ int ckv_oracle_reconstruct(int H, int d_g, int d_u, int P, int dtype, int64_t po
  * the load is s*d_u + s).  Counts are per K and V together, over T positions and H heads.
  *   stored_elems = T*H*2*(d_u + 1)       full_elems = T*H*2*d_a
  *   stored_bytes = T*H*2*(d_u*e + index_bytes)   full_bytes = T*H*2*d_a*e
+ * With only one side shared the other side contributes its full d_a columns and no index.
  */
-void ckv_oracle_cache_size(int64_t T, int H, int d_g, int d_u, int dtype, int index_bytes,
+void ckv_oracle_cache_size(int64_t T, int H, int d_g, int d_u, int dtype, int index_bytes, int share,
                            int64_t *stored_elems, int64_t *full_elems,
                            int64_t *stored_bytes, int64_t *full_bytes)
 {
     const int64_t e = (int64_t)elem_size(dtype);
     const int64_t ph = T * H;
-    *stored_elems = ph * 2 * ((int64_t)d_u + 1);
+    *stored_elems = 0;
+    *stored_bytes = 0;
+    for (int side = 0; side < 2; ++side) {
+        int du, dg;
+        side_dims(share, side, d_u, d_g, &du, &dg);
+        /* a shared side stores its user slice and one index; an ordinary side stores d_a columns */
+        *stored_elems += ph * ((int64_t)du + (dg > 0 ? 1 : 0));
+        *stored_bytes += ph * ((int64_t)du * e + (dg > 0 ? index_bytes : 0));
+    }
     *full_elems = ph * 2 * ((int64_t)d_u + d_g);
-    *stored_bytes = ph * 2 * ((int64_t)d_u * e + index_bytes);
     *full_bytes = ph * 2 * ((int64_t)d_u + d_g) * e;
 }
 

@@ -74,28 +74,27 @@ static void project(double *dst, const double *s, const void *w, const float *b,
     }
 }
 
-/* What the prefill stage caches for T positions.  P may be 0 (no pool: indices are not
- * written) and d_u may be 0 (no user slices).  Returns 0, or -1 on a bad argument. */
-int ckv_oracle_prefill(int H, int d_e, int d_u, int P, int dtype, int64_t T, const void *S,
+/* What the prefill stage caches for T positions.  The two sides have their own sizes (sharing only
+ * keys or only values, ablation "sharing keys or values": the ordinary side has no router, P = 0,
+ * and all its d_a columns come from the projection): P_k, P_v pool entries and d_uk, d_uv
+ * projected columns.  P = 0: that side's indices are not written; d_u = 0: no user slice.
+ * user_k is [T][H][d_uk], user_v [T][H][d_uv].  Returns 0, or -1 on a bad argument. */
+int ckv_oracle_prefill(int H, int d_e, int d_uk, int d_uv, int P_k, int P_v, int dtype, int64_t T, const void *S,
                        const void *w_rk, const float *b_rk, const void *w_rv, const float *b_rv,
                        const void *w_k, const float *b_k, const void *w_v, const float *b_v,
                        int32_t *idx_k, int32_t *idx_v, double *user_k, double *user_v)
 {
-    if (H < 1 || d_e < 1 || d_u < 0 || P < 0 || T < 0 || (dtype != 0 && dtype != 1))
+    if (H < 1 || d_e < 1 || d_uk < 0 || d_uv < 0 || P_k < 0 || P_v < 0 || T < 0 || (dtype != 0 && dtype != 1))
         return -1;
 #pragma omp parallel for schedule(dynamic, 16)
     for (int64_t t = 0; t < T; ++t) {
         double *s = (double *)malloc(sizeof(double) * (size_t)d_e);
         for (int c = 0; c < d_e; ++c) s[c] = widen_p(S, t * d_e + c, dtype);
         for (int h = 0; h < H; ++h) {
-            if (P > 0) {
-                idx_k[t * H + h] = route(s, w_rk, b_rk, h, P, d_e, dtype);
-                idx_v[t * H + h] = route(s, w_rv, b_rv, h, P, d_e, dtype);
-            }
-            if (d_u > 0) {
-                project(user_k + (t * H + h) * (int64_t)d_u, s, w_k, b_k, h, d_u, d_e, dtype);
-                project(user_v + (t * H + h) * (int64_t)d_u, s, w_v, b_v, h, d_u, d_e, dtype);
-            }
+            if (P_k > 0) idx_k[t * H + h] = route(s, w_rk, b_rk, h, P_k, d_e, dtype);
+            if (P_v > 0) idx_v[t * H + h] = route(s, w_rv, b_rv, h, P_v, d_e, dtype);
+            if (d_uk > 0) project(user_k + (t * H + h) * (int64_t)d_uk, s, w_k, b_k, h, d_uk, d_e, dtype);
+            if (d_uv > 0) project(user_v + (t * H + h) * (int64_t)d_uv, s, w_v, b_v, h, d_uv, d_e, dtype);
         }
         free(s);
     }

@@ -34,14 +34,14 @@ def _load():
         lib = ctypes.CDLL(_LIB)
         vp, i32, i64, dbl = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_double
         lib.ckv_oracle_attend.restype = ctypes.c_int
-        lib.ckv_oracle_attend.argtypes = [i32] * 8 + [dbl, i64] + [vp] * 9 + [vp, i32]
+        lib.ckv_oracle_attend.argtypes = [i32] * 9 + [dbl, i64] + [vp] * 9 + [vp, i32]
         lib.ckv_oracle_reconstruct.restype = ctypes.c_int
-        lib.ckv_oracle_reconstruct.argtypes = [i32] * 5 + [i64, i64] + [vp] * 8
+        lib.ckv_oracle_reconstruct.argtypes = [i32] * 6 + [i64, i64] + [vp] * 8
         lib.ckv_oracle_cache_size.restype = None
-        lib.ckv_oracle_cache_size.argtypes = [i64, i32, i32, i32, i32, i32] + [vp] * 4
+        lib.ckv_oracle_cache_size.argtypes = [i64, i32, i32, i32, i32, i32, i32] + [vp] * 4
         lib.ckv_oracle_threads.restype = ctypes.c_int
         lib.ckv_oracle_prefill.restype = ctypes.c_int
-        lib.ckv_oracle_prefill.argtypes = [i32] * 5 + [i64] + [vp] * 13
+        lib.ckv_oracle_prefill.argtypes = [i32] * 7 + [i64] + [vp] * 13
         lib.ckv_oracle_router_gap.restype = ctypes.c_int
         lib.ckv_oracle_router_gap.argtypes = [i32] * 4 + [i64] + [vp] * 6
         _lib = lib
@@ -80,7 +80,7 @@ def attend(w, users=None):
         ulist = np.ascontiguousarray(users, dtype=np.int32)
         uptr, nu = _ptr(ulist), len(ulist)
     rc = lib.ckv_oracle_attend(
-        w["B"], w["H"], w["d_g"], w["d_u"], w["P"], w["Nq"], dt, w["mode"],
+        w["B"], w["H"], w["d_g"], w["d_u"], w["P"], w["Nq"], dt, w["mode"], int(w.get("share", 0)),
         float(w["scale"]), int(w["pool_ld"]),
         _ptr(lengths), _ptr(idx_k), _ptr(idx_v), *[_ptr(a) for a in arrs], _ptr(out), uptr, nu)
     if rc != 0:
@@ -101,23 +101,33 @@ def reconstruct(w):
     idx_v = np.ascontiguousarray(w["idx_v"], dtype=np.int32)
     arrs = [_check_store(w[k], dt, k) for k in ("user_k", "user_v", "pool_k", "pool_v")]
     rc = lib.ckv_oracle_reconstruct(
-        w["H"], w["d_g"], w["d_u"], w["P"], dt, int(w["pool_ld"]), T,
+        w["H"], w["d_g"], w["d_u"], w["P"], dt, int(w.get("share", 0)), int(w["pool_ld"]), T,
         _ptr(idx_k), _ptr(idx_v), *[_ptr(a) for a in arrs], _ptr(k_full), _ptr(v_full))
     if rc != 0:
         raise ValueError("ckv_oracle_reconstruct rejected its arguments")
     return k_full, v_full
 
 
-def cache_size(T, H, d_g, d_u, dtype, index_bytes=4):
-    """(stored_elems, full_elems, stored_bytes, full_bytes) of a CollectiveKV cache."""
+def cache_size(T, H, d_g, d_u, dtype, index_bytes=4, share=0):
+    """(stored_elems, full_elems, stored_bytes, full_bytes) of a CollectiveKV cache (share: 0 both sides
+    shared, 1 only K, 2 only V)."""
     lib = _load()
     vals = [ctypes.c_int64(0) for _ in range(4)]
-    lib.ckv_oracle_cache_size(int(T), H, d_g, d_u, dtype, index_bytes, *[ctypes.byref(v) for v in vals])
+    lib.ckv_oracle_cache_size(int(T), H, d_g, d_u, dtype, index_bytes, share, *[ctypes.byref(v) for v in vals])
     return tuple(int(v.value) for v in vals)
 
 
 def threads():
     return int(_load().ckv_oracle_threads())
+
+
+def prefill_side_dims(r):
+    """(d_uk, d_uv, P_k, P_v) of a prefill workload: an unshared side projects all d_a columns and has no router."""
+    share = r.get("share", 0)
+    d_u, P = r["d_u"], r["P"]
+    d_uk, P_k = (d_u, P) if share in (0, 1) else (r["d_a"], 0)
+    d_uv, P_v = (d_u, P) if share in (0, 2) else (r["d_a"], 0)
+    return d_uk, d_uv, P_k, P_v
 
 
 def _prefill_arrays(r):
@@ -132,15 +142,18 @@ def prefill(r):
 
     `r` is a prefill workload dict as made by the seeded generators: keys H, d_e, d_u, P, dtype,
     S [T][d_e], w_rk, w_rv [H][P][d_e], b_rk, b_rv [H][P], w_k, w_v [H][d_u][d_e], b_k, b_v [H][d_u].
+    With r["share"] = 1 (2) only the key (value) side is shared: the other side has no router and its
+    projection has r["d_a"] rows.
     """
     lib = _load()
     (S, w_rk, w_rv, w_k, w_v), (b_rk, b_rv, b_k, b_v) = _prefill_arrays(r)
-    T, H, d_u = S.shape[0], r["H"], r["d_u"]
+    T, H = S.shape[0], r["H"]
+    d_uk, d_uv, P_k, P_v = prefill_side_dims(r)
     idx_k = np.zeros((T, H), dtype=np.int32)
     idx_v = np.zeros((T, H), dtype=np.int32)
-    user_k = np.zeros((T, H, d_u), dtype=np.float64)
-    user_v = np.zeros((T, H, d_u), dtype=np.float64)
-    rc = lib.ckv_oracle_prefill(H, r["d_e"], d_u, r["P"], r["dtype"], T, _ptr(S), _ptr(w_rk), _ptr(b_rk), _ptr(w_rv),
+    user_k = np.zeros((T, H, d_uk), dtype=np.float64)
+    user_v = np.zeros((T, H, d_uv), dtype=np.float64)
+    rc = lib.ckv_oracle_prefill(H, r["d_e"], d_uk, d_uv, P_k, P_v, r["dtype"], T, _ptr(S), _ptr(w_rk), _ptr(b_rk), _ptr(w_rv),
                                 _ptr(b_rv), _ptr(w_k), _ptr(b_k), _ptr(w_v), _ptr(b_v), _ptr(idx_k), _ptr(idx_v),
                                 _ptr(user_k), _ptr(user_v))
     if rc != 0:

@@ -6,6 +6,7 @@ distributions, drawn from a counter-based generator (Philox) keyed by `seed`.
 
 A workload is a plain dict:
   B, H, d_g, d_u, P, Nq, pool_ld : ints          dtype : 0 fp32 | 1 bf16     mode : 0 softmax | 1 SiLU/n
+  share : 0 keys and values shared | 1 only keys | 2 only values
   scale : float
   lengths [B] int32                               history length n of every user
   idx_k, idx_v   [T][H] int32                     pool row per position and head (user-major, ragged)
@@ -19,6 +20,15 @@ import numpy as np
 
 F32, BF16 = 0, 1
 SOFTMAX, SILU_OVER_N = 0, 1
+SHARE_KV, SHARE_K, SHARE_V = 0, 1, 2   # both sides shared (CollectiveKV), only keys (CollectiveK), only values (CollectiveV)
+
+
+def side_dims(d_u, d_g, share):
+    """((d_u, d_g) of the K side, (d_u, d_g) of the V side): a side that is not shared is the ordinary cache,
+    all d_a columns stored per position and no pool."""
+    full = (d_u + d_g, 0)
+    return ((d_u, d_g) if share in (SHARE_KV, SHARE_K) else full,
+            (d_u, d_g) if share in (SHARE_KV, SHARE_V) else full)
 
 # name -> recipe.  L = (lo, hi) inclusive, uniform per user.  sigma_* are standard deviations.
 CONFIGS = {
@@ -85,9 +95,12 @@ def _draw_idx(rng, kind, P, shape, perm_rng):
 
 
 def make(B, L, H, d_a, d_u, P, idx, Nq, mode, dtype, sigma_pool, seed,
-         sigma_user=0.1, sigma_q=1.0, pool_ld=None, scale=None, lengths=None, pad_nan=True):
-    """Build one workload dict from a recipe (see CONFIGS)."""
+         sigma_user=0.1, sigma_q=1.0, pool_ld=None, scale=None, lengths=None, pad_nan=True, share=SHARE_KV):
+    """Build one workload dict from a recipe (see CONFIGS).  share: SHARE_K / SHARE_V give the ablation
+    variants that share only keys / only values; the other side's user array then has d_a columns (drawn
+    like pool entries) and its indices are zeros that nothing reads."""
     d_g = d_a - d_u
+    (d_uk, d_gk), (d_uv, d_gv) = side_dims(d_u, d_g, share)
     if pool_ld is None:
         pool_ld = d_a if d_g > 0 else 0
     if lengths is None:
@@ -97,15 +110,11 @@ def make(B, L, H, d_a, d_u, P, idx, Nq, mode, dtype, sigma_pool, seed,
     assert lengths.shape == (B,)
     T = int(lengths.sum())
     P_eff = max(P, 1)
-    if d_g > 0:
-        perm_rng = _rng(seed, 9)
-        idx_k = _draw_idx(_rng(seed, 1), idx, P_eff, (T, H), perm_rng)
-        idx_v = _draw_idx(_rng(seed, 2), idx, P_eff, (T, H), perm_rng)
-    else:
-        idx_k = np.zeros((T, H), dtype=np.int32)
-        idx_v = np.zeros((T, H), dtype=np.int32)
-    user_k = _normal(_rng(seed, 3), (T, H, d_u), sigma_user, dtype)
-    user_v = _normal(_rng(seed, 4), (T, H, d_u), sigma_user, dtype)
+    perm_rng = _rng(seed, 9)
+    idx_k = _draw_idx(_rng(seed, 1), idx, P_eff, (T, H), perm_rng) if d_gk > 0 else np.zeros((T, H), dtype=np.int32)
+    idx_v = _draw_idx(_rng(seed, 2), idx, P_eff, (T, H), perm_rng) if d_gv > 0 else np.zeros((T, H), dtype=np.int32)
+    user_k = _normal(_rng(seed, 3), (T, H, d_uk), sigma_user if d_gk > 0 or d_g == 0 else sigma_pool, dtype)
+    user_v = _normal(_rng(seed, 4), (T, H, d_uv), sigma_user if d_gv > 0 or d_g == 0 else sigma_pool, dtype)
     pool_k = _normal(_rng(seed, 5), (H, P_eff, pool_ld), sigma_pool, dtype)
     pool_v = _normal(_rng(seed, 6), (H, P_eff, pool_ld), sigma_pool, dtype)
     if pad_nan and pool_ld > d_g:
@@ -116,7 +125,7 @@ def make(B, L, H, d_a, d_u, P, idx, Nq, mode, dtype, sigma_pool, seed,
     if scale is None:
         scale = d_a ** -0.5 if mode == SOFTMAX else 1.0
     return dict(B=B, H=H, d_g=d_g, d_u=d_u, P=P_eff, Nq=Nq, pool_ld=int(pool_ld), dtype=dtype,
-                mode=mode, scale=float(scale), lengths=lengths, idx_k=idx_k, idx_v=idx_v,
+                mode=mode, share=share, scale=float(scale), lengths=lengths, idx_k=idx_k, idx_v=idx_v,
                 user_k=user_k, user_v=user_v, pool_k=pool_k, pool_v=pool_v, q=q)
 
 
@@ -134,21 +143,28 @@ def algorithmic_bytes(w):
     e = 4 if w["dtype"] == F32 else 2
     ph = int(np.sum(w["lengths"], dtype=np.int64)) * w["H"]
     d_a = w["d_g"] + w["d_u"]
-    compressed = ph * (8 + 2 * w["d_u"] * e)
-    gathered = ph * 2 * w["d_g"] * e
+    sides = side_dims(w["d_u"], w["d_g"], w.get("share", SHARE_KV))
+    compressed = ph * sum((4 if dg > 0 else 0) + du * e for du, dg in sides)
+    gathered = ph * sum(dg * e for _, dg in sides)
     q_out = 2 * w["B"] * w["H"] * w["Nq"] * d_a * e
     return dict(position_heads=ph, compressed=compressed, gathered=gathered, q_out=q_out,
                 E=compressed + gathered + q_out)
 
 
-def make_prefill(T, H, d_e, d_u, P, dtype, seed, sigma_s=1.0, sigma_b=0.1, integers=None):
+def make_prefill(T, H, d_e, d_u, P, dtype, seed, sigma_s=1.0, sigma_b=0.1, integers=None, share=SHARE_KV, d_a=None):
     """Inputs of the prefill stage (section 4.2 / 4.3): history embedding S [T][d_e] shared by the heads,
     per-head router weights w_rk, w_rv [H][P][d_e] (row j = column j of the paper's W_r) with fp32 bias
     b_rk, b_rv [H][P], per-head projection weights w_k, w_v [H][d_u][d_e] with fp32 bias b_k, b_v [H][d_u].
     Weights are N(0, 1/sqrt(d_e)), S is N(0, sigma_s), biases N(0, sigma_b).  With integers=m every value is
     a uniform integer in [-m, m]: all sums are then exact in fp32, so equal routing scores (ties) are common
-    and every implementation must agree bit for bit.  They stand in for trained embeddings and routers."""
+    and every implementation must agree bit for bit.  They stand in for trained embeddings and routers.
+    share = SHARE_K / SHARE_V (needs d_a): the side that is not shared projects all d_a columns (w_v or w_k has
+    d_a rows) and its router is not used."""
     P_eff = max(P, 1)
+    if share != SHARE_KV:
+        assert d_a is not None and d_a >= d_u
+    d_uk = d_u if share in (SHARE_KV, SHARE_K) else d_a
+    d_uv = d_u if share in (SHARE_KV, SHARE_V) else d_a
 
     def draw(stream, shape, sigma, dt):
         rng = _rng(seed, stream)
@@ -158,12 +174,12 @@ def make_prefill(T, H, d_e, d_u, P, dtype, seed, sigma_s=1.0, sigma_b=0.1, integ
         return _normal(rng, shape, sigma, dt)
 
     sw = d_e ** -0.5
-    return dict(H=H, d_e=d_e, d_u=d_u, P=P_eff, dtype=dtype, T=T,
+    return dict(H=H, d_e=d_e, d_u=d_u, P=P_eff, dtype=dtype, T=T, share=share, d_a=d_a,
                 S=draw(20, (T, d_e), sigma_s, dtype),
                 w_rk=draw(21, (H, P_eff, d_e), sw, dtype), w_rv=draw(22, (H, P_eff, d_e), sw, dtype),
                 b_rk=draw(23, (H, P_eff), sigma_b, F32), b_rv=draw(24, (H, P_eff), sigma_b, F32),
-                w_k=draw(25, (H, d_u, d_e), sw, dtype), w_v=draw(26, (H, d_u, d_e), sw, dtype),
-                b_k=draw(27, (H, d_u), sigma_b, F32), b_v=draw(28, (H, d_u), sigma_b, F32))
+                w_k=draw(25, (H, d_uk, d_e), sw, dtype), w_v=draw(26, (H, d_uv, d_e), sw, dtype),
+                b_k=draw(27, (H, d_uk), sigma_b, F32), b_v=draw(28, (H, d_uv), sigma_b, F32))
 
 
 # Prefill workloads: the cache shapes of configs 2 and 3 (T positions, heads, d_u, pool size), an embedding

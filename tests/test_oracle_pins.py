@@ -282,3 +282,67 @@ def test_compression_rate_of_the_workloads(name, byte_cr, elem_cr):
     se, fe, sb, fb = oracle.cache_size(T=12345, H=r["H"], d_g=r["d_a"] - r["d_u"], d_u=r["d_u"], dtype=r["dtype"])
     assert se / fe == elem_cr
     assert sb / fb == byte_cr
+
+
+# ---------------------------------------------------------------------------------------------
+# sharing only keys or only values (ablation "sharing keys or values": CollectiveK, CollectiveV)
+def dense_kv_shared(w):
+    """Explicit final K, V per (user, head): a shared side is cat(user slice, pool[index]); a side that is
+    not shared is its own d_a-wide array, untouched."""
+    dt = w["dtype"]
+    (d_uk, d_gk), (d_uv, d_gv) = wl.side_dims(w["d_u"], w["d_g"], w["share"])
+    uk, uv = (torch.from_numpy(wl.to_f64(w[k], dt)) for k in ("user_k", "user_v"))
+    pk, pv = (torch.from_numpy(wl.to_f64(w[k], dt)) for k in ("pool_k", "pool_v"))
+    ik, iv = (torch.from_numpy(w[k].astype(np.int64)) for k in ("idx_k", "idx_v"))
+    off = np.concatenate([[0], np.cumsum(w["lengths"])])
+    for b in range(w["B"]):
+        for h in range(w["H"]):
+            s = slice(int(off[b]), int(off[b + 1]))
+            K = torch.cat([uk[s, h, :], pk[h][ik[s, h]][:, :d_gk]], dim=1) if d_gk else uk[s, h, :]
+            V = torch.cat([uv[s, h, :], pv[h][iv[s, h]][:, :d_gv]], dim=1) if d_gv else uv[s, h, :]
+            yield b, h, K, V
+
+
+@pytest.mark.parametrize("share", [wl.SHARE_K, wl.SHARE_V])
+@pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
+def test_single_side_sharing_matches_library_attention(share, mode):
+    w = small(dtype=wl.BF16, mode=mode, share=share)
+    assert w["user_k"].shape[2] == (3 if share == wl.SHARE_K else 16)
+    assert w["user_v"].shape[2] == (16 if share == wl.SHARE_K else 3)
+    q = torch.from_numpy(wl.to_f64(w["q"], w["dtype"]))
+    ref = torch.zeros_like(q)
+    for b, h, K, V in dense_kv_shared(w):
+        assert K.shape[1] == 16 and V.shape[1] == 16
+        if K.shape[0] == 0:
+            continue
+        if mode == wl.SOFTMAX:
+            ref[b, h] = torch.nn.functional.scaled_dot_product_attention(q[b, h][None], K[None], V[None], scale=w["scale"])[0]
+        else:
+            ref[b, h] = torch.nn.functional.silu(w["scale"] * q[b, h] @ K.T) @ V / K.shape[0]
+    np.testing.assert_allclose(oracle.attend(w), ref.numpy(), rtol=1e-11, atol=1e-13)
+
+
+def test_unshared_side_fed_with_reconstructed_rows_gives_the_shared_result():
+    """A cache that shares both sides, and the same cache with its V rows (or K rows) materialised and handed
+    over as an ordinary cache, are the same attention problem."""
+    w = small(dtype=wl.F32)
+    ref = oracle.attend(w)
+    k_full, v_full = oracle.reconstruct(w)
+    wk = dict(w, share=wl.SHARE_K, user_v=v_full)
+    wv = dict(w, share=wl.SHARE_V, user_k=k_full)
+    np.testing.assert_array_equal(oracle.attend(wk), ref)
+    np.testing.assert_array_equal(oracle.attend(wv), ref)
+    for w2 in (wk, wv):
+        k2, v2 = oracle.reconstruct(w2)
+        np.testing.assert_array_equal(k2, k_full)
+        np.testing.assert_array_equal(v2, v_full)
+
+
+def test_cache_size_with_one_side_shared():
+    # the shared side stores d_u + 1 elements per position, the ordinary side d_a
+    se, fe, sb, fb = oracle.cache_size(T=100, H=2, d_g=56, d_u=8, dtype=oracle.BF16, share=wl.SHARE_K)
+    assert (se, fe) == (100 * 2 * (8 + 1 + 64), 100 * 2 * 128)
+    assert (sb, fb) == (100 * 2 * (8 * 2 + 4 + 64 * 2), 100 * 2 * 128 * 2)
+    assert oracle.cache_size(T=100, H=2, d_g=56, d_u=8, dtype=oracle.BF16, share=wl.SHARE_V) == (se, fe, sb, fb)
+    both = oracle.cache_size(T=100, H=2, d_g=56, d_u=8, dtype=oracle.BF16)
+    assert both[0] == 100 * 2 * 2 * 9 and both[0] < se

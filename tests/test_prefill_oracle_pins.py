@@ -162,3 +162,19 @@ def test_prefill_then_decode_is_dense_attention_over_projected_and_routed_rows()
             p = np.exp(sc - sc.max(axis=1, keepdims=True))
             ref = (p / p.sum(axis=1, keepdims=True)) @ V
             np.testing.assert_allclose(out[b, h], ref, rtol=1e-10, atol=1e-12)
+
+
+@pytest.mark.parametrize("share", [wl.SHARE_K, wl.SHARE_V])
+def test_prefill_with_one_side_shared(share):
+    """The side that is not shared has no router; all its d_a columns are the projection."""
+    r = wl.make_prefill(T=40, H=2, d_e=12, d_u=3, P=21, dtype=wl.F32, seed=14, share=share, d_a=10)
+    ik, iv, uk, uv = oracle.prefill(r)
+    S = f64(r, "S")
+    shared, plain = (("k", ik, uk), ("v", iv, uv)) if share == wl.SHARE_K else (("v", iv, uv), ("k", ik, uk))
+    assert shared[2].shape == (40, 2, 3) and plain[2].shape == (40, 2, 10)
+    assert (plain[1] == 0).all()
+    for h in range(2):
+        M = S @ f64(r, "w_r" + shared[0])[h].T + r["b_r" + shared[0]][h]
+        np.testing.assert_array_equal(shared[1][:, h], M.argmax(axis=1))
+        for side, _, u in (shared, plain):
+            np.testing.assert_allclose(u[:, h, :], S @ f64(r, "w_" + side)[h].T + r["b_" + side][h], rtol=1e-12, atol=1e-12)
