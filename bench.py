@@ -32,6 +32,8 @@ DESCRIBE = {
     "cfg2_f32": "config 2 SASRec-like: B=1024 L=200 H=2 d=56+8 P=4096 Nq=1 softmax fp32",
     "cfg2_bf16": "config 2 SASRec-like: B=1024 L=200 H=2 d=56+8 P=4096 Nq=1 softmax bf16",
     "cfg3": "config 3 HSTU-style: B=512 L=1024 H=4 d=60+4 P=16384 Zipf(1.1) Nq=64 SiLU/L bf16",
+    "cfg3_ck": "config 3 with only the keys shared (CollectiveK): V is an ordinary 64-column cache",
+    "cfg3_cv": "config 3 with only the values shared (CollectiveV): K is an ordinary 64-column cache",
     "cfg4": "config 4 long ragged: B=128 L~U[2048,8192] H=8 d=120+8 P=65536 Nq=128 softmax bf16",
     "cfg5": "config 5 large batch: B=8192 L~U[512,2048] H=4 d=62+2 P=1048576 Zipf(1.05) Nq=16 softmax bf16",
 }
@@ -41,8 +43,9 @@ def compulsory_bytes(w, ab):
     """Compressed stream + every distinct touched pool row once + q + out."""
     e = 4 if w["dtype"] == 0 else 2
     rows = 0
+    share = w.get("share", 0)
     for h in range(w["H"]):
-        rows += len(np.unique(w["idx_k"][:, h])) + len(np.unique(w["idx_v"][:, h]))
+        rows += (len(np.unique(w["idx_k"][:, h])) if share in (0, 1) else 0) + (len(np.unique(w["idx_v"][:, h])) if share in (0, 2) else 0)
     return ab["compressed"] + rows * w["d_g"] * e + ab["q_out"]
 
 
@@ -205,7 +208,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=100,
                     help="untimed steps; the GPU needs ~50 back-to-back launches to reach its steady clocks")
     ap.add_argument("--workload", default="cfg4", choices=sorted(DESCRIBE))
-    ap.add_argument("--also", default="cfg2_f32,cfg2_bf16,cfg3", help="comma list of further workloads ('' for none)")
+    ap.add_argument("--also", default="cfg2_f32,cfg2_bf16,cfg3,cfg3_ck", help="comma list of further workloads ('' for none)")
     ap.add_argument("--prefill", default="prefill_cfg2",
                     help="comma list of prefill workloads reported under 'prefill' (prefill_cfg2, prefill_cfg3; '' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")

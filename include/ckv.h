@@ -37,6 +37,11 @@ extern "C" {
 
 enum { CKV_F32 = 0, CKV_BF16 = 1 };
 enum { CKV_SOFTMAX = 0, CKV_SILU_OVER_N = 1 };
+/* Which sides gather from a pool (ablation "sharing keys or values"): both (CollectiveKV), only the
+ * keys (CollectiveK) or only the values (CollectiveV).  A side that is not shared is the ordinary
+ * cache: its user array holds all d_a columns of every position (d_u' = d_a, d_g' = 0), and its
+ * index plane, pool and router are never read. */
+enum { CKV_SHARE_KV = 0, CKV_SHARE_K = 1, CKV_SHARE_V = 2 };
 
 enum {
     CKV_OK = 0,
@@ -61,7 +66,7 @@ typedef struct ckv_shape {
     int32_t dtype;   /* CKV_F32 | CKV_BF16 */
     int32_t mode;    /* CKV_SOFTMAX | CKV_SILU_OVER_N */
     float scale;
-    int32_t reserved; /* must be 0 */
+    int32_t share;   /* CKV_SHARE_KV (0) | CKV_SHARE_K | CKV_SHARE_V */
     int64_t pool_ld;
 } ckv_shape;
 
@@ -81,6 +86,8 @@ typedef struct ckv_cache ckv_cache;
  *             head h, 0-based, each in [0, P).  Ignored (may be NULL) when d_g == 0.
  *   user_k,
  *   user_v    host [T][H][d_u] in shape->dtype.  Ignored (may be NULL) when d_u == 0.
+ *             With share = CKV_SHARE_K, user_v is [T][H][d_a] and idx_v is ignored (may be NULL);
+ *             with CKV_SHARE_V the same holds for user_k and idx_k.
  *   out       receives the handle.
  *   stream    uploads and the packing kernel run on this stream; the call synchronises it
  *             before returning (it has to read back the index check).
@@ -124,6 +131,8 @@ int ckv_cache_is_offloaded(const ckv_cache* c);
  * w_k[h] is column c of W_k.  Biases are always float.
  *   w_rk, w_rv  [H][P][d_e]    b_rk, b_rv  [H][P]       (ignored when d_g == 0)
  *   w_k,  w_v   [H][d_u][d_e]  b_k,  b_v   [H][d_u]     (ignored when d_u == 0)
+ * For a side that is not shared (shape->share) the router is ignored and the projection has d_a
+ * rows: w_v [H][d_a][d_e], b_v [H][d_a] with CKV_SHARE_K, likewise w_k, b_k with CKV_SHARE_V.
  * Arithmetic: products of the stored values accumulated in fp32, bias added in fp32; user slices
  * are rounded to shape->dtype (nearest even).  Of equal routing scores the lowest pool entry
  * wins.  Scores that differ by less than the fp32 rounding of their sums may resolve either way;
@@ -134,8 +143,8 @@ int ckv_cache_is_offloaded(const ckv_cache* c);
  * launch metadata and synchronises the stream before returning.  ckv_prefill_into recomputes the
  * packed cache of an existing, device-resident handle (same shape and lengths) from new S or
  * weights: no allocation, no synchronisation.  ckv_prefill_kernel_name names the kernel the pair
- * (shape, router) dispatches to: a matrix-core kernel for bf16 with d_e of 64, 128 or 256 and
- * d_u <= 32, a scalar kernel otherwise.
+ * (shape, router) dispatches to: a matrix-core kernel for bf16 with d_e of 64, 128 or 256, a
+ * scalar kernel otherwise.
  * Errors: CKV_ERR_NULL, _SHAPE, _LENGTH, _UNSUPPORTED (pointer not 16-byte aligned), _HIP.
  */
 typedef struct ckv_router {
@@ -157,8 +166,8 @@ const char* ckv_prefill_kernel_name(const ckv_shape* shape, const ckv_router* ro
 
 /* Borrowed device views of the packed cache; valid until ckv_free. */
 const int32_t* ckv_cache_idx(const ckv_cache* c);     /* device int32 [2][H][T]        */
-const void* ckv_cache_user_k(const ckv_cache* c);     /* device [H][T][d_u]            */
-const void* ckv_cache_user_v(const ckv_cache* c);     /* device [H][T][d_u]            */
+const void* ckv_cache_user_k(const ckv_cache* c);     /* device [H][T][d_u] ([H][T][d_a] if K is not shared) */
+const void* ckv_cache_user_v(const ckv_cache* c);     /* device [H][T][d_u] ([H][T][d_a] if V is not shared) */
 const int32_t* ckv_cache_lengths(const ckv_cache* c); /* device int32 [B]              */
 int64_t ckv_cache_positions(const ckv_cache* c);      /* T                             */
 /* Bytes of the stored cache (indices + user slices; the quantity whose ratio to the full

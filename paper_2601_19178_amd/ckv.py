@@ -16,6 +16,7 @@ _LIBPATH = os.path.join(_HERE, "libckv.so")
 
 CKV_F32, CKV_BF16 = 0, 1
 CKV_SOFTMAX, CKV_SILU_OVER_N = 0, 1
+CKV_SHARE_KV, CKV_SHARE_K, CKV_SHARE_V = 0, 1, 2
 CKV_OK, CKV_ERR_NULL, CKV_ERR_SHAPE, CKV_ERR_INDEX, CKV_ERR_LENGTH, CKV_ERR_UNSUPPORTED, CKV_ERR_HIP = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = [
@@ -29,7 +30,7 @@ EXPORTS = [
 class ckv_shape(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("d_g", ctypes.c_int32), ("d_u", ctypes.c_int32),
                 ("P", ctypes.c_int32), ("Nq", ctypes.c_int32), ("dtype", ctypes.c_int32), ("mode", ctypes.c_int32),
-                ("scale", ctypes.c_float), ("reserved", ctypes.c_int32), ("pool_ld", ctypes.c_int64)]
+                ("scale", ctypes.c_float), ("share", ctypes.c_int32), ("pool_ld", ctypes.c_int64)]
 
 
 class ckv_router(ctypes.Structure):
@@ -115,8 +116,8 @@ def ckv_last_error():
     return _lib.ckv_last_error().decode()
 
 
-def make_shape(B, H, d_g, d_u, P, Nq, dtype, mode, scale, pool_ld):
-    return ckv_shape(B, H, d_g, d_u, P, Nq, dtype, mode, scale, 0, pool_ld)
+def make_shape(B, H, d_g, d_u, P, Nq, dtype, mode, scale, pool_ld, share=CKV_SHARE_KV):
+    return ckv_shape(B, H, d_g, d_u, P, Nq, dtype, mode, scale, share, pool_ld)
 
 
 def ckv_build_cache(shape, lengths, idx_k, idx_v, user_k, user_v, stream=0):

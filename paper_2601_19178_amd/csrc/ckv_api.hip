@@ -40,7 +40,7 @@ template <typename U>
 __global__ void ckv_pack_kernel(const int32_t* __restrict__ in_k, const int32_t* __restrict__ in_v,
                                 const U* __restrict__ in_uk, const U* __restrict__ in_uv,
                                 int32_t* __restrict__ idx, U* __restrict__ uk, U* __restrict__ uv,
-                                int64_t T, int H, int d_u, int P, int has_pool,
+                                int64_t T, int H, int d_uk, int d_uv, int P, int pool_k, int pool_v,
                                 unsigned long long* __restrict__ bad) {
     const int64_t total = T * H;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
@@ -48,16 +48,14 @@ __global__ void ckv_pack_kernel(const int32_t* __restrict__ in_k, const int32_t*
         const int64_t t = i / H;
         const int h = (int)(i - t * H);
         const int64_t o = (int64_t)h * T + t;
-        if (has_pool) {
-            const int32_t a = in_k[i], b = in_v[i];
+        if (idx) {  // a plane whose side has no pool is filled with zeros and never read
+            const int32_t a = pool_k ? in_k[i] : 0, b = pool_v ? in_v[i] : 0;
             if (a < 0 || a >= P || b < 0 || b >= P) atomicMin(bad, (unsigned long long)i);
             idx[o] = a;
             idx[(int64_t)H * T + o] = b;
         }
-        for (int c = 0; c < d_u; ++c) {
-            uk[o * d_u + c] = in_uk[i * d_u + c];
-            uv[o * d_u + c] = in_uv[i * d_u + c];
-        }
+        for (int c = 0; c < d_uk; ++c) uk[o * d_uk + c] = in_uk[i * d_uk + c];
+        for (int c = 0; c < d_uv; ++c) uv[o * d_uv + c] = in_uv[i * d_uv + c];
     }
 }
 
@@ -152,7 +150,7 @@ int pick_stream_vec(const ckv_shape& s) {
     int best = 1, best_ncb = (d_a + 15) / 16;
     for (int v : {4, 8}) {
         if (v == 8 && s.dtype == CKV_F32) continue;
-        if (s.d_u % v || s.d_g % v || (s.d_g > 0 && s.pool_ld % v)) continue;
+        if (s.d_u % v || s.d_g % v || (s.d_g > 0 && s.pool_ld % v)) continue;  // (d_a = d_u + d_g is then a multiple too)
         const int ncb = (d_a + 16 * v - 1) / (16 * v);
         if (ncb < best_ncb) {
             best = v;
@@ -463,7 +461,7 @@ void choose_variant(ckv_cache* c) {
             // wavefronts per SIMD overlap better than one wavefront with two query groups)
             int nw = s.Nq <= 32 ? 1 : (s.Nq <= 64 ? 2 : 4), qg = 1;
             if (const char* shp = getenv("CKV_DMA_SHAPE")) sscanf(shp, "%d,%d", &nw, &qg);  // tuning knob "nw,qg"
-            const int nui = s.d_g > 0 && ckv_dma_supported(d_a, nw, qg) ? ckv_dma_nui(d_a, nw, s.d_u) : -1;
+            const int nui = s.d_g > 0 && s.share == CKV_SHARE_KV && ckv_dma_supported(d_a, nw, qg) ? ckv_dma_nui(d_a, nw, s.d_u) : -1;
             if (nui >= 0 && !(impl && strcmp(impl, "staged") == 0)) {
                 c->family = CKV_K_DMA;
                 c->nw = nw;
@@ -542,9 +540,11 @@ static int cache_new(const char* who, const ckv_shape* shape, const int32_t* len
                      ckv_cache** out, std::vector<int64_t>& offs, hipDeviceProp_t* prop) {
     const ckv_shape s = *shape;
     const int64_t d_a = (int64_t)s.d_g + s.d_u;
-    if (s.B < 1 || s.H < 1 || s.d_g < 0 || s.d_u < 0 || d_a < 1 || s.Nq < 1 || s.reserved != 0)
+    if (s.B < 1 || s.H < 1 || s.d_g < 0 || s.d_u < 0 || d_a < 1 || s.Nq < 1)
         return fail(CKV_ERR_SHAPE, "%s: need B,H,Nq >= 1, d_g,d_u >= 0, d_g+d_u >= 1 (B=%d H=%d d_g=%d d_u=%d Nq=%d)", who,
                     s.B, s.H, s.d_g, s.d_u, s.Nq);
+    if (s.share != CKV_SHARE_KV && s.share != CKV_SHARE_K && s.share != CKV_SHARE_V)
+        return fail(CKV_ERR_SHAPE, "%s: unknown sharing mode %d", who, s.share);
     if (s.d_g > 0 && (s.P < 1 || s.pool_ld < s.d_g))
         return fail(CKV_ERR_SHAPE, "%s: need P >= 1 and pool_ld >= d_g (P=%d pool_ld=%lld d_g=%d)", who, s.P,
                     (long long)s.pool_ld, s.d_g);
@@ -582,11 +582,13 @@ static int cache_new(const char* who, const ckv_shape* shape, const int32_t* len
     }
     CKV_HIP(hipMalloc((void**)&c->d_lengths, sizeof(int32_t) * (size_t)s.B));
     CKV_HIP(hipMemcpyAsync(c->d_lengths, lengths, sizeof(int32_t) * (size_t)s.B, hipMemcpyHostToDevice, st));
-    if (n_ph > 0 && s.d_g > 0) CKV_HIP(cache_alloc(c, (void**)&c->d_idx, sizeof(int32_t) * 2 * n_ph));
-    if (n_ph > 0 && s.d_u > 0) {
-        const size_t ub = n_ph * (size_t)s.d_u * esize(s.dtype);
-        CKV_HIP(cache_alloc(c, &c->d_user_k, ub));
-        CKV_HIP(cache_alloc(c, &c->d_user_v, ub));
+    {
+        int d_uk, d_gk, d_uv, d_gv;
+        ckv_side_dims(s, 0, &d_uk, &d_gk);
+        ckv_side_dims(s, 1, &d_uv, &d_gv);
+        if (n_ph > 0 && s.d_g > 0) CKV_HIP(cache_alloc(c, (void**)&c->d_idx, sizeof(int32_t) * 2 * n_ph));
+        if (n_ph > 0 && d_uk > 0) CKV_HIP(cache_alloc(c, &c->d_user_k, n_ph * (size_t)d_uk * esize(s.dtype)));
+        if (n_ph > 0 && d_uv > 0) CKV_HIP(cache_alloc(c, &c->d_user_v, n_ph * (size_t)d_uv * esize(s.dtype)));
     }
 done:
     if (rc != CKV_OK) {
@@ -652,8 +654,15 @@ static int build_cache_impl(const ckv_shape* shape, const int32_t* lengths, cons
     {
         int64_t T = 0;
         for (int b = 0; b < shape->B; ++b) T += lengths[b] > 0 ? lengths[b] : 0;
-        if (T > 0 && shape->d_g > 0 && (!idx_k || !idx_v)) return fail(CKV_ERR_NULL, "ckv_build_cache: idx_k/idx_v are NULL but d_g > 0");
-        if (T > 0 && shape->d_u > 0 && (!user_k || !user_v)) return fail(CKV_ERR_NULL, "ckv_build_cache: user_k/user_v are NULL but d_u > 0");
+        int d_uk = 0, d_gk = 0, d_uv = 0, d_gv = 0;
+        if (shape->share >= CKV_SHARE_KV && shape->share <= CKV_SHARE_V) {
+            ckv_side_dims(*shape, 0, &d_uk, &d_gk);
+            ckv_side_dims(*shape, 1, &d_uv, &d_gv);
+        }
+        if (T > 0 && ((d_gk > 0 && !idx_k) || (d_gv > 0 && !idx_v)))
+            return fail(CKV_ERR_NULL, "ckv_build_cache: an index array is NULL but its side gathers from a pool");
+        if (T > 0 && ((d_uk > 0 && !user_k) || (d_uv > 0 && !user_v)))
+            return fail(CKV_ERR_NULL, "ckv_build_cache: a user array is NULL but its side has user columns");
     }
     int rc = cache_new("ckv_build_cache", shape, lengths, offloaded, st, &c, offs, &prop);
     if (rc != CKV_OK) return rc;
@@ -666,19 +675,25 @@ static int build_cache_impl(const ckv_shape* shape, const int32_t* lengths, cons
     unsigned long long* d_bad = nullptr;
     unsigned long long h_bad = ~0ull;
 
+    int d_uk, d_gk, d_uv, d_gv;
+    ckv_side_dims(s, 0, &d_uk, &d_gk);
+    ckv_side_dims(s, 1, &d_uv, &d_gv);
     if (n_ph > 0) {
-        if (s.d_g > 0) {
+        if (d_gk > 0) {
             CKV_HIP(hipMalloc((void**)&s_ik, sizeof(int32_t) * n_ph));
-            CKV_HIP(hipMalloc((void**)&s_iv, sizeof(int32_t) * n_ph));
             CKV_HIP(hipMemcpyAsync(s_ik, idx_k, sizeof(int32_t) * n_ph, hipMemcpyHostToDevice, st));
+        }
+        if (d_gv > 0) {
+            CKV_HIP(hipMalloc((void**)&s_iv, sizeof(int32_t) * n_ph));
             CKV_HIP(hipMemcpyAsync(s_iv, idx_v, sizeof(int32_t) * n_ph, hipMemcpyHostToDevice, st));
         }
-        if (s.d_u > 0) {
-            const size_t ub = n_ph * (size_t)s.d_u * e;
-            CKV_HIP(hipMalloc(&s_uk, ub));
-            CKV_HIP(hipMalloc(&s_uv, ub));
-            CKV_HIP(hipMemcpyAsync(s_uk, user_k, ub, hipMemcpyHostToDevice, st));
-            CKV_HIP(hipMemcpyAsync(s_uv, user_v, ub, hipMemcpyHostToDevice, st));
+        if (d_uk > 0) {
+            CKV_HIP(hipMalloc(&s_uk, n_ph * (size_t)d_uk * e));
+            CKV_HIP(hipMemcpyAsync(s_uk, user_k, n_ph * (size_t)d_uk * e, hipMemcpyHostToDevice, st));
+        }
+        if (d_uv > 0) {
+            CKV_HIP(hipMalloc(&s_uv, n_ph * (size_t)d_uv * e));
+            CKV_HIP(hipMemcpyAsync(s_uv, user_v, n_ph * (size_t)d_uv * e, hipMemcpyHostToDevice, st));
         }
         CKV_HIP(hipMalloc((void**)&d_bad, sizeof h_bad));
         CKV_HIP(hipMemcpyAsync(d_bad, &h_bad, sizeof h_bad, hipMemcpyHostToDevice, st));
@@ -688,11 +703,11 @@ static int build_cache_impl(const ckv_shape* shape, const int32_t* lengths, cons
             if (e == 4)
                 hipLaunchKernelGGL(ckv_pack_kernel<uint32_t>, dim3(blocks), dim3(threads), 0, st, s_ik, s_iv,
                                    (const uint32_t*)s_uk, (const uint32_t*)s_uv, c->d_idx, (uint32_t*)c->d_user_k,
-                                   (uint32_t*)c->d_user_v, T, s.H, s.d_u, s.P, s.d_g > 0 ? 1 : 0, d_bad);
+                                   (uint32_t*)c->d_user_v, T, s.H, d_uk, d_uv, s.P, d_gk > 0 ? 1 : 0, d_gv > 0 ? 1 : 0, d_bad);
             else
                 hipLaunchKernelGGL(ckv_pack_kernel<uint16_t>, dim3(blocks), dim3(threads), 0, st, s_ik, s_iv,
                                    (const uint16_t*)s_uk, (const uint16_t*)s_uv, c->d_idx, (uint16_t*)c->d_user_k,
-                                   (uint16_t*)c->d_user_v, T, s.H, s.d_u, s.P, s.d_g > 0 ? 1 : 0, d_bad);
+                                   (uint16_t*)c->d_user_v, T, s.H, d_uk, d_uv, s.P, d_gk > 0 ? 1 : 0, d_gv > 0 ? 1 : 0, d_bad);
             CKV_HIP(hipGetLastError());
         }
         CKV_HIP(hipMemcpyAsync(&h_bad, d_bad, sizeof h_bad, hipMemcpyDeviceToHost, st));
@@ -702,7 +717,7 @@ static int build_cache_impl(const ckv_shape* shape, const int32_t* lengths, cons
         const long long t = (long long)(h_bad / (unsigned long long)s.H);
         const int h = (int)(h_bad % (unsigned long long)s.H);
         rc = fail(CKV_ERR_INDEX, "ckv_build_cache: pool index out of range [0,%d) at position %lld head %d (idx_k=%d idx_v=%d)", s.P,
-                  t, h, idx_k[h_bad], idx_v[h_bad]);
+                  t, h, d_gk > 0 ? idx_k[h_bad] : 0, d_gv > 0 ? idx_v[h_bad] : 0);
         goto done;
     }
     rc = cache_finish(c, lengths, offs, prop, st);
@@ -726,10 +741,13 @@ static int router_args(const char* who, const ckv_shape& s, const ckv_router* r,
     if (!r) return fail(CKV_ERR_NULL, "%s: router is NULL", who);
     if (r->d_e < 1) return fail(CKV_ERR_SHAPE, "%s: d_e = %d must be >= 1", who, r->d_e);
     if (T > 0 && !S) return fail(CKV_ERR_NULL, "%s: S is NULL", who);
-    if (T > 0 && s.d_g > 0 && (!r->w_rk || !r->b_rk || !r->w_rv || !r->b_rv))
-        return fail(CKV_ERR_NULL, "%s: router weights or biases are NULL but d_g > 0", who);
-    if (T > 0 && s.d_u > 0 && (!r->w_k || !r->b_k || !r->w_v || !r->b_v))
-        return fail(CKV_ERR_NULL, "%s: projection weights or biases are NULL but d_u > 0", who);
+    int d_uk, d_gk, d_uv, d_gv;
+    ckv_side_dims(s, 0, &d_uk, &d_gk);
+    ckv_side_dims(s, 1, &d_uv, &d_gv);
+    if (T > 0 && ((d_gk > 0 && (!r->w_rk || !r->b_rk)) || (d_gv > 0 && (!r->w_rv || !r->b_rv))))
+        return fail(CKV_ERR_NULL, "%s: router weights or biases are NULL for a side that gathers from a pool", who);
+    if (T > 0 && ((d_uk > 0 && (!r->w_k || !r->b_k)) || (d_uv > 0 && (!r->w_v || !r->b_v))))
+        return fail(CKV_ERR_NULL, "%s: projection weights or biases are NULL for a side that has user columns", who);
     const uintptr_t align = (uintptr_t)S | (uintptr_t)r->w_rk | (uintptr_t)r->w_rv | (uintptr_t)r->w_k | (uintptr_t)r->w_v |
                             (uintptr_t)r->b_rk | (uintptr_t)r->b_rv | (uintptr_t)r->b_k | (uintptr_t)r->b_v;
     if (align & 15) return fail(CKV_ERR_UNSUPPORTED, "%s: every device pointer must be 16-byte aligned", who);
@@ -744,8 +762,10 @@ static int router_args(const char* who, const ckv_shape& s, const ckv_router* r,
     a->b_u[1] = r->b_v;
     a->T = T;
     a->H = s.H;
-    a->P = s.d_g > 0 ? s.P : 0;
-    a->d_u = s.d_u;
+    a->P[0] = d_gk > 0 ? s.P : 0;
+    a->P[1] = d_gv > 0 ? s.P : 0;
+    a->d_u[0] = d_uk;
+    a->d_u[1] = d_uv;
     a->d_e = r->d_e;
     return CKV_OK;
 }
@@ -770,7 +790,7 @@ int ckv_prefill_into(ckv_cache* c, const ckv_router* router, const void* S, void
     a.user[1] = c->d_user_v;
     hipError_t e = ckv_launch_prefill(a, c->shape.dtype, (hipStream_t)stream);
     if (e != hipSuccess) return fail(CKV_ERR_HIP, "ckv_prefill_into: kernel launch (%s): %s",
-                                     ckv_prefill_variant(c->shape.dtype, router->d_e, c->shape.d_u), hipGetErrorString(e));
+                                     ckv_prefill_variant(c->shape.dtype, router->d_e), hipGetErrorString(e));
     return CKV_OK;
 }
 
@@ -796,7 +816,7 @@ int ckv_prefill(const ckv_shape* shape, const ckv_router* router, const int32_t*
 
 const char* ckv_prefill_kernel_name(const ckv_shape* shape, const ckv_router* router) {
     if (!shape || !router) return "";
-    return ckv_prefill_variant(shape->dtype, router->d_e, shape->d_u);
+    return ckv_prefill_variant(shape->dtype, router->d_e);
 }
 
 int ckv_cache_is_offloaded(const ckv_cache* c) { return c ? c->offloaded : 0; }
@@ -809,7 +829,13 @@ int64_t ckv_cache_positions(const ckv_cache* c) { return c ? c->T : -1; }
 int64_t ckv_cache_stored_bytes(const ckv_cache* c) {
     if (!c) return -1;
     const int64_t ph = c->T * c->shape.H;
-    return ph * 2 * ((c->shape.d_g > 0 ? (int64_t)sizeof(int32_t) : 0) + (int64_t)c->shape.d_u * (int64_t)esize(c->shape.dtype));
+    int64_t per = 0;
+    for (int side = 0; side < 2; ++side) {
+        int d_u, d_g;
+        ckv_side_dims(c->shape, side, &d_u, &d_g);
+        per += (d_g > 0 ? (int64_t)sizeof(int32_t) : 0) + (int64_t)d_u * (int64_t)esize(c->shape.dtype);
+    }
+    return ph * per;
 }
 const char* ckv_variant(const ckv_cache* c) { return c ? c->variant : ""; }
 
@@ -817,8 +843,12 @@ int ckv_attend(const ckv_cache* c, const void* pool_k, const void* pool_v, const
                const void* user_v, const void* q, const int32_t* lengths, void* out, void* stream) {
     if (!c || !q || !out || !lengths) return fail(CKV_ERR_NULL, "ckv_attend: cache, q, lengths and out must not be NULL");
     const ckv_shape& s = c->shape;
-    if (c->T > 0 && s.d_g > 0 && (!pool_k || !pool_v || !idx)) return fail(CKV_ERR_NULL, "ckv_attend: pool_k, pool_v or idx is NULL");
-    if (c->T > 0 && s.d_u > 0 && (!user_k || !user_v)) return fail(CKV_ERR_NULL, "ckv_attend: user_k or user_v is NULL");
+    int d_uk, d_gk, d_uv, d_gv;
+    ckv_side_dims(s, 0, &d_uk, &d_gk);
+    ckv_side_dims(s, 1, &d_uv, &d_gv);
+    if (c->T > 0 && ((d_gk > 0 && (!pool_k || !idx)) || (d_gv > 0 && (!pool_v || !idx))))
+        return fail(CKV_ERR_NULL, "ckv_attend: pool_k, pool_v or idx is NULL for a side that gathers from a pool");
+    if (c->T > 0 && ((d_uk > 0 && !user_k) || (d_uv > 0 && !user_v))) return fail(CKV_ERR_NULL, "ckv_attend: user_k or user_v is NULL");
     const uintptr_t align = (uintptr_t)pool_k | (uintptr_t)pool_v | (uintptr_t)idx | (uintptr_t)user_k | (uintptr_t)user_v |
                             (uintptr_t)q | (uintptr_t)out;
     if (align & 15) return fail(CKV_ERR_UNSUPPORTED, "ckv_attend: every device pointer must be 16-byte aligned");
@@ -843,6 +873,10 @@ int ckv_attend(const ckv_cache* c, const void* pool_k, const void* pool_v, const
     a.d_g = s.d_g;
     a.d_u = s.d_u;
     a.d_a = s.d_g + s.d_u;
+    a.d_uk = d_uk;
+    a.d_gk = d_gk;
+    a.d_uv = d_uv;
+    a.d_gv = d_gv;
     a.Nq = s.Nq;
     a.QB = c->QB;
     a.scale = s.scale;
@@ -887,7 +921,10 @@ int ckv_attend(const ckv_cache* c, const void* pool_k, const void* pool_v, const
 int ckv_reconstruct(const ckv_cache* c, const void* pool_k, const void* pool_v, void* k_full, void* v_full, void* stream) {
     if (!c) return fail(CKV_ERR_NULL, "ckv_reconstruct: cache is NULL");
     const ckv_shape& s = c->shape;
-    if (s.d_g > 0 && c->T > 0 && ((k_full && !pool_k) || (v_full && !pool_v)))
+    int side_du[2], side_dg[2];
+    ckv_side_dims(s, 0, &side_du[0], &side_dg[0]);
+    ckv_side_dims(s, 1, &side_du[1], &side_dg[1]);
+    if (c->T > 0 && ((k_full && side_dg[0] > 0 && !pool_k) || (v_full && side_dg[1] > 0 && !pool_v)))
         return fail(CKV_ERR_NULL, "ckv_reconstruct: pool pointer is NULL");
     const int64_t total = (int64_t)s.H * c->T * (s.d_g + s.d_u);
     if (total == 0) return CKV_OK;
@@ -902,10 +939,10 @@ int ckv_reconstruct(const ckv_cache* c, const void* pool_k, const void* pool_v, 
         const int32_t* idx = c->d_idx ? c->d_idx + (int64_t)side * s.H * c->T : nullptr;
         if (s.dtype == CKV_F32)
             hipLaunchKernelGGL(ckv_reconstruct_kernel<uint32_t>, dim3(blocks), dim3(threads), 0, st, idx, (const uint32_t*)user,
-                               (const uint32_t*)pool, (uint32_t*)full, c->T, s.H, s.d_u, s.d_g, s.P, s.pool_ld);
+                               (const uint32_t*)pool, (uint32_t*)full, c->T, s.H, side_du[side], side_dg[side], s.P, s.pool_ld);
         else
             hipLaunchKernelGGL(ckv_reconstruct_kernel<uint16_t>, dim3(blocks), dim3(threads), 0, st, idx, (const uint16_t*)user,
-                               (const uint16_t*)pool, (uint16_t*)full, c->T, s.H, s.d_u, s.d_g, s.P, s.pool_ld);
+                               (const uint16_t*)pool, (uint16_t*)full, c->T, s.H, side_du[side], side_dg[side], s.P, s.pool_ld);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return fail(CKV_ERR_HIP, "ckv_reconstruct: launch: %s", hipGetErrorString(e));
     }

@@ -42,21 +42,31 @@ struct ckv_args {
     int64_t T;
     int64_t pool_ld;
     int32_t H, P, d_g, d_u, d_a, Nq;
+    int32_t d_uk, d_gk, d_uv, d_gv;  // per side: d_u, d_g of the shape for a shared side, (d_a, 0) otherwise
     int32_t QB;            // queries per block (rows of a workspace slot)
     float scale;
 };
 
+// Columns of one side (0 = K, 1 = V) that come from the user array and from the pool.
+inline void ckv_side_dims(const ckv_shape& s, int side, int* d_u, int* d_g) {
+    const bool shared = s.share == CKV_SHARE_KV || (s.share == CKV_SHARE_K && side == 0) || (s.share == CKV_SHARE_V && side == 1);
+    *d_u = shared ? s.d_u : s.d_u + s.d_g;
+    *d_g = shared ? s.d_g : 0;
+}
+
 // Kernel arguments of the prefill kernels.  Index 0 of every pair is the key side, 1 the value side.
 struct ckv_prefill_args {
     const void* S;            // [T][d_e]
-    const void* w_r[2];       // [H][P][d_e]
-    const float* b_r[2];      // [H][P]
-    const void* w_u[2];       // [H][d_u][d_e]
-    const float* b_u[2];      // [H][d_u]
+    const void* w_r[2];       // [H][P[side]][d_e]
+    const float* b_r[2];      // [H][P[side]]
+    const void* w_u[2];       // [H][d_u[side]][d_e]
+    const float* b_u[2];      // [H][d_u[side]]
     int32_t* idx;             // out [2][H][T]
-    void* user[2];            // out [H][T][d_u]
+    void* user[2];            // out [H][T][d_u[side]]
     int64_t T;
-    int32_t H, P, d_u, d_e;
+    int32_t P[2];             // pool entries routed to (0: that side has no router)
+    int32_t d_u[2];           // projected columns
+    int32_t H, d_e;
 };
 
 enum ckv_kernel_family { CKV_K_STREAM = 0, CKV_K_MFMA = 1, CKV_K_DMA = 2 };
@@ -107,7 +117,7 @@ bool ckv_dma_supported(int d_a, int nw, int qg);
 
 // Prefill (projection + router argmax into the packed cache layout).
 hipError_t ckv_launch_prefill(const ckv_prefill_args& a, int dtype, hipStream_t s);
-const char* ckv_prefill_variant(int dtype, int d_e, int d_u);
-bool ckv_prefill_mfma_supported(int dtype, int d_e, int d_u);
+const char* ckv_prefill_variant(int dtype, int d_e);
+bool ckv_prefill_mfma_supported(int dtype, int d_e);
 
 #endif

@@ -81,7 +81,7 @@ __global__ __launch_bounds__(NW * 64, (DA == 128 ? 2 : 2)) void ckv_mfma_kernel(
     constexpr int RPP = NT / CH;       // rows gathered per pass
     constexpr int NL = TP / RPP;       // passes per tile (chunks per lane per tile, K and V each)
     constexpr int KS = DA * 2 + 16;    // LDS row stride of K in bytes (conflict-free 16-byte row reads)
-    constexpr int VS = DA * 2 + 32;    // LDS row stride of V in bytes (conflict-free transpose reads)
+    constexpr int VS = DA * 2 + 64;    // LDS row stride of V in bytes (conflict-free transpose reads: four rows x 64 bytes per clock)
     constexpr int BUF = TP * (KS + VS);
     constexpr int NKK = DA / 16;       // k-steps of S^T = K Q^T
     constexpr int NDT = DA / 32;       // 32-row tiles of O^T
@@ -93,14 +93,15 @@ __global__ __launch_bounds__(NW * 64, (DA == 128 ? 2 : 2)) void ckv_mfma_kernel(
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int qn = lane & 31, hh = lane >> 5;
-    const int d_g = a.d_g, d_u = a.d_u;
+    // pool and user columns of each side (a side that is not shared: all user, no pool)
+    const int d_gk = a.d_gk, d_uk = a.d_uk, d_gv = a.d_gv, d_uv = a.d_uv;
     const int n = it.n;
 
     const int64_t hT = (int64_t)it.h * a.T + it.t0;
     const int32_t* __restrict__ ik = a.idx_k + hT;
     const int32_t* __restrict__ iv = a.idx_v + hT;
-    const uint16_t* __restrict__ uk = (const uint16_t*)a.user_k + hT * d_u;
-    const uint16_t* __restrict__ uv = (const uint16_t*)a.user_v + hT * d_u;
+    const uint16_t* __restrict__ uk = (const uint16_t*)a.user_k + hT * d_uk;
+    const uint16_t* __restrict__ uv = (const uint16_t*)a.user_v + hT * d_uv;
     const uint16_t* __restrict__ pk = (const uint16_t*)a.pool_k + (int64_t)it.h * a.P * a.pool_ld;
     const uint16_t* __restrict__ pv = (const uint16_t*)a.pool_v + (int64_t)it.h * a.P * a.pool_ld;
 
@@ -116,7 +117,7 @@ __global__ __launch_bounds__(NW * 64, (DA == 128 ? 2 : 2)) void ckv_mfma_kernel(
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const int ci = 16 * kk + 8 * hh + e;
-                const int pc = ci < d_g ? ci + d_u : ci - d_g;
+                const int pc = ci < d_gk ? ci + d_uk : ci - d_gk;  // kernel column of K -> column of q
                 const uint16_t x = qok ? qp[pc] : (uint16_t)0;
                 qreg[kk][e] = __builtin_bit_cast(__bf16, x);
             }
@@ -141,16 +142,16 @@ __global__ __launch_bounds__(NW * 64, (DA == 128 ? 2 : 2)) void ckv_mfma_kernel(
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             const int pos = min(tile * TP + p0 + i * RPP, n - 1);
-            rk[i] = d_g > 0 ? ik[pos] : 0;
-            rv[i] = d_g > 0 ? iv[pos] : 0;
+            rk[i] = d_gk > 0 ? ik[pos] : 0;
+            rv[i] = d_gv > 0 ? iv[pos] : 0;
         }
     };
     auto load_rows = [&](int tile) {
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             const int pos = min(tile * TP + p0 + i * RPP, n - 1);
-            kreg[i] = gather_chunk(pk, rk[i], a.pool_ld, uk + (int64_t)pos * d_u, c, d_g, d_u);
-            vreg[i] = gather_chunk(pv, rv[i], a.pool_ld, uv + (int64_t)pos * d_u, c, d_g, d_u);
+            kreg[i] = gather_chunk(pk, rk[i], a.pool_ld, uk + (int64_t)pos * d_uk, c, d_gk, d_uk);
+            vreg[i] = gather_chunk(pv, rv[i], a.pool_ld, uv + (int64_t)pos * d_uv, c, d_gv, d_uv);
         }
     };
     auto store_rows = [&](int buf) {
@@ -268,7 +269,7 @@ __global__ __launch_bounds__(NW * 64, (DA == 128 ? 2 : 2)) void ckv_mfma_kernel(
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int ci = 32 * dt + 8 * (r >> 2) + 4 * hh + (r & 3);
-                    const int pc = ci < d_g ? ci + d_u : ci - d_g;
+                    const int pc = ci < d_gv ? ci + d_uv : ci - d_gv;  // kernel column of V -> column of out
                     op[pc] = f2bf(oacc[dt][r] * inv);
                 }
         }
@@ -280,7 +281,7 @@ __global__ __launch_bounds__(NW * 64, (DA == 128 ? 2 : 2)) void ckv_mfma_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int ci = 32 * dt + 8 * (r >> 2) + 4 * hh + (r & 3);
-                const int pc = ci < d_g ? ci + d_u : ci - d_g;
+                const int pc = ci < d_gv ? ci + d_uv : ci - d_gv;
                 ws[(int64_t)j * DA + pc] = oacc[dt][r];
             }
         if (hh == 0) {
@@ -292,7 +293,7 @@ __global__ __launch_bounds__(NW * 64, (DA == 128 ? 2 : 2)) void ckv_mfma_kernel(
 
 template <int DA, int NW, int TP>
 constexpr int lds_bytes() {
-    return 2 * TP * ((DA * 2 + 16) + (DA * 2 + 32));
+    return 2 * TP * ((DA * 2 + 16) + (DA * 2 + 64));
 }
 
 template <int DA, int NW, int TP, int MODE>

@@ -15,7 +15,8 @@
 // (rare after the first tiles) is the entry that attains it located.  Equal scores keep the
 // lowest pool entry: tiles are visited in increasing order and replaced only on a strict
 // improvement, and inside a tile the lowest matching register wins.
-// The projection is one more tile whose 32 "pool entries" are the d_u rows of W_k (or W_v).
+// The projection is more tiles of the same kind whose 32 "pool entries" are rows of W_k (or W_v):
+// one tile for the usual small d_u, d_a / 32 tiles for a side that is not shared.
 //
 // Scalar kernel: any d_e and either storage type, one thread per (position, head, side).
 #include <type_traits>
@@ -97,7 +98,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
     const int cls = blockIdx.x % ncls;
     const int64_t pblock = blockIdx.x / ncls;
     const int h = cls >> 1, side = cls & 1;
-    const int P = a.P, d_u = a.d_u;
+    const int P = a.P[side], d_u = a.d_u[side];  // this side's pool entries (0: not shared) and projected columns
 
     const unsigned char* __restrict__ wr = (const unsigned char*)a.w_r[side] + (int64_t)h * P * G::ROWB;
     const float* __restrict__ br = a.b_r[side] + (int64_t)h * P;
@@ -105,7 +106,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
     const float* __restrict__ bu = a.b_u[side] + (int64_t)h * d_u;
     const int nfull = P / TR;                      // stages made of TR valid router rows
     const int nrt = (P + TR - 1) / TR;             // router stages
-    const int ntt = nrt + (d_u > 0 ? 1 : 0);       // plus the projection stage
+    const int npj = (d_u + SR - 1) / SR;           // projection stages: 32 columns of the user slice each
+    const int ntt = nrt + npj;
     if (ntt == 0) return;
 
     // ---- positions of this wavefront: B operands, 16 bytes per lane and k-step, straight from S
@@ -151,13 +153,13 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
             dma4_uniform(br + (int64_t)tile * TR, boff, st + G::WT + wave * 256);
             return;
         }
-        // ragged last router stage, the projection stage, or a repeat of the last stage into a retired
+        // ragged last router stage, a projection stage, or a repeat of the last stage into a retired
         // slot (never read): rows are clamped to the last valid one
         tile = min(tile, ntt - 1);
         const bool proj = tile >= nrt;
         const unsigned char* wbase = proj ? wu : wr;
         const float* bbase = proj ? bu : br;
-        const int row0 = proj ? 0 : tile * TR;
+        const int row0 = proj ? (tile - nrt) * SR : tile * TR;
         const int rmax = (proj ? d_u : P) - 1;
 #pragma unroll
         for (int i = 0; i < G::NI; ++i) {
@@ -177,7 +179,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
     const uint32_t arow = qn * G::ROWB;
     const int ax = G::swz(qn);
 
-    // One stage: KIND 0 = TR valid router rows, 1 = last router stage with fewer, 2 = projection.
+    // One stage: KIND 0 = TR valid router rows, 1 = last router stage with fewer, 2 = projection
+    // (32 columns of the user slice).
     // The three are separate instantiations so that the loop over full stages stays free of their branches.
     // Iteration t issues the loads of stage t+NS-1 into the slot stage t-1 used (retired by the barrier at
     // the end of iteration t-1), computes stage t, then waits until only the loads of the last NS-2 issues
@@ -203,7 +206,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
 #pragma unroll
             for (int g = 0; g < QG; ++g) acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[kk], sreg[g][kk], acc[g], 0, 0, 0);
         if (KIND == 2) {
-            // projection: row c of the block is column c of the user slice
+            // projection: row c of the block is column c0 + c of the user slice
+            const int c0 = (t - nrt) * SR;
 #pragma unroll
             for (int g = 0; g < QG; ++g) {
                 const int64_t pos = pos0 + g * 32 + qn;
@@ -211,7 +215,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
                     uint16_t* dst = (uint16_t*)a.user[side] + ((int64_t)h * a.T + pos) * d_u;
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        const int c = 8 * (r >> 2) + 4 * hh + (r & 3);
+                        const int c = c0 + 8 * (r >> 2) + 4 * hh + (r & 3);
                         if (c < d_u) dst[c] = f2bf(acc[g][r]);
                     }
                 }
@@ -254,7 +258,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
     lds_barrier();
     for (int t = 0; t < nfull; ++t) stage(std::integral_constant<int, 0>{}, t);
     if (nrt > nfull) stage(std::integral_constant<int, 1>{}, nfull);
-    if (d_u > 0) stage(std::integral_constant<int, 2>{}, nrt);
+    for (int t = nrt; t < ntt; ++t) stage(std::integral_constant<int, 2>{}, t);
     wait_vm<0>();  // the repeated loads past the last stage must land before the workgroup gives its LDS back
 
     if (nrt > 0) {
@@ -291,12 +295,13 @@ __global__ __launch_bounds__(256) void ckv_prefill_scalar_kernel(ckv_prefill_arg
         const int cls = (int)(i / a.T);
         const int h = cls >> 1, side = cls & 1;
         const U* __restrict__ s = (const U*)a.S + pos * d_e;
-        if (a.P > 0) {
-            const U* __restrict__ w = (const U*)a.w_r[side] + (int64_t)h * a.P * d_e;
-            const float* __restrict__ b = a.b_r[side] + (int64_t)h * a.P;
+        const int P = a.P[side], d_u = a.d_u[side];
+        if (P > 0) {
+            const U* __restrict__ w = (const U*)a.w_r[side] + (int64_t)h * P * d_e;
+            const float* __restrict__ b = a.b_r[side] + (int64_t)h * P;
             float best = -INFINITY;
             int bj = 0;
-            for (int j = 0; j < a.P; ++j) {
+            for (int j = 0; j < P; ++j) {
                 float m = 0.f;
                 for (int c = 0; c < d_e; ++c) m = fmaf(widen<U>(s[c]), widen<U>(w[(int64_t)j * d_e + c]), m);
                 m += b[j];
@@ -307,11 +312,11 @@ __global__ __launch_bounds__(256) void ckv_prefill_scalar_kernel(ckv_prefill_arg
             }
             a.idx[((int64_t)side * a.H + h) * a.T + pos] = bj;
         }
-        if (a.d_u > 0) {
-            const U* __restrict__ w = (const U*)a.w_u[side] + (int64_t)h * a.d_u * d_e;
-            const float* __restrict__ b = a.b_u[side] + (int64_t)h * a.d_u;
-            U* dst = (U*)a.user[side] + ((int64_t)h * a.T + pos) * a.d_u;
-            for (int c0 = 0; c0 < a.d_u; ++c0) {
+        if (d_u > 0) {
+            const U* __restrict__ w = (const U*)a.w_u[side] + (int64_t)h * d_u * d_e;
+            const float* __restrict__ b = a.b_u[side] + (int64_t)h * d_u;
+            U* dst = (U*)a.user[side] + ((int64_t)h * a.T + pos) * d_u;
+            for (int c0 = 0; c0 < d_u; ++c0) {
                 float m = 0.f;
                 for (int c = 0; c < d_e; ++c) m = fmaf(widen<U>(s[c]), widen<U>(w[(int64_t)c0 * d_e + c]), m);
                 narrow(dst + c0, m + b[c0]);
@@ -335,18 +340,18 @@ hipError_t launch_mfma(const ckv_prefill_args& a, hipStream_t s) {
 
 }  // namespace
 
-bool ckv_prefill_mfma_supported(int dtype, int d_e, int d_u) {
-    return dtype == CKV_BF16 && (d_e == 64 || d_e == 128 || d_e == 256) && d_u <= 32;
+bool ckv_prefill_mfma_supported(int dtype, int d_e) {
+    return dtype == CKV_BF16 && (d_e == 64 || d_e == 128 || d_e == 256);
 }
 
-const char* ckv_prefill_variant(int dtype, int d_e, int d_u) {
-    if (ckv_prefill_mfma_supported(dtype, d_e, d_u)) return d_e == 64 ? "prefill_mfma_bf16_e64" : (d_e == 128 ? "prefill_mfma_bf16_e128" : "prefill_mfma_bf16_e256");
+const char* ckv_prefill_variant(int dtype, int d_e) {
+    if (ckv_prefill_mfma_supported(dtype, d_e)) return d_e == 64 ? "prefill_mfma_bf16_e64" : (d_e == 128 ? "prefill_mfma_bf16_e128" : "prefill_mfma_bf16_e256");
     return dtype == CKV_F32 ? "prefill_scalar_f32" : "prefill_scalar_bf16";
 }
 
 hipError_t ckv_launch_prefill(const ckv_prefill_args& a, int dtype, hipStream_t s) {
-    if (a.T == 0 || (a.P == 0 && a.d_u == 0)) return hipSuccess;
-    if (ckv_prefill_mfma_supported(dtype, a.d_e, a.d_u)) {
+    if (a.T == 0) return hipSuccess;
+    if (ckv_prefill_mfma_supported(dtype, a.d_e)) {
         if (a.d_e == 64) return launch_mfma<64, 4, 2, 32, 4, 3>(a, s);
         if (a.d_e == 128) return launch_mfma<128, 4, 2, 32, 4, 3>(a, s);
         return launch_mfma<256, 4, 1, 32, 4, 3>(a, s);

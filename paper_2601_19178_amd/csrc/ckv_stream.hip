@@ -8,7 +8,8 @@
 // lanes share one final K (or V) row: lane c of the group owns the columns
 // (cb*16 + c)*VEC .. +VEC of every column block cb, taken from the user slice when the
 // column is < d_u and from the gathered pool row otherwise (eq. "eq: Kc", "eq: K": the
-// concat exists only as this column test).  Four rows are processed per step.  The score of
+// concat exists only as this column test; a side that is not shared has d_u = d_a and never
+// reaches the pool).  Four rows are processed per step.  The score of
 // position 4*t + r ends up in lane 16*r + t, so softmax maxima and sums are wavefront
 // shuffles, and the weight is shuffled back to the row's sixteen lanes for the V pass.
 #include "ckv_internal.h"
@@ -61,12 +62,13 @@ __global__ __launch_bounds__(kLanes * kWaves) void ckv_stream_kernel(ckv_args a)
     const ckv_item it = a.items[blockIdx.x];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane >> 4, c = lane & 15;
-    const int d_u = a.d_u, d_a = a.d_a;
+    // user columns of each side: d_u of the shape, or all d_a columns for a side that is not shared
+    const int d_uk = a.d_uk, d_uv = a.d_uv, d_a = a.d_a;
     const int64_t hT = (int64_t)it.h * a.T + it.t0;
     const int32_t* ik = a.idx_k + hT;
     const int32_t* iv = a.idx_v + hT;
-    const T* uk = (const T*)a.user_k + hT * d_u;
-    const T* uv = (const T*)a.user_v + hT * d_u;
+    const T* uk = (const T*)a.user_k + hT * d_uk;
+    const T* uv = (const T*)a.user_v + hT * d_uv;
     const T* pk = (const T*)a.pool_k + (int64_t)it.h * a.P * a.pool_ld;
     const T* pv = (const T*)a.pool_v + (int64_t)it.h * a.P * a.pool_ld;
     const int n = it.n;
@@ -99,8 +101,8 @@ __global__ __launch_bounds__(kLanes * kWaves) void ckv_stream_kernel(ckv_args a)
             const int nt = min(n - t0, kLanes);
             const int nsteps = (nt + 3) >> 2;  // four rows per step
             const int myslot = min(slot_of_lane, nt - 1);
-            const int my_ik = a.d_g > 0 ? ik[t0 + myslot] : 0;
-            const int my_iv = a.d_g > 0 ? iv[t0 + myslot] : 0;
+            const int my_ik = a.d_gk > 0 ? ik[t0 + myslot] : 0;
+            const int my_iv = a.d_gv > 0 ? iv[t0 + myslot] : 0;
             // ---- scores
             float s_mine = 0.f;
             for (int tb = 0; tb < nsteps; tb += 4)
@@ -113,8 +115,8 @@ __global__ __launch_bounds__(kLanes * kWaves) void ckv_stream_kernel(ckv_args a)
                 for (int cb = 0; cb < NCB; ++cb) {
                     if (col[cb] >= 0) {
                         float kv[VEC];
-                        const T* src = col[cb] < d_u ? uk + (int64_t)(t0 + pos) * d_u + col[cb]
-                                                     : pk + (int64_t)row * a.pool_ld + (col[cb] - d_u);
+                        const T* src = col[cb] < d_uk ? uk + (int64_t)(t0 + pos) * d_uk + col[cb]
+                                                      : pk + (int64_t)row * a.pool_ld + (col[cb] - d_uk);
                         load_vec<T, VEC>(kv, src);
 #pragma unroll
                         for (int v = 0; v < VEC; ++v) part = fmaf(kv[v], qreg[cb][v], part);
@@ -154,8 +156,8 @@ __global__ __launch_bounds__(kLanes * kWaves) void ckv_stream_kernel(ckv_args a)
                 for (int cb = 0; cb < NCB; ++cb) {
                     if (col[cb] >= 0) {
                         float vv[VEC];
-                        const T* src = col[cb] < d_u ? uv + (int64_t)(t0 + pos) * d_u + col[cb]
-                                                     : pv + (int64_t)row * a.pool_ld + (col[cb] - d_u);
+                        const T* src = col[cb] < d_uv ? uv + (int64_t)(t0 + pos) * d_uv + col[cb]
+                                                      : pv + (int64_t)row * a.pool_ld + (col[cb] - d_uv);
                         load_vec<T, VEC>(vv, src);
 #pragma unroll
                         for (int v = 0; v < VEC; ++v) acc[cb][v] = fmaf(wr, vv[v], acc[cb][v]);

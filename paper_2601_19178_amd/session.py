@@ -34,8 +34,12 @@ class Session:
         self.w = w
         self.dtype = w["dtype"]
         self.d_a = w["d_g"] + w["d_u"]
+        self.share = w.get("share", 0)
         self.shape = ckv.make_shape(w["B"], w["H"], w["d_g"], w["d_u"], w["P"], w["Nq"], w["dtype"], w["mode"],
-                                    w["scale"], w["pool_ld"])
+                                    w["scale"], w["pool_ld"], self.share)
+        # user columns of each side: d_u, or all d_a columns for a side that is not shared
+        self.d_uk = w["d_u"] if self.share in (0, 1) else self.d_a
+        self.d_uv = w["d_u"] if self.share in (0, 2) else self.d_a
         self.stream = torch.cuda.current_stream().cuda_stream
         self.pool_k = _to_device(w["pool_k"], self.dtype) if w["d_g"] > 0 else None
         self.pool_v = _to_device(w["pool_v"], self.dtype) if w["d_g"] > 0 else None
@@ -46,6 +50,7 @@ class Session:
         if prefill is not None:
             r = prefill
             assert not offloaded and r["H"] == w["H"] and r["d_u"] == w["d_u"] and r["dtype"] == w["dtype"]
+            assert r.get("share", 0) == self.share
             assert r["T"] == int(np.sum(w["lengths"])) and (w["d_g"] == 0 or r["P"] == w["P"])
             self.S = _to_device(r["S"], self.dtype)
             self.rw = {k: _to_device(r[k], self.dtype) for k in ("w_rk", "w_rv", "w_k", "w_v")}
@@ -89,7 +94,7 @@ class Session:
 
     def packed_views(self):
         """Copies of the packed cache as numpy: idx [2][H][T], user_k/user_v [H][T][d_u] storage arrays."""
-        H, T, d_u = self.w["H"], self.T, self.w["d_u"]
+        H, T = self.w["H"], self.T
         e = 4 if self.dtype == ckv.CKV_F32 else 2
 
         def pull(addr, nbytes, npdt):
@@ -102,8 +107,8 @@ class Session:
 
         idx = pull(ckv.ckv_cache_idx(self.cache), 2 * H * T * 4, np.int32).reshape(2, H, T) if self.w["d_g"] > 0 else None
         sdt = np.float32 if self.dtype == ckv.CKV_F32 else np.uint16
-        uk = pull(ckv.ckv_cache_user_k(self.cache), H * T * d_u * e, sdt).reshape(H, T, d_u)
-        uv = pull(ckv.ckv_cache_user_v(self.cache), H * T * d_u * e, sdt).reshape(H, T, d_u)
+        uk = pull(ckv.ckv_cache_user_k(self.cache), H * T * self.d_uk * e, sdt).reshape(H, T, self.d_uk)
+        uv = pull(ckv.ckv_cache_user_v(self.cache), H * T * self.d_uv * e, sdt).reshape(H, T, self.d_uv)
         return idx, uk, uv
 
     def close(self):

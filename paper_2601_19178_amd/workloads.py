@@ -42,6 +42,12 @@ CONFIGS = {
                  mode=SILU_OVER_N, dtype=BF16, sigma_pool=1.0 / 8.0, seed=1003),
     "cfg4": dict(B=128, L=(2048, 8192), H=8, d_a=128, d_u=8, P=65536, idx="uniform", Nq=128,
                  mode=SOFTMAX, dtype=BF16, sigma_pool=128.0 ** -0.5, seed=1004),
+    # config 3 with only the keys shared (CollectiveK) / only the values shared (CollectiveV): the other side
+    # is an ordinary 64-column cache
+    "cfg3_ck": dict(B=512, L=(1024, 1024), H=4, d_a=64, d_u=4, P=16384, idx=("zipf", 1.1), Nq=64,
+                    mode=SILU_OVER_N, dtype=BF16, sigma_pool=1.0 / 8.0, seed=1003, share=SHARE_K),
+    "cfg3_cv": dict(B=512, L=(1024, 1024), H=4, d_a=64, d_u=4, P=16384, idx=("zipf", 1.1), Nq=64,
+                    mode=SILU_OVER_N, dtype=BF16, sigma_pool=1.0 / 8.0, seed=1003, share=SHARE_V),
     "cfg5": dict(B=8192, L=(512, 2048), H=4, d_a=64, d_u=2, P=1048576, idx=("zipf", 1.05), Nq=16,
                  mode=SOFTMAX, dtype=BF16, sigma_pool=1.0 / 8.0, seed=1005),
 }

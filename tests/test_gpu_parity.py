@@ -220,6 +220,55 @@ def test_offloaded_cache_matches_resident(gpu, kind):
 
 
 # ---------------------------------------------------------------------------------------------
+# sharing only keys or only values (CollectiveK / CollectiveV): the other side is an ordinary d_a-wide cache
+@pytest.mark.parametrize("share", [wl.SHARE_K, wl.SHARE_V])
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+def test_single_side_sharing_pack_and_reconstruct_bit_exact(gpu, share, dtype):
+    ckv, session = gpu
+    w = make(RAGGED, dtype, wl.SOFTMAX, d_a=24, d_u=3, H=3, P=101, Nq=2, pool_ld=29, share=share)
+    say(f"[case] reconstruct share={share} dtype={dtype}")
+    with session.Session(w) as s:
+        idx, uk, uv = s.packed_views()
+        k_full, v_full = s.reconstruct()
+        stored = ckv.ckv_cache_stored_bytes(s.cache)
+    shared_plane, plain_plane = (0, 1) if share == wl.SHARE_K else (1, 0)
+    np.testing.assert_array_equal(idx[shared_plane], w["idx_k" if share == wl.SHARE_K else "idx_v"].T)
+    assert (idx[plain_plane] == 0).all()
+    np.testing.assert_array_equal(uk, w["user_k"].transpose(1, 0, 2))
+    np.testing.assert_array_equal(uv, w["user_v"].transpose(1, 0, 2))
+    ok, ov = oracle.reconstruct(w)
+    np.testing.assert_array_equal(k_full, ok.transpose(1, 0, 2))
+    np.testing.assert_array_equal(v_full, ov.transpose(1, 0, 2))
+    _, _, sb, _ = oracle.cache_size(int(w["lengths"].sum()), w["H"], w["d_g"], w["d_u"], dtype, share=share)
+    assert stored == sb
+
+
+@pytest.mark.parametrize("share", [wl.SHARE_K, wl.SHARE_V])
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+@pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
+def test_single_side_sharing_stream(gpu, share, dtype, mode):
+    w = make(RAGGED, dtype, mode, d_a=64, d_u=8, H=2, P=300, Nq=2, share=share)
+    run_and_check(gpu, w, f"stream share={share} dtype={dtype} mode={mode}", expect_variant="stream")
+    w = make(RAGGED, dtype, mode, d_a=20, d_u=3, H=1, P=77, Nq=1, pool_ld=19, share=share)
+    run_and_check(gpu, w, f"stream unaligned share={share} dtype={dtype} mode={mode}", expect_variant="stream")
+
+
+@pytest.mark.parametrize("share", [wl.SHARE_K, wl.SHARE_V])
+@pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
+@pytest.mark.parametrize("d_a,d_u,Nq", [(64, 4, 64), (128, 8, 128), (64, 3, 20), (128, 16, 40)])
+def test_single_side_sharing_matrix_core(gpu, share, mode, d_a, d_u, Nq):
+    w = make(MFMA_LENGTHS, wl.BF16, mode, d_a=d_a, d_u=d_u, H=2, P=700, Nq=Nq, share=share)
+    run_and_check(gpu, w, f"mfma share={share} d_a={d_a} d_u={d_u} Nq={Nq} mode={mode}", expect_variant="mfma_bf16")
+
+
+def test_single_side_sharing_split_history(gpu):
+    w = make((5000, 70, 2300, 1025), wl.BF16, wl.SOFTMAX, d_a=128, d_u=8, H=2, P=5000, Nq=128, share=wl.SHARE_K)
+    run_and_check(gpu, w, "mfma split share=K", expect_variant="mfma_bf16")
+    w = make((5000, 70, 2300), wl.F32, wl.SOFTMAX, d_a=64, d_u=8, H=2, P=500, Nq=2, share=wl.SHARE_V)
+    run_and_check(gpu, w, "stream split share=V", expect_variant="stream")
+
+
+# ---------------------------------------------------------------------------------------------
 # error paths that need the device
 def test_out_of_range_index_is_rejected(gpu):
     ckv, session = gpu

@@ -35,10 +35,12 @@ def gpu():
 def decode_workload(lengths, r, Nq=2, mode=wl.SOFTMAX, d_g=None, seed=31):
     """A decode workload whose cache shape matches the prefill workload r."""
     lengths = np.asarray(lengths, dtype=np.int32)
+    if r.get("share", 0) != wl.SHARE_KV:
+        d_g = r["d_a"] - r["d_u"]
     d_g = (56 if r["P"] > 1 else 0) if d_g is None else d_g
     d_a = d_g + r["d_u"]
     return wl.make(B=len(lengths), L=None, H=r["H"], d_a=d_a, d_u=r["d_u"], P=r["P"], idx="uniform", Nq=Nq, mode=mode,
-                   dtype=r["dtype"], sigma_pool=max(d_a, 1) ** -0.5, seed=seed, lengths=lengths)
+                   dtype=r["dtype"], sigma_pool=max(d_a, 1) ** -0.5, seed=seed, lengths=lengths, share=r.get("share", 0))
 
 
 def user_tolerance(ref, dtype):
@@ -63,7 +65,10 @@ def run_prefill(gpu, lengths, r, what, expect_kernel, exact, d_g=None):
     ik, iv, ruk, ruv = oracle.prefill(r)
     T, H = r["T"], r["H"]
     if w["d_g"] > 0:
+        shared_sides = {wl.SHARE_KV: "kv", wl.SHARE_K: "k", wl.SHARE_V: "v"}[w["share"]]
         for side, got, ref in (("k", idx[0].T, ik), ("v", idx[1].T, iv)):
+            if side not in shared_sides:
+                continue
             assert got.size == 0 or (got.min() >= 0 and got.max() < r["P"])
             same = float((got == ref).mean()) if got.size else 1.0
             if exact:
@@ -88,7 +93,10 @@ def run_prefill(gpu, lengths, r, what, expect_kernel, exact, d_g=None):
     if T > 0:
         w2 = dict(w)
         if w["d_g"] > 0:
-            w2["idx_k"], w2["idx_v"] = np.ascontiguousarray(idx[0].T), np.ascontiguousarray(idx[1].T)
+            if w["share"] in (wl.SHARE_KV, wl.SHARE_K):
+                w2["idx_k"] = np.ascontiguousarray(idx[0].T)
+            if w["share"] in (wl.SHARE_KV, wl.SHARE_V):
+                w2["idx_v"] = np.ascontiguousarray(idx[1].T)
         w2["user_k"] = np.ascontiguousarray(uk.astype(sdt).transpose(1, 0, 2))
         w2["user_v"] = np.ascontiguousarray(uv.astype(sdt).transpose(1, 0, 2))
         check(out, oracle.attend(w2), w["dtype"], what=what + " (decode over the prefilled cache)")
@@ -125,6 +133,17 @@ def test_no_pool_and_no_user_columns(gpu):
     run_prefill(gpu, LENGTHS, r, "prefill d_g=0", "prefill_mfma_bf16", exact=True, d_g=0)
     r = wl.make_prefill(T=sum(LENGTHS), H=2, d_e=128, d_u=0, P=200, dtype=wl.BF16, seed=71, integers=1)
     run_prefill(gpu, LENGTHS, r, "prefill d_u=0", "prefill_mfma_bf16", exact=True, d_g=64)
+
+
+@pytest.mark.parametrize("share", [wl.SHARE_K, wl.SHARE_V])
+def test_prefill_with_one_side_shared(gpu, share):
+    # the side that is not shared has no router; its projection has d_a rows (several 32-column tiles)
+    r = wl.make_prefill(T=sum(LENGTHS), H=2, d_e=128, d_u=8, P=1000, dtype=wl.BF16, seed=80, integers=1, share=share, d_a=64)
+    run_prefill(gpu, LENGTHS, r, f"prefill mfma exact share={share}", "prefill_mfma_bf16", exact=True)
+    r = wl.make_prefill(T=sum(LENGTHS), H=2, d_e=64, d_u=3, P=333, dtype=wl.BF16, seed=81, share=share, d_a=40)
+    run_prefill(gpu, LENGTHS, r, f"prefill mfma random share={share}", "prefill_mfma_bf16", exact=False)
+    r = wl.make_prefill(T=200, H=2, d_e=24, d_u=3, P=61, dtype=wl.F32, seed=82, integers=2, share=share, d_a=16)
+    run_prefill(gpu, (5, 0, 131, 64), r, f"prefill scalar exact share={share}", "prefill_scalar", exact=True)
 
 
 def test_all_histories_empty(gpu):
