@@ -300,14 +300,24 @@ struct Piece {
     int64_t n;       // positions
 };
 
-double assign_static(const ckv_cache* c, const std::vector<Unit>& units, int64_t piece_len, int64_t slots, int64_t overhead,
-                     double part_positions, std::vector<std::vector<Piece>>& lists, int* n_parts_out) {
+double assign_static(const ckv_cache* c, const std::vector<Unit>& units, int64_t piece_len, int64_t slots, int cus, double slow_speed,
+                     int64_t overhead, double part_positions, std::vector<std::vector<Piece>>& lists, int* n_parts_out) {
     const ckv_shape& s = c->shape;
     int ncls = 1;
     if (s.H >= 8 && s.H % 8 == 0) ncls = 8;
     else if (s.H < 8 && 8 % s.H == 0) ncls = s.H;
     lists.assign((size_t)slots, {});
     std::vector<int64_t> load((size_t)slots, 0);
+    // Relative speed of a workgroup.  When a SIMD holds more than one wavefront of this kernel the hardware
+    // favours the wavefront slot that was filled first: the workgroups of the first dispatch wave (indices
+    // below slots / workgroups-per-CU) were measured to advance 1.2 to 1.3 times faster than those that
+    // share their SIMDs (traced on both matrix-core workloads), finish early and leave the CU half empty.
+    // Giving them proportionally more positions makes all workgroups of a CU finish together.
+    const int wg_per_cu = std::max<int>(1, (int)(slots / std::max(1, cus)));
+    std::vector<double> speed((size_t)slots, 1.0);
+    if (wg_per_cu * c->nw > 4)
+        for (int64_t i = slots / wg_per_cu; i < slots; ++i) speed[(size_t)i] = slow_speed;
+    auto time_of = [&](int w) { return (double)load[(size_t)w] / speed[(size_t)w]; };
     std::vector<int> pieces_of_unit(units.size(), 0);
     double worst = 0;
     for (int cls = 0; cls < ncls; ++cls) {
@@ -331,31 +341,38 @@ double assign_static(const ckv_cache* c, const std::vector<Unit>& units, int64_t
             }
         }
         std::stable_sort(ps.begin(), ps.end(), [](const Piece& x, const Piece& y) { return x.n > y.n; });
-        // longest first onto the least loaded workgroup
-        auto cmp = [&](int x, int y) { return load[(size_t)x] > load[(size_t)y] || (load[(size_t)x] == load[(size_t)y] && x > y); };
-        std::vector<int> heap = wgs;
-        std::make_heap(heap.begin(), heap.end(), cmp);
+        // longest first onto the workgroup that would finish it earliest
         for (const Piece& p : ps) {
-            std::pop_heap(heap.begin(), heap.end(), cmp);
-            const int w = heap.back();
-            lists[(size_t)w].push_back(p);
-            load[(size_t)w] += p.n + overhead;
-            std::push_heap(heap.begin(), heap.end(), cmp);
+            int best = wgs[0];
+            double best_t = 1e300;
+            for (int w : wgs) {
+                const double t = (double)(load[(size_t)w] + p.n + overhead) / speed[(size_t)w];
+                if (t < best_t) {
+                    best_t = t;
+                    best = w;
+                }
+            }
+            lists[(size_t)best].push_back(p);
+            load[(size_t)best] += p.n + overhead;
         }
-        // move load from the fullest to the emptiest workgroup
-        int64_t total = 0;
-        for (int w : wgs) total += load[(size_t)w];
-        const int64_t target = total / (int64_t)wgs.size();
-        const int64_t tol = std::max<int64_t>(target / 50, 256);
-        for (size_t iter = 0; iter < 2 * wgs.size(); ++iter) {
+        // move load from the workgroup that finishes last to the one that finishes first
+        double total = 0, total_speed = 0;
+        for (int w : wgs) {
+            total += (double)load[(size_t)w];
+            total_speed += speed[(size_t)w];
+        }
+        const double target = total / total_speed;  // common finish time, in positions of a speed-1 workgroup
+        const double tol = std::max(target / 50.0, 256.0);
+        for (size_t iter = 0; iter < 4 * wgs.size(); ++iter) {
             int d = wgs[0], r = wgs[0];
             for (int w : wgs) {
-                if (load[(size_t)w] > load[(size_t)d]) d = w;
-                if (load[(size_t)w] < load[(size_t)r]) r = w;
+                if (time_of(w) > time_of(d)) d = w;
+                if (time_of(w) < time_of(r)) r = w;
             }
-            const int64_t excess = load[(size_t)d] - target, deficit = target - load[(size_t)r] - overhead;
-            if (excess < tol || deficit < 256) break;
-            int64_t move = std::min(excess, deficit) / 32 * 32;
+            const double excess = (time_of(d) - target) * speed[(size_t)d];
+            const double deficit = (target - time_of(r)) * speed[(size_t)r] - (double)overhead;
+            if (time_of(d) - target < tol || deficit < 256) break;
+            int64_t move = (int64_t)std::min(excess, deficit) / 32 * 32;
             if (move < 256) break;
             // cut the tail off the longest piece of the donor
             std::vector<Piece>& dl = lists[(size_t)d];
@@ -372,7 +389,7 @@ double assign_static(const ckv_cache* c, const std::vector<Unit>& units, int64_t
             load[(size_t)d] -= move;
             load[(size_t)r] += move + overhead;
         }
-        for (int w : wgs) worst = std::max(worst, (double)load[(size_t)w]);
+        for (int w : wgs) worst = std::max(worst, time_of(w));
     }
     int parts = 0;
     for (int k : pieces_of_unit)
@@ -400,6 +417,8 @@ void build_work_static(ckv_cache* c, const int32_t* lengths, const std::vector<i
             }
     const int64_t overhead = 192;  // per-item fill, drain and epilogue, in positions
     const double part_positions = (double)c->QB * (d_a + 2) * 8.0 / (2.0 * d_a * 2.0 + 8.0);
+    double slow_speed = 0.75;  // speed of a workgroup that shares its SIMDs with an older one (see assign_static)
+    if (const char* e = getenv("CKV_DMA_SLOW_SPEED")) slow_speed = atof(e);  // tuning knob
     std::vector<std::vector<Piece>> best;
     double best_cost = -1;
     int64_t best_piece = 0;
@@ -407,7 +426,7 @@ void build_work_static(ckv_cache* c, const int32_t* lengths, const std::vector<i
         if (piece != INT64_MAX) piece = (piece + 63) / 64 * 64;
         std::vector<std::vector<Piece>> lists;
         int parts = 0;
-        const double cost = assign_static(c, units, piece, slots, overhead, part_positions, lists, &parts);
+        const double cost = assign_static(c, units, piece, slots, cus, slow_speed, overhead, part_positions, lists, &parts);
         if (best_cost < 0 || cost < best_cost) {
             best_cost = cost;
             best.swap(lists);
