@@ -509,6 +509,7 @@ void choose_variant(ckv_cache* c) {
     int ncb = (d_a + 16 * c->vec - 1) / (16 * c->vec);
     c->ncb = ncb <= 1 ? 1 : (ncb <= 2 ? 2 : (ncb <= 4 ? 4 : 8));
     c->QB = s.Nq;
+    c->nw = 4;  // wavefronts per item; cache_finish drops to 2 when the items outnumber the resident workgroups
     snprintf(c->variant, sizeof c->variant, "stream_%s_v%d_c%d_%s", s.dtype == CKV_F32 ? "f32" : "bf16", c->vec,
              c->ncb, s.mode == CKV_SOFTMAX ? "softmax" : "silu");
 }
@@ -648,6 +649,17 @@ static int cache_finish(ckv_cache* c, const int32_t* lengths, const std::vector<
     }
     c->n_items = (int)items.size();
     c->n_merge = (int)merges.size();
+    if (c->family == CKV_K_STREAM && c->ncb == 1) {
+        // The kernel holds a tile in registers, which leaves room for four wavefronts per SIMD at 8 bytes per
+        // lane and row and two at 16.  Four wavefronts per item give the shortest chain for one item; when
+        // that needs more than one round of workgroups but two per item fit in a single round, two are faster.
+        const int64_t resident = (int64_t)prop.multiProcessorCount * 4 * (esize(c->shape.dtype) * (size_t)c->vec <= 8 ? 4 : 2);
+        if ((int64_t)c->n_items * 4 > resident && (int64_t)c->n_items * 2 <= resident) {
+            c->nw = 2;
+            const size_t len = strlen(c->variant);
+            if (len + 4 < sizeof c->variant) memcpy(c->variant + len, "_w2", 4);
+        }
+    }
     if (c->n_items > 0) {
         CKV_HIP(hipMalloc((void**)&c->d_items, sizeof(ckv_item) * items.size()));
         CKV_HIP(hipMemcpyAsync(c->d_items, items.data(), sizeof(ckv_item) * items.size(), hipMemcpyHostToDevice, st));

@@ -1,10 +1,10 @@
 // Streaming (vector-ALU) gather-concat-attend kernel: the path for few queries per user
 // (target attention, Q in R^{1 x d}, section 2.1) and the general fallback for any shape.
 //
-// A workgroup of four 64-lane wavefronts serves one work item (a run of positions of one user
-// and head) for every query of the block, one query after the other.  A tile is 64 positions;
-// wavefront w takes tiles w, w+4, ... and the four partial results (maximum, sum, weighted sum)
-// are merged through LDS.  Sixteen
+// A workgroup of four (or two) 64-lane wavefronts serves one work item (a run of positions of one
+// user and head) for every query of the block, one query after the other.  A tile is 64 positions;
+// wavefront w takes tiles w, w+4, ... and the partial results (maximum, sum, weighted sum) are
+// merged through LDS.  Sixteen
 // lanes share one final K (or V) row: lane c of the group owns the columns
 // (cb*16 + c)*VEC .. +VEC of every column block cb, taken from the user slice when the
 // column is < d_u and from the gathered pool row otherwise (eq. "eq: Kc", "eq: K": the
@@ -18,7 +18,6 @@ namespace {
 
 constexpr int kLanes = 64;
 constexpr int kGroup = 16;  // lanes per row
-constexpr int kWaves = 4;   // wavefronts per work item
 
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
@@ -55,8 +54,16 @@ __device__ __forceinline__ void load_vec(float (&dst)[VEC], const T* src) {
     for (int i = 0; i < VEC; ++i) dst[i] = Elem<T>::up(p.v[i]);
 }
 
-template <typename T, int VEC, int NCB, int MODE>
-__global__ __launch_bounds__(kLanes * kWaves) void ckv_stream_kernel(ckv_args a) {
+// Wavefronts per SIMD the register budget is sized for: a whole tile of K and V rows is held in registers
+// (one column block), which costs 64 registers at 8 bytes per lane and row and 128 at 16 bytes.
+template <typename T, int VEC, int NCB>
+constexpr int stream_waves() { return NCB == 1 ? (sizeof(T) * VEC <= 8 ? 4 : 2) : 1; }
+
+// kWaves = wavefronts per work item (2 or 4): four shorten the chain of one item, two let twice as many
+// items be resident at once; the host takes two when four would need more than one round of workgroups.
+template <typename T, int VEC, int NCB, int MODE, int kWaves>
+__global__ __launch_bounds__(kLanes * kWaves)
+__attribute__((amdgpu_waves_per_eu(stream_waves<T, VEC, NCB>(), 8))) void ckv_stream_kernel(ckv_args a) {
     __shared__ float sm_acc[kWaves][NCB * kGroup * VEC];
     __shared__ float sm_ml[kWaves][2];
     const ckv_item it = a.items[blockIdx.x];
@@ -103,8 +110,64 @@ __global__ __launch_bounds__(kLanes * kWaves) void ckv_stream_kernel(ckv_args a)
             const int myslot = min(slot_of_lane, nt - 1);
             const int my_ik = a.d_gk > 0 ? ik[t0 + myslot] : 0;
             const int my_iv = a.d_gv > 0 ? iv[t0 + myslot] : 0;
-            // ---- scores
             float s_mine = 0.f;
+            float w;
+            if (NCB == 1 && (sizeof(T) * VEC <= 8 || sizeof(T) == 4)) {
+                // One column block: the whole tile's K and V rows (16 steps of four rows) are requested
+                // before anything is computed, so that a tile costs one memory round trip after its
+                // indices instead of one per group of steps.  Steps past the end of the tile read a
+                // clamped position and are masked by their zero weight.
+                Pack<T, VEC> kraw[16], vraw[16];
+                const bool own = col[0] >= 0;
+                const int c0 = own ? col[0] : 0;
+#pragma unroll
+                for (int t = 0; t < 16; ++t) {
+                    const int pos = min(4 * t + r, nt - 1);
+                    const int src_lane = (lane & 48) | t;
+                    const int rowk = __shfl(my_ik, src_lane, kLanes);
+                    const int rowv = __shfl(my_iv, src_lane, kLanes);
+                    const T* ksrc = c0 < d_uk ? uk + (int64_t)(t0 + pos) * d_uk + c0 : pk + (int64_t)rowk * a.pool_ld + (c0 - d_uk);
+                    const T* vsrc = c0 < d_uv ? uv + (int64_t)(t0 + pos) * d_uv + c0 : pv + (int64_t)rowv * a.pool_ld + (c0 - d_uv);
+                    if (own) {
+                        kraw[t] = *reinterpret_cast<const Pack<T, VEC>*>(ksrc);
+                        vraw[t] = *reinterpret_cast<const Pack<T, VEC>*>(vsrc);
+                    } else {
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) kraw[t].v[v] = vraw[t].v[v] = T(0);
+                    }
+                }
+#pragma unroll
+                for (int t = 0; t < 16; ++t) {
+                    float part = 0.f;
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) part = fmaf(Elem<T>::up(kraw[t].v[v]), qreg[0][v], part);
+#pragma unroll
+                    for (int o = 8; o > 0; o >>= 1) part += __shfl_xor(part, o, kLanes);
+                    if (c == t) s_mine = part;
+                }
+                const bool valid = slot_of_lane < nt;
+                if (MODE == CKV_SOFTMAX) {
+                    const float sv = valid ? s_mine * a.scale : -INFINITY;
+                    const float m_new = fmaxf(m_run, wave_max(sv));
+                    const float alpha = __expf(m_run - m_new);  // first tile: exp(-inf) = 0
+                    w = valid ? __expf(sv - m_new) : 0.f;
+                    l_run = l_run * alpha + wave_sum(w);
+                    m_run = m_new;
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) acc[0][v] *= alpha;
+                } else {
+                    const float sv = s_mine * a.scale;
+                    w = valid ? sv / (1.f + __expf(-sv)) : 0.f;
+                }
+#pragma unroll
+                for (int t = 0; t < 16; ++t) {
+                    const float wr = __shfl(w, (lane & 48) | t, kLanes);
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) acc[0][v] = fmaf(wr, Elem<T>::up(vraw[t].v[v]), acc[0][v]);
+                }
+                continue;
+            }
+            // ---- scores
             for (int tb = 0; tb < nsteps; tb += 4)
 #pragma unroll
             for (int t = tb; t < tb + 4; ++t) {  // steps past nsteps touch clamped, masked positions
@@ -128,7 +191,6 @@ __global__ __launch_bounds__(kLanes * kWaves) void ckv_stream_kernel(ckv_args a)
             }
             // ---- weights
             const bool valid = slot_of_lane < nt;
-            float w;
             if (MODE == CKV_SOFTMAX) {
                 const float s = valid ? s_mine * a.scale : -INFINITY;
                 const float m_new = fmaxf(m_run, wave_max(s));
@@ -240,14 +302,19 @@ __global__ __launch_bounds__(kLanes * kWaves) void ckv_stream_kernel(ckv_args a)
     }
 }
 
+template <typename T, int VEC, int NCB, int NWV>
+hipError_t launch_waves(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
+    dim3 grid(c->n_items), block(kLanes * NWV);
+    if (c->shape.mode == CKV_SOFTMAX)
+        hipLaunchKernelGGL((ckv_stream_kernel<T, VEC, NCB, CKV_SOFTMAX, NWV>), grid, block, 0, s, a);
+    else
+        hipLaunchKernelGGL((ckv_stream_kernel<T, VEC, NCB, CKV_SILU_OVER_N, NWV>), grid, block, 0, s, a);
+    return hipGetLastError();
+}
+
 template <typename T, int VEC, int NCB>
 hipError_t launch_mode(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
-    dim3 grid(c->n_items), block(kLanes * kWaves);
-    if (c->shape.mode == CKV_SOFTMAX)
-        hipLaunchKernelGGL((ckv_stream_kernel<T, VEC, NCB, CKV_SOFTMAX>), grid, block, 0, s, a);
-    else
-        hipLaunchKernelGGL((ckv_stream_kernel<T, VEC, NCB, CKV_SILU_OVER_N>), grid, block, 0, s, a);
-    return hipGetLastError();
+    return c->nw == 2 ? launch_waves<T, VEC, NCB, 2>(c, a, s) : launch_waves<T, VEC, NCB, 4>(c, a, s);
 }
 
 template <typename T, int VEC>
