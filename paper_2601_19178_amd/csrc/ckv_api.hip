@@ -480,7 +480,7 @@ void choose_variant(ckv_cache* c) {
             // wavefronts per SIMD overlap better than one wavefront with two query groups)
             int nw = s.Nq <= 32 ? 1 : (s.Nq <= 64 ? 2 : 4), qg = 1;
             if (const char* shp = getenv("CKV_DMA_SHAPE")) sscanf(shp, "%d,%d", &nw, &qg);  // tuning knob "nw,qg"
-            const int nui = s.d_g > 0 && s.share == CKV_SHARE_KV && ckv_dma_supported(d_a, nw, qg) ? ckv_dma_nui(d_a, nw, s.d_u) : -1;
+            const int nui = s.d_g > 0 && ckv_dma_supported(d_a, nw, qg) ? ckv_dma_nui(d_a, nw, s.d_u) : -1;
             if (nui >= 0 && !(impl && strcmp(impl, "staged") == 0)) {
                 c->family = CKV_K_DMA;
                 c->nw = nw;

@@ -143,6 +143,12 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
     }
     const int qn = lane & 31, hh = lane >> 5;
     const int d_g = a.d_g, d_u = a.d_u;
+    // A side that is not shared (only keys or only values gather from a pool) keeps whole d_a-wide rows in
+    // its user array: its tile rows are fetched from there, position by position, with the same
+    // instructions that fetch pool rows for a shared side, and it has no user slice to append.
+    const bool ksh = a.d_gk > 0, vsh = a.d_gv > 0;
+    const int dgk = ksh ? d_g : DA, duk = DA - dgk;  // pool and user columns of a K row in LDS
+    const int dgv = vsh ? d_g : DA, duv = DA - dgv;
     const int n = it.n;
 
     const int64_t hT = (int64_t)it.h * a.T + it.t0;
@@ -150,9 +156,12 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
     const int32_t* __restrict__ iv = a.idx_v + hT;
     const uint32_t* __restrict__ uk32 = (const uint32_t*)((const uint16_t*)a.user_k + hT * d_u);
     const uint32_t* __restrict__ uv32 = (const uint32_t*)((const uint16_t*)a.user_v + hT * d_u);
-    const unsigned char* __restrict__ pk = (const unsigned char*)a.pool_k + (int64_t)it.h * a.P * a.pool_ld * 2;
-    const unsigned char* __restrict__ pv = (const unsigned char*)a.pool_v + (int64_t)it.h * a.P * a.pool_ld * 2;
-    const uint32_t row_bytes = (uint32_t)a.pool_ld * 2;
+    const unsigned char* __restrict__ pk = ksh ? (const unsigned char*)a.pool_k + (int64_t)it.h * a.P * a.pool_ld * 2
+                                               : (const unsigned char*)a.user_k + hT * (DA * 2);
+    const unsigned char* __restrict__ pv = vsh ? (const unsigned char*)a.pool_v + (int64_t)it.h * a.P * a.pool_ld * 2
+                                               : (const unsigned char*)a.user_v + hT * (DA * 2);
+    const uint32_t krow_bytes = ksh ? (uint32_t)a.pool_ld * 2 : (uint32_t)(DA * 2);
+    const uint32_t vrow_bytes = vsh ? (uint32_t)a.pool_ld * 2 : (uint32_t)(DA * 2);
 
     // ---- queries: the wavefront's 32*QG query rows are copied row-major into LDS with
     //      coalesced 16-byte loads, then every lane picks its B operands (kernel column order
@@ -180,7 +189,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int ci = 16 * kk + 8 * hh + 2 * j;
-                    const int pc = ci < d_g ? ci + d_u : ci - d_g;
+                    const int pc = ci < dgk ? ci + duk : ci - dgk;
                     w[j] = *(const lds_u32*)(uintptr_t)(qlds + (g * 32 + qn) * QS + pc * 2);
                 }
                 qreg[g][kk] = __builtin_bit_cast(bf16x8, w);
@@ -220,8 +229,8 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
             gp[i] = (i * NW + wave) * G::RPI + lane / G::CH;
             int ck = gslot ^ fk<DA>(gp[i]);
             int cv = gslot ^ fv<DA>(gp[i]);
-            if (ck * 8 >= d_g) ck = 0;  // a pure user chunk: fetch something valid, the concat overwrites it
-            if (cv * 8 >= d_g) cv = 0;
+            if (ck * 8 >= dgk) ck = 0;  // a pure user chunk: fetch something valid, the concat overwrites it
+            if (cv * 8 >= dgv) cv = 0;
             gk_off[i] = ck * 16;
             gv_off[i] = cv * 16;
         }
@@ -243,6 +252,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
             const int slice = jj / hd;            // kv * ROWS_W + o
             uoff[u] = jj - slice * hd;
             uisv[u] = slice >= ROWS_W;
+            uok[u] = uok[u] && (uisv[u] ? vsh : ksh);  // nothing to append on a side that is not shared
             const int o = uisv[u] ? slice - ROWS_W : slice;
             up[u] = ((o / G::RPI) * NW + wave) * G::RPI + (o % G::RPI);
             const int col = d_g + 2 * uoff[u];
@@ -269,14 +279,15 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
             int rk[G::NI], rv[G::NI];
 #pragma unroll
             for (int i = 0; i < G::NI; ++i) {
-                rk[i] = islot[gp[i]];
-                rv[i] = islot[32 + gp[i]];
+                const int pos = min(tile * TP + gp[i], n - 1);
+                rk[i] = ksh ? (int)islot[gp[i]] : pos;
+                rv[i] = vsh ? (int)islot[32 + gp[i]] : pos;
             }
 #pragma unroll
             for (int i = 0; i < G::NI; ++i) {
                 const uint32_t dst = (i * NW + wave) * G::RPI * G::ROWB;
-                dma16(pk + (uint64_t)(uint32_t)rk[i] * row_bytes + gk_off[i], st + dst);
-                dma16(pv + (uint64_t)(uint32_t)rv[i] * row_bytes + gv_off[i], st + G::KV + dst);
+                dma16(pk + (uint64_t)(uint32_t)rk[i] * krow_bytes + gk_off[i], st + dst);
+                dma16(pv + (uint64_t)(uint32_t)rv[i] * vrow_bytes + gv_off[i], st + G::KV + dst);
             }
 #pragma unroll
             for (int u = 0; u < G::NUI_MAX; ++u) {
@@ -427,7 +438,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
 #pragma unroll
                 for (int r = 0; r < 16; r += 2) {
                     const int ci = 32 * dt + 8 * (r >> 2) + 4 * hh + (r & 3);
-                    const int pc = ci < d_g ? ci + d_u : ci - d_g;
+                    const int pc = ci < dgv ? ci + duv : ci - dgv;
                     const uint32_t two = (uint32_t)f2bf(oacc[g][dt][r] * inv) | ((uint32_t)f2bf(oacc[g][dt][r + 1] * inv) << 16);
                     *(lds_u32*)(uintptr_t)(qlds + (g * 32 + qn) * QS + pc * 2) = two;
                 }
@@ -449,7 +460,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int ci = 32 * dt + 8 * (r >> 2) + 4 * hh + (r & 3);
-                    const int pc = ci < d_g ? ci + d_u : ci - d_g;
+                    const int pc = ci < dgv ? ci + duv : ci - dgv;
                     ws[(int64_t)j * DA + pc] = oacc[g][dt][r];
                 }
             if (hh == 0) {

@@ -182,6 +182,11 @@ def test_config3_full(gpu):
     run_and_check(gpu, w, "cfg3", users=sampled_users(w["B"], 24, 3), expect_variant="mfma_dma_bf16_d64_w2_g1")
 
 
+def test_config3_keys_only_full(gpu):
+    w = wl.config("cfg3_ck")
+    run_and_check(gpu, w, "cfg3_ck", users=sampled_users(w["B"], 16, 6), expect_variant="mfma_dma_bf16_d64_w2")
+
+
 def test_config4_full(gpu):
     w = wl.config("cfg4")
     users = sampled_users(w["B"], 3, 4)
@@ -253,17 +258,23 @@ def test_single_side_sharing_stream(gpu, share, dtype, mode):
     run_and_check(gpu, w, f"stream unaligned share={share} dtype={dtype} mode={mode}", expect_variant="stream")
 
 
+@pytest.mark.parametrize("impl", [None, "staged"])
 @pytest.mark.parametrize("share", [wl.SHARE_K, wl.SHARE_V])
 @pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
-@pytest.mark.parametrize("d_a,d_u,Nq", [(64, 4, 64), (128, 8, 128), (64, 3, 20), (128, 16, 40)])
-def test_single_side_sharing_matrix_core(gpu, share, mode, d_a, d_u, Nq):
+@pytest.mark.parametrize("d_a,d_u,Nq", [(64, 4, 64), (128, 8, 128), (64, 3, 20), (128, 16, 40), (64, 2, 16), (128, 0, 32)])
+def test_single_side_sharing_matrix_core(gpu, impl, share, mode, d_a, d_u, Nq):
     w = make(MFMA_LENGTHS, wl.BF16, mode, d_a=d_a, d_u=d_u, H=2, P=700, Nq=Nq, share=share)
-    run_and_check(gpu, w, f"mfma share={share} d_a={d_a} d_u={d_u} Nq={Nq} mode={mode}", expect_variant="mfma_bf16")
+    dma_ok = d_u % 2 == 0 and d_u <= 8
+    expect = "mfma_dma" if (impl is None and dma_ok) else "mfma_bf16"
+    run_and_check(gpu, w, f"mfma share={share} d_a={d_a} d_u={d_u} Nq={Nq} mode={mode} impl={impl}", expect_variant=expect, impl=impl)
 
 
-def test_single_side_sharing_split_history(gpu):
+@pytest.mark.parametrize("impl", [None, "staged"])
+def test_single_side_sharing_split_history(gpu, impl):
     w = make((5000, 70, 2300, 1025), wl.BF16, wl.SOFTMAX, d_a=128, d_u=8, H=2, P=5000, Nq=128, share=wl.SHARE_K)
-    run_and_check(gpu, w, "mfma split share=K", expect_variant="mfma_bf16")
+    run_and_check(gpu, w, f"mfma split share=K impl={impl}", expect_variant="mfma", impl=impl)
+    w = make((5000, 70, 2300, 1025), wl.BF16, wl.SILU_OVER_N, d_a=64, d_u=4, H=2, P=5000, Nq=64, share=wl.SHARE_V)
+    run_and_check(gpu, w, f"mfma split share=V impl={impl}", expect_variant="mfma", impl=impl)
     w = make((5000, 70, 2300), wl.F32, wl.SOFTMAX, d_a=64, d_u=8, H=2, P=500, Nq=2, share=wl.SHARE_V)
     run_and_check(gpu, w, "stream split share=V", expect_variant="stream")
 
