@@ -293,6 +293,29 @@ def test_out_of_range_index_is_rejected(gpu):
         session.Session(w)
 
 
+def test_attend_rejects_unaligned_and_missing_pointers(gpu):
+    ckv, session = gpu
+    w = make((10, 20), wl.BF16, wl.SOFTMAX, d_a=64, d_u=8, H=1, P=50, Nq=16)
+    with session.Session(w) as s:
+        c = s.cache
+        args = [s.pool_k, s.pool_v, ckv.ckv_cache_idx(c), ckv.ckv_cache_user_k(c), ckv.ckv_cache_user_v(c), s.q,
+                ckv.ckv_cache_lengths(c), s.out]
+        for i, code in ((5, ckv.CKV_ERR_UNSUPPORTED), (7, ckv.CKV_ERR_UNSUPPORTED)):
+            bad = list(args)
+            bad[i] = bad[i].data_ptr() + 2
+            with pytest.raises(ckv.CkvError) as e:
+                ckv.ckv_attend(c, *bad, s.stream)
+            assert e.value.code == code
+        for i in (0, 2, 3, 5, 7):
+            bad = list(args)
+            bad[i] = None
+            with pytest.raises(ckv.CkvError) as e:
+                ckv.ckv_attend(c, *bad, s.stream)
+            assert e.value.code == ckv.CKV_ERR_NULL
+        s.attend()  # the handle is still usable
+        check(s.output(), oracle.attend(w), w["dtype"], what="after rejected calls")
+
+
 def test_all_histories_empty(gpu):
     w = make((0, 0, 0), wl.BF16, wl.SOFTMAX, d_a=64, d_u=8, H=2, P=10, Nq=16)
     out = run_and_check(gpu, w, "all empty")
