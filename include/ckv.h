@@ -206,6 +206,23 @@ int ckv_attend(const ckv_cache* cache, const void* pool_k, const void* pool_v,
 int ckv_reconstruct(const ckv_cache* cache, const void* pool_k, const void* pool_v,
                     void* k_full, void* v_full, void* stream);
 
+/*
+ * Host only (no device is touched): the work lists ckv_build_cache would attach to a handle of this shape
+ * and these lengths on a GPU with `cus` compute units that keeps `wg_per_cu` workgroups of the chosen
+ * kernel resident per unit.  One record of 8 int64 per work item, in launch order:
+ *   [0] user b  [1] head h  [2] first query q0 of the block  [3] positions n of the piece
+ *   [4] first flattened position t0  [5] slot in the split workspace, or -1 for a whole history
+ *   [6] the user's full length n_b  [7] workgroup that runs the item
+ * Every (user, head, query block) is covered by pieces that tile [0, n_b) exactly once; pieces of a split
+ * history carry consecutive workspace slots in position order.  Up to max_records records are written
+ * (records may be NULL); the return value is the total number of items, or a negative CKV_ERR_* code.
+ * n_workgroups receives the number of workgroups launched, variant (if not NULL) the kernel name.
+ * Exists so that the scheduling arithmetic can be checked without a GPU.
+ */
+int64_t ckv_plan(const ckv_shape* shape, const int32_t* lengths, int cus, int wg_per_cu,
+                 int64_t* records, int64_t max_records, int32_t* n_workgroups,
+                 char* variant, size_t variant_size);
+
 /* Release the handle and the device memory it owns.  NULL is allowed. */
 void ckv_free(ckv_cache* cache);
 

@@ -21,7 +21,7 @@ CKV_OK, CKV_ERR_NULL, CKV_ERR_SHAPE, CKV_ERR_INDEX, CKV_ERR_LENGTH, CKV_ERR_UNSU
 
 EXPORTS = [
     "ckv_build_cache", "ckv_build_cache_offloaded", "ckv_cache_is_offloaded", "ckv_prefill", "ckv_prefill_into",
-    "ckv_prefill_kernel_name", "ckv_cache_idx", "ckv_cache_user_k", "ckv_cache_user_v", "ckv_cache_lengths",
+    "ckv_prefill_kernel_name", "ckv_plan", "ckv_cache_idx", "ckv_cache_user_k", "ckv_cache_user_v", "ckv_cache_lengths",
     "ckv_cache_positions", "ckv_cache_stored_bytes", "ckv_attend", "ckv_reconstruct", "ckv_free",
     "ckv_last_error", "ckv_set_timing", "ckv_kernel_ms", "ckv_variant", "ckv_copy", "ckv_trace_enable", "ckv_trace_read",
 ]
@@ -60,6 +60,9 @@ _lib.ckv_prefill_into.restype = ctypes.c_int
 _lib.ckv_prefill_into.argtypes = [_vp, ctypes.POINTER(ckv_router), _vp, _vp]
 _lib.ckv_prefill_kernel_name.restype = ctypes.c_char_p
 _lib.ckv_prefill_kernel_name.argtypes = [ctypes.POINTER(ckv_shape), ctypes.POINTER(ckv_router)]
+_lib.ckv_plan.restype = _i64
+_lib.ckv_plan.argtypes = [ctypes.POINTER(ckv_shape), _vp, ctypes.c_int, ctypes.c_int, _vp, _i64, ctypes.POINTER(_i32), ctypes.c_char_p,
+                          ctypes.c_size_t]
 _lib.ckv_cache_is_offloaded.restype = ctypes.c_int
 _lib.ckv_cache_is_offloaded.argtypes = [_vp]
 for _n in ("ckv_cache_idx", "ckv_cache_user_k", "ckv_cache_user_v", "ckv_cache_lengths"):
@@ -155,6 +158,21 @@ def ckv_prefill_into(cache, router, S, stream=0):
 
 def ckv_prefill_kernel_name(shape, router):
     return _lib.ckv_prefill_kernel_name(ctypes.byref(shape), ctypes.byref(router)).decode()
+
+
+def ckv_plan(shape, lengths, cus=256, wg_per_cu=2):
+    """Host only: (records int64 [n][8], number of workgroups, kernel name) of the work lists for this shape."""
+    keep = _host(lengths, np.int32)
+    nwg = _i32(0)
+    name = ctypes.create_string_buffer(96)
+    n = _lib.ckv_plan(ctypes.byref(shape), keep[1], cus, wg_per_cu, _vp(0), 0, ctypes.byref(nwg), name, 96)
+    if n < 0:
+        raise CkvError(int(n), ckv_last_error())
+    rec = np.zeros((max(int(n), 1), 8), dtype=np.int64)
+    n = _lib.ckv_plan(ctypes.byref(shape), keep[1], cus, wg_per_cu, _vp(rec.ctypes.data), int(n), ctypes.byref(nwg), name, 96)
+    if n < 0:
+        raise CkvError(int(n), ckv_last_error())
+    return rec[:n], int(nwg.value), name.value.decode()
 
 
 def ckv_cache_is_offloaded(cache):

@@ -230,14 +230,20 @@ int64_t simulate_dispatch(const std::vector<ckv_item>& items, int64_t slots, int
     return makespan;
 }
 
-void build_work(ckv_cache* c, const int32_t* lengths, const std::vector<int64_t>& offs, int cus,
+// Resident workgroups per CU of the handle's kernel, asked of the runtime (needs a device).
+int resident_workgroups(const ckv_cache* c) {
+    const ckv_shape& s = c->shape;
+    const int d_a = s.d_g + s.d_u;
+    if (c->family == CKV_K_MFMA) return std::max(1, ckv_mfma_occupancy(d_a, c->nw, c->tp, s.mode));
+    if (c->family == CKV_K_DMA) return std::max(1, ckv_dma_occupancy(d_a, c->nw, c->qg, s.mode));
+    return 8;
+}
+
+void build_work(ckv_cache* c, const int32_t* lengths, const std::vector<int64_t>& offs, int cus, int wg_per_cu,
                 std::vector<ckv_item>& items, std::vector<ckv_merge>& merges) {
     const ckv_shape& s = c->shape;
     const int d_a = s.d_g + s.d_u;
     const int nqb = (s.Nq + c->QB - 1) / c->QB;
-    int wg_per_cu = 8;
-    if (c->family == CKV_K_MFMA) wg_per_cu = std::max(1, ckv_mfma_occupancy(d_a, c->nw, c->tp, s.mode));
-    if (c->family == CKV_K_DMA) wg_per_cu = std::max(1, ckv_dma_occupancy(d_a, c->nw, c->qg, s.mode));
     const int64_t slots = (int64_t)cus * wg_per_cu;
     std::vector<Unit> units;
     units.reserve((size_t)s.B * s.H * nqb);
@@ -400,12 +406,11 @@ double assign_static(const ckv_cache* c, const std::vector<Unit>& units, int64_t
     return cost;
 }
 
-void build_work_static(ckv_cache* c, const int32_t* lengths, const std::vector<int64_t>& offs, int cus,
+void build_work_static(ckv_cache* c, const int32_t* lengths, const std::vector<int64_t>& offs, int cus, int wg_per_cu,
                        std::vector<ckv_item>& items, std::vector<ckv_merge>& merges, std::vector<int32_t>& wg_begin) {
     const ckv_shape& s = c->shape;
     const int d_a = s.d_g + s.d_u;
     const int nqb = (s.Nq + c->QB - 1) / c->QB;
-    const int wg_per_cu = std::max(1, ckv_dma_occupancy(d_a, c->nw, c->qg, s.mode));
     const int64_t slots = (int64_t)cus * wg_per_cu;
     std::vector<Unit> units;
     int64_t longest = 0;
@@ -619,13 +624,16 @@ done:
     return CKV_OK;
 }
 
-// Build and upload the work lists (and the split workspace) of a handle whose packed cache is in place.
-static int cache_finish(ckv_cache* c, const int32_t* lengths, const std::vector<int64_t>& offs, const hipDeviceProp_t& prop,
-                        hipStream_t st) {
-    int rc = CKV_OK;
-    const int64_t d_a = (int64_t)c->shape.d_g + c->shape.d_u;
+// The work lists of a handle: items (in workgroup order for the persistent kernel), merge entries of split
+// histories, and for the persistent kernel the first item of every workgroup.  Host arithmetic only.
+struct ckv_plan_lists {
     std::vector<ckv_item> items;
     std::vector<ckv_merge> merges;
+    std::vector<int32_t> wg_begin;  // persistent kernel only
+};
+
+static void plan_work(ckv_cache* c, const int32_t* lengths, const std::vector<int64_t>& offs, int cus, int wg_per_cu,
+                      ckv_plan_lists& p) {
     if (c->family == CKV_K_DMA) {
         // Two ways to hand out work.  Static (default): one resident workgroup per slot with its
         // own item list, no relaunch gaps.  Dynamic: one workgroup per item in longest-first order,
@@ -633,32 +641,44 @@ static int cache_finish(ckv_cache* c, const int32_t* lengths, const std::vector<
         // workload (uniform lengths: by 20 %; two long ragged histories per slot: by 2 %).
         bool use_static = true;
         if (const char* e = getenv("CKV_DMA_SCHED")) use_static = strcmp(e, "static") == 0;  // tuning knob
-        std::vector<int32_t> wg_begin;
         if (use_static) {
-            build_work_static(c, lengths, offs, prop.multiProcessorCount, items, merges, wg_begin);
+            build_work_static(c, lengths, offs, cus, wg_per_cu, p.items, p.merges, p.wg_begin);
         } else {
-            build_work(c, lengths, offs, prop.multiProcessorCount, items, merges);
-            wg_begin.resize(items.size() + 1);
-            for (size_t i = 0; i <= items.size(); ++i) wg_begin[i] = (int32_t)i;
+            build_work(c, lengths, offs, cus, wg_per_cu, p.items, p.merges);
+            p.wg_begin.resize(p.items.size() + 1);
+            for (size_t i = 0; i <= p.items.size(); ++i) p.wg_begin[i] = (int32_t)i;
         }
-        c->n_wg = (int)wg_begin.size() - 1;
-        CKV_HIP(hipMalloc((void**)&c->d_wg_begin, sizeof(int32_t) * wg_begin.size()));
-        CKV_HIP(hipMemcpy(c->d_wg_begin, wg_begin.data(), sizeof(int32_t) * wg_begin.size(), hipMemcpyHostToDevice));
+        c->n_wg = (int)p.wg_begin.size() - 1;
     } else {
-        build_work(c, lengths, offs, prop.multiProcessorCount, items, merges);
+        build_work(c, lengths, offs, cus, wg_per_cu, p.items, p.merges);
     }
-    c->n_items = (int)items.size();
-    c->n_merge = (int)merges.size();
+    c->n_items = (int)p.items.size();
+    c->n_merge = (int)p.merges.size();
     if (c->family == CKV_K_STREAM && c->ncb == 1) {
         // The kernel holds a tile in registers, which leaves room for four wavefronts per SIMD at 8 bytes per
         // lane and row and two at 16.  Four wavefronts per item give the shortest chain for one item; when
         // that needs more than one round of workgroups but two per item fit in a single round, two are faster.
-        const int64_t resident = (int64_t)prop.multiProcessorCount * 4 * (esize(c->shape.dtype) * (size_t)c->vec <= 8 ? 4 : 2);
+        const int64_t resident = (int64_t)cus * 4 * (esize(c->shape.dtype) * (size_t)c->vec <= 8 ? 4 : 2);
         if ((int64_t)c->n_items * 4 > resident && (int64_t)c->n_items * 2 <= resident) {
             c->nw = 2;
             const size_t len = strlen(c->variant);
             if (len + 4 < sizeof c->variant) memcpy(c->variant + len, "_w2", 4);
         }
+    }
+}
+
+// Build and upload the work lists (and the split workspace) of a handle whose packed cache is in place.
+static int cache_finish(ckv_cache* c, const int32_t* lengths, const std::vector<int64_t>& offs, const hipDeviceProp_t& prop,
+                        hipStream_t st) {
+    int rc = CKV_OK;
+    const int64_t d_a = (int64_t)c->shape.d_g + c->shape.d_u;
+    ckv_plan_lists plan;
+    plan_work(c, lengths, offs, prop.multiProcessorCount, resident_workgroups(c), plan);
+    std::vector<ckv_item>& items = plan.items;
+    std::vector<ckv_merge>& merges = plan.merges;
+    if (c->family == CKV_K_DMA) {
+        CKV_HIP(hipMalloc((void**)&c->d_wg_begin, sizeof(int32_t) * plan.wg_begin.size()));
+        CKV_HIP(hipMemcpy(c->d_wg_begin, plan.wg_begin.data(), sizeof(int32_t) * plan.wg_begin.size(), hipMemcpyHostToDevice));
     }
     if (c->n_items > 0) {
         CKV_HIP(hipMalloc((void**)&c->d_items, sizeof(ckv_item) * items.size()));
@@ -848,6 +868,48 @@ int ckv_prefill(const ckv_shape* shape, const ckv_router* router, const int32_t*
 const char* ckv_prefill_kernel_name(const ckv_shape* shape, const ckv_router* router) {
     if (!shape || !router) return "";
     return ckv_prefill_variant(shape->dtype, router->d_e);
+}
+
+int64_t ckv_plan(const ckv_shape* shape, const int32_t* lengths, int cus, int wg_per_cu, int64_t* records, int64_t max_records,
+                 int32_t* n_workgroups, char* variant, size_t variant_size) {
+    if (!shape || !lengths) return fail(CKV_ERR_NULL, "ckv_plan: shape and lengths must not be NULL");
+    if (cus < 1 || wg_per_cu < 1) return fail(CKV_ERR_SHAPE, "ckv_plan: cus and wg_per_cu must be >= 1");
+    const ckv_shape s = *shape;
+    if (s.B < 1 || s.H < 1 || s.d_g < 0 || s.d_u < 0 || s.d_g + s.d_u < 1 || s.Nq < 1 || s.share < CKV_SHARE_KV || s.share > CKV_SHARE_V)
+        return fail(CKV_ERR_SHAPE, "ckv_plan: bad shape");
+    std::vector<int64_t> offs((size_t)s.B + 1, 0);
+    for (int b = 0; b < s.B; ++b) {
+        if (lengths[b] < 0) return fail(CKV_ERR_LENGTH, "ckv_plan: lengths[%d] = %d is negative", b, lengths[b]);
+        offs[(size_t)b + 1] = offs[(size_t)b] + lengths[b];
+    }
+    ckv_cache c;
+    memset(&c, 0, sizeof c);
+    c.shape = s;
+    c.T = offs[(size_t)s.B];
+    choose_variant(&c);
+    ckv_plan_lists plan;
+    plan_work(&c, lengths, offs, cus, wg_per_cu, plan);
+    if (n_workgroups) *n_workgroups = c.family == CKV_K_DMA ? c.n_wg : c.n_items;
+    if (variant && variant_size > 0) snprintf(variant, variant_size, "%s", c.variant);
+    const int64_t n = (int64_t)plan.items.size();
+    if (records) {
+        size_t wg = 0;
+        for (int64_t i = 0; i < n && i < max_records; ++i) {
+            const ckv_item& it = plan.items[(size_t)i];
+            if (c.family == CKV_K_DMA)
+                while (wg + 1 < plan.wg_begin.size() && plan.wg_begin[wg + 1] <= i) ++wg;
+            int64_t* r = records + 8 * i;
+            r[0] = it.b;
+            r[1] = it.h;
+            r[2] = it.q0;
+            r[3] = it.n;
+            r[4] = it.t0;
+            r[5] = it.part;
+            r[6] = it.n_total;
+            r[7] = c.family == CKV_K_DMA ? (int64_t)wg : i;
+        }
+    }
+    return n;
 }
 
 int ckv_cache_is_offloaded(const ckv_cache* c) { return c ? c->offloaded : 0; }
