@@ -163,6 +163,20 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
     const uint32_t krow_bytes = ksh ? (uint32_t)a.pool_ld * 2 : (uint32_t)(DA * 2);
     const uint32_t vrow_bytes = vsh ? (uint32_t)a.pool_ld * 2 : (uint32_t)(DA * 2);
 
+    // ---- the indices of the first three tiles are requested before the queries, so that the two round
+    //      trips overlap (the index slots are private to the wavefront and apart from the query staging)
+    const uint32_t idx_lds = lds0 + NS * G::STAGE + wave * G::NIS * G::IDX;
+    auto issue_idx = [&](int tile) {
+        const int pos = min(tile * TP + qn, n - 1);
+        const int32_t* g = (hh ? iv : ik) + pos;
+        dma4(g, idx_lds + (tile & (G::NIS - 1)) * G::IDX);
+    };
+    if (n > 0) {
+        issue_idx(0);
+        issue_idx(1);
+        issue_idx(2);
+    }
+
     // ---- queries: the wavefront's 32*QG query rows are copied row-major into LDS with
     //      coalesced 16-byte loads, then every lane picks its B operands (kernel column order
     //      [pool | user], i.e. paper column + d_u for pool columns) out of LDS.
@@ -266,13 +280,6 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
         const uint32_t vrow = G::KV + (4 * hh + (s16 >> 2)) * G::ROWB + (s16 & 1) * 8;
         const int vc = 2 * (g16 & 1) + ((s16 & 3) >> 1), vx = fv<DA>(s16 >> 2);
 
-        const uint32_t idx_lds = lds0 + NS * G::STAGE + wave * G::NIS * G::IDX;
-
-        auto issue_idx = [&](int tile) {
-            const int pos = min(tile * TP + qn, n - 1);
-            const int32_t* g = (hh ? iv : ik) + pos;
-            dma4(g, idx_lds + (tile & (G::NIS - 1)) * G::IDX);
-        };
         auto issue_gather = [&](int tile) {
             const uint32_t st = lds0 + (tile & (NS - 1)) * G::STAGE;
             const lds_u32* islot = (const lds_u32*)(uintptr_t)(idx_lds + (tile & (G::NIS - 1)) * G::IDX);
@@ -317,10 +324,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
         // while one is computed, and the indices a gather needs landed at least one wait earlier.
         // After its wait the wavefront concatenates its own rows of tile t+1; the barrier then
         // publishes tile t+1 to the workgroup and retires tile t's stage.
-        issue_idx(0);
-        issue_idx(1);
-        issue_idx(2);
-        wait_vm<0>();
+        wait_vm<0>();  // the indices of tiles 0..2, requested before the queries
         if (tr && tid == 0) tr[1] = wall_clock64();
         for (int t = -(NS - 1); t < ntiles; ++t) {
             issue_idx(t + NS + 2);
