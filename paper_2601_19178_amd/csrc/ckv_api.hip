@@ -143,21 +143,27 @@ struct Unit {
     int64_t t0;
 };
 
-int pick_stream_vec(const ckv_shape& s) {
-    // widest vector the alignment allows, but no wider than what keeps all sixteen lanes of a row
-    // busy: among the admissible widths take the one with the fewest column blocks, narrowest first
+// Vector width (elements per lane) and lanes per row of the streaming kernel: among the widths the
+// alignment allows and 16 or 8 lanes per row, the pair with the fewest row-load instructions per tile
+// (steps per tile x column blocks); ties go to 16 lanes and to the narrower vector.
+void pick_stream_vec(const ckv_shape& s, int* vec, int* grp) {
     const int d_a = s.d_g + s.d_u;
-    int best = 1, best_ncb = (d_a + 15) / 16;
+    int best_v = 1, best_g = 16, best_cost = 16 * ((d_a + 15) / 16);
     for (int v : {4, 8}) {
         if (v == 8 && s.dtype == CKV_F32) continue;
         if (s.d_u % v || s.d_g % v || (s.d_g > 0 && s.pool_ld % v)) continue;  // (d_a = d_u + d_g is then a multiple too)
-        const int ncb = (d_a + 16 * v - 1) / (16 * v);
-        if (ncb < best_ncb) {
-            best = v;
-            best_ncb = ncb;
+        for (int g : {16, 8}) {
+            if (g == 8 && (size_t)v * esize(s.dtype) != 16) continue;  // eight lanes per row only with 16-byte lanes
+            const int cost = g * ((d_a + g * v - 1) / (g * v));
+            if (cost < best_cost) {
+                best_cost = cost;
+                best_v = v;
+                best_g = g;
+            }
         }
     }
-    return best;
+    *vec = best_v;
+    *grp = best_g;
 }
 
 // Cut units into pieces of at most `piece` positions and order them (see above).
@@ -510,13 +516,13 @@ void choose_variant(ckv_cache* c) {
             return;
         }
     }
-    c->vec = pick_stream_vec(s);
-    int ncb = (d_a + 16 * c->vec - 1) / (16 * c->vec);
+    pick_stream_vec(s, &c->vec, &c->grp);
+    int ncb = (d_a + c->grp * c->vec - 1) / (c->grp * c->vec);
     c->ncb = ncb <= 1 ? 1 : (ncb <= 2 ? 2 : (ncb <= 4 ? 4 : 8));
     c->QB = s.Nq;
-    c->nw = 4;  // wavefronts per item; cache_finish drops to 2 when the items outnumber the resident workgroups
-    snprintf(c->variant, sizeof c->variant, "stream_%s_v%d_c%d_%s", s.dtype == CKV_F32 ? "f32" : "bf16", c->vec,
-             c->ncb, s.mode == CKV_SOFTMAX ? "softmax" : "silu");
+    c->nw = 4;  // wavefronts per item; plan_work drops to 2 when the items outnumber the resident workgroups
+    snprintf(c->variant, sizeof c->variant, "stream_%s_v%d_c%d%s_%s", s.dtype == CKV_F32 ? "f32" : "bf16", c->vec,
+             c->ncb, c->grp == 8 ? "_g8" : "", s.mode == CKV_SOFTMAX ? "softmax" : "silu");
 }
 
 // The packed cache lives in device memory, or (offloaded handle) in pinned host memory that the
@@ -591,7 +597,7 @@ static int cache_new(const char* who, const ckv_shape* shape, const int32_t* len
     c->T = T;
     c->offloaded = offloaded ? 1 : 0;
     choose_variant(c);
-    if (c->family == CKV_K_STREAM && (d_a + 16 * c->vec - 1) / (16 * c->vec) > 8) {
+    if (c->family == CKV_K_STREAM && (d_a + c->grp * c->vec - 1) / (c->grp * c->vec) > 8) {
         const int vec = c->vec;
         delete c;
         return fail(CKV_ERR_UNSUPPORTED, "%s: d_a = %lld exceeds the streaming kernel's limit of %d columns at this alignment", who,
@@ -658,7 +664,7 @@ static void plan_work(ckv_cache* c, const int32_t* lengths, const std::vector<in
         // The kernel holds a tile in registers, which leaves room for four wavefronts per SIMD at 8 bytes per
         // lane and row and two at 16.  Four wavefronts per item give the shortest chain for one item; when
         // that needs more than one round of workgroups but two per item fit in a single round, two are faster.
-        const int64_t resident = (int64_t)cus * 4 * (esize(c->shape.dtype) * (size_t)c->vec <= 8 ? 4 : 2);
+        const int64_t resident = (int64_t)cus * 4 * ((size_t)c->grp * esize(c->shape.dtype) * (size_t)c->vec <= 128 ? 4 : 2);
         if ((int64_t)c->n_items * 4 > resident && (int64_t)c->n_items * 2 <= resident) {
             c->nw = 2;
             const size_t len = strlen(c->variant);

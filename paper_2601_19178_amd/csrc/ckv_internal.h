@@ -84,6 +84,7 @@ struct ckv_cache {
     // launch metadata
     int family;          // ckv_kernel_family
     int vec, ncb;        // stream kernel: elements per lane per column block, column blocks
+    int grp;             // stream kernel: lanes that share a row (16 or 8)
     int nw, tp;          // mfma kernels: waves per workgroup, positions per tile
     int nui;             // dma kernel: user-slice load instructions per wavefront and tile
     int qg;              // dma kernel: groups of 32 queries per wavefront

@@ -17,7 +17,6 @@
 namespace {
 
 constexpr int kLanes = 64;
-constexpr int kGroup = 16;  // lanes per row
 
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
@@ -56,19 +55,22 @@ __device__ __forceinline__ void load_vec(float (&dst)[VEC], const T* src) {
 
 // Wavefronts per SIMD the register budget is sized for: a whole tile of K and V rows is held in registers
 // (one column block), which costs 64 registers at 8 bytes per lane and row and 128 at 16 bytes.
-template <typename T, int VEC, int NCB>
-constexpr int stream_waves() { return NCB == 1 ? (sizeof(T) * VEC <= 8 ? 4 : 2) : 1; }
+template <typename T, int VEC, int NCB, int kGroup>
+constexpr int stream_waves() { return NCB == 1 ? (kGroup * sizeof(T) * VEC <= 128 ? 4 : 2) : 1; }
 
 // kWaves = wavefronts per work item (2 or 4): four shorten the chain of one item, two let twice as many
 // items be resident at once; the host takes two when four would need more than one round of workgroups.
-template <typename T, int VEC, int NCB, int MODE, int kWaves>
+// kGroup = lanes that share one row (16, or 8 when eight lanes of VEC elements cover d_a: half as many
+// load instructions per tile); a step covers 64 / kGroup rows and a tile has kGroup steps.
+template <typename T, int VEC, int NCB, int MODE, int kWaves, int kGroup>
 __global__ __launch_bounds__(kLanes * kWaves)
-__attribute__((amdgpu_waves_per_eu(stream_waves<T, VEC, NCB>(), 8))) void ckv_stream_kernel(ckv_args a) {
+__attribute__((amdgpu_waves_per_eu(stream_waves<T, VEC, NCB, kGroup>(), 8))) void ckv_stream_kernel(ckv_args a) {
+    constexpr int RS = kLanes / kGroup;  // rows per step
     __shared__ float sm_acc[kWaves][NCB * kGroup * VEC];
     __shared__ float sm_ml[kWaves][2];
     const ckv_item it = a.items[blockIdx.x];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int r = lane >> 4, c = lane & 15;
+    const int r = lane / kGroup, c = lane % kGroup;
     // user columns of each side: d_u of the shape, or all d_a columns for a side that is not shared
     const int d_uk = a.d_uk, d_uv = a.d_uv, d_a = a.d_a;
     const int64_t hT = (int64_t)it.h * a.T + it.t0;
@@ -79,7 +81,7 @@ __attribute__((amdgpu_waves_per_eu(stream_waves<T, VEC, NCB>(), 8))) void ckv_st
     const T* pk = (const T*)a.pool_k + (int64_t)it.h * a.P * a.pool_ld;
     const T* pv = (const T*)a.pool_v + (int64_t)it.h * a.P * a.pool_ld;
     const int n = it.n;
-    const int slot_of_lane = 4 * c + r;  // position (within a tile) whose score this lane keeps
+    const int slot_of_lane = RS * c + r;  // position (within a tile) whose score this lane keeps
 
     // column ownership: col[cb] = first final-K column of this lane in block cb (or -1)
     int col[NCB];
@@ -106,43 +108,51 @@ __attribute__((amdgpu_waves_per_eu(stream_waves<T, VEC, NCB>(), 8))) void ckv_st
 
         for (int t0 = wave * kLanes; t0 < n; t0 += kLanes * kWaves) {
             const int nt = min(n - t0, kLanes);
-            const int nsteps = (nt + 3) >> 2;  // four rows per step
+            const int nsteps = (nt + RS - 1) / RS;
             const int myslot = min(slot_of_lane, nt - 1);
             const int my_ik = a.d_gk > 0 ? ik[t0 + myslot] : 0;
             const int my_iv = a.d_gv > 0 ? iv[t0 + myslot] : 0;
             float s_mine = 0.f;
             float w;
-            if (NCB == 1 && (sizeof(T) * VEC <= 8 || sizeof(T) == 4)) {
-                // One column block: the whole tile's K and V rows (16 steps of four rows) are requested
+            if constexpr (NCB == 1 && sizeof(T) * VEC >= 4) {
+                // One column block: the whole tile's K and V rows (kGroup steps of RS rows) are requested
                 // before anything is computed, so that a tile costs one memory round trip after its
                 // indices instead of one per group of steps.  Steps past the end of the tile read a
                 // clamped position and are masked by their zero weight.
-                Pack<T, VEC> kraw[16], vraw[16];
+                // rows are kept as raw 32-bit words (two bf16 per word) so that they cost no more registers
+                // than their bytes
+                constexpr int NWORD = (int)(sizeof(T) * VEC / 4);  // >= 1 here
+                typedef uint32_t Raw __attribute__((ext_vector_type(NWORD)));
+                auto elem = [](const Raw& w, int v) -> float {
+                    if (sizeof(T) == 4) return __uint_as_float(w[v]);
+                    return __uint_as_float((v & 1) ? (w[v >> 1] & 0xFFFF0000u) : (w[v >> 1] << 16));
+                };
+                Raw kraw[kGroup], vraw[kGroup];
                 const bool own = col[0] >= 0;
                 const int c0 = own ? col[0] : 0;
 #pragma unroll
-                for (int t = 0; t < 16; ++t) {
-                    const int pos = min(4 * t + r, nt - 1);
-                    const int src_lane = (lane & 48) | t;
+                for (int t = 0; t < kGroup; ++t) {
+                    const int pos = min(RS * t + r, nt - 1);
+                    const int src_lane = (lane & ~(kGroup - 1)) | t;
                     const int rowk = __shfl(my_ik, src_lane, kLanes);
                     const int rowv = __shfl(my_iv, src_lane, kLanes);
                     const T* ksrc = c0 < d_uk ? uk + (int64_t)(t0 + pos) * d_uk + c0 : pk + (int64_t)rowk * a.pool_ld + (c0 - d_uk);
                     const T* vsrc = c0 < d_uv ? uv + (int64_t)(t0 + pos) * d_uv + c0 : pv + (int64_t)rowv * a.pool_ld + (c0 - d_uv);
                     if (own) {
-                        kraw[t] = *reinterpret_cast<const Pack<T, VEC>*>(ksrc);
-                        vraw[t] = *reinterpret_cast<const Pack<T, VEC>*>(vsrc);
+                        kraw[t] = *reinterpret_cast<const Raw*>(ksrc);
+                        vraw[t] = *reinterpret_cast<const Raw*>(vsrc);
                     } else {
 #pragma unroll
-                        for (int v = 0; v < VEC; ++v) kraw[t].v[v] = vraw[t].v[v] = T(0);
+                        for (int v = 0; v < NWORD; ++v) kraw[t][v] = vraw[t][v] = 0u;
                     }
                 }
 #pragma unroll
-                for (int t = 0; t < 16; ++t) {
+                for (int t = 0; t < kGroup; ++t) {
                     float part = 0.f;
 #pragma unroll
-                    for (int v = 0; v < VEC; ++v) part = fmaf(Elem<T>::up(kraw[t].v[v]), qreg[0][v], part);
+                    for (int v = 0; v < VEC; ++v) part = fmaf(elem(kraw[t], v), qreg[0][v], part);
 #pragma unroll
-                    for (int o = 8; o > 0; o >>= 1) part += __shfl_xor(part, o, kLanes);
+                    for (int o = kGroup / 2; o > 0; o >>= 1) part += __shfl_xor(part, o, kLanes);
                     if (c == t) s_mine = part;
                 }
                 const bool valid = slot_of_lane < nt;
@@ -160,10 +170,10 @@ __attribute__((amdgpu_waves_per_eu(stream_waves<T, VEC, NCB>(), 8))) void ckv_st
                     w = valid ? sv / (1.f + __expf(-sv)) : 0.f;
                 }
 #pragma unroll
-                for (int t = 0; t < 16; ++t) {
-                    const float wr = __shfl(w, (lane & 48) | t, kLanes);
+                for (int t = 0; t < kGroup; ++t) {
+                    const float wr = __shfl(w, (lane & ~(kGroup - 1)) | t, kLanes);
 #pragma unroll
-                    for (int v = 0; v < VEC; ++v) acc[0][v] = fmaf(wr, Elem<T>::up(vraw[t].v[v]), acc[0][v]);
+                    for (int v = 0; v < VEC; ++v) acc[0][v] = fmaf(wr, elem(vraw[t], v), acc[0][v]);
                 }
                 continue;
             }
@@ -171,8 +181,8 @@ __attribute__((amdgpu_waves_per_eu(stream_waves<T, VEC, NCB>(), 8))) void ckv_st
             for (int tb = 0; tb < nsteps; tb += 4)
 #pragma unroll
             for (int t = tb; t < tb + 4; ++t) {  // steps past nsteps touch clamped, masked positions
-                const int pos = min(4 * t + r, nt - 1);
-                const int row = __shfl(my_ik, (lane & 48) | t, kLanes);
+                const int pos = min(RS * t + r, nt - 1);
+                const int row = __shfl(my_ik, (lane & ~(kGroup - 1)) | t, kLanes);
                 float part = 0.f;
 #pragma unroll
                 for (int cb = 0; cb < NCB; ++cb) {
@@ -186,7 +196,7 @@ __attribute__((amdgpu_waves_per_eu(stream_waves<T, VEC, NCB>(), 8))) void ckv_st
                     }
                 }
 #pragma unroll
-                for (int o = 8; o > 0; o >>= 1) part += __shfl_xor(part, o, kLanes);
+                for (int o = kGroup / 2; o > 0; o >>= 1) part += __shfl_xor(part, o, kLanes);
                 if (c == t) s_mine = part;
             }
             // ---- weights
@@ -210,8 +220,8 @@ __attribute__((amdgpu_waves_per_eu(stream_waves<T, VEC, NCB>(), 8))) void ckv_st
             for (int tb = 0; tb < nsteps; tb += 4)
 #pragma unroll
             for (int t = tb; t < tb + 4; ++t) {
-                const int pos = min(4 * t + r, nt - 1);
-                const int src_lane = (lane & 48) | t;
+                const int pos = min(RS * t + r, nt - 1);
+                const int src_lane = (lane & ~(kGroup - 1)) | t;
                 const int row = __shfl(my_iv, src_lane, kLanes);
                 const float wr = __shfl(w, src_lane, kLanes);
 #pragma unroll
@@ -233,8 +243,8 @@ __attribute__((amdgpu_waves_per_eu(stream_waves<T, VEC, NCB>(), 8))) void ckv_st
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
                 float x = acc[cb][v];
-                x += __shfl_xor(x, 16, kLanes);
-                x += __shfl_xor(x, 32, kLanes);
+#pragma unroll
+                for (int o = kGroup; o < kLanes; o <<= 1) x += __shfl_xor(x, o, kLanes);
                 acc[cb][v] = x;
             }
         // ---- merge the four wavefronts through LDS (exact: rescale to the common maximum)
@@ -302,14 +312,21 @@ __attribute__((amdgpu_waves_per_eu(stream_waves<T, VEC, NCB>(), 8))) void ckv_st
     }
 }
 
-template <typename T, int VEC, int NCB, int NWV>
-hipError_t launch_waves(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
+template <typename T, int VEC, int NCB, int NWV, int GRP>
+hipError_t launch_group(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
     dim3 grid(c->n_items), block(kLanes * NWV);
     if (c->shape.mode == CKV_SOFTMAX)
-        hipLaunchKernelGGL((ckv_stream_kernel<T, VEC, NCB, CKV_SOFTMAX, NWV>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((ckv_stream_kernel<T, VEC, NCB, CKV_SOFTMAX, NWV, GRP>), grid, block, 0, s, a);
     else
-        hipLaunchKernelGGL((ckv_stream_kernel<T, VEC, NCB, CKV_SILU_OVER_N, NWV>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((ckv_stream_kernel<T, VEC, NCB, CKV_SILU_OVER_N, NWV, GRP>), grid, block, 0, s, a);
     return hipGetLastError();
+}
+
+template <typename T, int VEC, int NCB, int NWV>
+hipError_t launch_waves(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
+    // eight lanes per row only exist for the widest vectors (the host asks for them only there)
+    if (c->grp == 8 && sizeof(T) * VEC == 16) return launch_group<T, VEC, NCB, NWV, 8>(c, a, s);
+    return launch_group<T, VEC, NCB, NWV, 16>(c, a, s);
 }
 
 template <typename T, int VEC, int NCB>
