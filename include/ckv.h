@@ -223,6 +223,25 @@ int64_t ckv_plan(const ckv_shape* shape, const int32_t* lengths, int cus, int wg
                  int64_t* records, int64_t max_records, int32_t* n_workgroups,
                  char* variant, size_t variant_size);
 
+/*
+ * Frequency renumbering of the pool rows.  The router sends many positions of many users to the same pool
+ * entries (appendix "Analysis of Router Activations for Highly Similar Users"); this call counts, per head
+ * and side, how often the handle's cache refers to every row, renumbers the rows most used first (equal
+ * counts keep their order), writes the permuted pools and rewrites the handle's stored indices, so that
+ * the hot rows of a head are one contiguous block at the start of its pool.  A pure relabeling: ckv_attend
+ * with the new pools gives bit-identical results.
+ *
+ *   pool_k, pool_v          device [H][P][pool_ld], the current pools (a side that is not shared is ignored)
+ *   pool_k_out, pool_v_out  device [H][P][pool_ld], receive the permuted pools; must not alias the inputs
+ *   new_id                  device int32 [2][H][P] or NULL: new number of every old row (plane 0 keys,
+ *                           plane 1 values), e.g. to permute the rows of a router the same way
+ * The handle must be device-resident.  Allocates temporaries, sorts on the host and synchronises `stream`:
+ * a maintenance call (after a pool refresh), not part of the request path.  After it the handle is only
+ * valid together with the new pools.  Errors: CKV_ERR_NULL, _UNSUPPORTED (offloaded handle), _HIP.
+ */
+int ckv_remap_hot_rows(ckv_cache* cache, const void* pool_k, const void* pool_v, void* pool_k_out, void* pool_v_out,
+                       int32_t* new_id, void* stream);
+
 /* Release the handle and the device memory it owns.  NULL is allowed. */
 void ckv_free(ckv_cache* cache);
 

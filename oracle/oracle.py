@@ -179,3 +179,23 @@ def router_gap(r, side, cand):
     if rc != 0:
         raise ValueError("ckv_oracle_router_gap rejected its arguments")
     return gap, mag
+
+
+def hot_row_order(w):
+    """Frequency renumbering of the pool rows (router activations overlap across users, appendix "Analysis of
+    Router Activations"): for every side and head, rows sorted by how often the cache refers to them, most
+    used first, equal counts by row number.  Returns (new_id_k, new_id_v), each int32 [H][P] mapping an old
+    row number to its new one (zeros for a side that is not shared).  Plain numpy: bincount + stable argsort."""
+    H, P = w["H"], w["P"]
+    share = w.get("share", 0)
+    out = []
+    for side, idx in ((0, w["idx_k"]), (1, w["idx_v"])):
+        shared = w["d_g"] > 0 and (share == 0 or (share == 1 and side == 0) or (share == 2 and side == 1))
+        new_id = np.zeros((H, P), dtype=np.int32)
+        if shared:
+            for h in range(H):
+                counts = np.bincount(idx[:, h], minlength=P)
+                order = np.argsort(-counts, kind="stable")     # old rows in their new order
+                new_id[h, order] = np.arange(P, dtype=np.int32)
+        out.append(new_id)
+    return out[0], out[1]

@@ -21,7 +21,7 @@ CKV_OK, CKV_ERR_NULL, CKV_ERR_SHAPE, CKV_ERR_INDEX, CKV_ERR_LENGTH, CKV_ERR_UNSU
 
 EXPORTS = [
     "ckv_build_cache", "ckv_build_cache_offloaded", "ckv_cache_is_offloaded", "ckv_prefill", "ckv_prefill_into",
-    "ckv_prefill_kernel_name", "ckv_plan", "ckv_cache_idx", "ckv_cache_user_k", "ckv_cache_user_v", "ckv_cache_lengths",
+    "ckv_prefill_kernel_name", "ckv_plan", "ckv_remap_hot_rows", "ckv_cache_idx", "ckv_cache_user_k", "ckv_cache_user_v", "ckv_cache_lengths",
     "ckv_cache_positions", "ckv_cache_stored_bytes", "ckv_attend", "ckv_reconstruct", "ckv_free",
     "ckv_last_error", "ckv_set_timing", "ckv_kernel_ms", "ckv_variant", "ckv_copy", "ckv_trace_enable", "ckv_trace_read",
 ]
@@ -60,6 +60,8 @@ _lib.ckv_prefill_into.restype = ctypes.c_int
 _lib.ckv_prefill_into.argtypes = [_vp, ctypes.POINTER(ckv_router), _vp, _vp]
 _lib.ckv_prefill_kernel_name.restype = ctypes.c_char_p
 _lib.ckv_prefill_kernel_name.argtypes = [ctypes.POINTER(ckv_shape), ctypes.POINTER(ckv_router)]
+_lib.ckv_remap_hot_rows.restype = ctypes.c_int
+_lib.ckv_remap_hot_rows.argtypes = [_vp] * 7
 _lib.ckv_plan.restype = _i64
 _lib.ckv_plan.argtypes = [ctypes.POINTER(ckv_shape), _vp, ctypes.c_int, ctypes.c_int, _vp, _i64, ctypes.POINTER(_i32), ctypes.c_char_p,
                           ctypes.c_size_t]
@@ -173,6 +175,10 @@ def ckv_plan(shape, lengths, cus=256, wg_per_cu=2):
     if n < 0:
         raise CkvError(int(n), ckv_last_error())
     return rec[:n], int(nwg.value), name.value.decode()
+
+
+def ckv_remap_hot_rows(cache, pool_k, pool_v, pool_k_out, pool_v_out, new_id=None, stream=0):
+    _check(_lib.ckv_remap_hot_rows(cache, _dev(pool_k), _dev(pool_v), _dev(pool_k_out), _dev(pool_v_out), _dev(new_id), _vp(stream)))
 
 
 def ckv_cache_is_offloaded(cache):

@@ -125,6 +125,33 @@ __global__ __launch_bounds__(256) void ckv_merge_kernel(const ckv_merge* __restr
     }
 }
 
+// Frequency renumbering of pool rows: count how often every row of a head is referred to ...
+__global__ void ckv_histogram_kernel(const int32_t* __restrict__ idx, uint32_t* __restrict__ counts, int64_t T, int H, int P) {
+    const int64_t total = (int64_t)H * T;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int h = (int)(i / T);
+        atomicAdd(&counts[(int64_t)h * P + idx[i]], 1u);
+    }
+}
+// ... rewrite the stored indices with the new row numbers ...
+__global__ void ckv_renumber_kernel(int32_t* __restrict__ idx, const int32_t* __restrict__ new_id, int64_t T, int H, int P) {
+    const int64_t total = (int64_t)H * T;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int h = (int)(i / T);
+        idx[i] = new_id[(int64_t)h * P + idx[i]];
+    }
+}
+// ... and move every pool row to its new place (16 threads per row, whole elements of `e` bytes).
+__global__ void ckv_permute_rows_kernel(const unsigned char* __restrict__ src, unsigned char* __restrict__ dst,
+                                        const int32_t* __restrict__ new_id, int64_t rows, int P, int64_t row_bytes) {
+    const int64_t r = (int64_t)blockIdx.x * (blockDim.x / 16) + threadIdx.x / 16;
+    if (r >= rows) return;
+    const int64_t h = r / P;
+    const unsigned char* s = src + r * row_bytes;
+    unsigned char* d = dst + (h * P + new_id[r]) * row_bytes;
+    for (int64_t b = (threadIdx.x & 15) * 2; b < row_bytes; b += 32) *(uint16_t*)(d + b) = *(const uint16_t*)(s + b);
+}
+
 __global__ void ckv_copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n16, int tail) {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
         dst[i] = src[i];
@@ -1111,6 +1138,71 @@ int64_t ckv_trace_read(ckv_cache* c, unsigned long long* host, int64_t max_items
     if (e == hipSuccess) e = hipMemcpy(host, c->d_trace, sizeof(unsigned long long) * 8 * (size_t)n, hipMemcpyDeviceToHost);
     if (e != hipSuccess) return fail(CKV_ERR_HIP, "ckv_trace_read: %s", hipGetErrorString(e));
     return n;
+}
+
+int ckv_remap_hot_rows(ckv_cache* c, const void* pool_k, const void* pool_v, void* pool_k_out, void* pool_v_out,
+                       int32_t* new_id, void* stream) {
+    if (!c) return fail(CKV_ERR_NULL, "ckv_remap_hot_rows: cache is NULL");
+    const ckv_shape& s = c->shape;
+    if (c->offloaded) return fail(CKV_ERR_UNSUPPORTED, "ckv_remap_hot_rows: the handle's cache lives in host memory");
+    int side_du[2], side_dg[2];
+    ckv_side_dims(s, 0, &side_du[0], &side_dg[0]);
+    ckv_side_dims(s, 1, &side_du[1], &side_dg[1]);
+    const void* pin[2] = {pool_k, pool_v};
+    void* pout[2] = {pool_k_out, pool_v_out};
+    for (int side = 0; side < 2; ++side)
+        if (side_dg[side] > 0 && (!pin[side] || !pout[side] || pin[side] == pout[side]))
+            return fail(CKV_ERR_NULL, "ckv_remap_hot_rows: a shared side needs distinct input and output pools");
+    if (s.d_g == 0) return CKV_OK;
+    hipStream_t st = (hipStream_t)stream;
+    int rc = CKV_OK;
+    const size_t hp = (size_t)s.H * (size_t)s.P;
+    uint32_t* d_counts = nullptr;
+    int32_t* d_new = nullptr;
+    std::vector<uint32_t> counts(2 * hp, 0);
+    std::vector<int32_t> ids(2 * hp, 0);
+    std::vector<int32_t> order((size_t)s.P);
+    const int64_t n_ph = (int64_t)s.H * c->T;
+    const int blocks = (int)std::max<int64_t>(1, std::min<int64_t>((n_ph + 255) / 256, 65536));
+    CKV_HIP(hipMalloc((void**)&d_counts, sizeof(uint32_t) * 2 * hp));
+    CKV_HIP(hipMalloc((void**)&d_new, sizeof(int32_t) * 2 * hp));
+    CKV_HIP(hipMemsetAsync(d_counts, 0, sizeof(uint32_t) * 2 * hp, st));
+    for (int side = 0; side < 2; ++side)
+        if (side_dg[side] > 0 && n_ph > 0)
+            hipLaunchKernelGGL(ckv_histogram_kernel, dim3(blocks), dim3(256), 0, st, c->d_idx + (int64_t)side * n_ph,
+                               d_counts + (size_t)side * hp, c->T, s.H, s.P);
+    CKV_HIP(hipGetLastError());
+    CKV_HIP(hipMemcpyAsync(counts.data(), d_counts, sizeof(uint32_t) * 2 * hp, hipMemcpyDeviceToHost, st));
+    CKV_HIP(hipStreamSynchronize(st));
+    // most used first, equal counts by row number (a stable sort of the row numbers)
+    for (int side = 0; side < 2; ++side) {
+        if (side_dg[side] == 0) continue;
+        for (int h = 0; h < s.H; ++h) {
+            const uint32_t* cnt = counts.data() + (size_t)side * hp + (size_t)h * s.P;
+            std::iota(order.begin(), order.end(), 0);
+            std::stable_sort(order.begin(), order.end(), [cnt](int32_t x, int32_t y) { return cnt[x] > cnt[y]; });
+            int32_t* id = ids.data() + (size_t)side * hp + (size_t)h * s.P;
+            for (int32_t k = 0; k < s.P; ++k) id[order[(size_t)k]] = k;
+        }
+    }
+    CKV_HIP(hipMemcpyAsync(d_new, ids.data(), sizeof(int32_t) * 2 * hp, hipMemcpyHostToDevice, st));
+    for (int side = 0; side < 2; ++side) {
+        if (side_dg[side] == 0) continue;
+        const int64_t rows = (int64_t)hp;
+        const int64_t row_bytes = s.pool_ld * (int64_t)esize(s.dtype);
+        hipLaunchKernelGGL(ckv_permute_rows_kernel, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, (const unsigned char*)pin[side],
+                           (unsigned char*)pout[side], d_new + (size_t)side * hp, rows, s.P, row_bytes);
+        if (n_ph > 0)
+            hipLaunchKernelGGL(ckv_renumber_kernel, dim3(blocks), dim3(256), 0, st, c->d_idx + (int64_t)side * n_ph,
+                               d_new + (size_t)side * hp, c->T, s.H, s.P);
+    }
+    CKV_HIP(hipGetLastError());
+    if (new_id) CKV_HIP(hipMemcpyAsync(new_id, d_new, sizeof(int32_t) * 2 * hp, hipMemcpyDeviceToDevice, st));
+    CKV_HIP(hipStreamSynchronize(st));
+done:
+    (void)hipFree(d_counts);
+    (void)hipFree(d_new);
+    return rc;
 }
 
 int ckv_copy(void* dst, const void* src, size_t nbytes, void* stream) {

@@ -75,6 +75,21 @@ class Session:
         """Recompute the packed cache in place from the embedding and the router (no allocation)."""
         ckv.ckv_prefill_into(self.cache, self.router, self.S, self.stream if stream is None else stream)
 
+    def remap_hot_rows(self):
+        """Renumber the pool rows most used first; returns new_id as numpy int32 [2][H][P]."""
+        H, P = self.w["H"], self.w["P"]
+        new_id = torch.zeros((2, H, P), dtype=torch.int32, device="cuda")
+        pk = torch.empty_like(self.pool_k) if self.pool_k is not None else None
+        pv = torch.empty_like(self.pool_v) if self.pool_v is not None else None
+        ckv.ckv_remap_hot_rows(self.cache, self.pool_k, self.pool_v, pk, pv, new_id, self.stream)
+        d_gk = self.w["d_g"] if self.share in (0, 1) else 0
+        d_gv = self.w["d_g"] if self.share in (0, 2) else 0
+        if d_gk > 0:
+            self.pool_k = pk
+        if d_gv > 0:
+            self.pool_v = pv
+        return new_id.cpu().numpy()
+
     def output(self):
         """Output of the last attend() as float64 numpy (exact widening of the stored values)."""
         torch.cuda.synchronize()

@@ -280,6 +280,60 @@ def test_single_side_sharing_split_history(gpu, impl):
 
 
 # ---------------------------------------------------------------------------------------------
+# frequency renumbering of the pool rows: a relabeling that must not change any output bit
+@pytest.mark.parametrize("share", [wl.SHARE_KV, wl.SHARE_K, wl.SHARE_V])
+@pytest.mark.parametrize("kind", ["stream", "dma"])
+def test_hot_row_renumbering(gpu, share, kind):
+    ckv, session = gpu
+    if kind == "stream":
+        w = make(RAGGED, wl.F32, wl.SOFTMAX, d_a=24, d_u=3, H=3, P=101, Nq=2, pool_ld=29, idx=("zipf", 1.2), share=share)
+    else:
+        w = make(MFMA_LENGTHS, wl.BF16, wl.SOFTMAX, d_a=64, d_u=4, H=2, P=700, Nq=64, idx=("zipf", 1.1), share=share)
+    say(f"[case] hot-row renumbering {kind} share={share}")
+    with session.Session(w) as s:
+        s.attend()
+        before = s.output().copy()
+        old_pk = session._to_host(s.pool_k, w["dtype"]).copy()
+        old_pv = session._to_host(s.pool_v, w["dtype"]).copy()
+        new_id = s.remap_hot_rows()
+        idx, _, _ = s.packed_views()
+        new_pk = session._to_host(s.pool_k, w["dtype"])
+        new_pv = session._to_host(s.pool_v, w["dtype"])
+        s.out.fill_(float("nan"))
+        s.attend()
+        after = s.output()
+        k_full, v_full = s.reconstruct()
+    nk, nv = oracle.hot_row_order(w)
+    np.testing.assert_array_equal(new_id[0], nk)
+    np.testing.assert_array_equal(new_id[1], nv)
+    for h in range(w["H"]):
+        if share in (wl.SHARE_KV, wl.SHARE_K):
+            np.testing.assert_array_equal(idx[0][h], nk[h][w["idx_k"][:, h]])
+            np.testing.assert_array_equal(new_pk[h][nk[h]].view(np.uint8), old_pk[h].view(np.uint8))   # bytes, padding included
+        if share in (wl.SHARE_KV, wl.SHARE_V):
+            np.testing.assert_array_equal(idx[1][h], nv[h][w["idx_v"][:, h]])
+            np.testing.assert_array_equal(new_pv[h][nv[h]].view(np.uint8), old_pv[h].view(np.uint8))
+    np.testing.assert_array_equal(after, before)
+    ok, ov = oracle.reconstruct(w)
+    np.testing.assert_array_equal(k_full, ok.transpose(1, 0, 2))
+    np.testing.assert_array_equal(v_full, ov.transpose(1, 0, 2))
+    check(after, oracle.attend(w), w["dtype"], what=f"renumbered {kind} share={share}")
+
+
+def test_hot_row_renumbering_rejects_offloaded_and_aliased(gpu):
+    ckv, session = gpu
+    w = make((10, 20), wl.BF16, wl.SOFTMAX, d_a=64, d_u=8, H=1, P=50, Nq=1)
+    with session.Session(w, offloaded=True) as s:
+        with pytest.raises(ckv.CkvError) as e:
+            s.remap_hot_rows()
+        assert e.value.code == ckv.CKV_ERR_UNSUPPORTED
+    with session.Session(w) as s:
+        with pytest.raises(ckv.CkvError) as e:
+            ckv.ckv_remap_hot_rows(s.cache, s.pool_k, s.pool_v, s.pool_k, s.pool_v, None, s.stream)
+        assert e.value.code == ckv.CKV_ERR_NULL
+
+
+# ---------------------------------------------------------------------------------------------
 # error paths that need the device
 def test_out_of_range_index_is_rejected(gpu):
     ckv, session = gpu

@@ -346,3 +346,33 @@ def test_cache_size_with_one_side_shared():
     assert oracle.cache_size(T=100, H=2, d_g=56, d_u=8, dtype=oracle.BF16, share=wl.SHARE_V) == (se, fe, sb, fb)
     both = oracle.cache_size(T=100, H=2, d_g=56, d_u=8, dtype=oracle.BF16)
     assert both[0] == 100 * 2 * 2 * 9 and both[0] < se
+
+
+# ---------------------------------------------------------------------------------------------
+# frequency renumbering of pool rows: a relabeling, so attention must not change
+def test_hot_row_renumbering_is_a_relabeling():
+    w = small(dtype=wl.BF16, idx=("zipf", 1.2), lengths=(40, 3, 0, 77, 64, 9), P=23)
+    nk, nv = oracle.hot_row_order(w)
+    ref = oracle.attend(w)
+    w2 = dict(w)
+    w2["pool_k"], w2["pool_v"] = np.empty_like(w["pool_k"]), np.empty_like(w["pool_v"])
+    for h in range(w["H"]):
+        assert sorted(nk[h]) == list(range(w["P"])) and sorted(nv[h]) == list(range(w["P"]))
+        w2["pool_k"][h][nk[h]] = w["pool_k"][h]
+        w2["pool_v"][h][nv[h]] = w["pool_v"][h]
+        # most used first: counts are non-increasing along the new numbering, ties by old row number
+        for new_id, idx in ((nk, w["idx_k"]), (nv, w["idx_v"])):
+            counts = np.bincount(idx[:, h], minlength=w["P"])
+            by_new = np.empty(w["P"], dtype=np.int64)
+            by_new[new_id[h]] = counts
+            assert (np.diff(by_new) <= 0).all()
+            old_of_new = np.argsort(new_id[h])
+            same = np.diff(by_new) == 0
+            assert (np.diff(old_of_new)[same] > 0).all()
+    w2["idx_k"] = np.stack([nk[h][w["idx_k"][:, h]] for h in range(w["H"])], axis=1).astype(np.int32)
+    w2["idx_v"] = np.stack([nv[h][w["idx_v"][:, h]] for h in range(w["H"])], axis=1).astype(np.int32)
+    np.testing.assert_array_equal(oracle.attend(w2), ref)   # same rows, same order of summation: bit for bit
+    ok, ov = oracle.reconstruct(w)
+    ok2, ov2 = oracle.reconstruct(w2)
+    np.testing.assert_array_equal(ok, ok2)
+    np.testing.assert_array_equal(ov, ov2)
