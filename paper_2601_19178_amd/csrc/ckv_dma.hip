@@ -45,6 +45,14 @@ __device__ __forceinline__ float other_half(float x) {
     return threadIdx.x & 32 ? __uint_as_float(r[0]) : __uint_as_float(r[1]);
 }
 __device__ __forceinline__ uint16_t f2bf(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
+// Masks one score of a ragged last tile.  The empty volatile asm pins the select inside the (wavefront-
+// uniform) branch that calls it; without it the compiler turns that branch into sixteen compares and
+// selects that every whole tile executes as well.
+__device__ __forceinline__ float mask_tail(float x, bool past_end, float fill) {
+    float v = past_end ? fill : x;
+    asm volatile("" : "+v"(v));
+    return v;
+}
 
 // 16 bytes per lane, global -> LDS[lds_base + 16*lane].  lds_base is wavefront-uniform.
 __device__ __forceinline__ void dma16(const void* g, uint32_t lds_base) {
@@ -230,6 +238,8 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
             for (int r = 0; r < 16; ++r) oacc[g][dt][r] = 0.f;
     }
     const float sc = MODE == CKV_SOFTMAX ? a.scale * kLog2e : a.scale;
+    const float nsc = -kLog2e * a.scale;    // SiLU: exponent of 2 per unit of raw score
+    const bool unit_scale = a.scale == 1.f;  // SiLU(QK^T) taken literally: one multiply less per weight
 
     const int ntiles = (n + TP - 1) / TP;
     if (ntiles > 0) {
@@ -368,10 +378,9 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
                 for (int g = 0; g < QG; ++g) {
                     bf16x8 pb[2];
                     if (MODE == CKV_SOFTMAX) {
-                        if (ragged) {
+                        if (ragged) {  // see mask_tail: only the last tile of a history comes here
 #pragma unroll
-                            for (int r = 0; r < 16; ++r)
-                                if (8 * (r >> 2) + 4 * hh + (r & 3) >= nt) sacc[g][r] = -INFINITY;
+                            for (int r = 0; r < 16; ++r) sacc[g][r] = mask_tail(sacc[g][r], 8 * (r >> 2) + 4 * hh + (r & 3) >= nt, -INFINITY);
                         }
                         float tmax = sacc[g][0];
 #pragma unroll
@@ -396,12 +405,23 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
                         }
                         lsum[g] += psum;
                     } else {
+                        if (ragged) {  // SiLU(0) = 0: positions past the end get a zero score
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const float x = sacc[g][r] * sc;
-                            float p = x * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-kLog2e * x));
-                            if (ragged && 8 * (r >> 2) + 4 * hh + (r & 3) >= nt) p = 0.f;
-                            pb[r >> 3][r & 7] = (__bf16)p;
+                            for (int r = 0; r < 16; ++r) sacc[g][r] = mask_tail(sacc[g][r], 8 * (r >> 2) + 4 * hh + (r & 3) >= nt, 0.f);
+                        }
+                        // p = x / (1 + 2^(-x log2 e)) with x = sc * score
+                        if (unit_scale) {
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) {
+                                const float e = __builtin_amdgcn_exp2f(sacc[g][r] * -kLog2e);
+                                pb[r >> 3][r & 7] = (__bf16)(sacc[g][r] * __builtin_amdgcn_rcpf(1.f + e));
+                            }
+                        } else {
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) {
+                                const float e = __builtin_amdgcn_exp2f(sacc[g][r] * nsc);
+                                pb[r >> 3][r & 7] = (__bf16)((sacc[g][r] * sc) * __builtin_amdgcn_rcpf(1.f + e));
+                            }
                         }
                     }
                     // O^T += V^T P^T
