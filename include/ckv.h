@@ -190,7 +190,10 @@ int64_t ckv_cache_stored_bytes(const ckv_cache* c);
  * No allocation, no synchronisation, no validation pass over the data: indices were checked
  * when the cache was built; passing other index buffers with out-of-range entries is
  * undefined.  Calls on the same handle share its split workspace, so two calls on one handle
- * must not overlap in time (serialise them on one stream).
+ * must not overlap in time (serialise them on one stream).  The call enqueues kernel launches
+ * only (no memset, no copy, no event unless ckv_set_timing switched timing on), so it may be
+ * recorded into a HIP graph by stream capture and replayed; a replay reads the buffers whose
+ * addresses were captured.
  * Errors: CKV_ERR_NULL, CKV_ERR_HIP (launch failure).
  */
 int ckv_attend(const ckv_cache* cache, const void* pool_k, const void* pool_v,

@@ -389,3 +389,88 @@ def test_repeated_calls_are_deterministic(gpu):
         s.attend()
         b = s.output()
     np.testing.assert_array_equal(a, b)
+
+
+@pytest.mark.parametrize("kind", ["stream", "dma_split"])
+def test_attend_replayed_from_a_captured_graph(gpu, kind):
+    """A serving loop records ckv_attend once and replays it; every replay (new queries in the captured
+    buffer, eager work and synchronisations in between) must equal the eager call bit for bit."""
+    import torch
+    ckv, session = gpu
+    if kind == "stream":
+        w = make((300, 0, 41, 1200), wl.F32, wl.SOFTMAX, d_a=32, d_u=4, H=2, P=700, Nq=1)
+    else:  # one long history among short ones: split into pieces, merged by a second kernel
+        w = make((9000, 64, 3, 0, 500), wl.BF16, wl.SILU_OVER_N, d_a=64, d_u=4, H=2, P=3000, Nq=64)
+    rng = np.random.default_rng(5)
+    with session.Session(w) as s:
+        say(f"[case] graph replay {kind}: variant {ckv.ckv_variant(s.cache)}")
+        if kind == "dma_split":
+            assert ckv.ckv_variant(s.cache).startswith("mfma_dma")
+        s.attend()
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):  # capture runs on `side`; nothing executes yet
+            s.attend(stream=torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        for rep in range(3):
+            qn = torch.randn(s.q.shape, generator=torch.Generator().manual_seed(100 + rep)).to(s.q.dtype).cuda()
+            s.q.copy_(qn)
+            s.out.fill_(float("nan"))
+            graph.replay()
+            torch.cuda.synchronize()
+            got = s.output().copy()
+            s.out.fill_(float("nan"))
+            s.attend()
+            want = s.output()
+            np.testing.assert_array_equal(got, want)
+            say(f"  replay {rep} equals the eager call")
+        # the last queries against the oracle as well
+        w2 = dict(w)
+        w2["q"] = session._to_host(s.q, w["dtype"])
+    check(want, oracle.attend(w2), w["dtype"], what=f"graph replay {kind}")
+
+
+@pytest.mark.parametrize("kind", ["dma", "staged", "stream"])
+def test_pool_rows_beyond_four_gib(gpu, kind):
+    """A pool of more than 2^24 rows of 256 bytes: byte offsets of the rows pass 2^32, so an address
+    computed in 32 bits would wrap onto another row.  The pool repeats a random block whose period
+    (a prime) does not divide 2^24, which makes a wrapped row differ from the right one."""
+    P_big, period = (1 << 24) + 4099, 65521
+    Nq = 1 if kind == "stream" else 128
+    w = make((700, 3, 0, 1500), wl.BF16, wl.SOFTMAX, d_a=128, d_u=8, H=1, P=period, Nq=Nq, seed=23)
+    rng = np.random.default_rng(23)
+    T = int(w["lengths"].sum())
+    for side in ("k", "v"):
+        block = w["pool_" + side][0]
+        big = np.empty((1, P_big, block.shape[1]), dtype=block.dtype)
+        for r0 in range(0, P_big, period):
+            n = min(period, P_big - r0)
+            big[0, r0:r0 + n] = block[:n]
+        w["pool_" + side] = big
+        idx = rng.integers(0, P_big, size=(T, 1), dtype=np.int64)
+        high = rng.random((T, 1)) < 0.5
+        idx[high] = rng.integers(1 << 24, P_big, size=int(high.sum()))
+        idx[0, 0], idx[1, 0] = P_big - 1, 1 << 24
+        w["idx_" + side] = idx.astype(np.int32)
+    w["P"] = P_big
+    assert w["pool_k"].nbytes > 1 << 32 and int(w["idx_k"].max()) * w["pool_ld"] * 2 >= 1 << 32
+    ckv, session = gpu
+    import os
+    if kind == "staged":
+        os.environ["CKV_MFMA_IMPL"] = "staged"
+    try:
+        say(f"[case] pool beyond 4 GiB, {kind}: P={P_big}, {w['pool_k'].nbytes / 2**30:.2f} GiB per side")
+        with session.Session(w) as s:
+            variant = ckv.ckv_variant(s.cache)
+            say(f"  variant {variant}")
+            assert variant.startswith({"dma": "mfma_dma", "staged": "mfma_bf16", "stream": "stream"}[kind]), variant
+            s.attend()
+            out = s.output()
+            k_full, v_full = s.reconstruct()
+    finally:
+        os.environ.pop("CKV_MFMA_IMPL", None)
+    ok, ov = oracle.reconstruct(w)
+    assert np.array_equal(k_full, ok.transpose(1, 0, 2)) and np.array_equal(v_full, ov.transpose(1, 0, 2))
+    norm = check(out, oracle.attend(w), w["dtype"], what=f"pool beyond 4 GiB ({kind})")
+    say(f"  ok, norm-wise error {norm:.3e}, rows bit-exact")
