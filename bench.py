@@ -209,7 +209,7 @@ def main():
                     help="untimed steps; the GPU needs ~50 back-to-back launches to reach its steady clocks")
     ap.add_argument("--workload", default="cfg4", choices=sorted(DESCRIBE))
     ap.add_argument("--also", default="cfg2_f32,cfg2_bf16,cfg3,cfg3_ck", help="comma list of further workloads ('' for none)")
-    ap.add_argument("--prefill", default="prefill_cfg2",
+    ap.add_argument("--prefill", default="prefill_cfg2,prefill_cfg3",
                     help="comma list of prefill workloads reported under 'prefill' (prefill_cfg2, prefill_cfg3; '' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--offloaded-sweep", action="store_true",

@@ -142,7 +142,14 @@ int ckv_cache_is_offloaded(const ckv_cache* c);
  * ckv_prefill allocates the handle (device-resident), enqueues the kernels on `stream`, builds the
  * launch metadata and synchronises the stream before returning.  ckv_prefill_into recomputes the
  * packed cache of an existing, device-resident handle (same shape and lengths) from new S or
- * weights: no allocation, no synchronisation.  ckv_prefill_kernel_name names the kernel the pair
+ * weights: no allocation, no synchronisation.
+ * The matrix-core kernel runs equal workgroups of 256 positions x one (head, side) in rounds; when
+ * the last round (for a short batch: the only one) would leave most compute units idle, its
+ * workgroups are cut along the pool entries and meet in a 64-bit atomic maximum per position, which
+ * needs a small workspace.  ckv_prefill sizes and owns it (ckv_cache_prefill_workspace returns its
+ * number of 8-byte entries, 0 if none is needed); a handle made by ckv_build_cache has none, and
+ * ckv_prefill_into on it simply runs the uncut rounds.  Results do not depend on the cut: ties
+ * still go to the lowest pool entry.  Calls on one handle must not overlap (they share it).  ckv_prefill_kernel_name names the kernel the pair
  * (shape, router) dispatches to: a matrix-core kernel for bf16 with d_e of 64, 128 or 256, a
  * scalar kernel otherwise.
  * Errors: CKV_ERR_NULL, _SHAPE, _LENGTH, _UNSUPPORTED (pointer not 16-byte aligned), _HIP.
@@ -162,6 +169,7 @@ typedef struct ckv_router {
 int ckv_prefill(const ckv_shape* shape, const ckv_router* router, const int32_t* lengths, const void* S,
                 ckv_cache** out, void* stream);
 int ckv_prefill_into(ckv_cache* cache, const ckv_router* router, const void* S, void* stream);
+int64_t ckv_cache_prefill_workspace(const ckv_cache* cache);
 const char* ckv_prefill_kernel_name(const ckv_shape* shape, const ckv_router* router);
 
 /* Borrowed device views of the packed cache; valid until ckv_free. */

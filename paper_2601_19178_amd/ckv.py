@@ -21,7 +21,7 @@ CKV_OK, CKV_ERR_NULL, CKV_ERR_SHAPE, CKV_ERR_INDEX, CKV_ERR_LENGTH, CKV_ERR_UNSU
 
 EXPORTS = [
     "ckv_build_cache", "ckv_build_cache_offloaded", "ckv_cache_is_offloaded", "ckv_prefill", "ckv_prefill_into",
-    "ckv_prefill_kernel_name", "ckv_plan", "ckv_remap_hot_rows", "ckv_cache_idx", "ckv_cache_user_k", "ckv_cache_user_v", "ckv_cache_lengths",
+    "ckv_cache_prefill_workspace", "ckv_prefill_kernel_name", "ckv_plan", "ckv_remap_hot_rows", "ckv_cache_idx", "ckv_cache_user_k", "ckv_cache_user_v", "ckv_cache_lengths",
     "ckv_cache_positions", "ckv_cache_stored_bytes", "ckv_attend", "ckv_reconstruct", "ckv_free",
     "ckv_last_error", "ckv_set_timing", "ckv_kernel_ms", "ckv_variant", "ckv_copy", "ckv_trace_enable", "ckv_trace_read",
 ]
@@ -57,6 +57,8 @@ _lib.ckv_build_cache_offloaded.argtypes = _lib.ckv_build_cache.argtypes
 _lib.ckv_prefill.restype = ctypes.c_int
 _lib.ckv_prefill.argtypes = [ctypes.POINTER(ckv_shape), ctypes.POINTER(ckv_router), _vp, _vp, ctypes.POINTER(_vp), _vp]
 _lib.ckv_prefill_into.restype = ctypes.c_int
+_lib.ckv_cache_prefill_workspace.restype = ctypes.c_int64
+_lib.ckv_cache_prefill_workspace.argtypes = [_vp]
 _lib.ckv_prefill_into.argtypes = [_vp, ctypes.POINTER(ckv_router), _vp, _vp]
 _lib.ckv_prefill_kernel_name.restype = ctypes.c_char_p
 _lib.ckv_prefill_kernel_name.argtypes = [ctypes.POINTER(ckv_shape), ctypes.POINTER(ckv_router)]
@@ -156,6 +158,10 @@ def ckv_prefill(shape, router, lengths, S, stream=0):
 
 def ckv_prefill_into(cache, router, S, stream=0):
     _check(_lib.ckv_prefill_into(cache, ctypes.byref(router), _dev(S), _vp(stream)))
+
+
+def ckv_cache_prefill_workspace(cache):
+    return int(_lib.ckv_cache_prefill_workspace(cache))
 
 
 def ckv_prefill_kernel_name(shape, router):

@@ -580,6 +580,7 @@ void destroy(ckv_cache* c) {
     (void)hipFree(c->d_merge);
     (void)hipFree(c->d_partial);
     (void)hipFree(c->d_trace);
+    (void)hipFree(c->d_pf_ws);
     for (int i = 0; i < 2 * c->timing; ++i) (void)hipEventDestroy(c->ev[i]);
     delete[] c->ev;
     delete c;
@@ -851,6 +852,10 @@ static int router_args(const char* who, const ckv_shape& s, const ckv_router* r,
     a->d_u[0] = d_uk;
     a->d_u[1] = d_uv;
     a->d_e = r->d_e;
+    a->ws = nullptr;
+    a->ws_entries = 0;
+    a->split_first = 0;
+    a->split_s = 1;
     return CKV_OK;
 }
 
@@ -872,6 +877,8 @@ int ckv_prefill_into(ckv_cache* c, const ckv_router* router, const void* S, void
     a.idx = c->d_idx;
     a.user[0] = c->d_user_k;
     a.user[1] = c->d_user_v;
+    a.ws = c->d_pf_ws;
+    a.ws_entries = c->pf_ws_entries;
     hipError_t e = ckv_launch_prefill(a, c->shape.dtype, (hipStream_t)stream);
     if (e != hipSuccess) return fail(CKV_ERR_HIP, "ckv_prefill_into: kernel launch (%s): %s",
                                      ckv_prefill_variant(c->shape.dtype, router->d_e), hipGetErrorString(e));
@@ -888,7 +895,22 @@ int ckv_prefill(const ckv_shape* shape, const ckv_router* router, const int32_t*
     hipDeviceProp_t prop;
     int rc = cache_new("ckv_prefill", shape, lengths, false, st, &c, offs, &prop);
     if (rc != CKV_OK) return rc;
-    rc = ckv_prefill_into(c, router, S, stream);
+    {
+        // workspace that lets the matrix-core kernel fill the chip when its last round of workgroups is short
+        ckv_prefill_args a;
+        rc = router_args("ckv_prefill", c->shape, router, S, c->T, &a);
+        const int64_t entries = rc == CKV_OK ? ckv_prefill_workspace_entries(a, c->shape.dtype) : 0;
+        if (entries > 0) {
+            hipError_t e = hipMalloc((void**)&c->d_pf_ws, sizeof(unsigned long long) * (size_t)entries);
+            if (e == hipSuccess) e = hipMemsetAsync(c->d_pf_ws, 0, sizeof(unsigned long long) * (size_t)entries, st);
+            if (e != hipSuccess) {
+                destroy(c);
+                return fail(CKV_ERR_HIP, "ckv_prefill: workspace of %lld entries: %s", (long long)entries, hipGetErrorString(e));
+            }
+            c->pf_ws_entries = entries;
+        }
+    }
+    if (rc == CKV_OK) rc = ckv_prefill_into(c, router, S, stream);
     if (rc == CKV_OK) rc = cache_finish(c, lengths, offs, prop, st);
     if (rc != CKV_OK) {
         destroy(c);
@@ -897,6 +919,8 @@ int ckv_prefill(const ckv_shape* shape, const ckv_router* router, const int32_t*
     *out = c;
     return CKV_OK;
 }
+
+int64_t ckv_cache_prefill_workspace(const ckv_cache* c) { return c ? c->pf_ws_entries : 0; }
 
 const char* ckv_prefill_kernel_name(const ckv_shape* shape, const ckv_router* router) {
     if (!shape || !router) return "";

@@ -67,6 +67,11 @@ struct ckv_prefill_args {
     int32_t P[2];             // pool entries routed to (0: that side has no router)
     int32_t d_u[2];           // projected columns
     int32_t H, d_e;
+    // blocks of a partly filled last round, cut into split_s workgroups each (matrix-core kernel; set by its launcher)
+    unsigned long long* ws;   // one 64-bit maximum per position of a split block, zero between calls; may be NULL
+    int64_t ws_entries;
+    int64_t split_first;      // first split block
+    int32_t split_s;
 };
 
 enum ckv_kernel_family { CKV_K_STREAM = 0, CKV_K_MFMA = 1, CKV_K_DMA = 2 };
@@ -96,6 +101,8 @@ struct ckv_cache {
     ckv_merge* d_merge;
     float* d_partial;
     unsigned long long* d_trace;  // 8 words per item while tracing is on
+    unsigned long long* d_pf_ws;  // handles made by ckv_prefill: workspace of the split last round, zero between calls
+    int64_t pf_ws_entries;
     // timing: ring of event pairs around the main kernel, filled while timing > 0
     int timing;            // number of pairs in the ring (0 = off)
     long long ev_count;    // launches recorded since timing was switched on
@@ -118,6 +125,8 @@ bool ckv_dma_supported(int d_a, int nw, int qg);
 
 // Prefill (projection + router argmax into the packed cache layout).
 hipError_t ckv_launch_prefill(const ckv_prefill_args& a, int dtype, hipStream_t s);
+// 64-bit workspace entries the matrix-core prefill kernel would use to split its partly filled last round (0: none).
+int64_t ckv_prefill_workspace_entries(const ckv_prefill_args& a, int dtype);
 const char* ckv_prefill_variant(int dtype, int d_e);
 bool ckv_prefill_mfma_supported(int dtype, int d_e);
 

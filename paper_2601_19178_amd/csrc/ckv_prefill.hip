@@ -19,6 +19,7 @@
 // one tile for the usual small d_u, d_a / 32 tiles for a side that is not shared.
 //
 // Scalar kernel: any d_e and either storage type, one thread per (position, head, side).
+#include <algorithm>
 #include <type_traits>
 
 #include "ckv_internal.h"
@@ -95,8 +96,18 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
     const int lane = threadIdx.x & 63;
     const int qn = lane & 31, hh = lane >> 5;
     const int ncls = 2 * a.H;
-    const int cls = blockIdx.x % ncls;
-    const int64_t pblock = blockIdx.x / ncls;
+    // Blocks from split_first on are cut into split_s workgroups, each taking a share of the router tiles
+    // (see launch_mfma); `part` of `nparts` is this workgroup's share.
+    int64_t blk = blockIdx.x;
+    int part = 0, nparts = 1;
+    if (blk >= a.split_first) {
+        const int64_t u = blk - a.split_first;
+        blk = a.split_first + u / a.split_s;
+        part = (int)(u % a.split_s);
+        nparts = a.split_s;
+    }
+    const int cls = (int)(blk % ncls);
+    const int64_t pblock = blk / ncls;
     const int h = cls >> 1, side = cls & 1;
     const int P = a.P[side], d_u = a.d_u[side];  // this side's pool entries (0: not shared) and projected columns
 
@@ -107,8 +118,11 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
     const int nfull = P / TR;                      // stages made of TR valid router rows
     const int nrt = (P + TR - 1) / TR;             // router stages
     const int npj = (d_u + SR - 1) / SR;           // projection stages: 32 columns of the user slice each
-    const int ntt = nrt + npj;
-    if (ntt == 0) return;
+    // this workgroup's stages: router tiles [t_lo, t_hi), then (first part only) the projection tiles
+    const int t_lo = (int)((int64_t)nrt * part / nparts), t_hi = (int)((int64_t)nrt * (part + 1) / nparts);
+    const int nr_loc = t_hi - t_lo;
+    const int n_loc = nr_loc + (part == 0 ? npj : 0);
+    if (n_loc == 0) return;
 
     // ---- positions of this wavefront: B operands, 16 bytes per lane and k-step, straight from S
     const int64_t pos0 = pblock * (32 * QG * NW) + (int64_t)wave * QG * 32;
@@ -144,9 +158,11 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
         loff[i] = (uint32_t)lrow[i] * G::ROWB + lchunk[i];
     }
     const uint32_t boff = (uint32_t)(lane & (TR - 1)) * 4;
-    auto issue = [&](int tile) {
-        const uint32_t st = lds0 + (tile % NS) * G::STAGE;
-        if (tile < nfull) {
+    auto issue = [&](int i) {  // stage i of this workgroup (past the last one: a repeat nothing reads)
+        const uint32_t st = lds0 + (i % NS) * G::STAGE;
+        const int ic = min(i, n_loc - 1);
+        int tile = ic < nr_loc ? t_lo + ic : nrt + (ic - nr_loc);
+        if (i < nr_loc && tile < nfull) {
             const unsigned char* base = wr + (int64_t)tile * (TR * G::ROWB);
 #pragma unroll
             for (int i = 0; i < G::NI; ++i) dma16_uniform(base, loff[i], st + (i * NW + wave) * G::RPI * G::ROWB);
@@ -155,7 +171,6 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
         }
         // ragged last router stage, a projection stage, or a repeat of the last stage into a retired
         // slot (never read): rows are clamped to the last valid one
-        tile = min(tile, ntt - 1);
         const bool proj = tile >= nrt;
         const unsigned char* wbase = proj ? wu : wr;
         const float* bbase = proj ? bu : br;
@@ -207,7 +222,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
             for (int g = 0; g < QG; ++g) acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[kk], sreg[g][kk], acc[g], 0, 0, 0);
         if (KIND == 2) {
             // projection: row c of the block is column c0 + c of the user slice
-            const int c0 = (t - nrt) * SR;
+            const int c0 = (t - nr_loc) * SR;
 #pragma unroll
             for (int g = 0; g < QG; ++g) {
                 const int64_t pos = pos0 + g * 32 + qn;
@@ -221,7 +236,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
                 }
             }
         } else {
-            const int j0 = t * TR;
+            const int j0 = (t_lo + t) * TR;
             float tmax[QG];
 #pragma unroll
             for (int g = 0; g < QG; ++g) {
@@ -256,21 +271,50 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
     for (int i = 0; i < NS - 1; ++i) issue(i);
     wait_vm<(NS - 2) * (G::NI + 1)>();
     lds_barrier();
-    for (int t = 0; t < nfull; ++t) stage(std::integral_constant<int, 0>{}, t);
-    if (nrt > nfull) stage(std::integral_constant<int, 1>{}, nfull);
-    for (int t = nrt; t < ntt; ++t) stage(std::integral_constant<int, 2>{}, t);
+    int t = 0;
+    for (; t < nr_loc && t_lo + t < nfull; ++t) stage(std::integral_constant<int, 0>{}, t);
+    if (t < nr_loc) stage(std::integral_constant<int, 1>{}, t++);  // the part that owns the ragged last router tile
+    for (; t < n_loc; ++t) stage(std::integral_constant<int, 2>{}, t);
     wait_vm<0>();  // the repeated loads past the last stage must land before the workgroup gives its LDS back
 
-    if (nrt > 0) {
+    if (nr_loc > 0) {
 #pragma unroll
         for (int g = 0; g < QG; ++g) {
             const float ov = __uint_as_float(swap_halves(__float_as_uint(bv[g])));
             const int oj = (int)swap_halves((uint32_t)bj[g]);
-            const int best = (ov > bv[g] || (ov == bv[g] && oj < bj[g])) ? oj : bj[g];
+            const bool other = ov > bv[g] || (ov == bv[g] && oj < bj[g]);
+            const int best = other ? oj : bj[g];
             const int64_t pos = pos0 + g * 32 + qn;
-            if (hh == 0 && pos < a.T) a.idx[((int64_t)side * a.H + h) * a.T + pos] = best;
+            if (hh == 0 && pos < a.T) {
+                if (nparts == 1) {
+                    a.idx[((int64_t)side * a.H + h) * a.T + pos] = best;
+                } else {
+                    // the parts of a block meet in one 64-bit maximum per position: score (as an ordered
+                    // integer, -0 folded into +0) above, complement of the index below, so that of equal
+                    // scores the lowest pool entry wins, as inside a workgroup
+                    const uint32_t u = __float_as_uint((other ? ov : bv[g]) + 0.0f);
+                    const uint32_t ord = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+                    const unsigned long long key = ((unsigned long long)ord << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)best);
+                    atomicMax(a.ws + (blk - a.split_first) * (32 * QG * NW) + (wave * QG + g) * 32 + qn, key);
+                }
+            }
         }
     }
+}
+
+// Indices of the positions whose blocks were split: unpack the winning key, leave the workspace zeroed
+// for the next call.
+__global__ __launch_bounds__(256) void ckv_prefill_finish_kernel(ckv_prefill_args a, int per_wg, int64_t entries) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= entries) return;
+    const int ncls = 2 * a.H;
+    const int64_t blk = a.split_first + e / per_wg;
+    const int cls = (int)(blk % ncls);
+    const int h = cls >> 1, side = cls & 1;
+    const int64_t pos = blk / ncls * per_wg + e % per_wg;
+    const unsigned long long key = a.ws[e];
+    a.ws[e] = 0ull;
+    if (pos < a.T && a.P[side] > 0) a.idx[((int64_t)side * a.H + h) * a.T + pos] = (int32_t)(0xFFFFFFFFu - (uint32_t)key);
 }
 
 // Any d_e, fp32 or bf16 storage: one thread per (position, head, side); fp32 accumulation in
@@ -325,16 +369,65 @@ __global__ __launch_bounds__(256) void ckv_prefill_scalar_kernel(ckv_prefill_arg
     }
 }
 
+// Split policy.  All workgroups do the same amount of work, so a launch of nb blocks on `slots` resident
+// workgroups runs in rounds and the last round is only partly full (or the only round, for a short batch).
+// When it is less than 60 % full, each of its blocks is cut into s workgroups that take 1/s of the router
+// tiles each and meet in a 64-bit atomic maximum per position (workspace of the handle), so that the round
+// fills the chip: a batch of one or two users then uses all compute units instead of a handful.
+struct SplitPlan {
+    int64_t first;  // first split block (== nb: nothing is split)
+    int s;
+    int64_t entries;  // workspace entries needed
+};
+static SplitPlan plan_split(int64_t nb, int64_t slots, int per_wg, int max_router_tiles, size_t ws_entries) {
+    SplitPlan p{nb, 1, 0};
+    if (nb == 0 || slots <= 0) return p;
+    const int64_t rem = nb % slots;
+    if (rem == 0 || rem * 10 > slots * 6) return p;
+    const int64_t s = std::min<int64_t>(std::min<int64_t>(slots / rem, max_router_tiles / 8), 64);
+    if (s < 2 || (size_t)(rem * per_wg) > ws_entries) return p;
+    p.first = nb - rem;
+    p.s = (int)s;
+    p.entries = rem * per_wg;
+    return p;
+}
+
 template <int DE, int NW, int QG, int TR, int NS, int WPE>
-hipError_t launch_mfma(const ckv_prefill_args& a, hipStream_t s) {
+int64_t resident_slots() {
+    static const int64_t slots = [] {
+        int dev = 0, cus = 0, per_cu = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return (int64_t)0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return (int64_t)0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)ckv_prefill_mfma_kernel<DE, NW, QG, TR, NS, WPE>,
+                                                         NW * 64, PGeo<DE, NW, TR, NS>::LDS) != hipSuccess)
+            return (int64_t)0;
+        return (int64_t)cus * per_cu;
+    }();
+    return slots;
+}
+
+template <int DE, int NW, int QG, int TR, int NS, int WPE>
+hipError_t launch_mfma(ckv_prefill_args a, hipStream_t s, bool plan_only, int64_t* entries) {
     constexpr int lds = PGeo<DE, NW, TR, NS>::LDS;
     static hipError_t prepared = hipFuncSetAttribute((const void*)ckv_prefill_mfma_kernel<DE, NW, QG, TR, NS, WPE>,
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (prepared != hipSuccess) return prepared;
-    const int64_t per_wg = 32 * QG * NW;
-    const int64_t blocks = (a.T + per_wg - 1) / per_wg * 2 * a.H;
+    constexpr int per_wg = 32 * QG * NW;
+    const int64_t nb = (a.T + per_wg - 1) / per_wg * 2 * a.H;
+    const int max_tiles = (std::max(a.P[0], a.P[1]) + TR - 1) / TR;
+    const SplitPlan sp = plan_split(nb, resident_slots<DE, NW, QG, TR, NS, WPE>(), per_wg, max_tiles,
+                                    plan_only ? (size_t)-1 : (a.ws ? a.ws_entries : 0));
+    if (plan_only) {
+        *entries = sp.entries;
+        return hipSuccess;
+    }
+    a.split_first = sp.first;
+    a.split_s = sp.s;
+    const int64_t blocks = sp.first + (nb - sp.first) * sp.s;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     hipLaunchKernelGGL((ckv_prefill_mfma_kernel<DE, NW, QG, TR, NS, WPE>), dim3((unsigned)blocks), dim3(NW * 64), lds, s, a);
+    if (sp.entries > 0)
+        hipLaunchKernelGGL(ckv_prefill_finish_kernel, dim3((unsigned)((sp.entries + 255) / 256)), dim3(256), 0, s, a, per_wg, sp.entries);
     return hipGetLastError();
 }
 
@@ -349,13 +442,22 @@ const char* ckv_prefill_variant(int dtype, int d_e) {
     return dtype == CKV_F32 ? "prefill_scalar_f32" : "prefill_scalar_bf16";
 }
 
+static hipError_t dispatch_mfma(const ckv_prefill_args& a, hipStream_t s, bool plan_only, int64_t* entries) {
+    if (a.d_e == 64) return launch_mfma<64, 4, 2, 32, 4, 3>(a, s, plan_only, entries);
+    if (a.d_e == 128) return launch_mfma<128, 4, 2, 32, 4, 3>(a, s, plan_only, entries);
+    return launch_mfma<256, 4, 1, 32, 4, 3>(a, s, plan_only, entries);
+}
+
+int64_t ckv_prefill_workspace_entries(const ckv_prefill_args& a, int dtype) {
+    int64_t entries = 0;
+    if (a.T == 0 || !ckv_prefill_mfma_supported(dtype, a.d_e)) return 0;
+    if (dispatch_mfma(a, nullptr, true, &entries) != hipSuccess) return 0;
+    return entries;
+}
+
 hipError_t ckv_launch_prefill(const ckv_prefill_args& a, int dtype, hipStream_t s) {
     if (a.T == 0) return hipSuccess;
-    if (ckv_prefill_mfma_supported(dtype, a.d_e)) {
-        if (a.d_e == 64) return launch_mfma<64, 4, 2, 32, 4, 3>(a, s);
-        if (a.d_e == 128) return launch_mfma<128, 4, 2, 32, 4, 3>(a, s);
-        return launch_mfma<256, 4, 1, 32, 4, 3>(a, s);
-    }
+    if (ckv_prefill_mfma_supported(dtype, a.d_e)) return dispatch_mfma(a, s, false, nullptr);
     const int64_t total = a.T * a.H * 2;
     const int blocks = (int)((total + 255) / 256 < 65536 ? (total + 255) / 256 : 65536);
     if (dtype == CKV_F32) hipLaunchKernelGGL(ckv_prefill_scalar_kernel<float>, dim3(blocks), dim3(256), 0, s, a);

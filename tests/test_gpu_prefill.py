@@ -215,3 +215,47 @@ def test_full_size_prefill_sampled(gpu):
     for got, ref in ((uk, ruk), (uv, ruv)):
         g = wl.to_f64(got.astype(np.uint16), wl.BF16).transpose(1, 0, 2)[sample]
         assert (np.abs(g - ref) <= user_tolerance(ref, wl.BF16)).all()
+
+
+def test_short_batch_is_cut_along_the_pool(gpu):
+    """A batch too short to fill the chip: the workgroups are cut along the pool entries and meet in an atomic
+    maximum.  Ties across the cut (integer inputs; scores of +0 and -0) must still go to the lowest entry, a second
+    call must find the workspace clean, and a handle without workspace must give the same cache."""
+    import torch
+    ckv, session = gpu
+    lengths = (300, 0, 77, 1)
+    r = wl.make_prefill(T=sum(lengths), H=2, d_e=128, d_u=8, P=4096, dtype=wl.BF16, seed=90, integers=1)
+    w = decode_workload(lengths, r)
+    say("[case] prefill cut along the pool")
+    ik, iv, ruk, ruv = oracle.prefill(r)
+    with session.Session(w, prefill=r) as s:
+        assert ckv.ckv_cache_prefill_workspace(s.cache) > 0, "this shape should have been cut"
+        first = [a.copy() for a in s.packed_views()]
+        np.testing.assert_array_equal(first[0][0].T, ik)
+        np.testing.assert_array_equal(first[0][1].T, iv)
+        s.prefill_again()
+        s.prefill_again()
+        for a, b in zip(first, s.packed_views()):
+            np.testing.assert_array_equal(a, b)
+        # the same router through a handle that ckv_build_cache made (no workspace: uncut rounds)
+        with session.Session(w) as plain:
+            assert ckv.ckv_cache_prefill_workspace(plain.cache) == 0
+            ckv.ckv_prefill_into(plain.cache, s.router, s.S, plain.stream)
+            for a, b in zip(first, plain.packed_views()):
+                np.testing.assert_array_equal(a, b)
+    # all scores equal, but -0 in the first half of the pool and +0 in the second: entry 0 must win everywhere
+    r["S"][:] = 0
+    for k in ("w_rk", "w_rv"):
+        r[k][:, :2048] = wl.f32_to_bf16_bits(np.full((2, 2048, 128), -1.0, np.float32))
+        r[k][:, 2048:] = wl.f32_to_bf16_bits(np.full((2, 2048, 128), 1.0, np.float32))
+    r["b_rk"][:] = 0.0
+    r["b_rv"][:] = 0.0
+    r["b_rk"][:, :2048] = -0.0
+    r["b_rv"][:, :2048] = -0.0
+    ik, iv, _, _ = oracle.prefill(r)
+    assert (ik == 0).all() and (iv == 0).all()
+    with session.Session(w, prefill=r) as s:
+        assert ckv.ckv_cache_prefill_workspace(s.cache) > 0
+        idx = s.packed_views()[0]
+    assert (idx == 0).all(), "equal scores across the cut did not go to the lowest pool entry"
+    say("  ok")
