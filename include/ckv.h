@@ -60,6 +60,14 @@ enum {
  * Attention is non-causal over the user's n_b positions.  A user with n_b = 0 gets out = 0.
  * pool_ld is the row stride of both pools in elements, pool_ld >= d_g; columns
  * [d_g, pool_ld) of a pool row are padding and are never interpreted.
+ * Limits (checked by ckv_build_cache / ckv_prefill, which fail with the code named):
+ *   B, H, Nq >= 1; d_g, d_u >= 0 with d_a >= 1; P >= 1 when d_g > 0 (CKV_ERR_SHAPE);
+ *   lengths >= 0 and T * H <= 2^40 (CKV_ERR_LENGTH); pools may exceed 4 GiB (row offsets are 64-bit);
+ *   d_a <= 256 for any widths and stride; d_a <= 512 when d_u, d_g and pool_ld are multiples of 4,
+ *   <= 1024 for bf16 when they are multiples of 8 (CKV_ERR_UNSUPPORTED beyond);
+ *   every device pointer 16-byte aligned (CKV_ERR_UNSUPPORTED); device gfx950 (CKV_ERR_UNSUPPORTED).
+ * The matrix-core kernels take bf16 with d_a of 64 or 128, Nq >= 8 and pool_ld a multiple of 8 (scale > 0
+ * for softmax); every other shape runs the streaming kernel.  ckv_variant names the choice.
  */
 typedef struct ckv_shape {
     int32_t B, H, d_g, d_u, P, Nq;

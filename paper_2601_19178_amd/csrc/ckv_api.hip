@@ -545,7 +545,7 @@ void choose_variant(ckv_cache* c) {
     }
     pick_stream_vec(s, &c->vec, &c->grp);
     int ncb = (d_a + c->grp * c->vec - 1) / (c->grp * c->vec);
-    c->ncb = ncb <= 1 ? 1 : (ncb <= 2 ? 2 : (ncb <= 4 ? 4 : 8));
+    c->ncb = ncb <= 1 ? 1 : (ncb <= 2 ? 2 : (ncb <= 4 ? 4 : (ncb <= 8 ? 8 : 16)));
     c->QB = s.Nq;
     c->nw = 4;  // wavefronts per item; plan_work drops to 2 when the items outnumber the resident workgroups
     snprintf(c->variant, sizeof c->variant, "stream_%s_v%d_c%d%s_%s", s.dtype == CKV_F32 ? "f32" : "bf16", c->vec,
@@ -625,11 +625,12 @@ static int cache_new(const char* who, const ckv_shape* shape, const int32_t* len
     c->T = T;
     c->offloaded = offloaded ? 1 : 0;
     choose_variant(c);
-    if (c->family == CKV_K_STREAM && (d_a + c->grp * c->vec - 1) / (c->grp * c->vec) > 8) {
-        const int vec = c->vec;
+    // column blocks the streaming kernel is built for: 8 (16 when it moves single elements)
+    if (c->family == CKV_K_STREAM && (d_a + c->grp * c->vec - 1) / (c->grp * c->vec) > (c->vec == 1 ? 16 : 8)) {
+        const int limit = c->grp * c->vec * (c->vec == 1 ? 16 : 8);
         delete c;
         return fail(CKV_ERR_UNSUPPORTED, "%s: d_a = %lld exceeds the streaming kernel's limit of %d columns at this alignment", who,
-                    (long long)d_a, 128 * vec);
+                    (long long)d_a, limit);
     }
     int rc = CKV_OK;
     const size_t n_ph = (size_t)T * s.H;

@@ -341,8 +341,13 @@ hipError_t launch_ncb(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
         case 2: return launch_mode<T, VEC, 2>(c, a, s);
         case 4: return launch_mode<T, VEC, 4>(c, a, s);
         case 8: return launch_mode<T, VEC, 8>(c, a, s);
-        default: return hipErrorInvalidValue;
+        default: break;
     }
+    // wide rows that allow no vector loads (odd widths or strides): one element per lane, up to 256 columns
+    if constexpr (VEC == 1) {
+        if (c->ncb == 16) return launch_mode<T, VEC, 16>(c, a, s);
+    }
+    return hipErrorInvalidValue;
 }
 
 }  // namespace

@@ -104,6 +104,10 @@ def test_stream_ragged(gpu, dtype, mode):
     (wl.BF16, 96, 16, 80, 5),    # 8-wide bf16 vectors, Nq not a power of two
     (wl.F32, 12, 0, 12, 2),      # d_u = 0: pure pool attention
     (wl.F32, 12, 12, 0, 2),      # d_g = 0: ordinary attention over the user K/V
+    (wl.F32, 255, 7, 250, 2),    # the widest rows at each alignment: single elements, sixteen column blocks
+    (wl.BF16, 256, 3, 253, 3),
+    (wl.F32, 512, 8, 504, 1),    # 4-wide vectors, eight column blocks
+    (wl.BF16, 1024, 8, 1016, 2), # 8-wide bf16 vectors, eight column blocks
 ])
 def test_stream_shapes(gpu, dtype, d_a, d_u, pool_ld, Nq):
     w = make(RAGGED, dtype, wl.SOFTMAX, d_a=d_a, d_u=d_u, H=2, P=77, Nq=Nq, pool_ld=pool_ld)
@@ -474,3 +478,36 @@ def test_pool_rows_beyond_four_gib(gpu, kind):
     assert np.array_equal(k_full, ok.transpose(1, 0, 2)) and np.array_equal(v_full, ov.transpose(1, 0, 2))
     norm = check(out, oracle.attend(w), w["dtype"], what=f"pool beyond 4 GiB ({kind})")
     say(f"  ok, norm-wise error {norm:.3e}, rows bit-exact")
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_seeded_random_shapes(gpu, block):
+    """Twelve seeded random shapes per block, drawn over everything the dispatcher looks at (storage type,
+    head width, user width, pool stride, query count, weighting, which side is shared, ragged lengths with
+    empty histories), each against the oracle element by element."""
+    for case in range(12):
+        rng = np.random.default_rng(1000 * block + case)
+        matrix = rng.random() < 0.6
+        if matrix:
+            dtype, d_a = wl.BF16, int(rng.choice([64, 128]))
+            d_u = int(rng.choice([0, 2, 4, 6, 8, 3, 16, 24]))
+            Nq = int(rng.integers(8, 300))
+        else:
+            dtype = int(rng.choice([wl.F32, wl.BF16]))
+            d_a = int(rng.choice([8, 12, 16, 40, 64, 72, 128, 200]))
+            d_u = int(rng.integers(0, min(d_a, 16) + 1))
+            Nq = int(rng.integers(1, 8))
+        d_g = d_a - d_u
+        align = 8 if matrix else 1
+        pool_ld = 0 if d_g == 0 else int(rng.choice([(d_g + align - 1) // align * align, d_a, d_a + 8]))
+        if d_g > 0 and pool_ld < d_g:
+            pool_ld = d_a
+        share = int(rng.choice([wl.SHARE_KV, wl.SHARE_KV, wl.SHARE_K, wl.SHARE_V])) if d_g > 0 else wl.SHARE_KV
+        mode = int(rng.choice([wl.SOFTMAX, wl.SILU_OVER_N]))
+        B = int(rng.integers(1, 9))
+        lengths = rng.choice([0, 1, 31, 32, 33, 64, 100, 257, 900, 3000], size=B).astype(np.int32)
+        H, P = int(rng.integers(1, 4)), int(rng.choice([1, 2, 77, 700, 5000]))
+        kw = dict(pool_ld=pool_ld) if d_g > 0 else {}
+        w = make(lengths, dtype, mode, d_a=d_a, d_u=d_u, H=H, P=P, Nq=Nq, seed=2000 + 100 * block + case,
+                 idx=("zipf", 1.1) if rng.random() < 0.3 else "uniform", share=share, **kw)
+        run_and_check(gpu, w, f"random shape {block}.{case}: d_a={d_a} d_u={d_u} ld={pool_ld} share={share} lengths={lengths.tolist()}")

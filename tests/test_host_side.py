@@ -60,8 +60,8 @@ def test_build_cache_validates_before_touching_the_device():
     expect(ckv.CKV_ERR_SHAPE, mode=5)
     expect(ckv.CKV_ERR_SHAPE, scale=float("nan"))
     expect(ckv.CKV_ERR_SHAPE, share=3)
-    # wider than the streaming kernel serves at this alignment (scalar loads: 128 columns), and no matrix-core shape
-    expect(ckv.CKV_ERR_UNSUPPORTED, d_g=129, pool_ld=129)
+    # wider than the streaming kernel serves at this alignment (scalar loads: 256 columns), and no matrix-core shape
+    expect(ckv.CKV_ERR_UNSUPPORTED, d_g=257, pool_ld=257)
     # sharing only the keys: idx_v may be absent, idx_k may not
     expect(ckv.CKV_ERR_NULL, idx=(None, zeros), share=ckv.CKV_SHARE_K)
     expect(ckv.CKV_ERR_LENGTH, lengths=np.array([3, -2], np.int32))
