@@ -259,3 +259,29 @@ def test_short_batch_is_cut_along_the_pool(gpu):
         idx = s.packed_views()[0]
     assert (idx == 0).all(), "equal scores across the cut did not go to the lowest pool entry"
     say("  ok")
+
+
+@pytest.mark.parametrize("block", range(3))
+def test_seeded_random_prefill_shapes(gpu, block):
+    """Eight seeded random prefill shapes per block (embedding width, pool size, user width, heads, which side is
+    shared, batch from one short history to several position blocks: both the cut and the uncut launch), on
+    integer inputs where every index and user slice is fixed exactly, and on random inputs to the fp32 bound."""
+    for case in range(8):
+        rng = np.random.default_rng(500 + 10 * block + case)
+        mfma = rng.random() < 0.75
+        d_e = int(rng.choice([64, 128, 256])) if mfma else int(rng.choice([8, 24, 72, 100, 200]))
+        dtype = wl.BF16 if mfma else int(rng.choice([wl.F32, wl.BF16]))
+        P = int(rng.choice([2, 31, 32, 33, 77, 333, 1000, 2049, 5000]))
+        d_u = int(rng.choice([0, 1, 3, 4, 8, 16, 33]))
+        H = int(rng.integers(1, 4))
+        B = int(rng.integers(1, 7))
+        lengths = rng.choice([0, 1, 31, 64, 100, 257, 700], size=B).astype(np.int32)
+        if lengths.sum() == 0:
+            lengths[0] = 5
+        share = int(rng.choice([wl.SHARE_KV, wl.SHARE_KV, wl.SHARE_K, wl.SHARE_V]))
+        d_a = d_u + int(rng.choice([8, 24, 56]))
+        exact = rng.random() < 0.6
+        r = wl.make_prefill(T=int(lengths.sum()), H=H, d_e=d_e, d_u=d_u, P=P, dtype=dtype, seed=600 + 10 * block + case,
+                            integers=1 if exact else None, share=share, d_a=d_a if share != wl.SHARE_KV else None)
+        run_prefill(gpu, lengths, r, f"random prefill {block}.{case}: d_e={d_e} P={P} d_u={d_u} H={H} share={share} lengths={lengths.tolist()}",
+                    "prefill_mfma_bf16" if mfma else "prefill_scalar", exact=exact, d_g=d_a - d_u)
