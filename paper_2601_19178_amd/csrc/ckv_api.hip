@@ -81,46 +81,112 @@ __global__ void ckv_reconstruct_kernel(const int32_t* __restrict__ idx, const U*
 
 // Merge of the pieces of a split history.  Softmax pieces carry (acc, m, l) with acc and l
 // relative to the piece maximum m; SiLU pieces carry only acc.  Block (x, y) handles merge
-// entry x and queries 16y .. 16y+15, sixteen threads per query.
+// entry x and queries 16y .. 16y+15, sixteen threads per query, eight columns per thread and pass.
+// The kernel is a chain of memory round trips, so it is written to have few: the (m, l) of up to 64
+// pieces and the rows of the first four are requested together; the weights exp(m_p - M) are computed
+// once per query into LDS; the rows of the next four pieces are requested before the current four are
+// accumulated.
 template <typename U, int MODE>
 __global__ __launch_bounds__(256) void ckv_merge_kernel(const ckv_merge* __restrict__ list, const float* __restrict__ partial,
                                                         U* __restrict__ out, int H, int Nq, int d_a, int QB) {
+    constexpr int PCH = 64, CB = 8, SP = 4;
+    __shared__ float sw[16][PCH];
     const ckv_merge mg = list[blockIdx.x];
     const int64_t stride = (int64_t)QB * (d_a + 2);
-    const int j = blockIdx.y * 16 + (threadIdx.x >> 4);
+    const int jq = threadIdx.x >> 4;
+    const int j = blockIdx.y * 16 + jq;
     const int c0 = threadIdx.x & 15;
-    if (j >= QB || mg.q0 + j >= Nq) return;
+    const bool valid = j < QB && mg.q0 + j < Nq;  // (no early exit: the block meets at barriers)
+    const int jj = valid ? j : 0;
     const float* base = partial + (int64_t)mg.part0 * stride;
+    const float* mrow = base + (int64_t)QB * d_a + jj;  // m of piece p at mrow[p * stride], l at mrow[p * stride + QB]
+    const int nparts = mg.nparts;
     float M = -INFINITY, denom = 0.f;
     if (MODE == CKV_SOFTMAX) {
-        for (int p = 0; p < mg.nparts; ++p) M = fmaxf(M, base[p * stride + (int64_t)QB * d_a + j]);
-        for (int p = 0; p < mg.nparts; ++p) {
-            const float mp = base[p * stride + (int64_t)QB * d_a + j];
-            denom += (mp == -INFINITY ? 0.f : __expf(mp - M)) * base[p * stride + (int64_t)QB * d_a + QB + j];
+        if (nparts > PCH) {  // more pieces than one chunk: the maximum needs a pass of its own
+            for (int p = c0; p < nparts; p += 16) M = fmaxf(M, mrow[p * stride]);
+#pragma unroll
+            for (int d = 1; d < 16; d <<= 1) M = fmaxf(M, __shfl_xor(M, d));
         }
     } else {
         denom = (float)mg.n_total;
     }
-    const float inv = denom > 0.f ? 1.f / denom : 0.f;
-    const int64_t o = (((int64_t)mg.b * H + mg.h) * Nq + mg.q0 + j) * d_a;
-    for (int c = c0; c < d_a; c += 16) {
-        float acc = 0.f;
-        for (int p = 0; p < mg.nparts; ++p) {
-            float w = 1.f;
-            if (MODE == CKV_SOFTMAX) {
-                const float mp = base[p * stride + (int64_t)QB * d_a + j];
-                w = mp == -INFINITY ? 0.f : __expf(mp - M);
+    const int64_t o = (((int64_t)mg.b * H + mg.h) * Nq + mg.q0 + jj) * d_a;
+    for (int cbase = 0; cbase < d_a; cbase += 16 * CB) {
+        float acc[CB];
+#pragma unroll
+        for (int k = 0; k < CB; ++k) acc[k] = 0.f;
+        auto load_rows = [&](int p, float (&v)[SP][CB]) {  // rows of pieces p .. p+SP-1 (zeros past the last)
+#pragma unroll
+            for (int i = 0; i < SP; ++i) {
+                const float* row = base + (int64_t)(p + i) * stride + (int64_t)jj * d_a + cbase + c0;
+#pragma unroll
+                for (int k = 0; k < CB; ++k) v[i][k] = (p + i < nparts && cbase + c0 + 16 * k < d_a) ? row[16 * k] : 0.f;
             }
-            acc += w * base[p * stride + (int64_t)j * d_a + c];
+        };
+        for (int p0 = 0; p0 < nparts; p0 += PCH) {
+            const int np = min(PCH, nparts - p0);
+            float v[SP][CB];
+            load_rows(p0, v);
+            if (MODE == CKV_SOFTMAX) {
+                float mp[PCH / 16], lp[PCH / 16];
+#pragma unroll
+                for (int i = 0; i < PCH / 16; ++i) {
+                    const int pp = c0 + 16 * i;
+                    mp[i] = pp < np ? mrow[(p0 + pp) * stride] : -INFINITY;
+                    lp[i] = pp < np ? mrow[(p0 + pp) * stride + QB] : 0.f;
+                }
+                if (nparts <= PCH) {
+#pragma unroll
+                    for (int i = 0; i < PCH / 16; ++i) M = fmaxf(M, mp[i]);
+#pragma unroll
+                    for (int d = 1; d < 16; d <<= 1) M = fmaxf(M, __shfl_xor(M, d));
+                }
+                __syncthreads();  // the previous chunk's weights are no longer read
+#pragma unroll
+                for (int i = 0; i < PCH / 16; ++i) {
+                    const float w = mp[i] == -INFINITY ? 0.f : __expf(mp[i] - M);
+                    sw[jq][c0 + 16 * i] = w;
+                    if (cbase == 0) denom += w * lp[i];
+                }
+                __syncthreads();
+            }
+            for (int q0 = 0; q0 < np; q0 += SP) {
+                float vn[SP][CB];
+                const bool more = q0 + SP < np;
+                if (more) load_rows(p0 + q0 + SP, vn);
+#pragma unroll
+                for (int i = 0; i < SP; ++i) {
+                    const float w = MODE == CKV_SOFTMAX ? sw[jq][min(q0 + i, PCH - 1)] : 1.f;
+#pragma unroll
+                    for (int k = 0; k < CB; ++k) acc[k] += w * v[i][k];  // pieces past the last were loaded as zeros
+                }
+                if (more) {
+#pragma unroll
+                    for (int i = 0; i < SP; ++i)
+#pragma unroll
+                        for (int k = 0; k < CB; ++k) v[i][k] = vn[i][k];
+                }
+            }
         }
-        const float r = acc * inv;
-        if (sizeof(U) == 4) {
-            ((float*)out)[o + c] = r;
-        } else {
-            uint32_t u = __float_as_uint(r);
-            if ((u & 0x7FFFFFFFu) > 0x7F800000u) u |= 0x400000u;
-            else u += 0x7FFFu + ((u >> 16) & 1u);
-            ((uint16_t*)out)[o + c] = (uint16_t)(u >> 16);
+        if (MODE == CKV_SOFTMAX && cbase == 0) {
+#pragma unroll
+            for (int d = 1; d < 16; d <<= 1) denom += __shfl_xor(denom, d);
+        }
+        const float inv = denom > 0.f ? 1.f / denom : 0.f;
+#pragma unroll
+        for (int k = 0; k < CB; ++k) {
+            const int c = cbase + c0 + 16 * k;
+            if (!valid || c >= d_a) continue;
+            const float r = acc[k] * inv;
+            if (sizeof(U) == 4) {
+                ((float*)out)[o + c] = r;
+            } else {
+                uint32_t u = __float_as_uint(r);
+                if ((u & 0x7FFFFFFFu) > 0x7F800000u) u |= 0x400000u;
+                else u += 0x7FFFu + ((u >> 16) & 1u);
+                ((uint16_t*)out)[o + c] = (uint16_t)(u >> 16);
+            }
         }
     }
 }
@@ -287,7 +353,7 @@ void build_work(ckv_cache* c, const int32_t* lengths, const std::vector<int64_t>
                 units.push_back({b, h, qb * c->QB, lengths[b], offs[b]});
                 longest = std::max<int64_t>(longest, lengths[b]);
             }
-    // Candidate piece lengths: no split, then halvings of the longest history down to 512.
+    // Candidate piece lengths: no split, then halvings of the longest history down to 128.
     // Cost of a candidate, in positions per slot: simulated finish time plus the traffic of the
     // split workspace (written and read once) expressed in positions of gather traffic.
     const int64_t overhead = c->family == CKV_K_STREAM ? 16 : 128;  // per-item fill/drain, in positions
@@ -298,7 +364,7 @@ void build_work(ckv_cache* c, const int32_t* lengths, const std::vector<int64_t>
     double best_cost = -1.0;
     int best_parts = 0;
     int64_t best_piece = 0;
-    for (int64_t piece = INT64_MAX; piece >= 512; piece = (piece == INT64_MAX ? (longest + 1) / 2 : piece / 2)) {
+    for (int64_t piece = INT64_MAX; piece >= 128; piece = (piece == INT64_MAX ? (longest + 1) / 2 : piece / 2)) {
         if (piece != INT64_MAX) piece = (piece + 63) / 64 * 64;
         std::vector<ckv_item> it2;
         std::vector<ckv_merge> mg2;
@@ -313,7 +379,7 @@ void build_work(ckv_cache* c, const int32_t* lengths, const std::vector<int64_t>
             best_parts = parts;
             best_piece = piece;
         }
-        if (piece != INT64_MAX && piece <= 512) break;
+        if (piece != INT64_MAX && piece <= 128) break;
         if (units.size() > (size_t)(64 * slots)) break;  // plenty of units: splitting cannot pay
     }
     items.swap(best_items);
@@ -460,7 +526,10 @@ void build_work_static(ckv_cache* c, const int32_t* lengths, const std::vector<i
     std::vector<std::vector<Piece>> best;
     double best_cost = -1;
     int64_t best_piece = 0;
-    for (int64_t piece = INT64_MAX; piece >= 512; piece = (piece == INT64_MAX ? (longest + 1) / 2 : piece / 2)) {
+    // shortest piece tried: with few users a history is cut until the pieces fill the workgroups (one user of
+    // config 4: 64 items of ~590 positions take 37 us, 200 of ~190 take 32; config 3: 24 -> 14 us)
+    const int64_t min_piece = 128;
+    for (int64_t piece = INT64_MAX; piece >= min_piece; piece = (piece == INT64_MAX ? (longest + 1) / 2 : piece / 2)) {
         if (piece != INT64_MAX) piece = (piece + 63) / 64 * 64;
         std::vector<std::vector<Piece>> lists;
         int parts = 0;
@@ -470,7 +539,7 @@ void build_work_static(ckv_cache* c, const int32_t* lengths, const std::vector<i
             best.swap(lists);
             best_piece = piece;
         }
-        if (piece != INT64_MAX && piece <= 512) break;
+        if (piece != INT64_MAX && piece <= min_piece) break;
         if (units.size() > (size_t)(8 * slots)) break;  // plenty of units per workgroup: uniform cuts cannot pay
     }
     // part slots: the pieces of a split unit get consecutive workspace slots, in position order
