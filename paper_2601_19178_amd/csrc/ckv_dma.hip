@@ -31,6 +31,7 @@ typedef __attribute__((address_space(3))) unsigned char lds_u8;
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
 typedef __attribute__((address_space(3))) uint32_t lds_u32;
+typedef __attribute__((address_space(3))) float lds_f32;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
 
@@ -475,7 +476,12 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
             if (row < qrows) *reinterpret_cast<u32x4*>(odst + (int64_t)row * (DA * 2) + c * 16) = v;
         }
     } else {
+        // the fp32 accumulators go through LDS too (a lane holds one query's columns; written straight
+        // to memory every store would touch 64 cache lines), then out as whole rows, 16 bytes per lane
         float* ws = a.partial + (int64_t)it.part * a.QB * (DA + 2);
+        constexpr int FS = DA * 4 + 16;  // bytes per staged row
+        static_assert(NW * QG * 32 * FS <= NS * G::STAGE, "the staged accumulators must fit in the retired stages");
+        const uint32_t flds = lds0 + wave * (QG * 32 * FS);
 #pragma unroll
         for (int g = 0; g < QG; ++g) {
             const int j = (wave * QG + g) * 32 + qn;
@@ -485,13 +491,22 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
                 for (int r = 0; r < 16; ++r) {
                     const int ci = 32 * dt + 8 * (r >> 2) + 4 * hh + (r & 3);
                     const int pc = ci < dgv ? ci + duv : ci - dgv;
-                    ws[(int64_t)j * DA + pc] = oacc[g][dt][r];
+                    *(lds_f32*)(uintptr_t)(flds + (g * 32 + qn) * FS + pc * 4) = oacc[g][dt][r];
                 }
             if (hh == 0) {
                 ws[(int64_t)a.QB * DA + j] = m_ref[g] * kLn2;
                 ws[(int64_t)a.QB * DA + a.QB + j] = l_tot[g];
             }
         }
+        float* wdst = ws + (int64_t)(wave * QG * 32) * DA;
+#pragma unroll
+        for (int i = 0; i < QG * 32 * (DA / 4) / 64; ++i) {
+            const int e = i * 64 + lane, row = e / (DA / 4), c = e % (DA / 4);
+            const u32x4 v = *(const lds_u32x4*)(uintptr_t)(flds + row * FS + c * 16);
+            *reinterpret_cast<u32x4*>(wdst + (int64_t)row * DA + c * 4) = v;
+        }
+        // this wavefront's staging rows lie where other wavefronts stage the next item's queries
+        lds_barrier();
     }
     if (tr && tid == 0) tr[3] = wall_clock64();
     }  // items of this workgroup
