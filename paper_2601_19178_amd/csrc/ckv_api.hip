@@ -364,14 +364,22 @@ void build_work(ckv_cache* c, const int32_t* lengths, const std::vector<int64_t>
     double best_cost = -1.0;
     int best_parts = 0;
     int64_t best_piece = 0;
-    for (int64_t piece = INT64_MAX; piece >= 128; piece = (piece == INT64_MAX ? (longest + 1) / 2 : piece / 2)) {
+    // The merge kernel is a chain of memory round trips, about one per four pieces of a history: in positions
+    // of work of one workgroup, a microsecond is ~150 (streaming kernel) or ~25 (matrix-core kernel).
+    const int64_t min_piece = 128;
+    const double round_trip = c->family == CKV_K_STREAM ? 150.0 : 25.0;
+    for (int64_t piece = INT64_MAX; piece >= min_piece; piece = (piece == INT64_MAX ? (longest + 1) / 2 : piece / 2)) {
         if (piece != INT64_MAX) piece = (piece + 63) / 64 * 64;
         std::vector<ckv_item> it2;
         std::vector<ckv_merge> mg2;
         int parts = 0;
         make_items(c, units, piece, it2, mg2, &parts);
         double cost = (double)simulate_dispatch(it2, slots, overhead) + parts * part_positions / (double)slots;
-        if (parts > 0) cost *= 1.02;  // the merge is a second launch
+        if (parts > 0) {  // the merge is a second launch
+            int most = 0;
+            for (const ckv_merge& m : mg2) most = std::max(most, (int)m.nparts);
+            cost = cost * 1.02 + round_trip * (2 + (most + 3) / 4);
+        }
         if (best_cost < 0 || cost < best_cost) {
             best_cost = cost;
             best_items.swap(it2);
@@ -379,7 +387,7 @@ void build_work(ckv_cache* c, const int32_t* lengths, const std::vector<int64_t>
             best_parts = parts;
             best_piece = piece;
         }
-        if (piece != INT64_MAX && piece <= 128) break;
+        if (piece != INT64_MAX && piece <= min_piece) break;
         if (units.size() > (size_t)(64 * slots)) break;  // plenty of units: splitting cannot pay
     }
     items.swap(best_items);
