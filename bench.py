@@ -94,6 +94,7 @@ def measure(name, steps, warmup, with_compulsory=True):
 
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+MFMA_F32_PEAK_TFLOPS = 157.3
 
 
 def measure_prefill(name, steps, warmup, with_cpu=False):
@@ -103,7 +104,8 @@ def measure_prefill(name, steps, warmup, with_cpu=False):
     from paper_2601_19178_amd import ckv, session, workloads as wl
 
     r = wl.prefill_config(name)
-    decode = {"prefill_cfg2": "cfg2_bf16", "prefill_cfg3": "cfg3"}[name]
+    decode = {"prefill_cfg2": "cfg2_bf16", "prefill_cfg3": "cfg3", "prefill_cfg2_f32": "cfg2_f32"}[name]
+    peak = MFMA_F32_PEAK_TFLOPS if r["dtype"] == wl.F32 else MFMA_BF16_PEAK_TFLOPS
     w = wl.config(decode)
     s = session.Session(w, prefill=r)
     for _ in range(warmup):
@@ -123,14 +125,14 @@ def measure_prefill(name, steps, warmup, with_cpu=False):
     flops = wl.prefill_flops(r)
     res = {
         "workload": name,
-        "describe": f"prefill of {decode}'s cache: T={r['T']} H={r['H']} d_e={r['d_e']} d_u={r['d_u']} P={r['P']} bf16",
+        "describe": f"prefill of {decode}'s cache: T={r['T']} H={r['H']} d_e={r['d_e']} d_u={r['d_u']} P={r['P']} {'fp32' if r['dtype'] == wl.F32 else 'bf16'}",
         "kernel": ckv.ckv_prefill_kernel_name(s.shape, s.router),
         "ms_per_step": ms_step, "kernel_ms": ms_kernel,
         "positions_per_s": r["T"] / (ms_step * 1e-3),
         "users_per_s": w["B"] / (ms_step * 1e-3),
         "flop": flops,
-        "roofline": {"bound": "mfma", "achieved": flops / (ms_kernel * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": flops / (ms_kernel * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
+        "roofline": {"bound": "mfma", "achieved": flops / (ms_kernel * 1e-3) / 1e12, "peak": peak,
+                     "unit": "TFLOP/s", "frac": flops / (ms_kernel * 1e-3) / 1e12 / peak, "traffic": None},
     }
     s.close()
     if with_cpu:
@@ -213,8 +215,8 @@ def main():
                     help="untimed steps; the GPU needs ~50 back-to-back launches to reach its steady clocks")
     ap.add_argument("--workload", default="cfg4", choices=sorted(DESCRIBE))
     ap.add_argument("--also", default="cfg2_f32,cfg2_bf16,cfg3,cfg3_ck", help="comma list of further workloads ('' for none)")
-    ap.add_argument("--prefill", default="prefill_cfg2,prefill_cfg3",
-                    help="comma list of prefill workloads reported under 'prefill' (prefill_cfg2, prefill_cfg3; '' for none)")
+    ap.add_argument("--prefill", default="prefill_cfg2,prefill_cfg3,prefill_cfg2_f32",
+                    help="comma list of prefill workloads reported under 'prefill' (prefill_cfg2, prefill_cfg3, prefill_cfg2_f32; '' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--offloaded-sweep", action="store_true",
                     help="latency of one decode batch with the compressed cache in pinned host memory vs resident vs "

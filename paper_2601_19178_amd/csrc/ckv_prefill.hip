@@ -31,7 +31,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((address_space(3))) unsigned char lds_u8;
-typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
+typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
 typedef __attribute__((address_space(3))) f32x4 lds_f32x4;
 
 constexpr int SR = 32;  // pool entries per MFMA row block
@@ -62,11 +62,31 @@ __device__ __forceinline__ uint32_t swap_halves(uint32_t x) {
 }
 __device__ __forceinline__ uint16_t f2bf(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
 
+// One 16-byte chunk of a router row (A) against the same chunk of a position's embedding (B).  bf16: eight
+// products per lane half in one v_mfma_f32_32x32x16_bf16.  fp32: four v_mfma_f32_32x32x2_f32; the
+// instruction takes k = 0 from lanes 0-31 and k = 1 from lanes 32-63, and since the lane halves hold
+// consecutive chunks, element e of both chunks is a valid (k = 0, k = 1) pair: the order in which the
+// columns of a row are summed is permuted, which no result depends on beyond rounding.
+template <typename U>
+__device__ __forceinline__ f32x16 mma_chunk(u32x4 wa, u32x4 sb, f32x16 c);
+template <>
+__device__ __forceinline__ f32x16 mma_chunk<uint16_t>(u32x4 wa, u32x4 sb, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wa), __builtin_bit_cast(bf16x8, sb), c, 0, 0, 0);
+}
+template <>
+__device__ __forceinline__ f32x16 mma_chunk<float>(u32x4 wa, u32x4 sb, f32x16 c) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(wa[e]), __uint_as_float(sb[e]), c, 0, 0, 0);
+    return c;
+}
+__device__ __forceinline__ void store_user(uint16_t* p, float x) { *p = __builtin_bit_cast(uint16_t, (__bf16)x); }
+__device__ __forceinline__ void store_user(float* p, float x) { *p = x; }
+
 // TR = pool entries per stage (one barrier per stage), NS = stages in the LDS ring.
-template <int DE, int NW, int TR, int NS>
+template <int ES, int DE, int NW, int TR, int NS>
 struct PGeo {
-    static constexpr int CH = DE / 8;            // 16-byte chunks per weight row
-    static constexpr int ROWB = DE * 2;          // bytes per weight row
+    static constexpr int ROWB = DE * ES;         // bytes per weight row (ES = bytes per stored element)
+    static constexpr int CH = ROWB / 16;         // 16-byte chunks per weight row
     static constexpr int RPI = 64 / CH;          // rows filled by one wavefront load instruction
     static constexpr int NI = TR / RPI / NW;     // load instructions per wavefront and stage
     static constexpr int WT = TR * ROWB;         // bytes of the weight rows of a stage
@@ -75,7 +95,7 @@ struct PGeo {
     static constexpr int NSUB = TR / SR;         // MFMA row blocks per stage
     // 16-byte chunk c of row p is stored at slot c ^ swz(p).  A 16-byte-per-lane LDS read is served sixteen
     // lanes at a time from 64 banks, so sixteen consecutive rows must land in sixteen different slots
-    // modulo 16: rows of 256 or 512 bytes use the low four bits of the row, rows of 128 bytes (two rows
+    // modulo 16: rows of 256 bytes or more use the low four bits of the row, rows of 128 bytes (two rows
     // per 16 slots) the next three.
     __device__ static constexpr int swz(int p) { return CH >= 16 ? (p & 15) : ((p >> 1) & 7); }
     static_assert(NI >= 1 && (TR == 32 || TR == 64), "stage geometry");
@@ -85,10 +105,10 @@ struct PGeo {
 // WPE resident wavefronts per SIMD; with at most 256 registers per wavefront the accumulators live in
 // ordinary vector registers, where the maximum search reads them without copies.  Three wavefronts per
 // SIMD measured 10 % faster than two: while one searches its accumulators another feeds the matrix core.
-template <int DE, int NW, int QG, int TR, int NS, int WPE>
+template <typename U, int DE, int NW, int QG, int TR, int NS, int WPE>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WPE))) void ckv_prefill_mfma_kernel(ckv_prefill_args a) {
-    using G = PGeo<DE, NW, TR, NS>;
-    constexpr int NKK = DE / 16;
+    using G = PGeo<sizeof(U), DE, NW, TR, NS>;
+    constexpr int NKK = G::CH / 2;  // k-steps: one 16-byte chunk per lane half each
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_u8*)smem;
 
@@ -126,7 +146,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
 
     // ---- positions of this wavefront: B operands, 16 bytes per lane and k-step, straight from S
     const int64_t pos0 = pblock * (32 * QG * NW) + (int64_t)wave * QG * 32;
-    bf16x8 sreg[QG][NKK];
+    u32x4 sreg[QG][NKK];
 #pragma unroll
     for (int g = 0; g < QG; ++g) {
         const int64_t pos = pos0 + g * 32 + qn;
@@ -135,7 +155,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
         for (int kk = 0; kk < NKK; ++kk) {
             u32x4 v = {0u, 0u, 0u, 0u};
             if (pos < a.T) v = *reinterpret_cast<const u32x4*>(src + kk * 32);
-            sreg[g][kk] = __builtin_bit_cast(bf16x8, v);
+            sreg[g][kk] = v;
         }
     }
     // these loads have to be complete before the asynchronous loads below start: a wait the
@@ -204,9 +224,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
         constexpr int KIND = decltype(kind)::value;
         issue(t + NS - 1);
         const uint32_t st = lds0 + (t % NS) * G::STAGE;
-        bf16x8 wa[NKK];  // A operand: this lane's router row, all k-steps
+        u32x4 wa[NKK];  // A operand: this lane's router row, all k-steps
 #pragma unroll
-        for (int kk = 0; kk < NKK; ++kk) wa[kk] = *(const lds_bf16x8*)(uintptr_t)(st + arow + (((2 * kk + hh) ^ ax) << 4));
+        for (int kk = 0; kk < NKK; ++kk) wa[kk] = *(const lds_u32x4*)(uintptr_t)(st + arow + (((2 * kk + hh) ^ ax) << 4));
         f32x16 acc[QG];  // accumulators start from the biases of this lane's sixteen rows
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) {
@@ -219,7 +239,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk)
 #pragma unroll
-            for (int g = 0; g < QG; ++g) acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[kk], sreg[g][kk], acc[g], 0, 0, 0);
+            for (int g = 0; g < QG; ++g) acc[g] = mma_chunk<U>(wa[kk], sreg[g][kk], acc[g]);
         if (KIND == 2) {
             // projection: row c of the block is column c0 + c of the user slice
             const int c0 = (t - nr_loc) * SR;
@@ -227,11 +247,11 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
             for (int g = 0; g < QG; ++g) {
                 const int64_t pos = pos0 + g * 32 + qn;
                 if (pos < a.T) {
-                    uint16_t* dst = (uint16_t*)a.user[side] + ((int64_t)h * a.T + pos) * d_u;
+                    U* dst = (U*)a.user[side] + ((int64_t)h * a.T + pos) * d_u;
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int c = c0 + 8 * (r >> 2) + 4 * hh + (r & 3);
-                        if (c < d_u) dst[c] = f2bf(acc[g][r]);
+                        if (c < d_u) store_user(dst + c, acc[g][r]);
                     }
                 }
             }
@@ -392,30 +412,31 @@ static SplitPlan plan_split(int64_t nb, int64_t slots, int per_wg, int max_route
     return p;
 }
 
-template <int DE, int NW, int QG, int TR, int NS, int WPE>
+template <typename U, int DE, int NW, int QG, int TR, int NS, int WPE>
 int64_t resident_slots() {
     static const int64_t slots = [] {
         int dev = 0, cus = 0, per_cu = 0;
         if (hipGetDevice(&dev) != hipSuccess) return (int64_t)0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return (int64_t)0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)ckv_prefill_mfma_kernel<DE, NW, QG, TR, NS, WPE>,
-                                                         NW * 64, PGeo<DE, NW, TR, NS>::LDS) != hipSuccess)
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)ckv_prefill_mfma_kernel<U, DE, NW, QG, TR, NS, WPE>,
+                                                         NW * 64, PGeo<sizeof(U), DE, NW, TR, NS>::LDS) != hipSuccess)
             return (int64_t)0;
         return (int64_t)cus * per_cu;
     }();
     return slots;
 }
 
-template <int DE, int NW, int QG, int TR, int NS, int WPE>
+template <typename U, int DE, int NW, int QG, int TR, int NS, int WPE>
 hipError_t launch_mfma(ckv_prefill_args a, hipStream_t s, bool plan_only, int64_t* entries) {
-    constexpr int lds = PGeo<DE, NW, TR, NS>::LDS;
-    static hipError_t prepared = hipFuncSetAttribute((const void*)ckv_prefill_mfma_kernel<DE, NW, QG, TR, NS, WPE>,
+    constexpr int lds = PGeo<sizeof(U), DE, NW, TR, NS>::LDS;
+    static_assert(lds <= 163840, "LDS of one compute unit");
+    static hipError_t prepared = hipFuncSetAttribute((const void*)ckv_prefill_mfma_kernel<U, DE, NW, QG, TR, NS, WPE>,
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (prepared != hipSuccess) return prepared;
     constexpr int per_wg = 32 * QG * NW;
     const int64_t nb = (a.T + per_wg - 1) / per_wg * 2 * a.H;
     const int max_tiles = (std::max(a.P[0], a.P[1]) + TR - 1) / TR;
-    const SplitPlan sp = plan_split(nb, resident_slots<DE, NW, QG, TR, NS, WPE>(), per_wg, max_tiles,
+    const SplitPlan sp = plan_split(nb, resident_slots<U, DE, NW, QG, TR, NS, WPE>(), per_wg, max_tiles,
                                     plan_only ? (size_t)-1 : (a.ws ? a.ws_entries : 0));
     if (plan_only) {
         *entries = sp.entries;
@@ -425,7 +446,7 @@ hipError_t launch_mfma(ckv_prefill_args a, hipStream_t s, bool plan_only, int64_
     a.split_s = sp.s;
     const int64_t blocks = sp.first + (nb - sp.first) * sp.s;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((ckv_prefill_mfma_kernel<DE, NW, QG, TR, NS, WPE>), dim3((unsigned)blocks), dim3(NW * 64), lds, s, a);
+    hipLaunchKernelGGL((ckv_prefill_mfma_kernel<U, DE, NW, QG, TR, NS, WPE>), dim3((unsigned)blocks), dim3(NW * 64), lds, s, a);
     if (sp.entries > 0)
         hipLaunchKernelGGL(ckv_prefill_finish_kernel, dim3((unsigned)((sp.entries + 255) / 256)), dim3(256), 0, s, a, per_wg, sp.entries);
     return hipGetLastError();
@@ -434,30 +455,41 @@ hipError_t launch_mfma(ckv_prefill_args a, hipStream_t s, bool plan_only, int64_
 }  // namespace
 
 bool ckv_prefill_mfma_supported(int dtype, int d_e) {
-    return dtype == CKV_BF16 && (d_e == 64 || d_e == 128 || d_e == 256);
+    return (dtype == CKV_BF16 || dtype == CKV_F32) && (d_e == 64 || d_e == 128 || d_e == 256);
 }
 
 const char* ckv_prefill_variant(int dtype, int d_e) {
-    if (ckv_prefill_mfma_supported(dtype, d_e)) return d_e == 64 ? "prefill_mfma_bf16_e64" : (d_e == 128 ? "prefill_mfma_bf16_e128" : "prefill_mfma_bf16_e256");
+    if (ckv_prefill_mfma_supported(dtype, d_e)) {
+        if (dtype == CKV_BF16) return d_e == 64 ? "prefill_mfma_bf16_e64" : (d_e == 128 ? "prefill_mfma_bf16_e128" : "prefill_mfma_bf16_e256");
+        return d_e == 64 ? "prefill_mfma_f32_e64" : (d_e == 128 ? "prefill_mfma_f32_e128" : "prefill_mfma_f32_e256");
+    }
     return dtype == CKV_F32 ? "prefill_scalar_f32" : "prefill_scalar_bf16";
 }
 
-static hipError_t dispatch_mfma(const ckv_prefill_args& a, hipStream_t s, bool plan_only, int64_t* entries) {
-    if (a.d_e == 64) return launch_mfma<64, 4, 2, 32, 4, 3>(a, s, plan_only, entries);
-    if (a.d_e == 128) return launch_mfma<128, 4, 2, 32, 4, 3>(a, s, plan_only, entries);
-    return launch_mfma<256, 4, 1, 32, 4, 3>(a, s, plan_only, entries);
+// <storage type, d_e, wavefronts, position groups per wavefront, pool entries per stage, stages, wavefronts per SIMD>.
+// fp32 rows are twice as long and the fp32 matrix instruction is sixteen times slower per product, so one
+// position group per wavefront is enough to hide everything else behind it.
+static hipError_t dispatch_mfma(const ckv_prefill_args& a, int dtype, hipStream_t s, bool plan_only, int64_t* entries) {
+    if (dtype == CKV_BF16) {
+        if (a.d_e == 64) return launch_mfma<uint16_t, 64, 4, 2, 32, 4, 3>(a, s, plan_only, entries);
+        if (a.d_e == 128) return launch_mfma<uint16_t, 128, 4, 2, 32, 4, 3>(a, s, plan_only, entries);
+        return launch_mfma<uint16_t, 256, 4, 1, 32, 4, 3>(a, s, plan_only, entries);
+    }
+    if (a.d_e == 64) return launch_mfma<float, 64, 4, 2, 32, 4, 3>(a, s, plan_only, entries);
+    if (a.d_e == 128) return launch_mfma<float, 128, 4, 1, 32, 3, 3>(a, s, plan_only, entries);
+    return launch_mfma<float, 256, 4, 1, 32, 2, 2>(a, s, plan_only, entries);
 }
 
 int64_t ckv_prefill_workspace_entries(const ckv_prefill_args& a, int dtype) {
     int64_t entries = 0;
     if (a.T == 0 || !ckv_prefill_mfma_supported(dtype, a.d_e)) return 0;
-    if (dispatch_mfma(a, nullptr, true, &entries) != hipSuccess) return 0;
+    if (dispatch_mfma(a, dtype, nullptr, true, &entries) != hipSuccess) return 0;
     return entries;
 }
 
 hipError_t ckv_launch_prefill(const ckv_prefill_args& a, int dtype, hipStream_t s) {
     if (a.T == 0) return hipSuccess;
-    if (ckv_prefill_mfma_supported(dtype, a.d_e)) return dispatch_mfma(a, s, false, nullptr);
+    if (ckv_prefill_mfma_supported(dtype, a.d_e)) return dispatch_mfma(a, dtype, s, false, nullptr);
     const int64_t total = a.T * a.H * 2;
     const int blocks = (int)((total + 255) / 256 < 65536 ? (total + 255) / 256 : 65536);
     if (dtype == CKV_F32) hipLaunchKernelGGL(ckv_prefill_scalar_kernel<float>, dim3(blocks), dim3(256), 0, s, a);

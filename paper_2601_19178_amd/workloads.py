@@ -193,6 +193,7 @@ def make_prefill(T, H, d_e, d_u, P, dtype, seed, sigma_s=1.0, sigma_b=0.1, integ
 PREFILL_CONFIGS = {
     "prefill_cfg2": dict(T=1024 * 200, H=2, d_e=128, d_u=8, P=4096, dtype=BF16, seed=1102),
     "prefill_cfg3": dict(T=512 * 1024, H=4, d_e=128, d_u=4, P=16384, dtype=BF16, seed=1103),
+    "prefill_cfg2_f32": dict(T=1024 * 200, H=2, d_e=128, d_u=8, P=4096, dtype=F32, seed=1102),
 }
 
 

@@ -119,6 +119,16 @@ def test_mfma_random_inputs(gpu, d_e, d_u, P, H):
     run_prefill(gpu, LENGTHS, r, f"prefill mfma random d_e={d_e} d_u={d_u} P={P}", "prefill_mfma_bf16", exact=False)
 
 
+@pytest.mark.parametrize("d_e,d_u,P,H,integers", [(64, 8, 1000, 2, 1), (128, 3, 77, 3, 2), (128, 8, 4096, 1, 1), (256, 32, 333, 2, 1),
+                                                   (64, 4, 2049, 2, None), (128, 8, 1000, 2, None), (256, 5, 500, 1, None)])
+def test_mfma_fp32_storage(gpu, d_e, d_u, P, H, integers):
+    """fp32 embeddings and weights on the fp32 matrix instruction: exact on integer inputs, within the fp32
+    rounding bound on random ones."""
+    r = wl.make_prefill(T=sum(LENGTHS), H=H, d_e=d_e, d_u=d_u, P=P, dtype=wl.F32, seed=140 + d_u, integers=integers)
+    run_prefill(gpu, LENGTHS, r, f"prefill mfma fp32 d_e={d_e} d_u={d_u} P={P} integers={integers}", "prefill_mfma_f32",
+                exact=integers is not None)
+
+
 @pytest.mark.parametrize("dtype,d_e,d_u,P,integers", [(wl.F32, 24, 3, 61, 2), (wl.F32, 100, 8, 300, None),
                                                        (wl.BF16, 40, 5, 129, 2), (wl.BF16, 72, 2, 50, None)])
 def test_scalar_kernel(gpu, dtype, d_e, d_u, P, integers):
