@@ -158,8 +158,10 @@ int ckv_cache_is_offloaded(const ckv_cache* c);
  * number of 8-byte entries, 0 if none is needed); a handle made by ckv_build_cache has none, and
  * ckv_prefill_into on it simply runs the uncut rounds.  Results do not depend on the cut: ties
  * still go to the lowest pool entry.  Calls on one handle must not overlap (they share it).  ckv_prefill_kernel_name names the kernel the pair
- * (shape, router) dispatches to: a matrix-core kernel for d_e of 64, 128 or 256 (bf16 storage on the
- * bf16 matrix instruction, fp32 storage on the fp32 one), a scalar kernel for any other d_e.
+ * (shape, router) dispatches to: a matrix-core kernel when a row of d_e elements is a whole number of
+ * 16-byte chunks and d_e <= 256 (bf16 storage on the bf16 matrix instruction, fp32 storage on the fp32
+ * one; built for 64, 128 and 256 columns, a narrower row runs in the next wider kernel), a scalar
+ * kernel, slower by orders of magnitude, for any other d_e.
  * Errors: CKV_ERR_NULL, _SHAPE, _LENGTH, _UNSUPPORTED (pointer not 16-byte aligned), _HIP.
  */
 typedef struct ckv_router {

@@ -7,8 +7,9 @@
 // router weights through LDS in tiles of 32 pool entries and keeps a running (maximum, index)
 // per position.
 //
-// Matrix-core kernel (bf16 storage, d_e = 64, 128 or 256): M^T = W_r S^T with
-// v_mfma_f32_32x32x16_bf16, router rows as the A operand (read from LDS), positions as the B
+// Matrix-core kernel (d_e up to 256 in whole 16-byte chunks; built for 64, 128 and 256 columns, bf16 storage
+// on v_mfma_f32_32x32x16_bf16, fp32 storage on v_mfma_f32_32x32x2_f32): M^T = W_r S^T,
+// router rows as the A operand (read from LDS), positions as the B
 // operand (registers), so that a lane owns one position and sixteen pool entries of the tile;
 // the bias enters as the initial value of the accumulator (fp32, exact).  The maximum over the
 // lane's sixteen entries costs eight v_max3; only when it beats the lane's running maximum
@@ -18,7 +19,8 @@
 // The projection is more tiles of the same kind whose 32 "pool entries" are rows of W_k (or W_v):
 // one tile for the usual small d_u, d_a / 32 tiles for a side that is not shared.
 //
-// Scalar kernel: any d_e and either storage type, one thread per (position, head, side).
+// Scalar kernel: any other d_e (wider than 256, or rows that are not whole 16-byte chunks), either storage
+// type, one thread per (position, head, side).
 #include <algorithm>
 #include <type_traits>
 
@@ -131,9 +133,14 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
     const int h = cls >> 1, side = cls & 1;
     const int P = a.P[side], d_u = a.d_u[side];  // this side's pool entries (0: not shared) and projected columns
 
-    const unsigned char* __restrict__ wr = (const unsigned char*)a.w_r[side] + (int64_t)h * P * G::ROWB;
+    // d_e may be smaller than the width DE the kernel is built for: rows in memory are `rs` bytes apart and
+    // hold `nch` 16-byte chunks; the missing columns are zeros of the embedding (the weight chunk loaded
+    // for them is a valid one of the same row, multiplied by zero)
+    const int rs = a.d_e * (int)sizeof(U);
+    const int nch = rs >> 4;
+    const unsigned char* __restrict__ wr = (const unsigned char*)a.w_r[side] + (int64_t)h * P * rs;
     const float* __restrict__ br = a.b_r[side] + (int64_t)h * P;
-    const unsigned char* __restrict__ wu = (const unsigned char*)a.w_u[side] + (int64_t)h * d_u * G::ROWB;
+    const unsigned char* __restrict__ wu = (const unsigned char*)a.w_u[side] + (int64_t)h * d_u * rs;
     const float* __restrict__ bu = a.b_u[side] + (int64_t)h * d_u;
     const int nfull = P / TR;                      // stages made of TR valid router rows
     const int nrt = (P + TR - 1) / TR;             // router stages
@@ -150,11 +157,11 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
 #pragma unroll
     for (int g = 0; g < QG; ++g) {
         const int64_t pos = pos0 + g * 32 + qn;
-        const unsigned char* src = (const unsigned char*)a.S + pos * G::ROWB + hh * 16;
+        const unsigned char* src = (const unsigned char*)a.S + pos * rs + hh * 16;
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk) {
             u32x4 v = {0u, 0u, 0u, 0u};
-            if (pos < a.T) v = *reinterpret_cast<const u32x4*>(src + kk * 32);
+            if (pos < a.T && 2 * kk + hh < nch) v = *reinterpret_cast<const u32x4*>(src + kk * 32);
             sreg[g][kk] = v;
         }
     }
@@ -174,8 +181,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
 #pragma unroll
     for (int i = 0; i < G::NI; ++i) {
         lrow[i] = (i * NW + wave) * G::RPI + lane / G::CH;
-        lchunk[i] = (uint32_t)(((lane % G::CH) ^ G::swz(lrow[i])) * 16);
-        loff[i] = (uint32_t)lrow[i] * G::ROWB + lchunk[i];
+        lchunk[i] = (uint32_t)(min((lane % G::CH) ^ G::swz(lrow[i]), nch - 1) * 16);
+        loff[i] = (uint32_t)lrow[i] * rs + lchunk[i];
     }
     const uint32_t boff = (uint32_t)(lane & (TR - 1)) * 4;
     auto issue = [&](int i) {  // stage i of this workgroup (past the last one: a repeat nothing reads)
@@ -183,7 +190,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
         const int ic = min(i, n_loc - 1);
         int tile = ic < nr_loc ? t_lo + ic : nrt + (ic - nr_loc);
         if (i < nr_loc && tile < nfull) {
-            const unsigned char* base = wr + (int64_t)tile * (TR * G::ROWB);
+            const unsigned char* base = wr + (int64_t)tile * (TR * rs);
 #pragma unroll
             for (int i = 0; i < G::NI; ++i) dma16_uniform(base, loff[i], st + (i * NW + wave) * G::RPI * G::ROWB);
             dma4_uniform(br + (int64_t)tile * TR, boff, st + G::WT + wave * 256);
@@ -199,7 +206,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
 #pragma unroll
         for (int i = 0; i < G::NI; ++i) {
             const int row = min(row0 + lrow[i], rmax);
-            dma16(wbase + (int64_t)row * G::ROWB + lchunk[i], st + (i * NW + wave) * G::RPI * G::ROWB);
+            dma16(wbase + (int64_t)row * rs + lchunk[i], st + (i * NW + wave) * G::RPI * G::ROWB);
         }
         dma4(bbase + min(row0 + (lane & (TR - 1)), rmax), st + G::WT + wave * 256);
     };
@@ -454,14 +461,19 @@ hipError_t launch_mfma(ckv_prefill_args a, hipStream_t s, bool plan_only, int64_
 
 }  // namespace
 
+// Rows of whole 16-byte chunks, up to 256 columns; the kernel is built for 64, 128 and 256 columns and a
+// narrower row runs in the next wider one.
 bool ckv_prefill_mfma_supported(int dtype, int d_e) {
-    return (dtype == CKV_BF16 || dtype == CKV_F32) && (d_e == 64 || d_e == 128 || d_e == 256);
+    const int es = dtype == CKV_F32 ? 4 : 2;
+    return (dtype == CKV_BF16 || dtype == CKV_F32) && d_e >= 1 && d_e <= 256 && (d_e * es) % 16 == 0;
 }
+static int prefill_width(int d_e) { return d_e <= 64 ? 64 : (d_e <= 128 ? 128 : 256); }
 
 const char* ckv_prefill_variant(int dtype, int d_e) {
     if (ckv_prefill_mfma_supported(dtype, d_e)) {
-        if (dtype == CKV_BF16) return d_e == 64 ? "prefill_mfma_bf16_e64" : (d_e == 128 ? "prefill_mfma_bf16_e128" : "prefill_mfma_bf16_e256");
-        return d_e == 64 ? "prefill_mfma_f32_e64" : (d_e == 128 ? "prefill_mfma_f32_e128" : "prefill_mfma_f32_e256");
+        const int w = prefill_width(d_e);
+        if (dtype == CKV_BF16) return w == 64 ? "prefill_mfma_bf16_e64" : (w == 128 ? "prefill_mfma_bf16_e128" : "prefill_mfma_bf16_e256");
+        return w == 64 ? "prefill_mfma_f32_e64" : (w == 128 ? "prefill_mfma_f32_e128" : "prefill_mfma_f32_e256");
     }
     return dtype == CKV_F32 ? "prefill_scalar_f32" : "prefill_scalar_bf16";
 }
@@ -470,13 +482,14 @@ const char* ckv_prefill_variant(int dtype, int d_e) {
 // fp32 rows are twice as long and the fp32 matrix instruction is sixteen times slower per product, so one
 // position group per wavefront is enough to hide everything else behind it.
 static hipError_t dispatch_mfma(const ckv_prefill_args& a, int dtype, hipStream_t s, bool plan_only, int64_t* entries) {
+    const int w = prefill_width(a.d_e);
     if (dtype == CKV_BF16) {
-        if (a.d_e == 64) return launch_mfma<uint16_t, 64, 4, 2, 32, 4, 3>(a, s, plan_only, entries);
-        if (a.d_e == 128) return launch_mfma<uint16_t, 128, 4, 2, 32, 4, 3>(a, s, plan_only, entries);
+        if (w == 64) return launch_mfma<uint16_t, 64, 4, 2, 32, 4, 3>(a, s, plan_only, entries);
+        if (w == 128) return launch_mfma<uint16_t, 128, 4, 2, 32, 4, 3>(a, s, plan_only, entries);
         return launch_mfma<uint16_t, 256, 4, 1, 32, 4, 3>(a, s, plan_only, entries);
     }
-    if (a.d_e == 64) return launch_mfma<float, 64, 4, 2, 32, 4, 3>(a, s, plan_only, entries);
-    if (a.d_e == 128) return launch_mfma<float, 128, 4, 1, 32, 3, 3>(a, s, plan_only, entries);
+    if (w == 64) return launch_mfma<float, 64, 4, 2, 32, 4, 3>(a, s, plan_only, entries);
+    if (w == 128) return launch_mfma<float, 128, 4, 1, 32, 3, 3>(a, s, plan_only, entries);
     return launch_mfma<float, 256, 4, 1, 32, 2, 2>(a, s, plan_only, entries);
 }
 

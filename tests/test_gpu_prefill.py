@@ -129,12 +129,29 @@ def test_mfma_fp32_storage(gpu, d_e, d_u, P, H, integers):
                 exact=integers is not None)
 
 
-@pytest.mark.parametrize("dtype,d_e,d_u,P,integers", [(wl.F32, 24, 3, 61, 2), (wl.F32, 100, 8, 300, None),
-                                                       (wl.BF16, 40, 5, 129, 2), (wl.BF16, 72, 2, 50, None)])
+def expected_kernel(dtype, d_e):
+    """Matrix-core kernel for rows of whole 16-byte chunks up to 256 columns, scalar kernel otherwise."""
+    es = 4 if dtype == wl.F32 else 2
+    if d_e <= 256 and (d_e * es) % 16 == 0:
+        return ("prefill_mfma_f32" if dtype == wl.F32 else "prefill_mfma_bf16") + f"_e{64 if d_e <= 64 else (128 if d_e <= 128 else 256)}"
+    return "prefill_scalar"
+
+
+@pytest.mark.parametrize("dtype,d_e,d_u,P,integers", [(wl.F32, 25, 3, 61, 2), (wl.F32, 300, 8, 300, None),
+                                                       (wl.BF16, 36, 5, 129, 2), (wl.BF16, 260, 2, 50, None)])
 def test_scalar_kernel(gpu, dtype, d_e, d_u, P, integers):
     lengths = (5, 0, 120, 1, 64)
     r = wl.make_prefill(T=sum(lengths), H=2, d_e=d_e, d_u=d_u, P=P, dtype=dtype, seed=60 + d_e, integers=integers)
     run_prefill(gpu, lengths, r, f"prefill scalar dtype={dtype} d_e={d_e}", "prefill_scalar", exact=integers is not None)
+
+
+@pytest.mark.parametrize("dtype,d_e,d_u,P,integers", [(wl.F32, 24, 3, 61, 2), (wl.F32, 100, 8, 300, None), (wl.F32, 4, 2, 40, 2),
+                                                       (wl.BF16, 40, 5, 129, 2), (wl.BF16, 72, 2, 50, None), (wl.BF16, 8, 1, 33, 2),
+                                                       (wl.BF16, 200, 8, 1000, None), (wl.F32, 192, 4, 700, 1)])
+def test_narrow_rows_run_in_the_next_wider_kernel(gpu, dtype, d_e, d_u, P, integers):
+    """An embedding narrower than the width a kernel is built for: its missing columns count as zeros."""
+    r = wl.make_prefill(T=sum(LENGTHS), H=2, d_e=d_e, d_u=d_u, P=P, dtype=dtype, seed=160 + d_e, integers=integers)
+    run_prefill(gpu, LENGTHS, r, f"prefill narrow rows dtype={dtype} d_e={d_e}", expected_kernel(dtype, d_e), exact=integers is not None)
 
 
 def test_no_pool_and_no_user_columns(gpu):
@@ -153,6 +170,8 @@ def test_prefill_with_one_side_shared(gpu, share):
     r = wl.make_prefill(T=sum(LENGTHS), H=2, d_e=64, d_u=3, P=333, dtype=wl.BF16, seed=81, share=share, d_a=40)
     run_prefill(gpu, LENGTHS, r, f"prefill mfma random share={share}", "prefill_mfma_bf16", exact=False)
     r = wl.make_prefill(T=200, H=2, d_e=24, d_u=3, P=61, dtype=wl.F32, seed=82, integers=2, share=share, d_a=16)
+    run_prefill(gpu, (5, 0, 131, 64), r, f"prefill fp32 narrow exact share={share}", "prefill_mfma_f32_e64", exact=True)
+    r = wl.make_prefill(T=200, H=2, d_e=25, d_u=3, P=61, dtype=wl.F32, seed=83, integers=2, share=share, d_a=16)
     run_prefill(gpu, (5, 0, 131, 64), r, f"prefill scalar exact share={share}", "prefill_scalar", exact=True)
 
 
@@ -294,4 +313,4 @@ def test_seeded_random_prefill_shapes(gpu, block):
         r = wl.make_prefill(T=int(lengths.sum()), H=H, d_e=d_e, d_u=d_u, P=P, dtype=dtype, seed=600 + 10 * block + case,
                             integers=1 if exact else None, share=share, d_a=d_a if share != wl.SHARE_KV else None)
         run_prefill(gpu, lengths, r, f"random prefill {block}.{case}: d_e={d_e} P={P} d_u={d_u} H={H} share={share} lengths={lengths.tolist()}",
-                    "prefill_mfma_bf16" if mfma else "prefill_scalar", exact=exact, d_g=d_a - d_u)
+                    expected_kernel(dtype, d_e), exact=exact, d_g=d_a - d_u)
