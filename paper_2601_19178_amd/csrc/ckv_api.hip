@@ -333,7 +333,7 @@ int64_t simulate_dispatch(const std::vector<ckv_item>& items, int64_t slots, int
 int resident_workgroups(const ckv_cache* c) {
     const ckv_shape& s = c->shape;
     const int d_a = s.d_g + s.d_u;
-    if (c->family == CKV_K_MFMA) return std::max(1, ckv_mfma_occupancy(d_a, c->nw, c->tp, s.mode));
+    if (c->family == CKV_K_MFMA) return std::max(1, ckv_mfma_occupancy(d_a <= 64 ? 64 : 128, c->nw, c->tp, s.mode));
     if (c->family == CKV_K_DMA) return std::max(1, ckv_dma_occupancy(d_a, c->nw, c->qg, s.mode));
     return 8;
 }
@@ -587,15 +587,16 @@ void choose_variant(ckv_cache* c) {
     const int d_a = s.d_g + s.d_u;
     c->family = CKV_K_STREAM;
     // the matrix-core kernels take the running maximum before scaling, which needs scale > 0
-    if (s.dtype == CKV_BF16 && (d_a == 64 || d_a == 128) && s.Nq >= 8 && (s.d_g == 0 || s.pool_ld % 8 == 0) &&
+    if (s.dtype == CKV_BF16 && d_a <= 128 && s.Nq >= 8 && (s.d_g == 0 || s.pool_ld % 8 == 0) &&
         (s.mode == CKV_SILU_OVER_N || s.scale > 0.f)) {
+        const int dak = d_a <= 64 ? 64 : 128;  // row width the register-staged kernel is built for
         const char* impl = getenv("CKV_MFMA_IMPL");  // tuning knob: "staged" forces the register-staged kernel
         {
             // direct-to-LDS kernel: 32 queries per wavefront, up to 4 wavefronts per workgroup (two
             // wavefronts per SIMD overlap better than one wavefront with two query groups)
             int nw = s.Nq <= 32 ? 1 : (s.Nq <= 64 ? 2 : 4), qg = 1;
             if (const char* shp = getenv("CKV_DMA_SHAPE")) sscanf(shp, "%d,%d", &nw, &qg);  // tuning knob "nw,qg"
-            const int nui = s.d_g > 0 && ckv_dma_supported(d_a, nw, qg) ? ckv_dma_nui(d_a, nw, s.d_u) : -1;
+            const int nui = s.d_g > 0 && d_a == dak && ckv_dma_supported(d_a, nw, qg) ? ckv_dma_nui(d_a, nw, s.d_u) : -1;
             if (nui >= 0 && !(impl && strcmp(impl, "staged") == 0)) {
                 c->family = CKV_K_DMA;
                 c->nw = nw;
@@ -609,13 +610,13 @@ void choose_variant(ckv_cache* c) {
             }
         }
         const int nw = s.Nq <= 32 ? 1 : (s.Nq <= 64 ? 2 : 4);
-        const int tp = (d_a == 128 && nw == 1) ? 32 : 64;
-        if (ckv_mfma_supported(d_a, nw, tp)) {
+        const int tp = (dak == 128 && nw == 1) ? 32 : 64;
+        if (ckv_mfma_supported(dak, nw, tp)) {
             c->family = CKV_K_MFMA;
             c->nw = nw;
             c->tp = tp;
             c->QB = 32 * nw;
-            snprintf(c->variant, sizeof c->variant, "mfma_bf16_d%d_w%d_t%d_%s", d_a, nw, tp,
+            snprintf(c->variant, sizeof c->variant, "mfma_bf16_d%d_w%d_t%d_%s", dak, nw, tp,
                      s.mode == CKV_SOFTMAX ? "softmax" : "silu");
             return;
         }

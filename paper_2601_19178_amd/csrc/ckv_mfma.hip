@@ -1,5 +1,6 @@
 // Matrix-core gather-concat-attend kernel for many candidate queries per user (bf16 storage,
-// fp32 accumulation, d_a = 64 or 128).
+// fp32 accumulation, built for rows of DA = 64 or 128 columns; a narrower d_a runs in the next
+// wider kernel with its missing columns as zeros of K, V and q).
 //
 // A workgroup of NW wavefronts serves one work item: a run of positions of one user and head
 // and a block of 32*NW queries; wavefront w owns queries 32w .. 32w+31 and every wavefront
@@ -63,8 +64,8 @@ __device__ __forceinline__ uint4 gather_chunk(const uint16_t* __restrict__ pool_
             uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                if (e >= first && c0 + e < d_g + d_u) {
-                    const uint32_t x = u[e - first];
+                if (e >= first) {  // a user column, or past the end of a row narrower than the kernel's: zero
+                    const uint32_t x = c0 + e < d_g + d_u ? u[e - first] : 0u;
                     w[e >> 1] = (e & 1) ? ((w[e >> 1] & 0x0000FFFFu) | (x << 16)) : ((w[e >> 1] & 0xFFFF0000u) | x);
                 }
             }
@@ -95,6 +96,7 @@ __global__ __launch_bounds__(NW * 64, (DA == 128 ? 2 : 2)) void ckv_mfma_kernel(
     const int qn = lane & 31, hh = lane >> 5;
     // pool and user columns of each side (a side that is not shared: all user, no pool)
     const int d_gk = a.d_gk, d_uk = a.d_uk, d_gv = a.d_gv, d_uv = a.d_uv;
+    const int d_a = a.d_a;  // <= DA: columns d_a .. DA-1 of the kernel's rows are zeros
     const int n = it.n;
 
     const int64_t hT = (int64_t)it.h * a.T + it.t0;
@@ -108,7 +110,7 @@ __global__ __launch_bounds__(NW * 64, (DA == 128 ? 2 : 2)) void ckv_mfma_kernel(
     // ---- queries of this lane, kernel column order, as B operands
     const int qj = it.q0 + wave * 32 + qn;
     const bool qok = qj < a.Nq;
-    const int64_t qo = (((int64_t)it.b * a.H + it.h) * a.Nq + (qok ? qj : 0)) * DA;
+    const int64_t qo = (((int64_t)it.b * a.H + it.h) * a.Nq + (qok ? qj : 0)) * d_a;
     bf16x8 qreg[NKK];
     {
         const uint16_t* qp = (const uint16_t*)a.q + qo;
@@ -118,7 +120,7 @@ __global__ __launch_bounds__(NW * 64, (DA == 128 ? 2 : 2)) void ckv_mfma_kernel(
             for (int e = 0; e < 8; ++e) {
                 const int ci = 16 * kk + 8 * hh + e;
                 const int pc = ci < d_gk ? ci + d_uk : ci - d_gk;  // kernel column of K -> column of q
-                const uint16_t x = qok ? qp[pc] : (uint16_t)0;
+                const uint16_t x = qok && ci < d_a ? qp[pc] : (uint16_t)0;
                 qreg[kk][e] = __builtin_bit_cast(__bf16, x);
             }
         }
@@ -270,11 +272,11 @@ __global__ __launch_bounds__(NW * 64, (DA == 128 ? 2 : 2)) void ckv_mfma_kernel(
                 for (int r = 0; r < 16; ++r) {
                     const int ci = 32 * dt + 8 * (r >> 2) + 4 * hh + (r & 3);
                     const int pc = ci < d_gv ? ci + d_uv : ci - d_gv;  // kernel column of V -> column of out
-                    op[pc] = f2bf(oacc[dt][r] * inv);
+                    if (ci < d_a) op[pc] = f2bf(oacc[dt][r] * inv);
                 }
         }
     } else {
-        float* ws = a.partial + (int64_t)it.part * a.QB * (DA + 2);
+        float* ws = a.partial + (int64_t)it.part * a.QB * (d_a + 2);
         const int j = wave * 32 + qn;
 #pragma unroll
         for (int dt = 0; dt < NDT; ++dt)
@@ -282,11 +284,11 @@ __global__ __launch_bounds__(NW * 64, (DA == 128 ? 2 : 2)) void ckv_mfma_kernel(
             for (int r = 0; r < 16; ++r) {
                 const int ci = 32 * dt + 8 * (r >> 2) + 4 * hh + (r & 3);
                 const int pc = ci < d_gv ? ci + d_uv : ci - d_gv;
-                ws[(int64_t)j * DA + pc] = oacc[dt][r];
+                if (ci < d_a) ws[(int64_t)j * d_a + pc] = oacc[dt][r];
             }
         if (hh == 0) {
-            ws[(int64_t)a.QB * DA + j] = m_ref * kLn2;  // natural-log units, as the merge expects
-            ws[(int64_t)a.QB * DA + a.QB + j] = l_tot;
+            ws[(int64_t)a.QB * d_a + j] = m_ref * kLn2;  // natural-log units, as the merge expects
+            ws[(int64_t)a.QB * d_a + a.QB + j] = l_tot;
         }
     }
 }
@@ -347,7 +349,7 @@ int ckv_mfma_occupancy(int d_a, int nw, int tp, int mode) {
 
 hipError_t ckv_launch_mfma(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
     if (c->n_items == 0) return hipSuccess;
-    const int d_a = a.d_a, nw = c->nw, tp = c->tp;
+    const int d_a = a.d_a <= 64 ? 64 : 128, nw = c->nw, tp = c->tp;  // the kernel's row width
 #define X(DA, NW, TP)                                                                         \
     if (d_a == DA && nw == NW && tp == TP)                                                    \
         return c->shape.mode == CKV_SOFTMAX ? launch<DA, NW, TP, CKV_SOFTMAX>(c, a, s)         \

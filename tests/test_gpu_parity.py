@@ -511,3 +511,21 @@ def test_seeded_random_shapes(gpu, block):
         w = make(lengths, dtype, mode, d_a=d_a, d_u=d_u, H=H, P=P, Nq=Nq, seed=2000 + 100 * block + case,
                  idx=("zipf", 1.1) if rng.random() < 0.3 else "uniform", share=share, **kw)
         run_and_check(gpu, w, f"random shape {block}.{case}: d_a={d_a} d_u={d_u} ld={pool_ld} share={share} lengths={lengths.tolist()}")
+
+
+@pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
+@pytest.mark.parametrize("d_a,d_u,pool_ld,Nq", [(96, 8, 88, 64), (32, 4, 32, 16), (40, 5, 40, 20), (120, 16, 104, 130),
+                                                 (8, 2, 8, 9), (72, 0, 72, 33), (100, 3, 104, 64), (56, 56, 0, 40)])
+def test_narrow_heads_run_in_the_next_wider_matrix_core_kernel(gpu, mode, d_a, d_u, pool_ld, Nq):
+    """bf16 heads narrower than 64 or 128 columns, many queries: the register-staged kernel with zero columns."""
+    w = make(MFMA_LENGTHS, wl.BF16, mode, d_a=d_a, d_u=d_u, H=2, P=700, Nq=Nq, **({"pool_ld": pool_ld} if pool_ld else {}))
+    run_and_check(gpu, w, f"narrow head d_a={d_a} d_u={d_u} ld={pool_ld} Nq={Nq} mode={mode}",
+                  expect_variant=f"mfma_bf16_d{64 if d_a <= 64 else 128}")
+
+
+def test_narrow_head_split_history_and_one_side_shared(gpu):
+    w = make((5000, 70, 2300), wl.BF16, wl.SOFTMAX, d_a=96, d_u=8, H=2, P=5000, Nq=64, pool_ld=88)
+    run_and_check(gpu, w, "narrow head, split history", expect_variant="mfma_bf16_d128")
+    for share in (wl.SHARE_K, wl.SHARE_V):
+        w = make(MFMA_LENGTHS, wl.BF16, wl.SILU_OVER_N, d_a=48, d_u=4, H=2, P=300, Nq=32, share=share)
+        run_and_check(gpu, w, f"narrow head, share={share}", expect_variant="mfma_bf16_d64")
