@@ -335,6 +335,7 @@ int resident_workgroups(const ckv_cache* c) {
     const int d_a = s.d_g + s.d_u;
     if (c->family == CKV_K_MFMA) return std::max(1, ckv_mfma_occupancy(d_a <= 64 ? 64 : 128, c->nw, c->tp, s.mode));
     if (c->family == CKV_K_DMA) return std::max(1, ckv_dma_occupancy(d_a, c->nw, c->qg, s.mode));
+    if (c->family == CKV_K_MFMA32) return std::max(1, ckv_mfma32_occupancy(d_a <= 64 ? 64 : 128, s.mode));
     return 8;
 }
 
@@ -620,6 +621,17 @@ void choose_variant(ckv_cache* c) {
                      s.mode == CKV_SOFTMAX ? "softmax" : "silu");
             return;
         }
+    }
+    // fp32 storage, many queries: the same organisation on the fp32 matrix instruction
+    if (s.dtype == CKV_F32 && d_a <= 128 && s.Nq >= 8 && (s.d_g == 0 || s.pool_ld % 4 == 0) &&
+        (s.mode == CKV_SILU_OVER_N || s.scale > 0.f)) {
+        const int dak = d_a <= 64 ? 64 : 128;
+        c->family = CKV_K_MFMA32;
+        c->nw = 4;
+        c->tp = ckv_mfma32_tile(dak);
+        c->QB = 128;
+        snprintf(c->variant, sizeof c->variant, "mfma_f32_d%d_w4_t%d_%s", dak, c->tp, s.mode == CKV_SOFTMAX ? "softmax" : "silu");
+        return;
     }
     pick_stream_vec(s, &c->vec, &c->grp);
     int ncb = (d_a + c->grp * c->vec - 1) / (c->grp * c->vec);
@@ -1116,7 +1128,10 @@ int ckv_attend(const ckv_cache* c, const void* pool_k, const void* pool_v, const
         e = hipEventRecord(c->ev[2 * slot], st);
         if (e != hipSuccess) return fail(CKV_ERR_HIP, "ckv_attend: hipEventRecord: %s", hipGetErrorString(e));
     }
-    e = c->family == CKV_K_DMA ? ckv_launch_dma(c, a, st) : (c->family == CKV_K_MFMA ? ckv_launch_mfma(c, a, st) : ckv_launch_stream(c, a, st));
+    e = c->family == CKV_K_DMA      ? ckv_launch_dma(c, a, st)
+        : c->family == CKV_K_MFMA   ? ckv_launch_mfma(c, a, st)
+        : c->family == CKV_K_MFMA32 ? ckv_launch_mfma32(c, a, st)
+                                    : ckv_launch_stream(c, a, st);
     if (e != hipSuccess) return fail(CKV_ERR_HIP, "ckv_attend: kernel launch (%s): %s", c->variant, hipGetErrorString(e));
     if (c->timing) {
         e = hipEventRecord(c->ev[2 * slot + 1], st);

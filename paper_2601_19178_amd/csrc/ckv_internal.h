@@ -74,7 +74,7 @@ struct ckv_prefill_args {
     int32_t split_s;
 };
 
-enum ckv_kernel_family { CKV_K_STREAM = 0, CKV_K_MFMA = 1, CKV_K_DMA = 2 };
+enum ckv_kernel_family { CKV_K_STREAM = 0, CKV_K_MFMA = 1, CKV_K_DMA = 2, CKV_K_MFMA32 = 3 };
 
 struct ckv_cache {
     ckv_shape shape;
@@ -122,6 +122,11 @@ hipError_t ckv_launch_dma(const ckv_cache* c, const ckv_args& a, hipStream_t s);
 int ckv_dma_nui(int d_a, int nw, int d_u);  // -1: shape not served
 int ckv_dma_occupancy(int d_a, int nw, int qg, int mode);
 bool ckv_dma_supported(int d_a, int nw, int qg);
+
+// fp32-storage variant of the register-staged mfma kernel (four wavefronts, 128 queries per block).
+hipError_t ckv_launch_mfma32(const ckv_cache* c, const ckv_args& a, hipStream_t s);
+int ckv_mfma32_occupancy(int dak, int mode);  // dak: row width the kernel is built for (64 or 128)
+int ckv_mfma32_tile(int dak);                 // positions per tile
 
 // Prefill (projection + router argmax into the packed cache layout).
 hipError_t ckv_launch_prefill(const ckv_prefill_args& a, int dtype, hipStream_t s);

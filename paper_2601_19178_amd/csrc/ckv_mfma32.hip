@@ -1,0 +1,313 @@
+// Matrix-core gather-concat-attend kernel for many candidate queries per user, fp32 storage
+// (fp32 products and accumulation on v_mfma_f32_32x32x2_f32; built for rows of DA = 64 or 128
+// columns, a narrower d_a runs in the next wider kernel with zero columns).
+//
+// Same organisation as the bf16 register-staged kernel: a workgroup of four wavefronts serves one
+// work item (a run of positions of one user and head, a block of 128 queries; wavefront w owns
+// queries 32w .. 32w+31, a wavefront whose queries lie past Nq only helps with the gathers).  Per
+// tile of TP positions the workgroup gathers the final K and V rows into LDS, 16 bytes (four
+// columns) per lane, in kernel column order [pool | user]; then per 32 positions each wavefront
+// computes
+//   S^T (32 pos x 32 q)  = K (A operand from LDS) * Q^T (B operand, registers)
+//   O^T (d_a x 32 q)    += V^T (A operand, one LDS word per lane) * P^T (B operand = the weights
+//                          as they sit in the accumulator registers of S^T)
+// The instruction multiplies a 32 x 2 by a 2 x 32 block: k = 0 comes from lanes 0-31, k = 1 from
+// lanes 32-63.  For S^T the lane halves hold consecutive 16-byte chunks of a row, so element e of
+// both chunks forms a valid pair (the columns of a row are summed in a permuted order); for O^T
+// register r of the two halves holds the weights of positions 8*(r/4) + r%4 and that + 4, and the
+// V words are read from exactly those two rows.
+#include "ckv_internal.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kLazy = 8.f;  // rescale only when the maximum grows by more than 2^8
+
+__device__ __forceinline__ float other_half(float x) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return threadIdx.x & 32 ? __uint_as_float(r[0]) : __uint_as_float(r[1]);
+}
+
+// One 16-byte chunk of a final row in kernel order [pool | user]: columns 4c .. 4c+3; columns past
+// d_g + d_u (a row narrower than the kernel's) are zeros.
+__device__ __forceinline__ u32x4 gather_chunk(const float* __restrict__ pool_h, int row, int64_t pool_ld,
+                                              const float* __restrict__ user_pos, int c, int d_g, int d_u) {
+    u32x4 v = {0u, 0u, 0u, 0u};
+    const int c0 = 4 * c;
+    if (c0 < d_g) v = *reinterpret_cast<const u32x4*>(pool_h + (int64_t)row * pool_ld + c0);
+    if (c0 + 4 > d_g) {
+        const int first = d_g > c0 ? d_g - c0 : 0;  // first element of the chunk that is not a pool column
+        const float* u = user_pos + (c0 + first - d_g);
+        if (first == 0 && c0 + 4 <= d_g + d_u && ((d_g | d_u) & 3) == 0) {
+            v = *reinterpret_cast<const u32x4*>(u);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (e >= first) v[e] = c0 + e < d_g + d_u ? __float_as_uint(u[e - first]) : 0u;
+        }
+    }
+    return v;
+}
+
+template <int DA, int TP, int MODE>
+__global__ __launch_bounds__(256, 2) void ckv_mfma32_kernel(ckv_args a) {
+    constexpr int NT = 256;            // threads: four wavefronts
+    constexpr int CH = DA / 4;         // 16-byte chunks per row
+    constexpr int RPP = NT / CH;       // rows gathered per pass
+    constexpr int NL = TP / RPP;       // passes per tile (chunks per lane per tile, K and V each)
+    constexpr int KS = DA * 4 + 16;    // LDS row stride of K: sixteen rows of one chunk column fall in sixteen bank groups
+    constexpr int VS = DA * 4 + 32;    // LDS row stride of V: rows p and p + 4 are 32 banks apart (one word per lane, two rows per read)
+    constexpr int BUF = TP * (KS + VS);
+    constexpr int NKK = DA / 8;        // k-steps of S^T: one chunk per lane half each, four instructions
+    constexpr int NDT = DA / 32;       // 32-row tiles of O^T
+    static_assert(TP % RPP == 0 && TP % 32 == 0, "tile shape");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const ckv_item it = a.items[blockIdx.x];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int qn = lane & 31, hh = lane >> 5;
+    const int d_gk = a.d_gk, d_uk = a.d_uk, d_gv = a.d_gv, d_uv = a.d_uv;
+    const int d_a = a.d_a;  // <= DA
+    const int n = it.n;
+
+    const int64_t hT = (int64_t)it.h * a.T + it.t0;
+    const int32_t* __restrict__ ik = a.idx_k + hT;
+    const int32_t* __restrict__ iv = a.idx_v + hT;
+    const float* __restrict__ uk = (const float*)a.user_k + hT * d_uk;
+    const float* __restrict__ uv = (const float*)a.user_v + hT * d_uv;
+    const float* __restrict__ pk = (const float*)a.pool_k + (int64_t)it.h * a.P * a.pool_ld;
+    const float* __restrict__ pv = (const float*)a.pool_v + (int64_t)it.h * a.P * a.pool_ld;
+
+    // ---- queries of this lane, kernel column order, as B operands
+    const bool wave_has_q = it.q0 + wave * 32 < a.Nq;  // wavefront-uniform
+    const int qj = it.q0 + wave * 32 + qn;
+    const bool qok = qj < a.Nq;
+    const int64_t qo = (((int64_t)it.b * a.H + it.h) * a.Nq + (qok ? qj : 0)) * d_a;
+    float qreg[NKK][4];
+    {
+        const float* qp = (const float*)a.q + qo;
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int ci = 4 * (2 * kk + hh) + e;
+                const int pc = ci < d_gk ? ci + d_uk : ci - d_gk;  // kernel column of K -> column of q
+                qreg[kk][e] = qok && ci < d_a ? qp[pc] : 0.f;
+            }
+    }
+
+    f32x16 oacc[NDT];
+#pragma unroll
+    for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
+    float m_ref = -INFINITY, lsum = 0.f;
+    const float sc = MODE == CKV_SOFTMAX ? a.scale * kLog2e : a.scale;
+
+    // ---- gather bookkeeping: this lane owns chunk c of rows p0 + i*RPP
+    const int c = tid % CH, p0 = tid / CH;
+    int rk[NL], rv[NL];
+    u32x4 kreg[NL], vreg[NL];
+    const int ntiles = (n + TP - 1) / TP;
+
+    auto load_idx = [&](int tile) {
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const int pos = min(tile * TP + p0 + i * RPP, n - 1);
+            rk[i] = d_gk > 0 ? ik[pos] : 0;
+            rv[i] = d_gv > 0 ? iv[pos] : 0;
+        }
+    };
+    auto load_rows = [&](int tile) {
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const int pos = min(tile * TP + p0 + i * RPP, n - 1);
+            kreg[i] = gather_chunk(pk, rk[i], a.pool_ld, uk + (int64_t)pos * d_uk, c, d_gk, d_uk);
+            vreg[i] = gather_chunk(pv, rv[i], a.pool_ld, uv + (int64_t)pos * d_uv, c, d_gv, d_uv);
+        }
+    };
+    auto store_rows = [&](int buf) {
+        unsigned char* kb = smem + buf * BUF;
+        unsigned char* vb = kb + TP * KS;
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const int p = p0 + i * RPP;
+            *reinterpret_cast<u32x4*>(kb + p * KS + c * 16) = kreg[i];
+            *reinterpret_cast<u32x4*>(vb + p * VS + c * 16) = vreg[i];
+        }
+    };
+
+    if (ntiles > 0) {
+        load_idx(0);
+        load_rows(0);
+        if (ntiles > 1) load_idx(1);
+        store_rows(0);
+        __syncthreads();
+    }
+
+    for (int t = 0; t < ntiles; ++t) {
+        const int buf = t & 1;
+        if (t + 1 < ntiles) load_rows(t + 1);
+        if (t + 2 < ntiles) load_idx(t + 2);
+
+        const unsigned char* kb = smem + buf * BUF;
+        const unsigned char* vb = kb + TP * KS;
+        const int nt = min(n - t * TP, TP);
+#pragma unroll
+        for (int s = 0; s < TP / 32; ++s) {
+            if (wave_has_q && 32 * s < nt) {
+                // S^T = K Q^T
+                f32x16 sacc;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+                const unsigned char* krow = kb + (32 * s + qn) * KS + hh * 16;
+#pragma unroll
+                for (int kk = 0; kk < NKK; ++kk) {
+                    const u32x4 ka = *reinterpret_cast<const u32x4*>(krow + kk * 32);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        sacc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(ka[e]), qreg[kk][e], sacc, 0, 0, 0);
+                }
+                // weights
+                const bool ragged = 32 * s + 32 > nt;
+                float p[16];
+                if (MODE == CKV_SOFTMAX) {
+                    if (ragged) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            if (32 * s + 8 * (r >> 2) + 4 * hh + (r & 3) >= nt) sacc[r] = -INFINITY;
+                    }
+                    float tmax = sacc[0];
+#pragma unroll
+                    for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, sacc[r]);
+                    tmax = fmaxf(tmax, other_half(tmax)) * sc;
+                    if (__any(tmax > m_ref + kLazy)) {
+                        const float m_new = fmaxf(m_ref, tmax);
+                        const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
+                        lsum *= alpha;
+#pragma unroll
+                        for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+                        m_ref = m_new;
+                    }
+                    float psum = 0.f;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        p[r] = __builtin_amdgcn_exp2f(fmaf(sacc[r], sc, -m_ref));
+                        psum += p[r];
+                    }
+                    lsum += psum;
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float x = sacc[r] * sc;
+                        p[r] = x * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-kLog2e * x));
+                        if (ragged && 32 * s + 8 * (r >> 2) + 4 * hh + (r & 3) >= nt) p[r] = 0.f;
+                    }
+                }
+                // O^T += V^T P^T: register r pairs position 8*(r/4) + r%4 (lanes 0-31) with that + 4 (lanes 32-63)
+                const unsigned char* vcol = vb + (32 * s + 4 * hh) * VS + qn * 4;
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+#pragma unroll
+                    for (int dt = 0; dt < NDT; ++dt) {
+                        const float va = *reinterpret_cast<const float*>(vcol + (8 * (r >> 2) + (r & 3)) * VS + dt * 128);
+                        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x2f32(va, p[r], oacc[dt], 0, 0, 0);
+                    }
+            }
+        }
+
+        if (t + 1 < ntiles) store_rows((t + 1) & 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue
+    float l_tot = 0.f;
+    if (MODE == CKV_SOFTMAX) l_tot = lsum + other_half(lsum);
+    if (it.part < 0) {
+        float inv;
+        if (MODE == CKV_SOFTMAX) inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+        else inv = it.n_total > 0 ? 1.f / (float)it.n_total : 0.f;
+        if (qok) {
+            float* op = (float*)a.out + qo;
+#pragma unroll
+            for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int ci = 32 * dt + 8 * (r >> 2) + 4 * hh + (r & 3);
+                    const int pc = ci < d_gv ? ci + d_uv : ci - d_gv;  // kernel column of V -> column of out
+                    if (ci < d_a) op[pc] = oacc[dt][r] * inv;
+                }
+        }
+    } else {
+        float* ws = a.partial + (int64_t)it.part * a.QB * (d_a + 2);
+        const int j = wave * 32 + qn;
+#pragma unroll
+        for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int ci = 32 * dt + 8 * (r >> 2) + 4 * hh + (r & 3);
+                const int pc = ci < d_gv ? ci + d_uv : ci - d_gv;
+                if (ci < d_a) ws[(int64_t)j * d_a + pc] = oacc[dt][r];
+            }
+        if (hh == 0) {
+            ws[(int64_t)a.QB * d_a + j] = m_ref * kLn2;  // natural-log units, as the merge expects
+            ws[(int64_t)a.QB * d_a + a.QB + j] = l_tot;
+        }
+    }
+}
+
+template <int DA, int TP>
+constexpr int lds_bytes() {
+    return 2 * TP * ((DA * 4 + 16) + (DA * 4 + 32));
+}
+
+template <int DA, int TP, int MODE>
+hipError_t prepare() {
+    constexpr int lds = lds_bytes<DA, TP>();
+    static hipError_t done =
+        hipFuncSetAttribute((const void*)ckv_mfma32_kernel<DA, TP, MODE>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    return done;
+}
+
+template <int DA, int TP, int MODE>
+hipError_t launch(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
+    hipError_t e = prepare<DA, TP, MODE>();
+    if (e != hipSuccess) return e;
+    constexpr int lds = lds_bytes<DA, TP>();
+    hipLaunchKernelGGL((ckv_mfma32_kernel<DA, TP, MODE>), dim3(c->n_items), dim3(256), lds, s, a);
+    return hipGetLastError();
+}
+
+template <int DA, int TP, int MODE>
+int occupancy() {
+    if (prepare<DA, TP, MODE>() != hipSuccess) return 0;
+    int nb = 0;
+    constexpr int lds = lds_bytes<DA, TP>();
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)ckv_mfma32_kernel<DA, TP, MODE>, 256, lds) != hipSuccess) return 0;
+    return nb;
+}
+
+}  // namespace
+
+// (row width the kernel is built for) -> positions per tile
+int ckv_mfma32_tile(int dak) { return dak == 64 ? 64 : 32; }
+
+int ckv_mfma32_occupancy(int dak, int mode) {
+    if (dak == 64) return mode == CKV_SOFTMAX ? occupancy<64, 64, CKV_SOFTMAX>() : occupancy<64, 64, CKV_SILU_OVER_N>();
+    return mode == CKV_SOFTMAX ? occupancy<128, 32, CKV_SOFTMAX>() : occupancy<128, 32, CKV_SILU_OVER_N>();
+}
+
+hipError_t ckv_launch_mfma32(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
+    if (c->n_items == 0) return hipSuccess;
+    const bool softmax = c->shape.mode == CKV_SOFTMAX;
+    if (a.d_a <= 64) return softmax ? launch<64, 64, CKV_SOFTMAX>(c, a, s) : launch<64, 64, CKV_SILU_OVER_N>(c, a, s);
+    return softmax ? launch<128, 32, CKV_SOFTMAX>(c, a, s) : launch<128, 32, CKV_SILU_OVER_N>(c, a, s);
+}

@@ -529,3 +529,27 @@ def test_narrow_head_split_history_and_one_side_shared(gpu):
     for share in (wl.SHARE_K, wl.SHARE_V):
         w = make(MFMA_LENGTHS, wl.BF16, wl.SILU_OVER_N, d_a=48, d_u=4, H=2, P=300, Nq=32, share=share)
         run_and_check(gpu, w, f"narrow head, share={share}", expect_variant="mfma_bf16_d64")
+
+
+# ---------------------------------------------------------------------------------------------
+# fp32 storage, many queries: the fp32 matrix instruction
+@pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
+@pytest.mark.parametrize("d_a,d_u,pool_ld,Nq", [(64, 8, 64, 64), (128, 8, 128, 128), (64, 4, 60, 16), (128, 0, 128, 40),
+                                                 (64, 3, 64, 20), (96, 8, 88, 33), (128, 24, 104, 200), (32, 32, 0, 9),
+                                                 (100, 5, 96, 64), (8, 2, 8, 8)])
+def test_fp32_many_queries(gpu, mode, d_a, d_u, pool_ld, Nq):
+    w = make(MFMA_LENGTHS, wl.F32, mode, d_a=d_a, d_u=d_u, H=2, P=700, Nq=Nq, **({"pool_ld": pool_ld} if pool_ld else {}))
+    run_and_check(gpu, w, f"fp32 many queries d_a={d_a} d_u={d_u} ld={pool_ld} Nq={Nq} mode={mode}",
+                  expect_variant=f"mfma_f32_d{64 if d_a <= 64 else 128}")
+
+
+def test_fp32_many_queries_split_history_sharing_and_large_scores(gpu):
+    w = make((5000, 70, 2300, 1024, 1025), wl.F32, wl.SOFTMAX, d_a=128, d_u=8, H=2, P=5000, Nq=128)
+    run_and_check(gpu, w, "fp32 many queries, split history", expect_variant="mfma_f32_d128")
+    for share in (wl.SHARE_K, wl.SHARE_V):
+        w = make(MFMA_LENGTHS, wl.F32, wl.SILU_OVER_N, d_a=64, d_u=4, H=2, P=300, Nq=32, share=share)
+        run_and_check(gpu, w, f"fp32 many queries, share={share}", expect_variant="mfma_f32_d64")
+    w = make((700, 129), wl.F32, wl.SOFTMAX, d_a=64, d_u=8, H=1, P=300, Nq=32, sigma_q=6.0, scale=1.0)
+    run_and_check(gpu, w, "fp32 many queries, large scores", expect_variant="mfma_f32_d64")
+    w = make((70, 33), wl.F32, wl.SOFTMAX, d_a=64, d_u=8, H=1, P=50, Nq=16, scale=-0.125)
+    run_and_check(gpu, w, "fp32 negative scale", expect_variant="stream")
