@@ -333,7 +333,7 @@ int64_t simulate_dispatch(const std::vector<ckv_item>& items, int64_t slots, int
 int resident_workgroups(const ckv_cache* c) {
     const ckv_shape& s = c->shape;
     const int d_a = s.d_g + s.d_u;
-    if (c->family == CKV_K_MFMA) return std::max(1, ckv_mfma_occupancy(d_a <= 64 ? 64 : 128, c->nw, c->tp, s.mode));
+    if (c->family == CKV_K_MFMA) return std::max(1, ckv_mfma_occupancy(d_a <= 64 ? 64 : (d_a <= 128 ? 128 : 256), c->nw, c->tp, s.mode));
     if (c->family == CKV_K_DMA) return std::max(1, ckv_dma_occupancy(d_a, c->nw, c->qg, s.mode));
     if (c->family == CKV_K_MFMA32) return std::max(1, ckv_mfma32_occupancy(d_a <= 64 ? 64 : 128, s.mode));
     return 8;
@@ -588,9 +588,9 @@ void choose_variant(ckv_cache* c) {
     const int d_a = s.d_g + s.d_u;
     c->family = CKV_K_STREAM;
     // the matrix-core kernels take the running maximum before scaling, which needs scale > 0
-    if (s.dtype == CKV_BF16 && d_a <= 128 && s.Nq >= 8 && (s.d_g == 0 || s.pool_ld % 8 == 0) &&
+    if (s.dtype == CKV_BF16 && d_a <= 256 && s.Nq >= 8 && (s.d_g == 0 || s.pool_ld % 8 == 0) &&
         (s.mode == CKV_SILU_OVER_N || s.scale > 0.f)) {
-        const int dak = d_a <= 64 ? 64 : 128;  // row width the register-staged kernel is built for
+        const int dak = d_a <= 64 ? 64 : (d_a <= 128 ? 128 : 256);  // row width the register-staged kernel is built for
         const char* impl = getenv("CKV_MFMA_IMPL");  // tuning knob: "staged" forces the register-staged kernel
         {
             // direct-to-LDS kernel: 32 queries per wavefront, up to 4 wavefronts per workgroup (two
@@ -610,8 +610,8 @@ void choose_variant(ckv_cache* c) {
                 return;
             }
         }
-        const int nw = s.Nq <= 32 ? 1 : (s.Nq <= 64 ? 2 : 4);
-        const int tp = (dak == 128 && nw == 1) ? 32 : 64;
+        const int nw = dak == 256 ? 4 : (s.Nq <= 32 ? 1 : (s.Nq <= 64 ? 2 : 4));
+        const int tp = (dak == 256 || (dak == 128 && nw == 1)) ? 32 : 64;
         if (ckv_mfma_supported(dak, nw, tp)) {
             c->family = CKV_K_MFMA;
             c->nw = nw;

@@ -1,6 +1,7 @@
 // Matrix-core gather-concat-attend kernel for many candidate queries per user (bf16 storage,
-// fp32 accumulation, built for rows of DA = 64 or 128 columns; a narrower d_a runs in the next
-// wider kernel with its missing columns as zeros of K, V and q).
+// fp32 accumulation, built for rows of DA = 64, 128 or 256 columns; a narrower d_a runs in the next
+// wider kernel with its missing columns as zeros of K, V and q; the 256-column kernel keeps one
+// workgroup of four wavefronts per compute unit, its accumulators need the whole register file).
 //
 // A workgroup of NW wavefronts serves one work item: a run of positions of one user and head
 // and a block of 32*NW queries; wavefront w owns queries 32w .. 32w+31 and every wavefront
@@ -76,7 +77,7 @@ __device__ __forceinline__ uint4 gather_chunk(const uint16_t* __restrict__ pool_
 }
 
 template <int DA, int NW, int TP, int MODE>
-__global__ __launch_bounds__(NW * 64, (DA == 128 ? 2 : 2)) void ckv_mfma_kernel(ckv_args a) {
+__global__ __launch_bounds__(NW * 64, (DA == 256 ? 1 : 2)) void ckv_mfma_kernel(ckv_args a) {
     constexpr int NT = NW * 64;        // threads
     constexpr int CH = DA / 8;         // 16-byte chunks per row
     constexpr int RPP = NT / CH;       // rows gathered per pass
@@ -326,7 +327,7 @@ int occupancy() {
     return nb;
 }
 
-#define CKV_MFMA_SHAPES(X) X(64, 1, 64) X(64, 2, 64) X(64, 4, 64) X(128, 1, 32) X(128, 2, 64) X(128, 4, 64)
+#define CKV_MFMA_SHAPES(X) X(64, 1, 64) X(64, 2, 64) X(64, 4, 64) X(128, 1, 32) X(128, 2, 64) X(128, 4, 64) X(256, 4, 32)
 
 }  // namespace
 
@@ -349,7 +350,7 @@ int ckv_mfma_occupancy(int d_a, int nw, int tp, int mode) {
 
 hipError_t ckv_launch_mfma(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
     if (c->n_items == 0) return hipSuccess;
-    const int d_a = a.d_a <= 64 ? 64 : 128, nw = c->nw, tp = c->tp;  // the kernel's row width
+    const int d_a = a.d_a <= 64 ? 64 : (a.d_a <= 128 ? 128 : 256), nw = c->nw, tp = c->tp;  // the kernel's row width
 #define X(DA, NW, TP)                                                                         \
     if (d_a == DA && nw == NW && tp == TP)                                                    \
         return c->shape.mode == CKV_SOFTMAX ? launch<DA, NW, TP, CKV_SOFTMAX>(c, a, s)         \

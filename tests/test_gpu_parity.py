@@ -553,3 +553,17 @@ def test_fp32_many_queries_split_history_sharing_and_large_scores(gpu):
     run_and_check(gpu, w, "fp32 many queries, large scores", expect_variant="mfma_f32_d64")
     w = make((70, 33), wl.F32, wl.SOFTMAX, d_a=64, d_u=8, H=1, P=50, Nq=16, scale=-0.125)
     run_and_check(gpu, w, "fp32 negative scale", expect_variant="stream")
+
+
+@pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
+@pytest.mark.parametrize("d_a,d_u,pool_ld,Nq", [(256, 8, 256, 128), (256, 0, 256, 16), (192, 16, 176, 64), (200, 5, 200, 40),
+                                                 (136, 8, 128, 200)])
+def test_wide_bf16_heads_many_queries(gpu, mode, d_a, d_u, pool_ld, Nq):
+    """Heads of 129 to 256 columns: the 256-column register-staged kernel (one workgroup per compute unit)."""
+    w = make(MFMA_LENGTHS, wl.BF16, mode, d_a=d_a, d_u=d_u, H=2, P=700, Nq=Nq, pool_ld=pool_ld)
+    run_and_check(gpu, w, f"wide head d_a={d_a} d_u={d_u} ld={pool_ld} Nq={Nq} mode={mode}", expect_variant="mfma_bf16_d256")
+
+
+def test_wide_bf16_head_split_history(gpu):
+    w = make((5000, 70, 2300), wl.BF16, wl.SOFTMAX, d_a=256, d_u=8, H=2, P=5000, Nq=64)
+    run_and_check(gpu, w, "wide head, split history", expect_variant="mfma_bf16_d256")
