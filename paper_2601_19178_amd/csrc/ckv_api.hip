@@ -335,7 +335,7 @@ int resident_workgroups(const ckv_cache* c) {
     const int d_a = s.d_g + s.d_u;
     if (c->family == CKV_K_MFMA) return std::max(1, ckv_mfma_occupancy(d_a <= 64 ? 64 : (d_a <= 128 ? 128 : 256), c->nw, c->tp, s.mode));
     if (c->family == CKV_K_DMA) return std::max(1, ckv_dma_occupancy(d_a, c->nw, c->qg, s.mode));
-    if (c->family == CKV_K_MFMA32) return std::max(1, ckv_mfma32_occupancy(d_a <= 64 ? 64 : 128, s.mode));
+    if (c->family == CKV_K_MFMA32) return std::max(1, ckv_mfma32_occupancy(d_a <= 64 ? 64 : (d_a <= 128 ? 128 : 256), s.mode));
     return 8;
 }
 
@@ -623,9 +623,9 @@ void choose_variant(ckv_cache* c) {
         }
     }
     // fp32 storage, many queries: the same organisation on the fp32 matrix instruction
-    if (s.dtype == CKV_F32 && d_a <= 128 && s.Nq >= 8 && (s.d_g == 0 || s.pool_ld % 4 == 0) &&
+    if (s.dtype == CKV_F32 && d_a <= 256 && s.Nq >= 8 && (s.d_g == 0 || s.pool_ld % 4 == 0) &&
         (s.mode == CKV_SILU_OVER_N || s.scale > 0.f)) {
-        const int dak = d_a <= 64 ? 64 : 128;
+        const int dak = d_a <= 64 ? 64 : (d_a <= 128 ? 128 : 256);
         c->family = CKV_K_MFMA32;
         c->nw = 4;
         c->tp = ckv_mfma32_tile(dak);

@@ -1,6 +1,7 @@
 // Matrix-core gather-concat-attend kernel for many candidate queries per user, fp32 storage
-// (fp32 products and accumulation on v_mfma_f32_32x32x2_f32; built for rows of DA = 64 or 128
-// columns, a narrower d_a runs in the next wider kernel with zero columns).
+// (fp32 products and accumulation on v_mfma_f32_32x32x2_f32; built for rows of DA = 64, 128 or 256
+// columns, a narrower d_a runs in the next wider kernel with zero columns; the 256-column kernel
+// keeps one workgroup per compute unit, it needs the whole register file and most of the LDS).
 //
 // Same organisation as the bf16 register-staged kernel: a workgroup of four wavefronts serves one
 // work item (a run of positions of one user and head, a block of 128 queries; wavefront w owns
@@ -54,7 +55,7 @@ __device__ __forceinline__ u32x4 gather_chunk(const float* __restrict__ pool_h, 
 }
 
 template <int DA, int TP, int MODE>
-__global__ __launch_bounds__(256, 2) void ckv_mfma32_kernel(ckv_args a) {
+__global__ __launch_bounds__(256, (DA == 256 ? 1 : 2)) void ckv_mfma32_kernel(ckv_args a) {
     constexpr int NT = 256;            // threads: four wavefronts
     constexpr int CH = DA / 4;         // 16-byte chunks per row
     constexpr int RPP = NT / CH;       // rows gathered per pass
@@ -302,12 +303,14 @@ int ckv_mfma32_tile(int dak) { return dak == 64 ? 64 : 32; }
 
 int ckv_mfma32_occupancy(int dak, int mode) {
     if (dak == 64) return mode == CKV_SOFTMAX ? occupancy<64, 64, CKV_SOFTMAX>() : occupancy<64, 64, CKV_SILU_OVER_N>();
-    return mode == CKV_SOFTMAX ? occupancy<128, 32, CKV_SOFTMAX>() : occupancy<128, 32, CKV_SILU_OVER_N>();
+    if (dak == 128) return mode == CKV_SOFTMAX ? occupancy<128, 32, CKV_SOFTMAX>() : occupancy<128, 32, CKV_SILU_OVER_N>();
+    return mode == CKV_SOFTMAX ? occupancy<256, 32, CKV_SOFTMAX>() : occupancy<256, 32, CKV_SILU_OVER_N>();
 }
 
 hipError_t ckv_launch_mfma32(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
     if (c->n_items == 0) return hipSuccess;
     const bool softmax = c->shape.mode == CKV_SOFTMAX;
     if (a.d_a <= 64) return softmax ? launch<64, 64, CKV_SOFTMAX>(c, a, s) : launch<64, 64, CKV_SILU_OVER_N>(c, a, s);
-    return softmax ? launch<128, 32, CKV_SOFTMAX>(c, a, s) : launch<128, 32, CKV_SILU_OVER_N>(c, a, s);
+    if (a.d_a <= 128) return softmax ? launch<128, 32, CKV_SOFTMAX>(c, a, s) : launch<128, 32, CKV_SILU_OVER_N>(c, a, s);
+    return softmax ? launch<256, 32, CKV_SOFTMAX>(c, a, s) : launch<256, 32, CKV_SILU_OVER_N>(c, a, s);
 }

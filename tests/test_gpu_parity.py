@@ -567,3 +567,10 @@ def test_wide_bf16_heads_many_queries(gpu, mode, d_a, d_u, pool_ld, Nq):
 def test_wide_bf16_head_split_history(gpu):
     w = make((5000, 70, 2300), wl.BF16, wl.SOFTMAX, d_a=256, d_u=8, H=2, P=5000, Nq=64)
     run_and_check(gpu, w, "wide head, split history", expect_variant="mfma_bf16_d256")
+
+
+@pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
+@pytest.mark.parametrize("d_a,d_u,pool_ld,Nq", [(256, 8, 256, 128), (192, 16, 176, 40), (130, 3, 128, 9)])
+def test_wide_fp32_heads_many_queries(gpu, mode, d_a, d_u, pool_ld, Nq):
+    w = make(MFMA_LENGTHS, wl.F32, mode, d_a=d_a, d_u=d_u, H=2, P=700, Nq=Nq, pool_ld=pool_ld)
+    run_and_check(gpu, w, f"wide fp32 head d_a={d_a} d_u={d_u} ld={pool_ld} Nq={Nq} mode={mode}", expect_variant="mfma_f32_d256")
