@@ -66,7 +66,8 @@ enum {
  *   d_a <= 256 for any widths and stride; d_a <= 512 when d_u, d_g and pool_ld are multiples of 4,
  *   <= 1024 for bf16 when they are multiples of 8 (CKV_ERR_UNSUPPORTED beyond);
  *   every device pointer 16-byte aligned (CKV_ERR_UNSUPPORTED); device gfx950 (CKV_ERR_UNSUPPORTED).
- * The matrix-core kernels take Nq >= 8 (scale > 0 for softmax): bf16 with d_a <= 256 and pool_ld a multiple
+ * The matrix-core kernels take Nq >= 8 (>= 3 for the fastest bf16 shapes, >= 6 in fp32; scale > 0 for
+ * softmax): bf16 with d_a <= 256 and pool_ld a multiple
  * of 8 (fastest at d_a of exactly 64 or 128 with an even d_u <= 8), fp32 with d_a <= 256 and pool_ld a
  * multiple of 4 (on the fp32 matrix instruction, a sixteenth of the bf16 rate).  Every other shape runs the streaming kernel,
  * which is made for few queries.  ckv_variant names the choice.

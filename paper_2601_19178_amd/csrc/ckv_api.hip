@@ -587,8 +587,12 @@ void choose_variant(ckv_cache* c) {
     const ckv_shape& s = c->shape;
     const int d_a = s.d_g + s.d_u;
     c->family = CKV_K_STREAM;
+    // Fewest queries for which a matrix-core kernel beats the streaming kernel (whose time grows with the
+    // number of queries while theirs does not, up to 32 per wavefront): measured crossovers on configs 2, 3
+    // and 4 are 2-3 queries for the direct-to-LDS kernel, ~5 for the fp32 kernel, ~8 for the register-staged one.
+    constexpr int kMinNqDma = 3, kMinNqF32 = 6, kMinNqStaged = 8;
     // the matrix-core kernels take the running maximum before scaling, which needs scale > 0
-    if (s.dtype == CKV_BF16 && d_a <= 256 && s.Nq >= 8 && (s.d_g == 0 || s.pool_ld % 8 == 0) &&
+    if (s.dtype == CKV_BF16 && d_a <= 256 && s.Nq >= kMinNqDma && (s.d_g == 0 || s.pool_ld % 8 == 0) &&
         (s.mode == CKV_SILU_OVER_N || s.scale > 0.f)) {
         const int dak = d_a <= 64 ? 64 : (d_a <= 128 ? 128 : 256);  // row width the register-staged kernel is built for
         const char* impl = getenv("CKV_MFMA_IMPL");  // tuning knob: "staged" forces the register-staged kernel
@@ -612,7 +616,7 @@ void choose_variant(ckv_cache* c) {
         }
         const int nw = dak == 256 ? 4 : (s.Nq <= 32 ? 1 : (s.Nq <= 64 ? 2 : 4));
         const int tp = (dak == 256 || (dak == 128 && nw == 1)) ? 32 : 64;
-        if (ckv_mfma_supported(dak, nw, tp)) {
+        if (s.Nq >= kMinNqStaged && ckv_mfma_supported(dak, nw, tp)) {
             c->family = CKV_K_MFMA;
             c->nw = nw;
             c->tp = tp;
@@ -623,7 +627,7 @@ void choose_variant(ckv_cache* c) {
         }
     }
     // fp32 storage, many queries: the same organisation on the fp32 matrix instruction
-    if (s.dtype == CKV_F32 && d_a <= 256 && s.Nq >= 8 && (s.d_g == 0 || s.pool_ld % 4 == 0) &&
+    if (s.dtype == CKV_F32 && d_a <= 256 && s.Nq >= kMinNqF32 && (s.d_g == 0 || s.pool_ld % 4 == 0) &&
         (s.mode == CKV_SILU_OVER_N || s.scale > 0.f)) {
         const int dak = d_a <= 64 ? 64 : (d_a <= 128 ? 128 : 256);
         c->family = CKV_K_MFMA32;

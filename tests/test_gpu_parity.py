@@ -574,3 +574,15 @@ def test_wide_bf16_head_split_history(gpu):
 def test_wide_fp32_heads_many_queries(gpu, mode, d_a, d_u, pool_ld, Nq):
     w = make(MFMA_LENGTHS, wl.F32, mode, d_a=d_a, d_u=d_u, H=2, P=700, Nq=Nq, pool_ld=pool_ld)
     run_and_check(gpu, w, f"wide fp32 head d_a={d_a} d_u={d_u} ld={pool_ld} Nq={Nq} mode={mode}", expect_variant="mfma_f32_d256")
+
+
+@pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
+@pytest.mark.parametrize("dtype,d_a,d_u,Nq,expect", [(wl.BF16, 64, 8, 3, "mfma_dma_bf16_d64_w1"), (wl.BF16, 128, 4, 5, "mfma_dma_bf16_d128_w1"),
+                                                      (wl.BF16, 64, 2, 7, "mfma_dma_bf16_d64_w1"), (wl.BF16, 64, 8, 2, "stream"),
+                                                      (wl.BF16, 64, 3, 7, "stream"), (wl.F32, 64, 8, 6, "mfma_f32_d64"),
+                                                      (wl.F32, 128, 8, 5, "stream"), (wl.F32, 128, 8, 7, "mfma_f32_d128")])
+def test_few_queries_cross_over_to_the_matrix_core_kernels(gpu, mode, dtype, d_a, d_u, Nq, expect):
+    """The streaming kernel's time grows with the number of queries, the matrix-core kernels' does not: from three
+    queries on (six in fp32, eight for the register-staged kernel) the matrix-core kernels are chosen."""
+    w = make(MFMA_LENGTHS, dtype, mode, d_a=d_a, d_u=d_u, H=2, P=700, Nq=Nq)
+    run_and_check(gpu, w, f"few queries dtype={dtype} d_a={d_a} d_u={d_u} Nq={Nq} mode={mode}", expect_variant=expect)
