@@ -68,7 +68,7 @@ enum {
  *   every device pointer 16-byte aligned (CKV_ERR_UNSUPPORTED); device gfx950 (CKV_ERR_UNSUPPORTED).
  * The matrix-core kernels take Nq >= 8 (>= 3 for the fastest bf16 shapes, >= 6 in fp32; scale > 0 for
  * softmax): bf16 with d_a <= 256 and pool_ld a multiple
- * of 8 (fastest at d_a of exactly 64 or 128 with an even d_u <= 8), fp32 with d_a <= 256 and pool_ld a
+ * of 8 (fastest at d_a of exactly 64 or 128 with d_u of 0, 1, 2, 3, 4, 6 or 8), fp32 with d_a <= 256 and pool_ld a
  * multiple of 4 (on the fp32 matrix instruction, a sixteenth of the bf16 rate).  Every other shape runs the streaming kernel,
  * which is made for few queries.  ckv_variant names the choice.
  */
@@ -208,6 +208,8 @@ int64_t ckv_cache_stored_bytes(const ckv_cache* c);
  *   q         device [B][H][Nq][d_a]: queries, columns in final-K order (user columns first).
  *   out       device [B][H][Nq][d_a]: written completely (zeros for users with n_b = 0).
  *
+ * With bf16 and an odd d_u the user arrays are read in aligned 4-byte words: they must be readable up to
+ * a multiple of 4 bytes (the handle's own views are).
  * No allocation, no synchronisation, no validation pass over the data: indices were checked
  * when the cache was built; passing other index buffers with out-of-range entries is
  * undefined.  Calls on the same handle share its split workspace, so two calls on one handle

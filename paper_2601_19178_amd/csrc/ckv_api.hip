@@ -601,7 +601,8 @@ void choose_variant(ckv_cache* c) {
             // wavefronts per SIMD overlap better than one wavefront with two query groups)
             int nw = s.Nq <= 32 ? 1 : (s.Nq <= 64 ? 2 : 4), qg = 1;
             if (const char* shp = getenv("CKV_DMA_SHAPE")) sscanf(shp, "%d,%d", &nw, &qg);  // tuning knob "nw,qg"
-            const int nui = s.d_g > 0 && d_a == dak && ckv_dma_supported(d_a, nw, qg) ? ckv_dma_nui(d_a, nw, s.d_u) : -1;
+            const int nui = s.d_g > 0 && d_a == dak && ckv_dma_supported(d_a, nw, qg) && (qg == 1 || !(s.d_u & 1))
+                                ? ckv_dma_nui(d_a, nw, s.d_u) : -1;
             if (nui >= 0 && !(impl && strcmp(impl, "staged") == 0)) {
                 c->family = CKV_K_DMA;
                 c->nw = nw;
@@ -741,8 +742,9 @@ static int cache_new(const char* who, const ckv_shape* shape, const int32_t* len
         ckv_side_dims(s, 0, &d_uk, &d_gk);
         ckv_side_dims(s, 1, &d_uv, &d_gv);
         if (n_ph > 0 && s.d_g > 0) CKV_HIP(cache_alloc(c, (void**)&c->d_idx, sizeof(int32_t) * 2 * n_ph));
-        if (n_ph > 0 && d_uk > 0) CKV_HIP(cache_alloc(c, &c->d_user_k, n_ph * (size_t)d_uk * esize(s.dtype)));
-        if (n_ph > 0 && d_uv > 0) CKV_HIP(cache_alloc(c, &c->d_user_v, n_ph * (size_t)d_uv * esize(s.dtype)));
+        // (rounded up to whole 16-byte chunks: an odd number of bf16 elements is read in aligned dwords)
+        if (n_ph > 0 && d_uk > 0) CKV_HIP(cache_alloc(c, &c->d_user_k, (n_ph * (size_t)d_uk * esize(s.dtype) + 15) / 16 * 16));
+        if (n_ph > 0 && d_uv > 0) CKV_HIP(cache_alloc(c, &c->d_user_v, (n_ph * (size_t)d_uv * esize(s.dtype) + 15) / 16 * 16));
     }
 done:
     if (rc != CKV_OK) {

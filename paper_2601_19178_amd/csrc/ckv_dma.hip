@@ -31,6 +31,7 @@ typedef __attribute__((address_space(3))) unsigned char lds_u8;
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
 typedef __attribute__((address_space(3))) uint32_t lds_u32;
+typedef __attribute__((address_space(3))) uint16_t lds_u16;
 typedef __attribute__((address_space(3))) float lds_f32;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
@@ -124,7 +125,8 @@ struct Geo {
 // QG = groups of 32 queries owned by one wavefront.  With QG = 2 every K and V operand read
 // from LDS feeds two MFMAs, and the weight arithmetic of one group can run while the matrix
 // core works on the other.
-template <int DA, int NW, int QG, int MODE>
+// UODD: d_u is odd (1 or 3); an instantiation of its own, so that the even case carries none of its code.
+template <int DA, int NW, int QG, int MODE, bool UODD>
 __global__ __launch_bounds__(NW * 64)
 __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES_PER_EU))) void ckv_dma_kernel(ckv_args a, int nui) {
     using G = Geo<DA, NW>;
@@ -152,6 +154,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
     }
     const int qn = lane & 31, hh = lane >> 5;
     const int d_g = a.d_g, d_u = a.d_u;
+    constexpr bool uodd = UODD;  // user and pool columns then change places at an odd column: no 32-bit shortcuts
     // A side that is not shared (only keys or only values gather from a pool) keeps whole d_a-wide rows in
     // its user array: its tile rows are fetched from there, position by position, with the same
     // instructions that fetch pool rows for a shared side, and it has no user slice to append.
@@ -213,7 +216,13 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
                 for (int j = 0; j < 4; ++j) {
                     const int ci = 16 * kk + 8 * hh + 2 * j;
                     const int pc = ci < dgk ? ci + duk : ci - dgk;
-                    w[j] = *(const lds_u32*)(uintptr_t)(qlds + (g * 32 + qn) * QS + pc * 2);
+                    if (!uodd) {
+                        w[j] = *(const lds_u32*)(uintptr_t)(qlds + (g * 32 + qn) * QS + pc * 2);
+                    } else {
+                        const int pc1 = ci + 1 < dgk ? ci + 1 + duk : ci + 1 - dgk;
+                        w[j] = (uint32_t) * (const lds_u16*)(uintptr_t)(qlds + (g * 32 + qn) * QS + pc * 2) |
+                               ((uint32_t) * (const lds_u16*)(uintptr_t)(qlds + (g * 32 + qn) * QS + pc1 * 2) << 16);
+                    }
                 }
                 qreg[g][kk] = __builtin_bit_cast(bf16x8, w);
             }
@@ -264,8 +273,10 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
         //      row tails (the concat) without depending on any other wavefront.  Dword jj of the
         //      wavefront's block is ((kv * ROWS_W + o) * hd + off): kv = K or V, o = ordinal of the
         //      own row, off = dword inside the d_u-wide slice (hd = d_u / 2 dwords).
+        //      An odd d_u (1 or 3) cannot be moved in whole dwords: a lane then stands for one element, fetches
+        //      the aligned dword that holds it and appends its half with a 16-bit LDS write.
         constexpr int ROWS_W = TP / NW;
-        const int hd = d_u > 0 ? d_u >> 1 : 1;
+        const int hd = d_u > 0 ? (uodd ? d_u : d_u >> 1) : 1;  // lanes per slice
         int up[G::NUI_MAX], uoff[G::NUI_MAX];
         bool uisv[G::NUI_MAX], uok[G::NUI_MAX];
         uint32_t cdst[G::NUI_MAX];
@@ -280,7 +291,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
             uok[u] = uok[u] && (uisv[u] ? vsh : ksh);  // nothing to append on a side that is not shared
             const int o = uisv[u] ? slice - ROWS_W : slice;
             up[u] = ((o / G::RPI) * NW + wave) * G::RPI + (o % G::RPI);
-            const int col = d_g + 2 * uoff[u];
+            const int col = d_g + (uodd ? uoff[u] : 2 * uoff[u]);
             const int slot = (col >> 3) ^ (uisv[u] ? fv<DA>(up[u]) : fk<DA>(up[u]));
             cdst[u] = (uisv[u] ? G::KV : 0) + up[u] * G::ROWB + slot * 16 + (col & 7) * 2;
         }
@@ -311,7 +322,9 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
             for (int u = 0; u < G::NUI_MAX; ++u) {
                 if (u < nui) {
                     const int pos = min(tile * TP + up[u], n - 1);
-                    const uint32_t* g = (uisv[u] ? uv32 : uk32) + (int64_t)pos * hd + uoff[u];
+                    const uint32_t* g;
+                    if (uodd) g = (const uint32_t*)(uisv[u] ? a.user_v : a.user_k) + (((hT + pos) * d_u + uoff[u]) >> 1);
+                    else g = (uisv[u] ? uv32 : uk32) + (int64_t)pos * hd + uoff[u];
                     dma4(g, st + 2 * G::KV + (wave * G::NUI_MAX + u) * 256);
                 }
             }
@@ -323,6 +336,16 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
 #pragma unroll
             for (int u = 0; u < G::NUI_MAX; ++u)
                 if (uok[u]) x[u] = *(const lds_u32*)(uintptr_t)(st + 2 * G::KV + (wave * G::NUI_MAX + u) * 256 + lane * 4);
+            if (uodd) {
+#pragma unroll
+                for (int u = 0; u < G::NUI_MAX; ++u)
+                    if (uok[u]) {
+                        const int pos = min(tile * TP + up[u], n - 1);
+                        const bool upper = ((hT + pos) * d_u + uoff[u]) & 1;  // which half of the fetched dword
+                        *(lds_u16*)(uintptr_t)(st + cdst[u]) = (uint16_t)(upper ? x[u] >> 16 : x[u]);
+                    }
+                return;
+            }
 #pragma unroll
             for (int u = 0; u < G::NUI_MAX; ++u)
                 if (uok[u]) *(lds_u32*)(uintptr_t)(st + cdst[u]) = x[u];
@@ -464,8 +487,14 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
                 for (int r = 0; r < 16; r += 2) {
                     const int ci = 32 * dt + 8 * (r >> 2) + 4 * hh + (r & 3);
                     const int pc = ci < dgv ? ci + duv : ci - dgv;
-                    const uint32_t two = (uint32_t)f2bf(oacc[g][dt][r] * inv) | ((uint32_t)f2bf(oacc[g][dt][r + 1] * inv) << 16);
-                    *(lds_u32*)(uintptr_t)(qlds + (g * 32 + qn) * QS + pc * 2) = two;
+                    if (!uodd) {
+                        const uint32_t two = (uint32_t)f2bf(oacc[g][dt][r] * inv) | ((uint32_t)f2bf(oacc[g][dt][r + 1] * inv) << 16);
+                        *(lds_u32*)(uintptr_t)(qlds + (g * 32 + qn) * QS + pc * 2) = two;
+                    } else {
+                        const int pc1 = ci + 1 < dgv ? ci + 1 + duv : ci + 1 - dgv;
+                        *(lds_u16*)(uintptr_t)(qlds + (g * 32 + qn) * QS + pc * 2) = f2bf(oacc[g][dt][r] * inv);
+                        *(lds_u16*)(uintptr_t)(qlds + (g * 32 + qn) * QS + pc1 * 2) = f2bf(oacc[g][dt][r + 1] * inv);
+                    }
                 }
         }
         unsigned char* odst = (unsigned char*)a.out + qbyte0;
@@ -512,29 +541,29 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
     }  // items of this workgroup
 }
 
-template <int DA, int NW, int QG, int MODE>
+template <int DA, int NW, int QG, int MODE, bool UODD>
 hipError_t prepare() {
     constexpr int lds = Geo<DA, NW>::LDS;
     static hipError_t done =
-        hipFuncSetAttribute((const void*)ckv_dma_kernel<DA, NW, QG, MODE>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        hipFuncSetAttribute((const void*)ckv_dma_kernel<DA, NW, QG, MODE, UODD>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     return done;
 }
 
-template <int DA, int NW, int QG, int MODE>
+template <int DA, int NW, int QG, int MODE, bool UODD>
 hipError_t launch(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
-    hipError_t e = prepare<DA, NW, QG, MODE>();
+    hipError_t e = prepare<DA, NW, QG, MODE, UODD>();
     if (e != hipSuccess) return e;
     constexpr int lds = Geo<DA, NW>::LDS;
-    hipLaunchKernelGGL((ckv_dma_kernel<DA, NW, QG, MODE>), dim3(c->n_wg), dim3(NW * 64), lds, s, a, c->nui);
+    hipLaunchKernelGGL((ckv_dma_kernel<DA, NW, QG, MODE, UODD>), dim3(c->n_wg), dim3(NW * 64), lds, s, a, c->nui);
     return hipGetLastError();
 }
 
-template <int DA, int NW, int QG, int MODE>
+template <int DA, int NW, int QG, int MODE, bool UODD>
 int occupancy() {
-    if (prepare<DA, NW, QG, MODE>() != hipSuccess) return 0;
+    if (prepare<DA, NW, QG, MODE, UODD>() != hipSuccess) return 0;
     int nb = 0;
     constexpr int lds = Geo<DA, NW>::LDS;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)ckv_dma_kernel<DA, NW, QG, MODE>, NW * 64, lds) !=
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)ckv_dma_kernel<DA, NW, QG, MODE, UODD>, NW * 64, lds) !=
         hipSuccess)
         return 0;
     return nb;
@@ -558,15 +587,17 @@ bool ckv_dma_supported(int d_a, int nw, int qg) {
 // served by this kernel.
 int ckv_dma_nui(int d_a, int nw, int d_u) {
     if ((d_a != 64 && d_a != 128) || (nw != 1 && nw != 2 && nw != 4)) return -1;
-    if (d_u < 0 || d_u > 8 || (d_u & 1)) return -1;
-    const int need = (32 * d_u + nw * 64 - 1) / (nw * 64);  // ceil(dwords of K_u and V_u / lanes)
+    if (d_u < 0 || d_u > 8 || ((d_u & 1) && d_u > 3)) return -1;
+    // lanes that move the user slices of a tile: one per dword, or one per element when d_u is odd
+    const int need = ((d_u & 1 ? 64 : 32) * d_u + nw * 64 - 1) / (nw * 64);
     return need <= 1 ? need : (need <= 2 ? 2 : 4);
 }
 
 int ckv_dma_occupancy(int d_a, int nw, int qg, int mode) {
+    // (the instantiation for an odd d_u has the same resources to within a few registers)
 #define X(DA, NW, QG)                          \
     if (d_a == DA && nw == NW && qg == QG)     \
-        return mode == CKV_SOFTMAX ? occupancy<DA, NW, QG, CKV_SOFTMAX>() : occupancy<DA, NW, QG, CKV_SILU_OVER_N>();
+        return mode == CKV_SOFTMAX ? occupancy<DA, NW, QG, CKV_SOFTMAX, false>() : occupancy<DA, NW, QG, CKV_SILU_OVER_N, false>();
     CKV_DMA_SHAPES(X)
 #undef X
     return 0;
@@ -575,10 +606,19 @@ int ckv_dma_occupancy(int d_a, int nw, int qg, int mode) {
 hipError_t ckv_launch_dma(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
     if (c->n_items == 0) return hipSuccess;
     const int d_a = a.d_a, nw = c->nw, qg = c->qg;
-#define X(DA, NW, QG)                                                                    \
-    if (d_a == DA && nw == NW && qg == QG)                                               \
-        return c->shape.mode == CKV_SOFTMAX ? launch<DA, NW, QG, CKV_SOFTMAX>(c, a, s)    \
-                                            : launch<DA, NW, QG, CKV_SILU_OVER_N>(c, a, s);
+    if (a.d_u & 1) {  // one query group per wavefront only
+#define X(DA, NW)                                                                          \
+    if (d_a == DA && nw == NW && qg == 1)                                                  \
+        return c->shape.mode == CKV_SOFTMAX ? launch<DA, NW, 1, CKV_SOFTMAX, true>(c, a, s) \
+                                            : launch<DA, NW, 1, CKV_SILU_OVER_N, true>(c, a, s);
+        X(64, 1) X(64, 2) X(64, 4) X(128, 1) X(128, 2) X(128, 4)
+#undef X
+        return hipErrorInvalidValue;
+    }
+#define X(DA, NW, QG)                                                                           \
+    if (d_a == DA && nw == NW && qg == QG)                                                      \
+        return c->shape.mode == CKV_SOFTMAX ? launch<DA, NW, QG, CKV_SOFTMAX, false>(c, a, s)    \
+                                            : launch<DA, NW, QG, CKV_SILU_OVER_N, false>(c, a, s);
     CKV_DMA_SHAPES(X)
 #undef X
     return hipErrorInvalidValue;

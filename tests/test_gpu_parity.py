@@ -139,7 +139,7 @@ MFMA_LENGTHS = (1, 31, 32, 33, 64, 65, 0, 127, 200, 1500, 96, 2)
                                          (128, 2, 16), (128, 4, 64), (64, 6, 128), (128, 0, 32), (64, 8, 8)])
 def test_mfma_ragged(gpu, impl, mode, d_a, d_u, Nq):
     w = make(MFMA_LENGTHS, wl.BF16, mode, d_a=d_a, d_u=d_u, H=2, P=700, Nq=Nq)
-    dma_ok = d_u % 2 == 0 and d_u <= 8
+    dma_ok = d_u <= 8 and (d_u % 2 == 0 or d_u <= 3)
     expect = "mfma_dma" if (impl is None and dma_ok) else "mfma_bf16"
     run_and_check(gpu, w, f"mfma ragged d_a={d_a} d_u={d_u} Nq={Nq} mode={mode} impl={impl}", expect_variant=expect, impl=impl)
 
@@ -268,7 +268,7 @@ def test_single_side_sharing_stream(gpu, share, dtype, mode):
 @pytest.mark.parametrize("d_a,d_u,Nq", [(64, 4, 64), (128, 8, 128), (64, 3, 20), (128, 16, 40), (64, 2, 16), (128, 0, 32)])
 def test_single_side_sharing_matrix_core(gpu, impl, share, mode, d_a, d_u, Nq):
     w = make(MFMA_LENGTHS, wl.BF16, mode, d_a=d_a, d_u=d_u, H=2, P=700, Nq=Nq, share=share)
-    dma_ok = d_u % 2 == 0 and d_u <= 8
+    dma_ok = d_u <= 8 and (d_u % 2 == 0 or d_u <= 3)
     expect = "mfma_dma" if (impl is None and dma_ok) else "mfma_bf16"
     run_and_check(gpu, w, f"mfma share={share} d_a={d_a} d_u={d_u} Nq={Nq} mode={mode} impl={impl}", expect_variant=expect, impl=impl)
 
@@ -579,10 +579,28 @@ def test_wide_fp32_heads_many_queries(gpu, mode, d_a, d_u, pool_ld, Nq):
 @pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
 @pytest.mark.parametrize("dtype,d_a,d_u,Nq,expect", [(wl.BF16, 64, 8, 3, "mfma_dma_bf16_d64_w1"), (wl.BF16, 128, 4, 5, "mfma_dma_bf16_d128_w1"),
                                                       (wl.BF16, 64, 2, 7, "mfma_dma_bf16_d64_w1"), (wl.BF16, 64, 8, 2, "stream"),
-                                                      (wl.BF16, 64, 3, 7, "stream"), (wl.F32, 64, 8, 6, "mfma_f32_d64"),
+                                                      (wl.BF16, 64, 5, 7, "stream"), (wl.BF16, 64, 1, 4, "mfma_dma_bf16_d64_w1"), (wl.F32, 64, 8, 6, "mfma_f32_d64"),
                                                       (wl.F32, 128, 8, 5, "stream"), (wl.F32, 128, 8, 7, "mfma_f32_d128")])
 def test_few_queries_cross_over_to_the_matrix_core_kernels(gpu, mode, dtype, d_a, d_u, Nq, expect):
     """The streaming kernel's time grows with the number of queries, the matrix-core kernels' does not: from three
     queries on (six in fp32, eight for the register-staged kernel) the matrix-core kernels are chosen."""
     w = make(MFMA_LENGTHS, dtype, mode, d_a=d_a, d_u=d_u, H=2, P=700, Nq=Nq)
     run_and_check(gpu, w, f"few queries dtype={dtype} d_a={d_a} d_u={d_u} Nq={Nq} mode={mode}", expect_variant=expect)
+
+
+@pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
+@pytest.mark.parametrize("d_a,d_u,Nq", [(64, 1, 16), (64, 1, 64), (64, 1, 128), (128, 1, 128), (128, 3, 32), (64, 3, 64), (128, 3, 100), (128, 1, 40)])
+def test_odd_user_width_in_the_direct_to_lds_kernel(gpu, mode, d_a, d_u, Nq):
+    """d_u of 1 (the paper's smallest cache, CR = 2 / d_a) and 3: the slices cannot be moved as whole dwords; with an
+    odd number of positions before a head (T is odd here) its slices start on odd elements too."""
+    assert sum(MFMA_LENGTHS) % 2 == 1
+    w = make(MFMA_LENGTHS, wl.BF16, mode, d_a=d_a, d_u=d_u, H=3, P=700, Nq=Nq)
+    run_and_check(gpu, w, f"odd d_u: d_a={d_a} d_u={d_u} Nq={Nq} mode={mode}", expect_variant="mfma_dma")
+
+
+def test_odd_user_width_split_history_and_one_side_shared(gpu):
+    w = make((5001, 70, 2300, 1023), wl.BF16, wl.SOFTMAX, d_a=128, d_u=1, H=2, P=5000, Nq=128)
+    run_and_check(gpu, w, "odd d_u, split history", expect_variant="mfma_dma")
+    for share in (wl.SHARE_K, wl.SHARE_V):
+        w = make(MFMA_LENGTHS, wl.BF16, wl.SILU_OVER_N, d_a=64, d_u=3, H=2, P=300, Nq=32, share=share)
+        run_and_check(gpu, w, f"odd d_u, share={share}", expect_variant="mfma_dma")
