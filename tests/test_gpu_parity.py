@@ -604,3 +604,23 @@ def test_odd_user_width_split_history_and_one_side_shared(gpu):
     for share in (wl.SHARE_K, wl.SHARE_V):
         w = make(MFMA_LENGTHS, wl.BF16, wl.SILU_OVER_N, d_a=64, d_u=3, H=2, P=300, Nq=32, share=share)
         run_and_check(gpu, w, f"odd d_u, share={share}", expect_variant="mfma_dma")
+
+
+@pytest.mark.parametrize("kind", ["dma", "fp32", "stream", "staged"])
+def test_one_very_long_history(gpu, kind):
+    """A single user with 150000 positions: the history is cut into hundreds of pieces over the whole chip and merged
+    (several chunks of pieces in the merge kernel); accuracy must hold over the long sums."""
+    n = 150001
+    if kind == "dma":
+        w = make((n,), wl.BF16, wl.SOFTMAX, d_a=128, d_u=8, H=2, P=20000, Nq=64, idx=("zipf", 1.05))
+        expect = "mfma_dma"
+    elif kind == "fp32":
+        w = make((n,), wl.F32, wl.SILU_OVER_N, d_a=64, d_u=4, H=1, P=20000, Nq=32)
+        expect = "mfma_f32"
+    elif kind == "staged":
+        w = make((n,), wl.BF16, wl.SOFTMAX, d_a=64, d_u=16, H=1, P=20000, Nq=32)
+        expect = "mfma_bf16"
+    else:
+        w = make((n, 3), wl.F32, wl.SOFTMAX, d_a=64, d_u=8, H=2, P=20000, Nq=2)
+        expect = "stream"
+    run_and_check(gpu, w, f"one very long history ({kind})", expect_variant=expect)
