@@ -35,6 +35,8 @@ DESCRIBE = {
     "cfg3_ck": "config 3 with only the keys shared (CollectiveK): V is an ordinary 64-column cache",
     "cfg3_cv": "config 3 with only the values shared (CollectiveV): K is an ordinary 64-column cache",
     "cfg4": "config 4 long ragged: B=128 L~U[2048,8192] H=8 d=120+8 P=65536 Nq=128 softmax bf16",
+    "cfg3_plain": "config 3 with an ordinary K/V cache (d_g = 0): the same decode without compression",
+    "cfg4_plain": "config 4 with an ordinary K/V cache (d_g = 0): the same decode without compression",
     "cfg5": "config 5 large batch: B=8192 L~U[512,2048] H=4 d=62+2 P=1048576 Zipf(1.05) Nq=16 softmax bf16",
 }
 

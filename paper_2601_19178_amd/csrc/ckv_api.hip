@@ -601,8 +601,9 @@ void choose_variant(ckv_cache* c) {
             // wavefronts per SIMD overlap better than one wavefront with two query groups)
             int nw = s.Nq <= 32 ? 1 : (s.Nq <= 64 ? 2 : 4), qg = 1;
             if (const char* shp = getenv("CKV_DMA_SHAPE")) sscanf(shp, "%d,%d", &nw, &qg);  // tuning knob "nw,qg"
-            const int nui = s.d_g > 0 && d_a == dak && ckv_dma_supported(d_a, nw, qg) && (qg == 1 || !(s.d_u & 1))
-                                ? ckv_dma_nui(d_a, nw, s.d_u) : -1;
+            // (d_g = 0, ordinary attention over the user arrays: rows are fetched by position, nothing is appended)
+            const int nui = d_a == dak && ckv_dma_supported(d_a, nw, qg) && (s.d_g == 0 || qg == 1 || !(s.d_u & 1))
+                                ? (s.d_g == 0 ? 0 : ckv_dma_nui(d_a, nw, s.d_u)) : -1;
             if (nui >= 0 && !(impl && strcmp(impl, "staged") == 0)) {
                 c->family = CKV_K_DMA;
                 c->nw = nw;

@@ -178,9 +178,12 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
     // ---- the indices of the first three tiles are requested before the queries, so that the two round
     //      trips overlap (the index slots are private to the wavefront and apart from the query staging)
     const uint32_t idx_lds = lds0 + NS * G::STAGE + wave * G::NIS * G::IDX;
+    // (with no pool at all, d_g = 0, there may be no index buffer: the load still has to be issued, because the
+    // waits below count instructions, so it reads the work list instead and its value is never used)
+    const bool any_pool = ksh || vsh;
     auto issue_idx = [&](int tile) {
         const int pos = min(tile * TP + qn, n - 1);
-        const int32_t* g = (hh ? iv : ik) + pos;
+        const int32_t* g = any_pool ? (hh ? iv : ik) + pos : (const int32_t*)a.items + (qn & 7);
         dma4(g, idx_lds + (tile & (G::NIS - 1)) * G::IDX);
     };
     if (n > 0) {

@@ -48,6 +48,12 @@ CONFIGS = {
                     mode=SILU_OVER_N, dtype=BF16, sigma_pool=1.0 / 8.0, seed=1003, share=SHARE_K),
     "cfg3_cv": dict(B=512, L=(1024, 1024), H=4, d_a=64, d_u=4, P=16384, idx=("zipf", 1.1), Nq=64,
                     mode=SILU_OVER_N, dtype=BF16, sigma_pool=1.0 / 8.0, seed=1003, share=SHARE_V),
+    # configs 3 and 4 with an ordinary K/V cache (d_g = 0: every column is user specific; section 5.3's degenerate
+    # case): the same decode without compression, for comparison on the same kernel
+    "cfg3_plain": dict(B=512, L=(1024, 1024), H=4, d_a=64, d_u=64, P=1, idx="uniform", Nq=64,
+                       mode=SILU_OVER_N, dtype=BF16, sigma_pool=1.0 / 8.0, sigma_user=1.0 / 8.0, seed=1003),
+    "cfg4_plain": dict(B=128, L=(2048, 8192), H=8, d_a=128, d_u=128, P=1, idx="uniform", Nq=128,
+                       mode=SOFTMAX, dtype=BF16, sigma_pool=128.0 ** -0.5, sigma_user=128.0 ** -0.5, seed=1004),
     "cfg5": dict(B=8192, L=(512, 2048), H=4, d_a=64, d_u=2, P=1048576, idx=("zipf", 1.05), Nq=16,
                  mode=SOFTMAX, dtype=BF16, sigma_pool=1.0 / 8.0, seed=1005),
 }

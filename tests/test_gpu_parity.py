@@ -164,9 +164,13 @@ def test_negative_scale_falls_back_to_streaming(gpu):
     run_and_check(gpu, w, "negative scale", expect_variant="stream")
 
 
-def test_mfma_all_users_is_ordinary_attention_when_dg_zero(gpu):
+@pytest.mark.parametrize("impl", [None, "staged"])
+def test_mfma_all_users_is_ordinary_attention_when_dg_zero(gpu, impl):
+    """d_g = 0 (section 5.3: the method degenerates into the ordinary K/V cache): no pool, no indices."""
     w = make(MFMA_LENGTHS, wl.BF16, wl.SOFTMAX, d_a=64, d_u=64, H=1, P=1, Nq=16)
-    run_and_check(gpu, w, "mfma d_g=0", expect_variant="mfma")
+    run_and_check(gpu, w, "mfma d_g=0", expect_variant="mfma_dma" if impl is None else "mfma_bf16", impl=impl)
+    w = make((5000, 70, 2300, 1025), wl.BF16, wl.SILU_OVER_N, d_a=128, d_u=128, H=2, P=1, Nq=128)
+    run_and_check(gpu, w, "mfma d_g=0, 128 columns, split history", expect_variant="mfma_dma" if impl is None else "mfma_bf16", impl=impl)
 
 
 def test_mfma_large_scores_softmax(gpu):
