@@ -20,6 +20,8 @@
 // so N is a constant.
 #include <cstdlib>
 
+#include <type_traits>
+
 #include "ckv_internal.h"
 
 namespace {
@@ -67,22 +69,6 @@ __device__ __forceinline__ void dma4(const void* g, uint32_t lds_base) {
 template <int N>
 __device__ __forceinline__ void wait_vm() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-// wait until at most `base + nui` vector-memory operations are outstanding (nui in {0,1,2,4})
-template <int BASE>
-__device__ __forceinline__ void wait_vm_plus(int nui) {
-    if (nui == 0) wait_vm<BASE>();
-    else if (nui == 1) wait_vm<BASE + 1>();
-    else if (nui == 2) wait_vm<BASE + 2>();
-    else wait_vm<BASE + 4>();
-}
-// wait until at most 2 * (base + nui) vector-memory operations are outstanding
-template <int BASE>
-__device__ __forceinline__ void wait_vm_twice(int nui) {
-    if (nui == 0) wait_vm<2 * BASE>();
-    else if (nui == 1) wait_vm<2 * (BASE + 1)>();
-    else if (nui == 2) wait_vm<2 * (BASE + 2)>();
-    else wait_vm<2 * (BASE + 4)>();
 }
 __device__ __forceinline__ void lds_barrier() {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
@@ -307,15 +293,19 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
         const uint32_t vrow = G::KV + (4 * hh + (s16 >> 2)) * G::ROWB + (s16 & 1) * 8;
         const int vc = 2 * (g16 & 1) + ((s16 & 3) >> 1), vx = fv<DA>(s16 >> 2);
 
-        auto issue_gather = [&](int tile) {
+        // (generic in the number NUI of user-slice loads per wavefront and tile, so that the tile loop, which is
+        // instantiated per value below, carries no test of it)
+        auto issue_gather = [&](auto nui_c, int tile) {
+            constexpr int NUI = decltype(nui_c)::value;
             const uint32_t st = lds0 + (tile & (NS - 1)) * G::STAGE;
             const lds_u32* islot = (const lds_u32*)(uintptr_t)(idx_lds + (tile & (G::NIS - 1)) * G::IDX);
             int rk[G::NI], rv[G::NI];
 #pragma unroll
             for (int i = 0; i < G::NI; ++i) {
                 const int pos = min(tile * TP + gp[i], n - 1);
-                rk[i] = ksh ? (int)islot[gp[i]] : pos;
-                rv[i] = vsh ? (int)islot[32 + gp[i]] : pos;
+                const int jk = (int)islot[gp[i]], jv = (int)islot[32 + gp[i]];  // read in any case: a select, not a branch
+                rk[i] = ksh ? jk : pos;
+                rv[i] = vsh ? jv : pos;
             }
 #pragma unroll
             for (int i = 0; i < G::NI; ++i) {
@@ -325,7 +315,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
             }
 #pragma unroll
             for (int u = 0; u < G::NUI_MAX; ++u) {
-                if (u < nui) {
+                if (u < NUI) {
                     const int pos = min(tile * TP + up[u], n - 1);
                     const uint32_t* g;
                     if (uodd) g = (const uint32_t*)(uisv[u] ? a.user_v : a.user_k) + (((hT + pos) * d_u + uoff[u]) >> 1);
@@ -335,16 +325,17 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
             }
         };
         // the paper's concat: user columns behind the pool columns of the wavefront's own rows
-        auto concat = [&](int tile) {
+        auto concat = [&](auto nui_c, int tile) {
+            constexpr int NUI = decltype(nui_c)::value;
             const uint32_t st = lds0 + (tile & (NS - 1)) * G::STAGE;
             uint32_t x[G::NUI_MAX];
 #pragma unroll
             for (int u = 0; u < G::NUI_MAX; ++u)
-                if (uok[u]) x[u] = *(const lds_u32*)(uintptr_t)(st + 2 * G::KV + (wave * G::NUI_MAX + u) * 256 + lane * 4);
+                if (u < NUI && uok[u]) x[u] = *(const lds_u32*)(uintptr_t)(st + 2 * G::KV + (wave * G::NUI_MAX + u) * 256 + lane * 4);
             if (uodd) {
 #pragma unroll
                 for (int u = 0; u < G::NUI_MAX; ++u)
-                    if (uok[u]) {
+                    if (u < NUI && uok[u]) {
                         const int pos = min(tile * TP + up[u], n - 1);
                         const bool upper = ((hT + pos) * d_u + uoff[u]) & 1;  // which half of the fetched dword
                         *(lds_u16*)(uintptr_t)(st + cdst[u]) = (uint16_t)(upper ? x[u] >> 16 : x[u]);
@@ -353,7 +344,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
             }
 #pragma unroll
             for (int u = 0; u < G::NUI_MAX; ++u)
-                if (uok[u]) *(lds_u32*)(uintptr_t)(st + cdst[u]) = x[u];
+                if (u < NUI && uok[u]) *(lds_u32*)(uintptr_t)(st + cdst[u]) = x[u];
         };
 
         // Order of the asynchronous loads of one wavefront: iteration t issues idx(t+6), then the
@@ -365,9 +356,11 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
         // publishes tile t+1 to the workgroup and retires tile t's stage.
         wait_vm<0>();  // the indices of tiles 0..2, requested before the queries
         if (tr && tid == 0) tr[1] = wall_clock64();
+        auto tile_loop = [&](auto nui_c) {
+        constexpr int NUI = decltype(nui_c)::value;
         for (int t = -(NS - 1); t < ntiles; ++t) {
             issue_idx(t + NS + 2);
-            issue_gather(t + NS - 1);
+            issue_gather(nui_c, t + NS - 1);
             if (t >= 0) {
                 const uint32_t st = lds0 + (t & (NS - 1)) * G::STAGE;
                 const int nt = min(n - t * TP, TP);
@@ -463,10 +456,15 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
             }
             // own gathers of tile t+1 have landed once only the loads of this and the previous
             // iteration are outstanding
-            wait_vm_twice<2 * G::NI + 1>(nui);
-            if (t + 1 >= 0 && t + 1 < ntiles && d_u > 0) concat(t + 1);
+            wait_vm<2 * (2 * G::NI + 1 + NUI)>();
+            if (NUI > 0 && t + 1 >= 0 && t + 1 < ntiles) concat(nui_c, t + 1);
             lds_barrier();
         }
+        };
+        if (nui == 0) tile_loop(std::integral_constant<int, 0>{});
+        else if (nui == 1) tile_loop(std::integral_constant<int, 1>{});
+        else if (G::NUI_MAX >= 2 && nui == 2) tile_loop(std::integral_constant<int, G::NUI_MAX >= 2 ? 2 : 0>{});
+        else if (G::NUI_MAX >= 4) tile_loop(std::integral_constant<int, G::NUI_MAX >= 4 ? 4 : 0>{});
         // the clamped loads past the last tile must have landed, for every wavefront, before the
         // epilogue reuses the stages (and before the workgroup gives its LDS back)
         wait_vm<0>();
