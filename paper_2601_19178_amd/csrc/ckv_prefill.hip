@@ -185,8 +185,17 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
         loff[i] = (uint32_t)lrow[i] * rs + lchunk[i];
     }
     const uint32_t boff = (uint32_t)(lane & (TR - 1)) * 4;
+    // stage i of this workgroup when it is known to be a router tile of TR valid rows: no test, no vector arithmetic
+    auto issue_full = [&](int i) {
+        const uint32_t st = __builtin_amdgcn_readfirstlane(lds0 + (i % NS) * G::STAGE);  // (uniform; kept in a scalar register)
+        const int tile = __builtin_amdgcn_readfirstlane(t_lo + i);  // (uniform anyway; the loads take it in scalar registers)
+        const unsigned char* base = wr + (int64_t)tile * (TR * rs);
+#pragma unroll
+        for (int k = 0; k < G::NI; ++k) dma16_uniform(base, loff[k], st + (k * NW + wave) * G::RPI * G::ROWB);
+        dma4_uniform(br + (int64_t)tile * TR, boff, st + G::WT + wave * 256);
+    };
     auto issue = [&](int i) {  // stage i of this workgroup (past the last one: a repeat nothing reads)
-        const uint32_t st = lds0 + (i % NS) * G::STAGE;
+        const uint32_t st = __builtin_amdgcn_readfirstlane(lds0 + (i % NS) * G::STAGE);  // (uniform; kept in a scalar register)
         const int ic = min(i, n_loc - 1);
         int tile = ic < nr_loc ? t_lo + ic : nrt + (ic - nr_loc);
         if (i < nr_loc && tile < nfull) {
@@ -227,9 +236,10 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
     // Iteration t issues the loads of stage t+NS-1 into the slot stage t-1 used (retired by the barrier at
     // the end of iteration t-1), computes stage t, then waits until only the loads of the last NS-2 issues
     // are outstanding, i.e. until its own part of stage t+1 has landed; the barrier publishes stage t+1.
-    auto stage = [&](auto kind, int t) {
+    auto stage = [&](auto kind, int t, auto full_ahead) {
         constexpr int KIND = decltype(kind)::value;
-        issue(t + NS - 1);
+        if (decltype(full_ahead)::value) issue_full(t + NS - 1);
+        else issue(t + NS - 1);
         const uint32_t st = lds0 + (t % NS) * G::STAGE;
         u32x4 wa[NKK];  // A operand: this lane's router row, all k-steps
 #pragma unroll
@@ -299,9 +309,12 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
     wait_vm<(NS - 2) * (G::NI + 1)>();
     lds_barrier();
     int t = 0;
-    for (; t < nr_loc && t_lo + t < nfull; ++t) stage(std::integral_constant<int, 0>{}, t);
-    if (t < nr_loc) stage(std::integral_constant<int, 1>{}, t++);  // the part that owns the ragged last router tile
-    for (; t < n_loc; ++t) stage(std::integral_constant<int, 2>{}, t);
+    // while the stage issued NS-1 ahead is itself a full router tile the loop body has no branch for it
+    const int t_ahead = min(nr_loc, nfull - t_lo) - (NS - 1);
+    for (; t < t_ahead; ++t) stage(std::integral_constant<int, 0>{}, t, std::true_type{});
+    for (; t < nr_loc && t_lo + t < nfull; ++t) stage(std::integral_constant<int, 0>{}, t, std::false_type{});
+    if (t < nr_loc) stage(std::integral_constant<int, 1>{}, t++, std::false_type{});  // the part that owns the ragged last router tile
+    for (; t < n_loc; ++t) stage(std::integral_constant<int, 2>{}, t, std::false_type{});
     wait_vm<0>();  // the repeated loads past the last stage must land before the workgroup gives its LDS back
 
     if (nr_loc > 0) {
