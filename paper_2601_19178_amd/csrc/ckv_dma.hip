@@ -295,17 +295,23 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
 
         // (generic in the number NUI of user-slice loads per wavefront and tile, so that the tile loop, which is
         // instantiated per value below, carries no test of it)
-        auto issue_gather = [&](auto nui_c, int tile) {
+        auto issue_gather = [&](auto nui_c, auto both_c, int tile) {
             constexpr int NUI = decltype(nui_c)::value;
+            constexpr bool kBoth = decltype(both_c)::value;  // both sides gather from their pool: the usual case
             const uint32_t st = lds0 + (tile & (NS - 1)) * G::STAGE;
             const lds_u32* islot = (const lds_u32*)(uintptr_t)(idx_lds + (tile & (G::NIS - 1)) * G::IDX);
             int rk[G::NI], rv[G::NI];
 #pragma unroll
             for (int i = 0; i < G::NI; ++i) {
-                const int pos = min(tile * TP + gp[i], n - 1);
                 const int jk = (int)islot[gp[i]], jv = (int)islot[32 + gp[i]];  // read in any case: a select, not a branch
-                rk[i] = ksh ? jk : pos;
-                rv[i] = vsh ? jv : pos;
+                if (kBoth) {
+                    rk[i] = jk;
+                    rv[i] = jv;
+                } else {
+                    const int pos = min(tile * TP + gp[i], n - 1);
+                    rk[i] = ksh ? jk : pos;
+                    rv[i] = vsh ? jv : pos;
+                }
             }
 #pragma unroll
             for (int i = 0; i < G::NI; ++i) {
@@ -356,11 +362,11 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
         // publishes tile t+1 to the workgroup and retires tile t's stage.
         wait_vm<0>();  // the indices of tiles 0..2, requested before the queries
         if (tr && tid == 0) tr[1] = wall_clock64();
-        auto tile_loop = [&](auto nui_c) {
+        auto tile_loop = [&](auto nui_c, auto both_c) {
         constexpr int NUI = decltype(nui_c)::value;
         for (int t = -(NS - 1); t < ntiles; ++t) {
             issue_idx(t + NS + 2);
-            issue_gather(nui_c, t + NS - 1);
+            issue_gather(nui_c, both_c, t + NS - 1);
             if (t >= 0) {
                 const uint32_t st = lds0 + (t & (NS - 1)) * G::STAGE;
                 const int nt = min(n - t * TP, TP);
@@ -461,10 +467,14 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
             lds_barrier();
         }
         };
-        if (nui == 0) tile_loop(std::integral_constant<int, 0>{});
-        else if (nui == 1) tile_loop(std::integral_constant<int, 1>{});
-        else if (G::NUI_MAX >= 2 && nui == 2) tile_loop(std::integral_constant<int, G::NUI_MAX >= 2 ? 2 : 0>{});
-        else if (G::NUI_MAX >= 4) tile_loop(std::integral_constant<int, G::NUI_MAX >= 4 ? 4 : 0>{});
+        auto with_nui = [&](auto nui_c) {
+            if (ksh && vsh) tile_loop(nui_c, std::true_type{});
+            else tile_loop(nui_c, std::false_type{});
+        };
+        if (nui == 0) with_nui(std::integral_constant<int, 0>{});
+        else if (nui == 1) with_nui(std::integral_constant<int, 1>{});
+        else if (G::NUI_MAX >= 2 && nui == 2) with_nui(std::integral_constant<int, G::NUI_MAX >= 2 ? 2 : 0>{});
+        else if (G::NUI_MAX >= 4) with_nui(std::integral_constant<int, G::NUI_MAX >= 4 ? 4 : 0>{});
         // the clamped loads past the last tile must have landed, for every wavefront, before the
         // epilogue reuses the stages (and before the workgroup gives its LDS back)
         wait_vm<0>();
