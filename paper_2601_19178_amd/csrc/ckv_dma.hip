@@ -104,7 +104,11 @@ struct Geo {
     static constexpr int LDS = NS * STAGE + NW * NIS * IDX;
     // wavefronts per SIMD that LDS lets be resident; the register budget is sized for exactly that
     static constexpr int WG_PER_CU = 163840 / LDS;
-    static constexpr int WAVES_PER_EU = WG_PER_CU * NW / 4 < 1 ? 1 : (WG_PER_CU * NW / 4 > 8 ? 8 : WG_PER_CU * NW / 4);
+    // (not below 2 for 64 columns, also where LDS leaves one wavefront per SIMD: with more than 256 registers the compiler puts
+    // the accumulators into AGPRs and copies them back and forth for the weight arithmetic, over 100 moves per tile)
+    // (the 128-column one-wavefront kernel needs more than 256 registers either way and keeps its budget of 512)
+    static constexpr int WAVES_PER_EU =
+        WG_PER_CU * NW / 4 < 2 ? (DA == 64 ? 2 : 1) : (WG_PER_CU * NW / 4 > 8 ? 8 : WG_PER_CU * NW / 4);
     static_assert(NI >= 1, "tile too small for this many wavefronts");
 };
 
