@@ -1,5 +1,5 @@
 // Matrix-core gather-concat-attend kernel with direct global->LDS gathers (bf16 storage, fp32
-// accumulation, d_a = 64 or 128, even d_u <= 8).
+// accumulation, d_a = 64, 128 or 256, d_u even up to 8 (16 at d_a = 256) or 1 or 3).
 //
 // Same mathematics and MFMA operand layouts as the register-staged kernel next to it
 // (S^T = K Q^T, O^T += V^T P^T, one query per lane), but the final K and V rows of a tile are
@@ -83,10 +83,11 @@ __device__ __forceinline__ void lds_barrier() {
 //   V rows (ds_read_b64_tr_b16, four consecutive rows x four consecutive chunks per clock): the row's low
 //   two bits select one of the four 64-byte quarters of a 256-byte row; for 128-byte rows bit 1 of the row
 //   selects one of the two halves.
+//   512-byte rows (d_a = 256) start on the same bank as 256-byte rows and use the same functions.
 template <int DA>
-__device__ __forceinline__ int fk(int p) { return DA == 128 ? (p & 15) : ((p >> 1) & 7); }
+__device__ __forceinline__ int fk(int p) { return DA >= 128 ? (p & 15) : ((p >> 1) & 7); }
 template <int DA>
-__device__ __forceinline__ int fv(int p) { return DA == 128 ? ((p & 3) << 2) : (((p >> 1) & 1) << 2); }
+__device__ __forceinline__ int fv(int p) { return DA >= 128 ? ((p & 3) << 2) : (((p >> 1) & 1) << 2); }
 
 template <int DA, int NW>
 struct Geo {
@@ -95,9 +96,9 @@ struct Geo {
     static constexpr int ROWB = DA * 2;          // bytes per row
     static constexpr int RPI = 64 / CH;          // rows filled by one wavefront instruction
     static constexpr int NI = TP / RPI / NW;     // gather instructions per wavefront, K and V each
-    static constexpr int NUI_MAX = 4 / NW;       // user-slice instructions per wavefront (d_u <= 8)
+    static constexpr int NUI_MAX = (DA == 256 ? 8 : 4) / NW;  // user-slice instructions per wavefront (d_u <= 8, or 16 at 256 columns)
     static constexpr int KV = TP * ROWB;         // bytes of the K (or V) rows of a stage
-    static constexpr int USER = NW * 64 * 4 * NUI_MAX;  // bytes of the user staging of a stage (1 KiB)
+    static constexpr int USER = NW * 64 * 4 * NUI_MAX;  // bytes of the user staging of a stage (1 or 2 KiB)
     static constexpr int STAGE = 2 * KV + USER;
     static constexpr int IDX = 256;              // bytes of one index slot: 32 x I_k, 32 x I_v
     static constexpr int NIS = 4;                // index slots per wavefront (indices run 3 tiles ahead of the gathers)
@@ -110,6 +111,7 @@ struct Geo {
     static constexpr int WAVES_PER_EU =
         WG_PER_CU * NW / 4 < 2 ? (DA == 64 ? 2 : 1) : (WG_PER_CU * NW / 4 > 8 ? 8 : WG_PER_CU * NW / 4);
     static_assert(NI >= 1, "tile too small for this many wavefronts");
+    static_assert(2 * (2 * NI + 1 + NUI_MAX) <= 63, "the wait of the tile loop must fit the 6-bit counter");
 };
 
 // QG = groups of 32 queries owned by one wavefront.  With QG = 2 every K and V operand read
@@ -478,7 +480,8 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
         if (nui == 0) with_nui(std::integral_constant<int, 0>{});
         else if (nui == 1) with_nui(std::integral_constant<int, 1>{});
         else if (G::NUI_MAX >= 2 && nui == 2) with_nui(std::integral_constant<int, G::NUI_MAX >= 2 ? 2 : 0>{});
-        else if (G::NUI_MAX >= 4) with_nui(std::integral_constant<int, G::NUI_MAX >= 4 ? 4 : 0>{});
+        else if (G::NUI_MAX >= 4 && nui == 4) with_nui(std::integral_constant<int, G::NUI_MAX >= 4 ? 4 : 0>{});
+        else if (G::NUI_MAX >= 8) with_nui(std::integral_constant<int, G::NUI_MAX >= 8 ? 8 : 0>{});
         // the clamped loads past the last tile must have landed, for every wavefront, before the
         // epilogue reuses the stages (and before the workgroup gives its LDS back)
         wait_vm<0>();
@@ -588,7 +591,8 @@ int occupancy() {
 
 // (d_a, wavefronts per workgroup, query groups per wavefront)
 #define CKV_DMA_SHAPES(X) \
-    X(64, 1, 1) X(64, 1, 2) X(64, 2, 1) X(64, 2, 2) X(64, 4, 1) X(128, 1, 1) X(128, 1, 2) X(128, 2, 1) X(128, 2, 2) X(128, 4, 1)
+    X(64, 1, 1) X(64, 1, 2) X(64, 2, 1) X(64, 2, 2) X(64, 4, 1) X(128, 1, 1) X(128, 1, 2) X(128, 2, 1) X(128, 2, 2) X(128, 4, 1) \
+    X(256, 2, 1) X(256, 4, 1)
 
 }  // namespace
 
@@ -603,11 +607,12 @@ bool ckv_dma_supported(int d_a, int nw, int qg) {
 // Number of user-slice load instructions per wavefront and tile, or -1 if the shape is not
 // served by this kernel.
 int ckv_dma_nui(int d_a, int nw, int d_u) {
-    if ((d_a != 64 && d_a != 128) || (nw != 1 && nw != 2 && nw != 4)) return -1;
-    if (d_u < 0 || d_u > 8 || ((d_u & 1) && d_u > 3)) return -1;
+    if ((d_a != 64 && d_a != 128 && d_a != 256) || (nw != 1 && nw != 2 && nw != 4)) return -1;
+    if (d_a == 256 && nw == 1) return -1;  // (one wavefront would have more loads in flight than the wait counter holds)
+    if (d_u < 0 || d_u > (d_a == 256 ? 16 : 8) || ((d_u & 1) && d_u > 3)) return -1;
     // lanes that move the user slices of a tile: one per dword, or one per element when d_u is odd
     const int need = ((d_u & 1 ? 64 : 32) * d_u + nw * 64 - 1) / (nw * 64);
-    return need <= 1 ? need : (need <= 2 ? 2 : 4);
+    return need <= 1 ? need : (need <= 2 ? 2 : (need <= 4 ? 4 : 8));
 }
 
 int ckv_dma_occupancy(int d_a, int nw, int qg, int mode) {
@@ -628,7 +633,7 @@ hipError_t ckv_launch_dma(const ckv_cache* c, const ckv_args& a, hipStream_t s) 
     if (d_a == DA && nw == NW && qg == 1)                                                  \
         return c->shape.mode == CKV_SOFTMAX ? launch<DA, NW, 1, CKV_SOFTMAX, true>(c, a, s) \
                                             : launch<DA, NW, 1, CKV_SILU_OVER_N, true>(c, a, s);
-        X(64, 1) X(64, 2) X(64, 4) X(128, 1) X(128, 2) X(128, 4)
+        X(64, 1) X(64, 2) X(64, 4) X(128, 1) X(128, 2) X(128, 4) X(256, 2) X(256, 4)
 #undef X
         return hipErrorInvalidValue;
     }

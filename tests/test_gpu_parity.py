@@ -565,12 +565,35 @@ def test_fp32_many_queries_split_history_sharing_and_large_scores(gpu):
 def test_wide_bf16_heads_many_queries(gpu, mode, d_a, d_u, pool_ld, Nq):
     """Heads of 129 to 256 columns: the 256-column register-staged kernel (one workgroup per compute unit)."""
     w = make(MFMA_LENGTHS, wl.BF16, mode, d_a=d_a, d_u=d_u, H=2, P=700, Nq=Nq, pool_ld=pool_ld)
-    run_and_check(gpu, w, f"wide head d_a={d_a} d_u={d_u} ld={pool_ld} Nq={Nq} mode={mode}", expect_variant="mfma_bf16_d256")
+    run_and_check(gpu, w, f"wide head d_a={d_a} d_u={d_u} ld={pool_ld} Nq={Nq} mode={mode}", expect_variant="mfma_bf16_d256",
+                  impl="staged")
 
 
 def test_wide_bf16_head_split_history(gpu):
     w = make((5000, 70, 2300), wl.BF16, wl.SOFTMAX, d_a=256, d_u=8, H=2, P=5000, Nq=64)
-    run_and_check(gpu, w, "wide head, split history", expect_variant="mfma_bf16_d256")
+    run_and_check(gpu, w, "wide head, split history", expect_variant="mfma_bf16_d256", impl="staged")
+
+
+@pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
+@pytest.mark.parametrize("d_u,Nq", [(1, 128), (2, 64), (3, 40), (4, 128), (6, 200), (10, 128), (10, 64), (16, 33), (8, 3), (0, 16)])
+def test_256_column_heads_in_the_direct_to_lds_kernel(gpu, mode, d_u, Nq):
+    """d_a = 256 with the user widths behind the compression ratios of Table 1 (d_u = 1, 2, 3, 4, 6, 10) and the
+    widest slice the kernel appends (16): rows of 512 bytes, up to eight slice loads per wavefront and tile."""
+    w = make(MFMA_LENGTHS, wl.BF16, mode, d_a=256, d_u=d_u, H=3, P=700, Nq=Nq)
+    run_and_check(gpu, w, f"256 columns d_u={d_u} Nq={Nq} mode={mode}",
+                  expect_variant=f"mfma_dma_bf16_d256_w{2 if Nq <= 64 else 4}")
+
+
+def test_256_column_heads_split_history_one_side_shared_and_plain_cache(gpu):
+    w = make((5000, 70, 2300), wl.BF16, wl.SOFTMAX, d_a=256, d_u=8, H=2, P=5000, Nq=64)
+    run_and_check(gpu, w, "256 columns, split history", expect_variant="mfma_dma_bf16_d256_w2")
+    w = make((9000, 31), wl.BF16, wl.SOFTMAX, d_a=256, d_u=10, H=1, P=3000, Nq=128)
+    run_and_check(gpu, w, "256 columns, split history, d_u=10", expect_variant="mfma_dma_bf16_d256_w4")
+    for share in (wl.SHARE_K, wl.SHARE_V):
+        w = make(MFMA_LENGTHS, wl.BF16, wl.SILU_OVER_N, d_a=256, d_u=4, H=2, P=300, Nq=96, share=share)
+        run_and_check(gpu, w, f"256 columns, share={share}", expect_variant="mfma_dma_bf16_d256_w4")
+    w = make(MFMA_LENGTHS, wl.BF16, wl.SOFTMAX, d_a=256, d_u=256, H=2, P=1, Nq=128)
+    run_and_check(gpu, w, "256 columns, ordinary cache", expect_variant="mfma_dma_bf16_d256_w4")
 
 
 @pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
