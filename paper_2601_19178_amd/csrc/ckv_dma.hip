@@ -123,6 +123,9 @@ __global__ __launch_bounds__(NW * 64)
 __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES_PER_EU))) void ckv_dma_kernel(ckv_args a, int nui) {
     using G = Geo<DA, NW>;
     constexpr int NKK = DA / 16, NDT = DA / 32;
+    constexpr bool kWide = DA > 128;  // operands of a whole tile no longer fit into registers beside the accumulators
+    static_assert(!kWide || QG == 1, "one query group per wavefront at 256 columns");
+    constexpr bool kAccInAgprs = G::WAVES_PER_EU == 1;  // a budget above 256 registers makes the compiler use the AGPR form of the MFMAs
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_u8*)smem;
 
@@ -301,12 +304,10 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
 
         // (generic in the number NUI of user-slice loads per wavefront and tile, so that the tile loop, which is
         // instantiated per value below, carries no test of it)
-        auto issue_gather = [&](auto nui_c, auto both_c, int tile) {
-            constexpr int NUI = decltype(nui_c)::value;
+        // rows of the tile that this wavefront's gather instructions fetch (pool index, or position for a side without pool)
+        auto gather_rows = [&](auto both_c, int tile, int (&rk)[G::NI], int (&rv)[G::NI]) {
             constexpr bool kBoth = decltype(both_c)::value;  // both sides gather from their pool: the usual case
-            const uint32_t st = lds0 + (tile & (NS - 1)) * G::STAGE;
             const lds_u32* islot = (const lds_u32*)(uintptr_t)(idx_lds + (tile & (G::NIS - 1)) * G::IDX);
-            int rk[G::NI], rv[G::NI];
 #pragma unroll
             for (int i = 0; i < G::NI; ++i) {
                 const int jk = (int)islot[gp[i]], jv = (int)islot[32 + gp[i]];  // read in any case: a select, not a branch
@@ -319,22 +320,30 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
                     rv[i] = vsh ? jv : pos;
                 }
             }
-#pragma unroll
-            for (int i = 0; i < G::NI; ++i) {
+        };
+        // load instruction number s of a tile: 2 * NI gathers (K and V alternating), then the user slices
+        auto tile_dma = [&](int tile, int s, const int (&rk)[G::NI], const int (&rv)[G::NI]) {
+            const uint32_t st = lds0 + (tile & (NS - 1)) * G::STAGE;
+            if (s < 2 * G::NI) {
+                const int i = s >> 1;
                 const uint32_t dst = (i * NW + wave) * G::RPI * G::ROWB;
-                dma16(pk + (uint64_t)(uint32_t)rk[i] * krow_bytes + gk_off[i], st + dst);
-                dma16(pv + (uint64_t)(uint32_t)rv[i] * vrow_bytes + gv_off[i], st + G::KV + dst);
+                if (!(s & 1)) dma16(pk + (uint64_t)(uint32_t)rk[i] * krow_bytes + gk_off[i], st + dst);
+                else dma16(pv + (uint64_t)(uint32_t)rv[i] * vrow_bytes + gv_off[i], st + G::KV + dst);
+            } else {
+                const int u = s - 2 * G::NI;
+                const int pos = min(tile * TP + up[u], n - 1);
+                const uint32_t* g;
+                if (uodd) g = (const uint32_t*)(uisv[u] ? a.user_v : a.user_k) + (((hT + pos) * d_u + uoff[u]) >> 1);
+                else g = (uisv[u] ? uv32 : uk32) + (int64_t)pos * hd + uoff[u];
+                dma4(g, st + 2 * G::KV + (wave * G::NUI_MAX + u) * 256);
             }
+        };
+        auto issue_gather = [&](auto nui_c, auto both_c, int tile) {
+            constexpr int NUI = decltype(nui_c)::value;
+            int rk[G::NI], rv[G::NI];
+            gather_rows(both_c, tile, rk, rv);
 #pragma unroll
-            for (int u = 0; u < G::NUI_MAX; ++u) {
-                if (u < NUI) {
-                    const int pos = min(tile * TP + up[u], n - 1);
-                    const uint32_t* g;
-                    if (uodd) g = (const uint32_t*)(uisv[u] ? a.user_v : a.user_k) + (((hT + pos) * d_u + uoff[u]) >> 1);
-                    else g = (uisv[u] ? uv32 : uk32) + (int64_t)pos * hd + uoff[u];
-                    dma4(g, st + 2 * G::KV + (wave * G::NUI_MAX + u) * 256);
-                }
-            }
+            for (int s = 0; s < 2 * G::NI + NUI; ++s) tile_dma(tile, s, rk, rv);
         };
         // the paper's concat: user columns behind the pool columns of the wavefront's own rows
         auto concat = [&](auto nui_c, int tile) {
@@ -391,13 +400,24 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
 #pragma unroll
                     for (int kk = 0; kk < NKK; ++kk)
                         sacc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk], qreg[g][kk], sacc[g], 0, 0, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, NKK, 0);       // all LDS reads ...
-                __builtin_amdgcn_sched_group_barrier(0x008, NKK * QG, 0);  // ... then the MFMAs
+                if (!kWide) {
+                    __builtin_amdgcn_sched_group_barrier(0x100, NKK, 0);       // all LDS reads ...
+                    __builtin_amdgcn_sched_group_barrier(0x008, NKK * QG, 0);  // ... then the MFMAs
+                } else {
+                    // 256 columns: a window of eight operands, refilled four at a time under the MFMAs
+                    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+#pragma unroll
+                    for (int i = 0; i < (NKK - 8) / 4; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+                }
                 // V^T operands of the whole tile: issued now, so that their LDS latency is hidden
                 // behind the MFMAs above and the weight arithmetic below
+                // (256 columns: the first sixteen positions now, the other sixteen under the first half's MFMAs)
                 bf16x8 va[2][NDT];
-#pragma unroll
-                for (int ks = 0; ks < 2; ++ks)
+                auto load_v = [&](int ks) {
 #pragma unroll
                     for (int dt = 0; dt < NDT; ++dt) {
                         const uint32_t ad = st + vrow + (16 * ks) * G::ROWB + (((4 * dt + vc) ^ vx) << 4);
@@ -405,7 +425,10 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
                         const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(uintptr_t)(ad + 8 * G::ROWB));
                         va[ks][dt] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                     }
-                __builtin_amdgcn_sched_group_barrier(0x100, 4 * NDT, 0);
+                };
+                load_v(0);
+                if (!kWide) load_v(1);
+                __builtin_amdgcn_sched_group_barrier(0x100, (kWide ? 2 : 4) * NDT, 0);
                 __builtin_amdgcn_sched_barrier(0);
                 const bool ragged = nt < TP;
 #pragma unroll
@@ -425,9 +448,15 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
                             const float alpha = __builtin_amdgcn_exp2f(m_ref[g] - m_new);
                             lsum[g] *= alpha;
 #pragma unroll
-                            for (int dt = 0; dt < NDT; ++dt)
+                            for (int dt = 0; dt < NDT; ++dt) {
+                                // (accumulators in AGPRs: pinned there on both sides of the multiplication, so that
+                                // their way through VGPRs stays inside this rare branch; otherwise every tile copies
+                                // all of them out in case the branch is taken)
+                                if (kAccInAgprs) asm volatile("" : "+a"(oacc[g][dt]));
 #pragma unroll
                                 for (int r = 0; r < 16; ++r) oacc[g][dt][r] *= alpha;
+                                if (kAccInAgprs) asm volatile("" : "+a"(oacc[g][dt]));
+                            }
                             m_ref[g] = m_new;
                         }
                         float psum = 0.f;
@@ -459,6 +488,10 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
                         }
                     }
                     // O^T += V^T P^T
+                    if (kWide) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        load_v(1);
+                    }
 #pragma unroll
                     for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
