@@ -599,8 +599,8 @@ void choose_variant(ckv_cache* c) {
         {
             // direct-to-LDS kernel: 32 queries per wavefront, up to 4 wavefronts per workgroup (two
             // wavefronts per SIMD overlap better than one wavefront with two query groups)
-            // (256 columns: two wavefronts at least, the second one idle in the matrix phases below 33 queries)
-            int nw = s.Nq <= 32 && dak != 256 ? 1 : (s.Nq <= 64 ? 2 : 4), qg = 1;
+            // (256 columns: always four wavefronts, those without queries only gather)
+            int nw = dak == 256 ? 4 : (s.Nq <= 32 ? 1 : (s.Nq <= 64 ? 2 : 4)), qg = 1;
             if (const char* shp = getenv("CKV_DMA_SHAPE")) sscanf(shp, "%d,%d", &nw, &qg);  // tuning knob "nw,qg"
             // (d_g = 0, ordinary attention over the user arrays: rows are fetched by position, nothing is appended)
             const int nui = d_a == dak && ckv_dma_supported(d_a, nw, qg) && (s.d_g == 0 || qg == 1 || !(s.d_u & 1))

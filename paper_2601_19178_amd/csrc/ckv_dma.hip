@@ -625,7 +625,7 @@ int occupancy() {
 // (d_a, wavefronts per workgroup, query groups per wavefront)
 #define CKV_DMA_SHAPES(X) \
     X(64, 1, 1) X(64, 1, 2) X(64, 2, 1) X(64, 2, 2) X(64, 4, 1) X(128, 1, 1) X(128, 1, 2) X(128, 2, 1) X(128, 2, 2) X(128, 4, 1) \
-    X(256, 2, 1) X(256, 4, 1)
+    X(256, 4, 1)
 
 }  // namespace
 
@@ -641,7 +641,7 @@ bool ckv_dma_supported(int d_a, int nw, int qg) {
 // served by this kernel.
 int ckv_dma_nui(int d_a, int nw, int d_u) {
     if ((d_a != 64 && d_a != 128 && d_a != 256) || (nw != 1 && nw != 2 && nw != 4)) return -1;
-    if (d_a == 256 && nw == 1) return -1;  // (one wavefront would have more loads in flight than the wait counter holds)
+    if (d_a == 256 && nw != 4) return -1;  // (256 columns: four wavefronts only)
     if (d_u < 0 || d_u > (d_a == 256 ? 16 : 8) || ((d_u & 1) && d_u > 3)) return -1;
     // lanes that move the user slices of a tile: one per dword, or one per element when d_u is odd
     const int need = ((d_u & 1 ? 64 : 32) * d_u + nw * 64 - 1) / (nw * 64);
@@ -666,7 +666,7 @@ hipError_t ckv_launch_dma(const ckv_cache* c, const ckv_args& a, hipStream_t s) 
     if (d_a == DA && nw == NW && qg == 1)                                                  \
         return c->shape.mode == CKV_SOFTMAX ? launch<DA, NW, 1, CKV_SOFTMAX, true>(c, a, s) \
                                             : launch<DA, NW, 1, CKV_SILU_OVER_N, true>(c, a, s);
-        X(64, 1) X(64, 2) X(64, 4) X(128, 1) X(128, 2) X(128, 4) X(256, 2) X(256, 4)
+        X(64, 1) X(64, 2) X(64, 4) X(128, 1) X(128, 2) X(128, 4) X(256, 4)
 #undef X
         return hipErrorInvalidValue;
     }

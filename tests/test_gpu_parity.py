@@ -581,12 +581,12 @@ def test_256_column_heads_in_the_direct_to_lds_kernel(gpu, mode, d_u, Nq):
     widest slice the kernel appends (16): rows of 512 bytes, up to eight slice loads per wavefront and tile."""
     w = make(MFMA_LENGTHS, wl.BF16, mode, d_a=256, d_u=d_u, H=3, P=700, Nq=Nq)
     run_and_check(gpu, w, f"256 columns d_u={d_u} Nq={Nq} mode={mode}",
-                  expect_variant=f"mfma_dma_bf16_d256_w{2 if Nq <= 64 else 4}")
+                  expect_variant="mfma_dma_bf16_d256_w4")
 
 
 def test_256_column_heads_split_history_one_side_shared_and_plain_cache(gpu):
     w = make((5000, 70, 2300), wl.BF16, wl.SOFTMAX, d_a=256, d_u=8, H=2, P=5000, Nq=64)
-    run_and_check(gpu, w, "256 columns, split history", expect_variant="mfma_dma_bf16_d256_w2")
+    run_and_check(gpu, w, "256 columns, split history", expect_variant="mfma_dma_bf16_d256_w4")
     w = make((9000, 31), wl.BF16, wl.SOFTMAX, d_a=256, d_u=10, H=1, P=3000, Nq=128)
     run_and_check(gpu, w, "256 columns, split history, d_u=10", expect_variant="mfma_dma_bf16_d256_w4")
     for share in (wl.SHARE_K, wl.SHARE_V):
