@@ -37,6 +37,8 @@ DESCRIBE = {
     "cfg4": "config 4 long ragged: B=128 L~U[2048,8192] H=8 d=120+8 P=65536 Nq=128 softmax bf16",
     "cfg3_plain": "config 3 with an ordinary K/V cache (d_g = 0): the same decode without compression",
     "cfg4_plain": "config 4 with an ordinary K/V cache (d_g = 0): the same decode without compression",
+    "d256_u4": "256-column heads (Table 1's width, CR 0.020): B=128 L~U[2048,8192] H=4 d=252+4 P=32768 Nq=128 softmax bf16",
+    "d256_u10": "256-column heads (Table 1's width, CR 0.043): B=128 L~U[2048,8192] H=4 d=246+10 P=32768 Nq=128 softmax bf16",
     "cfg5": "config 5 large batch: B=8192 L~U[512,2048] H=4 d=62+2 P=1048576 Zipf(1.05) Nq=16 softmax bf16",
 }
 
@@ -216,7 +218,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=100,
                     help="untimed steps; the GPU needs ~50 back-to-back launches to reach its steady clocks")
     ap.add_argument("--workload", default="cfg4", choices=sorted(DESCRIBE))
-    ap.add_argument("--also", default="cfg2_f32,cfg2_bf16,cfg3,cfg3_ck", help="comma list of further workloads ('' for none)")
+    ap.add_argument("--also", default="cfg2_f32,cfg2_bf16,cfg3,cfg3_ck,d256_u4", help="comma list of further workloads ('' for none)")
     ap.add_argument("--prefill", default="prefill_cfg2,prefill_cfg3,prefill_cfg2_f32",
                     help="comma list of prefill workloads reported under 'prefill' (prefill_cfg2, prefill_cfg3, prefill_cfg2_f32; '' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -56,6 +56,12 @@ CONFIGS = {
                        mode=SOFTMAX, dtype=BF16, sigma_pool=128.0 ** -0.5, sigma_user=128.0 ** -0.5, seed=1004),
     "cfg5": dict(B=8192, L=(512, 2048), H=4, d_a=64, d_u=2, P=1048576, idx=("zipf", 1.05), Nq=16,
                  mode=SOFTMAX, dtype=BF16, sigma_pool=1.0 / 8.0, seed=1005),
+    # the head width behind the compression ratios of Table 1 (d = 256; CR 0.020 is d_u = 4, CR 0.043 is d_u = 10),
+    # on config 4's batch of long ragged histories
+    "d256_u4": dict(B=128, L=(2048, 8192), H=4, d_a=256, d_u=4, P=32768, idx="uniform", Nq=128,
+                    mode=SOFTMAX, dtype=BF16, sigma_pool=1.0 / 16.0, seed=1006),
+    "d256_u10": dict(B=128, L=(2048, 8192), H=4, d_a=256, d_u=10, P=32768, idx="uniform", Nq=128,
+                     mode=SOFTMAX, dtype=BF16, sigma_pool=1.0 / 16.0, seed=1006),
 }
 
 

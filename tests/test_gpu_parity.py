@@ -202,6 +202,16 @@ def test_config4_full(gpu):
     run_and_check(gpu, w, "cfg4", users=users, expect_variant="mfma_dma_bf16_d128_w4_g1")
 
 
+@pytest.mark.parametrize("name,Nq", [("d256_u4", 128), ("d256_u10", 128), ("d256_u4", 40)])
+def test_256_column_heads_full(gpu, name, Nq):
+    """Table 1's head width at config 4's batch, in the launch configuration the bench times; 40 queries leave
+    wavefronts without queries that only gather."""
+    w = wl.config(name, Nq=Nq)
+    users = sampled_users(w["B"], 3, 7)
+    users = np.unique(np.concatenate([users, [int(np.argmax(w["lengths"])), int(np.argmin(w["lengths"]))]])).astype(np.int32)
+    run_and_check(gpu, w, f"{name} Nq={Nq}", users=users, expect_variant="mfma_dma_bf16_d256_w4_g1")
+
+
 def test_config5_full(gpu):
     w = wl.config("cfg5")
     run_and_check(gpu, w, "cfg5", users=sampled_users(w["B"], 48, 5), expect_variant="mfma_dma_bf16_d64_w1_g1")
