@@ -334,7 +334,7 @@ int resident_workgroups(const ckv_cache* c) {
     const ckv_shape& s = c->shape;
     const int d_a = s.d_g + s.d_u;
     if (c->family == CKV_K_MFMA) return std::max(1, ckv_mfma_occupancy(d_a <= 64 ? 64 : (d_a <= 128 ? 128 : 256), c->nw, c->tp, s.mode));
-    if (c->family == CKV_K_DMA) return std::max(1, ckv_dma_occupancy(d_a, c->nw, c->qg, s.mode));
+    if (c->family == CKV_K_DMA) return std::max(1, ckv_dma_occupancy(d_a, c->nw, c->qg, s.mode, s.d_g == 0 ? 0 : s.d_u));
     if (c->family == CKV_K_MFMA32) return std::max(1, ckv_mfma32_occupancy(d_a <= 64 ? 64 : (d_a <= 128 ? 128 : 256), s.mode));
     return 8;
 }
@@ -603,7 +603,7 @@ void choose_variant(ckv_cache* c) {
             int nw = dak == 256 ? 4 : (s.Nq <= 32 ? 1 : (s.Nq <= 64 ? 2 : 4)), qg = 1;
             if (const char* shp = getenv("CKV_DMA_SHAPE")) sscanf(shp, "%d,%d", &nw, &qg);  // tuning knob "nw,qg"
             // (d_g = 0, ordinary attention over the user arrays: rows are fetched by position, nothing is appended)
-            const int nui = d_a == dak && ckv_dma_supported(d_a, nw, qg) && (s.d_g == 0 || qg == 1 || !(s.d_u & 1))
+            const int nui = d_a == dak && ckv_dma_supported(d_a, nw, qg) && (s.d_g == 0 || qg == 1 || (!(s.d_u & 1) && (s.d_u <= 8 || dak == 256)))
                                 ? (s.d_g == 0 ? 0 : ckv_dma_nui(d_a, nw, s.d_u)) : -1;
             if (nui >= 0 && !(impl && strcmp(impl, "staged") == 0)) {
                 c->family = CKV_K_DMA;

@@ -1,5 +1,5 @@
 // Matrix-core gather-concat-attend kernel with direct global->LDS gathers (bf16 storage, fp32
-// accumulation, d_a = 64, 128 or 256, d_u even up to 8 (16 at d_a = 256) or 1 or 3).
+// accumulation, d_a = 64, 128 or 256, d_u even up to 16 or 1 or 3).
 //
 // Same mathematics and MFMA operand layouts as the register-staged kernel next to it
 // (S^T = K Q^T, O^T += V^T P^T, one query per lane), but the final K and V rows of a tile are
@@ -89,14 +89,15 @@ __device__ __forceinline__ int fk(int p) { return DA >= 128 ? (p & 15) : ((p >> 
 template <int DA>
 __device__ __forceinline__ int fv(int p) { return DA >= 128 ? ((p & 3) << 2) : (((p >> 1) & 1) << 2); }
 
-template <int DA, int NW>
+// WIDEU: user slices of 10 to 16 columns at 64 or 128 columns (a larger staging area; the 256-column geometry always has it)
+template <int DA, int NW, bool WIDEU = false>
 struct Geo {
     static constexpr int NT = NW * 64;
     static constexpr int CH = DA / 8;            // 16-byte chunks per row
     static constexpr int ROWB = DA * 2;          // bytes per row
     static constexpr int RPI = 64 / CH;          // rows filled by one wavefront instruction
     static constexpr int NI = TP / RPI / NW;     // gather instructions per wavefront, K and V each
-    static constexpr int NUI_MAX = (DA == 256 ? 8 : 4) / NW;  // user-slice instructions per wavefront (d_u <= 8, or 16 at 256 columns)
+    static constexpr int NUI_MAX = (DA == 256 || WIDEU ? 8 : 4) / NW;  // user-slice instructions per wavefront (d_u <= 8, or <= 16)
     static constexpr int KV = TP * ROWB;         // bytes of the K (or V) rows of a stage
     static constexpr int USER = NW * 64 * 4 * NUI_MAX;  // bytes of the user staging of a stage (1 or 2 KiB)
     static constexpr int STAGE = 2 * KV + USER;
@@ -117,11 +118,12 @@ struct Geo {
 // QG = groups of 32 queries owned by one wavefront.  With QG = 2 every K and V operand read
 // from LDS feeds two MFMAs, and the weight arithmetic of one group can run while the matrix
 // core works on the other.
-// UODD: d_u is odd (1 or 3); an instantiation of its own, so that the even case carries none of its code.
-template <int DA, int NW, int QG, int MODE, bool UODD>
+// UK: kind of user slice. 0: d_u even, up to 8 (16 at 256 columns); 1: d_u odd (1 or 3), an instantiation of its own, so
+// that the even case carries none of its code; 2: d_u even, 10 to 16, at 64 or 128 columns (larger staging area).
+template <int DA, int NW, int QG, int MODE, int UK>
 __global__ __launch_bounds__(NW * 64)
-__attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES_PER_EU))) void ckv_dma_kernel(ckv_args a, int nui) {
-    using G = Geo<DA, NW>;
+__attribute__((amdgpu_waves_per_eu(Geo<DA, NW, UK == 2>::WAVES_PER_EU, Geo<DA, NW, UK == 2>::WAVES_PER_EU))) void ckv_dma_kernel(ckv_args a, int nui) {
+    using G = Geo<DA, NW, UK == 2>;
     constexpr int NKK = DA / 16, NDT = DA / 32;
     constexpr bool kWide = DA > 128;  // operands of a whole tile no longer fit into registers beside the accumulators
     static_assert(!kWide || QG == 1, "one query group per wavefront at 256 columns");
@@ -149,7 +151,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
     }
     const int qn = lane & 31, hh = lane >> 5;
     const int d_g = a.d_g, d_u = a.d_u;
-    constexpr bool uodd = UODD;  // user and pool columns then change places at an odd column: no 32-bit shortcuts
+    constexpr bool uodd = UK == 1;  // user and pool columns then change places at an odd column: no 32-bit shortcuts
     // A side that is not shared (only keys or only values gather from a pool) keeps whole d_a-wide rows in
     // its user array: its tile rows are fetched from there, position by position, with the same
     // instructions that fetch pool rows for a shared side, and it has no user slice to append.
@@ -596,29 +598,29 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW>::WAVES_PER_EU, Geo<DA, NW>::WAVES
     }  // items of this workgroup
 }
 
-template <int DA, int NW, int QG, int MODE, bool UODD>
+template <int DA, int NW, int QG, int MODE, int UK>
 hipError_t prepare() {
-    constexpr int lds = Geo<DA, NW>::LDS;
+    constexpr int lds = Geo<DA, NW, UK == 2>::LDS;
     static hipError_t done =
-        hipFuncSetAttribute((const void*)ckv_dma_kernel<DA, NW, QG, MODE, UODD>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        hipFuncSetAttribute((const void*)ckv_dma_kernel<DA, NW, QG, MODE, UK>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     return done;
 }
 
-template <int DA, int NW, int QG, int MODE, bool UODD>
+template <int DA, int NW, int QG, int MODE, int UK>
 hipError_t launch(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
-    hipError_t e = prepare<DA, NW, QG, MODE, UODD>();
+    hipError_t e = prepare<DA, NW, QG, MODE, UK>();
     if (e != hipSuccess) return e;
-    constexpr int lds = Geo<DA, NW>::LDS;
-    hipLaunchKernelGGL((ckv_dma_kernel<DA, NW, QG, MODE, UODD>), dim3(c->n_wg), dim3(NW * 64), lds, s, a, c->nui);
+    constexpr int lds = Geo<DA, NW, UK == 2>::LDS;
+    hipLaunchKernelGGL((ckv_dma_kernel<DA, NW, QG, MODE, UK>), dim3(c->n_wg), dim3(NW * 64), lds, s, a, c->nui);
     return hipGetLastError();
 }
 
-template <int DA, int NW, int QG, int MODE, bool UODD>
+template <int DA, int NW, int QG, int MODE, int UK>
 int occupancy() {
-    if (prepare<DA, NW, QG, MODE, UODD>() != hipSuccess) return 0;
+    if (prepare<DA, NW, QG, MODE, UK>() != hipSuccess) return 0;
     int nb = 0;
-    constexpr int lds = Geo<DA, NW>::LDS;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)ckv_dma_kernel<DA, NW, QG, MODE, UODD>, NW * 64, lds) !=
+    constexpr int lds = Geo<DA, NW, UK == 2>::LDS;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)ckv_dma_kernel<DA, NW, QG, MODE, UK>, NW * 64, lds) !=
         hipSuccess)
         return 0;
     return nb;
@@ -628,6 +630,8 @@ int occupancy() {
 #define CKV_DMA_SHAPES(X) \
     X(64, 1, 1) X(64, 1, 2) X(64, 2, 1) X(64, 2, 2) X(64, 4, 1) X(128, 1, 1) X(128, 1, 2) X(128, 2, 1) X(128, 2, 2) X(128, 4, 1) \
     X(256, 4, 1)
+// (d_a, wavefronts) of the instantiations with one query group that exist for odd and for wide user slices
+#define CKV_DMA_NARROW(X) X(64, 1) X(64, 2) X(64, 4) X(128, 1) X(128, 2) X(128, 4)
 
 }  // namespace
 
@@ -644,17 +648,28 @@ bool ckv_dma_supported(int d_a, int nw, int qg) {
 int ckv_dma_nui(int d_a, int nw, int d_u) {
     if ((d_a != 64 && d_a != 128 && d_a != 256) || (nw != 1 && nw != 2 && nw != 4)) return -1;
     if (d_a == 256 && nw != 4) return -1;  // (256 columns: four wavefronts only)
-    if (d_u < 0 || d_u > (d_a == 256 ? 16 : 8) || ((d_u & 1) && d_u > 3)) return -1;
+    if (d_u < 0 || d_u > 16 || ((d_u & 1) && d_u > 3)) return -1;
     // lanes that move the user slices of a tile: one per dword, or one per element when d_u is odd
     const int need = ((d_u & 1 ? 64 : 32) * d_u + nw * 64 - 1) / (nw * 64);
     return need <= 1 ? need : (need <= 2 ? 2 : (need <= 4 ? 4 : 8));
 }
 
-int ckv_dma_occupancy(int d_a, int nw, int qg, int mode) {
+// (user slices of 10 to 16 columns at 64 or 128 columns: the instantiation with the larger staging area)
+static bool wide_slices(int d_a, int d_u) { return d_a != 256 && !(d_u & 1) && d_u > 8; }
+
+int ckv_dma_occupancy(int d_a, int nw, int qg, int mode, int d_u) {
+    if (wide_slices(d_a, d_u)) {
+#define X(DA, NW)                          \
+    if (d_a == DA && nw == NW && qg == 1)  \
+        return mode == CKV_SOFTMAX ? occupancy<DA, NW, 1, CKV_SOFTMAX, 2>() : occupancy<DA, NW, 1, CKV_SILU_OVER_N, 2>();
+        CKV_DMA_NARROW(X)
+#undef X
+        return 0;
+    }
     // (the instantiation for an odd d_u has the same resources to within a few registers)
 #define X(DA, NW, QG)                          \
     if (d_a == DA && nw == NW && qg == QG)     \
-        return mode == CKV_SOFTMAX ? occupancy<DA, NW, QG, CKV_SOFTMAX, false>() : occupancy<DA, NW, QG, CKV_SILU_OVER_N, false>();
+        return mode == CKV_SOFTMAX ? occupancy<DA, NW, QG, CKV_SOFTMAX, 0>() : occupancy<DA, NW, QG, CKV_SILU_OVER_N, 0>();
     CKV_DMA_SHAPES(X)
 #undef X
     return 0;
@@ -666,16 +681,25 @@ hipError_t ckv_launch_dma(const ckv_cache* c, const ckv_args& a, hipStream_t s) 
     if (a.d_u & 1) {  // one query group per wavefront only
 #define X(DA, NW)                                                                          \
     if (d_a == DA && nw == NW && qg == 1)                                                  \
-        return c->shape.mode == CKV_SOFTMAX ? launch<DA, NW, 1, CKV_SOFTMAX, true>(c, a, s) \
-                                            : launch<DA, NW, 1, CKV_SILU_OVER_N, true>(c, a, s);
-        X(64, 1) X(64, 2) X(64, 4) X(128, 1) X(128, 2) X(128, 4) X(256, 4)
+        return c->shape.mode == CKV_SOFTMAX ? launch<DA, NW, 1, CKV_SOFTMAX, 1>(c, a, s) \
+                                            : launch<DA, NW, 1, CKV_SILU_OVER_N, 1>(c, a, s);
+        CKV_DMA_NARROW(X) X(256, 4)
+#undef X
+        return hipErrorInvalidValue;
+    }
+    if (a.d_g > 0 && wide_slices(d_a, a.d_u)) {  // one query group per wavefront only
+#define X(DA, NW)                                                                       \
+    if (d_a == DA && nw == NW && qg == 1)                                               \
+        return c->shape.mode == CKV_SOFTMAX ? launch<DA, NW, 1, CKV_SOFTMAX, 2>(c, a, s) \
+                                            : launch<DA, NW, 1, CKV_SILU_OVER_N, 2>(c, a, s);
+        CKV_DMA_NARROW(X)
 #undef X
         return hipErrorInvalidValue;
     }
 #define X(DA, NW, QG)                                                                           \
     if (d_a == DA && nw == NW && qg == QG)                                                      \
-        return c->shape.mode == CKV_SOFTMAX ? launch<DA, NW, QG, CKV_SOFTMAX, false>(c, a, s)    \
-                                            : launch<DA, NW, QG, CKV_SILU_OVER_N, false>(c, a, s);
+        return c->shape.mode == CKV_SOFTMAX ? launch<DA, NW, QG, CKV_SOFTMAX, 0>(c, a, s)    \
+                                            : launch<DA, NW, QG, CKV_SILU_OVER_N, 0>(c, a, s);
     CKV_DMA_SHAPES(X)
 #undef X
     return hipErrorInvalidValue;

@@ -120,7 +120,7 @@ bool ckv_mfma_supported(int d_a, int nw, int tp);
 // Direct-to-LDS variant of the mfma kernel.
 hipError_t ckv_launch_dma(const ckv_cache* c, const ckv_args& a, hipStream_t s);
 int ckv_dma_nui(int d_a, int nw, int d_u);  // -1: shape not served
-int ckv_dma_occupancy(int d_a, int nw, int qg, int mode);
+int ckv_dma_occupancy(int d_a, int nw, int qg, int mode, int d_u);
 bool ckv_dma_supported(int d_a, int nw, int qg);
 
 // fp32-storage variant of the register-staged mfma kernel (four wavefronts, 128 queries per block).

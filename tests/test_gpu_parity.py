@@ -139,7 +139,7 @@ MFMA_LENGTHS = (1, 31, 32, 33, 64, 65, 0, 127, 200, 1500, 96, 2)
                                          (128, 2, 16), (128, 4, 64), (64, 6, 128), (128, 0, 32), (64, 8, 8)])
 def test_mfma_ragged(gpu, impl, mode, d_a, d_u, Nq):
     w = make(MFMA_LENGTHS, wl.BF16, mode, d_a=d_a, d_u=d_u, H=2, P=700, Nq=Nq)
-    dma_ok = d_u <= 8 and (d_u % 2 == 0 or d_u <= 3)
+    dma_ok = d_u <= 16 and (d_u % 2 == 0 or d_u <= 3)
     expect = "mfma_dma" if (impl is None and dma_ok) else "mfma_bf16"
     run_and_check(gpu, w, f"mfma ragged d_a={d_a} d_u={d_u} Nq={Nq} mode={mode} impl={impl}", expect_variant=expect, impl=impl)
 
@@ -282,7 +282,7 @@ def test_single_side_sharing_stream(gpu, share, dtype, mode):
 @pytest.mark.parametrize("d_a,d_u,Nq", [(64, 4, 64), (128, 8, 128), (64, 3, 20), (128, 16, 40), (64, 2, 16), (128, 0, 32)])
 def test_single_side_sharing_matrix_core(gpu, impl, share, mode, d_a, d_u, Nq):
     w = make(MFMA_LENGTHS, wl.BF16, mode, d_a=d_a, d_u=d_u, H=2, P=700, Nq=Nq, share=share)
-    dma_ok = d_u <= 8 and (d_u % 2 == 0 or d_u <= 3)
+    dma_ok = d_u <= 16 and (d_u % 2 == 0 or d_u <= 3)
     expect = "mfma_dma" if (impl is None and dma_ok) else "mfma_bf16"
     run_and_check(gpu, w, f"mfma share={share} d_a={d_a} d_u={d_u} Nq={Nq} mode={mode} impl={impl}", expect_variant=expect, impl=impl)
 
@@ -594,6 +594,25 @@ def test_256_column_heads_in_the_direct_to_lds_kernel(gpu, mode, d_u, Nq):
                   expect_variant="mfma_dma_bf16_d256_w4")
 
 
+@pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
+@pytest.mark.parametrize("d_a,d_u,Nq", [(128, 10, 128), (128, 12, 64), (128, 16, 32), (128, 14, 100), (64, 10, 64), (64, 16, 128),
+                                         (64, 12, 16), (128, 16, 3)])
+def test_user_slices_of_ten_to_sixteen_columns_in_the_direct_to_lds_kernel(gpu, mode, d_a, d_u, Nq):
+    """Even d_u from 10 to 16 at 64 and 128 columns: the instantiation with the larger slice staging area, with one,
+    two and four wavefronts (up to eight slice loads per wavefront and tile)."""
+    w = make(MFMA_LENGTHS, wl.BF16, mode, d_a=d_a, d_u=d_u, H=3, P=700, Nq=Nq)
+    nw = 1 if Nq <= 32 else (2 if Nq <= 64 else 4)
+    run_and_check(gpu, w, f"wide slices d_a={d_a} d_u={d_u} Nq={Nq} mode={mode}", expect_variant=f"mfma_dma_bf16_d{d_a}_w{nw}_g1")
+
+
+def test_wide_user_slices_split_history_and_one_side_shared(gpu):
+    w = make((5000, 70, 2300), wl.BF16, wl.SOFTMAX, d_a=128, d_u=12, H=2, P=5000, Nq=64)
+    run_and_check(gpu, w, "wide slices, split history", expect_variant="mfma_dma_bf16_d128_w2")
+    for share in (wl.SHARE_K, wl.SHARE_V):
+        w = make(MFMA_LENGTHS, wl.BF16, wl.SILU_OVER_N, d_a=64, d_u=10, H=2, P=300, Nq=96, share=share)
+        run_and_check(gpu, w, f"wide slices, share={share}", expect_variant="mfma_dma_bf16_d64_w4")
+
+
 def test_256_column_heads_split_history_one_side_shared_and_plain_cache(gpu):
     w = make((5000, 70, 2300), wl.BF16, wl.SOFTMAX, d_a=256, d_u=8, H=2, P=5000, Nq=64)
     run_and_check(gpu, w, "256 columns, split history", expect_variant="mfma_dma_bf16_d256_w4")
@@ -655,7 +674,7 @@ def test_one_very_long_history(gpu, kind):
         w = make((n,), wl.F32, wl.SILU_OVER_N, d_a=64, d_u=4, H=1, P=20000, Nq=32)
         expect = "mfma_f32"
     elif kind == "staged":
-        w = make((n,), wl.BF16, wl.SOFTMAX, d_a=64, d_u=16, H=1, P=20000, Nq=32)
+        w = make((n,), wl.BF16, wl.SOFTMAX, d_a=64, d_u=24, H=1, P=20000, Nq=32)
         expect = "mfma_bf16"
     else:
         w = make((n, 3), wl.F32, wl.SOFTMAX, d_a=64, d_u=8, H=2, P=20000, Nq=2)
