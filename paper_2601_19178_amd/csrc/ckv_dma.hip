@@ -1,5 +1,5 @@
 // Matrix-core gather-concat-attend kernel with direct global->LDS gathers (bf16 storage, fp32
-// accumulation, d_a = 64, 128 or 256, d_u even up to 16 or 1 or 3).
+// accumulation, d_a = 64, 128 or 256, d_u even up to 16 or odd up to 7).
 //
 // Same mathematics and MFMA operand layouts as the register-staged kernel next to it
 // (S^T = K Q^T, O^T += V^T P^T, one query per lane), but the final K and V rows of a tile are
@@ -118,12 +118,14 @@ struct Geo {
 // QG = groups of 32 queries owned by one wavefront.  With QG = 2 every K and V operand read
 // from LDS feeds two MFMAs, and the weight arithmetic of one group can run while the matrix
 // core works on the other.
-// UK: kind of user slice. 0: d_u even, up to 8 (16 at 256 columns); 1: d_u odd (1 or 3), an instantiation of its own, so
-// that the even case carries none of its code; 2: d_u even, 10 to 16, at 64 or 128 columns (larger staging area).
+// UK: kind of user slice. 0: d_u even, up to 8 (16 at 256 columns); 1: d_u odd, 1 or 3 (up to 7 at 256 columns), an
+// instantiation of its own, so that the even case carries none of its code; 2: d_u even, 10 to 16, at 64 or 128 columns;
+// 3: d_u odd, 5 or 7, at 64 or 128 columns.  2 and 3 have the larger staging area (an odd slice takes a lane per element);
+// with it a 64-column kernel loses one of its four resident workgroups, which is why 1 and 3 are apart.
 template <int DA, int NW, int QG, int MODE, int UK>
 __global__ __launch_bounds__(NW * 64)
-__attribute__((amdgpu_waves_per_eu(Geo<DA, NW, UK == 2>::WAVES_PER_EU, Geo<DA, NW, UK == 2>::WAVES_PER_EU))) void ckv_dma_kernel(ckv_args a, int nui) {
-    using G = Geo<DA, NW, UK == 2>;
+__attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU))) void ckv_dma_kernel(ckv_args a, int nui) {
+    using G = Geo<DA, NW, (UK >= 2)>;
     constexpr int NKK = DA / 16, NDT = DA / 32;
     constexpr bool kWide = DA > 128;  // operands of a whole tile no longer fit into registers beside the accumulators
     static_assert(!kWide || QG == 1, "one query group per wavefront at 256 columns");
@@ -151,7 +153,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, UK == 2>::WAVES_PER_EU, Geo<DA, N
     }
     const int qn = lane & 31, hh = lane >> 5;
     const int d_g = a.d_g, d_u = a.d_u;
-    constexpr bool uodd = UK == 1;  // user and pool columns then change places at an odd column: no 32-bit shortcuts
+    constexpr bool uodd = UK == 1 || UK == 3;  // user and pool columns then change places at an odd column: no 32-bit shortcuts
     // A side that is not shared (only keys or only values gather from a pool) keeps whole d_a-wide rows in
     // its user array: its tile rows are fetched from there, position by position, with the same
     // instructions that fetch pool rows for a shared side, and it has no user slice to append.
@@ -275,7 +277,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, UK == 2>::WAVES_PER_EU, Geo<DA, N
         //      row tails (the concat) without depending on any other wavefront.  Dword jj of the
         //      wavefront's block is ((kv * ROWS_W + o) * hd + off): kv = K or V, o = ordinal of the
         //      own row, off = dword inside the d_u-wide slice (hd = d_u / 2 dwords).
-        //      An odd d_u (1 or 3) cannot be moved in whole dwords: a lane then stands for one element, fetches
+        //      An odd d_u (1 to 7) cannot be moved in whole dwords: a lane then stands for one element, fetches
         //      the aligned dword that holds it and appends its half with a 16-bit LDS write.
         constexpr int ROWS_W = TP / NW;
         const int hd = d_u > 0 ? (uodd ? d_u : d_u >> 1) : 1;  // lanes per slice
@@ -600,7 +602,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, UK == 2>::WAVES_PER_EU, Geo<DA, N
 
 template <int DA, int NW, int QG, int MODE, int UK>
 hipError_t prepare() {
-    constexpr int lds = Geo<DA, NW, UK == 2>::LDS;
+    constexpr int lds = Geo<DA, NW, (UK >= 2)>::LDS;
     static hipError_t done =
         hipFuncSetAttribute((const void*)ckv_dma_kernel<DA, NW, QG, MODE, UK>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     return done;
@@ -610,7 +612,7 @@ template <int DA, int NW, int QG, int MODE, int UK>
 hipError_t launch(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
     hipError_t e = prepare<DA, NW, QG, MODE, UK>();
     if (e != hipSuccess) return e;
-    constexpr int lds = Geo<DA, NW, UK == 2>::LDS;
+    constexpr int lds = Geo<DA, NW, (UK >= 2)>::LDS;
     hipLaunchKernelGGL((ckv_dma_kernel<DA, NW, QG, MODE, UK>), dim3(c->n_wg), dim3(NW * 64), lds, s, a, c->nui);
     return hipGetLastError();
 }
@@ -619,7 +621,7 @@ template <int DA, int NW, int QG, int MODE, int UK>
 int occupancy() {
     if (prepare<DA, NW, QG, MODE, UK>() != hipSuccess) return 0;
     int nb = 0;
-    constexpr int lds = Geo<DA, NW, UK == 2>::LDS;
+    constexpr int lds = Geo<DA, NW, (UK >= 2)>::LDS;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)ckv_dma_kernel<DA, NW, QG, MODE, UK>, NW * 64, lds) !=
         hipSuccess)
         return 0;
@@ -648,16 +650,32 @@ bool ckv_dma_supported(int d_a, int nw, int qg) {
 int ckv_dma_nui(int d_a, int nw, int d_u) {
     if ((d_a != 64 && d_a != 128 && d_a != 256) || (nw != 1 && nw != 2 && nw != 4)) return -1;
     if (d_a == 256 && nw != 4) return -1;  // (256 columns: four wavefronts only)
-    if (d_u < 0 || d_u > 16 || ((d_u & 1) && d_u > 3)) return -1;
+    if (d_u < 0 || d_u > 16 || ((d_u & 1) && d_u > 7)) return -1;
     // lanes that move the user slices of a tile: one per dword, or one per element when d_u is odd
     const int need = ((d_u & 1 ? 64 : 32) * d_u + nw * 64 - 1) / (nw * 64);
     return need <= 1 ? need : (need <= 2 ? 2 : (need <= 4 ? 4 : 8));
 }
 
-// (user slices of 10 to 16 columns at 64 or 128 columns: the instantiation with the larger staging area)
-static bool wide_slices(int d_a, int d_u) { return d_a != 256 && !(d_u & 1) && d_u > 8; }
+// (user slices of 10 to 16 columns, or of 5 or 7, at 64 or 128 columns: the instantiations with the larger staging area)
+static bool wide_slices(int d_a, int d_u) { return d_a != 256 && (d_u & 1 ? d_u > 3 : d_u > 8); }
 
 int ckv_dma_occupancy(int d_a, int nw, int qg, int mode, int d_u) {
+    if ((d_u & 1) && !wide_slices(d_a, d_u)) {
+#define X(DA, NW)                          \
+    if (d_a == DA && nw == NW && qg == 1)  \
+        return mode == CKV_SOFTMAX ? occupancy<DA, NW, 1, CKV_SOFTMAX, 1>() : occupancy<DA, NW, 1, CKV_SILU_OVER_N, 1>();
+        CKV_DMA_NARROW(X) X(256, 4)
+#undef X
+        return 0;
+    }
+    if (d_u & 1) {
+#define X(DA, NW)                          \
+    if (d_a == DA && nw == NW && qg == 1)  \
+        return mode == CKV_SOFTMAX ? occupancy<DA, NW, 1, CKV_SOFTMAX, 3>() : occupancy<DA, NW, 1, CKV_SILU_OVER_N, 3>();
+        CKV_DMA_NARROW(X)
+#undef X
+        return 0;
+    }
     if (wide_slices(d_a, d_u)) {
 #define X(DA, NW)                          \
     if (d_a == DA && nw == NW && qg == 1)  \
@@ -666,7 +684,6 @@ int ckv_dma_occupancy(int d_a, int nw, int qg, int mode, int d_u) {
 #undef X
         return 0;
     }
-    // (the instantiation for an odd d_u has the same resources to within a few registers)
 #define X(DA, NW, QG)                          \
     if (d_a == DA && nw == NW && qg == QG)     \
         return mode == CKV_SOFTMAX ? occupancy<DA, NW, QG, CKV_SOFTMAX, 0>() : occupancy<DA, NW, QG, CKV_SILU_OVER_N, 0>();
@@ -678,6 +695,15 @@ int ckv_dma_occupancy(int d_a, int nw, int qg, int mode, int d_u) {
 hipError_t ckv_launch_dma(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
     if (c->n_items == 0) return hipSuccess;
     const int d_a = a.d_a, nw = c->nw, qg = c->qg;
+    if ((a.d_u & 1) && wide_slices(d_a, a.d_u)) {  // one query group per wavefront only
+#define X(DA, NW)                                                                       \
+    if (d_a == DA && nw == NW && qg == 1)                                               \
+        return c->shape.mode == CKV_SOFTMAX ? launch<DA, NW, 1, CKV_SOFTMAX, 3>(c, a, s) \
+                                            : launch<DA, NW, 1, CKV_SILU_OVER_N, 3>(c, a, s);
+        CKV_DMA_NARROW(X)
+#undef X
+        return hipErrorInvalidValue;
+    }
     if (a.d_u & 1) {  // one query group per wavefront only
 #define X(DA, NW)                                                                          \
     if (d_a == DA && nw == NW && qg == 1)                                                  \

@@ -139,7 +139,7 @@ MFMA_LENGTHS = (1, 31, 32, 33, 64, 65, 0, 127, 200, 1500, 96, 2)
                                          (128, 2, 16), (128, 4, 64), (64, 6, 128), (128, 0, 32), (64, 8, 8)])
 def test_mfma_ragged(gpu, impl, mode, d_a, d_u, Nq):
     w = make(MFMA_LENGTHS, wl.BF16, mode, d_a=d_a, d_u=d_u, H=2, P=700, Nq=Nq)
-    dma_ok = d_u <= 16 and (d_u % 2 == 0 or d_u <= 3)
+    dma_ok = d_u <= 16 and (d_u % 2 == 0 or d_u <= 7)
     expect = "mfma_dma" if (impl is None and dma_ok) else "mfma_bf16"
     run_and_check(gpu, w, f"mfma ragged d_a={d_a} d_u={d_u} Nq={Nq} mode={mode} impl={impl}", expect_variant=expect, impl=impl)
 
@@ -282,7 +282,7 @@ def test_single_side_sharing_stream(gpu, share, dtype, mode):
 @pytest.mark.parametrize("d_a,d_u,Nq", [(64, 4, 64), (128, 8, 128), (64, 3, 20), (128, 16, 40), (64, 2, 16), (128, 0, 32)])
 def test_single_side_sharing_matrix_core(gpu, impl, share, mode, d_a, d_u, Nq):
     w = make(MFMA_LENGTHS, wl.BF16, mode, d_a=d_a, d_u=d_u, H=2, P=700, Nq=Nq, share=share)
-    dma_ok = d_u <= 16 and (d_u % 2 == 0 or d_u <= 3)
+    dma_ok = d_u <= 16 and (d_u % 2 == 0 or d_u <= 7)
     expect = "mfma_dma" if (impl is None and dma_ok) else "mfma_bf16"
     run_and_check(gpu, w, f"mfma share={share} d_a={d_a} d_u={d_u} Nq={Nq} mode={mode} impl={impl}", expect_variant=expect, impl=impl)
 
@@ -503,8 +503,8 @@ def test_seeded_random_shapes(gpu, block):
         rng = np.random.default_rng(1000 * block + case)
         matrix = rng.random() < 0.6
         if matrix:
-            dtype, d_a = wl.BF16, int(rng.choice([64, 128]))
-            d_u = int(rng.choice([0, 2, 4, 6, 8, 3, 16, 24]))
+            dtype, d_a = wl.BF16, int(rng.choice([64, 128, 256]))
+            d_u = int(rng.choice([0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 12, 14, 16, 24]))
             Nq = int(rng.integers(8, 300))
         else:
             dtype = int(rng.choice([wl.F32, wl.BF16]))
@@ -635,7 +635,7 @@ def test_wide_fp32_heads_many_queries(gpu, mode, d_a, d_u, pool_ld, Nq):
 @pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
 @pytest.mark.parametrize("dtype,d_a,d_u,Nq,expect", [(wl.BF16, 64, 8, 3, "mfma_dma_bf16_d64_w1"), (wl.BF16, 128, 4, 5, "mfma_dma_bf16_d128_w1"),
                                                       (wl.BF16, 64, 2, 7, "mfma_dma_bf16_d64_w1"), (wl.BF16, 64, 8, 2, "stream"),
-                                                      (wl.BF16, 64, 5, 7, "stream"), (wl.BF16, 64, 1, 4, "mfma_dma_bf16_d64_w1"), (wl.F32, 64, 8, 6, "mfma_f32_d64"),
+                                                      (wl.BF16, 64, 9, 7, "stream"), (wl.BF16, 64, 1, 4, "mfma_dma_bf16_d64_w1"), (wl.F32, 64, 8, 6, "mfma_f32_d64"),
                                                       (wl.F32, 128, 8, 5, "stream"), (wl.F32, 128, 8, 7, "mfma_f32_d128")])
 def test_few_queries_cross_over_to_the_matrix_core_kernels(gpu, mode, dtype, d_a, d_u, Nq, expect):
     """The streaming kernel's time grows with the number of queries, the matrix-core kernels' does not: from three
@@ -645,7 +645,8 @@ def test_few_queries_cross_over_to_the_matrix_core_kernels(gpu, mode, dtype, d_a
 
 
 @pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
-@pytest.mark.parametrize("d_a,d_u,Nq", [(64, 1, 16), (64, 1, 64), (64, 1, 128), (128, 1, 128), (128, 3, 32), (64, 3, 64), (128, 3, 100), (128, 1, 40)])
+@pytest.mark.parametrize("d_a,d_u,Nq", [(64, 1, 16), (64, 1, 64), (64, 1, 128), (128, 1, 128), (128, 3, 32), (64, 3, 64), (128, 3, 100), (128, 1, 40),
+                                         (128, 5, 128), (64, 7, 64), (128, 7, 20), (64, 5, 100), (256, 5, 64), (256, 7, 128)])
 def test_odd_user_width_in_the_direct_to_lds_kernel(gpu, mode, d_a, d_u, Nq):
     """d_u of 1 (the paper's smallest cache, CR = 2 / d_a) and 3: the slices cannot be moved as whole dwords; with an
     odd number of positions before a head (T is odd here) its slices start on odd elements too."""
