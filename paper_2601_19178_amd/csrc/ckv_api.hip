@@ -429,8 +429,9 @@ double assign_static(const ckv_cache* c, const std::vector<Unit>& units, int64_t
     // Giving them proportionally more positions makes all workgroups of a CU finish together.
     const int wg_per_cu = std::max<int>(1, (int)(slots / std::max(1, cus)));
     std::vector<double> speed((size_t)slots, 1.0);
+    // (the first 4 / nw workgroups of a CU each find an empty SIMD per wavefront)
     if (wg_per_cu * c->nw > 4)
-        for (int64_t i = slots / wg_per_cu; i < slots; ++i) speed[(size_t)i] = slow_speed;
+        for (int64_t i = (slots / wg_per_cu) * std::max(1, 4 / c->nw); i < slots; ++i) speed[(size_t)i] = slow_speed;
     auto time_of = [&](int w) { return (double)load[(size_t)w] / speed[(size_t)w]; };
     std::vector<int> pieces_of_unit(units.size(), 0);
     double worst = 0;
@@ -530,7 +531,10 @@ void build_work_static(ckv_cache* c, const int32_t* lengths, const std::vector<i
             }
     const int64_t overhead = 192;  // per-item fill, drain and epilogue, in positions
     const double part_positions = (double)c->QB * (d_a + 2) * 8.0 / (2.0 * d_a * 2.0 + 8.0);
-    double slow_speed = 0.75;  // speed of a workgroup that shares its SIMDs with an older one (see assign_static)
+    // speed of a workgroup that shares its SIMDs with an older one (see assign_static); measured best: 0.75 with four
+    // wavefronts per workgroup (config 4: 0.465 ms against 0.482 ms at 1.0), no difference with two (config 3), 1.0 with one
+    // (config 5: 0.834 ms against 0.867 ms at 0.75)
+    double slow_speed = c->nw == 1 ? 1.0 : 0.75;
     if (const char* e = getenv("CKV_DMA_SLOW_SPEED")) slow_speed = atof(e);  // tuning knob
     std::vector<std::vector<Piece>> best;
     double best_cost = -1;

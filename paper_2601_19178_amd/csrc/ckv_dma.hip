@@ -14,7 +14,7 @@
 //     (global_load_lds_dword) into small staging areas; the "concat" of the paper
 //     (eq. "eq: K") is an LDS->LDS copy of the user columns into the tail of each row.
 // Tiles are 32 positions; a ring of 4 stages keeps two to three tiles of gathers in flight
-// per workgroup while one tile is computed.  The loads are issued from inline asm and
+// per workgroup while one tile is computed (2 stages, one tile in flight, for workgroups of one wavefront).  The loads are issued from inline asm and
 // waited for with explicit s_waitcnt vmcnt(N): every wavefront issues the same number of
 // loads per iteration (positions past the end of the history are clamped to the last one),
 // so N is a constant.
@@ -42,7 +42,6 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kLazy = 8.f;
 constexpr int TP = 32;  // positions per tile
-constexpr int NS = 4;   // stages in the ring
 
 __device__ __forceinline__ float other_half(float x) {
     auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
@@ -93,6 +92,10 @@ __device__ __forceinline__ int fv(int p) { return DA >= 128 ? ((p & 3) << 2) : (
 template <int DA, int NW, bool WIDEU = false>
 struct Geo {
     static constexpr int NT = NW * 64;
+    // stages in the ring (a power of two).  Workgroups of one wavefront: two stages, so that LDS leaves room for twice
+    // the workgroups on a CU (64 columns: eight, two wavefronts per SIMD; 128 columns: four, one on every SIMD instead
+    // of on every other); measured faster than the deeper ring by 7.5 % (config 5) and 5.8 % (config 4 with 32 queries)
+    static constexpr int NS = (DA <= 128 && NW == 1 && !WIDEU) ? 2 : 4;
     static constexpr int CH = DA / 8;            // 16-byte chunks per row
     static constexpr int ROWB = DA * 2;          // bytes per row
     static constexpr int RPI = 64 / CH;          // rows filled by one wavefront instruction
@@ -112,7 +115,7 @@ struct Geo {
     static constexpr int WAVES_PER_EU =
         WG_PER_CU * NW / 4 < 2 ? (DA == 64 ? 2 : 1) : (WG_PER_CU * NW / 4 > 8 ? 8 : WG_PER_CU * NW / 4);
     static_assert(NI >= 1, "tile too small for this many wavefronts");
-    static_assert(2 * (2 * NI + 1 + NUI_MAX) <= 63, "the wait of the tile loop must fit the 6-bit counter");
+    static_assert((NS - 2) * (2 * NI + 1 + NUI_MAX) <= 63, "the wait of the tile loop must fit the 6-bit counter");
 };
 
 // QG = groups of 32 queries owned by one wavefront.  With QG = 2 every K and V operand read
@@ -176,7 +179,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
 
     // ---- the indices of the first three tiles are requested before the queries, so that the two round
     //      trips overlap (the index slots are private to the wavefront and apart from the query staging)
-    const uint32_t idx_lds = lds0 + NS * G::STAGE + wave * G::NIS * G::IDX;
+    const uint32_t idx_lds = lds0 + G::NS * G::STAGE + wave * G::NIS * G::IDX;
     // (with no pool at all, d_g = 0, there may be no index buffer: the load still has to be issued, because the
     // waits below count instructions, so it reads the work list instead and its value is never used)
     // (base and clamp are chosen once per item: a select inside the tile loop cost config 4 over 1 %)
@@ -327,7 +330,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
         };
         // load instruction number s of a tile: 2 * NI gathers (K and V alternating), then the user slices
         auto tile_dma = [&](int tile, int s, const int (&rk)[G::NI], const int (&rv)[G::NI]) {
-            const uint32_t st = lds0 + (tile & (NS - 1)) * G::STAGE;
+            const uint32_t st = lds0 + (tile & (G::NS - 1)) * G::STAGE;
             if (s < 2 * G::NI) {
                 const int i = s >> 1;
                 const uint32_t dst = (i * NW + wave) * G::RPI * G::ROWB;
@@ -345,7 +348,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
         // the paper's concat: user columns behind the pool columns of the wavefront's own rows
         auto concat = [&](auto nui_c, int tile) {
             constexpr int NUI = decltype(nui_c)::value;
-            const uint32_t st = lds0 + (tile & (NS - 1)) * G::STAGE;
+            const uint32_t st = lds0 + (tile & (G::NS - 1)) * G::STAGE;
             uint32_t x[G::NUI_MAX];
 #pragma unroll
             for (int u = 0; u < G::NUI_MAX; ++u)
@@ -382,6 +385,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
         constexpr bool kAhead = !kWide;
         int rk[G::NI], rv[G::NI];
         if (kAhead) gather_rows(both_c, 0, rk, rv);
+        constexpr int NS = G::NS;
         for (int t = -(NS - 1); t < ntiles; ++t) {
             issue_idx(t + NS + 2);
             if (!kAhead) gather_rows(both_c, t + NS - 1, rk, rv);
@@ -506,7 +510,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
             }
             // own gathers of tile t+1 have landed once only the loads of this and the previous
             // iteration are outstanding
-            wait_vm<2 * (2 * G::NI + 1 + NUI)>();
+            wait_vm<(NS - 2) * (2 * G::NI + 1 + NUI)>();
             if (NUI > 0 && t + 1 >= 0 && t + 1 < ntiles) concat(nui_c, t + 1);
             if (kAhead) gather_rows(both_c, t + NS, rk, rv);  // (the indices of tile t+4 were requested two iterations ago: they have landed)
             lds_barrier();
@@ -568,7 +572,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
         // to memory every store would touch 64 cache lines), then out as whole rows, 16 bytes per lane
         float* ws = a.partial + (int64_t)it.part * a.QB * (DA + 2);
         constexpr int FS = DA * 4 + 16;  // bytes per staged row
-        static_assert(NW * QG * 32 * FS <= NS * G::STAGE, "the staged accumulators must fit in the retired stages");
+        static_assert(NW * QG * 32 * FS <= G::NS * G::STAGE, "the staged accumulators must fit in the retired stages");
         const uint32_t flds = lds0 + wave * (QG * 32 * FS);
 #pragma unroll
         for (int g = 0; g < QG; ++g) {
