@@ -14,10 +14,10 @@
 //     (global_load_lds_dword) into small staging areas; the "concat" of the paper
 //     (eq. "eq: K") is an LDS->LDS copy of the user columns into the tail of each row.
 // Tiles are 32 positions; a ring of 4 stages keeps two to three tiles of gathers in flight
-// per workgroup while one tile is computed (2 stages, one tile in flight, for workgroups of one wavefront).  The loads are issued from inline asm and
-// waited for with explicit s_waitcnt vmcnt(N): every wavefront issues the same number of
-// loads per iteration (positions past the end of the history are clamped to the last one),
-// so N is a constant.
+// per workgroup while one tile is computed (2 stages, one tile in flight, for workgroups of
+// one wavefront).  The loads are issued from inline asm and waited for with explicit
+// s_waitcnt vmcnt(N): every wavefront issues the same number of loads per iteration
+// (positions past the end of the history are clamped to the last one), so N is a constant.
 #include <cstdlib>
 
 #include <type_traits>
@@ -368,13 +368,15 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
                 if (u < NUI && uok[u]) *(lds_u32*)(uintptr_t)(st + cdst[u]) = x[u];
         };
 
-        // Order of the asynchronous loads of one wavefront: iteration t issues idx(t+6), then the
-        // gathers of tile t+3 (whose rows were read from idx(t+3) in LDS behind the previous iteration's wait).  The wait at the end of iteration t
-        // lets the last two iterations' loads stay outstanding, so it completes the wavefront's
-        // gathers of tile t+1 and, being older, idx(t+4): three tiles of gathers are in flight
-        // while one is computed, and the indices a gather needs landed at least one wait earlier.
-        // After its wait the wavefront concatenates its own rows of tile t+1; the barrier then
-        // publishes tile t+1 to the workgroup and retires tile t's stage.
+        // Order of the asynchronous loads of one wavefront, for NS stages (written out for NS = 4): iteration t
+        // issues idx(t+NS+2) = idx(t+6), then the gathers of tile t+NS-1 = t+3 (whose rows were read from idx(t+3)
+        // in LDS behind the previous iteration's wait).  The wait at the end of iteration t lets the loads of the
+        // last NS-2 = two iterations stay outstanding, so it completes the wavefront's gathers of tile t+1 and,
+        // being older, idx(t+4): NS-1 = three tiles of gathers are in flight while one is computed, and the
+        // indices a gather needs landed at least one wait earlier.  After its wait the wavefront concatenates
+        // its own rows of tile t+1; the barrier then publishes tile t+1 to the workgroup and retires tile t's
+        // stage.  (More loads can be outstanding than the 6-bit counter holds, e.g. 75 with eight slice loads
+        // at one wavefront and four stages: the hardware then holds back the issue, the waits stay exact.)
         wait_vm<0>();  // the indices of tiles 0..2, requested before the queries
         if (tr && tid == 0) tr[1] = wall_clock64();
         auto tile_loop = [&](auto nui_c, auto both_c) {
