@@ -95,7 +95,7 @@ struct Geo {
     // stages in the ring (a power of two).  Workgroups of one wavefront: two stages, so that LDS leaves room for twice
     // the workgroups on a CU (64 columns: eight, two wavefronts per SIMD; 128 columns: four, one on every SIMD instead
     // of on every other); measured faster than the deeper ring by 7.5 % (config 5) and 5.8 % (config 4 with 32 queries)
-    static constexpr int NS = (DA <= 128 && NW == 1 && !WIDEU) ? 2 : 4;
+    static constexpr int NS = (DA <= 128 && NW == 1) ? 2 : 4;
     static constexpr int CH = DA / 8;            // 16-byte chunks per row
     static constexpr int ROWB = DA * 2;          // bytes per row
     static constexpr int RPI = 64 / CH;          // rows filled by one wavefront instruction
@@ -115,6 +115,7 @@ struct Geo {
     static constexpr int WAVES_PER_EU =
         WG_PER_CU * NW / 4 < 2 ? (DA == 64 ? 2 : 1) : (WG_PER_CU * NW / 4 > 8 ? 8 : WG_PER_CU * NW / 4);
     static_assert(NI >= 1, "tile too small for this many wavefronts");
+    static_assert((NS - 1) * (2 * NI + 1 + NUI_MAX) <= 63, "no more loads outstanding than the 6-bit counter holds");
     static_assert((NS - 2) * (2 * NI + 1 + NUI_MAX) <= 63, "the wait of the tile loop must fit the 6-bit counter");
 };
 
@@ -375,8 +376,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
         // being older, idx(t+4): NS-1 = three tiles of gathers are in flight while one is computed, and the
         // indices a gather needs landed at least one wait earlier.  After its wait the wavefront concatenates
         // its own rows of tile t+1; the barrier then publishes tile t+1 to the workgroup and retires tile t's
-        // stage.  (More loads can be outstanding than the 6-bit counter holds, e.g. 75 with eight slice loads
-        // at one wavefront and four stages: the hardware then holds back the issue, the waits stay exact.)
+        // stage.  (At most NS-1 iterations' loads are ever outstanding, which the 6-bit counter holds.)
         wait_vm<0>();  // the indices of tiles 0..2, requested before the queries
         if (tr && tid == 0) tr[1] = wall_clock64();
         auto tile_loop = [&](auto nui_c, auto both_c) {
