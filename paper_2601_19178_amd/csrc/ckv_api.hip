@@ -605,6 +605,11 @@ void choose_variant(ckv_cache* c) {
             // wavefronts per SIMD overlap better than one wavefront with two query groups)
             // (256 columns: always four wavefronts, those without queries only gather)
             int nw = dak == 256 ? 4 : (s.Nq <= 32 ? 1 : (s.Nq <= 64 ? 2 : 4)), qg = 1;
+            // (64 columns, 33 to 64 queries: one wavefront with two query groups and the two-stage ring, eight workgroups
+            // per CU, measured faster than two wavefronts with four stages: config 3 77.8 -> 75.4 us, a config-5-like batch
+            // with 64 queries 349 -> 309 us; at 128 columns it is the other way round, 380 against 575 us, and so it is
+            // for an ordinary cache, d_g = 0, whose rows all stream from HBM: 113 against 128 us)
+            if (dak == 64 && s.Nq > 32 && s.Nq <= 64 && s.d_g > 0 && !(s.d_u & 1) && s.d_u <= 8) nw = 1, qg = 2;
             if (const char* shp = getenv("CKV_DMA_SHAPE")) sscanf(shp, "%d,%d", &nw, &qg);  // tuning knob "nw,qg"
             // (d_g = 0, ordinary attention over the user arrays: rows are fetched by position, nothing is appended)
             const int nui = d_a == dak && ckv_dma_supported(d_a, nw, qg) && (s.d_g == 0 || qg == 1 || (!(s.d_u & 1) && (s.d_u <= 8 || dak == 256)))

@@ -187,12 +187,12 @@ def sampled_users(B, k, seed):
 
 def test_config3_full(gpu):
     w = wl.config("cfg3")
-    run_and_check(gpu, w, "cfg3", users=sampled_users(w["B"], 24, 3), expect_variant="mfma_dma_bf16_d64_w2_g1")
+    run_and_check(gpu, w, "cfg3", users=sampled_users(w["B"], 24, 3), expect_variant="mfma_dma_bf16_d64_w1_g2")
 
 
 def test_config3_keys_only_full(gpu):
     w = wl.config("cfg3_ck")
-    run_and_check(gpu, w, "cfg3_ck", users=sampled_users(w["B"], 16, 6), expect_variant="mfma_dma_bf16_d64_w2")
+    run_and_check(gpu, w, "cfg3_ck", users=sampled_users(w["B"], 16, 6), expect_variant="mfma_dma_bf16_d64_w1_g2")
 
 
 def test_config4_full(gpu):

@@ -107,7 +107,7 @@ def test_sharing_one_side_keeps_the_kernel_family():
     lengths = np.full(64, 512)
     for share in (0, 1, 2):
         _, rec, _, name = plan(lengths, 2, 64, 4, 64, BF16, share=share)
-        assert name.startswith("mfma_dma_bf16_d64_w2")
+        assert name.startswith("mfma_dma_bf16_d64_w1_g2")
         check_cover(lengths.astype(np.int32), rec, 2, 64, name)
 
 
