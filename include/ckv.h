@@ -68,7 +68,7 @@ enum {
  *   every device pointer 16-byte aligned (CKV_ERR_UNSUPPORTED); device gfx950 (CKV_ERR_UNSUPPORTED).
  * The matrix-core kernels take Nq >= 8 (>= 3 for the fastest bf16 shapes, >= 6 in fp32; scale > 0 for
  * softmax): bf16 with d_a <= 256 and pool_ld a multiple
- * of 8 (fastest at d_a of exactly 64, 128 or 256 with d_u odd up to 7 or even up to 16), fp32 with d_a <= 256 and pool_ld a
+ * of 8 (fastest at d_a of exactly 64, 128 or 256 with d_u odd up to 7 or even up to 16, up to 32 at 256 columns), fp32 with d_a <= 256 and pool_ld a
  * multiple of 4 (on the fp32 matrix instruction, a sixteenth of the bf16 rate).  Every other shape runs the streaming kernel,
  * which is made for few queries.  ckv_variant names the choice.
  */

@@ -1,5 +1,5 @@
 // Matrix-core gather-concat-attend kernel with direct global->LDS gathers (bf16 storage, fp32
-// accumulation, d_a = 64, 128 or 256, d_u even up to 16 or odd up to 7).
+// accumulation, d_a = 64, 128 or 256, d_u even up to 16 (32 at 256 columns) or odd up to 7).
 //
 // Same mathematics and MFMA operand layouts as the register-staged kernel next to it
 // (S^T = K Q^T, O^T += V^T P^T, one query per lane), but the final K and V rows of a tile are
@@ -100,9 +100,9 @@ struct Geo {
     static constexpr int ROWB = DA * 2;          // bytes per row
     static constexpr int RPI = 64 / CH;          // rows filled by one wavefront instruction
     static constexpr int NI = TP / RPI / NW;     // gather instructions per wavefront, K and V each
-    static constexpr int NUI_MAX = (DA == 256 || WIDEU ? 8 : 4) / NW;  // user-slice instructions per wavefront (d_u <= 8, or <= 16)
+    static constexpr int NUI_MAX = (DA == 256 ? 16 : WIDEU ? 8 : 4) / NW;  // user-slice instructions per wavefront (d_u <= 8, <= 16, or <= 32 at 256 columns)
     static constexpr int KV = TP * ROWB;         // bytes of the K (or V) rows of a stage
-    static constexpr int USER = NW * 64 * 4 * NUI_MAX;  // bytes of the user staging of a stage (1 or 2 KiB)
+    static constexpr int USER = NW * 64 * 4 * NUI_MAX;  // bytes of the user staging of a stage (1, 2 or 4 KiB)
     static constexpr int STAGE = 2 * KV + USER;
     static constexpr int IDX = 256;              // bytes of one index slot: 32 x I_k, 32 x I_v
     static constexpr int NIS = 4;                // index slots per wavefront (indices run 3 tiles ahead of the gathers)
@@ -656,10 +656,10 @@ bool ckv_dma_supported(int d_a, int nw, int qg) {
 int ckv_dma_nui(int d_a, int nw, int d_u) {
     if ((d_a != 64 && d_a != 128 && d_a != 256) || (nw != 1 && nw != 2 && nw != 4)) return -1;
     if (d_a == 256 && nw != 4) return -1;  // (256 columns: four wavefronts only)
-    if (d_u < 0 || d_u > 16 || ((d_u & 1) && d_u > 7)) return -1;
+    if (d_u < 0 || d_u > (d_a == 256 ? 32 : 16) || ((d_u & 1) && d_u > 7)) return -1;
     // lanes that move the user slices of a tile: one per dword, or one per element when d_u is odd
     const int need = ((d_u & 1 ? 64 : 32) * d_u + nw * 64 - 1) / (nw * 64);
-    return need <= 1 ? need : (need <= 2 ? 2 : (need <= 4 ? 4 : 8));
+    return need <= 1 ? need : (need <= 2 ? 2 : (need <= 4 ? 4 : 8));  // (never above NUI_MAX of the geometry that serves the shape)
 }
 
 // (user slices of 10 to 16 columns, or of 5 or 7, at 64 or 128 columns: the instantiations with the larger staging area)

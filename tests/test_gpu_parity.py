@@ -585,10 +585,11 @@ def test_wide_bf16_head_split_history(gpu):
 
 
 @pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
-@pytest.mark.parametrize("d_u,Nq", [(1, 128), (2, 64), (3, 40), (4, 128), (6, 200), (10, 128), (10, 64), (16, 33), (8, 3), (0, 16)])
+@pytest.mark.parametrize("d_u,Nq", [(1, 128), (2, 64), (3, 40), (4, 128), (6, 200), (10, 128), (10, 64), (16, 33), (8, 3), (0, 16),
+                                    (24, 128), (32, 64), (20, 40), (30, 200)])
 def test_256_column_heads_in_the_direct_to_lds_kernel(gpu, mode, d_u, Nq):
-    """d_a = 256 with the user widths behind the compression ratios of Table 1 (d_u = 1, 2, 3, 4, 6, 10) and the
-    widest slice the kernel appends (16): rows of 512 bytes, up to eight slice loads per wavefront and tile."""
+    """d_a = 256 with the user widths behind the compression ratios of Table 1 (d_u = 1, 2, 3, 4, 6, 10) and up to the
+    widest slice the kernel appends (32): rows of 512 bytes, up to four slice loads per wavefront and tile."""
     w = make(MFMA_LENGTHS, wl.BF16, mode, d_a=256, d_u=d_u, H=3, P=700, Nq=Nq)
     run_and_check(gpu, w, f"256 columns d_u={d_u} Nq={Nq} mode={mode}",
                   expect_variant="mfma_dma_bf16_d256_w4")
