@@ -119,3 +119,27 @@ def test_plan_rejects_bad_arguments():
     with pytest.raises(ckv.CkvError) as e:
         ckv.ckv_plan(sh, np.array([1, 1], np.int32), cus=0)
     assert e.value.code == ckv.CKV_ERR_SHAPE
+
+
+@pytest.mark.parametrize("d_a,d_u,Nq,dtype,expect", [
+    # direct-to-LDS kernel: wavefronts and query groups by width and query count
+    (64, 4, 16, BF16, "mfma_dma_bf16_d64_w1_g1"), (64, 4, 64, BF16, "mfma_dma_bf16_d64_w1_g2"),
+    (64, 4, 100, BF16, "mfma_dma_bf16_d64_w4_g1"), (64, 64, 64, BF16, "mfma_dma_bf16_d64_w2_g1"),  # ordinary cache: two wavefronts
+    (128, 8, 32, BF16, "mfma_dma_bf16_d128_w1_g1"), (128, 8, 64, BF16, "mfma_dma_bf16_d128_w2_g1"),
+    (128, 8, 128, BF16, "mfma_dma_bf16_d128_w4_g1"), (256, 4, 16, BF16, "mfma_dma_bf16_d256_w4_g1"),
+    (256, 10, 128, BF16, "mfma_dma_bf16_d256_w4_g1"), (256, 32, 64, BF16, "mfma_dma_bf16_d256_w4_g1"),
+    # user widths it takes: odd up to 7, even up to 16 (one query group per wavefront from 10 on)
+    (64, 7, 64, BF16, "mfma_dma_bf16_d64_w2_g1"), (64, 10, 64, BF16, "mfma_dma_bf16_d64_w2_g1"), (128, 16, 20, BF16, "mfma_dma_bf16_d128_w1_g1"),
+    (128, 5, 128, BF16, "mfma_dma_bf16_d128_w4_g1"), (64, 1, 3, BF16, "mfma_dma_bf16_d64_w1_g1"),
+    # what stays in the register-staged kernel (from 8 queries on), and below that in the streaming kernel
+    (128, 9, 64, BF16, "mfma_bf16_d128"), (128, 24, 64, BF16, "mfma_bf16_d128"), (64, 18, 8, BF16, "mfma_bf16_d64"),
+    (96, 8, 64, BF16, "mfma_bf16_d128"), (200, 8, 64, BF16, "mfma_bf16_d256"), (256, 34, 64, BF16, "mfma_bf16_d256"),
+    (128, 9, 7, BF16, "stream"), (64, 8, 2, BF16, "stream"), (320, 8, 64, BF16, "stream"),
+    # fp32 storage
+    (64, 8, 6, F32, "mfma_f32_d64"), (128, 8, 5, F32, "stream"), (256, 8, 64, F32, "mfma_f32_d256"),
+])
+def test_kernel_choice_by_shape(d_a, d_u, Nq, dtype, expect):
+    """Which kernel the dispatcher picks, and that its work lists cover the batch (host arithmetic only)."""
+    lengths, rec, _, name = plan(np.array([700, 33, 0, 2048, 5]), 2, d_a, d_u, Nq, dtype)
+    assert name.startswith(expect), name
+    check_cover(lengths, rec, 2, Nq, name)
