@@ -81,14 +81,28 @@ static void final_row(double *row, const void *user, const void *pool, const int
 /*
  * Attention outputs of the listed users.  users[] holds n_users user numbers (or NULL for
  * all B users in order); rows of out that belong to other users are not touched.
+ * rss (same shape as out, or NULL) receives, for every output element c, the scale against which a
+ * rounding error of the weights shows in that element: the positions are grouped by the value of
+ * their weight (equal weights are rounded alike, so their errors add up coherently; different
+ * weights err independently), and rss[c] = sqrt(sum over groups g of (sum_{i in g} w_i V_i[c])^2).
+ * With all weights different this is the root-sum-square of the summands w_i V_i[c]; with all
+ * weights equal it is |out[c]|.  It is an extra output for the comparison rule of the tests; out
+ * does not depend on it.
  * Returns 0, or -1 on a bad argument (index outside [0,P), negative length, unknown mode).
  */
-int ckv_oracle_attend(int B, int H, int d_g, int d_u, int P, int Nq, int dtype, int mode, int share,
-                      double scale, int64_t pool_ld,
-                      const int32_t *lengths, const int32_t *idx_k, const int32_t *idx_v,
-                      const void *user_k, const void *user_v,
-                      const void *pool_k, const void *pool_v, const void *q,
-                      double *out, const int32_t *users, int n_users)
+struct weighted { double w; int i; };
+static int by_weight(const void *a, const void *b)
+{
+    const double x = ((const struct weighted *)a)->w, y = ((const struct weighted *)b)->w;
+    return x < y ? -1 : (x > y ? 1 : 0);
+}
+
+static int attend_impl(int B, int H, int d_g, int d_u, int P, int Nq, int dtype, int mode, int share,
+                       double scale, int64_t pool_ld,
+                       const int32_t *lengths, const int32_t *idx_k, const int32_t *idx_v,
+                       const void *user_k, const void *user_v,
+                       const void *pool_k, const void *pool_v, const void *q,
+                       double *out, double *rss, const int32_t *users, int n_users)
 {
     const int d_a = d_u + d_g;
     if (B < 0 || H < 1 || d_g < 0 || d_u < 0 || d_a < 1 || Nq < 1 || pool_ld < d_g)
@@ -154,12 +168,53 @@ int ckv_oracle_attend(int B, int H, int d_g, int d_u, int P, int Nq, int dtype, 
                     for (int i = 0; i < n; ++i) a += w[i] * V[(int64_t)i * d_a + c];
                     out[qo + c] = a;
                 }
+                if (rss) {
+                    /* positions in order of their weight, so that equal weights are neighbours */
+                    struct weighted *ord = (struct weighted *)malloc(sizeof(struct weighted) * (size_t)(n > 0 ? n : 1));
+                    for (int i = 0; i < n; ++i) { ord[i].w = w[i]; ord[i].i = i; }
+                    qsort(ord, (size_t)n, sizeof ord[0], by_weight);
+                    for (int c = 0; c < d_a; ++c) {
+                        double a2 = 0.0, group = 0.0;
+                        for (int k = 0; k < n; ++k) {
+                            group += ord[k].w * V[(int64_t)ord[k].i * d_a + c];
+                            if (k + 1 == n || ord[k + 1].w != ord[k].w) {  /* the group ends here */
+                                a2 += group * group;
+                                group = 0.0;
+                            }
+                        }
+                        rss[qo + c] = sqrt(a2);
+                    }
+                    free(ord);
+                }
             }
             free(K); free(V); free(w); free(qv);
         }
     }
     free(offset);
     return bad ? -1 : 0;
+}
+
+int ckv_oracle_attend(int B, int H, int d_g, int d_u, int P, int Nq, int dtype, int mode, int share,
+                      double scale, int64_t pool_ld,
+                      const int32_t *lengths, const int32_t *idx_k, const int32_t *idx_v,
+                      const void *user_k, const void *user_v,
+                      const void *pool_k, const void *pool_v, const void *q,
+                      double *out, const int32_t *users, int n_users)
+{
+    return attend_impl(B, H, d_g, d_u, P, Nq, dtype, mode, share, scale, pool_ld, lengths, idx_k, idx_v, user_k, user_v,
+                       pool_k, pool_v, q, out, NULL, users, n_users);
+}
+
+/* The same, and the root-sum-square of every element's summands in rss (see above). */
+int ckv_oracle_attend_rss(int B, int H, int d_g, int d_u, int P, int Nq, int dtype, int mode, int share,
+                          double scale, int64_t pool_ld,
+                          const int32_t *lengths, const int32_t *idx_k, const int32_t *idx_v,
+                          const void *user_k, const void *user_v,
+                          const void *pool_k, const void *pool_v, const void *q,
+                          double *out, double *rss, const int32_t *users, int n_users)
+{
+    return attend_impl(B, H, d_g, d_u, P, Nq, dtype, mode, share, scale, pool_ld, lengths, idx_k, idx_v, user_k, user_v,
+                       pool_k, pool_v, q, out, rss, users, n_users);
 }
 
 /*

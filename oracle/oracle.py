@@ -35,6 +35,8 @@ def _load():
         vp, i32, i64, dbl = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_double
         lib.ckv_oracle_attend.restype = ctypes.c_int
         lib.ckv_oracle_attend.argtypes = [i32] * 9 + [dbl, i64] + [vp] * 9 + [vp, i32]
+        lib.ckv_oracle_attend_rss.restype = ctypes.c_int
+        lib.ckv_oracle_attend_rss.argtypes = [i32] * 9 + [dbl, i64] + [vp] * 10 + [vp, i32]
         lib.ckv_oracle_reconstruct.restype = ctypes.c_int
         lib.ckv_oracle_reconstruct.argtypes = [i32] * 6 + [i64, i64] + [vp] * 8
         lib.ckv_oracle_cache_size.restype = None
@@ -59,12 +61,14 @@ def _check_store(a, dtype, name):
     return a
 
 
-def attend(w, users=None):
+def attend(w, users=None, with_rss=False):
     """Attention outputs, fp64 [B][H][Nq][d_a].
 
     `w` is a workload dict as made by the seeded generators: keys B, H, d_g, d_u, P, Nq,
     dtype, mode, scale, pool_ld, lengths, idx_k, idx_v, user_k, user_v, pool_k, pool_v, q.
     Rows of users not listed in `users` are NaN.
+    with_rss: also return, per output element c, the scale the tests' comparison rule uses (same shape):
+    sqrt(sum over groups g of positions with one and the same weight of (sum_{i in g} w_i V_i[c])^2).
     """
     lib = _load()
     dt = w["dtype"]
@@ -79,13 +83,17 @@ def attend(w, users=None):
     else:
         ulist = np.ascontiguousarray(users, dtype=np.int32)
         uptr, nu = _ptr(ulist), len(ulist)
-    rc = lib.ckv_oracle_attend(
-        w["B"], w["H"], w["d_g"], w["d_u"], w["P"], w["Nq"], dt, w["mode"], int(w.get("share", 0)),
-        float(w["scale"]), int(w["pool_ld"]),
-        _ptr(lengths), _ptr(idx_k), _ptr(idx_v), *[_ptr(a) for a in arrs], _ptr(out), uptr, nu)
+    head = (w["B"], w["H"], w["d_g"], w["d_u"], w["P"], w["Nq"], dt, w["mode"], int(w.get("share", 0)),
+            float(w["scale"]), int(w["pool_ld"]),
+            _ptr(lengths), _ptr(idx_k), _ptr(idx_v), *[_ptr(a) for a in arrs])
+    if with_rss:
+        rss = np.full(out.shape, np.nan, dtype=np.float64)
+        rc = lib.ckv_oracle_attend_rss(*head, _ptr(out), _ptr(rss), uptr, nu)
+    else:
+        rc = lib.ckv_oracle_attend(*head, _ptr(out), uptr, nu)
     if rc != 0:
         raise ValueError("ckv_oracle_attend rejected its arguments")
-    return out
+    return (out, rss) if with_rss else out
 
 
 def reconstruct(w):

@@ -376,3 +376,105 @@ def test_hot_row_renumbering_is_a_relabeling():
     ok2, ov2 = oracle.reconstruct(w2)
     np.testing.assert_array_equal(ok, ok2)
     np.testing.assert_array_equal(ov, ov2)
+
+
+# ---------------------------------------------------------------------------------------------
+# split-history merge identity (online softmax): the oracle on chunks of a history, joined by the
+# (m, l, acc) rule written out here, equals the oracle on the whole history
+def _scores(w, b, h):
+    """scale * q K^T of one (user, head), fp64 numpy [Nq][n], from explicitly concatenated K rows."""
+    for bb, hh, K, _ in dense_kv(w):
+        if (bb, hh) == (b, h):
+            return w["scale"] * wl.to_f64(w["q"], w["dtype"])[b, h] @ K.numpy().T
+    raise KeyError((b, h))
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+@pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
+@pytest.mark.parametrize("cuts", [(0, 1, 38, 64, 97), (0, 96, 97), (0, 50, 97), (0, 97)])
+def test_chunks_merged_by_max_sum_acc_equal_the_whole_history(dtype, mode, cuts):
+    n = cuts[-1]
+    w = small(dtype=dtype, mode=mode, lengths=(n,), H=2, Nq=3, P=11)
+    whole = oracle.attend(w)[0]                                   # [H][Nq][d_a]
+    merged = np.zeros_like(whole)
+    for h in range(w["H"]):
+        s = _scores(w, 0, h)                                      # [Nq][n]
+        m_c, l_c, acc_c = [], [], []
+        for lo, hi in zip(cuts[:-1], cuts[1:]):                   # the first chunk of the first case has one position
+            wc = dict(w)
+            wc["lengths"] = np.array([hi - lo], np.int32)
+            for k in ("idx_k", "idx_v", "user_k", "user_v"):
+                wc[k] = np.ascontiguousarray(w[k][lo:hi])
+            part = oracle.attend(wc)[0, h]                        # the chunk's own normalised output
+            if mode == wl.SOFTMAX:
+                m = s[:, lo:hi].max(axis=1)
+                l = np.exp(s[:, lo:hi] - m[:, None]).sum(axis=1)
+                m_c.append(m); l_c.append(l); acc_c.append(part * l[:, None])   # acc relative to the chunk maximum
+            else:
+                acc_c.append(part * (hi - lo))                    # undo the chunk's 1/n
+        if mode == wl.SOFTMAX:
+            M = np.max(np.stack(m_c), axis=0)
+            scale_c = [np.exp(m - M) for m in m_c]
+            denom = sum(a * l for a, l in zip(scale_c, l_c))
+            merged[h] = sum(a[:, None] * acc for a, acc in zip(scale_c, acc_c)) / denom[:, None]
+        else:
+            merged[h] = sum(acc_c) / n
+    np.testing.assert_allclose(merged, whole, rtol=1e-11, atol=1e-13)
+
+
+# ---------------------------------------------------------------------------------------------
+# the per-element scale of the comparison rule: root-sum-square of an element's summands
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+@pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
+@pytest.mark.parametrize("share", [wl.SHARE_KV, wl.SHARE_K, wl.SHARE_V])
+def test_summand_scale_matches_explicit_weights(dtype, mode, share):
+    w = small(dtype=dtype, mode=mode, share=share)
+    out, rss = oracle.attend(w, with_rss=True)
+    np.testing.assert_array_equal(out, oracle.attend(w))          # the extra output changes nothing
+    q = wl.to_f64(w["q"], dtype)
+    for b, h, K, V in dense_kv_shared(w):
+        n = K.shape[0]
+        if n == 0:
+            assert np.all(rss[b, h] == 0)
+            continue
+        s = torch.from_numpy(w["scale"] * q[b, h]) @ K.T
+        wt = torch.softmax(s, dim=-1) if mode == wl.SOFTMAX else torch.nn.functional.silu(s) / n
+        terms = wt[:, :, None] * V[None, :, :]                    # [Nq][n][d_a]
+        # the random workload has no two equal weights: every position is a group of its own
+        np.testing.assert_allclose(rss[b, h], terms.pow(2).sum(dim=1).sqrt().numpy(), rtol=1e-11, atol=1e-14)
+        np.testing.assert_allclose(out[b, h], terms.sum(dim=1).numpy(), rtol=1e-11, atol=1e-13)
+
+
+@pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
+def test_summand_scale_groups_positions_of_equal_weight(mode):
+    # no user columns and a key pool of three rows: a query sees at most three different weights, however long the
+    # history; positions that share a weight form one group whose summands are added before squaring
+    w = small(mode=mode, d_u=0, d_a=12, P=3, lengths=(50, 7), H=1, Nq=2)
+    out, rss = oracle.attend(w, with_rss=True)
+    q = wl.to_f64(w["q"], w["dtype"])
+    off = np.concatenate([[0], np.cumsum(w["lengths"])])
+    for b, h, K, V in dense_kv(w):
+        n, V = K.shape[0], V.numpy()
+        s = (w["scale"] * q[b, h]) @ K.numpy().T
+        wt = torch.softmax(torch.from_numpy(s), dim=-1).numpy() if mode == wl.SOFTMAX else s / (1 + np.exp(-s)) / n
+        rows = w["idx_k"][off[b]:off[b + 1], h]                   # the key row decides the weight
+        for j in range(w["Nq"]):
+            groups = np.stack([(wt[j][rows == r, None] * V[rows == r]).sum(axis=0) for r in np.unique(rows)])
+            assert len(np.unique(wt[j])) == len(groups) <= 3
+            np.testing.assert_allclose(rss[b, h, j], np.sqrt((groups ** 2).sum(axis=0)), rtol=1e-11, atol=1e-14)
+
+
+def test_summand_scale_closed_forms():
+    # one position: the only summand is the output itself
+    w = small(lengths=(1,), Nq=2)
+    out, rss = oracle.attend(w, with_rss=True)
+    np.testing.assert_allclose(rss, np.abs(out), rtol=1e-14)
+    # q = 0, softmax: every weight is 1/n, one group, so the scale is the output itself
+    w = small(lengths=(40,), H=1, Nq=1)
+    w["q"] = np.zeros_like(w["q"])
+    out, rss = oracle.attend(w, with_rss=True)
+    np.testing.assert_allclose(rss, np.abs(out), rtol=1e-12)
+    # users not listed stay NaN, like out
+    w = small()
+    _, rss = oracle.attend(w, users=[1], with_rss=True)
+    assert np.isnan(rss[0]).all() and np.isfinite(rss[1]).all()
