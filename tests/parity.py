@@ -1,32 +1,69 @@
-"""Comparison rule shared by the GPU parity tests.
+"""Comparison rule shared by the GPU parity tests, the smoke check and the benchmark.
 
 Tolerance (the benchmark spec): 1e-4 relative for fp32 storage, 2e-2 relative for bf16 storage.
-"Relative" is applied per output element against a floor of the row's own scale:
-    |g - r| <= tol * |r| + tol * rms(r over the d_a columns of that query)
-because an attention output is a signed sum, so single elements can sit arbitrarily close
-to zero while their rounding error is set by the size of the summands.  The norm-wise
-figure max|g - r| / max|r| is returned as well.
+An attention output is a signed sum r_c = sum_i w_i V_i[c]; single elements can sit arbitrarily
+close to zero (weights of both signs in the SiLU form, or value rows that cancel) while the rounding
+error they carry is set by the size of their summands, so "relative" needs a scale per element.
+The rule, for every output element:
+
+    |g_c - r_c| <= tol * |r_c| + tol * rss_c,
+    rss_c = sqrt(sum over groups g of (sum_{i in g} w_i V_i[c])^2),   a group = the positions with one and the same weight
+
+Where it comes from: the kernels keep products and sums in fp32 and round two things below that,
+the weights w_i (to the storage type before the second matrix product: relative error at most
+u = 2^-9 in bf16, 2^-24 in fp32) and the finished output (again u, the tol * |r_c| term).  The
+rounding error of a weight is a function of its value: positions with the same weight (same key
+row, same query) err alike and their errors add up coherently, different weights err
+independently.  Independent relative errors of size u on the group sums add up to an error of
+standard deviation u / sqrt(3) * rss_c, so tol * rss_c with tol = 2e-2 and u = 2^-9 is eighteen
+standard deviations of the modelled error: a floor derived from the arithmetic, not from the
+outputs.  (A CPU model of exactly these roundings lands at 0.2 to 0.5 of the bound on every seeded
+random shape, the near-cancelling ones included.)  For value rows without structure rss_c is about
+the root-mean-square of the output row, so on ordinary rows the rule is as strict as a floor of
+tol * rms(row); on a row that nearly cancels it stays proportional to what was added up.
+rss_c comes from the CPU oracle (fp64, from the oracle's inputs), never from the GPU output.
+Users with an empty history have r = 0 and rss = 0: their rows must be exactly zero.
+The norm-wise figure max|g - r| / max|r| is reported beside it.
 """
 import numpy as np
+
+from oracle import oracle
 
 TOL = {0: 1e-4, 1: 2e-2}
 
 
-def check(gpu, ref, dtype, rows=None, what=""):
-    """gpu, ref: float64 [B][H][Nq][d_a]; rows: optional index of users to compare."""
-    if rows is not None:
-        gpu, ref = gpu[rows], ref[rows]
-    assert gpu.shape == ref.shape
-    assert np.isfinite(ref).all(), f"{what}: oracle produced non-finite values"
-    assert np.isfinite(gpu).all(), f"{what}: GPU produced non-finite values"
+def compare(gpu, ref, rss, dtype):
+    """Statistics of one comparison: gpu, ref, rss float64 arrays of one shape.
+    worst_ratio = max over elements of |g - r| / (tol |r| + tol rss)  (<= 1 passes; an element with
+    a zero bound counts as 0 if it is exact and as infinity if it is not)."""
+    assert gpu.shape == ref.shape == rss.shape
     tol = TOL[dtype]
-    rms = np.sqrt(np.mean(ref * ref, axis=-1, keepdims=True))
-    bound = tol * np.abs(ref) + tol * rms
+    if ref.size == 0:
+        return {"tol": tol, "elements": 0, "norm_err": 0.0, "worst_ratio": 0.0, "finite": True}
+    finite = bool(np.isfinite(gpu).all())
     err = np.abs(gpu - ref)
-    worst = float(np.max(err - bound)) if err.size else 0.0
-    norm = float(err.max() / max(np.abs(ref).max(), 1e-300)) if err.size else 0.0
-    # exact zeros (empty histories) must be exact
-    zero_rows = (rms[..., 0] == 0)
-    assert np.all(gpu[zero_rows] == 0), f"{what}: rows that must be exactly zero are not"
-    assert worst <= 0, f"{what}: element error exceeds tol={tol}: max excess {worst:.3e}, norm-wise {norm:.3e}"
-    return norm
+    bound = tol * np.abs(ref) + tol * rss
+    with np.errstate(divide="ignore", invalid="ignore"):
+        ratio = np.where(bound > 0, err / bound, np.where(err == 0, 0.0, np.inf))
+    return {"tol": tol, "elements": int(ref.size), "finite": finite,
+            "norm_err": float(err.max() / max(np.abs(ref).max(), 1e-300)) if finite else float("inf"),
+            "worst_ratio": float(np.nanmax(ratio)) if finite else float("inf")}
+
+
+def check(gpu, ref, rss, dtype, rows=None, what=""):
+    """gpu, ref, rss: float64 [B][H][Nq][d_a]; rows: optional index of the users to compare.
+    Asserts the rule above on every element and returns the norm-wise error."""
+    if rows is not None:
+        gpu, ref, rss = gpu[rows], ref[rows], rss[rows]
+    assert np.isfinite(ref).all() and np.isfinite(rss).all(), f"{what}: oracle produced non-finite values"
+    assert np.isfinite(gpu).all(), f"{what}: GPU produced non-finite values"
+    st = compare(gpu, ref, rss, dtype)
+    assert st["worst_ratio"] <= 1.0, (f"{what}: element error exceeds tol={st['tol']}: worst |g-r| / (tol|r| + tol rss) = "
+                                      f"{st['worst_ratio']:.3f}, norm-wise {st['norm_err']:.3e}")
+    return st["norm_err"]
+
+
+def check_against_oracle(gpu, w, users=None, what=""):
+    """Run the oracle on workload `w` (all users, or the listed ones) and check `gpu` against it."""
+    ref, rss = oracle.attend(w, users=users, with_rss=True)
+    return check(gpu, ref, rss, w["dtype"], rows=users, what=what)

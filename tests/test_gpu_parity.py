@@ -6,7 +6,7 @@ import pytest
 
 from oracle import oracle
 from paper_2601_19178_amd import workloads as wl
-from tests.parity import check
+from tests.parity import check_against_oracle
 
 pytestmark = pytest.mark.gpu
 
@@ -32,14 +32,12 @@ def make(lengths, dtype, mode, d_a, d_u, H, P, Nq, seed=11, idx="uniform", **kw)
 
 def run_and_check(gpu, w, what, users=None, expect_variant=None, impl=None):
     """impl: None (library's choice) or "staged" (force the register-staged matrix-core kernel)."""
-    import os
     ckv, session = gpu
-    if impl:
-        os.environ["CKV_MFMA_IMPL"] = impl
+    ckv.ckv_set_option("mfma_impl", impl)
     try:
         return _run_and_check(ckv, session, w, what, users, expect_variant)
     finally:
-        os.environ.pop("CKV_MFMA_IMPL", None)
+        ckv.ckv_set_option(None)
 
 
 def _run_and_check(ckv, session, w, what, users, expect_variant):
@@ -52,8 +50,7 @@ def _run_and_check(ckv, session, w, what, users, expect_variant):
             assert variant.startswith(expect_variant), variant
         s.attend()
         out = s.output()
-    ref = oracle.attend(w, users=users)
-    norm = check(out, ref, w["dtype"], rows=users, what=what)
+    norm = check_against_oracle(out, w, users=users, what=what)
     say(f"  ok, norm-wise error {norm:.3e}")
     return out
 
@@ -180,41 +177,28 @@ def test_mfma_large_scores_softmax(gpu):
 
 
 # ---------------------------------------------------------------------------------------------
-# full-size workloads, in the launch configuration the benchmark times; oracle on sampled users
-def sampled_users(B, k, seed):
-    return np.sort(np.random.default_rng(seed).choice(B, size=k, replace=False)).astype(np.int32)
-
-
+# full-size workloads, in the launch configuration the benchmark times; every output of every user against the oracle
 def test_config3_full(gpu):
-    w = wl.config("cfg3")
-    run_and_check(gpu, w, "cfg3", users=sampled_users(w["B"], 24, 3), expect_variant="mfma_dma_bf16_d64_w1_g2")
+    run_and_check(gpu, wl.config("cfg3"), "cfg3", expect_variant="mfma_dma_bf16_d64_w1_g2")
 
 
 def test_config3_keys_only_full(gpu):
-    w = wl.config("cfg3_ck")
-    run_and_check(gpu, w, "cfg3_ck", users=sampled_users(w["B"], 16, 6), expect_variant="mfma_dma_bf16_d64_w1_g2")
+    run_and_check(gpu, wl.config("cfg3_ck"), "cfg3_ck", expect_variant="mfma_dma_bf16_d64_w1_g2")
 
 
 def test_config4_full(gpu):
-    w = wl.config("cfg4")
-    users = sampled_users(w["B"], 3, 4)
-    users = np.unique(np.concatenate([users, [int(np.argmax(w["lengths"])), int(np.argmin(w["lengths"]))]])).astype(np.int32)
-    run_and_check(gpu, w, "cfg4", users=users, expect_variant="mfma_dma_bf16_d128_w4_g1")
+    run_and_check(gpu, wl.config("cfg4"), "cfg4", expect_variant="mfma_dma_bf16_d128_w4_g1")
 
 
 @pytest.mark.parametrize("name,Nq", [("d256_u4", 128), ("d256_u10", 128), ("d256_u4", 40)])
 def test_256_column_heads_full(gpu, name, Nq):
     """Table 1's head width at config 4's batch, in the launch configuration the bench times; 40 queries leave
     wavefronts without queries that only gather."""
-    w = wl.config(name, Nq=Nq)
-    users = sampled_users(w["B"], 3, 7)
-    users = np.unique(np.concatenate([users, [int(np.argmax(w["lengths"])), int(np.argmin(w["lengths"]))]])).astype(np.int32)
-    run_and_check(gpu, w, f"{name} Nq={Nq}", users=users, expect_variant="mfma_dma_bf16_d256_w4_g1")
+    run_and_check(gpu, wl.config(name, Nq=Nq), f"{name} Nq={Nq}", expect_variant="mfma_dma_bf16_d256_w4_g1")
 
 
 def test_config5_full(gpu):
-    w = wl.config("cfg5")
-    run_and_check(gpu, w, "cfg5", users=sampled_users(w["B"], 48, 5), expect_variant="mfma_dma_bf16_d64_w1_g1")
+    run_and_check(gpu, wl.config("cfg5"), "cfg5", expect_variant="mfma_dma_bf16_d64_w1_g1")
 
 
 # ---------------------------------------------------------------------------------------------
@@ -239,7 +223,7 @@ def test_offloaded_cache_matches_resident(gpu, kind):
             np.testing.assert_array_equal(idx[0], w["idx_k"].T)
             np.testing.assert_array_equal(uv, w["user_v"].transpose(1, 0, 2))
     np.testing.assert_array_equal(outs[0], outs[1])
-    check(outs[1], oracle.attend(w), w["dtype"], what=f"offloaded {kind}")
+    check_against_oracle(outs[1], w, what=f"offloaded {kind}")
 
 
 # ---------------------------------------------------------------------------------------------
@@ -335,7 +319,7 @@ def test_hot_row_renumbering(gpu, share, kind):
     ok, ov = oracle.reconstruct(w)
     np.testing.assert_array_equal(k_full, ok.transpose(1, 0, 2))
     np.testing.assert_array_equal(v_full, ov.transpose(1, 0, 2))
-    check(after, oracle.attend(w), w["dtype"], what=f"renumbered {kind} share={share}")
+    check_against_oracle(after, w, what=f"renumbered {kind} share={share}")
 
 
 def test_hot_row_renumbering_rejects_offloaded_and_aliased(gpu):
@@ -385,7 +369,26 @@ def test_attend_rejects_unaligned_and_missing_pointers(gpu):
                 ckv.ckv_attend(c, *bad, s.stream)
             assert e.value.code == ckv.CKV_ERR_NULL
         s.attend()  # the handle is still usable
-        check(s.output(), oracle.attend(w), w["dtype"], what="after rejected calls")
+        check_against_oracle(s.output(), w, what="after rejected calls")
+
+
+def test_attend_refuses_lengths_that_are_not_the_handles(gpu):
+    """The work lists follow the lengths the handle was built with; another lengths array (even an equal copy)
+    is refused instead of being ignored."""
+    import torch
+    ckv, session = gpu
+    w = make((10, 20), wl.BF16, wl.SOFTMAX, d_a=64, d_u=8, H=1, P=50, Nq=16)
+    with session.Session(w) as s:
+        c = s.cache
+        grown = torch.tensor([10, 21], dtype=torch.int32, device="cuda")
+        same = torch.tensor([10, 20], dtype=torch.int32, device="cuda")
+        for other in (grown, same):
+            with pytest.raises(ckv.CkvError) as e:
+                ckv.ckv_attend(c, s.pool_k, s.pool_v, ckv.ckv_cache_idx(c), ckv.ckv_cache_user_k(c), ckv.ckv_cache_user_v(c), s.q,
+                               other, s.out, s.stream)
+            assert e.value.code == ckv.CKV_ERR_UNSUPPORTED and "ckv_cache_lengths" in str(e.value)
+        s.attend()
+        check_against_oracle(s.output(), w, what="after refused lengths")
 
 
 def test_all_histories_empty(gpu):
@@ -446,7 +449,7 @@ def test_attend_replayed_from_a_captured_graph(gpu, kind):
         # the last queries against the oracle as well
         w2 = dict(w)
         w2["q"] = session._to_host(s.q, w["dtype"])
-    check(want, oracle.attend(w2), w["dtype"], what=f"graph replay {kind}")
+    check_against_oracle(want, w2, what=f"graph replay {kind}")
 
 
 @pytest.mark.parametrize("kind", ["dma", "staged", "stream"])
@@ -474,9 +477,7 @@ def test_pool_rows_beyond_four_gib(gpu, kind):
     w["P"] = P_big
     assert w["pool_k"].nbytes > 1 << 32 and int(w["idx_k"].max()) * w["pool_ld"] * 2 >= 1 << 32
     ckv, session = gpu
-    import os
-    if kind == "staged":
-        os.environ["CKV_MFMA_IMPL"] = "staged"
+    ckv.ckv_set_option("mfma_impl", "staged" if kind == "staged" else None)
     try:
         say(f"[case] pool beyond 4 GiB, {kind}: P={P_big}, {w['pool_k'].nbytes / 2**30:.2f} GiB per side")
         with session.Session(w) as s:
@@ -487,44 +488,65 @@ def test_pool_rows_beyond_four_gib(gpu, kind):
             out = s.output()
             k_full, v_full = s.reconstruct()
     finally:
-        os.environ.pop("CKV_MFMA_IMPL", None)
+        ckv.ckv_set_option(None)
     ok, ov = oracle.reconstruct(w)
     assert np.array_equal(k_full, ok.transpose(1, 0, 2)) and np.array_equal(v_full, ov.transpose(1, 0, 2))
-    norm = check(out, oracle.attend(w), w["dtype"], what=f"pool beyond 4 GiB ({kind})")
+    norm = check_against_oracle(out, w, what=f"pool beyond 4 GiB ({kind})")
     say(f"  ok, norm-wise error {norm:.3e}, rows bit-exact")
+
+
+def random_shape(block, case):
+    """Seeded random shape number `case` of block `block`, drawn over everything the dispatcher looks at (storage
+    type, head width, user width, pool stride, query count, weighting, which side is shared, ragged lengths with
+    empty histories).  Returns (workload, description)."""
+    rng = np.random.default_rng(1000 * block + case)
+    matrix = rng.random() < 0.6
+    if matrix:
+        dtype, d_a = wl.BF16, int(rng.choice([64, 128, 256]))
+        d_u = int(rng.choice([0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 12, 14, 16, 24]))
+        Nq = int(rng.integers(8, 300))
+    else:
+        dtype = int(rng.choice([wl.F32, wl.BF16]))
+        d_a = int(rng.choice([8, 12, 16, 40, 64, 72, 128, 200]))
+        d_u = int(rng.integers(0, min(d_a, 16) + 1))
+        Nq = int(rng.integers(1, 8))
+    d_g = d_a - d_u
+    align = 8 if matrix else 1
+    pool_ld = 0 if d_g == 0 else int(rng.choice([(d_g + align - 1) // align * align, d_a, d_a + 8]))
+    if d_g > 0 and pool_ld < d_g:
+        pool_ld = d_a
+    share = int(rng.choice([wl.SHARE_KV, wl.SHARE_KV, wl.SHARE_K, wl.SHARE_V])) if d_g > 0 else wl.SHARE_KV
+    mode = int(rng.choice([wl.SOFTMAX, wl.SILU_OVER_N]))
+    B = int(rng.integers(1, 9))
+    lengths = rng.choice([0, 1, 31, 32, 33, 64, 100, 257, 900, 3000], size=B).astype(np.int32)
+    H, P = int(rng.integers(1, 4)), int(rng.choice([1, 2, 77, 700, 5000]))
+    kw = dict(pool_ld=pool_ld) if d_g > 0 else {}
+    w = make(lengths, dtype, mode, d_a=d_a, d_u=d_u, H=H, P=P, Nq=Nq, seed=2000 + 100 * block + case,
+             idx=("zipf", 1.1) if rng.random() < 0.3 else "uniform", share=share, **kw)
+    return w, f"random shape {block}.{case}: d_a={d_a} d_u={d_u} ld={pool_ld} share={share} lengths={lengths.tolist()}"
 
 
 @pytest.mark.parametrize("block", range(4))
 def test_seeded_random_shapes(gpu, block):
-    """Twelve seeded random shapes per block, drawn over everything the dispatcher looks at (storage type,
-    head width, user width, pool stride, query count, weighting, which side is shared, ragged lengths with
-    empty histories), each against the oracle element by element."""
+    """Twelve seeded random shapes per block, each against the oracle element by element."""
     for case in range(12):
-        rng = np.random.default_rng(1000 * block + case)
-        matrix = rng.random() < 0.6
-        if matrix:
-            dtype, d_a = wl.BF16, int(rng.choice([64, 128, 256]))
-            d_u = int(rng.choice([0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 12, 14, 16, 24]))
-            Nq = int(rng.integers(8, 300))
-        else:
-            dtype = int(rng.choice([wl.F32, wl.BF16]))
-            d_a = int(rng.choice([8, 12, 16, 40, 64, 72, 128, 200]))
-            d_u = int(rng.integers(0, min(d_a, 16) + 1))
-            Nq = int(rng.integers(1, 8))
-        d_g = d_a - d_u
-        align = 8 if matrix else 1
-        pool_ld = 0 if d_g == 0 else int(rng.choice([(d_g + align - 1) // align * align, d_a, d_a + 8]))
-        if d_g > 0 and pool_ld < d_g:
-            pool_ld = d_a
-        share = int(rng.choice([wl.SHARE_KV, wl.SHARE_KV, wl.SHARE_K, wl.SHARE_V])) if d_g > 0 else wl.SHARE_KV
-        mode = int(rng.choice([wl.SOFTMAX, wl.SILU_OVER_N]))
-        B = int(rng.integers(1, 9))
-        lengths = rng.choice([0, 1, 31, 32, 33, 64, 100, 257, 900, 3000], size=B).astype(np.int32)
-        H, P = int(rng.integers(1, 4)), int(rng.choice([1, 2, 77, 700, 5000]))
-        kw = dict(pool_ld=pool_ld) if d_g > 0 else {}
-        w = make(lengths, dtype, mode, d_a=d_a, d_u=d_u, H=H, P=P, Nq=Nq, seed=2000 + 100 * block + case,
-                 idx=("zipf", 1.1) if rng.random() < 0.3 else "uniform", share=share, **kw)
-        run_and_check(gpu, w, f"random shape {block}.{case}: d_a={d_a} d_u={d_u} ld={pool_ld} share={share} lengths={lengths.tolist()}")
+        w, what = random_shape(block, case)
+        run_and_check(gpu, w, what)
+
+
+# Shapes of further blocks of the same generator (blocks 4 to 109 were run once) on which a comparison rule with a
+# floor of tol * rms(output row) failed by 1e-7 to 1e-4 on a few elements: rows whose summands nearly cancel (SiLU
+# weights of both signs over a pool of one or two rows, or a handful of positions), so that the output row is far
+# smaller than what was added up.  All fourteen are kept; the rule in tests/parity.py scales the floor with the
+# summands of each element instead.
+NEAR_CANCELLING = [(26, 6), (39, 7), (43, 10), (47, 0), (57, 2), (59, 9), (67, 10), (72, 6), (75, 7), (82, 9), (84, 4),
+                   (99, 0), (103, 9), (104, 1)]
+
+
+@pytest.mark.parametrize("block,case", NEAR_CANCELLING)
+def test_random_shapes_with_near_cancelling_rows(gpu, block, case):
+    w, what = random_shape(block, case)
+    run_and_check(gpu, w, what)
 
 
 @pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
