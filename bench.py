@@ -6,13 +6,19 @@
 One step = one ckv_attend over the whole batch of the workload (main kernel + merge of split
 histories), inputs resident in HBM.  Prints ONE JSON line:
   value        users/s = B / step time (events on the launch stream around exactly K steps)
-  roofline     algorithmic bytes E per launch / mean duration of the main attention kernel
-               (event pairs recorded by the library around each of the K timed launches),
-               against the 8 TB/s HBM peak
-  cpu_baseline the CPU oracle on a sample of the same workload's users, on this host's cores
+  roofline     algorithmic bytes E per launch / mean duration of the main attention kernel over the K timed
+               launches (events recorded by the library on the launch stream around every launch), against
+               the 8 TB/s HBM peak; beside the mean: median, minimum and quartiles of the K launches, the
+               merge kernel's time, the counter-measured HBM traffic where a profile of the workload is
+               committed (a constant read from profiles/hbm_traffic.json, labelled as such), and the
+               matrix-core rate
+  steady_state the same per-launch statistics over a further block of launches after the timed steps (the
+               first ~50 back-to-back launches of a process run at lower clocks); not part of `value`
+  parity       the GPU output of the timed configuration against the CPU oracle on a seeded sample of users
+  cpu_baseline the CPU oracle timed on a sample of the same workload's users, on this host's cores
   also         the same figures for the other workloads (not the headline)
-  prefill      the prefill stage (router argmax + projection into the packed cache) on the cache shape of
-               config 2: positions/s and matrix-core TFLOP/s against the dense bf16 peak
+  prefill      the prefill stage (router argmax + projection into the packed cache): positions/s and
+               matrix-core TFLOP/s against the dense peak of its matrix instruction
 """
 import argparse
 import json
@@ -53,12 +59,44 @@ def compulsory_bytes(w, ab):
     return ab["compressed"] + rows * w["d_g"] * e + ab["q_out"]
 
 
-def measure(name, steps, warmup, with_compulsory=True):
+def launch_stats(ms):
+    """Mean, median, minimum, maximum and quartiles of per-launch milliseconds."""
+    ms = np.asarray(ms, dtype=np.float64)
+    q = np.percentile(ms, [25, 50, 75])
+    return {"launches": int(ms.size), "mean": float(ms.mean()), "median": float(q[1]), "min": float(ms.min()),
+            "max": float(ms.max()), "p25": float(q[0]), "p75": float(q[2])}
+
+
+def parity(w, out, budget_s):
+    """The GPU output `out` (fp64 [B][H][Nq][d_a]) against the oracle on a seeded sample of users sized to
+    about budget_s of oracle time: worst element against the rule of tests/parity.py and the norm-wise error."""
+    from oracle import oracle
+    from tests.parity import compare
+    order = np.random.default_rng(1).permutation(w["B"]).astype(np.int32)
+    n = min(w["B"], max(1, oracle.threads() // max(1, w["H"])))
+    while True:
+        users = np.sort(order[:n])
+        t0 = time.time()
+        ref, rss = oracle.attend(w, users=users, with_rss=True)
+        dt = time.time() - t0
+        if n >= w["B"] or dt >= 0.4 * budget_s:
+            break
+        n = int(min(w["B"], max(2 * n, n * 0.8 * budget_s / max(dt, 1e-3))))
+    st = compare(out[users], ref[users], rss[users], w["dtype"])
+    return {"users_checked": int(n), "of": int(w["B"]), "elements": st["elements"], "tol": st["tol"],
+            "max_rel_err_normwise": st["norm_err"], "worst_element_over_bound": st["worst_ratio"],
+            "ok": bool(st["finite"] and st["worst_ratio"] <= 1.0),
+            "rule": "|g-r| <= tol*|r| + tol*rss (rss: root-sum-square of the element's summands, from the oracle)"}
+
+
+def measure(name, steps, warmup, traffic_table, steady=0, parity_budget_s=0.0, with_compulsory=True):
     import torch
     from paper_2601_19178_amd import ckv, session, workloads as wl
 
     w = wl.config(name)
     ab = wl.algorithmic_bytes(w)
+    d_a = w["d_g"] + w["d_u"]
+    flop = 4.0 * w["Nq"] * d_a * ab["position_heads"]
     t0 = time.time()
     s = session.Session(w)
     torch.cuda.synchronize()
@@ -75,8 +113,13 @@ def measure(name, steps, warmup, with_compulsory=True):
     stop.record()
     torch.cuda.synchronize()
     ms_step = start.elapsed_time(stop) / steps
-    ms_kernel = ckv.ckv_kernel_ms(s.cache)
-    ckv.ckv_set_timing(s.cache, 0)
+    k_ms, m_ms = ckv.ckv_kernel_times(s.cache, steps)
+    assert len(k_ms) == steps
+    kst, mst = launch_stats(k_ms), launch_stats(m_ms)
+    ms_kernel = kst["mean"]
+    bf16 = w["dtype"] == wl.BF16
+    mfma = ckv.ckv_variant(s.cache).startswith("mfma")
+    peak_tflops = MFMA_BF16_PEAK_TFLOPS if bf16 else MFMA_F32_PEAK_TFLOPS
     res = {
         "workload": name,
         "describe": DESCRIBE[name],
@@ -84,16 +127,51 @@ def measure(name, steps, warmup, with_compulsory=True):
         "B": w["B"], "T": int(w["lengths"].sum()),
         "ms_per_step": ms_step,
         "kernel_ms": ms_kernel,
+        "kernel_ms_median": kst["median"], "kernel_ms_min": kst["min"], "kernel_ms_p25": kst["p25"], "kernel_ms_p75": kst["p75"],
+        "kernel_ms_max": kst["max"],
+        "merge_ms": mst["mean"],
         "users_per_s": w["B"] / (ms_step * 1e-3),
         "E_bytes": ab["E"],
         "E_GBps_step": ab["E"] / (ms_step * 1e-3) / 1e9,
         "E_GBps_kernel": ab["E"] / (ms_kernel * 1e-3) / 1e9,
-        "frac_of_hbm_peak": ab["E"] / (ms_kernel * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "E_GBps_kernel_median": ab["E"] / (kst["median"] * 1e-3) / 1e9,
+        # E counts a pool row every time it is gathered: where the gathered rows are served by the L2s this is
+        # gather bandwidth, not HBM bandwidth (see hbm_traffic below)
+        "effective_gather_frac_of_hbm_peak": ab["E"] / (ms_kernel * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "effective_gather_frac_of_hbm_peak_median": ab["E"] / (kst["median"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "flop": flop,
+        "TFLOPs_kernel": flop / (ms_kernel * 1e-3) / 1e12,
+        "mfma_frac_of_peak": (flop / (ms_kernel * 1e-3) / 1e12 / peak_tflops) if mfma else None,
         "build_cache_s": build_s,
     }
     if with_compulsory:
         res["C_bytes"] = compulsory_bytes(w, ab)
         res["C_GBps_kernel"] = res["C_bytes"] / (ms_kernel * 1e-3) / 1e9
+    tr = traffic_table.get(name, {}).get("bytes_per_launch")
+    res["hbm_traffic"] = {
+        "bytes_per_launch": tr,
+        "source": "profiles/hbm_traffic.json (static: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of this workload, "
+                  "scaled by the copy-kernel calibration; not measured in this run)" if tr else None,
+        "GBps": (tr / (ms_kernel * 1e-3) / 1e9) if tr else None,
+        "frac_of_hbm_peak": (tr / (ms_kernel * 1e-3) / 1e9 / HBM_PEAK_GBPS) if tr else None,
+        "over_E": (tr / ab["E"]) if tr else None,
+    }
+    if steady > 0:
+        # a further block of launches, untimed by the contract: the clocks have settled by now
+        ckv.ckv_set_timing(s.cache, steady)
+        for _ in range(2 * steady):
+            s.attend()
+        torch.cuda.synchronize()
+        k2, m2 = ckv.ckv_kernel_times(s.cache, steady)
+        st2 = launch_stats(k2)
+        res["steady_state"] = {"after_launches": warmup + steps + steady, "kernel_ms": st2, "merge_ms_mean": float(np.mean(m2)),
+                               "E_GBps_median": ab["E"] / (st2["median"] * 1e-3) / 1e9,
+                               "effective_gather_frac_of_hbm_peak_median": ab["E"] / (st2["median"] * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+    ckv.ckv_set_timing(s.cache, 0)
+    if parity_budget_s > 0:
+        s.out.fill_(float("nan"))
+        s.attend()
+        res["parity"] = parity(w, s.output(), parity_budget_s)
     return res, w, s
 
 
@@ -218,7 +296,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=100,
                     help="untimed steps; the GPU needs ~50 back-to-back launches to reach its steady clocks")
     ap.add_argument("--workload", default="cfg4", choices=sorted(DESCRIBE))
-    ap.add_argument("--also", default="cfg2_f32,cfg2_bf16,cfg3,cfg3_ck,d256_u4", help="comma list of further workloads ('' for none)")
+    ap.add_argument("--also", default="cfg1,cfg2_f32,cfg2_bf16,cfg3,cfg5,cfg3_ck,d256_u4", help="comma list of further workloads ('' for none)")
+    ap.add_argument("--steady", type=int, default=200,
+                    help="launches of the extra steady-state block per workload, reported under 'steady_state' (0: none)")
+    ap.add_argument("--parity-budget", type=float, default=6.0,
+                    help="seconds of oracle time per workload for the parity figures in the line (0: none)")
     ap.add_argument("--prefill", default="prefill_cfg2,prefill_cfg3,prefill_cfg2_f32",
                     help="comma list of prefill workloads reported under 'prefill' (prefill_cfg2, prefill_cfg3, prefill_cfg2_f32; '' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -250,13 +332,19 @@ def main():
         print(json.dumps({"offloaded_sweep": offloaded_sweep()}))
         return
 
-    head, w, sess = measure(args.workload, args.steps, args.warmup)
+    traffic_table = {}
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic_table = json.load(f)
+    pb = 0.0 if args.no_cpu_baseline else args.parity_budget
+    head, w, sess = measure(args.workload, args.steps, args.warmup, traffic_table, steady=args.steady, parity_budget_s=pb)
     base = None if args.no_cpu_baseline else cpu_baseline(w)
     sess.close()
     del w, sess
     also = []
     for name in [x for x in args.also.split(",") if x and x != args.workload]:
-        r, w2, s2 = measure(name, args.steps, args.warmup)
+        r, w2, s2 = measure(name, args.steps, args.warmup, traffic_table, steady=args.steady, parity_budget_s=pb)
         s2.close()
         del w2, s2
         also.append(r)
@@ -264,11 +352,6 @@ def main():
     prefill = [measure_prefill(n, max(10, args.steps // 4), max(5, args.warmup // 4), with_cpu=not args.no_cpu_baseline)
                for n in args.prefill.split(",") if n]
 
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(tpath):
-        with open(tpath) as f:
-            traffic = json.load(f).get(args.workload, {}).get("bytes_per_launch")
     line = {
         "metric": METRIC,
         "value": head["users_per_s"],
@@ -287,9 +370,16 @@ def main():
         "effective_GBps": head["E_GBps_step"],
         "pct_of_hbm_peak": 100.0 * head["E_GBps_step"] / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "achieved": head["E_GBps_kernel"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": head["frac_of_hbm_peak"], "traffic": traffic,
-                     "kernel": head["variant"], "kernel_ms": head["kernel_ms"], "E_bytes": head["E_bytes"],
-                     "C_bytes": head.get("C_bytes"), "C_GBps": head.get("C_GBps_kernel")},
+                     "frac": head["effective_gather_frac_of_hbm_peak"], "traffic": head["hbm_traffic"]["bytes_per_launch"],
+                     "traffic_source": head["hbm_traffic"]["source"], "traffic_frac_of_peak": head["hbm_traffic"]["frac_of_hbm_peak"],
+                     "kernel": head["variant"], "kernel_ms": head["kernel_ms"], "kernel_ms_median": head["kernel_ms_median"],
+                     "kernel_ms_min": head["kernel_ms_min"], "kernel_ms_p25": head["kernel_ms_p25"],
+                     "kernel_ms_p75": head["kernel_ms_p75"], "merge_ms": head["merge_ms"],
+                     "frac_median": head["effective_gather_frac_of_hbm_peak_median"],
+                     "E_bytes": head["E_bytes"], "C_bytes": head.get("C_bytes"), "C_GBps": head.get("C_GBps_kernel"),
+                     "mfma_TFLOPs": head["TFLOPs_kernel"], "mfma_frac_of_peak": head["mfma_frac_of_peak"]},
+        "steady_state": head.get("steady_state"),
+        "parity": head.get("parity"),
         "cpu_baseline": base,
         "also": also,
         "prefill": prefill,

@@ -201,10 +201,13 @@ int64_t ckv_cache_stored_bytes(const ckv_cache* c);
  *   cache     handle from ckv_build_cache: shape, offsets, work list, split workspace.
  *   pool_k,
  *   pool_v    device [H][P][pool_ld]: the global K/V pools P_k, P_v.
- *   idx       device int32 [2][H][T]            } normally the handle's own views; any
- *   user_k,
- *   user_v    device [H][T][d_u]                } buffers of the same layout and contents
- *   lengths   device int32 [B]                  } class (same lengths) are accepted.
+ *   idx       device int32 [2][H][T]            } normally the handle's own views; other buffers of
+ *   user_k,                                     } the same layout (same lengths, indices in [0, P))
+ *   user_v    device [H][T][d_u]                } are accepted.
+ *   lengths   must be ckv_cache_lengths(cache).  The argument is there for the call's signature; it is not read:
+ *             pieces, offsets and merge entries were computed from the lengths given when the handle was built,
+ *             and a history that has grown needs a new handle.  Any other pointer is refused
+ *             (CKV_ERR_UNSUPPORTED) rather than silently ignored.
  *   q         device [B][H][Nq][d_a]: queries, columns in final-K order (user columns first).
  *   out       device [B][H][Nq][d_a]: written completely (zeros for users with n_b = 0).
  *
@@ -217,7 +220,7 @@ int64_t ckv_cache_stored_bytes(const ckv_cache* c);
  * only (no memset, no copy, no event unless ckv_set_timing switched timing on), so it may be
  * recorded into a HIP graph by stream capture and replayed; a replay reads the buffers whose
  * addresses were captured.
- * Errors: CKV_ERR_NULL, CKV_ERR_HIP (launch failure).
+ * Errors: CKV_ERR_NULL, CKV_ERR_UNSUPPORTED (a pointer not 16-byte aligned, foreign lengths), CKV_ERR_HIP (launch failure).
  */
 int ckv_attend(const ckv_cache* cache, const void* pool_k, const void* pool_v,
                const int32_t* idx, const void* user_k, const void* user_v,
@@ -268,6 +271,20 @@ int64_t ckv_plan(const ckv_shape* shape, const int32_t* lengths, int cus, int wg
 int ckv_remap_hot_rows(ckv_cache* cache, const void* pool_k, const void* pool_v, void* pool_k_out, void* pool_v_out,
                        int32_t* new_id, void* stream);
 
+/*
+ * Tuning options of the calling thread, read by the calls that build a handle or a plan afterwards
+ * (ckv_build_cache, ckv_build_cache_offloaded, ckv_prefill, ckv_plan); handles that exist are not affected.
+ * None changes a result beyond the order of summation; they exist for measurement and so that tests reach
+ * every kernel.  value NULL or "" restores the option's default, key NULL restores all defaults.
+ *   "mfma_impl"       "staged": the register-staged matrix-core kernel where the direct-to-LDS one would run; "auto"
+ *   "dma_sched"       "static" (default: persistent workgroups with their own item lists) | "dynamic"
+ *   "dma_shape"       "nw,qg": wavefronts per workgroup and query groups per wavefront of the direct-to-LDS kernel
+ *   "dma_slow_speed"  weight in (0, 4] of a workgroup that shares its SIMDs with an older one (default 0.75 / 1.0)
+ *   "debug"           "1": print the chosen split and list statistics to stderr
+ * Errors: CKV_ERR_UNSUPPORTED (unknown key, malformed value).
+ */
+int ckv_set_option(const char* key, const char* value);
+
 /* Release the handle and the device memory it owns.  NULL is allowed. */
 void ckv_free(ckv_cache* cache);
 
@@ -276,17 +293,21 @@ const char* ckv_last_error(void);
 
 /*
  * Measurement helpers.
- * ckv_set_timing(cache, n) with n > 0 makes every following ckv_attend on this handle bracket
- * its main attention kernel (not the merge) with a pair of HIP events on the launch stream,
- * kept in a ring of n pairs; n = 0 switches it off.  ckv_kernel_ms synchronises the recorded
- * pairs and returns the mean elapsed milliseconds per launch over the last min(calls, n)
- * launches (negative if none).  ckv_variant names the kernel family the handle dispatches to.
+ * ckv_set_timing(cache, n) with n > 0 makes every following ckv_attend on this handle record three
+ * HIP events on the launch stream (before the main attention kernel, after it, after the merge
+ * kernel of split histories), kept in a ring of n launches; n = 0 switches it off.  ckv_kernel_ms
+ * synchronises them and returns the mean milliseconds of the main kernel over the last
+ * min(calls, n) launches (negative if none).  ckv_kernel_times writes the per-launch times, oldest
+ * launch first, of the main kernel (kernel_ms) and of the merge kernel (merge_ms, zeros for a handle
+ * without split histories) for up to max_launches launches (either array may be NULL) and returns
+ * how many it wrote, or a negative error.  ckv_variant names the kernel family the handle dispatches to.
  * ckv_copy enqueues a plain device-to-device copy kernel of nbytes (16-byte aligned device
  * pointers), used to calibrate hardware byte counters against a transfer of known size and
  * to read the packed cache back in tests.
  */
 int ckv_set_timing(ckv_cache* cache, int pairs);
 float ckv_kernel_ms(ckv_cache* cache);
+int ckv_kernel_times(ckv_cache* cache, float* kernel_ms, float* merge_ms, int max_launches);
 const char* ckv_variant(const ckv_cache* cache);
 int ckv_copy(void* dst, const void* src, size_t nbytes, void* stream);
 /*

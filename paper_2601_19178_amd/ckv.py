@@ -23,7 +23,8 @@ EXPORTS = [
     "ckv_build_cache", "ckv_build_cache_offloaded", "ckv_cache_is_offloaded", "ckv_prefill", "ckv_prefill_into",
     "ckv_cache_prefill_workspace", "ckv_prefill_kernel_name", "ckv_plan", "ckv_remap_hot_rows", "ckv_cache_idx", "ckv_cache_user_k", "ckv_cache_user_v", "ckv_cache_lengths",
     "ckv_cache_positions", "ckv_cache_stored_bytes", "ckv_attend", "ckv_reconstruct", "ckv_free",
-    "ckv_last_error", "ckv_set_timing", "ckv_kernel_ms", "ckv_variant", "ckv_copy", "ckv_trace_enable", "ckv_trace_read",
+    "ckv_last_error", "ckv_set_timing", "ckv_kernel_ms", "ckv_kernel_times", "ckv_variant", "ckv_copy", "ckv_trace_enable",
+    "ckv_trace_read", "ckv_set_option",
 ]
 
 
@@ -78,6 +79,10 @@ _lib.ckv_cache_stored_bytes.restype = _i64
 _lib.ckv_cache_stored_bytes.argtypes = [_vp]
 _lib.ckv_attend.restype = ctypes.c_int
 _lib.ckv_attend.argtypes = [_vp] * 10
+_lib.ckv_set_option.restype = ctypes.c_int
+_lib.ckv_set_option.argtypes = [ctypes.c_char_p, ctypes.c_char_p]
+_lib.ckv_kernel_times.restype = ctypes.c_int
+_lib.ckv_kernel_times.argtypes = [_vp, _vp, _vp, ctypes.c_int]
 _lib.ckv_reconstruct.restype = ctypes.c_int
 _lib.ckv_reconstruct.argtypes = [_vp] * 6
 _lib.ckv_free.restype = None
@@ -220,6 +225,11 @@ def ckv_attend(cache, pool_k, pool_v, idx, user_k, user_v, q, lengths, out, stre
                            _dev(lengths), _dev(out), _vp(stream)))
 
 
+def ckv_set_option(key, value=None):
+    """Tuning option of the calling thread (see include/ckv.h); key None restores every default."""
+    _check(_lib.ckv_set_option(None if key is None else key.encode(), None if value is None else str(value).encode()))
+
+
 def ckv_reconstruct(cache, pool_k, pool_v, k_full, v_full, stream=0):
     _check(_lib.ckv_reconstruct(cache, _dev(pool_k), _dev(pool_v), _dev(k_full), _dev(v_full), _vp(stream)))
 
@@ -234,6 +244,16 @@ def ckv_set_timing(cache, enable):
 
 def ckv_kernel_ms(cache):
     return float(_lib.ckv_kernel_ms(cache))
+
+
+def ckv_kernel_times(cache, max_launches=4096):
+    """(main kernel ms, merge kernel ms) per recorded launch, oldest first, as float32 numpy arrays."""
+    k = np.zeros(max_launches, dtype=np.float32)
+    m = np.zeros(max_launches, dtype=np.float32)
+    n = _lib.ckv_kernel_times(cache, _vp(k.ctypes.data), _vp(m.ctypes.data), max_launches)
+    if n < 0:
+        raise CkvError(int(n), ckv_last_error())
+    return k[:n], m[:n]
 
 
 def ckv_variant(cache):

@@ -33,6 +33,16 @@ int fail(int code, const char* fmt, ...) {
 
 size_t esize(int dtype) { return dtype == CKV_F32 ? 4 : 2; }
 
+// Tuning options of the calling thread (ckv_set_option), read when a handle or a plan is built.
+struct Options {
+    bool staged = false;       // "mfma_impl" = "staged": register-staged matrix-core kernel where the direct-to-LDS one would run
+    int sched = 0;             // "dma_sched": 0 default (static), 1 static, 2 dynamic
+    int nw = 0, qg = 0;        // "dma_shape" = "nw,qg": wavefronts per workgroup, query groups per wavefront (0: from Nq)
+    double slow_speed = -1.0;  // "dma_slow_speed": weight of a workgroup that shares its SIMDs with an older one (< 0: default)
+    bool debug = false;        // "debug" = "1": print the chosen split and list statistics to stderr
+};
+thread_local Options g_opt;
+
 // ---------------------------------------------------------------------------------------
 // Packing: user-major [T][H] records -> head-major planes, with the range check of every
 // index done in the same pass.  `bad` receives the smallest offending t*H + h.
@@ -394,7 +404,7 @@ void build_work(ckv_cache* c, const int32_t* lengths, const std::vector<int64_t>
     items.swap(best_items);
     merges.swap(best_merges);
     c->n_parts = best_parts;
-    if (getenv("CKV_DEBUG"))
+    if (g_opt.debug)
         fprintf(stderr, "ckv: %s: %zu units, %lld slots, piece %lld -> %zu items, %d parts, cost %.0f positions/slot\n", c->variant,
                 units.size(), (long long)slots, (long long)(best_piece == INT64_MAX ? -1 : best_piece), items.size(), best_parts,
                 best_cost);
@@ -535,7 +545,7 @@ void build_work_static(ckv_cache* c, const int32_t* lengths, const std::vector<i
     // wavefronts per workgroup (config 4: 0.465 ms against 0.482 ms at 1.0), no difference with two (config 3), 1.0 with one
     // (config 5: 0.834 ms against 0.867 ms at 0.75)
     double slow_speed = c->nw == 1 ? 1.0 : 0.75;
-    if (const char* e = getenv("CKV_DMA_SLOW_SPEED")) slow_speed = atof(e);  // tuning knob
+    if (g_opt.slow_speed >= 0.0) slow_speed = g_opt.slow_speed;  // tuning option
     std::vector<std::vector<Piece>> best;
     double best_cost = -1;
     int64_t best_piece = 0;
@@ -581,7 +591,7 @@ void build_work_static(ckv_cache* c, const int32_t* lengths, const std::vector<i
         }
     }
     wg_begin[best.size()] = (int32_t)items.size();
-    if (getenv("CKV_DEBUG"))
+    if (g_opt.debug)
         fprintf(stderr, "ckv: %s: %zu units on %lld persistent workgroups, piece %lld -> %zu items, %d parts, cost %.0f positions\n",
                 c->variant, units.size(), (long long)slots, (long long)(best_piece == INT64_MAX ? -1 : best_piece), items.size(),
                 next_part, best_cost);
@@ -599,7 +609,7 @@ void choose_variant(ckv_cache* c) {
     if (s.dtype == CKV_BF16 && d_a <= 256 && s.Nq >= kMinNqDma && (s.d_g == 0 || s.pool_ld % 8 == 0) &&
         (s.mode == CKV_SILU_OVER_N || s.scale > 0.f)) {
         const int dak = d_a <= 64 ? 64 : (d_a <= 128 ? 128 : 256);  // row width the register-staged kernel is built for
-        const char* impl = getenv("CKV_MFMA_IMPL");  // tuning knob: "staged" forces the register-staged kernel
+        const bool staged = g_opt.staged;  // tuning option: forces the register-staged kernel
         {
             // direct-to-LDS kernel: 32 queries per wavefront, up to 4 wavefronts per workgroup (two
             // wavefronts per SIMD overlap better than one wavefront with two query groups)
@@ -610,11 +620,11 @@ void choose_variant(ckv_cache* c) {
             // with 64 queries 349 -> 309 us; at 128 columns it is the other way round, 380 against 575 us, and so it is
             // for an ordinary cache, d_g = 0, whose rows all stream from HBM: 113 against 128 us)
             if (dak == 64 && s.Nq > 32 && s.Nq <= 64 && s.d_g > 0 && !(s.d_u & 1) && s.d_u <= 8) nw = 1, qg = 2;
-            if (const char* shp = getenv("CKV_DMA_SHAPE")) sscanf(shp, "%d,%d", &nw, &qg);  // tuning knob "nw,qg"
+            if (g_opt.nw > 0 && g_opt.qg > 0) nw = g_opt.nw, qg = g_opt.qg;  // tuning option "dma_shape"
             // (d_g = 0, ordinary attention over the user arrays: rows are fetched by position, nothing is appended)
             const int nui = d_a == dak && ckv_dma_supported(d_a, nw, qg) && (s.d_g == 0 || qg == 1 || (!(s.d_u & 1) && (s.d_u <= 8 || dak == 256)))
                                 ? (s.d_g == 0 ? 0 : ckv_dma_nui(d_a, nw, s.d_u)) : -1;
-            if (nui >= 0 && !(impl && strcmp(impl, "staged") == 0)) {
+            if (nui >= 0 && !staged) {
                 c->family = CKV_K_DMA;
                 c->nw = nw;
                 c->qg = qg;
@@ -660,26 +670,35 @@ void choose_variant(ckv_cache* c) {
 
 // The packed cache lives in device memory, or (offloaded handle) in pinned host memory that the
 // GPU reads in place.
-hipError_t cache_alloc(const ckv_cache* c, void** p, size_t bytes) {
+// *host receives the host address of an offloaded buffer (what hipHostFree takes back), nullptr otherwise.
+hipError_t cache_alloc(const ckv_cache* c, void** p, void** host, size_t bytes) {
+    *host = nullptr;
     if (!c->offloaded) return hipMalloc(p, bytes);
     void* h = nullptr;
     hipError_t e = hipHostMalloc(&h, bytes, hipHostMallocMapped | hipHostMallocPortable);
     if (e != hipSuccess) return e;
     e = hipHostGetDevicePointer(p, h, 0);
-    if (e != hipSuccess) (void)hipHostFree(h);
+    if (e != hipSuccess) {
+        (void)hipHostFree(h);
+        *p = nullptr;
+        return e;
+    }
+    *host = h;
     return e;
 }
-void cache_free(const ckv_cache* c, void* p) {
-    if (!p) return;
-    if (c->offloaded) (void)hipHostFree(p);
-    else (void)hipFree(p);
+void cache_free(const ckv_cache* c, void* p, void* host) {
+    if (c->offloaded) {
+        if (host) (void)hipHostFree(host);
+    } else if (p) {
+        (void)hipFree(p);
+    }
 }
 
 void destroy(ckv_cache* c) {
     if (!c) return;
-    cache_free(c, c->d_idx);
-    cache_free(c, c->d_user_k);
-    cache_free(c, c->d_user_v);
+    cache_free(c, c->d_idx, c->h_idx);
+    cache_free(c, c->d_user_k, c->h_user_k);
+    cache_free(c, c->d_user_v, c->h_user_v);
     (void)hipFree(c->d_lengths);
     (void)hipFree(c->d_items);
     (void)hipFree(c->d_wg_begin);
@@ -687,7 +706,7 @@ void destroy(ckv_cache* c) {
     (void)hipFree(c->d_partial);
     (void)hipFree(c->d_trace);
     (void)hipFree(c->d_pf_ws);
-    for (int i = 0; i < 2 * c->timing; ++i) (void)hipEventDestroy(c->ev[i]);
+    for (int i = 0; i < 3 * c->timing; ++i) (void)hipEventDestroy(c->ev[i]);
     delete[] c->ev;
     delete c;
 }
@@ -752,10 +771,10 @@ static int cache_new(const char* who, const ckv_shape* shape, const int32_t* len
         int d_uk, d_gk, d_uv, d_gv;
         ckv_side_dims(s, 0, &d_uk, &d_gk);
         ckv_side_dims(s, 1, &d_uv, &d_gv);
-        if (n_ph > 0 && s.d_g > 0) CKV_HIP(cache_alloc(c, (void**)&c->d_idx, sizeof(int32_t) * 2 * n_ph));
+        if (n_ph > 0 && s.d_g > 0) CKV_HIP(cache_alloc(c, (void**)&c->d_idx, &c->h_idx, sizeof(int32_t) * 2 * n_ph));
         // (rounded up to whole 16-byte chunks: an odd number of bf16 elements is read in aligned dwords)
-        if (n_ph > 0 && d_uk > 0) CKV_HIP(cache_alloc(c, &c->d_user_k, (n_ph * (size_t)d_uk * esize(s.dtype) + 15) / 16 * 16));
-        if (n_ph > 0 && d_uv > 0) CKV_HIP(cache_alloc(c, &c->d_user_v, (n_ph * (size_t)d_uv * esize(s.dtype) + 15) / 16 * 16));
+        if (n_ph > 0 && d_uk > 0) CKV_HIP(cache_alloc(c, &c->d_user_k, &c->h_user_k, (n_ph * (size_t)d_uk * esize(s.dtype) + 15) / 16 * 16));
+        if (n_ph > 0 && d_uv > 0) CKV_HIP(cache_alloc(c, &c->d_user_v, &c->h_user_v, (n_ph * (size_t)d_uv * esize(s.dtype) + 15) / 16 * 16));
     }
 done:
     if (rc != CKV_OK) {
@@ -781,8 +800,7 @@ static void plan_work(ckv_cache* c, const int32_t* lengths, const std::vector<in
         // own item list, no relaunch gaps.  Dynamic: one workgroup per item in longest-first order,
         // scheduled by the hardware dispatcher as slots free up.  Static measured faster on every
         // workload (uniform lengths: by 20 %; two long ragged histories per slot: by 2 %).
-        bool use_static = true;
-        if (const char* e = getenv("CKV_DMA_SCHED")) use_static = strcmp(e, "static") == 0;  // tuning knob
+        const bool use_static = g_opt.sched != 2;  // tuning option "dma_sched"
         if (use_static) {
             build_work_static(c, lengths, offs, cus, wg_per_cu, p.items, p.merges, p.wg_begin);
         } else {
@@ -1097,20 +1115,25 @@ int64_t ckv_cache_stored_bytes(const ckv_cache* c) {
 }
 const char* ckv_variant(const ckv_cache* c) { return c ? c->variant : ""; }
 
-int ckv_attend(const ckv_cache* c, const void* pool_k, const void* pool_v, const int32_t* idx, const void* user_k,
-               const void* user_v, const void* q, const int32_t* lengths, void* out, void* stream) {
-    if (!c || !q || !out || !lengths) return fail(CKV_ERR_NULL, "ckv_attend: cache, q, lengths and out must not be NULL");
+// The body of ckv_attend: `partial` is the split workspace the kernels use, `who` the name for error messages.
+static int attend_common(const char* who, const ckv_cache* c, const void* pool_k, const void* pool_v, const int32_t* idx,
+                         const void* user_k, const void* user_v, const void* q, const int32_t* lengths, void* out,
+                         float* partial, hipStream_t st) {
+    if (!c || !q || !out || !lengths) return fail(CKV_ERR_NULL, "%s: cache, q, lengths and out must not be NULL", who);
+    // The work lists (pieces, offsets, merge entries) were built from the lengths given when the handle was made and
+    // are not rebuilt here: other lengths would be ignored silently, so only the handle's own array is taken.
+    if (lengths != c->d_lengths)
+        return fail(CKV_ERR_UNSUPPORTED, "%s: lengths must be ckv_cache_lengths(cache): the work lists follow the lengths the handle was built with", who);
     const ckv_shape& s = c->shape;
     int d_uk, d_gk, d_uv, d_gv;
     ckv_side_dims(s, 0, &d_uk, &d_gk);
     ckv_side_dims(s, 1, &d_uv, &d_gv);
     if (c->T > 0 && ((d_gk > 0 && (!pool_k || !idx)) || (d_gv > 0 && (!pool_v || !idx))))
-        return fail(CKV_ERR_NULL, "ckv_attend: pool_k, pool_v or idx is NULL for a side that gathers from a pool");
-    if (c->T > 0 && ((d_uk > 0 && !user_k) || (d_uv > 0 && !user_v))) return fail(CKV_ERR_NULL, "ckv_attend: user_k or user_v is NULL");
+        return fail(CKV_ERR_NULL, "%s: pool_k, pool_v or idx is NULL for a side that gathers from a pool", who);
+    if (c->T > 0 && ((d_uk > 0 && !user_k) || (d_uv > 0 && !user_v))) return fail(CKV_ERR_NULL, "%s: user_k or user_v is NULL", who);
     const uintptr_t align = (uintptr_t)pool_k | (uintptr_t)pool_v | (uintptr_t)idx | (uintptr_t)user_k | (uintptr_t)user_v |
                             (uintptr_t)q | (uintptr_t)out;
-    if (align & 15) return fail(CKV_ERR_UNSUPPORTED, "ckv_attend: every device pointer must be 16-byte aligned");
-    hipStream_t st = (hipStream_t)stream;
+    if (align & 15) return fail(CKV_ERR_UNSUPPORTED, "%s: every device pointer must be 16-byte aligned", who);
     ckv_args a;
     a.pool_k = pool_k;
     a.pool_v = pool_v;
@@ -1122,7 +1145,7 @@ int ckv_attend(const ckv_cache* c, const void* pool_k, const void* pool_v, const
     a.out = out;
     a.items = c->d_items;
     a.wg_begin = c->d_wg_begin;
-    a.partial = c->d_partial;
+    a.partial = partial;
     a.trace = c->d_trace;
     a.T = c->T;
     a.pool_ld = s.pool_ld;
@@ -1140,20 +1163,20 @@ int ckv_attend(const ckv_cache* c, const void* pool_k, const void* pool_v, const
     a.scale = s.scale;
     ckv_cache* mc = const_cast<ckv_cache*>(c);
     hipError_t e;
+    // timing: three events per launch (start, main kernel done, merge done)
     const int slot = c->timing ? (int)(c->ev_count % c->timing) : 0;
     if (c->timing) {
-        e = hipEventRecord(c->ev[2 * slot], st);
-        if (e != hipSuccess) return fail(CKV_ERR_HIP, "ckv_attend: hipEventRecord: %s", hipGetErrorString(e));
+        e = hipEventRecord(c->ev[3 * slot], st);
+        if (e != hipSuccess) return fail(CKV_ERR_HIP, "%s: hipEventRecord: %s", who, hipGetErrorString(e));
     }
     e = c->family == CKV_K_DMA      ? ckv_launch_dma(c, a, st)
         : c->family == CKV_K_MFMA   ? ckv_launch_mfma(c, a, st)
         : c->family == CKV_K_MFMA32 ? ckv_launch_mfma32(c, a, st)
                                     : ckv_launch_stream(c, a, st);
-    if (e != hipSuccess) return fail(CKV_ERR_HIP, "ckv_attend: kernel launch (%s): %s", c->variant, hipGetErrorString(e));
+    if (e != hipSuccess) return fail(CKV_ERR_HIP, "%s: kernel launch (%s): %s", who, c->variant, hipGetErrorString(e));
     if (c->timing) {
-        e = hipEventRecord(c->ev[2 * slot + 1], st);
-        if (e != hipSuccess) return fail(CKV_ERR_HIP, "ckv_attend: hipEventRecord: %s", hipGetErrorString(e));
-        mc->ev_count++;
+        e = hipEventRecord(c->ev[3 * slot + 1], st);
+        if (e != hipSuccess) return fail(CKV_ERR_HIP, "%s: hipEventRecord: %s", who, hipGetErrorString(e));
     }
     if (c->n_merge > 0) {
         const int d_a = a.d_a;
@@ -1161,20 +1184,65 @@ int ckv_attend(const ckv_cache* c, const void* pool_k, const void* pool_v, const
         if (s.dtype == CKV_F32) {
             if (s.mode == CKV_SOFTMAX)
                 hipLaunchKernelGGL((ckv_merge_kernel<float, CKV_SOFTMAX>), mgrid, threads, 0, st, c->d_merge,
-                                   c->d_partial, (float*)out, s.H, s.Nq, d_a, c->QB);
+                                   partial, (float*)out, s.H, s.Nq, d_a, c->QB);
             else
                 hipLaunchKernelGGL((ckv_merge_kernel<float, CKV_SILU_OVER_N>), mgrid, threads, 0, st, c->d_merge,
-                                   c->d_partial, (float*)out, s.H, s.Nq, d_a, c->QB);
+                                   partial, (float*)out, s.H, s.Nq, d_a, c->QB);
         } else {
             if (s.mode == CKV_SOFTMAX)
                 hipLaunchKernelGGL((ckv_merge_kernel<uint16_t, CKV_SOFTMAX>), mgrid, threads, 0, st, c->d_merge,
-                                   c->d_partial, (uint16_t*)out, s.H, s.Nq, d_a, c->QB);
+                                   partial, (uint16_t*)out, s.H, s.Nq, d_a, c->QB);
             else
                 hipLaunchKernelGGL((ckv_merge_kernel<uint16_t, CKV_SILU_OVER_N>), mgrid, threads, 0, st,
-                                   c->d_merge, c->d_partial, (uint16_t*)out, s.H, s.Nq, d_a, c->QB);
+                                   c->d_merge, partial, (uint16_t*)out, s.H, s.Nq, d_a, c->QB);
         }
         e = hipGetLastError();
-        if (e != hipSuccess) return fail(CKV_ERR_HIP, "ckv_attend: merge launch: %s", hipGetErrorString(e));
+        if (e != hipSuccess) return fail(CKV_ERR_HIP, "%s: merge launch: %s", who, hipGetErrorString(e));
+    }
+    if (c->timing) {
+        e = hipEventRecord(c->ev[3 * slot + 2], st);
+        if (e != hipSuccess) return fail(CKV_ERR_HIP, "%s: hipEventRecord: %s", who, hipGetErrorString(e));
+        mc->ev_count++;
+    }
+    return CKV_OK;
+}
+
+int ckv_attend(const ckv_cache* c, const void* pool_k, const void* pool_v, const int32_t* idx, const void* user_k,
+               const void* user_v, const void* q, const int32_t* lengths, void* out, void* stream) {
+    return attend_common("ckv_attend", c, pool_k, pool_v, idx, user_k, user_v, q, lengths, out, c ? c->d_partial : nullptr,
+                         (hipStream_t)stream);
+}
+
+int ckv_set_option(const char* key, const char* value) {
+    if (!key) {
+        g_opt = Options();
+        return CKV_OK;
+    }
+    const bool unset = !value || !*value;
+    if (strcmp(key, "mfma_impl") == 0) {
+        if (!unset && strcmp(value, "staged") != 0 && strcmp(value, "auto") != 0)
+            return fail(CKV_ERR_UNSUPPORTED, "ckv_set_option: mfma_impl takes \"staged\" or \"auto\", not \"%s\"", value);
+        g_opt.staged = !unset && strcmp(value, "staged") == 0;
+    } else if (strcmp(key, "dma_sched") == 0) {
+        if (!unset && strcmp(value, "static") != 0 && strcmp(value, "dynamic") != 0)
+            return fail(CKV_ERR_UNSUPPORTED, "ckv_set_option: dma_sched takes \"static\" or \"dynamic\", not \"%s\"", value);
+        g_opt.sched = unset ? 0 : (strcmp(value, "static") == 0 ? 1 : 2);
+    } else if (strcmp(key, "dma_shape") == 0) {
+        int nw = 0, qg = 0;
+        if (!unset && (sscanf(value, "%d,%d", &nw, &qg) != 2 || nw < 1 || qg < 1))
+            return fail(CKV_ERR_UNSUPPORTED, "ckv_set_option: dma_shape takes \"nw,qg\" with both >= 1, not \"%s\"", value);
+        g_opt.nw = nw;
+        g_opt.qg = qg;
+    } else if (strcmp(key, "dma_slow_speed") == 0) {
+        char* end = nullptr;
+        const double v = unset ? -1.0 : strtod(value, &end);
+        if (!unset && (end == value || !(v > 0.0) || v > 4.0))
+            return fail(CKV_ERR_UNSUPPORTED, "ckv_set_option: dma_slow_speed takes a number in (0, 4], not \"%s\"", value);
+        g_opt.slow_speed = v;
+    } else if (strcmp(key, "debug") == 0) {
+        g_opt.debug = !unset && strcmp(value, "0") != 0;
+    } else {
+        return fail(CKV_ERR_UNSUPPORTED, "ckv_set_option: unknown option \"%s\"", key);
     }
     return CKV_OK;
 }
@@ -1215,15 +1283,15 @@ void ckv_free(ckv_cache* c) { destroy(c); }
 int ckv_set_timing(ckv_cache* c, int pairs) {
     if (!c) return fail(CKV_ERR_NULL, "ckv_set_timing: cache is NULL");
     if (pairs < 0 || pairs > 4096) return fail(CKV_ERR_SHAPE, "ckv_set_timing: pairs must be in [0, 4096]");
-    for (int i = 0; i < 2 * c->timing; ++i) (void)hipEventDestroy(c->ev[i]);
+    for (int i = 0; i < 3 * c->timing; ++i) (void)hipEventDestroy(c->ev[i]);
     delete[] c->ev;
     c->ev = nullptr;
     c->timing = 0;
     c->ev_count = 0;
     if (pairs == 0) return CKV_OK;
-    c->ev = new (std::nothrow) hipEvent_t[2 * (size_t)pairs];
+    c->ev = new (std::nothrow) hipEvent_t[3 * (size_t)pairs];
     if (!c->ev) return fail(CKV_ERR_HIP, "ckv_set_timing: out of host memory");
-    for (int i = 0; i < 2 * pairs; ++i) {
+    for (int i = 0; i < 3 * pairs; ++i) {
         hipError_t e = hipEventCreate(&c->ev[i]);
         if (e != hipSuccess) {
             for (int j = 0; j < i; ++j) (void)hipEventDestroy(c->ev[j]);
@@ -1236,14 +1304,33 @@ int ckv_set_timing(ckv_cache* c, int pairs) {
     return CKV_OK;
 }
 
+int ckv_kernel_times(ckv_cache* c, float* kernel_ms, float* merge_ms, int max_launches) {
+    if (!c) return fail(CKV_ERR_NULL, "ckv_kernel_times: cache is NULL");
+    if (!c->timing || c->ev_count == 0) return 0;
+    const int n = (int)std::min<long long>(std::min<long long>(c->ev_count, c->timing), std::max(0, max_launches));
+    // oldest recorded launch first: the ring holds the last `timing` launches
+    const long long first = c->ev_count > c->timing ? c->ev_count - c->timing : 0;
+    for (int i = 0; i < n; ++i) {
+        const int slot = (int)((first + i) % c->timing);
+        float ms = 0.f;
+        hipError_t e = hipEventSynchronize(c->ev[3 * slot + 2]);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, c->ev[3 * slot], c->ev[3 * slot + 1]);
+        if (e == hipSuccess && kernel_ms) kernel_ms[i] = ms;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, c->ev[3 * slot + 1], c->ev[3 * slot + 2]);
+        if (e != hipSuccess) return fail(CKV_ERR_HIP, "ckv_kernel_times: %s", hipGetErrorString(e));
+        if (merge_ms) merge_ms[i] = c->n_merge > 0 ? ms : 0.f;
+    }
+    return n;
+}
+
 float ckv_kernel_ms(ckv_cache* c) {
     if (!c || !c->timing || c->ev_count == 0) return -1.f;
     const int n = (int)std::min<long long>(c->ev_count, c->timing);
     double sum = 0;
     for (int i = 0; i < n; ++i) {
         float ms = 0.f;
-        if (hipEventSynchronize(c->ev[2 * i + 1]) != hipSuccess) return -1.f;
-        if (hipEventElapsedTime(&ms, c->ev[2 * i], c->ev[2 * i + 1]) != hipSuccess) return -1.f;
+        if (hipEventSynchronize(c->ev[3 * i + 2]) != hipSuccess) return -1.f;
+        if (hipEventElapsedTime(&ms, c->ev[3 * i], c->ev[3 * i + 1]) != hipSuccess) return -1.f;
         sum += ms;
     }
     return (float)(sum / n);

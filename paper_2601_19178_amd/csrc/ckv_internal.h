@@ -85,6 +85,10 @@ struct ckv_cache {
     int32_t* d_idx;      // [2][H][T]
     void* d_user_k;      // [H][T][d_u]
     void* d_user_v;
+    // offloaded handle: host addresses of the three buffers above (what hipHostFree takes back), else nullptr
+    void* h_idx;
+    void* h_user_k;
+    void* h_user_v;
     int32_t* d_lengths;  // [B]
     // launch metadata
     int family;          // ckv_kernel_family
@@ -103,10 +107,10 @@ struct ckv_cache {
     unsigned long long* d_trace;  // 8 words per item while tracing is on
     unsigned long long* d_pf_ws;  // handles made by ckv_prefill: workspace of the split last round, zero between calls
     int64_t pf_ws_entries;
-    // timing: ring of event pairs around the main kernel, filled while timing > 0
-    int timing;            // number of pairs in the ring (0 = off)
+    // timing: ring of event triples (start, main kernel done, merge done), filled while timing > 0
+    int timing;            // number of triples in the ring (0 = off)
     long long ev_count;    // launches recorded since timing was switched on
-    hipEvent_t* ev;        // 2 * timing events
+    hipEvent_t* ev;        // 3 * timing events
     char variant[96];
 };
 

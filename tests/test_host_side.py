@@ -72,6 +72,37 @@ def test_build_cache_validates_before_touching_the_device():
     assert e.value.code == ckv.CKV_ERR_NULL
 
 
+def test_options_are_validated_and_steer_the_plan():
+    """ckv_set_option: unknown keys and malformed values are refused; "mfma_impl" moves a shape from the
+    direct-to-LDS kernel to the register-staged one (seen through ckv_plan, no device); key None restores defaults."""
+    from paper_2601_19178_amd import ckv
+    for key, value in (("no_such_option", "1"), ("mfma_impl", "fastest"), ("dma_sched", "lazy"), ("dma_shape", "4"),
+                       ("dma_shape", "0,1"), ("dma_slow_speed", "fast"), ("dma_slow_speed", "-1")):
+        with pytest.raises(ckv.CkvError) as e:
+            ckv.ckv_set_option(key, value)
+        assert e.value.code == ckv.CKV_ERR_UNSUPPORTED
+    sh = ckv.make_shape(B=3, H=2, d_g=56, d_u=8, P=100, Nq=64, dtype=ckv.CKV_BF16, mode=0, scale=0.125, pool_ld=64)
+    lengths = np.array([100, 900, 33], np.int32)
+    try:
+        assert ckv.ckv_plan(sh, lengths)[2].startswith("mfma_dma_bf16_d64")
+        ckv.ckv_set_option("mfma_impl", "staged")
+        assert ckv.ckv_plan(sh, lengths)[2].startswith("mfma_bf16_d64")
+        ckv.ckv_set_option("mfma_impl", "auto")
+        assert ckv.ckv_plan(sh, lengths)[2].startswith("mfma_dma_bf16_d64")
+        ckv.ckv_set_option("dma_shape", "4,1")
+        assert "_w4_g1" in ckv.ckv_plan(sh, lengths)[2]
+        ckv.ckv_set_option("dma_shape", "")
+        rec_static, nwg_static, _ = ckv.ckv_plan(sh, lengths)
+        ckv.ckv_set_option("dma_sched", "dynamic")
+        rec_dyn, nwg_dyn, _ = ckv.ckv_plan(sh, lengths)
+        assert nwg_dyn == len(rec_dyn) and nwg_static != nwg_dyn      # one workgroup per item instead of persistent ones
+        ckv.ckv_set_option("mfma_impl", "staged")
+        ckv.ckv_set_option(None)
+        assert ckv.ckv_plan(sh, lengths)[2].startswith("mfma_dma_bf16_d64") and ckv.ckv_plan(sh, lengths)[1] == nwg_static
+    finally:
+        ckv.ckv_set_option(None)
+
+
 def test_workloads_are_seeded_and_shaped():
     a, b = wl.config("cfg1"), wl.config("cfg1")
     for k, v in a.items():
