@@ -227,6 +227,23 @@ int ckv_attend(const ckv_cache* cache, const void* pool_k, const void* pool_v,
                const void* q, const int32_t* lengths, void* out, void* stream);
 
 /*
+ * ckv_attend for callers that must not touch the allocator at all (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): same arguments, same kernels, same results bit for bit, but the split
+ * workspace (the unnormalised partial outputs of histories that were cut into pieces, joined by the merge
+ * kernel) is a fixed array of CKV_STATIC_SCRATCH_BYTES inside the library instead of the buffer the handle
+ * owns.  Every GPU the library runs on holds that array until the process ends.  A handle whose pieces need more
+ * (partial slots x queries per block x (d_a + 2) floats) is refused with CKV_ERR_UNSUPPORTED: use ckv_attend.
+ * The handle's device must be the current device (CKV_ERR_UNSUPPORTED otherwise).  The call allocates and frees
+ * nothing and calls no allocating routine.  All calls on one GPU share the one array, which keeps the last
+ * call's contents (nothing in it has to start at zero: every slot that is read was written earlier in the same
+ * call): calls that overlap in time on one GPU race, on any handle; serialise them on one stream.
+ */
+#define CKV_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+int ckv_attend_static_scratch(const ckv_cache* cache, const void* pool_k, const void* pool_v,
+                              const int32_t* idx, const void* user_k, const void* user_v,
+                              const void* q, const int32_t* lengths, void* out, void* stream);
+
+/*
  * Materialise the final K and V rows, k_full, v_full device [H][T][d_a], each row the
  * user slice followed by the gathered pool row (eq. "eq: Kc", "eq: K").  A pure copy,
  * bit-exact.  Exists for verification of the gather and the layouts; the attention path

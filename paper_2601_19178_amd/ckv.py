@@ -24,8 +24,9 @@ EXPORTS = [
     "ckv_cache_prefill_workspace", "ckv_prefill_kernel_name", "ckv_plan", "ckv_remap_hot_rows", "ckv_cache_idx", "ckv_cache_user_k", "ckv_cache_user_v", "ckv_cache_lengths",
     "ckv_cache_positions", "ckv_cache_stored_bytes", "ckv_attend", "ckv_reconstruct", "ckv_free",
     "ckv_last_error", "ckv_set_timing", "ckv_kernel_ms", "ckv_kernel_times", "ckv_variant", "ckv_copy", "ckv_trace_enable",
-    "ckv_trace_read", "ckv_set_option",
+    "ckv_trace_read", "ckv_set_option", "ckv_attend_static_scratch",
 ]
+CKV_STATIC_SCRATCH_BYTES = 32 << 20
 
 
 class ckv_shape(ctypes.Structure):
@@ -79,6 +80,8 @@ _lib.ckv_cache_stored_bytes.restype = _i64
 _lib.ckv_cache_stored_bytes.argtypes = [_vp]
 _lib.ckv_attend.restype = ctypes.c_int
 _lib.ckv_attend.argtypes = [_vp] * 10
+_lib.ckv_attend_static_scratch.restype = ctypes.c_int
+_lib.ckv_attend_static_scratch.argtypes = [_vp] * 10
 _lib.ckv_set_option.restype = ctypes.c_int
 _lib.ckv_set_option.argtypes = [ctypes.c_char_p, ctypes.c_char_p]
 _lib.ckv_kernel_times.restype = ctypes.c_int
@@ -223,6 +226,11 @@ def ckv_cache_stored_bytes(cache):
 def ckv_attend(cache, pool_k, pool_v, idx, user_k, user_v, q, lengths, out, stream=0):
     _check(_lib.ckv_attend(cache, _dev(pool_k), _dev(pool_v), _dev(idx), _dev(user_k), _dev(user_v), _dev(q),
                            _dev(lengths), _dev(out), _vp(stream)))
+
+
+def ckv_attend_static_scratch(cache, pool_k, pool_v, idx, user_k, user_v, q, lengths, out, stream=0):
+    _check(_lib.ckv_attend_static_scratch(cache, _dev(pool_k), _dev(pool_v), _dev(idx), _dev(user_k), _dev(user_v), _dev(q),
+                                          _dev(lengths), _dev(out), _vp(stream)))
 
 
 def ckv_set_option(key, value=None):

@@ -4,6 +4,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <numeric>
 #include <vector>
@@ -42,6 +43,11 @@ struct Options {
     bool debug = false;        // "debug" = "1": print the chosen split and list statistics to stderr
 };
 thread_local Options g_opt;
+
+// Scratch of the entry point that allocates nothing (ckv_attend_static_scratch): the split workspace of the matrix-core
+// and streaming kernels, in a fixed array that every GPU the library runs on holds until the process ends.
+constexpr size_t kStaticScratchBytes = CKV_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
 
 // ---------------------------------------------------------------------------------------
 // Packing: user-major [T][H] records -> head-major planes, with the range check of every
@@ -713,6 +719,30 @@ void destroy(ckv_cache* c) {
 
 }  // namespace
 
+// Scratch of ckv_attend_static_scratch.  In host code the array's name is only a stand-in: its device address is
+// asked of the runtime once per device (each GPU holds its own copy at its own address) and kept.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+std::mutex g_scratch_mutex;
+float* g_scratch_ptr[kMaxDevices] = {};
+bool g_scratch_known[kMaxDevices] = {};
+
+// Device address of `scratch` on device `dev`, which must be the current device.
+hipError_t static_scratch_address(int dev, float** out) {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_known[dev]) {
+        void* ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        g_scratch_ptr[dev] = (float*)ptr;
+        g_scratch_known[dev] = true;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+}  // namespace
+
 extern "C" {
 
 const char* ckv_last_error(void) { return g_err; }
@@ -1115,7 +1145,8 @@ int64_t ckv_cache_stored_bytes(const ckv_cache* c) {
 }
 const char* ckv_variant(const ckv_cache* c) { return c ? c->variant : ""; }
 
-// The body of ckv_attend: `partial` is the split workspace the kernels use, `who` the name for error messages.
+// The body of both attention entry points: `partial` is the split workspace the kernels use (the handle's own, or the
+// static scratch), `who` the name for error messages.
 static int attend_common(const char* who, const ckv_cache* c, const void* pool_k, const void* pool_v, const int32_t* idx,
                          const void* user_k, const void* user_v, const void* q, const int32_t* lengths, void* out,
                          float* partial, hipStream_t st) {
@@ -1211,6 +1242,33 @@ int ckv_attend(const ckv_cache* c, const void* pool_k, const void* pool_v, const
                const void* user_v, const void* q, const int32_t* lengths, void* out, void* stream) {
     return attend_common("ckv_attend", c, pool_k, pool_v, idx, user_k, user_v, q, lengths, out, c ? c->d_partial : nullptr,
                          (hipStream_t)stream);
+}
+
+// Bytes of split workspace the handle's kernels use per call (0: no history is split).
+static size_t split_workspace_bytes(const ckv_cache* c) {
+    if (!c || c->n_merge == 0) return 0;
+    return sizeof(float) * (size_t)c->n_parts * (size_t)c->QB * (size_t)(c->shape.d_g + c->shape.d_u + 2);
+}
+
+int ckv_attend_static_scratch(const ckv_cache* c, const void* pool_k, const void* pool_v, const int32_t* idx,
+                              const void* user_k, const void* user_v, const void* q, const int32_t* lengths, void* out,
+                              void* stream) {
+    static const char* who = "ckv_attend_static_scratch";
+    if (!c) return fail(CKV_ERR_NULL, "%s: cache is NULL", who);
+    const size_t need = split_workspace_bytes(c);
+    if (need > kStaticScratchBytes)
+        return fail(CKV_ERR_UNSUPPORTED, "%s: the handle's split workspace is %zu bytes, the static scratch holds %zu; use ckv_attend",
+                    who, need, kStaticScratchBytes);
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(CKV_ERR_HIP, "%s: hipGetDevice: %s", who, hipGetErrorString(e));
+    if (dev != c->device) return fail(CKV_ERR_UNSUPPORTED, "%s: the handle was built on device %d, the current device is %d", who, c->device, dev);
+    if (dev < 0 || dev >= kMaxDevices) return fail(CKV_ERR_UNSUPPORTED, "%s: device %d is beyond the %d devices this entry point keeps scratch for", who, dev, kMaxDevices);
+    float* scratch_ptr = nullptr;
+    e = static_scratch_address(dev, &scratch_ptr);
+    if (e != hipSuccess) return fail(CKV_ERR_HIP, "%s: hipGetSymbolAddress(scratch): %s", who, hipGetErrorString(e));
+    // (nothing in the workspace has to start at zero: every slot a merge entry reads is written by its piece in the same call)
+    return attend_common(who, c, pool_k, pool_v, idx, user_k, user_v, q, lengths, out, scratch_ptr, (hipStream_t)stream);
 }
 
 int ckv_set_option(const char* key, const char* value) {

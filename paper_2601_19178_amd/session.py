@@ -64,11 +64,13 @@ class Session:
             self.cache = build(self.shape, w["lengths"], w["idx_k"], w["idx_v"], w["user_k"], w["user_v"], self.stream)
         self.T = ckv.ckv_cache_positions(self.cache)
 
-    def attend(self, stream=None):
+    def attend(self, stream=None, static_scratch=False):
+        """static_scratch: go through the entry point that keeps the split workspace in the library's fixed array."""
         c = self.cache
-        ckv.ckv_attend(c, self.pool_k, self.pool_v, ckv.ckv_cache_idx(c), ckv.ckv_cache_user_k(c),
-                       ckv.ckv_cache_user_v(c), self.q, ckv.ckv_cache_lengths(c), self.out,
-                       self.stream if stream is None else stream)
+        call = ckv.ckv_attend_static_scratch if static_scratch else ckv.ckv_attend
+        call(c, self.pool_k, self.pool_v, ckv.ckv_cache_idx(c), ckv.ckv_cache_user_k(c),
+             ckv.ckv_cache_user_v(c), self.q, ckv.ckv_cache_lengths(c), self.out,
+             self.stream if stream is None else stream)
         return self.out
 
     def prefill_again(self, stream=None):

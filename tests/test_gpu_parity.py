@@ -383,10 +383,11 @@ def test_attend_refuses_lengths_that_are_not_the_handles(gpu):
         grown = torch.tensor([10, 21], dtype=torch.int32, device="cuda")
         same = torch.tensor([10, 20], dtype=torch.int32, device="cuda")
         for other in (grown, same):
-            with pytest.raises(ckv.CkvError) as e:
-                ckv.ckv_attend(c, s.pool_k, s.pool_v, ckv.ckv_cache_idx(c), ckv.ckv_cache_user_k(c), ckv.ckv_cache_user_v(c), s.q,
-                               other, s.out, s.stream)
-            assert e.value.code == ckv.CKV_ERR_UNSUPPORTED and "ckv_cache_lengths" in str(e.value)
+            for call in (ckv.ckv_attend, ckv.ckv_attend_static_scratch):
+                with pytest.raises(ckv.CkvError) as e:
+                    call(c, s.pool_k, s.pool_v, ckv.ckv_cache_idx(c), ckv.ckv_cache_user_k(c), ckv.ckv_cache_user_v(c), s.q,
+                         other, s.out, s.stream)
+                assert e.value.code == ckv.CKV_ERR_UNSUPPORTED and "ckv_cache_lengths" in str(e.value)
         s.attend()
         check_against_oracle(s.output(), w, what="after refused lengths")
 
