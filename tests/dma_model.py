@@ -141,7 +141,9 @@ def run_item(DA, NW, QG, shape, item, buffers, check_rows=True):
     Returns statistics (peak loads outstanding, LDS bytes).
     """
     d_g, d_u = shape["d_g"], shape["d_u"]
-    need(d_g + d_u == DA, "the kernel serves rows of exactly DA columns")
+    da = d_g + d_u                        # row width in memory
+    need(da == DA, "the kernel serves rows of exactly DA columns")
+    chq = da >> 3
     ksh, vsh = shape["share_k"], shape["share_v"]
     UK = slice_kind(DA, d_u, d_g)
     need(not (UK != 0 and QG != 1), "odd and wide user slices exist with one query group per wavefront only")
@@ -154,8 +156,8 @@ def run_item(DA, NW, QG, shape, item, buffers, check_rows=True):
     uodd = UK in (1, 3)
     n, h, t0 = item["n"], item["h"], item["t0"]
     hT = h * T + t0
-    dgk, dgv = (d_g if ksh else DA), (d_g if vsh else DA)
-    duk, duv = DA - dgk, DA - dgv
+    dgk, dgv = (d_g if ksh else da), (d_g if vsh else da)
+    duk, duv = da - dgk, da - dgv
 
     lds = Memory("LDS", np.zeros(G.LDS, np.uint8))
     g_idx = Memory("idx", buffers["idx"]) if buffers.get("idx") is not None else None
@@ -169,11 +171,11 @@ def run_item(DA, NW, QG, shape, item, buffers, check_rows=True):
     if ksh:
         g_pk, pk_base, krow_bytes = Memory("pool_k of the head", buffers["pool_k"].reshape(H, P, pool_ld)[h]), 0, pool_ld * 2
     else:
-        g_pk, pk_base, krow_bytes = g_uk, hT * DA * 2, DA * 2
+        g_pk, pk_base, krow_bytes = g_uk, hT * da * 2, da * 2
     if vsh:
         g_pv, pv_base, vrow_bytes = Memory("pool_v of the head", buffers["pool_v"].reshape(H, P, pool_ld)[h]), 0, pool_ld * 2
     else:
-        g_pv, pv_base, vrow_bytes = g_uv, hT * DA * 2, DA * 2
+        g_pv, pv_base, vrow_bytes = g_uv, hT * da * 2, da * 2
 
     lane = np.arange(64)
     qn, hh = lane & 31, lane >> 5
@@ -203,7 +205,7 @@ def run_item(DA, NW, QG, shape, item, buffers, check_rows=True):
     need(NW * QG * 32 * QS <= G.NS * G.STAGE, "query staging does not fit under the stages")
     qfirst = [item["q0"] + w * QG * 32 for w in range(NW)]
     qrows = [min(max(Nq - qf, 0), QG * 32) for qf in qfirst]
-    qbyte0 = [((item["b"] * H + h) * Nq + qf) * DA * 2 for qf in qfirst]
+    qbyte0 = [((item["b"] * H + h) * Nq + qf) * da * 2 for qf in qfirst]
 
     ntiles = (n + TP - 1) // TP
     if n > 0:
@@ -218,16 +220,22 @@ def run_item(DA, NW, QG, shape, item, buffers, check_rows=True):
             e = i * 64 + lane
             row, c = e // G.CH, e % G.CH
             vals = np.zeros((64, 16), np.uint8)
-            ok = row < qrows[w]
+            ok = (row < qrows[w]) & (c < chq)
             if ok.any():
-                vals[ok] = g_q.read(qbyte0[w] + row[ok] * DA * 2 + c[ok] * 16, 16, "query rows")
+                vals[ok] = g_q.read(qbyte0[w] + row[ok] * da * 2 + c[ok] * 16, 16, "query rows")
             lds.write(qlds + row * QS + c * 16, vals, "query staging")
         for g in range(QG):
             for kk in range(DA // 16):
                 for j in range(4):
                     ci = 16 * kk + 8 * hh + 2 * j
-                    pc = np.where(ci < dgk, ci + duk, ci - dgk)
-                    lds.read(qlds + (g * 32 + qn) * QS + pc * 2, 2 if uodd else 4, "query operand")
+                    pc = np.where(ci < dgk, ci + duk, np.where(ci < da, ci - dgk, ci))
+                    got = lds.read(qlds + (g * 32 + qn) * QS + pc * 2, 2 if uodd else 4, "query operand")
+                    pad = ci >= da
+                    need(not got[pad].any(), "a padding column of the queries is not zero")
+                    if check_rows and not uodd:                # the operand is the query's columns pc, pc + 1 as stored
+                        rows_ok = (g * 32 + qn < qrows[w]) & ~pad
+                        want = g_q.data[(qbyte0[w] + (g * 32 + qn) * da * 2 + pc * 2)[rows_ok, None] + np.arange(4)]
+                        need(np.array_equal(got[rows_ok], want), "a query operand is not the query's own columns")
                     if uodd:
                         pc1 = np.where(ci + 1 < dgk, ci + 1 + duk, ci + 1 - dgk)
                         lds.read(qlds + (g * 32 + qn) * QS + pc1 * 2, 2, "query operand (second half)")
@@ -349,8 +357,8 @@ def run_item(DA, NW, QG, shape, item, buffers, check_rows=True):
                         r = np.concatenate([r, uflat[start[:, None] + np.arange(d_u)]], axis=1)
                 else:
                     uflat = user.view(np.uint16).reshape(-1)
-                    start = (hT + pos) * DA
-                    r = uflat[start[:, None] + np.arange(DA)]
+                    start = (hT + pos) * da
+                    r = uflat[start[:, None] + np.arange(da)]
                 rows.append(np.ascontiguousarray(r, dtype=np.uint16))
             return rows
 
@@ -373,11 +381,19 @@ def run_item(DA, NW, QG, shape, item, buffers, check_rows=True):
             if check_rows:
                 ek, ev = expected_rows(tile)
                 nt = min(n - tile * TP, TP)       # rows past the end of the history hold a clamped copy: not checked
-                pp, cc = np.meshgrid(np.arange(nt), np.arange(G.CH), indexing="ij")
+                pp, cc = np.meshgrid(np.arange(nt), np.arange(chq), indexing="ij")
                 for side, exp, f in ((0, ek, fk), (1, ev, fv)):
                     off = st + side * G.KV + pp * G.ROWB + ((cc ^ f(DA, pp)) << 4)
-                    got = lds.data[off[..., None] + np.arange(16)].reshape(nt, G.CH, 16).view(np.uint16)
-                    want = exp[:nt].reshape(nt, G.CH, 8)
+                    got = lds.data[off[..., None] + np.arange(16)].reshape(nt, chq, 16).view(np.uint16)
+                    want = exp[:nt].reshape(nt, chq, 8)
+                    if side == 0 and chq < G.CH:
+                        # padding columns of a K row meet zero query columns: they must hold finite values, which a copy of
+                        # the row's own first chunk is
+                        pq, cq = np.meshgrid(np.arange(nt), np.arange(chq, G.CH), indexing="ij")
+                        offp = st + pq * G.ROWB + ((cq ^ f(DA, pq)) << 4)
+                        padv = lds.data[offp[..., None] + np.arange(16)].reshape(nt, G.CH - chq, 16).view(np.uint16)
+                        need(np.array_equal(padv, np.broadcast_to(exp[:nt, None, 0:8], padv.shape)),
+                             f"tile {tile}: padding columns of the K rows are not a copy of the rows' first chunk")
                     bad = np.argwhere((got != want).any(axis=2))
                     need(len(bad) == 0, f"tile {tile} {'KV'[side]}: {len(bad)} chunks differ from the final rows, first at row "
                                         f"{bad[0][0] if len(bad) else 0} chunk {bad[0][1] if len(bad) else 0}")
@@ -426,7 +442,8 @@ def run_item(DA, NW, QG, shape, item, buffers, check_rows=True):
                 for dt in range(DA // 32):
                     for r in range(0, 16, 2):
                         ci = 32 * dt + 8 * (r >> 2) + 4 * hh + (r & 3)
-                        pc = np.where(ci < dgv, ci + duv, ci - dgv)
+                        pc = np.where(ci < dgv, ci + duv, np.where(ci < da, ci - dgv, ci))
+                        need(((g * 32 + qn) * QS + pc * 2 + 4).max() <= NW * QG * 32 * QS, "output staging leaves its rows")
                         lds.write(qlds + (g * 32 + qn) * QS + pc * 2, np.zeros((64, 2 if uodd else 4), np.uint8), "output staging")
                         if uodd:
                             pc1 = np.where(ci + 1 < dgv, ci + 1 + duv, ci + 1 - dgv)
@@ -435,14 +452,14 @@ def run_item(DA, NW, QG, shape, item, buffers, check_rows=True):
                 e = i * 64 + lane
                 row, c = e // G.CH, e % G.CH
                 v = lds.read(qlds + row * QS + c * 16, 16, "output staging")
-                ok = row < qrows[w]
+                ok = (row < qrows[w]) & (c < chq)
                 if ok.any():
-                    g_out.write(qbyte0[w] + row[ok] * DA * 2 + c[ok] * 16, v[ok], "output rows")
+                    g_out.write(qbyte0[w] + row[ok] * da * 2 + c[ok] * 16, v[ok] + 1, "output rows")   # (+1: marks what was written)
         else:
             need(buffers.get("partial") is not None, "a piece of a split history needs the workspace")
             g_ws = Memory("partial", buffers["partial"])
             QB = item["QB"]
-            ws0 = item["part"] * QB * (DA + 2) * 4
+            ws0 = item["part"] * QB * (da + 2) * 4
             FS = DA * 4 + 16
             need(NW * QG * 32 * FS <= G.NS * G.STAGE, "the staged accumulators must fit in the retired stages")
             flds = w * QG * 32 * FS
@@ -451,14 +468,15 @@ def run_item(DA, NW, QG, shape, item, buffers, check_rows=True):
                 for dt in range(DA // 32):
                     for r in range(16):
                         ci = 32 * dt + 8 * (r >> 2) + 4 * hh + (r & 3)
-                        pc = np.where(ci < dgv, ci + duv, ci - dgv)
+                        pc = np.where(ci < dgv, ci + duv, np.where(ci < da, ci - dgv, ci))
                         lds.write(flds + (g * 32 + qn) * FS + pc * 4, np.zeros((64, 4), np.uint8), "accumulator staging")
                 low = hh == 0
-                g_ws.write(ws0 + (QB * DA + j[low]) * 4, np.zeros((int(low.sum()), 4), np.uint8), "piece maximum")
-                g_ws.write(ws0 + (QB * DA + QB + j[low]) * 4, np.zeros((int(low.sum()), 4), np.uint8), "piece sum")
+                g_ws.write(ws0 + (QB * da + j[low]) * 4, np.ones((int(low.sum()), 4), np.uint8), "piece maximum")
+                g_ws.write(ws0 + (QB * da + QB + j[low]) * 4, np.ones((int(low.sum()), 4), np.uint8), "piece sum")
             for i in range(QG * 32 * (DA // 4) // 64):
                 e = i * 64 + lane
                 row, c = e // (DA // 4), e % (DA // 4)
                 v = lds.read(flds + row * FS + c * 16, 16, "accumulator staging")
-                g_ws.write(ws0 + ((w * QG * 32 + row) * DA + c * 4) * 4, v, "piece accumulators")
+                ok = c < (da >> 2)
+                g_ws.write(ws0 + ((w * QG * 32 + row[ok]) * da + c[ok] * 4) * 4, v[ok] + 1, "piece accumulators")
     return {"peak_outstanding": max(wv.peak for wv in waves), "lds_bytes": G.LDS, "nui": nui, "UK": UK, "NS": G.NS}

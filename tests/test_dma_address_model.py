@@ -36,15 +36,17 @@ def buffers_for(rng, DA, d_u, share, H, P, pool_ld, T, B, Nq, parts=0, QB=32):
     return shape, buf
 
 
-def run_case(DA, NW, QG, d_u, share=0, lengths=(33, 1, 100), pool_ld=None, Nq=None, seed=0, split=False):
+def run_case(DA, NW, QG, d_u, share=0, lengths=(33, 1, 100), pool_ld=None, Nq=None, seed=0, split=False, d_a=None):
+    """d_a: the head's own width when it is narrower than the kernel's rows (DA)."""
     rng = np.random.default_rng(seed)
-    d_g = DA - d_u
+    d_a = DA if d_a is None else d_a
+    d_g = d_a - d_u
     H, P, B = 2, 37, len(lengths)
-    pool_ld = pool_ld if pool_ld is not None else (DA if d_g > 0 else 0)
+    pool_ld = pool_ld if pool_ld is not None else ((d_g + 7) // 8 * 8 if d_g > 0 else 0)
     T = int(sum(lengths))
     QB = 32 * NW * QG
     Nq = Nq if Nq is not None else QB - 5            # the last wavefront has fewer than 32 query rows
-    shape, buf = buffers_for(rng, DA, d_u, share, H, P, pool_ld, T, B, Nq, parts=4 if split else 0, QB=QB)
+    shape, buf = buffers_for(rng, d_a, d_u, share, H, P, pool_ld, T, B, Nq, parts=4 if split else 0, QB=QB)
     stats = None
     t0 = 0
     for b, n in enumerate(lengths):
@@ -57,6 +59,8 @@ def run_case(DA, NW, QG, d_u, share=0, lengths=(33, 1, 100), pool_ld=None, Nq=No
                 item = dict(b=b, h=h, q0=0, n=nn, t0=t0 + lo, part=part, QB=QB)
                 stats = dm.run_item(DA, NW, QG, shape, item, buf)
         t0 += n
+    if not split:       # every byte of every output row was written (the model marks what it writes), nothing beyond
+        assert (buf["out"].view(np.uint8) == 1).all()
     return stats
 
 
