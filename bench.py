@@ -19,6 +19,9 @@ histories), inputs resident in HBM.  Prints ONE JSON line:
   also         the same figures for the other workloads (not the headline)
   prefill      the prefill stage (router argmax + projection into the packed cache): positions/s and
                matrix-core TFLOP/s against the dense peak of its matrix instruction
+  offloaded    latency of one decode batch with the compressed cache read in place from pinned host memory, against the
+               resident cache and against loading the batch's full-width keys (the paper's latency-table scenario), for a
+               one-query and a many-candidate shape
 """
 import argparse
 import json
@@ -255,10 +258,18 @@ def cpu_baseline(w, budget_s=15.0):
             "sample": f"{n} of {w['B']} users (seeded choice), all heads and queries, {dt:.1f} s wall"}
 
 
-def offloaded_sweep(batches=(1, 8, 32, 64, 128, 256, 512), reps=30):
-    """Decode latency of one request batch (target attention: one query per user, L=200, 2 heads, d=56+8, pool
-    10000, bf16): compressed cache read in place from pinned host memory, compressed cache resident in HBM, and
-    the time to load the same batch's full-width keys from pinned host memory (the standard-KV-cache baseline)."""
+OFFLOADED_SHAPES = {
+    # target attention as in the paper's latency table: one query per user, streaming kernel
+    "target": dict(L=(200, 200), H=2, d_a=64, d_u=8, P=10000, idx="uniform", Nq=1, mode=0, sigma_pool=0.125),
+    # many candidates per user, HSTU-style weighting: matrix-core kernel (config 3's shape per user)
+    "candidates": dict(L=(1024, 1024), H=4, d_a=64, d_u=4, P=16384, idx=("zipf", 1.1), Nq=64, mode=1, sigma_pool=0.125),
+}
+
+
+def offloaded_sweep(batches=(1, 8, 32, 64, 128, 256, 512), reps=30, kinds=("target", "candidates")):
+    """Decode latency of one request batch per shape of OFFLOADED_SHAPES (bf16): compressed cache read in place from
+    pinned host memory, compressed cache resident in HBM, and the time to load the same batch's full-width keys from
+    pinned host memory (the standard-KV-cache baseline)."""
     import torch
     from paper_2601_19178_amd import ckv, session, workloads as wl
 
@@ -271,21 +282,25 @@ def offloaded_sweep(batches=(1, 8, 32, 64, 128, 256, 512), reps=30):
         return float(np.median(ts[reps // 3:]))
 
     rows = []
-    for B in batches:
-        w = wl.make(B=B, L=(200, 200), H=2, d_a=64, d_u=8, P=10000, idx="uniform", Nq=1, mode=wl.SOFTMAX, dtype=wl.BF16,
-                    sigma_pool=0.125, seed=2000 + B)
-        ab = wl.algorithmic_bytes(w)
-        full_keys = torch.empty(B * 200 * 2 * 64, dtype=torch.bfloat16).pin_memory()
-        dev_keys = torch.empty_like(full_keys, device="cuda")
-        row = {"batch": B, "compressed_bytes": ab["compressed"], "full_key_bytes": full_keys.numel() * 2}
-        for name, off in (("resident_ms", False), ("offloaded_ms", True)):
-            s = session.Session(w, offloaded=off)
-            for _ in range(5):
-                s.attend()
-            row[name] = median_ms(s.attend)
-            s.close()
-        row["full_key_load_ms"] = median_ms(lambda: dev_keys.copy_(full_keys, non_blocking=True))
-        rows.append(row)
+    for kind in kinds:
+        sh = OFFLOADED_SHAPES[kind]
+        for B in batches:
+            w = wl.make(B=B, dtype=wl.BF16, seed=2000 + B, **sh)
+            ab = wl.algorithmic_bytes(w)
+            T = int(w["lengths"].sum())
+            full_keys = torch.empty(T * sh["H"] * sh["d_a"], dtype=torch.bfloat16).pin_memory()
+            dev_keys = torch.empty_like(full_keys, device="cuda")
+            row = {"shape": kind, "batch": B, "compressed_bytes": ab["compressed"], "full_key_bytes": full_keys.numel() * 2}
+            for name, off in (("resident_ms", False), ("offloaded_ms", True)):
+                s = session.Session(w, offloaded=off)
+                row["kernel"] = ckv.ckv_variant(s.cache)
+                for _ in range(5):
+                    s.attend()
+                row[name] = median_ms(s.attend)
+                s.close()
+            row["full_key_load_ms"] = median_ms(lambda: dev_keys.copy_(full_keys, non_blocking=True))
+            row["offloaded_GBps_over_host_link"] = ab["compressed"] / (row["offloaded_ms"] * 1e-3) / 1e9
+            rows.append(row)
     return rows
 
 
@@ -304,6 +319,8 @@ def main():
     ap.add_argument("--prefill", default="prefill_cfg2,prefill_cfg3,prefill_cfg2_f32",
                     help="comma list of prefill workloads reported under 'prefill' (prefill_cfg2, prefill_cfg3, prefill_cfg2_f32; '' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--offloaded-batches", default="1,64,512",
+                    help="batch sizes of the offloaded-cache latencies reported under 'offloaded' in the line ('' for none)")
     ap.add_argument("--offloaded-sweep", action="store_true",
                     help="latency of one decode batch with the compressed cache in pinned host memory vs resident vs "
                          "loading a full-width key cache, batch 1..512 (the paper's latency-table scenario)")
@@ -351,6 +368,8 @@ def main():
 
     prefill = [measure_prefill(n, max(10, args.steps // 4), max(5, args.warmup // 4), with_cpu=not args.no_cpu_baseline)
                for n in args.prefill.split(",") if n]
+    ob = tuple(int(x) for x in args.offloaded_batches.split(",") if x)
+    offloaded = offloaded_sweep(batches=ob, reps=21) if ob else None
 
     line = {
         "metric": METRIC,
@@ -383,6 +402,7 @@ def main():
         "cpu_baseline": base,
         "also": also,
         "prefill": prefill,
+        "offloaded": offloaded,
     }
     print(json.dumps(line))
 

@@ -241,6 +241,12 @@ __global__ void ckv_copy_kernel(uint4* __restrict__ dst, const uint4* __restrict
         ((unsigned char*)(dst + n16))[threadIdx.x] = ((const unsigned char*)(src + n16))[threadIdx.x];
 }
 
+// XCC (accelerator complex die) that runs each workgroup of a small launch: the work lists assume workgroup i of a launch
+// runs on XCD i mod 8.
+__global__ void ckv_xcc_probe_kernel(uint32_t* __restrict__ xcc) {
+    if (threadIdx.x == 0) xcc[blockIdx.x] = (uint32_t)__builtin_amdgcn_s_getreg((20 << 0) | (0 << 6) | (3 << 11)) & 15u;  // XCC_ID[3:0]
+}
+
 // ---------------------------------------------------------------------------------------
 // Work list.  Units are (user, head, query block); long histories are cut into pieces when
 // there are too few units to fill and balance the chip.  Pieces are ordered longest first
@@ -275,10 +281,20 @@ void pick_stream_vec(const ckv_shape& s, int* vec, int* grp) {
     *grp = best_g;
 }
 
+// Number of head classes the work lists keep apart, one (or more) XCD per class: 8 or H when the heads divide over the
+// eight XCDs and consecutive workgroups of a launch do land on consecutive XCDs (probed once per device when a handle
+// is built; a host-only plan assumes it), else 1: no class, any workgroup takes any head.
+int head_classes(const ckv_cache* c) {
+    const ckv_shape& s = c->shape;
+    if (c->xcd_order_unknown) return 1;
+    if (s.H >= 8 && s.H % 8 == 0) return 8;
+    if (s.H < 8 && 8 % s.H == 0) return s.H;
+    return 1;
+}
+
 // Cut units into pieces of at most `piece` positions and order them (see above).
 void make_items(const ckv_cache* c, const std::vector<Unit>& units, int64_t piece, std::vector<ckv_item>& items,
                 std::vector<ckv_merge>& merges, int* n_parts_out) {
-    const ckv_shape& s = c->shape;
     items.clear();
     merges.clear();
     int n_parts = 0;
@@ -301,9 +317,7 @@ void make_items(const ckv_cache* c, const std::vector<Unit>& units, int64_t piec
     *n_parts_out = n_parts;
 
     // head classes for the XCD-aware order
-    int ncls = 1;
-    if (s.H >= 8 && s.H % 8 == 0) ncls = 8;
-    else if (s.H < 8 && 8 % s.H == 0) ncls = s.H;
+    const int ncls = head_classes(c);
     std::vector<std::vector<ckv_item>> cls((size_t)ncls);
     for (const ckv_item& it : items) cls[(size_t)(it.h % ncls)].push_back(it);
     for (auto& v : cls)
@@ -432,10 +446,7 @@ struct Piece {
 
 double assign_static(const ckv_cache* c, const std::vector<Unit>& units, int64_t piece_len, int64_t slots, int cus, double slow_speed,
                      int64_t overhead, double part_positions, std::vector<std::vector<Piece>>& lists, int* n_parts_out) {
-    const ckv_shape& s = c->shape;
-    int ncls = 1;
-    if (s.H >= 8 && s.H % 8 == 0) ncls = 8;
-    else if (s.H < 8 && 8 % s.H == 0) ncls = s.H;
+    const int ncls = head_classes(c);
     lists.assign((size_t)slots, {});
     std::vector<int64_t> load((size_t)slots, 0);
     // Relative speed of a workgroup.  When a SIMD holds more than one wavefront of this kernel the hardware
@@ -857,12 +868,38 @@ static void plan_work(ckv_cache* c, const int32_t* lengths, const std::vector<in
     }
 }
 
+// Whether consecutive workgroups of a launch land on consecutive XCDs of this device (round robin over eight), asked of
+// the hardware once per device with a launch of 64 one-wavefront workgroups.  A failure to ask counts as "no".
+static bool xcd_round_robin(int device, hipStream_t st) {
+    static std::mutex m;
+    static int known[64] = {};  // 0 unknown, 1 yes, 2 no
+    std::lock_guard<std::mutex> lock(m);
+    if (device < 0 || device >= 64) return false;
+    if (known[device]) return known[device] == 1;
+    constexpr int kBlocks = 64;
+    uint32_t* d = nullptr;
+    uint32_t h[kBlocks];
+    bool ok = hipMalloc((void**)&d, sizeof h) == hipSuccess;
+    if (ok) {
+        hipLaunchKernelGGL(ckv_xcc_probe_kernel, dim3(kBlocks), dim3(64), 0, st, d);
+        ok = hipGetLastError() == hipSuccess && hipMemcpyAsync(h, d, sizeof h, hipMemcpyDeviceToHost, st) == hipSuccess &&
+             hipStreamSynchronize(st) == hipSuccess;
+    }
+    (void)hipFree(d);
+    if (ok)
+        for (int i = 0; i < kBlocks; ++i) ok = ok && h[i] == (h[0] + (uint32_t)i) % 8u;
+    known[device] = ok ? 1 : 2;
+    return ok;
+}
+
 // Build and upload the work lists (and the split workspace) of a handle whose packed cache is in place.
 static int cache_finish(ckv_cache* c, const int32_t* lengths, const std::vector<int64_t>& offs, const hipDeviceProp_t& prop,
                         hipStream_t st) {
     int rc = CKV_OK;
     const int64_t d_a = (int64_t)c->shape.d_g + c->shape.d_u;
     ckv_plan_lists plan;
+    c->xcd_order_unknown = xcd_round_robin(c->device, st) ? 0 : 1;
+    if (g_opt.debug && c->xcd_order_unknown) fprintf(stderr, "ckv: workgroups do not land on XCD i mod 8 here: heads are not kept apart\n");
     plan_work(c, lengths, offs, prop.multiProcessorCount, resident_workgroups(c), plan);
     std::vector<ckv_item>& items = plan.items;
     std::vector<ckv_merge>& merges = plan.merges;

@@ -102,6 +102,7 @@ struct ckv_cache {
     ckv_item* d_items;
     int32_t* d_wg_begin;  // persistent kernel only
     int n_wg;             // persistent kernel only: workgroups launched
+    int xcd_order_unknown;  // 1: consecutive workgroups were not seen to land on consecutive XCDs; heads are then not kept apart
     ckv_merge* d_merge;
     float* d_partial;
     unsigned long long* d_trace;  // 8 words per item while tracing is on
