@@ -186,8 +186,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
     }
     const uint32_t boff = (uint32_t)(lane & (TR - 1)) * 4;
     // stage i of this workgroup when it is known to be a router tile of TR valid rows: no test, no vector arithmetic
-    auto issue_full = [&](int i) {
-        const uint32_t st = __builtin_amdgcn_readfirstlane(lds0 + (i % NS) * G::STAGE);  // (uniform; kept in a scalar register)
+    auto issue_full = [&](int i, auto slot_c) {
+        constexpr int SLOT = decltype(slot_c)::value;  // ring slot of stage i when the caller knows it (-1: i % NS)
+        const uint32_t st = __builtin_amdgcn_readfirstlane(lds0 + (SLOT >= 0 ? SLOT : i % NS) * G::STAGE);  // (uniform; kept in a scalar register)
         const int tile = __builtin_amdgcn_readfirstlane(t_lo + i);  // (uniform anyway; the loads take it in scalar registers)
         const unsigned char* base = wr + (int64_t)tile * (TR * rs);
 #pragma unroll
@@ -229,6 +230,10 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
     }
     const uint32_t arow = qn * G::ROWB;
     const int ax = G::swz(qn);
+    uint32_t waoff[NKK];  // this lane's sixteen-byte pieces of its router row within a stage, one per k-step
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk) waoff[kk] = lds0 + arow + (((2 * kk + hh) ^ ax) << 4);
+    const uint32_t boff_lane = lds0 + G::WT + wave * 256 + 16 * hh;  // this lane's biases within a stage
 
     // One stage: KIND 0 = TR valid router rows, 1 = last router stage with fewer, 2 = projection
     // (32 columns of the user slice).
@@ -236,18 +241,21 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
     // Iteration t issues the loads of stage t+NS-1 into the slot stage t-1 used (retired by the barrier at
     // the end of iteration t-1), computes stage t, then waits until only the loads of the last NS-2 issues
     // are outstanding, i.e. until its own part of stage t+1 has landed; the barrier publishes stage t+1.
-    auto stage = [&](auto kind, int t, auto full_ahead) {
+    // SLOT: the ring slot of stage t when it is known at compile time (the loop over full stages is unrolled over the
+    // ring, so that the stage's offset becomes an immediate of the LDS reads instead of a vector addition per read), else -1.
+    auto stage = [&](auto kind, int t, auto full_ahead, auto slot_c) {
         constexpr int KIND = decltype(kind)::value;
-        if (decltype(full_ahead)::value) issue_full(t + NS - 1);
+        constexpr int SLOT = decltype(slot_c)::value;
+        if (decltype(full_ahead)::value) issue_full(t + NS - 1, std::integral_constant<int, (SLOT >= 0 ? (SLOT + NS - 1) % NS : -1)>{});
         else issue(t + NS - 1);
-        const uint32_t st = lds0 + (t % NS) * G::STAGE;
+        const uint32_t st = (SLOT >= 0 ? SLOT : t % NS) * G::STAGE;  // (offset of the stage; the lane's part of an address is loop-invariant)
         u32x4 wa[NKK];  // A operand: this lane's router row, all k-steps
 #pragma unroll
-        for (int kk = 0; kk < NKK; ++kk) wa[kk] = *(const lds_u32x4*)(uintptr_t)(st + arow + (((2 * kk + hh) ^ ax) << 4));
+        for (int kk = 0; kk < NKK; ++kk) wa[kk] = *(const lds_u32x4*)(uintptr_t)(waoff[kk] + st);
         f32x16 acc[QG];  // accumulators start from the biases of this lane's sixteen rows
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) {
-            const f32x4 b4 = *(const lds_f32x4*)(uintptr_t)(st + G::WT + wave * 256 + (8 * g4 + 4 * hh) * 4);
+            const f32x4 b4 = *(const lds_f32x4*)(uintptr_t)(boff_lane + (st + 32 * g4));
 #pragma unroll
             for (int g = 0; g < QG; ++g)
 #pragma unroll
@@ -311,10 +319,18 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(WPE, WP
     int t = 0;
     // while the stage issued NS-1 ahead is itself a full router tile the loop body has no branch for it
     const int t_ahead = min(nr_loc, nfull - t_lo) - (NS - 1);
-    for (; t < t_ahead; ++t) stage(std::integral_constant<int, 0>{}, t, std::true_type{});
-    for (; t < nr_loc && t_lo + t < nfull; ++t) stage(std::integral_constant<int, 0>{}, t, std::false_type{});
-    if (t < nr_loc) stage(std::integral_constant<int, 1>{}, t++, std::false_type{});  // the part that owns the ragged last router tile
-    for (; t < n_loc; ++t) stage(std::integral_constant<int, 2>{}, t, std::false_type{});
+    constexpr std::integral_constant<int, -1> any_slot{};
+    // (t is a multiple of NS at the top of every round of this loop: stage t + k sits in ring slot k)
+    for (; t + NS <= t_ahead; t += NS) {
+        stage(std::integral_constant<int, 0>{}, t, std::true_type{}, std::integral_constant<int, 0>{});
+        stage(std::integral_constant<int, 0>{}, t + 1, std::true_type{}, std::integral_constant<int, 1 % NS>{});
+        if (NS > 2) stage(std::integral_constant<int, 0>{}, t + 2, std::true_type{}, std::integral_constant<int, 2 % NS>{});
+        if (NS > 3) stage(std::integral_constant<int, 0>{}, t + 3, std::true_type{}, std::integral_constant<int, 3 % NS>{});
+    }
+    for (; t < t_ahead; ++t) stage(std::integral_constant<int, 0>{}, t, std::true_type{}, any_slot);
+    for (; t < nr_loc && t_lo + t < nfull; ++t) stage(std::integral_constant<int, 0>{}, t, std::false_type{}, any_slot);
+    if (t < nr_loc) stage(std::integral_constant<int, 1>{}, t++, std::false_type{}, any_slot);  // the part that owns the ragged last router tile
+    for (; t < n_loc; ++t) stage(std::integral_constant<int, 2>{}, t, std::false_type{}, any_slot);
     wait_vm<0>();  // the repeated loads past the last stage must land before the workgroup gives its LDS back
 
     if (nr_loc > 0) {
