@@ -86,8 +86,15 @@ static void final_row(double *row, const void *user, const void *pool, const int
  * their weight (equal weights are rounded alike, so their errors add up coherently; different
  * weights err independently), and rss[c] = sqrt(sum over groups g of (sum_{i in g} w_i V_i[c])^2).
  * With all weights different this is the root-sum-square of the summands w_i V_i[c]; with all
- * weights equal it is |out[c]|.  It is an extra output for the comparison rule of the tests; out
- * does not depend on it.
+ * weights equal it is |out[c]|.
+ * sss (same shape, or NULL; needs rss) receives the scale against which a rounding error of the scores
+ * shows: a score s_i = scale q . K_i summed in finite precision is off by some delta_i times
+ * A_i = |scale| sum_k |q_k K_ik|, and to first order the output moves by
+ *   softmax:   sum_i w_i (V_i[c] - out[c]) A_i delta_i      (d w_i = w_i (d s_i - sum_j w_j d s_j))
+ *   SiLU / n:  sum_i f'(s_i) V_i[c] A_i delta_i / n,        f(s) = s sigma(s), f'(s) = sigma(s) (1 + s (1 - sigma(s)))
+ * with the same grouping (equal rows have equal scores and equal errors, different rows err
+ * independently): sss[c] = sqrt(sum over groups of (sum_{i in g} coefficient_i)^2).
+ * Both are extra outputs for the comparison rule of the tests; out does not depend on them.
  * Returns 0, or -1 on a bad argument (index outside [0,P), negative length, unknown mode).
  */
 struct weighted { double w; int i; };
@@ -102,7 +109,7 @@ static int attend_impl(int B, int H, int d_g, int d_u, int P, int Nq, int dtype,
                        const int32_t *lengths, const int32_t *idx_k, const int32_t *idx_v,
                        const void *user_k, const void *user_v,
                        const void *pool_k, const void *pool_v, const void *q,
-                       double *out, double *rss, const int32_t *users, int n_users)
+                       double *out, double *rss, double *sss, const int32_t *users, int n_users)
 {
     const int d_a = d_u + d_g;
     if (B < 0 || H < 1 || d_g < 0 || d_u < 0 || d_a < 1 || Nq < 1 || pool_ld < d_g)
@@ -138,6 +145,8 @@ static int attend_impl(int B, int H, int d_g, int d_u, int P, int Nq, int dtype,
             double *K = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1) * d_a);
             double *V = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1) * d_a);
             double *w = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
+            double *sc = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));  /* scores, and A_i (see above) */
+            double *sa = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
             double *qv = (double *)malloc(sizeof(double) * (size_t)d_a);
             /* gather + concat: the user's final K and V, n x d_a */
             for (int i = 0; i < n; ++i) {
@@ -149,9 +158,13 @@ static int attend_impl(int B, int H, int d_g, int d_u, int P, int Nq, int dtype,
                 for (int c = 0; c < d_a; ++c) qv[c] = widen(q, qo + c, dtype);
                 /* scores s_i = scale * q . K_i */
                 for (int i = 0; i < n; ++i) {
-                    double s = 0.0;
-                    for (int c = 0; c < d_a; ++c) s += qv[c] * K[(int64_t)i * d_a + c];
-                    w[i] = scale * s;
+                    double s = 0.0, m = 0.0;
+                    for (int c = 0; c < d_a; ++c) {
+                        s += qv[c] * K[(int64_t)i * d_a + c];
+                        m += fabs(qv[c] * K[(int64_t)i * d_a + c]);
+                    }
+                    w[i] = sc[i] = scale * s;
+                    sa[i] = fabs(scale) * m;
                 }
                 /* weights */
                 if (mode == ORACLE_SOFTMAX) {
@@ -184,10 +197,33 @@ static int attend_impl(int B, int H, int d_g, int d_u, int P, int Nq, int dtype,
                         }
                         rss[qo + c] = sqrt(a2);
                     }
+                    if (sss) {
+                        /* coefficient of delta_i without V: w_i A_i (softmax), f'(s_i) A_i / n (SiLU) */
+                        for (int i = 0; i < n; ++i) {
+                            if (mode == ORACLE_SOFTMAX) {
+                                sa[i] *= w[i];
+                            } else {
+                                const double sg = 1.0 / (1.0 + exp(-sc[i]));
+                                sa[i] *= sg * (1.0 + sc[i] * (1.0 - sg)) / (double)n;
+                            }
+                        }
+                        for (int c = 0; c < d_a; ++c) {
+                            const double centre = mode == ORACLE_SOFTMAX ? out[qo + c] : 0.0;
+                            double a2 = 0.0, group = 0.0;
+                            for (int k = 0; k < n; ++k) {
+                                group += sa[ord[k].i] * (V[(int64_t)ord[k].i * d_a + c] - centre);
+                                if (k + 1 == n || ord[k + 1].w != ord[k].w) {
+                                    a2 += group * group;
+                                    group = 0.0;
+                                }
+                            }
+                            sss[qo + c] = sqrt(a2);
+                        }
+                    }
                     free(ord);
                 }
             }
-            free(K); free(V); free(w); free(qv);
+            free(K); free(V); free(w); free(sc); free(sa); free(qv);
         }
     }
     free(offset);
@@ -202,7 +238,7 @@ int ckv_oracle_attend(int B, int H, int d_g, int d_u, int P, int Nq, int dtype, 
                       double *out, const int32_t *users, int n_users)
 {
     return attend_impl(B, H, d_g, d_u, P, Nq, dtype, mode, share, scale, pool_ld, lengths, idx_k, idx_v, user_k, user_v,
-                       pool_k, pool_v, q, out, NULL, users, n_users);
+                       pool_k, pool_v, q, out, NULL, NULL, users, n_users);
 }
 
 /* The same, and the root-sum-square of every element's summands in rss (see above). */
@@ -214,7 +250,19 @@ int ckv_oracle_attend_rss(int B, int H, int d_g, int d_u, int P, int Nq, int dty
                           double *out, double *rss, const int32_t *users, int n_users)
 {
     return attend_impl(B, H, d_g, d_u, P, Nq, dtype, mode, share, scale, pool_ld, lengths, idx_k, idx_v, user_k, user_v,
-                       pool_k, pool_v, q, out, rss, users, n_users);
+                       pool_k, pool_v, q, out, rss, NULL, users, n_users);
+}
+
+/* The same, and the scale of the scores' rounding errors in sss (see above). */
+int ckv_oracle_attend_scales(int B, int H, int d_g, int d_u, int P, int Nq, int dtype, int mode, int share,
+                             double scale, int64_t pool_ld,
+                             const int32_t *lengths, const int32_t *idx_k, const int32_t *idx_v,
+                             const void *user_k, const void *user_v,
+                             const void *pool_k, const void *pool_v, const void *q,
+                             double *out, double *rss, double *sss, const int32_t *users, int n_users)
+{
+    return attend_impl(B, H, d_g, d_u, P, Nq, dtype, mode, share, scale, pool_ld, lengths, idx_k, idx_v, user_k, user_v,
+                       pool_k, pool_v, q, out, rss, sss, users, n_users);
 }
 
 /*

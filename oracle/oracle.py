@@ -37,6 +37,8 @@ def _load():
         lib.ckv_oracle_attend.argtypes = [i32] * 9 + [dbl, i64] + [vp] * 9 + [vp, i32]
         lib.ckv_oracle_attend_rss.restype = ctypes.c_int
         lib.ckv_oracle_attend_rss.argtypes = [i32] * 9 + [dbl, i64] + [vp] * 10 + [vp, i32]
+        lib.ckv_oracle_attend_scales.restype = ctypes.c_int
+        lib.ckv_oracle_attend_scales.argtypes = [i32] * 9 + [dbl, i64] + [vp] * 11 + [vp, i32]
         lib.ckv_oracle_reconstruct.restype = ctypes.c_int
         lib.ckv_oracle_reconstruct.argtypes = [i32] * 6 + [i64, i64] + [vp] * 8
         lib.ckv_oracle_cache_size.restype = None
@@ -61,7 +63,7 @@ def _check_store(a, dtype, name):
     return a
 
 
-def attend(w, users=None, with_rss=False):
+def attend(w, users=None, with_rss=False, with_scales=False):
     """Attention outputs, fp64 [B][H][Nq][d_a].
 
     `w` is a workload dict as made by the seeded generators: keys B, H, d_g, d_u, P, Nq,
@@ -69,6 +71,10 @@ def attend(w, users=None, with_rss=False):
     Rows of users not listed in `users` are NaN.
     with_rss: also return, per output element c, the scale the tests' comparison rule uses (same shape):
     sqrt(sum over groups g of positions with one and the same weight of (sum_{i in g} w_i V_i[c])^2).
+    with_scales: return (out, rss, sss), sss being the scale of the scores' rounding errors: with
+    A_i = |scale| sum_k |q_k K_ik|, sqrt(sum over the same groups of (sum_{i in g} k_i)^2), where
+    k_i = w_i (V_i[c] - out[c]) A_i for softmax and f'(s_i) V_i[c] A_i / n for SiLU/n (first-order effect of an
+    error delta_i A_i of score i on the output).
     """
     lib = _load()
     dt = w["dtype"]
@@ -86,13 +92,19 @@ def attend(w, users=None, with_rss=False):
     head = (w["B"], w["H"], w["d_g"], w["d_u"], w["P"], w["Nq"], dt, w["mode"], int(w.get("share", 0)),
             float(w["scale"]), int(w["pool_ld"]),
             _ptr(lengths), _ptr(idx_k), _ptr(idx_v), *[_ptr(a) for a in arrs])
-    if with_rss:
+    if with_scales:
+        rss = np.full(out.shape, np.nan, dtype=np.float64)
+        sss = np.full(out.shape, np.nan, dtype=np.float64)
+        rc = lib.ckv_oracle_attend_scales(*head, _ptr(out), _ptr(rss), _ptr(sss), uptr, nu)
+    elif with_rss:
         rss = np.full(out.shape, np.nan, dtype=np.float64)
         rc = lib.ckv_oracle_attend_rss(*head, _ptr(out), _ptr(rss), uptr, nu)
     else:
         rc = lib.ckv_oracle_attend(*head, _ptr(out), uptr, nu)
     if rc != 0:
         raise ValueError("ckv_oracle_attend rejected its arguments")
+    if with_scales:
+        return out, rss, sss
     return (out, rss) if with_rss else out
 
 

@@ -6,8 +6,10 @@ close to zero (weights of both signs in the SiLU form, or value rows that cancel
 error they carry is set by the size of their summands, so "relative" needs a scale per element.
 The rule, for every output element:
 
-    |g_c - r_c| <= tol * |r_c| + tol * rss_c,
+    |g_c - r_c| <= tol * |r_c| + tol * rss_c + u_s * sss_c,
     rss_c = sqrt(sum over groups g of (sum_{i in g} w_i V_i[c])^2),   a group = the positions with one and the same weight
+    sss_c = sqrt(sum over groups g of (sum_{i in g} k_i)^2),          k_i = d r_c / d s_i * A_i,  A_i = |scale| sum_k |q_k K_ik|
+    u_s   = (d_a + 1) * 2^-24
 
 Where it comes from: the kernels keep products and sums in fp32 and round two things below that,
 the weights w_i (to the storage type before the second matrix product: relative error at most
@@ -21,7 +23,17 @@ outputs.  (A CPU model of exactly these roundings lands at 0.2 to 0.5 of the bou
 random shape, the near-cancelling ones included.)  For value rows without structure rss_c is about
 the root-mean-square of the output row, so on ordinary rows the rule is as strict as a floor of
 tol * rms(row); on a row that nearly cancels it stays proportional to what was added up.
-rss_c comes from the CPU oracle (fp64, from the oracle's inputs), never from the GPU output.
+The third term is the scores' own rounding.  A score s_i = scale q . K_i is a sum of d_a products kept in fp32 with
+either storage type (unit roundoff 2^-24; bf16 products are exact in fp32, fp32 products are rounded once), in whatever
+order the matrix instruction adds them: whatever the order, it is off by at most (d_a + 1) 2^-24 A_i (the standard bound
+for a dot product).  For softmax that is a relative error of the weight and far below tol.  The SiLU weight s sigma(s) / n
+passes through zero, where an absolute error of the score is an unbounded relative error of the weight: a short history
+whose one score is 1e-3 has a weight that is right to 1e-4 only, and no rule relative to the summands can hold.  To first
+order an error delta_i A_i of score i moves the output by k_i delta_i (softmax: k_i = w_i (V_i[c] - r_c) A_i, the
+normalisation included; SiLU/n: k_i = f'(s_i) V_i[c] A_i / n); equal rows have equal scores and err alike, different
+rows err independently, hence the same grouping.  With fp32 storage, 256 columns and SiLU this term is about twice
+tol * rss_c; with bf16 storage it is a hundredth of it.
+rss_c and sss_c come from the CPU oracle (fp64, from the oracle's inputs), never from the GPU output.
 Users with an empty history have r = 0 and rss = 0: their rows must be exactly zero.
 The norm-wise figure max|g - r| / max|r| is reported beside it.
 """
@@ -32,17 +44,26 @@ from oracle import oracle
 TOL = {0: 1e-4, 1: 2e-2}
 
 
-def compare(gpu, ref, rss, dtype):
-    """Statistics of one comparison: gpu, ref, rss float64 arrays of one shape.
-    worst_ratio = max over elements of |g - r| / (tol |r| + tol rss)  (<= 1 passes; an element with
+def score_unit(d_a):
+    """u_s of the rule above: the most a d_a-term dot product summed in fp32 can be off by, relative to the sum of the
+    magnitudes of its products."""
+    return (d_a + 1) * 2.0 ** -24
+
+
+def compare(gpu, ref, rss, dtype, sss=None):
+    """Statistics of one comparison: gpu, ref, rss, sss float64 arrays of one shape [...][d_a] (sss = None leaves the
+    third term out: a stricter rule).
+    worst_ratio = max over elements of |g - r| / (tol |r| + tol rss + u_s sss)  (<= 1 passes; an element with
     a zero bound counts as 0 if it is exact and as infinity if it is not)."""
-    assert gpu.shape == ref.shape == rss.shape
+    assert gpu.shape == ref.shape == rss.shape and (sss is None or sss.shape == ref.shape)
     tol = TOL[dtype]
     if ref.size == 0:
         return {"tol": tol, "elements": 0, "norm_err": 0.0, "worst_ratio": 0.0, "finite": True}
     finite = bool(np.isfinite(gpu).all())
     err = np.abs(gpu - ref)
     bound = tol * np.abs(ref) + tol * rss
+    if sss is not None:
+        bound = bound + score_unit(ref.shape[-1]) * sss
     with np.errstate(divide="ignore", invalid="ignore"):
         ratio = np.where(bound > 0, err / bound, np.where(err == 0, 0.0, np.inf))
     return {"tol": tol, "elements": int(ref.size), "finite": finite,
@@ -50,20 +71,22 @@ def compare(gpu, ref, rss, dtype):
             "worst_ratio": float(np.nanmax(ratio)) if finite else float("inf")}
 
 
-def check(gpu, ref, rss, dtype, rows=None, what=""):
-    """gpu, ref, rss: float64 [B][H][Nq][d_a]; rows: optional index of the users to compare.
+def check(gpu, ref, rss, dtype, rows=None, what="", sss=None):
+    """gpu, ref, rss, sss: float64 [B][H][Nq][d_a]; rows: optional index of the users to compare.
     Asserts the rule above on every element and returns the norm-wise error."""
     if rows is not None:
         gpu, ref, rss = gpu[rows], ref[rows], rss[rows]
+        sss = None if sss is None else sss[rows]
     assert np.isfinite(ref).all() and np.isfinite(rss).all(), f"{what}: oracle produced non-finite values"
+    assert sss is None or np.isfinite(sss).all(), f"{what}: oracle produced non-finite values"
     assert np.isfinite(gpu).all(), f"{what}: GPU produced non-finite values"
-    st = compare(gpu, ref, rss, dtype)
-    assert st["worst_ratio"] <= 1.0, (f"{what}: element error exceeds tol={st['tol']}: worst |g-r| / (tol|r| + tol rss) = "
+    st = compare(gpu, ref, rss, dtype, sss)
+    assert st["worst_ratio"] <= 1.0, (f"{what}: element error exceeds tol={st['tol']}: worst |g-r| / (tol|r| + tol rss + u_s sss) = "
                                       f"{st['worst_ratio']:.3f}, norm-wise {st['norm_err']:.3e}")
     return st["norm_err"]
 
 
 def check_against_oracle(gpu, w, users=None, what=""):
     """Run the oracle on workload `w` (all users, or the listed ones) and check `gpu` against it."""
-    ref, rss = oracle.attend(w, users=users, with_rss=True)
-    return check(gpu, ref, rss, w["dtype"], rows=users, what=what)
+    ref, rss, sss = oracle.attend(w, users=users, with_scales=True)
+    return check(gpu, ref, rss, w["dtype"], rows=users, what=what, sss=sss)

@@ -478,3 +478,82 @@ def test_summand_scale_closed_forms():
     w = small()
     _, rss = oracle.attend(w, users=[1], with_rss=True)
     assert np.isnan(rss[0]).all() and np.isfinite(rss[1]).all()
+
+
+# ---------------------------------------------------------------------------------------------
+# the scale of the scores' rounding errors: first-order effect of an error delta_i * A_i of score i on the output
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+@pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
+@pytest.mark.parametrize("share", [wl.SHARE_KV, wl.SHARE_K])
+def test_score_scale_matches_autograd_jacobian(dtype, mode, share):
+    """d out[c] / d s_i from torch's autograd through torch's own softmax / SiLU, times A_i = |scale| sum_k |q_k K_ik|;
+    the random workload has no two equal rows, so every position is a group of its own."""
+    w = small(dtype=dtype, mode=mode, share=share)
+    out, rss, sss = oracle.attend(w, with_scales=True)
+    o2, r2 = oracle.attend(w, with_rss=True)
+    np.testing.assert_array_equal(out, o2)                        # the extra outputs change nothing
+    np.testing.assert_array_equal(rss, r2)
+    q = wl.to_f64(w["q"], dtype)
+    for b, h, K, V in dense_kv_shared(w):
+        n = K.shape[0]
+        if n == 0:
+            assert np.all(sss[b, h] == 0)
+            continue
+        for j in range(w["Nq"]):
+            qj = torch.from_numpy(q[b, h, j])
+            s0 = (w["scale"] * qj) @ K.T
+            A = abs(w["scale"]) * (qj.abs()[None, :] * K.abs()).sum(dim=1)
+
+            def f(s):
+                wt = torch.softmax(s, dim=-1) if mode == wl.SOFTMAX else torch.nn.functional.silu(s) / n
+                return wt @ V
+            J = torch.autograd.functional.jacobian(f, s0)          # [d_a][n]
+            want = ((J * A[None, :]) ** 2).sum(dim=1).sqrt().numpy()
+            np.testing.assert_allclose(sss[b, h, j], want, rtol=1e-9, atol=1e-14)
+
+
+@pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
+def test_score_scale_groups_positions_of_equal_score(mode):
+    # a key pool of three rows and no user columns: positions with the same key row have the same score and the same
+    # error, so their effects are added before squaring
+    w = small(mode=mode, d_u=0, d_a=12, P=3, lengths=(50, 7), H=1, Nq=2)
+    out, _, sss = oracle.attend(w, with_scales=True)
+    q = wl.to_f64(w["q"], w["dtype"])
+    off = np.concatenate([[0], np.cumsum(w["lengths"])])
+    for b, h, K, V in dense_kv(w):
+        n = K.shape[0]
+        rows = w["idx_k"][off[b]:off[b + 1], h]
+        for j in range(w["Nq"]):
+            qj = torch.from_numpy(q[b, h, j])
+            s0 = (w["scale"] * qj) @ K.T
+            A = abs(w["scale"]) * (qj.abs()[None, :] * K.abs()).sum(dim=1)
+
+            def f(s):
+                wt = torch.softmax(s, dim=-1) if mode == wl.SOFTMAX else torch.nn.functional.silu(s) / n
+                return wt @ V
+            JA = (torch.autograd.functional.jacobian(f, s0) * A[None, :]).numpy()   # [d_a][n]
+            groups = np.stack([JA[:, rows == r].sum(axis=1) for r in np.unique(rows)])
+            np.testing.assert_allclose(sss[b, h, j], np.sqrt((groups ** 2).sum(axis=0)), rtol=1e-9, atol=1e-14)
+
+
+def test_score_scale_closed_forms():
+    # softmax over one position: the weight is 1 whatever the score, an error of the score changes nothing
+    w = small(lengths=(1,), Nq=2, mode=wl.SOFTMAX)
+    _, _, sss = oracle.attend(w, with_scales=True)
+    assert np.all(sss == 0)
+    # SiLU over one position: out = f(s) V, so the scale is |f'(s)| A |V| with f'(s) = sigma (1 + s (1 - sigma))
+    w = small(lengths=(1,), Nq=2, mode=wl.SILU_OVER_N, H=1)
+    _, _, sss = oracle.attend(w, with_scales=True)
+    q = wl.to_f64(w["q"], w["dtype"])
+    for b, h, K, V in dense_kv(w):
+        K, V = K.numpy()[0], V.numpy()[0]
+        for j in range(2):
+            s = w["scale"] * q[b, h, j] @ K
+            A = abs(w["scale"]) * np.abs(q[b, h, j] * K).sum()
+            sg = 1 / (1 + np.exp(-s))
+            np.testing.assert_allclose(sss[b, h, j], abs(sg * (1 + s * (1 - sg))) * A * np.abs(V), rtol=1e-12)
+    # q = 0: A = 0, no error to propagate
+    w = small(lengths=(40,), H=1, Nq=1)
+    w["q"] = np.zeros_like(w["q"])
+    _, _, sss = oracle.attend(w, with_scales=True)
+    assert np.all(sss == 0)
