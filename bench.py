@@ -48,6 +48,7 @@ DESCRIBE = {
     "cfg4_plain": "config 4 with an ordinary K/V cache (d_g = 0): the same decode without compression",
     "d256_u4": "256-column heads (Table 1's width, CR 0.020): B=128 L~U[2048,8192] H=4 d=252+4 P=32768 Nq=128 softmax bf16",
     "d256_u10": "256-column heads (Table 1's width, CR 0.043): B=128 L~U[2048,8192] H=4 d=246+10 P=32768 Nq=128 softmax bf16",
+    "cfg3_f32_d256": "config 3's shape with 256-column fp32 heads: B=128 L=1024 H=4 d=252+4 P=16384 Zipf(1.1) Nq=64 SiLU/L fp32",
     "cfg5": "config 5 large batch: B=8192 L~U[512,2048] H=4 d=62+2 P=1048576 Zipf(1.05) Nq=16 softmax bf16",
 }
 
@@ -80,16 +81,17 @@ def parity(w, out, budget_s):
     while True:
         users = np.sort(order[:n])
         t0 = time.time()
-        ref, rss = oracle.attend(w, users=users, with_rss=True)
+        ref, rss, sss = oracle.attend(w, users=users, with_scales=True)
         dt = time.time() - t0
         if n >= w["B"] or dt >= 0.4 * budget_s:
             break
         n = int(min(w["B"], max(2 * n, n * 0.8 * budget_s / max(dt, 1e-3))))
-    st = compare(out[users], ref[users], rss[users], w["dtype"])
+    st = compare(out[users], ref[users], rss[users], w["dtype"], sss[users])
     return {"users_checked": int(n), "of": int(w["B"]), "elements": st["elements"], "tol": st["tol"],
             "max_rel_err_normwise": st["norm_err"], "worst_element_over_bound": st["worst_ratio"],
             "ok": bool(st["finite"] and st["worst_ratio"] <= 1.0),
-            "rule": "|g-r| <= tol*|r| + tol*rss (rss: root-sum-square of the element's summands, from the oracle)"}
+            "rule": "|g-r| <= tol*|r| + tol*rss + (d_a+1)*2^-24*sss (rss: root-sum-square of the element's summands, "
+                    "sss: the same of the first-order effects of the scores' rounding; both from the oracle)"}
 
 
 def measure(name, steps, warmup, traffic_table, steady=0, parity_budget_s=0.0, with_compulsory=True):
@@ -311,7 +313,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=100,
                     help="untimed steps; the GPU needs ~50 back-to-back launches to reach its steady clocks")
     ap.add_argument("--workload", default="cfg4", choices=sorted(DESCRIBE))
-    ap.add_argument("--also", default="cfg1,cfg2_f32,cfg2_bf16,cfg3,cfg5,cfg3_ck,d256_u4", help="comma list of further workloads ('' for none)")
+    ap.add_argument("--also", default="cfg1,cfg2_f32,cfg2_bf16,cfg3,cfg5,cfg3_ck,d256_u4,cfg3_f32_d256", help="comma list of further workloads ('' for none)")
     ap.add_argument("--steady", type=int, default=200,
                     help="launches of the extra steady-state block per workload, reported under 'steady_state' (0: none)")
     ap.add_argument("--parity-budget", type=float, default=6.0,

@@ -672,7 +672,7 @@ void choose_variant(ckv_cache* c) {
         c->family = CKV_K_MFMA32;
         c->nw = 4;
         c->tp = ckv_mfma32_tile(dak);
-        c->QB = 128;
+        c->QB = ckv_mfma32_queries(dak);
         snprintf(c->variant, sizeof c->variant, "mfma_f32_d%d_w4_t%d_%s", dak, c->tp, s.mode == CKV_SOFTMAX ? "softmax" : "silu");
         return;
     }

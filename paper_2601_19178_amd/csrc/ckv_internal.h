@@ -130,8 +130,9 @@ bool ckv_dma_supported(int d_a, int nw, int qg);
 
 // fp32-storage variant of the register-staged mfma kernel (four wavefronts, 128 queries per block).
 hipError_t ckv_launch_mfma32(const ckv_cache* c, const ckv_args& a, hipStream_t s);
-int ckv_mfma32_occupancy(int dak, int mode);  // dak: row width the kernel is built for (64 or 128)
+int ckv_mfma32_occupancy(int dak, int mode);  // dak: row width the kernel is built for (64, 128 or 256)
 int ckv_mfma32_tile(int dak);                 // positions per tile
+int ckv_mfma32_queries(int dak);              // queries per work item (the 256-column kernel splits columns, not queries, over wavefront pairs)
 
 // Prefill (projection + router argmax into the packed cache layout).
 hipError_t ckv_launch_prefill(const ckv_prefill_args& a, int dtype, hipStream_t s);

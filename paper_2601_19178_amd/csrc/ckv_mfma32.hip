@@ -1,11 +1,16 @@
 // Matrix-core gather-concat-attend kernel for many candidate queries per user, fp32 storage
 // (fp32 products and accumulation on v_mfma_f32_32x32x2_f32; built for rows of DA = 64, 128 or 256
 // columns, a narrower d_a runs in the next wider kernel with zero columns; the 256-column kernel
-// keeps one workgroup per compute unit, it needs the whole register file and most of the LDS).
+// keeps one workgroup per compute unit, it needs most of the LDS).
 //
 // Same organisation as the bf16 register-staged kernel: a workgroup of four wavefronts serves one
 // work item (a run of positions of one user and head, a block of 128 queries; wavefront w owns
-// queries 32w .. 32w+31, a wavefront whose queries lie past Nq only helps with the gathers).  Per
+// queries 32w .. 32w+31, a wavefront whose queries lie past Nq only helps with the gathers).
+// The 256-column kernel splits the columns instead of the queries: a block of 64 queries, wavefronts
+// w and w + 2 share queries 32(w & 1) .. +31; each sums S^T over one half of the columns of K, the
+// two halves meet in LDS (a + b on one side, b + a on the other: the same bits), both form the same
+// weights and each accumulates one half of the columns of O^T.  Queries and outputs then take 64
+// registers each instead of 128, and 64 queries keep all four SIMDs busy.  Per
 // tile of TP positions the workgroup gathers the final K and V rows into LDS, 16 bytes (four
 // columns) per lane, in kernel column order [pool | user]; then per 32 positions each wavefront
 // computes
@@ -63,9 +68,10 @@ __global__ __launch_bounds__(256, (DA == 256 ? 1 : 2)) void ckv_mfma32_kernel(ck
     constexpr int KS = DA * 4 + 16;    // LDS row stride of K: sixteen rows of one chunk column fall in sixteen bank groups
     constexpr int VS = DA * 4 + 32;    // LDS row stride of V: rows p and p + 4 are 32 banks apart (one word per lane, two rows per read)
     constexpr int BUF = TP * (KS + VS);
-    constexpr int NKK = DA / 8;        // k-steps of S^T: one chunk per lane half each, four instructions
-    constexpr int NDT = DA / 32;       // 32-row tiles of O^T
-    static_assert(TP % RPP == 0 && TP % 32 == 0, "tile shape");
+    constexpr bool SPLIT = DA == 256;  // wavefront pairs split the columns (see above)
+    constexpr int NKK = DA / 8 / (SPLIT ? 2 : 1);   // this wavefront's k-steps of S^T: one chunk per lane half each, four instructions
+    constexpr int NDT = DA / 32 / (SPLIT ? 2 : 1);  // this wavefront's 32-row tiles of O^T
+    static_assert(TP % RPP == 0 && TP % 32 == 0 && (!SPLIT || TP == 32), "tile shape");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
@@ -86,8 +92,11 @@ __global__ __launch_bounds__(256, (DA == 256 ? 1 : 2)) void ckv_mfma32_kernel(ck
     const float* __restrict__ pv = (const float*)a.pool_v + (int64_t)it.h * a.P * a.pool_ld;
 
     // ---- queries of this lane, kernel column order, as B operands
-    const bool wave_has_q = it.q0 + wave * 32 < a.Nq;  // wavefront-uniform
-    const int qj = it.q0 + wave * 32 + qn;
+    const int qblk = SPLIT ? (wave & 1) : wave;  // which 32 queries of the block
+    const int half = SPLIT ? (wave >> 1) : 0;    // which half of the columns
+    const int kk0 = half * NKK, dt0 = half * NDT;
+    const bool wave_has_q = it.q0 + qblk * 32 < a.Nq;  // wavefront-uniform
+    const int qj = it.q0 + qblk * 32 + qn;
     const bool qok = qj < a.Nq;
     const int64_t qo = (((int64_t)it.b * a.H + it.h) * a.Nq + (qok ? qj : 0)) * d_a;
     float qreg[NKK][4];
@@ -97,10 +106,16 @@ __global__ __launch_bounds__(256, (DA == 256 ? 1 : 2)) void ckv_mfma32_kernel(ck
         for (int kk = 0; kk < NKK; ++kk)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const int ci = 4 * (2 * kk + hh) + e;
+                const int ci = 4 * (2 * (kk0 + kk) + hh) + e;
                 const int pc = ci < d_gk ? ci + d_uk : ci - d_gk;  // kernel column of K -> column of q
                 qreg[kk][e] = qok && ci < d_a ? qp[pc] : 0.f;
             }
+        // the queries have to have arrived before the tile loop: a wait for them that the compiler placed inside
+        // the loop would also wait for the row gathers of the next tile, which are meant to stay in flight
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) asm volatile("" : "+v"(qreg[kk][e]));
     }
 
     f32x16 oacc[NDT];
@@ -117,20 +132,48 @@ __global__ __launch_bounds__(256, (DA == 256 ? 1 : 2)) void ckv_mfma32_kernel(ck
     u32x4 kreg[NL], vreg[NL];
     const int ntiles = (n + TP - 1) / TP;
 
-    auto load_idx = [&](int tile) {
+    // (a side without pool columns keeps the zeros: nothing but loads may write these registers inside the tile
+    // loop, or the compiler guards the write with a wait for every load in flight, the row gathers included)
 #pragma unroll
-        for (int i = 0; i < NL; ++i) {
-            const int pos = min(tile * TP + p0 + i * RPP, n - 1);
-            rk[i] = d_gk > 0 ? ik[pos] : 0;
-            rv[i] = d_gv > 0 ? iv[pos] : 0;
+    for (int i = 0; i < NL; ++i) rk[i] = rv[i] = 0;
+    auto load_idx = [&](int tile) {
+        if (d_gk > 0) {
+#pragma unroll
+            for (int i = 0; i < NL; ++i) rk[i] = ik[min(tile * TP + p0 + i * RPP, n - 1)];
+        }
+        if (d_gv > 0) {
+#pragma unroll
+            for (int i = 0; i < NL; ++i) rv[i] = iv[min(tile * TP + p0 + i * RPP, n - 1)];
         }
     };
+    // When pool and user widths are multiples of four columns on both sides (workgroup-uniform), this lane's chunk
+    // lies for every row in one and the same place: in the pool row, in the user row, or past d_a.  Where it comes
+    // from is then settled once (source, column), and a row costs one address and one 16-byte load without a
+    // branch.  A chunk past d_a fetches chunk 0 instead: for K it meets query columns that are zero, for V it
+    // lands in rows of O^T that nobody stores (inputs are finite).
+    const bool chunked = ((d_gk | d_uk | d_gv | d_uv) & 3) == 0 && a.pool_ld <= 0x7fffffff;
+    const int ck = 4 * c < d_a ? 4 * c : 0, cv = ck;
+    const bool k_pool = ck < d_gk, v_pool = cv < d_gv;
+    // (source of this lane's chunk: first element of its column in row 0, and the distance between rows)
+    const float* const k_src = k_pool ? pk + ck : uk + (ck - d_gk);
+    const float* const v_src = v_pool ? pv + cv : uv + (cv - d_gv);
+    const uint32_t k_ld = k_pool ? (uint32_t)a.pool_ld : (uint32_t)d_uk, v_ld = v_pool ? (uint32_t)a.pool_ld : (uint32_t)d_uv;
     auto load_rows = [&](int tile) {
+        if (chunked) {
 #pragma unroll
-        for (int i = 0; i < NL; ++i) {
-            const int pos = min(tile * TP + p0 + i * RPP, n - 1);
-            kreg[i] = gather_chunk(pk, rk[i], a.pool_ld, uk + (int64_t)pos * d_uk, c, d_gk, d_uk);
-            vreg[i] = gather_chunk(pv, rv[i], a.pool_ld, uv + (int64_t)pos * d_uv, c, d_gv, d_uv);
+            for (int i = 0; i < NL; ++i) {
+                const int pos = min(tile * TP + p0 + i * RPP, n - 1);
+                const uint32_t krow = (uint32_t)(k_pool ? rk[i] : pos), vrow = (uint32_t)(v_pool ? rv[i] : pos);
+                kreg[i] = *reinterpret_cast<const u32x4*>(k_src + (uint64_t)krow * k_ld);
+                vreg[i] = *reinterpret_cast<const u32x4*>(v_src + (uint64_t)vrow * v_ld);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+                const int pos = min(tile * TP + p0 + i * RPP, n - 1);
+                kreg[i] = gather_chunk(pk, rk[i], a.pool_ld, uk + (int64_t)pos * d_uk, c, d_gk, d_uk);
+                vreg[i] = gather_chunk(pv, rv[i], a.pool_ld, uv + (int64_t)pos * d_uv, c, d_gv, d_uv);
+            }
         }
     };
     auto store_rows = [&](int buf) {
@@ -162,19 +205,51 @@ __global__ __launch_bounds__(256, (DA == 256 ? 1 : 2)) void ckv_mfma32_kernel(ck
         const int nt = min(n - t * TP, TP);
 #pragma unroll
         for (int s = 0; s < TP / 32; ++s) {
-            if (wave_has_q && 32 * s < nt) {
+            f32x16 sacc;
+            if (SPLIT || (wave_has_q && 32 * s < nt)) {
                 // S^T = K Q^T
-                f32x16 sacc;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
-                const unsigned char* krow = kb + (32 * s + qn) * KS + hh * 16;
+                const unsigned char* krow = kb + (32 * s + qn) * KS + (2 * kk0 + hh) * 16;
+                if (wave_has_q) {
+                    // two chains of dependent instructions, and the K chunk of the next k-step on its way while
+                    // this one is multiplied
+                    f32x16 sodd;
 #pragma unroll
-                for (int kk = 0; kk < NKK; ++kk) {
-                    const u32x4 ka = *reinterpret_cast<const u32x4*>(krow + kk * 32);
+                    for (int r = 0; r < 16; ++r) sodd[r] = 0.f;
+                    u32x4 kn = *reinterpret_cast<const u32x4*>(krow);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        sacc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(ka[e]), qreg[kk][e], sacc, 0, 0, 0);
+                    for (int kk = 0; kk < NKK; ++kk) {
+                        const u32x4 ka = kn;
+                        if (kk + 1 < NKK) kn = *reinterpret_cast<const u32x4*>(krow + (kk + 1) * 32);
+                        sacc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(ka[0]), qreg[kk][0], sacc, 0, 0, 0);
+                        sodd = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(ka[1]), qreg[kk][1], sodd, 0, 0, 0);
+                        sacc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(ka[2]), qreg[kk][2], sacc, 0, 0, 0);
+                        sodd = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(ka[3]), qreg[kk][3], sodd, 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) sacc[r] += sodd[r];
                 }
+            }
+            if (SPLIT) {
+                // the two halves of the sums meet: every wavefront leaves its sixteen registers in LDS (behind the
+                // row buffers; one tile per barrier pair, so the slot is free again when the next tile writes it)
+                float* xs = reinterpret_cast<float*>(smem + 2 * BUF);
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const u32x4 v = {__float_as_uint(sacc[4 * r4]), __float_as_uint(sacc[4 * r4 + 1]), __float_as_uint(sacc[4 * r4 + 2]),
+                                     __float_as_uint(sacc[4 * r4 + 3])};
+                    *reinterpret_cast<u32x4*>(xs + ((wave * 4 + r4) * 64 + lane) * 4) = v;
+                }
+                __syncthreads();
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const u32x4 v = *reinterpret_cast<const u32x4*>(xs + (((wave ^ 2) * 4 + r4) * 64 + lane) * 4);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) sacc[4 * r4 + e] += __uint_as_float(v[e]);
+                }
+            }
+            if (wave_has_q && 32 * s < nt) {
                 // weights
                 const bool ragged = 32 * s + 32 > nt;
                 float p[16];
@@ -215,13 +290,23 @@ __global__ __launch_bounds__(256, (DA == 256 ? 1 : 2)) void ckv_mfma32_kernel(ck
                 }
                 // O^T += V^T P^T: register r pairs position 8*(r/4) + r%4 (lanes 0-31) with that + 4 (lanes 32-63)
                 const unsigned char* vcol = vb + (32 * s + 4 * hh) * VS + qn * 4;
+                // (the V words of register r + 1 are on their way while those of r are multiplied)
+                float vn[NDT];
 #pragma unroll
-                for (int r = 0; r < 16; ++r)
+                for (int dt = 0; dt < NDT; ++dt) vn[dt] = *reinterpret_cast<const float*>(vcol + (dt0 + dt) * 128);
 #pragma unroll
-                    for (int dt = 0; dt < NDT; ++dt) {
-                        const float va = *reinterpret_cast<const float*>(vcol + (8 * (r >> 2) + (r & 3)) * VS + dt * 128);
-                        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x2f32(va, p[r], oacc[dt], 0, 0, 0);
+                for (int r = 0; r < 16; ++r) {
+                    float va[NDT];
+#pragma unroll
+                    for (int dt = 0; dt < NDT; ++dt) va[dt] = vn[dt];
+                    if (r + 1 < 16) {
+#pragma unroll
+                        for (int dt = 0; dt < NDT; ++dt)
+                            vn[dt] = *reinterpret_cast<const float*>(vcol + (8 * ((r + 1) >> 2) + ((r + 1) & 3)) * VS + (dt0 + dt) * 128);
                     }
+#pragma unroll
+                    for (int dt = 0; dt < NDT; ++dt) oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x2f32(va[dt], p[r], oacc[dt], 0, 0, 0);
+                }
             }
         }
 
@@ -242,23 +327,23 @@ __global__ __launch_bounds__(256, (DA == 256 ? 1 : 2)) void ckv_mfma32_kernel(ck
             for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const int ci = 32 * dt + 8 * (r >> 2) + 4 * hh + (r & 3);
+                    const int ci = 32 * (dt0 + dt) + 8 * (r >> 2) + 4 * hh + (r & 3);
                     const int pc = ci < d_gv ? ci + d_uv : ci - d_gv;  // kernel column of V -> column of out
                     if (ci < d_a) op[pc] = oacc[dt][r] * inv;
                 }
         }
     } else {
         float* ws = a.partial + (int64_t)it.part * a.QB * (d_a + 2);
-        const int j = wave * 32 + qn;
+        const int j = qblk * 32 + qn;
 #pragma unroll
         for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int ci = 32 * dt + 8 * (r >> 2) + 4 * hh + (r & 3);
+                const int ci = 32 * (dt0 + dt) + 8 * (r >> 2) + 4 * hh + (r & 3);
                 const int pc = ci < d_gv ? ci + d_uv : ci - d_gv;
                 if (ci < d_a) ws[(int64_t)j * d_a + pc] = oacc[dt][r];
             }
-        if (hh == 0) {
+        if (hh == 0 && half == 0) {
             ws[(int64_t)a.QB * d_a + j] = m_ref * kLn2;  // natural-log units, as the merge expects
             ws[(int64_t)a.QB * d_a + a.QB + j] = l_tot;
         }
@@ -267,7 +352,7 @@ __global__ __launch_bounds__(256, (DA == 256 ? 1 : 2)) void ckv_mfma32_kernel(ck
 
 template <int DA, int TP>
 constexpr int lds_bytes() {
-    return 2 * TP * ((DA * 4 + 16) + (DA * 4 + 32));
+    return 2 * TP * ((DA * 4 + 16) + (DA * 4 + 32)) + (DA == 256 ? 4 * 16 * 64 * 4 : 0);  // (+ the exchange of the column halves)
 }
 
 template <int DA, int TP, int MODE>
@@ -300,6 +385,7 @@ int occupancy() {
 
 // (row width the kernel is built for) -> positions per tile
 int ckv_mfma32_tile(int dak) { return dak == 64 ? 64 : 32; }
+int ckv_mfma32_queries(int dak) { return dak == 256 ? 64 : 128; }
 
 int ckv_mfma32_occupancy(int dak, int mode) {
     if (dak == 64) return mode == CKV_SOFTMAX ? occupancy<64, 64, CKV_SOFTMAX>() : occupancy<64, 64, CKV_SILU_OVER_N>();

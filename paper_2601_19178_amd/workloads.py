@@ -62,6 +62,9 @@ CONFIGS = {
                     mode=SOFTMAX, dtype=BF16, sigma_pool=1.0 / 16.0, seed=1006),
     "d256_u10": dict(B=128, L=(2048, 8192), H=4, d_a=256, d_u=10, P=32768, idx="uniform", Nq=128,
                      mode=SOFTMAX, dtype=BF16, sigma_pool=1.0 / 16.0, seed=1006),
+    # config 3's batch shape with 256-column heads in fp32 storage (128 users): the fp32 matrix-core kernel's widest instance
+    "cfg3_f32_d256": dict(B=128, L=(1024, 1024), H=4, d_a=256, d_u=4, P=16384, idx=("zipf", 1.1), Nq=64,
+                          mode=SILU_OVER_N, dtype=F32, sigma_pool=1.0 / 16.0, seed=1007),
 }
 
 

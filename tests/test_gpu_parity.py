@@ -197,6 +197,11 @@ def test_256_column_heads_full(gpu, name, Nq):
     run_and_check(gpu, wl.config(name, Nq=Nq), f"{name} Nq={Nq}", expect_variant="mfma_dma_bf16_d256_w4_g1")
 
 
+def test_fp32_256_column_heads_full(gpu):
+    """The fp32 matrix-core kernel's widest instance on the workload the bench reports for it."""
+    run_and_check(gpu, wl.config("cfg3_f32_d256"), "cfg3_f32_d256", expect_variant="mfma_f32_d256")
+
+
 def test_config5_full(gpu):
     run_and_check(gpu, wl.config("cfg5"), "cfg5", expect_variant="mfma_dma_bf16_d64_w1_g1")
 
@@ -654,6 +659,24 @@ def test_256_column_heads_split_history_one_side_shared_and_plain_cache(gpu):
 def test_wide_fp32_heads_many_queries(gpu, mode, d_a, d_u, pool_ld, Nq):
     w = make(MFMA_LENGTHS, wl.F32, mode, d_a=d_a, d_u=d_u, H=2, P=700, Nq=Nq, pool_ld=pool_ld)
     run_and_check(gpu, w, f"wide fp32 head d_a={d_a} d_u={d_u} ld={pool_ld} Nq={Nq} mode={mode}", expect_variant="mfma_f32_d256")
+
+
+@pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
+@pytest.mark.parametrize("Nq", [9, 32, 33, 64, 65, 200])
+def test_wide_fp32_heads_query_blocks(gpu, mode, Nq):
+    """The 256-column fp32 kernel serves 64 queries per work item with wavefront pairs that split the columns:
+    a pair without queries (Nq <= 32), exactly one and two full pairs, a second block of one query, several blocks;
+    one history long enough to be cut into pieces that meet in the merge kernel."""
+    w = make((3000, 70, 1, 257), wl.F32, mode, d_a=256, d_u=12, H=2, P=900, Nq=Nq)
+    run_and_check(gpu, w, f"wide fp32 head Nq={Nq} mode={mode}", expect_variant="mfma_f32_d256")
+
+
+@pytest.mark.parametrize("share", [wl.SHARE_K, wl.SHARE_V])
+def test_wide_fp32_heads_one_side_shared_and_plain_cache(gpu, share):
+    w = make(MFMA_LENGTHS, wl.F32, wl.SOFTMAX, d_a=200, d_u=8, H=2, P=300, Nq=70, share=share)
+    run_and_check(gpu, w, f"wide fp32 head, share={share}", expect_variant="mfma_f32_d256")
+    w = make(MFMA_LENGTHS, wl.F32, wl.SILU_OVER_N, d_a=256, d_u=256, H=2, P=1, Nq=64)
+    run_and_check(gpu, w, "wide fp32 head, ordinary cache", expect_variant="mfma_f32_d256")
 
 
 @pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
