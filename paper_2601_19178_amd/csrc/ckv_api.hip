@@ -365,7 +365,7 @@ int resident_workgroups(const ckv_cache* c) {
     const int d_a = s.d_g + s.d_u;
     if (c->family == CKV_K_MFMA) return std::max(1, ckv_mfma_occupancy(d_a <= 64 ? 64 : (d_a <= 128 ? 128 : 256), c->nw, c->tp, s.mode));
     if (c->family == CKV_K_DMA) return std::max(1, ckv_dma_occupancy(d_a, c->nw, c->qg, s.mode, s.d_g == 0 ? 0 : s.d_u));
-    if (c->family == CKV_K_MFMA32) return std::max(1, ckv_mfma32_occupancy(d_a <= 64 ? 64 : (d_a <= 128 ? 128 : 256), s.mode));
+    if (c->family == CKV_K_MFMA32) return std::max(1, ckv_mfma32_occupancy(d_a <= 64 ? 64 : (d_a <= 128 ? 128 : 256), s.mode, c->QB == 64));
     return 8;
 }
 
@@ -671,9 +671,10 @@ void choose_variant(ckv_cache* c) {
         const int dak = d_a <= 64 ? 64 : (d_a <= 128 ? 128 : 256);
         c->family = CKV_K_MFMA32;
         c->nw = 4;
-        c->tp = ckv_mfma32_tile(dak);
-        c->QB = ckv_mfma32_queries(dak);
-        snprintf(c->variant, sizeof c->variant, "mfma_f32_d%d_w4_t%d_%s", dak, c->tp, s.mode == CKV_SOFTMAX ? "softmax" : "silu");
+        const bool split = ckv_mfma32_split(dak, s.Nq);
+        c->tp = ckv_mfma32_tile(dak, split);
+        c->QB = ckv_mfma32_queries(split);
+        snprintf(c->variant, sizeof c->variant, "mfma_f32_d%d_w4_t%d%s_%s", dak, c->tp, split ? "_c2" : "", s.mode == CKV_SOFTMAX ? "softmax" : "silu");
         return;
     }
     pick_stream_vec(s, &c->vec, &c->grp);

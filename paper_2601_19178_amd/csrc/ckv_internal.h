@@ -130,9 +130,12 @@ bool ckv_dma_supported(int d_a, int nw, int qg);
 
 // fp32-storage variant of the register-staged mfma kernel (four wavefronts, 128 queries per block).
 hipError_t ckv_launch_mfma32(const ckv_cache* c, const ckv_args& a, hipStream_t s);
-int ckv_mfma32_occupancy(int dak, int mode);  // dak: row width the kernel is built for (64, 128 or 256)
-int ckv_mfma32_tile(int dak);                 // positions per tile
-int ckv_mfma32_queries(int dak);              // queries per work item (the 256-column kernel splits columns, not queries, over wavefront pairs)
+// dak: row width the kernel is built for (64, 128 or 256); split: wavefront pairs split the columns instead of the queries
+// (always at 256 columns, otherwise for 64 queries or fewer), which makes a work item 64 queries instead of 128
+bool ckv_mfma32_split(int dak, int Nq);
+int ckv_mfma32_occupancy(int dak, int mode, bool split);
+int ckv_mfma32_tile(int dak, bool split);     // positions per tile
+int ckv_mfma32_queries(bool split);           // queries per work item
 
 // Prefill (projection + router argmax into the packed cache layout).
 hipError_t ckv_launch_prefill(const ckv_prefill_args& a, int dtype, hipStream_t s);

@@ -24,6 +24,8 @@
 // V words are read from exactly those two rows.
 #include "ckv_internal.h"
 
+#include <type_traits>
+
 namespace {
 
 typedef __attribute__((ext_vector_type(16))) float f32x16;
@@ -59,7 +61,7 @@ __device__ __forceinline__ u32x4 gather_chunk(const float* __restrict__ pool_h, 
     return v;
 }
 
-template <int DA, int TP, int MODE>
+template <int DA, int TP, int MODE, bool SPLIT>
 __global__ __launch_bounds__(256, (DA == 256 ? 1 : 2)) void ckv_mfma32_kernel(ckv_args a) {
     constexpr int NT = 256;            // threads: four wavefronts
     constexpr int CH = DA / 4;         // 16-byte chunks per row
@@ -68,7 +70,8 @@ __global__ __launch_bounds__(256, (DA == 256 ? 1 : 2)) void ckv_mfma32_kernel(ck
     constexpr int KS = DA * 4 + 16;    // LDS row stride of K: sixteen rows of one chunk column fall in sixteen bank groups
     constexpr int VS = DA * 4 + 32;    // LDS row stride of V: rows p and p + 4 are 32 banks apart (one word per lane, two rows per read)
     constexpr int BUF = TP * (KS + VS);
-    constexpr bool SPLIT = DA == 256;  // wavefront pairs split the columns (see above)
+    // SPLIT: wavefront pairs split the columns (see above): always at 256 columns, and at 64 or 128 columns when a user
+    // has 64 queries or fewer, which would leave two of the four wavefronts (two of the four SIMDs) without work
     constexpr int NKK = DA / 8 / (SPLIT ? 2 : 1);   // this wavefront's k-steps of S^T: one chunk per lane half each, four instructions
     constexpr int NDT = DA / 32 / (SPLIT ? 2 : 1);  // this wavefront's 32-row tiles of O^T
     static_assert(TP % RPP == 0 && TP % 32 == 0 && (!SPLIT || TP == 32), "tile shape");
@@ -186,6 +189,35 @@ __global__ __launch_bounds__(256, (DA == 256 ? 1 : 2)) void ckv_mfma32_kernel(ck
             *reinterpret_cast<u32x4*>(vb + p * VS + c * 16) = vreg[i];
         }
     };
+    // The same work one row at a time, for a wavefront that multiplies (chunked widths only): with one or two wavefronts
+    // per SIMD whatever is issued outside the matrix instructions is serial time, so the loads of row i of the next
+    // tile go between the matrix instructions of S^T, the index loads of the tile after it behind them, and the LDS
+    // writes between those of O^T.  No branch: past the last tile the last tile is fetched again (into the idle
+    // buffer), and a side without pool columns reads one valid word (the first work item) that nothing uses.
+    const int32_t* const ik1 = d_gk > 0 ? ik : (const int32_t*)a.items;
+    const int32_t* const iv1 = d_gv > 0 ? iv : (const int32_t*)a.items;
+    const int istep_k = d_gk > 0 ? 1 : 0, istep_v = d_gv > 0 ? 1 : 0;
+    auto gather_piece = [&](int i, int tile) {
+        const int pos = min(tile * TP + p0 + i * RPP, n - 1);
+        const uint32_t krow = (uint32_t)(k_pool ? rk[i] : pos), vrow = (uint32_t)(v_pool ? rv[i] : pos);
+        kreg[i] = *reinterpret_cast<const u32x4*>(k_src + (uint64_t)krow * k_ld);
+        vreg[i] = *reinterpret_cast<const u32x4*>(v_src + (uint64_t)vrow * v_ld);
+    };
+    auto idx_piece = [&](int i, int tile) {
+        const int pos = min(tile * TP + p0 + i * RPP, n - 1);
+        rk[i] = ik1[pos * istep_k];
+        rv[i] = iv1[pos * istep_v];
+    };
+    auto store_piece = [&](int i, int buf) {
+        unsigned char* kb = smem + buf * BUF;
+        unsigned char* vb = kb + TP * KS;
+        const int p = p0 + i * RPP;
+        *reinterpret_cast<u32x4*>(kb + p * KS + c * 16) = kreg[i];
+        *reinterpret_cast<u32x4*>(vb + p * VS + c * 16) = vreg[i];
+    };
+    constexpr int GK = NKK / NL;  // k-steps of S^T per gathered row
+    constexpr int RS = 16 / NL;   // weight registers of O^T per stored row
+    static_assert(NKK % NL == 0 && GK >= 2 && 16 % NL == 0, "rows of the next tile are spread over the matrix instructions");
 
     if (ntiles > 0) {
         load_idx(0);
@@ -195,10 +227,17 @@ __global__ __launch_bounds__(256, (DA == 256 ? 1 : 2)) void ckv_mfma32_kernel(ck
         __syncthreads();
     }
 
+    // WOVEN: this wavefront multiplies and the widths are chunked, so its share of the gather is woven into the matrix
+    // instructions; otherwise (a wavefront without queries, or odd widths) it is issued before them and stored after.
+    auto tile_loop = [&](auto woven_c) {
+    constexpr bool WOVEN = decltype(woven_c)::value;
     for (int t = 0; t < ntiles; ++t) {
         const int buf = t & 1;
-        if (t + 1 < ntiles) load_rows(t + 1);
-        if (t + 2 < ntiles) load_idx(t + 2);
+        const int tnext = min(t + 1, ntiles - 1), tnext2 = min(t + 2, ntiles - 1);
+        if (!WOVEN) {
+            if (t + 1 < ntiles) load_rows(t + 1);
+            if (t + 2 < ntiles) load_idx(t + 2);
+        }
 
         const unsigned char* kb = smem + buf * BUF;
         const unsigned char* vb = kb + TP * KS;
@@ -220,6 +259,8 @@ __global__ __launch_bounds__(256, (DA == 256 ? 1 : 2)) void ckv_mfma32_kernel(ck
                     u32x4 kn = *reinterpret_cast<const u32x4*>(krow);
 #pragma unroll
                     for (int kk = 0; kk < NKK; ++kk) {
+                        if (WOVEN && s == 0 && kk % GK == 0) gather_piece(kk / GK, tnext);
+                        if (WOVEN && s == 0 && kk % GK == GK / 2) idx_piece(kk / GK, tnext2);
                         const u32x4 ka = kn;
                         if (kk + 1 < NKK) kn = *reinterpret_cast<const u32x4*>(krow + (kk + 1) * 32);
                         sacc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(ka[0]), qreg[kk][0], sacc, 0, 0, 0);
@@ -281,11 +322,21 @@ __global__ __launch_bounds__(256, (DA == 256 ? 1 : 2)) void ckv_mfma32_kernel(ck
                     }
                     lsum += psum;
                 } else {
+                    // (sixteen independent chains, one kind of instruction at a time: the transcendental unit's
+                    // latency is then covered by the other fifteen instead of being waited for sixteen times)
+                    float e[16];
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const float x = sacc[r] * sc;
-                        p[r] = x * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-kLog2e * x));
-                        if (ragged && 32 * s + 8 * (r >> 2) + 4 * hh + (r & 3) >= nt) p[r] = 0.f;
+                    for (int r = 0; r < 16; ++r) p[r] = sacc[r] * sc;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) e[r] = __builtin_amdgcn_exp2f(-kLog2e * p[r]);
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) e[r] = __builtin_amdgcn_rcpf(1.f + e[r]);
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) p[r] *= e[r];
+                    if (ragged) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            if (32 * s + 8 * (r >> 2) + 4 * hh + (r & 3) >= nt) p[r] = 0.f;
                     }
                 }
                 // O^T += V^T P^T: register r pairs position 8*(r/4) + r%4 (lanes 0-31) with that + 4 (lanes 32-63)
@@ -296,6 +347,7 @@ __global__ __launch_bounds__(256, (DA == 256 ? 1 : 2)) void ckv_mfma32_kernel(ck
                 for (int dt = 0; dt < NDT; ++dt) vn[dt] = *reinterpret_cast<const float*>(vcol + (dt0 + dt) * 128);
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
+                    if (WOVEN && s == TP / 32 - 1 && r % RS == 0) store_piece(r / RS, (t + 1) & 1);
                     float va[NDT];
 #pragma unroll
                     for (int dt = 0; dt < NDT; ++dt) va[dt] = vn[dt];
@@ -310,9 +362,12 @@ __global__ __launch_bounds__(256, (DA == 256 ? 1 : 2)) void ckv_mfma32_kernel(ck
             }
         }
 
-        if (t + 1 < ntiles) store_rows((t + 1) & 1);
+        if (!WOVEN && t + 1 < ntiles) store_rows((t + 1) & 1);
         __syncthreads();
     }
+    };
+    if (chunked && wave_has_q) tile_loop(std::true_type{});
+    else tile_loop(std::false_type{});
 
     // ---- epilogue
     float l_tot = 0.f;
@@ -350,53 +405,68 @@ __global__ __launch_bounds__(256, (DA == 256 ? 1 : 2)) void ckv_mfma32_kernel(ck
     }
 }
 
-template <int DA, int TP>
+template <int DA, int TP, bool SPLIT>
 constexpr int lds_bytes() {
-    return 2 * TP * ((DA * 4 + 16) + (DA * 4 + 32)) + (DA == 256 ? 4 * 16 * 64 * 4 : 0);  // (+ the exchange of the column halves)
+    return 2 * TP * ((DA * 4 + 16) + (DA * 4 + 32)) + (SPLIT ? 4 * 16 * 64 * 4 : 0);  // (+ the exchange of the column halves)
 }
 
-template <int DA, int TP, int MODE>
+template <int DA, int TP, int MODE, bool SPLIT>
 hipError_t prepare() {
-    constexpr int lds = lds_bytes<DA, TP>();
+    constexpr int lds = lds_bytes<DA, TP, SPLIT>();
+    static_assert(lds <= 163840, "LDS of one compute unit");
     static hipError_t done =
-        hipFuncSetAttribute((const void*)ckv_mfma32_kernel<DA, TP, MODE>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        hipFuncSetAttribute((const void*)ckv_mfma32_kernel<DA, TP, MODE, SPLIT>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     return done;
 }
 
-template <int DA, int TP, int MODE>
+template <int DA, int TP, int MODE, bool SPLIT>
 hipError_t launch(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
-    hipError_t e = prepare<DA, TP, MODE>();
+    hipError_t e = prepare<DA, TP, MODE, SPLIT>();
     if (e != hipSuccess) return e;
-    constexpr int lds = lds_bytes<DA, TP>();
-    hipLaunchKernelGGL((ckv_mfma32_kernel<DA, TP, MODE>), dim3(c->n_items), dim3(256), lds, s, a);
+    constexpr int lds = lds_bytes<DA, TP, SPLIT>();
+    hipLaunchKernelGGL((ckv_mfma32_kernel<DA, TP, MODE, SPLIT>), dim3(c->n_items), dim3(256), lds, s, a);
     return hipGetLastError();
 }
 
-template <int DA, int TP, int MODE>
+template <int DA, int TP, int MODE, bool SPLIT>
 int occupancy() {
-    if (prepare<DA, TP, MODE>() != hipSuccess) return 0;
+    if (prepare<DA, TP, MODE, SPLIT>() != hipSuccess) return 0;
     int nb = 0;
-    constexpr int lds = lds_bytes<DA, TP>();
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)ckv_mfma32_kernel<DA, TP, MODE>, 256, lds) != hipSuccess) return 0;
+    constexpr int lds = lds_bytes<DA, TP, SPLIT>();
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)ckv_mfma32_kernel<DA, TP, MODE, SPLIT>, 256, lds) != hipSuccess) return 0;
     return nb;
 }
 
+// one call per built kernel: F<DA, TP, MODE, SPLIT>
+#define CKV_MFMA32_DISPATCH(F, dak, split, softmax, ...)                                                                   \
+    do {                                                                                                                  \
+        if (dak == 64 && !split) return softmax ? F<64, 64, CKV_SOFTMAX, false>(__VA_ARGS__) : F<64, 64, CKV_SILU_OVER_N, false>(__VA_ARGS__);   \
+        if (dak == 64) return softmax ? F<64, 32, CKV_SOFTMAX, true>(__VA_ARGS__) : F<64, 32, CKV_SILU_OVER_N, true>(__VA_ARGS__);               \
+        if (dak == 128 && !split) return softmax ? F<128, 32, CKV_SOFTMAX, false>(__VA_ARGS__) : F<128, 32, CKV_SILU_OVER_N, false>(__VA_ARGS__); \
+        if (dak == 128) return softmax ? F<128, 32, CKV_SOFTMAX, true>(__VA_ARGS__) : F<128, 32, CKV_SILU_OVER_N, true>(__VA_ARGS__);            \
+        return softmax ? F<256, 32, CKV_SOFTMAX, true>(__VA_ARGS__) : F<256, 32, CKV_SILU_OVER_N, true>(__VA_ARGS__);                            \
+    } while (0)
+
 }  // namespace
 
-// (row width the kernel is built for) -> positions per tile
-int ckv_mfma32_tile(int dak) { return dak == 64 ? 64 : 32; }
-int ckv_mfma32_queries(int dak) { return dak == 256 ? 64 : 128; }
+// Wavefront pairs split the columns (64 queries per work item) at 256 columns, and at 64 or 128 columns for 64 queries or fewer.
+bool ckv_mfma32_split(int dak, int Nq) { return dak == 256 || Nq <= 64; }
+// positions per tile
+int ckv_mfma32_tile(int dak, bool split) { return dak == 64 && !split ? 64 : 32; }
+int ckv_mfma32_queries(bool split) { return split ? 64 : 128; }
 
-int ckv_mfma32_occupancy(int dak, int mode) {
-    if (dak == 64) return mode == CKV_SOFTMAX ? occupancy<64, 64, CKV_SOFTMAX>() : occupancy<64, 64, CKV_SILU_OVER_N>();
-    if (dak == 128) return mode == CKV_SOFTMAX ? occupancy<128, 32, CKV_SOFTMAX>() : occupancy<128, 32, CKV_SILU_OVER_N>();
-    return mode == CKV_SOFTMAX ? occupancy<256, 32, CKV_SOFTMAX>() : occupancy<256, 32, CKV_SILU_OVER_N>();
+int ckv_mfma32_occupancy(int dak, int mode, bool split) {
+    const bool softmax = mode == CKV_SOFTMAX;
+    CKV_MFMA32_DISPATCH(occupancy, dak, split, softmax);
 }
 
 hipError_t ckv_launch_mfma32(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
     if (c->n_items == 0) return hipSuccess;
     const bool softmax = c->shape.mode == CKV_SOFTMAX;
-    if (a.d_a <= 64) return softmax ? launch<64, 64, CKV_SOFTMAX>(c, a, s) : launch<64, 64, CKV_SILU_OVER_N>(c, a, s);
-    if (a.d_a <= 128) return softmax ? launch<128, 32, CKV_SOFTMAX>(c, a, s) : launch<128, 32, CKV_SILU_OVER_N>(c, a, s);
-    return softmax ? launch<256, 32, CKV_SOFTMAX>(c, a, s) : launch<256, 32, CKV_SILU_OVER_N>(c, a, s);
+    const int dak = a.d_a <= 64 ? 64 : (a.d_a <= 128 ? 128 : 256);
+    const bool split = c->QB == 64;
+    // the plan (queries per work item, positions per tile) must be the one the kernel is built for
+    if (a.d_a > 256 || (dak == 256 && !split) || c->QB != ckv_mfma32_queries(split) || c->tp != ckv_mfma32_tile(dak, split))
+        return hipErrorInvalidValue;
+    CKV_MFMA32_DISPATCH(launch, dak, split, softmax, c, a, s);
 }

@@ -578,8 +578,10 @@ def test_narrow_head_split_history_and_one_side_shared(gpu):
 @pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
 @pytest.mark.parametrize("d_a,d_u,pool_ld,Nq", [(64, 8, 64, 64), (128, 8, 128, 128), (64, 4, 60, 16), (128, 0, 128, 40),
                                                  (64, 3, 64, 20), (96, 8, 88, 33), (128, 24, 104, 200), (32, 32, 0, 9),
-                                                 (100, 5, 96, 64), (8, 2, 8, 8)])
+                                                 (100, 5, 96, 64), (8, 2, 8, 8), (64, 8, 64, 100), (48, 4, 48, 129)])
 def test_fp32_many_queries(gpu, mode, d_a, d_u, pool_ld, Nq):
+    """64 queries or fewer per user: wavefront pairs split the columns (work items of 64 queries); more: one wavefront per
+    32 queries (work items of 128 queries)."""
     w = make(MFMA_LENGTHS, wl.F32, mode, d_a=d_a, d_u=d_u, H=2, P=700, Nq=Nq, **({"pool_ld": pool_ld} if pool_ld else {}))
     run_and_check(gpu, w, f"fp32 many queries d_a={d_a} d_u={d_u} ld={pool_ld} Nq={Nq} mode={mode}",
                   expect_variant=f"mfma_f32_d{64 if d_a <= 64 else 128}")
