@@ -125,6 +125,10 @@ __global__ __launch_bounds__(NW * 64, (DA == 256 ? 1 : 2)) void ckv_mfma_kernel(
                 qreg[kk][e] = __builtin_bit_cast(__bf16, x);
             }
         }
+        // the queries have to have arrived before the tile loop: a wait for them that the compiler placed inside
+        // the loop would also wait for the row gathers of the next tile, which are meant to stay in flight
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk) asm volatile("" : "+v"(qreg[kk]));
     }
 
     f32x16 oacc[NDT];
@@ -141,20 +145,79 @@ __global__ __launch_bounds__(NW * 64, (DA == 256 ? 1 : 2)) void ckv_mfma_kernel(
     uint4 kreg[NL], vreg[NL];
     const int ntiles = (n + TP - 1) / TP;
 
-    auto load_idx = [&](int tile) {
+    // (a side without pool columns keeps the zeros: nothing but loads may write these registers inside the tile
+    // loop, or the compiler guards the write with a wait for every load in flight, the row gathers included)
 #pragma unroll
-        for (int i = 0; i < NL; ++i) {
-            const int pos = min(tile * TP + p0 + i * RPP, n - 1);
-            rk[i] = d_gk > 0 ? ik[pos] : 0;
-            rv[i] = d_gv > 0 ? iv[pos] : 0;
+    for (int i = 0; i < NL; ++i) rk[i] = rv[i] = 0;
+    auto load_idx = [&](int tile) {
+        if (d_gk > 0) {
+#pragma unroll
+            for (int i = 0; i < NL; ++i) rk[i] = ik[min(tile * TP + p0 + i * RPP, n - 1)];
+        }
+        if (d_gv > 0) {
+#pragma unroll
+            for (int i = 0; i < NL; ++i) rv[i] = iv[min(tile * TP + p0 + i * RPP, n - 1)];
         }
     };
-    auto load_rows = [&](int tile) {
+    // When pool and user widths are multiples of eight columns on both sides (workgroup-uniform), this lane's chunk
+    // lies for every row in one and the same place: in the pool row, in the user row, or past d_a.  Where it comes
+    // from is then settled once (source, column), and a row costs one address and one 16-byte load without a
+    // branch.  A chunk past d_a fetches chunk 0 instead: for K it meets query columns that are zero, for V it
+    // lands in rows of O^T that nobody stores (inputs are finite).
+    const bool chunked = ((d_gk | d_uk | d_gv | d_uv) & 7) == 0 && (a.pool_ld & 7) == 0 && a.pool_ld <= 0x7fffffff;
+    const int ck = 8 * c < d_a ? 8 * c : 0, cv = ck;
+    const bool k_pool = ck < d_gk, v_pool = cv < d_gv;
+    // (source of this lane's chunk: first element of its column in row 0, and the distance between rows)
+    const uint16_t* const k_src = k_pool ? pk + ck : uk + (ck - d_gk);
+    const uint16_t* const v_src = v_pool ? pv + cv : uv + (cv - d_gv);
+    const uint32_t k_ld = k_pool ? (uint32_t)a.pool_ld : (uint32_t)d_uk, v_ld = v_pool ? (uint32_t)a.pool_ld : (uint32_t)d_uv;
+    // The same with widths that are multiples of four columns (d_u = 4, the paper's usual slice): the two 8-byte halves
+    // of the chunk are settled separately and fetched with one 8-byte load each.
+    const bool halved = !chunked && ((d_gk | d_uk | d_gv | d_uv) & 3) == 0 && (a.pool_ld & 7) == 0 && a.pool_ld <= 0x7fffffff;
+    const uint16_t* kh_src[2];
+    const uint16_t* vh_src[2];
+    uint32_t kh_ld[2], vh_ld[2];
+    bool kh_pool[2], vh_pool[2];
 #pragma unroll
-        for (int i = 0; i < NL; ++i) {
-            const int pos = min(tile * TP + p0 + i * RPP, n - 1);
-            kreg[i] = gather_chunk(pk, rk[i], a.pool_ld, uk + (int64_t)pos * d_uk, c, d_gk, d_uk);
-            vreg[i] = gather_chunk(pv, rv[i], a.pool_ld, uv + (int64_t)pos * d_uv, c, d_gv, d_uv);
+    for (int hb = 0; hb < 2; ++hb) {
+        const int col = 8 * c + 4 * hb < d_a ? 8 * c + 4 * hb : 0;
+        kh_pool[hb] = col < d_gk;
+        vh_pool[hb] = col < d_gv;
+        kh_src[hb] = kh_pool[hb] ? pk + col : uk + (col - d_gk);
+        vh_src[hb] = vh_pool[hb] ? pv + col : uv + (col - d_gv);
+        kh_ld[hb] = kh_pool[hb] ? (uint32_t)a.pool_ld : (uint32_t)d_uk;
+        vh_ld[hb] = vh_pool[hb] ? (uint32_t)a.pool_ld : (uint32_t)d_uv;
+    }
+    auto load_rows = [&](int tile) {
+        if (halved) {
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+                const int pos = min(tile * TP + p0 + i * RPP, n - 1);
+                uint2 kh[2], vh[2];
+#pragma unroll
+                for (int hb = 0; hb < 2; ++hb) {
+                    const uint32_t krow = (uint32_t)(kh_pool[hb] ? rk[i] : pos), vrow = (uint32_t)(vh_pool[hb] ? rv[i] : pos);
+                    kh[hb] = *reinterpret_cast<const uint2*>(kh_src[hb] + (uint64_t)krow * kh_ld[hb]);
+                    vh[hb] = *reinterpret_cast<const uint2*>(vh_src[hb] + (uint64_t)vrow * vh_ld[hb]);
+                }
+                kreg[i] = make_uint4(kh[0].x, kh[0].y, kh[1].x, kh[1].y);
+                vreg[i] = make_uint4(vh[0].x, vh[0].y, vh[1].x, vh[1].y);
+            }
+        } else if (chunked) {
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+                const int pos = min(tile * TP + p0 + i * RPP, n - 1);
+                const uint32_t krow = (uint32_t)(k_pool ? rk[i] : pos), vrow = (uint32_t)(v_pool ? rv[i] : pos);
+                kreg[i] = *reinterpret_cast<const uint4*>(k_src + (uint64_t)krow * k_ld);
+                vreg[i] = *reinterpret_cast<const uint4*>(v_src + (uint64_t)vrow * v_ld);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+                const int pos = min(tile * TP + p0 + i * RPP, n - 1);
+                kreg[i] = gather_chunk(pk, rk[i], a.pool_ld, uk + (int64_t)pos * d_uk, c, d_gk, d_uk);
+                vreg[i] = gather_chunk(pv, rv[i], a.pool_ld, uv + (int64_t)pos * d_uv, c, d_gv, d_uv);
+            }
         }
     };
     auto store_rows = [&](int buf) {
@@ -229,13 +292,24 @@ __global__ __launch_bounds__(NW * 64, (DA == 256 ? 1 : 2)) void ckv_mfma_kernel(
                     }
                     lsum += psum;
                 } else {
+                    // (sixteen independent chains, one kind of instruction at a time: the transcendental unit's
+                    // latency is then covered by the other fifteen instead of being waited for sixteen times)
+                    float x[16], e[16];
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const float x = sacc[r] * sc;
-                        float p = x * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-kLog2e * x));
-                        if (ragged && 32 * s + 8 * (r >> 2) + 4 * hh + (r & 3) >= nt) p = 0.f;
-                        pb[r >> 3][r & 7] = (__bf16)p;
+                    for (int r = 0; r < 16; ++r) x[r] = sacc[r] * sc;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) e[r] = __builtin_amdgcn_exp2f(-kLog2e * x[r]);
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) e[r] = __builtin_amdgcn_rcpf(1.f + e[r]);
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) x[r] *= e[r];
+                    if (ragged) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            if (32 * s + 8 * (r >> 2) + 4 * hh + (r & 3) >= nt) x[r] = 0.f;
                     }
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) pb[r >> 3][r & 7] = (__bf16)x[r];
                 }
                 // O^T += V^T P^T
                 const int g16 = lane >> 4, s16 = lane & 15;
