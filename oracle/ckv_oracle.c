@@ -94,7 +94,12 @@ static void final_row(double *row, const void *user, const void *pool, const int
  *   SiLU / n:  sum_i f'(s_i) V_i[c] A_i delta_i / n,        f(s) = s sigma(s), f'(s) = sigma(s) (1 + s (1 - sigma(s)))
  * with the same grouping (equal rows have equal scores and equal errors, different rows err
  * independently): sss[c] = sqrt(sum over groups of (sum_{i in g} coefficient_i)^2).
- * Both are extra outputs for the comparison rule of the tests; out does not depend on them.
+ * acs (same shape, or NULL; needs rss) receives the scale against which the rounding of the additions of
+ * out[c] = sum_i w_i V_i[c] shows when they are carried out in single precision in an order the oracle does
+ * not know: sqrt(n) * (|out[c]| + sqrt(sum_i (w_i V_i[c])^2)), the positions taken one by one (a partial sum of
+ * k of the n summands in an order unrelated to their values has mean (k/n) out[c] and a spread of at most the
+ * root-sum-square of all summands, and there are n - 1 additions).
+ * All three are extra outputs for the comparison rule of the tests; out does not depend on them.
  * Returns 0, or -1 on a bad argument (index outside [0,P), negative length, unknown mode).
  */
 struct weighted { double w; int i; };
@@ -109,7 +114,7 @@ static int attend_impl(int B, int H, int d_g, int d_u, int P, int Nq, int dtype,
                        const int32_t *lengths, const int32_t *idx_k, const int32_t *idx_v,
                        const void *user_k, const void *user_v,
                        const void *pool_k, const void *pool_v, const void *q,
-                       double *out, double *rss, double *sss, const int32_t *users, int n_users)
+                       double *out, double *rss, double *sss, double *acs, const int32_t *users, int n_users)
 {
     const int d_a = d_u + d_g;
     if (B < 0 || H < 1 || d_g < 0 || d_u < 0 || d_a < 1 || Nq < 1 || pool_ld < d_g)
@@ -222,6 +227,16 @@ static int attend_impl(int B, int H, int d_g, int d_u, int P, int Nq, int dtype,
                     }
                     free(ord);
                 }
+                if (acs) {
+                    for (int c = 0; c < d_a; ++c) {
+                        double a2 = 0.0;
+                        for (int i = 0; i < n; ++i) {
+                            const double t = w[i] * V[(int64_t)i * d_a + c];
+                            a2 += t * t;
+                        }
+                        acs[qo + c] = sqrt((double)n) * (fabs(out[qo + c]) + sqrt(a2));
+                    }
+                }
             }
             free(K); free(V); free(w); free(sc); free(sa); free(qv);
         }
@@ -238,7 +253,7 @@ int ckv_oracle_attend(int B, int H, int d_g, int d_u, int P, int Nq, int dtype, 
                       double *out, const int32_t *users, int n_users)
 {
     return attend_impl(B, H, d_g, d_u, P, Nq, dtype, mode, share, scale, pool_ld, lengths, idx_k, idx_v, user_k, user_v,
-                       pool_k, pool_v, q, out, NULL, NULL, users, n_users);
+                       pool_k, pool_v, q, out, NULL, NULL, NULL, users, n_users);
 }
 
 /* The same, and the root-sum-square of every element's summands in rss (see above). */
@@ -250,19 +265,19 @@ int ckv_oracle_attend_rss(int B, int H, int d_g, int d_u, int P, int Nq, int dty
                           double *out, double *rss, const int32_t *users, int n_users)
 {
     return attend_impl(B, H, d_g, d_u, P, Nq, dtype, mode, share, scale, pool_ld, lengths, idx_k, idx_v, user_k, user_v,
-                       pool_k, pool_v, q, out, rss, NULL, users, n_users);
+                       pool_k, pool_v, q, out, rss, NULL, NULL, users, n_users);
 }
 
-/* The same, and the scale of the scores' rounding errors in sss (see above). */
+/* The same, and the scale of the scores' rounding errors in sss and of the single-precision additions in acs (see above; acs may be NULL). */
 int ckv_oracle_attend_scales(int B, int H, int d_g, int d_u, int P, int Nq, int dtype, int mode, int share,
                              double scale, int64_t pool_ld,
                              const int32_t *lengths, const int32_t *idx_k, const int32_t *idx_v,
                              const void *user_k, const void *user_v,
                              const void *pool_k, const void *pool_v, const void *q,
-                             double *out, double *rss, double *sss, const int32_t *users, int n_users)
+                             double *out, double *rss, double *sss, double *acs, const int32_t *users, int n_users)
 {
     return attend_impl(B, H, d_g, d_u, P, Nq, dtype, mode, share, scale, pool_ld, lengths, idx_k, idx_v, user_k, user_v,
-                       pool_k, pool_v, q, out, rss, sss, users, n_users);
+                       pool_k, pool_v, q, out, rss, sss, acs, users, n_users);
 }
 
 /*

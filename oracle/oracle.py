@@ -38,7 +38,7 @@ def _load():
         lib.ckv_oracle_attend_rss.restype = ctypes.c_int
         lib.ckv_oracle_attend_rss.argtypes = [i32] * 9 + [dbl, i64] + [vp] * 10 + [vp, i32]
         lib.ckv_oracle_attend_scales.restype = ctypes.c_int
-        lib.ckv_oracle_attend_scales.argtypes = [i32] * 9 + [dbl, i64] + [vp] * 11 + [vp, i32]
+        lib.ckv_oracle_attend_scales.argtypes = [i32] * 9 + [dbl, i64] + [vp] * 12 + [vp, i32]
         lib.ckv_oracle_reconstruct.restype = ctypes.c_int
         lib.ckv_oracle_reconstruct.argtypes = [i32] * 6 + [i64, i64] + [vp] * 8
         lib.ckv_oracle_cache_size.restype = None
@@ -71,10 +71,11 @@ def attend(w, users=None, with_rss=False, with_scales=False):
     Rows of users not listed in `users` are NaN.
     with_rss: also return, per output element c, the scale the tests' comparison rule uses (same shape):
     sqrt(sum over groups g of positions with one and the same weight of (sum_{i in g} w_i V_i[c])^2).
-    with_scales: return (out, rss, sss), sss being the scale of the scores' rounding errors: with
+    with_scales: return (out, rss, sss, acs), sss being the scale of the scores' rounding errors: with
     A_i = |scale| sum_k |q_k K_ik|, sqrt(sum over the same groups of (sum_{i in g} k_i)^2), where
     k_i = w_i (V_i[c] - out[c]) A_i for softmax and f'(s_i) V_i[c] A_i / n for SiLU/n (first-order effect of an
-    error delta_i A_i of score i on the output).
+    error delta_i A_i of score i on the output), and acs the scale of the roundings of out[c]'s own additions when they are
+    done in single precision in an unknown order: sqrt(n) * (|out[c]| + sqrt(sum_i (w_i V_i[c])^2)), n the user's length.
     """
     lib = _load()
     dt = w["dtype"]
@@ -95,7 +96,8 @@ def attend(w, users=None, with_rss=False, with_scales=False):
     if with_scales:
         rss = np.full(out.shape, np.nan, dtype=np.float64)
         sss = np.full(out.shape, np.nan, dtype=np.float64)
-        rc = lib.ckv_oracle_attend_scales(*head, _ptr(out), _ptr(rss), _ptr(sss), uptr, nu)
+        acs = np.full(out.shape, np.nan, dtype=np.float64)
+        rc = lib.ckv_oracle_attend_scales(*head, _ptr(out), _ptr(rss), _ptr(sss), _ptr(acs), uptr, nu)
     elif with_rss:
         rss = np.full(out.shape, np.nan, dtype=np.float64)
         rc = lib.ckv_oracle_attend_rss(*head, _ptr(out), _ptr(rss), uptr, nu)
@@ -104,7 +106,7 @@ def attend(w, users=None, with_rss=False, with_scales=False):
     if rc != 0:
         raise ValueError("ckv_oracle_attend rejected its arguments")
     if with_scales:
-        return out, rss, sss
+        return out, rss, sss, acs
     return (out, rss) if with_rss else out
 
 

@@ -6,10 +6,12 @@ close to zero (weights of both signs in the SiLU form, or value rows that cancel
 error they carry is set by the size of their summands, so "relative" needs a scale per element.
 The rule, for every output element:
 
-    |g_c - r_c| <= tol * |r_c| + tol * rss_c + u_s * sss_c,
+    |g_c - r_c| <= tol * |r_c| + tol * rss_c + u_s * sss_c + u_a * acs_c,
     rss_c = sqrt(sum over groups g of (sum_{i in g} w_i V_i[c])^2),   a group = the positions with one and the same weight
     sss_c = sqrt(sum over groups g of (sum_{i in g} k_i)^2),          k_i = d r_c / d s_i * A_i,  A_i = |scale| sum_k |q_k K_ik|
     u_s   = (d_a + 1) * 2^-24
+    acs_c = sqrt(n) * (|r_c| + sqrt(sum_i (w_i V_i[c])^2)),           n = the user's history length
+    u_a   = 8 * 2^-24
 
 Where it comes from: the kernels keep products and sums in fp32 and round two things below that,
 the weights w_i (to the storage type before the second matrix product: relative error at most
@@ -33,7 +35,18 @@ order an error delta_i A_i of score i moves the output by k_i delta_i (softmax: 
 normalisation included; SiLU/n: k_i = f'(s_i) V_i[c] A_i / n); equal rows have equal scores and err alike, different
 rows err independently, hence the same grouping.  With fp32 storage, 256 columns and SiLU this term is about twice
 tol * rss_c; with bf16 storage it is a hundredth of it.
-rss_c and sss_c come from the CPU oracle (fp64, from the oracle's inputs), never from the GPU output.
+The fourth term is the rounding of the output's own additions.  sum_i w_i V_i[c] is added up in fp32 with either
+storage type, n - 1 additions in an order the oracle does not know, each rounding a partial sum by at most 2^-24 of it
+(and, with fp32 storage, each product once).  A partial sum of k of the n summands, in an order unrelated to their values,
+has mean (k/n) r_c and a spread of at most rs_c = sqrt(sum_i (w_i V_i[c])^2), so independent roundings add up to a standard
+deviation of at most 2^-24 sqrt(n) (0.19 |r_c| + 0.36 rs_c) (uniform roundings, variance u^2 / 3; sum over k of (k/n)^2 is
+n/3 and of (k/n)(1 - k/n) is n/6; the products' own roundings add rs_c^2 u^2 / 3).  u_a = 8 * 2^-24 is at least eighteen of these
+standard deviations, the margin of the second term.  Where the weights differ this term is small beside tol * rss_c (fp32, n = 1024:
+a seventh of it; bf16: a ten-thousandth).  It matters where the weights are all equal (a key pool of one row, q = 0): then
+every error of the weights is common to all summands, rss_c collapses to |r_c|, and on an element whose value rows nearly
+cancel nothing but this term stands for the additions (found on a seeded random shape: fp32 storage, one key row, 64
+positions; plain IEEE fp32 addition in history order exceeds the first three terms there by 1.4, as the kernel did by 1.8).
+rss_c, sss_c and acs_c come from the CPU oracle (fp64, from the oracle's inputs), never from the GPU output.
 Users with an empty history have r = 0 and rss = 0: their rows must be exactly zero.
 The norm-wise figure max|g - r| / max|r| is reported beside it.
 """
@@ -50,12 +63,16 @@ def score_unit(d_a):
     return (d_a + 1) * 2.0 ** -24
 
 
-def compare(gpu, ref, rss, dtype, sss=None):
-    """Statistics of one comparison: gpu, ref, rss, sss float64 arrays of one shape [...][d_a] (sss = None leaves the
-    third term out: a stricter rule).
-    worst_ratio = max over elements of |g - r| / (tol |r| + tol rss + u_s sss)  (<= 1 passes; an element with
+ACC_UNIT = 8 * 2.0 ** -24   # u_a of the rule above
+
+
+def compare(gpu, ref, rss, dtype, sss=None, acs=None):
+    """Statistics of one comparison: gpu, ref, rss, sss, acs float64 arrays of one shape [...][d_a] (sss = None or
+    acs = None leaves the third or fourth term out: a stricter rule).
+    worst_ratio = max over elements of |g - r| / (tol |r| + tol rss + u_s sss + u_a acs)  (<= 1 passes; an element with
     a zero bound counts as 0 if it is exact and as infinity if it is not)."""
     assert gpu.shape == ref.shape == rss.shape and (sss is None or sss.shape == ref.shape)
+    assert acs is None or acs.shape == ref.shape
     tol = TOL[dtype]
     if ref.size == 0:
         return {"tol": tol, "elements": 0, "norm_err": 0.0, "worst_ratio": 0.0, "finite": True}
@@ -64,6 +81,8 @@ def compare(gpu, ref, rss, dtype, sss=None):
     bound = tol * np.abs(ref) + tol * rss
     if sss is not None:
         bound = bound + score_unit(ref.shape[-1]) * sss
+    if acs is not None:
+        bound = bound + ACC_UNIT * acs
     with np.errstate(divide="ignore", invalid="ignore"):
         ratio = np.where(bound > 0, err / bound, np.where(err == 0, 0.0, np.inf))
     return {"tol": tol, "elements": int(ref.size), "finite": finite,
@@ -71,22 +90,29 @@ def compare(gpu, ref, rss, dtype, sss=None):
             "worst_ratio": float(np.nanmax(ratio)) if finite else float("inf")}
 
 
-def check(gpu, ref, rss, dtype, rows=None, what="", sss=None):
-    """gpu, ref, rss, sss: float64 [B][H][Nq][d_a]; rows: optional index of the users to compare.
+def check(gpu, ref, rss, dtype, rows=None, what="", sss=None, acs=None):
+    """gpu, ref, rss, sss, acs: float64 [B][H][Nq][d_a]; rows: optional index of the users to compare.
     Asserts the rule above on every element and returns the norm-wise error."""
     if rows is not None:
         gpu, ref, rss = gpu[rows], ref[rows], rss[rows]
         sss = None if sss is None else sss[rows]
+        acs = None if acs is None else acs[rows]
     assert np.isfinite(ref).all() and np.isfinite(rss).all(), f"{what}: oracle produced non-finite values"
     assert sss is None or np.isfinite(sss).all(), f"{what}: oracle produced non-finite values"
+    assert acs is None or np.isfinite(acs).all(), f"{what}: oracle produced non-finite values"
     assert np.isfinite(gpu).all(), f"{what}: GPU produced non-finite values"
-    st = compare(gpu, ref, rss, dtype, sss)
-    assert st["worst_ratio"] <= 1.0, (f"{what}: element error exceeds tol={st['tol']}: worst |g-r| / (tol|r| + tol rss + u_s sss) = "
+    st = compare(gpu, ref, rss, dtype, sss, acs)
+    assert st["worst_ratio"] <= 1.0, (f"{what}: element error exceeds tol={st['tol']}: worst |g-r| / (tol|r| + tol rss + u_s sss + u_a acs) = "
                                       f"{st['worst_ratio']:.3f}, norm-wise {st['norm_err']:.3e}")
     return st["norm_err"]
 
 
-def check_against_oracle(gpu, w, users=None, what=""):
-    """Run the oracle on workload `w` (all users, or the listed ones) and check `gpu` against it."""
-    ref, rss, sss = oracle.attend(w, users=users, with_scales=True)
-    return check(gpu, ref, rss, w["dtype"], rows=users, what=what, sss=sss)
+def check_against_oracle(gpu, w, users=None, what="", queries=None):
+    """Run the oracle on workload `w` (all users, or the listed ones; all queries, or the listed ones of every user and head:
+    the oracle then gets the workload with only those queries) and check `gpu` against it."""
+    if queries is not None:
+        queries = np.asarray(queries)
+        w = dict(w, q=np.ascontiguousarray(w["q"][:, :, queries]), Nq=len(queries))
+        gpu = gpu[:, :, queries]
+    ref, rss, sss, acs = oracle.attend(w, users=users, with_scales=True)
+    return check(gpu, ref, rss, w["dtype"], rows=users, what=what, sss=sss, acs=acs)

@@ -555,6 +555,55 @@ def test_random_shapes_with_near_cancelling_rows(gpu, block, case):
     run_and_check(gpu, w, what)
 
 
+def random_shape_many_queries(case):
+    """Seeded random shape number `case` of a second generator, aimed at the fp32 matrix-core kernels and the
+    register-staged bf16 kernel: head widths that are not 64, 128 or 256 columns, wide and odd user slices, six queries
+    or more, pools of one or two rows among the sizes.  Returns (workload, description)."""
+    rng = np.random.default_rng(777000 + case)
+    fp32 = rng.random() < 0.5
+    dtype = wl.F32 if fp32 else wl.BF16
+    if fp32:
+        d_a = int(rng.choice([8, 16, 24, 48, 64, 72, 96, 100, 128, 130, 160, 192, 200, 256]))
+    else:
+        d_a = int(rng.choice([8, 16, 24, 32, 40, 48, 56, 72, 80, 96, 104, 120, 64, 128]))
+    d_u = min(int(rng.choice([0, 1, 2, 3, 4, 5, 8, 9, 12, 16, 20, 24, 32])), d_a)
+    if not fp32 and d_a in (64, 128):  # user widths that the direct-to-LDS kernel does not take
+        d_u = int(rng.choice([9, 11, 20, 24, 32]))
+    d_g = d_a - d_u
+    al = 4 if fp32 else 8
+    pool_ld = 0 if d_g == 0 else int(rng.choice([(d_g + al - 1) // al * al, (d_a + al - 1) // al * al, (d_a + al - 1) // al * al + al]))
+    Nq = int(rng.choice([6, 8, 9, 16, 31, 32, 33, 40, 64, 65, 100, 128, 129, 200]))
+    share = int(rng.choice([wl.SHARE_KV, wl.SHARE_KV, wl.SHARE_K, wl.SHARE_V])) if d_g > 0 else wl.SHARE_KV
+    mode = int(rng.choice([wl.SOFTMAX, wl.SILU_OVER_N]))
+    B = int(rng.integers(1, 6))
+    lengths = rng.choice([0, 1, 31, 32, 33, 64, 100, 257, 900, 2500], size=B).astype(np.int32)
+    H, P = int(rng.integers(1, 3)), int(rng.choice([1, 2, 77, 700, 3000]))
+    kw = dict(pool_ld=pool_ld) if d_g > 0 else {}
+    w = wl.make(B=B, L=None, H=H, d_a=d_a, d_u=d_u, P=P, idx=("zipf", 1.1) if rng.random() < 0.3 else "uniform", Nq=Nq, mode=mode,
+                dtype=dtype, sigma_pool=d_a ** -0.5, seed=5000 + case, lengths=lengths, share=share, **kw)
+    return w, (f"random many-query shape {case}: dtype={'f32' if fp32 else 'bf16'} d_a={d_a} d_u={d_u} ld={pool_ld} Nq={Nq} "
+               f"share={share} lengths={lengths.tolist()}")
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_seeded_random_shapes_many_queries(gpu, block):
+    """Forty seeded shapes of the second generator per block.  Case 77 (fp32, keys from a pool of one row, values an
+    ordinary cache, 64 positions: all weights equal, some value columns nearly cancel) is the shape that showed the
+    comparison rule needs its term for the rounding of the additions."""
+    for case in range(40 * block, 40 * block + 40):
+        w, what = random_shape_many_queries(case)
+        run_and_check(gpu, w, what)
+
+
+@pytest.mark.parametrize("dtype,d_a,Nq", [(wl.F32, 130, 9), (wl.F32, 64, 1), (wl.BF16, 128, 9), (wl.BF16, 72, 16), (wl.BF16, 64, 2)])
+@pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
+def test_equal_weights_over_cancelling_value_rows(gpu, mode, dtype, d_a, Nq):
+    # keys from a pool of one row and no user columns: every position has the same weight; the values are an ordinary cache
+    w = make([64, 64, 31, 1000, 1], dtype, mode, d_a=d_a, d_u=0, H=2, P=1, Nq=Nq, seed=5077, share=wl.SHARE_K,
+             pool_ld=(d_a + 7) // 8 * 8)
+    run_and_check(gpu, w, f"equal weights, dtype {dtype}, d_a={d_a}, Nq={Nq}, mode {mode}")
+
+
 @pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
 @pytest.mark.parametrize("d_a,d_u,pool_ld,Nq", [(96, 8, 88, 64), (32, 4, 32, 16), (40, 5, 40, 20), (120, 16, 104, 130),
                                                  (8, 2, 8, 9), (72, 0, 72, 33), (100, 3, 104, 64), (56, 56, 0, 40)])

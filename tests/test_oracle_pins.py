@@ -489,7 +489,7 @@ def test_score_scale_matches_autograd_jacobian(dtype, mode, share):
     """d out[c] / d s_i from torch's autograd through torch's own softmax / SiLU, times A_i = |scale| sum_k |q_k K_ik|;
     the random workload has no two equal rows, so every position is a group of its own."""
     w = small(dtype=dtype, mode=mode, share=share)
-    out, rss, sss = oracle.attend(w, with_scales=True)
+    out, rss, sss, _ = oracle.attend(w, with_scales=True)
     o2, r2 = oracle.attend(w, with_rss=True)
     np.testing.assert_array_equal(out, o2)                        # the extra outputs change nothing
     np.testing.assert_array_equal(rss, r2)
@@ -517,7 +517,7 @@ def test_score_scale_groups_positions_of_equal_score(mode):
     # a key pool of three rows and no user columns: positions with the same key row have the same score and the same
     # error, so their effects are added before squaring
     w = small(mode=mode, d_u=0, d_a=12, P=3, lengths=(50, 7), H=1, Nq=2)
-    out, _, sss = oracle.attend(w, with_scales=True)
+    out, _, sss, _ = oracle.attend(w, with_scales=True)
     q = wl.to_f64(w["q"], w["dtype"])
     off = np.concatenate([[0], np.cumsum(w["lengths"])])
     for b, h, K, V in dense_kv(w):
@@ -539,11 +539,11 @@ def test_score_scale_groups_positions_of_equal_score(mode):
 def test_score_scale_closed_forms():
     # softmax over one position: the weight is 1 whatever the score, an error of the score changes nothing
     w = small(lengths=(1,), Nq=2, mode=wl.SOFTMAX)
-    _, _, sss = oracle.attend(w, with_scales=True)
+    _, _, sss, _ = oracle.attend(w, with_scales=True)
     assert np.all(sss == 0)
     # SiLU over one position: out = f(s) V, so the scale is |f'(s)| A |V| with f'(s) = sigma (1 + s (1 - sigma))
     w = small(lengths=(1,), Nq=2, mode=wl.SILU_OVER_N, H=1)
-    _, _, sss = oracle.attend(w, with_scales=True)
+    _, _, sss, _ = oracle.attend(w, with_scales=True)
     q = wl.to_f64(w["q"], w["dtype"])
     for b, h, K, V in dense_kv(w):
         K, V = K.numpy()[0], V.numpy()[0]
@@ -555,5 +555,46 @@ def test_score_scale_closed_forms():
     # q = 0: A = 0, no error to propagate
     w = small(lengths=(40,), H=1, Nq=1)
     w["q"] = np.zeros_like(w["q"])
-    _, _, sss = oracle.attend(w, with_scales=True)
+    _, _, sss, _ = oracle.attend(w, with_scales=True)
     assert np.all(sss == 0)
+
+
+# ---------------------------------------------------------------------------------------------
+# the scale of the roundings of the output's own additions: sqrt(n) (|out| + root-sum-square of the summands one by one)
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+@pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
+@pytest.mark.parametrize("share", [wl.SHARE_KV, wl.SHARE_V])
+def test_addition_scale_matches_explicit_weights(dtype, mode, share):
+    w = small(dtype=dtype, mode=mode, share=share)
+    out, rss, _, acs = oracle.attend(w, with_scales=True)
+    q = wl.to_f64(w["q"], dtype)
+    for b, h, K, V in dense_kv_shared(w):
+        n = K.shape[0]
+        if n == 0:
+            assert np.all(acs[b, h] == 0)
+            continue
+        s = torch.from_numpy(w["scale"] * q[b, h]) @ K.T
+        wt = torch.softmax(s, dim=-1) if mode == wl.SOFTMAX else torch.nn.functional.silu(s) / n
+        terms = wt[:, :, None] * V[None, :, :]                    # [Nq][n][d_a]
+        want = np.sqrt(n) * (terms.sum(dim=1).abs() + terms.pow(2).sum(dim=1).sqrt()).numpy()
+        np.testing.assert_allclose(acs[b, h], want, rtol=1e-11, atol=1e-14)
+
+
+def test_addition_scale_does_not_group_equal_weights():
+    # q = 0, softmax: every weight is 1/n.  The weights' scale collapses to |out| (one group); the additions' scale
+    # still sees every summand: sqrt(n) (|mean_i V_i| + sqrt(sum_i V_i^2) / n)
+    w = small(lengths=(40,), H=1, Nq=1)
+    w["q"] = np.zeros_like(w["q"])
+    out, rss, _, acs = oracle.attend(w, with_scales=True)
+    for b, h, K, V in dense_kv(w):
+        V = V.numpy()
+        np.testing.assert_allclose(acs[b, h, 0], np.sqrt(40) * (np.abs(V.mean(axis=0)) + np.sqrt((V ** 2).sum(axis=0)) / 40), rtol=1e-12)
+    np.testing.assert_allclose(rss, np.abs(out), rtol=1e-12)
+    # one position: the sum has one summand, the scale is twice its size
+    w = small(lengths=(1,), Nq=2)
+    out, _, _, acs = oracle.attend(w, with_scales=True)
+    np.testing.assert_allclose(acs, 2 * np.abs(out), rtol=1e-14)
+    # users not listed stay NaN, like out
+    w = small()
+    _, _, _, acs = oracle.attend(w, users=[1], with_scales=True)
+    assert np.isnan(acs[0]).all() and np.isfinite(acs[1]).all()

@@ -96,7 +96,8 @@ def test_static_scratch_entry_point_refuses_what_does_not_fit():
             s.attend(static_scratch=True)
         assert e.value.code == ckv.CKV_ERR_UNSUPPORTED and "static scratch" in str(e.value)
         s.attend()      # the ordinary entry point still serves the handle
-        check_against_oracle(s.output(), w, what="after the refused call")
+        # (a sample of the queries, one from every block of 16: the oracle works through 150001 positions per query on two threads)
+        check_against_oracle(s.output(), w, what="after the refused call", queries=np.arange(5, 384, 16))
     # a handle without split histories uses no scratch at all and is served
     w = make((100, 33, 0), wl.BF16, wl.SOFTMAX, d_a=64, d_u=8, H=1, P=50, Nq=16)
     with session.Session(w) as s:
