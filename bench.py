@@ -48,6 +48,8 @@ DESCRIBE = {
     "cfg4_plain": "config 4 with an ordinary K/V cache (d_g = 0): the same decode without compression",
     "d256_u4": "256-column heads (Table 1's width, CR 0.020): B=128 L~U[2048,8192] H=4 d=252+4 P=32768 Nq=128 softmax bf16",
     "d256_u10": "256-column heads (Table 1's width, CR 0.043): B=128 L~U[2048,8192] H=4 d=246+10 P=32768 Nq=128 softmax bf16",
+    "tgt256_u1": "target attention over 256-column heads, d_u = 1 (Table 1's CR 0.008): B=1024 L~U[200,2000] H=1 d=255+1 P=16384 Nq=1 softmax bf16",
+    "tgt256_u10": "target attention over 256-column heads, d_u = 10 (Table 1's CR 0.043): B=1024 L~U[200,2000] H=1 d=246+10 P=16384 Nq=1 softmax bf16",
     "cfg3_f32_d256": "config 3's shape with 256-column fp32 heads: B=128 L=1024 H=4 d=252+4 P=16384 Zipf(1.1) Nq=64 SiLU/L fp32",
     "cfg5": "config 5 large batch: B=8192 L~U[512,2048] H=4 d=62+2 P=1048576 Zipf(1.05) Nq=16 softmax bf16",
 }
@@ -314,7 +316,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=100,
                     help="untimed steps; the GPU needs ~50 back-to-back launches to reach its steady clocks")
     ap.add_argument("--workload", default="cfg4", choices=sorted(DESCRIBE))
-    ap.add_argument("--also", default="cfg1,cfg2_f32,cfg2_bf16,cfg3,cfg5,cfg3_ck,d256_u4,cfg3_f32_d256", help="comma list of further workloads ('' for none)")
+    ap.add_argument("--also", default="cfg1,cfg2_f32,cfg2_bf16,cfg3,cfg5,cfg3_ck,d256_u4,cfg3_f32_d256,tgt256_u1,tgt256_u10", help="comma list of further workloads ('' for none)")
     ap.add_argument("--steady", type=int, default=200,
                     help="launches of the extra steady-state block per workload, reported under 'steady_state' (0: none)")
     ap.add_argument("--parity-budget", type=float, default=6.0,

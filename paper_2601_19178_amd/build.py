@@ -12,7 +12,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libckv.so")
-SOURCES = ["ckv_api.hip", "ckv_stream.hip", "ckv_mfma.hip", "ckv_mfma32.hip", "ckv_dma.hip", "ckv_prefill.hip"]
+SOURCES = ["ckv_api.hip", "ckv_stream.hip", "ckv_streamw.hip", "ckv_mfma.hip", "ckv_mfma32.hip", "ckv_dma.hip", "ckv_prefill.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -40,6 +40,7 @@ struct Options {
     int sched = 0;             // "dma_sched": 0 default (static), 1 static, 2 dynamic
     int nw = 0, qg = 0;        // "dma_shape" = "nw,qg": wavefronts per workgroup, query groups per wavefront (0: from Nq)
     double slow_speed = -1.0;  // "dma_slow_speed": weight of a workgroup that shares its SIMDs with an older one (< 0: default)
+    bool stream_narrow = false;  // "stream_impl" = "narrow": the column-block streaming kernel also where the wide-row one would run
     bool debug = false;        // "debug" = "1": print the chosen split and list statistics to stderr
 };
 thread_local Options g_opt;
@@ -682,6 +683,16 @@ void choose_variant(ckv_cache* c) {
     c->ncb = ncb <= 1 ? 1 : (ncb <= 2 ? 2 : (ncb <= 4 ? 4 : (ncb <= 8 ? 8 : 16)));
     c->QB = s.Nq;
     c->nw = 4;  // wavefronts per item; plan_work drops to 2 when the items outnumber the resident workgroups
+    // Rows that the kernel above would fetch in several column blocks, or in lanes of less than 16 bytes because the
+    // user slice breaks the alignment (d_u = 1, 2, 3, 6, 10 of Table 1's 256 columns), go to the wide-row kernel, which
+    // fetches pool row and slice separately.
+    c->sw_g = (c->ncb == 1 && (size_t)c->vec * esize(s.dtype) == 16) || g_opt.stream_narrow ? 0 : ckv_streamw_lanes(s);
+    if (c->sw_g) {
+        c->sw_nq = s.Nq >= 2 ? 2 : 1;
+        snprintf(c->variant, sizeof c->variant, "streamw_%s_g%d_q%d_%s", s.dtype == CKV_F32 ? "f32" : "bf16", c->sw_g, c->sw_nq,
+                 s.mode == CKV_SOFTMAX ? "softmax" : "silu");
+        return;
+    }
     snprintf(c->variant, sizeof c->variant, "stream_%s_v%d_c%d%s_%s", s.dtype == CKV_F32 ? "f32" : "bf16", c->vec,
              c->ncb, c->grp == 8 ? "_g8" : "", s.mode == CKV_SOFTMAX ? "softmax" : "silu");
 }
@@ -793,7 +804,7 @@ static int cache_new(const char* who, const ckv_shape* shape, const int32_t* len
     c->offloaded = offloaded ? 1 : 0;
     choose_variant(c);
     // column blocks the streaming kernel is built for: 8 (16 when it moves single elements)
-    if (c->family == CKV_K_STREAM && (d_a + c->grp * c->vec - 1) / (c->grp * c->vec) > (c->vec == 1 ? 16 : 8)) {
+    if (c->family == CKV_K_STREAM && !c->sw_g && (d_a + c->grp * c->vec - 1) / (c->grp * c->vec) > (c->vec == 1 ? 16 : 8)) {
         const int limit = c->grp * c->vec * (c->vec == 1 ? 16 : 8);
         delete c;
         return fail(CKV_ERR_UNSUPPORTED, "%s: d_a = %lld exceeds the streaming kernel's limit of %d columns at this alignment", who,
@@ -856,12 +867,20 @@ static void plan_work(ckv_cache* c, const int32_t* lengths, const std::vector<in
     }
     c->n_items = (int)p.items.size();
     c->n_merge = (int)p.merges.size();
-    if (c->family == CKV_K_STREAM && c->ncb == 1) {
-        // The kernel holds a tile in registers, which leaves room for four wavefronts per SIMD at 8 bytes per
-        // lane and row and two at 16.  Four wavefronts per item give the shortest chain for one item; when
-        // that needs more than one round of workgroups but two per item fit in a single round, two are faster.
-        const int64_t resident = (int64_t)cus * 4 * ((size_t)c->grp * esize(c->shape.dtype) * (size_t)c->vec <= 128 ? 4 : 2);
-        if ((int64_t)c->n_items * 4 > resident && (int64_t)c->n_items * 2 <= resident) {
+    if (c->family == CKV_K_STREAM && (c->ncb == 1 || c->sw_g)) {
+        // The column-block kernel holds a tile in registers, which leaves room for four wavefronts per SIMD at 8 bytes
+        // per lane and row and two at 16; the wide-row kernel has two or three.  Four wavefronts per item give the
+        // shortest chain for one item; when that needs more than one round of workgroups, two per item are faster
+        // (the column-block kernel: where two per item fit in a single round; the wide-row kernel: where an item is at most
+        // two tiles per wavefront, 512 positions: 1024 users of 200 positions at 256 bf16 columns 44 -> 33 us, of 1000
+        // positions 127 -> 132 us).
+        const int per_simd = c->sw_g ? ckv_streamw_waves_per_simd(c->shape, c->sw_g, c->sw_nq)
+                                     : ((size_t)c->grp * esize(c->shape.dtype) * (size_t)c->vec <= 128 ? 4 : 2);
+        const int64_t resident = (int64_t)cus * 4 * per_simd;
+        int64_t positions = 0;
+        for (const ckv_item& it : p.items) positions += it.n;
+        const bool fits = c->sw_g ? positions <= (int64_t)512 * c->n_items : (int64_t)c->n_items * 2 <= resident;
+        if ((int64_t)c->n_items * 4 > resident && fits) {
             c->nw = 2;
             const size_t len = strlen(c->variant);
             if (len + 4 < sizeof c->variant) memcpy(c->variant + len, "_w2", 4);
@@ -1241,6 +1260,7 @@ static int attend_common(const char* who, const ckv_cache* c, const void* pool_k
     e = c->family == CKV_K_DMA      ? ckv_launch_dma(c, a, st)
         : c->family == CKV_K_MFMA   ? ckv_launch_mfma(c, a, st)
         : c->family == CKV_K_MFMA32 ? ckv_launch_mfma32(c, a, st)
+        : c->sw_g                   ? ckv_launch_streamw(c, a, st)
                                     : ckv_launch_stream(c, a, st);
     if (e != hipSuccess) return fail(CKV_ERR_HIP, "%s: kernel launch (%s): %s", who, c->variant, hipGetErrorString(e));
     if (c->timing) {
@@ -1335,6 +1355,10 @@ int ckv_set_option(const char* key, const char* value) {
         if (!unset && (end == value || !(v > 0.0) || v > 4.0))
             return fail(CKV_ERR_UNSUPPORTED, "ckv_set_option: dma_slow_speed takes a number in (0, 4], not \"%s\"", value);
         g_opt.slow_speed = v;
+    } else if (strcmp(key, "stream_impl") == 0) {
+        if (!unset && strcmp(value, "narrow") != 0 && strcmp(value, "auto") != 0)
+            return fail(CKV_ERR_UNSUPPORTED, "ckv_set_option: stream_impl takes \"narrow\" or \"auto\", not \"%s\"", value);
+        g_opt.stream_narrow = !unset && strcmp(value, "narrow") == 0;
     } else if (strcmp(key, "debug") == 0) {
         g_opt.debug = !unset && strcmp(value, "0") != 0;
     } else {

@@ -94,6 +94,7 @@ struct ckv_cache {
     int family;          // ckv_kernel_family
     int vec, ncb;        // stream kernel: elements per lane per column block, column blocks
     int grp;             // stream kernel: lanes that share a row (16 or 8)
+    int sw_g, sw_nq;     // wide-row stream kernel: lanes per row (0: the shape runs in the other stream kernel), queries per pass
     int nw, tp;          // mfma kernels: waves per workgroup, positions per tile
     int nui;             // dma kernel: user-slice load instructions per wavefront and tile
     int qg;              // dma kernel: groups of 32 queries per wavefront
@@ -117,6 +118,10 @@ struct ckv_cache {
 
 // Launchers (each returns hipGetLastError() of its launch).
 hipError_t ckv_launch_stream(const ckv_cache* c, const ckv_args& a, hipStream_t s);
+// Streaming kernel for wide rows and user slices of any width; lanes per row it would use for a shape (0: not served).
+hipError_t ckv_launch_streamw(const ckv_cache* c, const ckv_args& a, hipStream_t s);
+int ckv_streamw_lanes(const ckv_shape& s);
+int ckv_streamw_waves_per_simd(const ckv_shape& s, int G, int nq);
 hipError_t ckv_launch_mfma(const ckv_cache* c, const ckv_args& a, hipStream_t s);
 // Resident workgroups per CU of the chosen mfma kernel (0 if the shape has no mfma kernel).
 int ckv_mfma_occupancy(int d_a, int nw, int tp, int mode);

@@ -62,6 +62,12 @@ CONFIGS = {
                     mode=SOFTMAX, dtype=BF16, sigma_pool=1.0 / 16.0, seed=1006),
     "d256_u10": dict(B=128, L=(2048, 8192), H=4, d_a=256, d_u=10, P=32768, idx="uniform", Nq=128,
                      mode=SOFTMAX, dtype=BF16, sigma_pool=1.0 / 16.0, seed=1006),
+    # target attention (one query per user, section 2.1) over 256-column heads with Table 1's smallest and largest user
+    # widths (CR 0.008 is d_u = 1, CR 0.043 is d_u = 10), histories of the benchmarks' lengths, a pool of the default size
+    "tgt256_u1": dict(B=1024, L=(200, 2000), H=1, d_a=256, d_u=1, P=16384, idx="uniform", Nq=1,
+                      mode=SOFTMAX, dtype=BF16, sigma_pool=1.0 / 16.0, seed=1008),
+    "tgt256_u10": dict(B=1024, L=(200, 2000), H=1, d_a=256, d_u=10, P=16384, idx="uniform", Nq=1,
+                       mode=SOFTMAX, dtype=BF16, sigma_pool=1.0 / 16.0, seed=1008),
     # config 3's batch shape with 256-column heads in fp32 storage (128 users): the fp32 matrix-core kernel's widest instance
     "cfg3_f32_d256": dict(B=128, L=(1024, 1024), H=4, d_a=256, d_u=4, P=16384, idx=("zipf", 1.1), Nq=64,
                           mode=SILU_OVER_N, dtype=F32, sigma_pool=1.0 / 16.0, seed=1007),

@@ -119,6 +119,78 @@ def test_stream_split_history(gpu):
     run_and_check(gpu, w, "stream split silu")
 
 
+# wide-row streaming kernel: rows fetched in 16-byte lanes (8, 16, 32 or 64 lanes per row) whatever the user width,
+# user slices element by element
+@pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
+@pytest.mark.parametrize("dtype,d_a,d_u,pool_ld,Nq,expect", [
+    # the widths behind Table 1's compression ratios: d_u of 256 columns, one query (target attention)
+    (wl.BF16, 256, 1, 256, 1, "streamw_bf16_g32_q1"), (wl.BF16, 256, 2, 256, 1, "streamw_bf16_g32_q1"),
+    (wl.BF16, 256, 3, 256, 1, "streamw_bf16_g32_q1"), (wl.BF16, 256, 4, 256, 1, "streamw_bf16_g32_q1"),
+    (wl.BF16, 256, 6, 256, 1, "streamw_bf16_g32_q1"), (wl.BF16, 256, 10, 248, 1, "streamw_bf16_g32_q1"),
+    (wl.BF16, 256, 10, 256, 2, "streamw_bf16_g32_q2"), (wl.BF16, 256, 4, 264, 2, "streamw_bf16_g32_q2"),
+    (wl.F32, 256, 1, 256, 1, "streamw_f32_g64_q1"), (wl.F32, 256, 6, 252, 2, "streamw_f32_g64_q2"),
+    (wl.F32, 256, 10, 256, 5, "streamw_f32_g64_q2"),             # five queries: two passes of two and one of one
+    # fewer lanes per row; slices of up to eight columns per lane of the row's octets
+    (wl.BF16, 64, 3, 64, 1, "streamw_bf16_g8_q1"), (wl.BF16, 64, 8, 56, 2, "stream_bf16_v8_c1_g8"),
+    (wl.BF16, 64, 6, 64, 2, "streamw_bf16_g8_q2"), (wl.BF16, 64, 12, 56, 1, "streamw_bf16_g16_q1"),
+    (wl.BF16, 128, 5, 128, 1, "streamw_bf16_g16_q1"), (wl.BF16, 128, 14, 120, 2, "streamw_bf16_g16_q2"),
+    (wl.BF16, 72, 9, 64, 7, "streamw_bf16_g16_q2"),               # a width no matrix-core kernel takes below eight queries
+    (wl.BF16, 200, 30, 176, 1, "streamw_bf16_g32_q1"), (wl.BF16, 512, 64, 448, 1, "streamw_bf16_g64_q1"),
+    (wl.F32, 64, 6, 60, 1, "streamw_f32_g16_q1"), (wl.F32, 128, 2, 128, 2, "streamw_f32_g32_q2"),
+    (wl.F32, 100, 7, 96, 3, "streamw_f32_g32_q2"), (wl.F32, 24, 24, 0, 1, "stream_f32"),   # (d_g = 0 with rows of 96 bytes: whole 16-byte lanes)
+])
+def test_wide_row_streaming_kernel(gpu, mode, dtype, d_a, d_u, pool_ld, Nq, expect):
+    kw = dict(pool_ld=pool_ld) if d_a > d_u else {}
+    w = make(RAGGED + (700,), dtype, mode, d_a=d_a, d_u=d_u, H=2, P=77, Nq=Nq, **kw)
+    run_and_check(gpu, w, f"wide-row stream d_a={d_a} d_u={d_u} ld={pool_ld} Nq={Nq}", expect_variant=expect)
+
+
+@pytest.mark.parametrize("share", [wl.SHARE_K, wl.SHARE_V])
+@pytest.mark.parametrize("dtype,d_a,d_u,Nq", [(wl.BF16, 256, 3, 1), (wl.BF16, 128, 10, 2), (wl.F32, 64, 5, 1), (wl.F32, 256, 4, 2)])
+def test_wide_row_streaming_kernel_one_side_shared(gpu, share, dtype, d_a, d_u, Nq):
+    for mode in (wl.SOFTMAX, wl.SILU_OVER_N):
+        w = make(RAGGED, dtype, mode, d_a=d_a, d_u=d_u, H=2, P=50, Nq=Nq, share=share, idx=("zipf", 1.1))
+        run_and_check(gpu, w, f"wide-row stream share={share} d_a={d_a} d_u={d_u} mode={mode}", expect_variant="streamw")
+
+
+def test_wide_row_streaming_kernel_split_history_many_items_and_plain_cache(gpu):
+    # one long history among few users: cut into pieces and merged
+    w = make((5000, 70, 2300, 0), wl.BF16, wl.SOFTMAX, d_a=256, d_u=6, H=2, P=500, Nq=2)
+    run_and_check(gpu, w, "wide-row stream split softmax", expect_variant="streamw_bf16_g32_q2")
+    w = make((5000, 70, 2300), wl.F32, wl.SILU_OVER_N, d_a=256, d_u=3, H=1, P=500, Nq=1)
+    run_and_check(gpu, w, "wide-row stream split silu", expect_variant="streamw_f32_g64_q1")
+    # more short items than resident workgroups: two wavefronts per item
+    rng = np.random.default_rng(5)
+    w = make(rng.integers(0, 300, size=2500), wl.BF16, wl.SOFTMAX, d_a=256, d_u=10, H=2, P=3000, Nq=1, idx=("zipf", 1.05))
+    out = run_and_check(gpu, w, "wide-row stream, many short items", expect_variant="streamw_bf16_g32_q1")
+    ckv, session = gpu
+    with session.Session(w) as s:
+        assert ckv.ckv_variant(s.cache).endswith("_w2")
+    # an ordinary cache (d_g = 0): both sides are rows of the user arrays, fetched by position
+    w = make(RAGGED, wl.BF16, wl.SOFTMAX, d_a=256, d_u=256, H=2, P=1, Nq=2)
+    run_and_check(gpu, w, "wide-row stream, ordinary cache", expect_variant="streamw_bf16_g32_q2")
+    # large scores: the reference maximum of a row group moves often
+    w = make((900, 33), wl.F32, wl.SOFTMAX, d_a=256, d_u=2, H=1, P=400, Nq=1, scale=6.0)
+    run_and_check(gpu, w, "wide-row stream, large scores", expect_variant="streamw_f32_g64_q1")
+    # the column-block kernel still serves the shape when asked to
+    w = make(RAGGED, wl.BF16, wl.SOFTMAX, d_a=256, d_u=6, H=2, P=77, Nq=1)
+    ckv.ckv_set_option("stream_impl", "narrow")
+    try:
+        with session.Session(w) as s:
+            assert ckv.ckv_variant(s.cache).startswith("stream_bf16_v1"), ckv.ckv_variant(s.cache)
+            s.attend()
+            narrow = s.output()
+    finally:
+        ckv.ckv_set_option(None)
+    check_against_oracle(narrow, w, what="column-block kernel on a wide-row shape")
+
+
+@pytest.mark.parametrize("name", ["tgt256_u1", "tgt256_u10"])
+def test_target_attention_over_256_columns_full(gpu, name):
+    # the benchmark's target-attention workloads (one query, Table 1's head width and user widths), every output
+    run_and_check(gpu, wl.config(name), name, expect_variant="streamw_bf16_g32_q1")
+
+
 @pytest.mark.parametrize("name", ["cfg2_f32", "cfg2_bf16"])
 def test_config2_full(gpu, name):
     run_and_check(gpu, wl.config(name), name, expect_variant="stream")

@@ -77,7 +77,7 @@ def test_options_are_validated_and_steer_the_plan():
     direct-to-LDS kernel to the register-staged one (seen through ckv_plan, no device); key None restores defaults."""
     from paper_2601_19178_amd import ckv
     for key, value in (("no_such_option", "1"), ("mfma_impl", "fastest"), ("dma_sched", "lazy"), ("dma_shape", "4"),
-                       ("dma_shape", "0,1"), ("dma_slow_speed", "fast"), ("dma_slow_speed", "-1")):
+                       ("dma_shape", "0,1"), ("dma_slow_speed", "fast"), ("dma_slow_speed", "-1"), ("stream_impl", "wide")):
         with pytest.raises(ckv.CkvError) as e:
             ckv.ckv_set_option(key, value)
         assert e.value.code == ckv.CKV_ERR_UNSUPPORTED
@@ -99,6 +99,18 @@ def test_options_are_validated_and_steer_the_plan():
         ckv.ckv_set_option("mfma_impl", "staged")
         ckv.ckv_set_option(None)
         assert ckv.ckv_plan(sh, lengths)[2].startswith("mfma_dma_bf16_d64") and ckv.ckv_plan(sh, lengths)[1] == nwg_static
+        # one query over 256 columns with a user width that breaks the 8- and 16-byte alignment: wide-row streaming kernel
+        # unless the column-block one is asked for
+        st = ckv.make_shape(B=3, H=2, d_g=246, d_u=10, P=100, Nq=1, dtype=ckv.CKV_BF16, mode=0, scale=0.0625, pool_ld=256)
+        assert ckv.ckv_plan(st, lengths)[2].startswith("streamw_bf16_g32_q1")
+        ckv.ckv_set_option("stream_impl", "narrow")
+        assert ckv.ckv_plan(st, lengths)[2].startswith("stream_bf16_v1_c16")
+        ckv.ckv_set_option("stream_impl", "auto")
+        assert ckv.ckv_plan(st, lengths)[2].startswith("streamw_bf16_g32_q1")
+        # many short items: two wavefronts per item
+        many = ckv.make_shape(B=3000, H=2, d_g=246, d_u=10, P=100, Nq=1, dtype=ckv.CKV_BF16, mode=0, scale=0.0625, pool_ld=256)
+        assert ckv.ckv_plan(many, np.full(3000, 150, np.int32))[2].endswith("_w2")
+        assert not ckv.ckv_plan(many, np.full(3000, 1500, np.int32))[2].endswith("_w2")
     finally:
         ckv.ckv_set_option(None)
 

@@ -134,9 +134,15 @@ def test_plan_rejects_bad_arguments():
     # what stays in the register-staged kernel (from 8 queries on), and below that in the streaming kernel
     (128, 9, 64, BF16, "mfma_bf16_d128"), (128, 24, 64, BF16, "mfma_bf16_d128"), (64, 18, 8, BF16, "mfma_bf16_d64"),
     (96, 8, 64, BF16, "mfma_bf16_d128"), (200, 8, 64, BF16, "mfma_bf16_d256"), (256, 34, 64, BF16, "mfma_bf16_d256"),
-    (128, 9, 7, BF16, "stream"), (64, 8, 2, BF16, "stream"), (320, 8, 64, BF16, "stream"),
+    (128, 9, 7, BF16, "streamw_bf16_g16_q2"), (64, 8, 2, BF16, "stream_bf16_v8_c1_g8"), (320, 8, 64, BF16, "streamw_bf16_g64_q2"),
     # fp32 storage
-    (64, 8, 6, F32, "mfma_f32_d64"), (128, 8, 5, F32, "stream"), (256, 8, 64, F32, "mfma_f32_d256"),
+    (64, 8, 6, F32, "mfma_f32_d64"), (128, 8, 5, F32, "streamw_f32_g32_q2"), (256, 8, 64, F32, "mfma_f32_d256"),
+    # target attention (one query): rows that fit one block of 16-byte lanes stay in the column-block streaming kernel,
+    # wider rows and user slices that break the alignment go to the wide-row one (Table 1's widths: d_u of 256 columns)
+    (64, 8, 1, BF16, "stream_bf16_v8_c1_g8"), (128, 8, 1, BF16, "stream_bf16_v8_c1"), (64, 8, 1, F32, "stream_f32_v4_c1"),
+    (256, 4, 1, BF16, "streamw_bf16_g32_q1"), (256, 10, 1, BF16, "streamw_bf16_g32_q1"), (256, 1, 1, BF16, "streamw_bf16_g32_q1"),
+    (256, 3, 2, BF16, "streamw_bf16_g32_q2"), (64, 3, 1, BF16, "streamw_bf16_g8_q1"), (64, 12, 1, BF16, "streamw_bf16_g16_q1"),
+    (256, 6, 1, F32, "streamw_f32_g64_q1"), (128, 2, 1, F32, "streamw_f32_g32_q1"), (1024, 8, 1, BF16, "stream_bf16_v8_c8"),
 ])
 def test_kernel_choice_by_shape(d_a, d_u, Nq, dtype, expect):
     """Which kernel the dispatcher picks, and that its work lists cover the batch (host arithmetic only)."""
