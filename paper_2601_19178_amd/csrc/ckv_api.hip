@@ -40,6 +40,7 @@ struct Options {
     int sched = 0;             // "dma_sched": 0 default (static), 1 static, 2 dynamic
     int nw = 0, qg = 0;        // "dma_shape" = "nw,qg": wavefronts per workgroup, query groups per wavefront (0: from Nq)
     double slow_speed = -1.0;  // "dma_slow_speed": weight of a workgroup that shares its SIMDs with an older one (< 0: default)
+    int stream_waves = 0;      // "stream_waves" = "2" | "4": wavefronts per work item of the streaming kernels (0: by the number of items)
     bool stream_narrow = false;  // "stream_impl" = "narrow": the column-block streaming kernel also where the wide-row one would run
     bool debug = false;        // "debug" = "1": print the chosen split and list statistics to stderr
 };
@@ -872,15 +873,15 @@ static void plan_work(ckv_cache* c, const int32_t* lengths, const std::vector<in
         // per lane and row and two at 16; the wide-row kernel has two or three.  Four wavefronts per item give the
         // shortest chain for one item; when that needs more than one round of workgroups, two per item are faster
         // (the column-block kernel: where two per item fit in a single round; the wide-row kernel: where an item is at most
-        // two tiles per wavefront, 512 positions: 1024 users of 200 positions at 256 bf16 columns 44 -> 33 us, of 1000
+        // one tile per wavefront, 256 positions: 1024 users of 200 positions at 256 bf16 columns 44 -> 33 us, pieces of 500
         // positions 127 -> 132 us).
         const int per_simd = c->sw_g ? ckv_streamw_waves_per_simd(c->shape, c->sw_g, c->sw_nq)
                                      : ((size_t)c->grp * esize(c->shape.dtype) * (size_t)c->vec <= 128 ? 4 : 2);
         const int64_t resident = (int64_t)cus * 4 * per_simd;
         int64_t positions = 0;
         for (const ckv_item& it : p.items) positions += it.n;
-        const bool fits = c->sw_g ? positions <= (int64_t)512 * c->n_items : (int64_t)c->n_items * 2 <= resident;
-        if ((int64_t)c->n_items * 4 > resident && fits) {
+        const bool fits = c->sw_g ? positions <= (int64_t)256 * c->n_items : (int64_t)c->n_items * 2 <= resident;
+        if (g_opt.stream_waves ? g_opt.stream_waves == 2 : ((int64_t)c->n_items * 4 > resident && fits)) {
             c->nw = 2;
             const size_t len = strlen(c->variant);
             if (len + 4 < sizeof c->variant) memcpy(c->variant + len, "_w2", 4);
@@ -1355,6 +1356,10 @@ int ckv_set_option(const char* key, const char* value) {
         if (!unset && (end == value || !(v > 0.0) || v > 4.0))
             return fail(CKV_ERR_UNSUPPORTED, "ckv_set_option: dma_slow_speed takes a number in (0, 4], not \"%s\"", value);
         g_opt.slow_speed = v;
+    } else if (strcmp(key, "stream_waves") == 0) {
+        if (!unset && strcmp(value, "2") != 0 && strcmp(value, "4") != 0)
+            return fail(CKV_ERR_UNSUPPORTED, "ckv_set_option: stream_waves takes \"2\" or \"4\", not \"%s\"", value);
+        g_opt.stream_waves = unset ? 0 : atoi(value);
     } else if (strcmp(key, "stream_impl") == 0) {
         if (!unset && strcmp(value, "narrow") != 0 && strcmp(value, "auto") != 0)
             return fail(CKV_ERR_UNSUPPORTED, "ckv_set_option: stream_impl takes \"narrow\" or \"auto\", not \"%s\"", value);

@@ -23,6 +23,7 @@ namespace {
 
 constexpr int kLanes = 64;
 constexpr int NSL_MAX = 8;  // most slice columns per lane (a position's slice is shared by G / 8 lanes)
+constexpr int NSL_SMALL = 2, NSL_MID = 4;  // slice columns per lane of the instantiations for narrower slices
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 template <typename T> struct Store;
@@ -60,7 +61,7 @@ template <> struct Store<uint16_t> {  // bfloat16 bit patterns
 
 // G = lanes per row (8, 16, 32 or 64), NQ = queries served per pass over the history (1 or 2)
 template <typename T, int G, int NQ, int MODE, int NSL, int kWaves>
-__global__ __launch_bounds__(kLanes * kWaves) __attribute__((amdgpu_waves_per_eu(NQ == 1 && NSL <= 2 ? 3 : 2, 8))) void ckv_streamw_kernel(ckv_args a) {
+__global__ __launch_bounds__(kLanes * kWaves) __attribute__((amdgpu_waves_per_eu(NQ == 1 && NSL <= NSL_MID ? 3 : 2, 8))) void ckv_streamw_kernel(ckv_args a) {
     using S = Store<T>;
     constexpr int EPL = S::EPL;
     constexpr int R = kLanes / G;  // rows per load instruction = row groups
@@ -93,12 +94,10 @@ __global__ __launch_bounds__(kLanes * kWaves) __attribute__((amdgpu_waves_per_eu
     // byte offset of this lane's 16 bytes in a row (lanes past the row's last 16 bytes fetch those again: every lane loads,
     // without a branch; what they get is masked off)
     const int koff = min(lg, (wk * (int)sizeof(T) + 15) / 16 - 1) * 16, voff = min(lg, (wv * (int)sizeof(T) + 15) / 16 - 1) * 16;
-    uint32_t kmask[4], vmask[4];
+    // (only K is masked: a V column past the row's width only reaches an accumulator that is never stored)
+    uint32_t kmask[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        kmask[i] = S::mask(lg * EPL, i, wk);
-        vmask[i] = S::mask(lg * EPL, i, wv);
-    }
+    for (int i = 0; i < 4; ++i) kmask[i] = S::mask(lg * EPL, i, wk);
     const int nslk = (sk + LP - 1) / LP, nslv = (sv + LP - 1) / LP;  // slice columns per lane in use (wavefront-uniform)
 
     for (int j0 = 0; j0 < a.QB; j0 += NQ) {
@@ -133,7 +132,7 @@ __global__ __launch_bounds__(kLanes * kWaves) __attribute__((amdgpu_waves_per_eu
         // this batch's partial dot products are taken, the V rows (and V slices) as soon as this batch's are added up.  With
         // one query the kernel fits three wavefronts per SIMD without that, which measured faster than two with it
         // (256 bf16 columns, 1024 users of 1000 positions: 128 against 137 us; two queries: 296 -> 159 us with it).
-        constexpr bool kAhead = NQ == 2 && NSL <= 2;  // (with wide slices as well it would not fit the registers)
+        constexpr bool kAhead = NQ == 2 && NSL <= NSL_SMALL;  // (with wide slices as well it would not fit the registers)
         u32x4 kraw[8], vraw[8];
         T ks[NSL], vs[NSL];
 #pragma unroll
@@ -292,10 +291,7 @@ __global__ __launch_bounds__(kLanes * kWaves) __attribute__((amdgpu_waves_per_eu
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     float vf[EPL];
-                    u32x4 w = vraw[i];
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) w[c] &= vmask[c];
-                    S::unpack(w, vf);
+                    S::unpack(vraw[i], vf);
 #pragma unroll
                     for (int q = 0; q < NQ; ++q) {
                         const float wr = __shfl(wgt[q], (lane & ~7) | i, kLanes);
@@ -426,11 +422,14 @@ hipError_t launch_waves(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
     return c->nw == 2 ? launch_mode<T, G, NQ, NSL, 2>(c, a, s) : launch_mode<T, G, NQ, NSL, 4>(c, a, s);
 }
 
-// (slices of at most two columns per lane, the usual small d_u, have an instantiation of their own: 24 registers fewer)
+// (slices of at most two and of at most four columns per lane have instantiations of their own, 24 and 16 registers
+// smaller: with one query they fit three wavefronts per SIMD, the second with a dozen registers spilled)
 template <typename T, int G, int NQ>
 hipError_t launch_nsl(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
     const int slice = a.d_gk > 0 && a.d_gv > 0 ? (a.d_uk > a.d_uv ? a.d_uk : a.d_uv) : (a.d_gk > 0 ? a.d_uk : (a.d_gv > 0 ? a.d_uv : 0));
-    return slice <= 2 * (G / 8) ? launch_waves<T, G, NQ, 2>(c, a, s) : launch_waves<T, G, NQ, NSL_MAX>(c, a, s);
+    if (slice <= NSL_SMALL * (G / 8)) return launch_waves<T, G, NQ, NSL_SMALL>(c, a, s);
+    if (slice <= NSL_MID * (G / 8)) return launch_waves<T, G, NQ, NSL_MID>(c, a, s);
+    return launch_waves<T, G, NQ, NSL_MAX>(c, a, s);
 }
 
 template <typename T, int G>
@@ -482,7 +481,7 @@ int ckv_streamw_waves_per_simd(const ckv_shape& s, int G, int nq) {
         ckv_side_dims(s, side, &du, &dg);
         if (dg > 0) slice = slice > du ? slice : du;
     }
-    return nq == 1 && slice <= 2 * (G / 8) ? 3 : 2;
+    return nq == 1 && slice <= NSL_MID * (G / 8) ? 3 : 2;
 }
 
 hipError_t ckv_launch_streamw(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
