@@ -266,12 +266,14 @@ def cpu_baseline(w, budget_s=15.0):
 OFFLOADED_SHAPES = {
     # target attention as in the paper's latency table: one query per user, streaming kernel
     "target": dict(L=(200, 200), H=2, d_a=64, d_u=8, P=10000, idx="uniform", Nq=1, mode=0, sigma_pool=0.125),
+    # the same over 256-column heads with d_u = 4 (Table 1's width, CR 0.020) and longer histories: wide-row streaming kernel
+    "target256": dict(L=(1000, 1000), H=1, d_a=256, d_u=4, P=16384, idx="uniform", Nq=1, mode=0, sigma_pool=0.0625),
     # many candidates per user, HSTU-style weighting: matrix-core kernel (config 3's shape per user)
     "candidates": dict(L=(1024, 1024), H=4, d_a=64, d_u=4, P=16384, idx=("zipf", 1.1), Nq=64, mode=1, sigma_pool=0.125),
 }
 
 
-def offloaded_sweep(batches=(1, 8, 32, 64, 128, 256, 512), reps=30, kinds=("target", "candidates")):
+def offloaded_sweep(batches=(1, 8, 32, 64, 128, 256, 512), reps=30, kinds=("target", "target256", "candidates")):
     """Decode latency of one request batch per shape of OFFLOADED_SHAPES (bf16): compressed cache read in place from
     pinned host memory, compressed cache resident in HBM, and the time to load the same batch's full-width keys from
     pinned host memory (the standard-KV-cache baseline)."""

@@ -368,6 +368,8 @@ int resident_workgroups(const ckv_cache* c) {
     if (c->family == CKV_K_MFMA) return std::max(1, ckv_mfma_occupancy(d_a <= 64 ? 64 : (d_a <= 128 ? 128 : 256), c->nw, c->tp, s.mode));
     if (c->family == CKV_K_DMA) return std::max(1, ckv_dma_occupancy(d_a, c->nw, c->qg, s.mode, s.d_g == 0 ? 0 : s.d_u));
     if (c->family == CKV_K_MFMA32) return std::max(1, ckv_mfma32_occupancy(d_a <= 64 ? 64 : (d_a <= 128 ? 128 : 256), s.mode, c->QB == 64));
+    // (wide-row streaming kernel: workgroups of four wavefronts, two or three wavefronts per SIMD by its registers)
+    if (c->sw_g) return ckv_streamw_waves_per_simd(s, c->sw_g, c->sw_nq);
     return 8;
 }
 
