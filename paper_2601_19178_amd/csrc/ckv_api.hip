@@ -40,6 +40,7 @@ struct Options {
     int sched = 0;             // "dma_sched": 0 default (static), 1 static, 2 dynamic
     int nw = 0, qg = 0;        // "dma_shape" = "nw,qg": wavefronts per workgroup, query groups per wavefront (0: from Nq)
     double slow_speed = -1.0;  // "dma_slow_speed": weight of a workgroup that shares its SIMDs with an older one (< 0: default)
+    int scores_ahead = -1;     // "dma_scores_ahead" = "0" | "1": tile loop of the direct-to-LDS kernel with the scores one tile ahead (< 0: default)
     int stream_waves = 0;      // "stream_waves" = "2" | "4": wavefronts per work item of the streaming kernels (0: by the number of items)
     bool stream_narrow = false;  // "stream_impl" = "narrow": the column-block streaming kernel also where the wide-row one would run
     bool debug = false;        // "debug" = "1": print the chosen split and list statistics to stderr
@@ -651,6 +652,10 @@ void choose_variant(ckv_cache* c) {
                 c->qg = qg;
                 c->tp = 32;
                 c->nui = nui;
+                // (the loop with the scores one tile ahead exists for four wavefronts of one query group at 128 columns; measured
+                // on the long ragged configuration: 449 -> 444 us where both sides gather from pools, 518 -> 531 us on an
+                // ordinary cache, whose rows all stream from HBM and want the deeper prefetch of the other loop)
+                c->scores_ahead = g_opt.scores_ahead < 0 ? (s.share == CKV_SHARE_KV && s.d_g > 0) : g_opt.scores_ahead;
                 c->QB = 32 * nw * qg;
                 snprintf(c->variant, sizeof c->variant, "mfma_dma_bf16_d%d_w%d_g%d_%s", d_a, nw, qg,
                          s.mode == CKV_SOFTMAX ? "softmax" : "silu");
@@ -1252,6 +1257,7 @@ static int attend_common(const char* who, const ckv_cache* c, const void* pool_k
     a.Nq = s.Nq;
     a.QB = c->QB;
     a.scale = s.scale;
+    a.scores_ahead = c->scores_ahead;
     ckv_cache* mc = const_cast<ckv_cache*>(c);
     hipError_t e;
     // timing: three events per launch (start, main kernel done, merge done)
@@ -1358,6 +1364,10 @@ int ckv_set_option(const char* key, const char* value) {
         if (!unset && (end == value || !(v > 0.0) || v > 4.0))
             return fail(CKV_ERR_UNSUPPORTED, "ckv_set_option: dma_slow_speed takes a number in (0, 4], not \"%s\"", value);
         g_opt.slow_speed = v;
+    } else if (strcmp(key, "dma_scores_ahead") == 0) {
+        if (!unset && strcmp(value, "0") != 0 && strcmp(value, "1") != 0)
+            return fail(CKV_ERR_UNSUPPORTED, "ckv_set_option: dma_scores_ahead takes \"0\" or \"1\", not \"%s\"", value);
+        g_opt.scores_ahead = unset ? -1 : atoi(value);
     } else if (strcmp(key, "stream_waves") == 0) {
         if (!unset && strcmp(value, "2") != 0 && strcmp(value, "4") != 0)
             return fail(CKV_ERR_UNSUPPORTED, "ckv_set_option: stream_waves takes \"2\" or \"4\", not \"%s\"", value);

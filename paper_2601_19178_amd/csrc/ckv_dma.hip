@@ -518,7 +518,154 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
             lds_barrier();
         }
         };
+        // The same loop with the scores one tile ahead (four wavefronts of one query group at 128 columns, the shape of the
+        // long ragged configuration): iteration t takes the weights and the output of tile t from scores that the previous
+        // iteration left in registers, and issues the score MFMAs of tile t + 1 between the exponentials of tile t, so that
+        // the matrix pipe works under the vector arithmetic of the same wavefront instead of being waited for.  Tile t + 1
+        // therefore has to be published one iteration earlier than above: the wait at the end of iteration t lets only that
+        // iteration's loads stay outstanding (two tiles of gathers in flight instead of three), and the barrier publishes
+        // tile t + 2.  The steady-state body (whole tiles) carries no test of the tile's length; the first score block and
+        // the last, possibly ragged, tile are peeled.
+        auto tile_loop_ahead = [&](auto nui_c, auto both_c) {
+            constexpr int NUI = decltype(nui_c)::value;
+            constexpr int NS = G::NS;
+            constexpr int LPI = 2 * G::NI + 1 + NUI;  // loads per iteration and wavefront
+            static_assert(QG == 1 && !kWide && NS == 4, "built for one query group on the four-stage ring");
+            int rk[G::NI], rv[G::NI];
+            gather_rows(both_c, 0, rk, rv);
+            auto front = [&](int t) {
+                issue_idx(t + NS + 2);
+#pragma unroll
+                for (int s = 0; s < 2 * G::NI + NUI; ++s) tile_dma(t + NS - 1, s, rk, rv);
+            };
+            auto back = [&](int t) {
+                // (the scheduler had moved this wait up to the first score MFMA, ahead of the arithmetic that is to hide the latency)
+                __builtin_amdgcn_sched_barrier(0);
+                wait_vm<(NS - 3) * LPI>();  // own gathers of tile t + 2 have landed
+                if (NUI > 0 && t + 2 >= 0 && t + 2 < ntiles) concat(nui_c, t + 2);
+                gather_rows(both_c, t + NS, rk, rv);
+                lds_barrier();  // tile t + 2 is published, the stage of tile t is retired
+            };
+            auto read_k = [&](int tile, bf16x8 (&ka)[NKK]) {
+                const uint32_t st = lds0 + (tile & (NS - 1)) * G::STAGE;
+#pragma unroll
+                for (int kk = 0; kk < NKK; ++kk) ka[kk] = *(const lds_bf16x8*)(uintptr_t)(st + krow + (((2 * kk + hh) ^ kx) << 4));
+            };
+            auto read_v = [&](int tile, bf16x8 (&va)[2][NDT]) {
+                const uint32_t st = lds0 + (tile & (NS - 1)) * G::STAGE;
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                    for (int dt = 0; dt < NDT; ++dt) {
+                        const uint32_t ad = st + vrow + (16 * ks) * G::ROWB + (((4 * dt + vc) ^ vx) << 4);
+                        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(uintptr_t)ad);
+                        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(uintptr_t)(ad + 8 * G::ROWB));
+                        va[ks][dt] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    }
+            };
+            // weights of one tile from its scores s; kNext: the score MFMAs of the next tile (operands ka) go between the
+            // exponentials and leave their result in s; then O^T += V^T P^T
+            auto weights_and_output = [&](auto next_c, f32x16& s, const bf16x8 (&ka)[NKK], const bf16x8 (&va)[2][NDT], int nt) {
+                constexpr bool kNext = decltype(next_c)::value;
+                bf16x8 pb[2];
+                f32x16 sn;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sn[r] = 0.f;
+                if (MODE == CKV_SOFTMAX) {
+                    if (!kNext && nt < TP) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) s[r] = mask_tail(s[r], 8 * (r >> 2) + 4 * hh + (r & 3) >= nt, -INFINITY);
+                    }
+                    float tmax = s[0];
+#pragma unroll
+                    for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, s[r]);
+                    tmax = fmaxf(tmax, other_half(tmax)) * sc;
+                    if (__any(tmax > m_ref[0] + kLazy)) {
+                        const float m_new = fmaxf(m_ref[0], tmax);
+                        const float alpha = __builtin_amdgcn_exp2f(m_ref[0] - m_new);
+                        lsum[0] *= alpha;
+#pragma unroll
+                        for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) oacc[0][dt][r] *= alpha;
+                        m_ref[0] = m_new;
+                    }
+                    if (kNext) {
+#pragma unroll
+                        for (int kk = 0; kk < NKK; ++kk) sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk], qreg[0][kk], sn, 0, 0, 0);
+                    }
+                    float psum = 0.f;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float p = __builtin_amdgcn_exp2f(fmaf(s[r], sc, -m_ref[0]));
+                        psum += p;
+                        pb[r >> 3][r & 7] = (__bf16)p;
+                    }
+                    lsum[0] += psum;
+                } else {
+                    if (!kNext && nt < TP) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) s[r] = mask_tail(s[r], 8 * (r >> 2) + 4 * hh + (r & 3) >= nt, 0.f);
+                    }
+                    if (kNext) {
+#pragma unroll
+                        for (int kk = 0; kk < NKK; ++kk) sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk], qreg[0][kk], sn, 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float e = __builtin_amdgcn_exp2f(s[r] * nsc);
+                        pb[r >> 3][r & 7] = (__bf16)((s[r] * sc) * __builtin_amdgcn_rcpf(1.f + e));
+                    }
+                }
+                if (kNext) {
+                    // one score MFMA of the next tile, then a share of this tile's weight arithmetic, eight times
+#pragma unroll
+                    for (int kk = 0; kk < NKK; ++kk) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+                    }
+                }
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                    for (int dt = 0; dt < NDT; ++dt)
+                        oacc[0][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ks][dt], pb[ks], oacc[0][dt], 0, 0, 0);
+                if (kNext) s = sn;
+            };
+            f32x16 s_cur;
+            bf16x8 ka[NKK], va[2][NDT];
+            front(-(NS - 1));
+            back(-(NS - 1));
+            front(-(NS - 2));
+            back(-(NS - 2));  // publishes tile 0
+            front(-1);
+            read_k(0, ka);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s_cur[r] = 0.f;
+#pragma unroll
+            for (int kk = 0; kk < NKK; ++kk) s_cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk], qreg[0][kk], s_cur, 0, 0, 0);
+            back(-1);
+            for (int t = 0; t < ntiles - 1; ++t) {
+                front(t);
+                read_k(t + 1, ka);
+                read_v(t, va);
+                weights_and_output(std::true_type{}, s_cur, ka, va, TP);
+                back(t);
+            }
+            front(ntiles - 1);
+            read_v(ntiles - 1, va);
+            weights_and_output(std::false_type{}, s_cur, ka, va, n - (ntiles - 1) * TP);
+            back(ntiles - 1);
+        };
+        constexpr bool kScoresAhead = DA == 128 && NW == 4 && QG == 1 && UK == 0;
         auto with_nui = [&](auto nui_c) {
+            if constexpr (kScoresAhead) {
+                if (a.scores_ahead) {
+                    if (ksh && vsh) tile_loop_ahead(nui_c, std::true_type{});
+                    else tile_loop_ahead(nui_c, std::false_type{});
+                    return;
+                }
+            }
             if (ksh && vsh) tile_loop(nui_c, std::true_type{});
             else tile_loop(nui_c, std::false_type{});
         };

@@ -45,6 +45,7 @@ struct ckv_args {
     int32_t d_uk, d_gk, d_uv, d_gv;  // per side: d_u, d_g of the shape for a shared side, (d_a, 0) otherwise
     int32_t QB;            // queries per block (rows of a workspace slot)
     float scale;
+    int32_t scores_ahead;  // direct-to-LDS kernel, four wavefronts at 128 columns: tile loop with the scores one tile ahead
 };
 
 // Columns of one side (0 = K, 1 = V) that come from the user array and from the pool.
@@ -98,6 +99,7 @@ struct ckv_cache {
     int nw, tp;          // mfma kernels: waves per workgroup, positions per tile
     int nui;             // dma kernel: user-slice load instructions per wavefront and tile
     int qg;              // dma kernel: groups of 32 queries per wavefront
+    int scores_ahead;    // dma kernel: tile loop with the scores one tile ahead (four wavefronts, one query group, 128 columns)
     int QB;              // queries per block
     int n_items, n_merge, n_parts;
     ckv_item* d_items;

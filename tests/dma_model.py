@@ -131,8 +131,15 @@ class Wave:
         return not any(t.startswith(tag_prefix) for _, _, t in self.pending)
 
 
-def run_item(DA, NW, QG, shape, item, buffers, check_rows=True):
+def scores_ahead_supported(DA, NW, QG, UK):
+    """The instantiations whose tile loop exists with the scores one tile ahead."""
+    return DA == 128 and NW == 4 and QG == 1 and UK == 0
+
+
+def run_item(DA, NW, QG, shape, item, buffers, check_rows=True, scores_ahead=False):
     """One work item through the kernel's access pattern.
+    scores_ahead: the tile loop that takes the scores of tile t + 1 in the iteration that finishes tile t (tiles are
+    published one iteration earlier, two tiles of gathers in flight instead of three).
 
     shape: dict(d_g, d_u, share_k, share_v (does the side gather from a pool), pool_ld, P, H, T, Nq)
     item:  dict(b, h, q0, n, t0, part (slot or -1), QB)
@@ -362,27 +369,35 @@ def run_item(DA, NW, QG, shape, item, buffers, check_rows=True):
                 rows.append(np.ascontiguousarray(r, dtype=np.uint16))
             return rows
 
-        def compute(tile):
-            """Operand reads of every wavefront on a published tile; contents of the stage against the definition."""
+        published = [-1]   # the last tile a barrier has published
+
+        def compute(tile, sides=(0, 1)):
+            """Operand reads of every wavefront on a published tile (K rows, V rows or both); contents of the stage against
+            the definition."""
             st = (tile & (G.NS - 1)) * G.STAGE
             need(stage_tile[tile & (G.NS - 1)] == tile, f"tile {tile} is computed from a stage that holds tile {stage_tile[tile & (G.NS - 1)]}")
+            need(tile <= published[0], f"tile {tile} is read before a barrier has published it")
             kx = fk(DA, qn)
             g16, s16 = lane >> 4, lane & 15
             vrow = G.KV + (4 * hh + (s16 >> 2)) * G.ROWB + (s16 & 1) * 8
             vc, vx = 2 * (g16 & 1) + ((s16 & 3) >> 1), fv(DA, s16 >> 2)
-            for kk in range(DA // 16):
-                lds.read(st + qn * G.ROWB + (((2 * kk + hh) ^ kx) << 4), 16, "K operand")
-            for ks in range(2):
-                for dt in range(DA // 32):
-                    ad = st + vrow + 16 * ks * G.ROWB + (((4 * dt + vc) ^ vx) << 4)
-                    need(ad.min() >= st + G.KV and (ad + 8 * G.ROWB + 8).max() <= st + 2 * G.KV, "V operand outside the V rows of its stage")
-                    lds.read(ad, 8, "V operand")
-                    lds.read(ad + 8 * G.ROWB, 8, "V operand")
+            if 0 in sides:
+                for kk in range(DA // 16):
+                    lds.read(st + qn * G.ROWB + (((2 * kk + hh) ^ kx) << 4), 16, "K operand")
+            if 1 in sides:
+                for ks in range(2):
+                    for dt in range(DA // 32):
+                        ad = st + vrow + 16 * ks * G.ROWB + (((4 * dt + vc) ^ vx) << 4)
+                        need(ad.min() >= st + G.KV and (ad + 8 * G.ROWB + 8).max() <= st + 2 * G.KV, "V operand outside the V rows of its stage")
+                        lds.read(ad, 8, "V operand")
+                        lds.read(ad + 8 * G.ROWB, 8, "V operand")
             if check_rows:
                 ek, ev = expected_rows(tile)
                 nt = min(n - tile * TP, TP)       # rows past the end of the history hold a clamped copy: not checked
                 pp, cc = np.meshgrid(np.arange(nt), np.arange(chq), indexing="ij")
                 for side, exp, f in ((0, ek, fk), (1, ev, fv)):
+                    if side not in sides:
+                        continue
                     off = st + side * G.KV + pp * G.ROWB + ((cc ^ f(DA, pp)) << 4)
                     got = lds.data[off[..., None] + np.arange(16)].reshape(nt, chq, 16).view(np.uint16)
                     want = exp[:nt].reshape(nt, chq, 8)
@@ -401,10 +416,38 @@ def run_item(DA, NW, QG, shape, item, buffers, check_rows=True):
         # ---- the tile loop, every wavefront in the kernel's order; a barrier is a point all wavefronts reach
         kAhead = DA <= 128
         NS = G.NS
+        need(not scores_ahead or scores_ahead_supported(DA, NW, QG, UK), "this instantiation has no tile loop with the scores ahead")
         for w in range(NW):
             waves[w].wait(0)                       # wait_vm<0>: the first indices
         rows = [gather_rows(w, 0) if kAhead else None for w in range(NW)]
-        for t in range(-(NS - 1), ntiles):
+        for t in (range(-(NS - 1), ntiles) if scores_ahead else ()):
+            # iteration t: this iteration's loads; K operands of tile t + 1 and V operands of tile t; the wait that lets only
+            # this iteration's loads stay outstanding; concat and publication of tile t + 2
+            for w in range(NW):
+                step[0] += 1
+                slot = (t + NS + 2) & (G.NIS - 1)
+                former = t + NS + 2 - G.NIS
+                need(former < 0 or former <= looked_up[w], f"indices of tile {former} are overwritten before their rows were looked up")
+                need(idx_last_read[w][slot] < step[0], "an index slot is overwritten before its last reader")
+                issue_idx(w, t + NS + 2)
+                tile_dma(w, t + NS - 1, *rows[w])
+            stage_tile[(t + NS - 1) & (NS - 1)] = t + NS - 1
+            if -1 <= t < ntiles - 1:
+                compute(t + 1, sides=(0,))
+            if t >= 0:
+                compute(t, sides=(1,))
+            for w in range(NW):
+                waves[w].wait((NS - 3) * (2 * G.NI + 1 + nui))
+                if nui > 0 and 0 <= t + 2 < ntiles:
+                    concat(w, t + 2)
+                rows[w] = gather_rows(w, t + NS)
+            if t + 2 < ntiles:
+                for w in range(NW):
+                    need(waves[w].landed(f"k:{t + 2}") and waves[w].landed(f"v:{t + 2}"),
+                         f"tile {t + 2} is published while gathers of wavefront {w} are in flight")
+            published[0] = t + 2
+            stage_free_at[t & (NS - 1)] = step[0] + 1 if t >= 0 else stage_free_at[t & (NS - 1)]
+        for t in (() if scores_ahead else range(-(NS - 1), ntiles)):
             for w in range(NW):
                 step[0] += 1
                 slot = (t + NS + 2) & (G.NIS - 1)
@@ -430,6 +473,7 @@ def run_item(DA, NW, QG, shape, item, buffers, check_rows=True):
                 for w in range(NW):
                     need(waves[w].landed(f"k:{t + 1}") and waves[w].landed(f"v:{t + 1}"),
                          f"tile {t + 1} is published while gathers of wavefront {w} are in flight")
+            published[0] = t + 1
             stage_free_at[t & (NS - 1)] = step[0] + 1 if t >= 0 else stage_free_at[t & (NS - 1)]
         for w in range(NW):
             waves[w].wait(0)

@@ -36,8 +36,9 @@ def buffers_for(rng, DA, d_u, share, H, P, pool_ld, T, B, Nq, parts=0, QB=32):
     return shape, buf
 
 
-def run_case(DA, NW, QG, d_u, share=0, lengths=(33, 1, 100), pool_ld=None, Nq=None, seed=0, split=False, d_a=None):
-    """d_a: the head's own width when it is narrower than the kernel's rows (DA)."""
+def run_case(DA, NW, QG, d_u, share=0, lengths=(33, 1, 100), pool_ld=None, Nq=None, seed=0, split=False, d_a=None, scores_ahead=False):
+    """d_a: the head's own width when it is narrower than the kernel's rows (DA).  scores_ahead: the tile loop that takes the
+    scores of a tile one iteration early."""
     rng = np.random.default_rng(seed)
     d_a = DA if d_a is None else d_a
     d_g = d_a - d_u
@@ -57,7 +58,7 @@ def run_case(DA, NW, QG, d_u, share=0, lengths=(33, 1, 100), pool_ld=None, Nq=No
                 pieces = [(0, n, -1)]
             for lo, nn, part in pieces:
                 item = dict(b=b, h=h, q0=0, n=nn, t0=t0 + lo, part=part, QB=QB)
-                stats = dm.run_item(DA, NW, QG, shape, item, buf)
+                stats = dm.run_item(DA, NW, QG, shape, item, buf, scores_ahead=scores_ahead)
         t0 += n
     if not split:       # every byte of every output row was written (the model marks what it writes), nothing beyond
         assert (buf["out"].view(np.uint8) == 1).all()
@@ -109,6 +110,24 @@ def test_unpadded_and_overpadded_pool_rows(DA, NW, QG):
     run_case(DA, NW, QG, 4, pool_ld=DA, Nq=3, seed=12)           # three queries: most staging rows are zeros
 
 
+@pytest.mark.parametrize("d_u", [0, 2, 4, 8])
+def test_tile_loop_with_the_scores_one_tile_ahead(d_u):
+    """The loop of the four-wavefront 128-column instance that publishes a tile one iteration earlier (K operands of tile
+    t + 1 are read in the iteration that finishes tile t): histories of one tile, of a few, ragged ends, split pieces,
+    one side shared, ordinary cache, unpadded pool rows."""
+    st = run_case(128, 4, 1, d_u, lengths=(33, 1, 100, 32, 64, 65, 0, 257), seed=20, scores_ahead=True)
+    assert st["UK"] == 0 and st["peak_outstanding"] <= 2 * (2 * 2 + 1 + 1)     # two iterations of loads at most
+    run_case(128, 4, 1, d_u, lengths=(31, 32, 257), seed=21, split=True, scores_ahead=True)
+    if d_u == 4:
+        run_case(128, 4, 1, 4, share=1, lengths=(65, 3), seed=22, scores_ahead=True)
+        run_case(128, 4, 1, 4, share=2, lengths=(65, 3), seed=23, scores_ahead=True)
+        run_case(128, 4, 1, 128, lengths=(65, 3), seed=24, scores_ahead=True)
+        run_case(128, 4, 1, 8, pool_ld=120, seed=25, scores_ahead=True)
+        run_case(128, 4, 1, 4, pool_ld=128, Nq=3, seed=26, scores_ahead=True)
+    with pytest.raises(dm.ModelError, match="no tile loop with the scores ahead"):
+        run_case(128, 2, 1, d_u, scores_ahead=True)
+
+
 def test_outstanding_loads_of_every_geometry_fit_the_wait_counter():
     """(NS - 1) iterations of loads are in flight at most: 2 NI gathers, one index load and the slice loads each."""
     for DA, NW, QG in SHAPES:
@@ -152,6 +171,14 @@ def test_model_notices_a_wait_that_is_too_lax(monkeypatch):
     monkeypatch.setattr(dm.Wave, "wait", lambda self, n: real(self, n + 3 if n > 0 else n))
     with pytest.raises(dm.ModelError, match="landed|in flight"):
         run_case(128, 4, 1, 8)
+
+
+def test_model_notices_a_lax_wait_in_the_loop_with_the_scores_ahead(monkeypatch):
+    # the wait of the other loop (two iterations of loads may stay outstanding) would publish a tile whose gathers are in flight
+    real = dm.Wave.wait
+    monkeypatch.setattr(dm.Wave, "wait", lambda self, n: real(self, 2 * n))
+    with pytest.raises(dm.ModelError, match="landed|in flight"):
+        run_case(128, 4, 1, 8, lengths=(200,), scores_ahead=True)
 
 
 def test_model_notices_too_many_loads_in_flight():

@@ -220,6 +220,29 @@ def test_mfma_split_history(gpu, impl, mode):
     run_and_check(gpu, w, f"mfma split mode={mode} impl={impl}", expect_variant="mfma", impl=impl)
 
 
+@pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
+def test_tile_loop_with_the_scores_one_tile_ahead(gpu, mode):
+    """Four wavefronts at 128 columns: the loop that takes the scores of tile t + 1 in the iteration that finishes tile t and
+    the loop that does not must agree bit for bit (the same arithmetic in the same order) and with the oracle: ragged
+    lengths (one tile, tile boundaries, empty), a split history, one side shared, an ordinary cache."""
+    ckv, session = gpu
+    cases = [dict(lengths=MFMA_LENGTHS + (95, 97, 160), d_u=8, Nq=128), dict(lengths=MFMA_LENGTHS, d_u=0, Nq=100),
+             dict(lengths=(5000, 70, 2300), d_u=8, Nq=128), dict(lengths=MFMA_LENGTHS, d_u=4, Nq=65, share=wl.SHARE_K),
+             dict(lengths=MFMA_LENGTHS, d_u=4, Nq=128, share=wl.SHARE_V), dict(lengths=(65, 1, 640), d_u=128, Nq=128)]
+    for c in cases:
+        w = make(c["lengths"], wl.BF16, mode, d_a=128, d_u=c["d_u"], H=2, P=700 if c["d_u"] < 128 else 1, Nq=c["Nq"],
+                 share=c.get("share", wl.SHARE_KV))
+        outs = []
+        for ahead in ("0", "1"):
+            ckv.ckv_set_option("dma_scores_ahead", ahead)
+            try:
+                outs.append(_run_and_check(ckv, session, w, f"scores ahead = {ahead}, d_u={c['d_u']} Nq={c['Nq']} mode={mode}", None,
+                                           "mfma_dma_bf16_d128_w4_g1"))
+            finally:
+                ckv.ckv_set_option(None)
+        np.testing.assert_array_equal(outs[0], outs[1])
+
+
 def test_mfma_unpadded_pool_rows(gpu):
     # pool_ld == d_g (a multiple of 8): the chunk that would be padding does not exist in memory
     w = make(MFMA_LENGTHS, wl.BF16, wl.SOFTMAX, d_a=64, d_u=8, H=2, P=333, Nq=16, pool_ld=56)
