@@ -64,13 +64,16 @@ enum {
  *   B, H, Nq >= 1; d_g, d_u >= 0 with d_a >= 1; P >= 1 when d_g > 0 (CKV_ERR_SHAPE);
  *   lengths >= 0 and T * H <= 2^40 (CKV_ERR_LENGTH); pools may exceed 4 GiB (row offsets are 64-bit);
  *   d_a <= 256 for any widths and stride; d_a <= 512 when d_u, d_g and pool_ld are multiples of 4,
- *   <= 1024 for bf16 when they are multiples of 8 (CKV_ERR_UNSUPPORTED beyond);
+ *   <= 1024 for bf16 when they are multiples of 8; also rows of up to 1024 bytes (512 bf16 or 256 fp32 columns) with any
+ *   d_u <= 64 when the row strides (pool_ld, and d_a for a side that is not shared) are whole multiples of 16 bytes
+ *   (CKV_ERR_UNSUPPORTED beyond);
  *   every device pointer 16-byte aligned (CKV_ERR_UNSUPPORTED); device gfx950 (CKV_ERR_UNSUPPORTED).
  * The matrix-core kernels take Nq >= 8 (>= 3 for the fastest bf16 shapes, >= 6 in fp32; scale > 0 for
  * softmax): bf16 with d_a <= 256 and pool_ld a multiple
  * of 8 (fastest at d_a of exactly 64, 128 or 256 with d_u odd up to 7 or even up to 16, up to 32 at 256 columns), fp32 with d_a <= 256 and pool_ld a
- * multiple of 4 (on the fp32 matrix instruction, a sixteenth of the bf16 rate).  Every other shape runs the streaming kernel,
- * which is made for few queries.  ckv_variant names the choice.
+ * multiple of 4 (on the fp32 matrix instruction, a sixteenth of the bf16 rate).  Every other shape runs one of the two streaming
+ * kernels, which are made for one or two queries (target attention): column blocks, or, for wide rows and user widths that
+ * break the alignment of the final row, pool rows in 16-byte lanes and user slices apart.  ckv_variant names the choice.
  */
 typedef struct ckv_shape {
     int32_t B, H, d_g, d_u, P, Nq;
