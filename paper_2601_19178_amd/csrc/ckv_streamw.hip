@@ -1,6 +1,6 @@
 // Streaming gather-concat-attend kernel for wide rows and for user slices of any width: target attention
-// (one or two queries per user, section 2.1) over heads of up to 256 columns, the width behind the
-// compression ratios of Table 1 (d_u = 1, 2, 3, 4, 6, 10 of d = 256).
+// (one or two queries per user, section 2.1) over rows of up to 1024 bytes, such as the 256 columns behind
+// the compression ratios of Table 1 (d_u = 1, 2, 3, 4, 6, 10 of d = 256) in bf16 or fp32.
 //
 // The final row of a position is [user slice | pool row] (eq. "eq: Kc", "eq: K").  The two parts sit in
 // different arrays with different alignment: a pool row starts on a 16-byte boundary whatever d_u is, a
@@ -15,8 +15,8 @@
 // score of batch position (i, g) (instruction i, row group g) ends up in the lanes g * G + o * 8 + i for
 // every octet o of the group; the G / 8 lanes of the octets share the slice of that position column-wise and
 // add their share before the last steps of the reduction.  Softmax is online per batch with one reference
-// maximum per row group (a reduction over eight lanes); the groups, and the four wavefronts of a workgroup,
-// which take the 64-position tiles of a work item in turn, are merged exactly at the end.
+// maximum per row group (a reduction over eight lanes); the groups, and the four (or two) wavefronts of a
+// workgroup, which take the 64-position tiles of a work item in turn, are merged exactly at the end.
 #include "ckv_internal.h"
 
 namespace {
@@ -59,7 +59,8 @@ template <> struct Store<uint16_t> {  // bfloat16 bit patterns
     }
 };
 
-// G = lanes per row (8, 16, 32 or 64), NQ = queries served per pass over the history (1 or 2)
+// G = lanes per row (8, 16, 32 or 64), NQ = queries served per pass over the history (1 or 2), NSL = slice columns
+// per lane (2, 4 or 8), kWaves = wavefronts per work item (4, or 2 where short items outnumber the resident wavefronts)
 template <typename T, int G, int NQ, int MODE, int NSL, int kWaves>
 __global__ __launch_bounds__(kLanes * kWaves) __attribute__((amdgpu_waves_per_eu(NQ == 1 && NSL <= NSL_MID ? 3 : 2, 8))) void ckv_streamw_kernel(ckv_args a) {
     using S = Store<T>;
@@ -126,7 +127,7 @@ __global__ __launch_bounds__(kLanes * kWaves) __attribute__((amdgpu_waves_per_eu
             for (int k = 0; k < NSL; ++k) accu[q][k] = 0.f;
         }
 
-        // ---- the wavefront's batches: tiles wave, wave + 4, ... of 64 positions, batches of NB positions inside a tile;
+        // ---- the wavefront's batches: tiles wave, wave + kWaves, ... of 64 positions, batches of NB positions inside a tile;
         // the indices run one tile ahead.  With two queries per pass (two wavefronts per SIMD by the registers) the loads
         // run one batch ahead into the same registers: the K rows (and K slices) of the next batch are requested as soon as
         // this batch's partial dot products are taken, the V rows (and V slices) as soon as this batch's are added up.  With
