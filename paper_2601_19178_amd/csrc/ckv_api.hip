@@ -694,7 +694,11 @@ void choose_variant(ckv_cache* c) {
     // Rows that the kernel above would fetch in several column blocks, or in lanes of less than 16 bytes because the
     // user slice breaks the alignment (d_u = 1, 2, 3, 6, 10 of Table 1's 256 columns), go to the wide-row kernel, which
     // fetches pool row and slice separately.
-    c->sw_g = (c->ncb == 1 && (size_t)c->vec * esize(s.dtype) == 16) || g_opt.stream_narrow ? 0 : ckv_streamw_lanes(s);
+    // (A row that the kernel above holds in one block of vector lanes stays there, also with 8-byte lanes: 64 bf16 columns with
+    // d_u = 4 or 12 measured 22 us there against 24 and 47 us; so do fp32 rows of several blocks with one query: 238 against 265 us.)
+    const bool one_block = c->ncb == 1 && c->vec > 1;
+    const bool f32_blocks = s.dtype == CKV_F32 && c->vec == 4 && s.Nq == 1;
+    c->sw_g = one_block || f32_blocks || g_opt.stream_narrow ? 0 : ckv_streamw_lanes(s);
     if (c->sw_g) {
         c->sw_nq = s.Nq >= 2 ? 2 : 1;
         snprintf(c->variant, sizeof c->variant, "streamw_%s_g%d_q%d_%s", s.dtype == CKV_F32 ? "f32" : "bf16", c->sw_g, c->sw_nq,

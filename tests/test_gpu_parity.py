@@ -132,7 +132,7 @@ def test_stream_split_history(gpu):
     (wl.F32, 256, 10, 256, 5, "streamw_f32_g64_q2"),             # five queries: two passes of two and one of one
     # fewer lanes per row; slices of up to eight columns per lane of the row's octets
     (wl.BF16, 64, 3, 64, 1, "streamw_bf16_g8_q1"), (wl.BF16, 64, 8, 56, 2, "stream_bf16_v8_c1_g8"),
-    (wl.BF16, 64, 6, 64, 2, "streamw_bf16_g8_q2"), (wl.BF16, 64, 12, 56, 1, "streamw_bf16_g16_q1"),
+    (wl.BF16, 64, 6, 64, 2, "streamw_bf16_g8_q2"), (wl.BF16, 64, 12, 56, 1, "stream_bf16_v4_c1"), (wl.BF16, 64, 10, 56, 1, "streamw_bf16_g16_q1"),
     (wl.BF16, 128, 5, 128, 1, "streamw_bf16_g16_q1"), (wl.BF16, 128, 14, 120, 2, "streamw_bf16_g16_q2"),
     (wl.BF16, 72, 9, 64, 7, "streamw_bf16_g16_q2"),               # a width no matrix-core kernel takes below eight queries
     (wl.BF16, 200, 30, 176, 1, "streamw_bf16_g32_q1"), (wl.BF16, 512, 64, 448, 1, "streamw_bf16_g64_q1"),

@@ -141,7 +141,8 @@ def test_plan_rejects_bad_arguments():
     # wider rows and user slices that break the alignment go to the wide-row one (Table 1's widths: d_u of 256 columns)
     (64, 8, 1, BF16, "stream_bf16_v8_c1_g8"), (128, 8, 1, BF16, "stream_bf16_v8_c1"), (64, 8, 1, F32, "stream_f32_v4_c1"),
     (256, 4, 1, BF16, "streamw_bf16_g32_q1"), (256, 10, 1, BF16, "streamw_bf16_g32_q1"), (256, 1, 1, BF16, "streamw_bf16_g32_q1"),
-    (256, 3, 2, BF16, "streamw_bf16_g32_q2"), (64, 3, 1, BF16, "streamw_bf16_g8_q1"), (64, 12, 1, BF16, "streamw_bf16_g16_q1"),
+    (256, 3, 2, BF16, "streamw_bf16_g32_q2"), (64, 3, 1, BF16, "streamw_bf16_g8_q1"), (64, 12, 1, BF16, "stream_bf16_v4_c1"),
+    (64, 10, 1, BF16, "streamw_bf16_g16_q1"), (256, 8, 1, F32, "stream_f32_v4_c4"), (256, 8, 2, F32, "streamw_f32_g64_q2"),
     (256, 6, 1, F32, "streamw_f32_g64_q1"), (128, 2, 1, F32, "streamw_f32_g32_q1"), (1024, 8, 1, BF16, "stream_bf16_v8_c8"),
 ])
 def test_kernel_choice_by_shape(d_a, d_u, Nq, dtype, expect):
