@@ -515,7 +515,7 @@ def test_repeated_calls_are_deterministic(gpu):
     np.testing.assert_array_equal(a, b)
 
 
-@pytest.mark.parametrize("kind", ["stream", "dma_split"])
+@pytest.mark.parametrize("kind", ["stream", "streamw", "dma_split"])
 def test_attend_replayed_from_a_captured_graph(gpu, kind):
     """A serving loop records ckv_attend once and replays it; every replay (new queries in the captured
     buffer, eager work and synchronisations in between) must equal the eager call bit for bit."""
@@ -523,6 +523,8 @@ def test_attend_replayed_from_a_captured_graph(gpu, kind):
     ckv, session = gpu
     if kind == "stream":
         w = make((300, 0, 41, 1200), wl.F32, wl.SOFTMAX, d_a=32, d_u=4, H=2, P=700, Nq=1)
+    elif kind == "streamw":  # wide-row streaming kernel, two queries, a split history and its merge kernel
+        w = make((3000, 0, 41, 1200), wl.BF16, wl.SOFTMAX, d_a=256, d_u=3, H=2, P=700, Nq=2)
     else:  # one long history among short ones: split into pieces, merged by a second kernel
         w = make((9000, 64, 3, 0, 500), wl.BF16, wl.SILU_OVER_N, d_a=64, d_u=4, H=2, P=3000, Nq=64)
     rng = np.random.default_rng(5)
@@ -530,6 +532,8 @@ def test_attend_replayed_from_a_captured_graph(gpu, kind):
         say(f"[case] graph replay {kind}: variant {ckv.ckv_variant(s.cache)}")
         if kind == "dma_split":
             assert ckv.ckv_variant(s.cache).startswith("mfma_dma")
+        if kind == "streamw":
+            assert ckv.ckv_variant(s.cache).startswith("streamw")
         s.attend()
         torch.cuda.synchronize()
         side = torch.cuda.Stream()

@@ -41,7 +41,7 @@ def split_workspace_bytes(ckv, s, w):
     return least * qb * (w["d_g"] + w["d_u"] + 2) * 4
 
 
-@pytest.mark.parametrize("kind", ["dma", "staged", "fp32", "stream"])
+@pytest.mark.parametrize("kind", ["dma", "staged", "fp32", "stream", "streamw"])
 def test_static_scratch_entry_point_matches_ckv_attend(kind):
     import torch
     assert torch.cuda.is_available(), "these tests need the MI355X"
@@ -55,6 +55,9 @@ def test_static_scratch_entry_point_matches_ckv_attend(kind):
     elif kind == "fp32":    # fp32 matrix-core kernel
         first = make((5000, 70, 2300), wl.F32, wl.SOFTMAX, d_a=128, d_u=8, H=2, P=5000, Nq=64)
         second = make((1500,), wl.F32, wl.SILU_OVER_N, d_a=64, d_u=4, H=1, P=300, Nq=8)
+    elif kind == "streamw":  # wide-row streaming kernel (user widths that break the alignment of the final row)
+        first = make((5000, 70, 2300), wl.BF16, wl.SOFTMAX, d_a=256, d_u=10, H=2, P=500, Nq=2)
+        second = make((3000, 5), wl.F32, wl.SILU_OVER_N, d_a=128, d_u=3, H=1, P=500, Nq=1)
     else:                   # streaming kernel
         first = make((5000, 70, 2300), wl.F32, wl.SOFTMAX, d_a=64, d_u=8, H=2, P=500, Nq=2)
         second = make((3000, 5), wl.BF16, wl.SILU_OVER_N, d_a=64, d_u=8, H=1, P=500, Nq=1)
