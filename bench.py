@@ -15,7 +15,7 @@ histories), inputs resident in HBM.  Prints ONE JSON line:
   steady_state the same per-launch statistics over a further block of launches after the timed steps (the
                first ~50 back-to-back launches of a process run at lower clocks); not part of `value`
   parity       the GPU output of the timed configuration against the CPU oracle on a seeded sample of users
-  cpu_baseline the CPU oracle timed on a sample of the same workload's users, on this host's cores
+  cpu_baseline the CPU oracle timed on a sample of the same workload's users, on this host's cores (and on one of them)
   also         the same figures for the other workloads (not the headline)
   prefill      the prefill stage (router argmax + projection into the packed cache): positions/s and
                matrix-core TFLOP/s against the dense peak of its matrix instruction
@@ -259,8 +259,19 @@ def cpu_baseline(w, budget_s=15.0):
         t0 = time.time()
         oracle.attend(w, users=order[:n])
         dt = time.time() - t0
+    # and on one thread, on a sample a sixteenth as large (a few seconds)
+    n1 = max(1, n // max(threads, 1))
+    oracle.set_threads(1)
+    try:
+        t0 = time.time()
+        oracle.attend(w, users=order[:n1])
+        dt1 = time.time() - t0
+    finally:
+        oracle.set_threads(threads)
     return {"value": n / dt, "unit": "users/s", "cores": threads, "kind": "oracle",
-            "sample": f"{n} of {w['B']} users (seeded choice), all heads and queries, {dt:.1f} s wall"}
+            "sample": f"{n} of {w['B']} users (seeded choice), all heads and queries, {dt:.1f} s wall",
+            "single_thread": {"value": n1 / dt1, "unit": "users/s", "cores": 1,
+                              "sample": f"{n1} of {w['B']} users, all heads and queries, {dt1:.1f} s wall"}}
 
 
 OFFLOADED_SHAPES = {

@@ -343,6 +343,17 @@ void ckv_oracle_cache_size(int64_t T, int H, int d_g, int d_u, int dtype, int in
     *full_bytes = ph * 2 * ((int64_t)d_u + d_g) * e;
 }
 
+/* Number of threads the (user, head) loop may use from now on (n >= 1; without OpenMP nothing changes). */
+void ckv_oracle_set_threads(int n)
+{
+#ifdef _OPENMP
+    extern void omp_set_num_threads(int);
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 int ckv_oracle_threads(void)
 {
 #ifdef _OPENMP

@@ -44,6 +44,8 @@ def _load():
         lib.ckv_oracle_cache_size.restype = None
         lib.ckv_oracle_cache_size.argtypes = [i64, i32, i32, i32, i32, i32, i32] + [vp] * 4
         lib.ckv_oracle_threads.restype = ctypes.c_int
+        lib.ckv_oracle_set_threads.restype = None
+        lib.ckv_oracle_set_threads.argtypes = [i32]
         lib.ckv_oracle_prefill.restype = ctypes.c_int
         lib.ckv_oracle_prefill.argtypes = [i32] * 7 + [i64] + [vp] * 13
         lib.ckv_oracle_router_gap.restype = ctypes.c_int
@@ -141,6 +143,11 @@ def cache_size(T, H, d_g, d_u, dtype, index_bytes=4, share=0):
 
 def threads():
     return int(_load().ckv_oracle_threads())
+
+
+def set_threads(n):
+    """Threads the (user, head) loop of the oracle uses from now on."""
+    _load().ckv_oracle_set_threads(int(n))
 
 
 def prefill_side_dims(r):
