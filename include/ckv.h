@@ -298,6 +298,8 @@ int ckv_remap_hot_rows(ckv_cache* cache, const void* pool_k, const void* pool_v,
  * every kernel.  value NULL or "" restores the option's default, key NULL restores all defaults.
  *   "mfma_impl"       "staged": the register-staged matrix-core kernel where the direct-to-LDS one would run; "auto"
  *   "stream_impl"     "narrow": the column-block streaming kernel where the wide-row one would run; "auto"
+ *   "stream_hot_rows" 0 .. 32: pool rows 0 .. n-1 of a work item's head that the wide-row streaming kernel copies into LDS and serves
+ *                     from there (the most used rows after ckv_remap_hot_rows; default 0: measured slower than leaving them to the L2s)
  *   "stream_waves"    "2" | "4": wavefronts per work item of the streaming kernels (default: by the number and length of the items)
  *   "dma_sched"       "static" (default: persistent workgroups with their own item lists) | "dynamic"
  *   "dma_shape"       "nw,qg": wavefronts per workgroup and query groups per wavefront of the direct-to-LDS kernel

@@ -41,6 +41,7 @@ struct Options {
     int nw = 0, qg = 0;        // "dma_shape" = "nw,qg": wavefronts per workgroup, query groups per wavefront (0: from Nq)
     double slow_speed = -1.0;  // "dma_slow_speed": weight of a workgroup that shares its SIMDs with an older one (< 0: default)
     int scores_ahead = -1;     // "dma_scores_ahead" = "0" | "1": tile loop of the direct-to-LDS kernel with the scores one tile ahead (< 0: default)
+    int hot_rows = 0;          // "stream_hot_rows" = n: pool rows the wide-row streaming kernel keeps in LDS per work item (default none)
     int stream_waves = 0;      // "stream_waves" = "2" | "4": wavefronts per work item of the streaming kernels (0: by the number of items)
     bool stream_narrow = false;  // "stream_impl" = "narrow": the column-block streaming kernel also where the wide-row one would run
     bool debug = false;        // "debug" = "1": print the chosen split and list statistics to stderr
@@ -701,6 +702,9 @@ void choose_variant(ckv_cache* c) {
     c->sw_g = one_block || f32_blocks || g_opt.stream_narrow ? 0 : ckv_streamw_lanes(s);
     if (c->sw_g) {
         c->sw_nq = s.Nq >= 2 ? 2 : 1;
+        // (hot rows in LDS, the second half of the frequency renumbering: only where the option asks for them; with them the
+        // kernel measured twice as slow on Zipf indices as with the same rows left to the L2s)
+        c->hot_rows = g_opt.hot_rows > 0 ? std::min(g_opt.hot_rows, ckv_streamw_hot_rows(s, c->sw_g, c->sw_nq)) : 0;
         snprintf(c->variant, sizeof c->variant, "streamw_%s_g%d_q%d_%s", s.dtype == CKV_F32 ? "f32" : "bf16", c->sw_g, c->sw_nq,
                  s.mode == CKV_SOFTMAX ? "softmax" : "silu");
         return;
@@ -1262,6 +1266,7 @@ static int attend_common(const char* who, const ckv_cache* c, const void* pool_k
     a.QB = c->QB;
     a.scale = s.scale;
     a.scores_ahead = c->scores_ahead;
+    a.hot_rows = c->family == CKV_K_STREAM && c->sw_g ? c->hot_rows : 0;
     ckv_cache* mc = const_cast<ckv_cache*>(c);
     hipError_t e;
     // timing: three events per launch (start, main kernel done, merge done)
@@ -1372,6 +1377,12 @@ int ckv_set_option(const char* key, const char* value) {
         if (!unset && strcmp(value, "0") != 0 && strcmp(value, "1") != 0)
             return fail(CKV_ERR_UNSUPPORTED, "ckv_set_option: dma_scores_ahead takes \"0\" or \"1\", not \"%s\"", value);
         g_opt.scores_ahead = unset ? -1 : atoi(value);
+    } else if (strcmp(key, "stream_hot_rows") == 0) {
+        char* end = nullptr;
+        const long v = unset ? 0 : strtol(value, &end, 10);
+        if (!unset && (end == value || *end || v < 0 || v > 32))
+            return fail(CKV_ERR_UNSUPPORTED, "ckv_set_option: stream_hot_rows takes a number from 0 to 32, not \"%s\"", value);
+        g_opt.hot_rows = (int)v;
     } else if (strcmp(key, "stream_waves") == 0) {
         if (!unset && strcmp(value, "2") != 0 && strcmp(value, "4") != 0)
             return fail(CKV_ERR_UNSUPPORTED, "ckv_set_option: stream_waves takes \"2\" or \"4\", not \"%s\"", value);

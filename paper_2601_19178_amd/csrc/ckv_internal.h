@@ -45,6 +45,7 @@ struct ckv_args {
     int32_t d_uk, d_gk, d_uv, d_gv;  // per side: d_u, d_g of the shape for a shared side, (d_a, 0) otherwise
     int32_t QB;            // queries per block (rows of a workspace slot)
     float scale;
+    int32_t hot_rows;      // wide-row streaming kernel: pool rows 0 .. hot_rows - 1 of the item's head are kept in LDS (0: none)
     int32_t scores_ahead;  // direct-to-LDS kernel, four wavefronts at 128 columns: tile loop with the scores one tile ahead
 };
 
@@ -95,6 +96,7 @@ struct ckv_cache {
     int family;          // ckv_kernel_family
     int vec, ncb;        // stream kernel: elements per lane per column block, column blocks
     int grp;             // stream kernel: lanes that share a row (16 or 8)
+    int hot_rows;        // wide-row stream kernel: pool rows kept in LDS per work item (0: none; tuning option stream_hot_rows)
     int sw_g, sw_nq;     // wide-row stream kernel: lanes per row (0: the shape runs in the other stream kernel), queries per pass
     int nw, tp;          // mfma kernels: waves per workgroup, positions per tile
     int nui;             // dma kernel: user-slice load instructions per wavefront and tile
@@ -124,6 +126,8 @@ hipError_t ckv_launch_stream(const ckv_cache* c, const ckv_args& a, hipStream_t 
 hipError_t ckv_launch_streamw(const ckv_cache* c, const ckv_args& a, hipStream_t s);
 int ckv_streamw_lanes(const ckv_shape& s);
 int ckv_streamw_waves_per_simd(const ckv_shape& s, int G, int nq);
+size_t ckv_streamw_hot_row_bytes(const ckv_shape& s);
+int ckv_streamw_hot_rows(const ckv_shape& s, int G, int nq);  // most hot rows the kernel can keep in LDS (0: none)
 hipError_t ckv_launch_mfma(const ckv_cache* c, const ckv_args& a, hipStream_t s);
 // Resident workgroups per CU of the chosen mfma kernel (0 if the shape has no mfma kernel).
 int ckv_mfma_occupancy(int d_a, int nw, int tp, int mode);

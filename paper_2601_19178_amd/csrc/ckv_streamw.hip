@@ -61,7 +61,10 @@ template <> struct Store<uint16_t> {  // bfloat16 bit patterns
 
 // G = lanes per row (8, 16, 32 or 64), NQ = queries served per pass over the history (1 or 2), NSL = slice columns
 // per lane (2, 4 or 8), kWaves = wavefronts per work item (4, or 2 where short items outnumber the resident wavefronts)
-template <typename T, int G, int NQ, int MODE, int NSL, int kWaves>
+// kHot: the first a.hot_rows rows of the item's pools (the most used ones once ckv_remap_hot_rows has renumbered them; the
+// appendix on router activations shows how much the activated entries of similar users overlap) are copied into LDS when the
+// item starts, and a position whose index is below that count takes its pool row from there instead of from memory.
+template <typename T, int G, int NQ, int MODE, int NSL, int kWaves, bool kHot>
 __global__ __launch_bounds__(kLanes * kWaves) __attribute__((amdgpu_waves_per_eu(NQ == 1 && NSL <= NSL_MID ? 3 : 2, 8))) void ckv_streamw_kernel(ckv_args a) {
     using S = Store<T>;
     constexpr int EPL = S::EPL;
@@ -71,6 +74,7 @@ __global__ __launch_bounds__(kLanes * kWaves) __attribute__((amdgpu_waves_per_eu
     constexpr int WMAX = G * EPL + NSL * LP;  // most columns of a final row
     __shared__ float sm_acc[kWaves][NQ][WMAX];
     __shared__ float sm_ml[kWaves][NQ][2];
+    extern __shared__ __attribute__((aligned(16))) unsigned char hot_lds[];  // kHot: a.hot_rows K rows, then as many V rows
 
     const ckv_item it = a.items[blockIdx.x];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -100,6 +104,22 @@ __global__ __launch_bounds__(kLanes * kWaves) __attribute__((amdgpu_waves_per_eu
 #pragma unroll
     for (int i = 0; i < 4; ++i) kmask[i] = S::mask(lg * EPL, i, wk);
     const int nslk = (sk + LP - 1) / LP, nslv = (sv + LP - 1) / LP;  // slice columns per lane in use (wavefront-uniform)
+    // hot rows: whole 16-byte lanes of the rows 0 .. hot - 1 of each pool of the item's head; no more of them than a quarter
+    // of the item's positions, so that fetching them stays a small part of the item
+    const int rbk = (wk * (int)sizeof(T) + 15) / 16 * 16, rbv = (wv * (int)sizeof(T) + 15) / 16 * 16;
+    const int hotk = kHot && ksh ? min(min(a.hot_rows, a.P), n >> 2) : 0, hotv = kHot && vsh ? min(min(a.hot_rows, a.P), n >> 2) : 0;
+    const uint32_t hotv_base = kHot ? (uint32_t)a.hot_rows * rbk : 0;
+    if (kHot) {
+        for (int c = threadIdx.x; c < hotk * (rbk / 16); c += kLanes * kWaves) {
+            const int r = c / (rbk / 16), ch = c % (rbk / 16);
+            *reinterpret_cast<u32x4*>(hot_lds + r * rbk + ch * 16) = *reinterpret_cast<const u32x4*>(kwide + r * kstride + ch * 16);
+        }
+        for (int c = threadIdx.x; c < hotv * (rbv / 16); c += kLanes * kWaves) {
+            const int r = c / (rbv / 16), ch = c % (rbv / 16);
+            *reinterpret_cast<u32x4*>(hot_lds + hotv_base + r * rbv + ch * 16) = *reinterpret_cast<const u32x4*>(vwide + r * vstride + ch * 16);
+        }
+        __syncthreads();
+    }
 
     for (int j0 = 0; j0 < a.QB; j0 += NQ) {
         if (it.q0 + j0 >= a.Nq) break;
@@ -146,7 +166,11 @@ __global__ __launch_bounds__(kLanes * kWaves) __attribute__((amdgpu_waves_per_eu
             for (int i = 0; i < 8; ++i) {
                 const int tp = min(b0 + i * R + g, nt - 1);
                 const int row = ksh ? __shfl(idx, tp, kLanes) : tp + t0;
-                kraw[i] = *reinterpret_cast<const u32x4*>(kwide + row * kstride + koff);
+                // (hot rows: one load through the flat address space, whose address is the row's copy in LDS or the row in memory,
+                // lane by lane; a branch around two kinds of load measured twice as slow as no hot rows at all)
+                const unsigned char* src = kwide + row * kstride + koff;
+                if (kHot) src = row < hotk ? (const unsigned char*)hot_lds + row * rbk + koff : src;
+                kraw[i] = *reinterpret_cast<const u32x4*>(src);
             }
             const int64_t ps = t0 + min(b0 + x * R + g, nt - 1);
 #pragma unroll
@@ -158,7 +182,9 @@ __global__ __launch_bounds__(kLanes * kWaves) __attribute__((amdgpu_waves_per_eu
             for (int i = 0; i < 8; ++i) {
                 const int tp = min(b0 + i * R + g, nt - 1);
                 const int row = vsh ? __shfl(idx, tp, kLanes) : tp + t0;
-                vraw[i] = *reinterpret_cast<const u32x4*>(vwide + row * vstride + voff);
+                const unsigned char* src = vwide + row * vstride + voff;
+                if (kHot) src = row < hotv ? (const unsigned char*)hot_lds + hotv_base + row * rbv + voff : src;
+                vraw[i] = *reinterpret_cast<const u32x4*>(src);
             }
             const int64_t ps = t0 + min(b0 + x * R + g, nt - 1);
 #pragma unroll
@@ -413,8 +439,19 @@ __global__ __launch_bounds__(kLanes * kWaves) __attribute__((amdgpu_waves_per_eu
 template <typename T, int G, int NQ, int NSL, int NWV>
 hipError_t launch_mode(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
     dim3 grid(c->n_items), block(kLanes * NWV);
-    if (c->shape.mode == CKV_SOFTMAX) hipLaunchKernelGGL((ckv_streamw_kernel<T, G, NQ, CKV_SOFTMAX, NSL, NWV>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((ckv_streamw_kernel<T, G, NQ, CKV_SILU_OVER_N, NSL, NWV>), grid, block, 0, s, a);
+    if constexpr (G >= 16 && NQ == 1 && NSL <= NSL_MID) {  // the instantiations that exist with hot rows in LDS
+        if (a.hot_rows > 0) {
+            const size_t lds = (size_t)a.hot_rows * ckv_streamw_hot_row_bytes(c->shape);
+            if (c->shape.mode == CKV_SOFTMAX)
+                hipLaunchKernelGGL((ckv_streamw_kernel<T, G, NQ, CKV_SOFTMAX, NSL, NWV, true>), grid, block, lds, s, a);
+            else
+                hipLaunchKernelGGL((ckv_streamw_kernel<T, G, NQ, CKV_SILU_OVER_N, NSL, NWV, true>), grid, block, lds, s, a);
+            return hipGetLastError();
+        }
+    }
+    if (a.hot_rows > 0) return hipErrorInvalidValue;  // (the host asks for hot rows only where ckv_streamw_hot_rows allows them)
+    if (c->shape.mode == CKV_SOFTMAX) hipLaunchKernelGGL((ckv_streamw_kernel<T, G, NQ, CKV_SOFTMAX, NSL, NWV, false>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((ckv_streamw_kernel<T, G, NQ, CKV_SILU_OVER_N, NSL, NWV, false>), grid, block, 0, s, a);
     return hipGetLastError();
 }
 
@@ -450,6 +487,36 @@ hipError_t launch_g(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
 }
 
 }  // namespace
+
+// Bytes of LDS one hot row takes (its K row and its V row in whole 16-byte lanes; a side without pool takes none).
+size_t ckv_streamw_hot_row_bytes(const ckv_shape& s) {
+    const int e = s.dtype == CKV_F32 ? 4 : 2;
+    size_t bytes = 0;
+    for (int side = 0; side < 2; ++side) {
+        int du, dg;
+        ckv_side_dims(s, side, &du, &dg);
+        // (the kernel places the V rows behind hot_rows K rows of the K side's row size, whatever the K side is)
+        const int wide = dg > 0 ? dg : s.d_g + s.d_u;
+        bytes += (size_t)((wide * e + 15) / 16 * 16);
+    }
+    return bytes;
+}
+
+// Most pool rows the kernel that serves the shape (G lanes per row, nq queries per pass) can keep in LDS: a multiple of
+// eight, at most 32, within 40 KB; 0 where the instantiation does not exist (fewer than 16 lanes per row, two queries per
+// pass, slices of more than four columns per lane) or the shape has no pool.
+int ckv_streamw_hot_rows(const ckv_shape& s, int G, int nq) {
+    if (G < 16 || nq != 1 || s.d_g == 0) return 0;
+    int slice = 0;
+    for (int side = 0; side < 2; ++side) {
+        int du, dg;
+        ckv_side_dims(s, side, &du, &dg);
+        if (dg > 0) slice = slice > du ? slice : du;
+    }
+    if (slice > NSL_MID * (G / 8)) return 0;
+    const int fit = (int)(40960 / ckv_streamw_hot_row_bytes(s)) / 8 * 8;
+    return fit > 32 ? 32 : fit;
+}
 
 // Lanes per row with which this kernel serves the shape (8, 16, 32 or 64), or 0 if it does not: the wide
 // part of each side must be addressable in whole 16-byte lanes (row strides that are multiples of 16 bytes),

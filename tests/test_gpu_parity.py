@@ -424,6 +424,37 @@ def test_hot_row_renumbering(gpu, share, kind):
     check_against_oracle(after, w, what=f"renumbered {kind} share={share}")
 
 
+@pytest.mark.parametrize("dtype,mode,d_a,d_u,H,P,share,idx,rows", [
+    (wl.BF16, wl.SOFTMAX, 256, 4, 2, 300, wl.SHARE_KV, ("zipf", 1.1), 32), (wl.BF16, wl.SILU_OVER_N, 256, 10, 2, 20, wl.SHARE_KV, "uniform", 32),
+    (wl.BF16, wl.SOFTMAX, 256, 3, 2, 300, wl.SHARE_K, ("zipf", 1.2), 16), (wl.BF16, wl.SOFTMAX, 256, 3, 2, 300, wl.SHARE_V, ("zipf", 1.2), 8),
+    (wl.F32, wl.SOFTMAX, 256, 6, 1, 500, wl.SHARE_KV, ("zipf", 1.1), 32), (wl.F32, wl.SILU_OVER_N, 128, 2, 2, 77, wl.SHARE_KV, "uniform", 21),
+    (wl.BF16, wl.SOFTMAX, 128, 5, 3, 1000, wl.SHARE_KV, ("zipf", 1.05), 32), (wl.BF16, wl.SOFTMAX, 512, 16, 1, 200, wl.SHARE_KV, ("zipf", 1.1), 32)])
+def test_hot_rows_in_lds_of_the_wide_row_streaming_kernel(gpu, dtype, mode, d_a, d_u, H, P, share, idx, rows):
+    """The second half of the frequency renumbering (appendix on router activations): the first rows of the pools copied into
+    LDS per work item and served from there.  Results must be bit-identical with and without (the same rows, the same
+    arithmetic), before and after the renumbering, and match the oracle; pools smaller than the row count, histories shorter
+    than four times the row count (fewer rows are then kept) and sides without pool are among the cases."""
+    ckv, session = gpu
+    w = make(RAGGED + (700, 31, 33, 97), dtype, mode, d_a=d_a, d_u=d_u, H=H, P=P, Nq=1, share=share, idx=idx)
+    outs = []
+    for hot in (0, rows):
+        ckv.ckv_set_option("stream_hot_rows", str(hot))
+        try:
+            with session.Session(w) as s:
+                assert ckv.ckv_variant(s.cache).startswith("streamw")
+                s.attend()
+                outs.append(s.output().copy())
+                s.remap_hot_rows()
+                s.out.fill_(float("nan"))
+                s.attend()
+                outs.append(s.output().copy())
+        finally:
+            ckv.ckv_set_option(None)
+    for o in outs[1:]:
+        np.testing.assert_array_equal(o, outs[0])
+    check_against_oracle(outs[3], w, what=f"hot rows in LDS, d_a={d_a} d_u={d_u} share={share}")
+
+
 def test_hot_row_renumbering_rejects_offloaded_and_aliased(gpu):
     ckv, session = gpu
     w = make((10, 20), wl.BF16, wl.SOFTMAX, d_a=64, d_u=8, H=1, P=50, Nq=1)

@@ -77,7 +77,7 @@ def test_options_are_validated_and_steer_the_plan():
     direct-to-LDS kernel to the register-staged one (seen through ckv_plan, no device); key None restores defaults."""
     from paper_2601_19178_amd import ckv
     for key, value in (("no_such_option", "1"), ("mfma_impl", "fastest"), ("dma_sched", "lazy"), ("dma_shape", "4"),
-                       ("dma_shape", "0,1"), ("dma_slow_speed", "fast"), ("dma_slow_speed", "-1"), ("stream_impl", "wide"), ("stream_waves", "3"),
+                       ("dma_shape", "0,1"), ("dma_slow_speed", "fast"), ("dma_slow_speed", "-1"), ("stream_impl", "wide"), ("stream_waves", "3"), ("stream_hot_rows", "33"), ("stream_hot_rows", "many"),
                        ("dma_scores_ahead", "yes")):
         with pytest.raises(ckv.CkvError) as e:
             ckv.ckv_set_option(key, value)
