@@ -303,6 +303,8 @@ int ckv_remap_hot_rows(ckv_cache* cache, const void* pool_k, const void* pool_v,
  *   "stream_waves"    "2" | "4": wavefronts per work item of the streaming kernels (default: by the number and length of the items)
  *   "dma_sched"       "static" (default: persistent workgroups with their own item lists) | "dynamic"
  *   "dma_shape"       "nw,qg": wavefronts per workgroup and query groups per wavefront of the direct-to-LDS kernel
+ *   "dma_q16"         "0" | "1": up to sixteen queries at 64 columns run sixteen to a work item on the 16x16x32 matrix instruction
+ *                     (default "1") or 32 to a work item like larger query counts
  *   "dma_scores_ahead" "0" | "1": tile loop of the direct-to-LDS kernel that takes the scores of a tile one iteration early (exists
  *                     for four wavefronts at 128 columns; default: on where both sides gather from pools)
  *   "dma_slow_speed"  weight in (0, 4] of a workgroup that shares its SIMDs with an older one (default 0.75 / 1.0)

@@ -40,6 +40,7 @@ struct Options {
     int sched = 0;             // "dma_sched": 0 default (static), 1 static, 2 dynamic
     int nw = 0, qg = 0;        // "dma_shape" = "nw,qg": wavefronts per workgroup, query groups per wavefront (0: from Nq)
     double slow_speed = -1.0;  // "dma_slow_speed": weight of a workgroup that shares its SIMDs with an older one (< 0: default)
+    int q16 = -1;              // "dma_q16" = "0" | "1": sixteen-query organisation of the direct-to-LDS kernel where it applies (< 0: default, on)
     int scores_ahead = -1;     // "dma_scores_ahead" = "0" | "1": tile loop of the direct-to-LDS kernel with the scores one tile ahead (< 0: default)
     int hot_rows = 0;          // "stream_hot_rows" = n: pool rows the wide-row streaming kernel keeps in LDS per work item (default none)
     int stream_waves = 0;      // "stream_waves" = "2" | "4": wavefronts per work item of the streaming kernels (0: by the number of items)
@@ -368,6 +369,7 @@ int resident_workgroups(const ckv_cache* c) {
     const ckv_shape& s = c->shape;
     const int d_a = s.d_g + s.d_u;
     if (c->family == CKV_K_MFMA) return std::max(1, ckv_mfma_occupancy(d_a <= 64 ? 64 : (d_a <= 128 ? 128 : 256), c->nw, c->tp, s.mode));
+    if (c->family == CKV_K_DMA && c->q16) return std::max(1, ckv_dma_q16_occupancy(s.mode));
     if (c->family == CKV_K_DMA) return std::max(1, ckv_dma_occupancy(d_a, c->nw, c->qg, s.mode, s.d_g == 0 ? 0 : s.d_u));
     if (c->family == CKV_K_MFMA32) return std::max(1, ckv_mfma32_occupancy(d_a <= 64 ? 64 : (d_a <= 128 ? 128 : 256), s.mode, c->QB == 64));
     // (wide-row streaming kernel: workgroups of four wavefronts, two or three wavefronts per SIMD by its registers)
@@ -658,6 +660,13 @@ void choose_variant(ckv_cache* c) {
                 // ordinary cache, whose rows all stream from HBM and want the deeper prefetch of the other loop)
                 c->scores_ahead = g_opt.scores_ahead < 0 ? (s.share == CKV_SHARE_KV && s.d_g > 0) : g_opt.scores_ahead;
                 c->QB = 32 * nw * qg;
+                // (sixteen queries or fewer at 64 columns: the organisation on the 16x16x32 instruction, which they fill)
+                c->q16 = g_opt.q16 != 0 && nw == 1 && qg == 1 && s.Nq <= 16 && ckv_dma_q16_supported(d_a, s.d_u, s.d_g);
+                if (c->q16) {
+                    c->QB = 16;
+                    snprintf(c->variant, sizeof c->variant, "mfma_dma_bf16_d%d_w1_q16_%s", d_a, s.mode == CKV_SOFTMAX ? "softmax" : "silu");
+                    return;
+                }
                 snprintf(c->variant, sizeof c->variant, "mfma_dma_bf16_d%d_w%d_g%d_%s", d_a, nw, qg,
                          s.mode == CKV_SOFTMAX ? "softmax" : "silu");
                 return;
@@ -1373,6 +1382,10 @@ int ckv_set_option(const char* key, const char* value) {
         if (!unset && (end == value || !(v > 0.0) || v > 4.0))
             return fail(CKV_ERR_UNSUPPORTED, "ckv_set_option: dma_slow_speed takes a number in (0, 4], not \"%s\"", value);
         g_opt.slow_speed = v;
+    } else if (strcmp(key, "dma_q16") == 0) {
+        if (!unset && strcmp(value, "0") != 0 && strcmp(value, "1") != 0)
+            return fail(CKV_ERR_UNSUPPORTED, "ckv_set_option: dma_q16 takes \"0\" or \"1\", not \"%s\"", value);
+        g_opt.q16 = unset ? -1 : atoi(value);
     } else if (strcmp(key, "dma_scores_ahead") == 0) {
         if (!unset && strcmp(value, "0") != 0 && strcmp(value, "1") != 0)
             return fail(CKV_ERR_UNSUPPORTED, "ckv_set_option: dma_scores_ahead takes \"0\" or \"1\", not \"%s\"", value);

@@ -126,10 +126,15 @@ struct Geo {
 // instantiation of its own, so that the even case carries none of its code; 2: d_u even, 10 to 16, at 64 or 128 columns;
 // 3: d_u odd, 5 or 7, at 64 or 128 columns.  2 and 3 have the larger staging area (an odd slice takes a lane per element);
 // with it a 64-column kernel loses one of its four resident workgroups, which is why 1 and 3 are apart.
-template <int DA, int NW, int QG, int MODE, int UK>
+// Q16: sixteen queries per work item on v_mfma_f32_16x16x32_bf16 (one wavefront, 64 columns, even user slices of up to 8
+// columns).  On the 32x32 instruction sixteen queries fill half of the query columns, so half of the matrix and weight
+// arithmetic is spent on nothing; here a lane holds one query and eight positions of a tile, nothing is idle.
+template <int DA, int NW, int QG, int MODE, int UK, bool Q16 = false>
 __global__ __launch_bounds__(NW * 64)
 __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU))) void ckv_dma_kernel(ckv_args a, int nui) {
     using G = Geo<DA, NW, (UK >= 2)>;
+    static_assert(!Q16 || (DA == 64 && NW == 1 && QG == 1 && UK == 0), "sixteen-query organisation: one wavefront at 64 columns");
+    typedef __attribute__((ext_vector_type(4))) float f32x4;
     constexpr int NKK = DA / 16, NDT = DA / 32;
     constexpr bool kWide = DA > 128;  // operands of a whole tile no longer fit into registers beside the accumulators
     static_assert(!kWide || QG == 1, "one query group per wavefront at 256 columns");
@@ -202,7 +207,8 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
     //      [pool | user], i.e. paper column + d_u for pool columns) out of LDS.
     constexpr int QS = DA * 2 + 16;  // bytes per staged row
     const int qfirst = it.q0 + wave * QG * 32;
-    const int qrows = min(max(a.Nq - qfirst, 0), QG * 32);
+    const int qrows = min(max(a.Nq - qfirst, 0), Q16 ? 16 : QG * 32);
+    const int q16 = lane & 15, g4 = lane >> 4;  // Q16: the lane's query and its group of eight positions
     const int64_t qbyte0 = (((int64_t)it.b * a.H + it.h) * a.Nq + qfirst) * (DA * 2);
     const uint32_t qlds = lds0 + wave * (QG * 32 * QS);
     bf16x8 qreg[QG][NKK];
@@ -216,7 +222,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
             *(lds_u32x4*)(uintptr_t)(qlds + row * QS + c * 16) = v;
         }
 #pragma unroll
-        for (int g = 0; g < QG; ++g)
+        for (int g = 0; g < (Q16 ? 0 : QG); ++g)
 #pragma unroll
             for (int kk = 0; kk < NKK; ++kk) {
                 u32x4 w;
@@ -234,13 +240,27 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
                 }
                 qreg[g][kk] = __builtin_bit_cast(bf16x8, w);
             }
+        if (Q16) {
+            // B operands of the 16x16x32 instruction: query lane % 16, columns 32 ks + 8 (lane / 16) .. + 8 of the kernel's order
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                u32x4 w;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int ci = 32 * ks + 8 * g4 + 2 * j;
+                    const int pc = ci < dgk ? ci + duk : ci - dgk;
+                    w[j] = *(const lds_u32*)(uintptr_t)(qlds + q16 * QS + pc * 2);
+                }
+                qreg[0][ks] = __builtin_bit_cast(bf16x8, w);
+            }
+        }
         // everything above (global loads included) has to be complete here: a compiler-inserted
         // wait inside the tile loop would also drain the asynchronous gathers it cannot see, and
         // the gathers are about to overwrite the staging area
 #pragma unroll
         for (int g = 0; g < QG; ++g)
 #pragma unroll
-            for (int kk = 0; kk < NKK; ++kk) asm volatile("" : "+v"(qreg[g][kk]));
+            for (int kk = 0; kk < (Q16 ? 2 : NKK); ++kk) asm volatile("" : "+v"(qreg[g][kk]));
         lds_barrier();
     }
 
@@ -255,6 +275,11 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
 #pragma unroll
             for (int r = 0; r < 16; ++r) oacc[g][dt][r] = 0.f;
     }
+    f32x4 o16[4];  // Q16: O^T blocks of 16 columns: query lane % 16, columns 16 dt + 4 (lane / 16) + r
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) o16[dt][r] = 0.f;
     const float sc = MODE == CKV_SOFTMAX ? a.scale * kLog2e : a.scale;
     const float nsc = -kLog2e * a.scale;    // SiLU: exponent of 2 per unit of raw score
     const bool unit_scale = a.scale == 1.f;  // SiLU(QK^T) taken literally: one multiply less per weight
@@ -657,8 +682,118 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
             weights_and_output(std::false_type{}, s_cur, ka, va, n - (ntiles - 1) * TP);
             back(ntiles - 1);
         };
+        // Sixteen queries: the same ring, waits and publication as tile_loop; a tile is two score blocks of sixteen positions.
+        // Row m of score block b is tile position 8 (m / 4) + 4 b + m % 4, so that a lane ends up with the weights of the
+        // eight consecutive positions 8 (lane / 16) .. + 8, which is what the B operand of the output instruction wants.
+        auto tile_loop_q16 = [&](auto nui_c, auto both_c) {
+            constexpr int NUI = decltype(nui_c)::value;
+            constexpr int NS = G::NS;
+            int rk[G::NI], rv[G::NI];
+            gather_rows(both_c, 0, rk, rv);
+            // operand addresses within a stage: K rows of the two score blocks (16-byte chunk 4 ks + lane / 16), and the
+            // transposed reads of V (the sixteen lanes of a group fetch four positions x sixteen columns, four columns each)
+            uint32_t kad[2][2];
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                const int p = 8 * (q16 >> 2) + 4 * b + (q16 & 3);
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) kad[b][ks] = p * G::ROWB + (((4 * ks + g4) ^ fk<DA>(p)) << 4);
+            }
+            const int vp = 8 * g4 + (q16 >> 2);  // position row of the lane's transposed read (and that + 4)
+            uint32_t vad[2][4];
+#pragma unroll
+            for (int hl = 0; hl < 2; ++hl)
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt) {
+                    const int p = vp + 4 * hl, col = 16 * dt + 4 * (q16 & 3);
+                    vad[hl][dt] = G::KV + p * G::ROWB + (((col >> 3) ^ fv<DA>(p)) << 4) + (col & 7) * 2;
+                }
+            for (int t = -(NS - 1); t < ntiles; ++t) {
+                issue_idx(t + NS + 2);
+#pragma unroll
+                for (int s = 0; s < 2 * G::NI + NUI; ++s) tile_dma(t + NS - 1, s, rk, rv);
+                if (t >= 0) {
+                    const uint32_t st = lds0 + (t & (NS - 1)) * G::STAGE;
+                    const int nt = min(n - t * TP, TP);
+                    bf16x8 ka[2][2], va[4];
+#pragma unroll
+                    for (int b = 0; b < 2; ++b)
+#pragma unroll
+                        for (int ks = 0; ks < 2; ++ks) ka[b][ks] = *(const lds_bf16x8*)(uintptr_t)(st + kad[b][ks]);
+#pragma unroll
+                    for (int dt = 0; dt < 4; ++dt) {
+                        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(uintptr_t)(st + vad[0][dt]));
+                        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(uintptr_t)(st + vad[1][dt]));
+                        va[dt] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    }
+                    f32x4 sb[2];
+#pragma unroll
+                    for (int b = 0; b < 2; ++b) {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) sb[b][r] = 0.f;
+#pragma unroll
+                        for (int ks = 0; ks < 2; ++ks) sb[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[b][ks], qreg[0][ks], sb[b], 0, 0, 0);
+                    }
+                    // the lane's eight scores, positions 8 (lane / 16) + i of the tile
+                    float sv[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) sv[i] = sb[i >> 2][i & 3];
+                    bf16x8 pb;
+                    if (MODE == CKV_SOFTMAX) {
+                        if (nt < TP) {
+#pragma unroll
+                            for (int i = 0; i < 8; ++i) sv[i] = mask_tail(sv[i], 8 * g4 + i >= nt, -INFINITY);
+                        }
+                        float tmax = sv[0];
+#pragma unroll
+                        for (int i = 1; i < 8; ++i) tmax = fmaxf(tmax, sv[i]);
+                        tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+                        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64)) * sc;
+                        if (__any(tmax > m_ref[0] + kLazy)) {
+                            const float m_new = fmaxf(m_ref[0], tmax);
+                            const float alpha = __builtin_amdgcn_exp2f(m_ref[0] - m_new);
+                            lsum[0] *= alpha;
+#pragma unroll
+                            for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                                for (int r = 0; r < 4; ++r) o16[dt][r] *= alpha;
+                            m_ref[0] = m_new;
+                        }
+                        float psum = 0.f;
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) {
+                            const float p = __builtin_amdgcn_exp2f(fmaf(sv[i], sc, -m_ref[0]));
+                            psum += p;
+                            pb[i] = (__bf16)p;
+                        }
+                        lsum[0] += psum;
+                    } else {
+                        if (nt < TP) {
+#pragma unroll
+                            for (int i = 0; i < 8; ++i) sv[i] = mask_tail(sv[i], 8 * g4 + i >= nt, 0.f);
+                        }
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) {
+                            const float e = __builtin_amdgcn_exp2f(sv[i] * nsc);
+                            pb[i] = (__bf16)((sv[i] * sc) * __builtin_amdgcn_rcpf(1.f + e));
+                        }
+                    }
+#pragma unroll
+                    for (int dt = 0; dt < 4; ++dt) o16[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[dt], pb, o16[dt], 0, 0, 0);
+                }
+                wait_vm<(NS - 2) * (2 * G::NI + 1 + NUI)>();
+                if (NUI > 0 && t + 1 >= 0 && t + 1 < ntiles) concat(nui_c, t + 1);
+                gather_rows(both_c, t + NS, rk, rv);
+                lds_barrier();
+            }
+        };
         constexpr bool kScoresAhead = DA == 128 && NW == 4 && QG == 1 && UK == 0;
         auto with_nui = [&](auto nui_c) {
+            if constexpr (Q16) {
+                if (ksh && vsh) tile_loop_q16(nui_c, std::true_type{});
+                else tile_loop_q16(nui_c, std::false_type{});
+                return;
+            }
             if constexpr (kScoresAhead) {
                 if (a.scores_ahead) {
                     if (ksh && vsh) tile_loop_ahead(nui_c, std::true_type{});
@@ -687,7 +822,58 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
     float l_tot[QG];
 #pragma unroll
     for (int g = 0; g < QG; ++g) l_tot[g] = MODE == CKV_SOFTMAX ? lsum[g] + other_half(lsum[g]) : 0.f;
-    if (it.part < 0) {
+    if constexpr (Q16) {
+        // a query's sum is spread over the four lanes that share it
+        float l16 = 0.f;
+        if (MODE == CKV_SOFTMAX) {
+            l16 = lsum[0] + __shfl_xor(lsum[0], 16, 64);
+            l16 += __shfl_xor(l16, 32, 64);
+        }
+        if (it.part < 0) {
+            float inv;
+            if (MODE == CKV_SOFTMAX) inv = l16 > 0.f ? 1.f / l16 : 0.f;
+            else inv = it.n_total > 0 ? 1.f / (float)it.n_total : 0.f;
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                for (int r = 0; r < 4; r += 2) {
+                    const int ci = 16 * dt + 4 * g4 + r;
+                    const int pc = ci < dgv ? ci + duv : ci - dgv;
+                    const uint32_t two = (uint32_t)f2bf(o16[dt][r] * inv) | ((uint32_t)f2bf(o16[dt][r + 1] * inv) << 16);
+                    *(lds_u32*)(uintptr_t)(qlds + q16 * QS + pc * 2) = two;
+                }
+            unsigned char* odst = (unsigned char*)a.out + qbyte0;
+#pragma unroll
+            for (int i = 0; i < 16 * G::CH / 64; ++i) {
+                const int e = i * 64 + lane, row = e / G::CH, c = e % G::CH;
+                const u32x4 v = *(const lds_u32x4*)(uintptr_t)(qlds + row * QS + c * 16);
+                if (row < qrows) *reinterpret_cast<u32x4*>(odst + (int64_t)row * (DA * 2) + c * 16) = v;
+            }
+        } else {
+            float* ws = a.partial + (int64_t)it.part * a.QB * (DA + 2);
+            constexpr int FS = DA * 4 + 16;  // bytes per staged row
+            static_assert(16 * FS <= G::NS * G::STAGE, "the staged accumulators must fit in the retired stages");
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int ci = 16 * dt + 4 * g4 + r;
+                    const int pc = ci < dgv ? ci + duv : ci - dgv;
+                    *(lds_f32*)(uintptr_t)(lds0 + q16 * FS + pc * 4) = o16[dt][r];
+                }
+            if (g4 == 0) {
+                ws[(int64_t)a.QB * DA + q16] = m_ref[0] * kLn2;
+                ws[(int64_t)a.QB * DA + a.QB + q16] = l16;
+            }
+#pragma unroll
+            for (int i = 0; i < 16 * (DA / 4) / 64; ++i) {
+                const int e = i * 64 + lane, row = e / (DA / 4), c = e % (DA / 4);
+                const u32x4 v = *(const lds_u32x4*)(uintptr_t)(lds0 + row * FS + c * 16);
+                *reinterpret_cast<u32x4*>(ws + (int64_t)row * DA + c * 4) = v;
+            }
+            lds_barrier();
+        }
+    } else if (it.part < 0) {
 #pragma unroll
         for (int g = 0; g < QG; ++g) {
             float inv;
@@ -753,29 +939,29 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
     }  // items of this workgroup
 }
 
-template <int DA, int NW, int QG, int MODE, int UK>
+template <int DA, int NW, int QG, int MODE, int UK, bool Q16 = false>
 hipError_t prepare() {
     constexpr int lds = Geo<DA, NW, (UK >= 2)>::LDS;
     static hipError_t done =
-        hipFuncSetAttribute((const void*)ckv_dma_kernel<DA, NW, QG, MODE, UK>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        hipFuncSetAttribute((const void*)ckv_dma_kernel<DA, NW, QG, MODE, UK, Q16>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     return done;
 }
 
-template <int DA, int NW, int QG, int MODE, int UK>
+template <int DA, int NW, int QG, int MODE, int UK, bool Q16 = false>
 hipError_t launch(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
-    hipError_t e = prepare<DA, NW, QG, MODE, UK>();
+    hipError_t e = prepare<DA, NW, QG, MODE, UK, Q16>();
     if (e != hipSuccess) return e;
     constexpr int lds = Geo<DA, NW, (UK >= 2)>::LDS;
-    hipLaunchKernelGGL((ckv_dma_kernel<DA, NW, QG, MODE, UK>), dim3(c->n_wg), dim3(NW * 64), lds, s, a, c->nui);
+    hipLaunchKernelGGL((ckv_dma_kernel<DA, NW, QG, MODE, UK, Q16>), dim3(c->n_wg), dim3(NW * 64), lds, s, a, c->nui);
     return hipGetLastError();
 }
 
-template <int DA, int NW, int QG, int MODE, int UK>
+template <int DA, int NW, int QG, int MODE, int UK, bool Q16 = false>
 int occupancy() {
-    if (prepare<DA, NW, QG, MODE, UK>() != hipSuccess) return 0;
+    if (prepare<DA, NW, QG, MODE, UK, Q16>() != hipSuccess) return 0;
     int nb = 0;
     constexpr int lds = Geo<DA, NW, (UK >= 2)>::LDS;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)ckv_dma_kernel<DA, NW, QG, MODE, UK>, NW * 64, lds) !=
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void*)ckv_dma_kernel<DA, NW, QG, MODE, UK, Q16>, NW * 64, lds) !=
         hipSuccess)
         return 0;
     return nb;
@@ -811,6 +997,12 @@ int ckv_dma_nui(int d_a, int nw, int d_u) {
 
 // (user slices of 10 to 16 columns, or of 5 or 7, at 64 or 128 columns: the instantiations with the larger staging area)
 static bool wide_slices(int d_a, int d_u) { return d_a != 256 && (d_u & 1 ? d_u > 3 : d_u > 8); }
+
+// Sixteen-query organisation (64 columns, one wavefront, even user slices of up to 8 columns).
+bool ckv_dma_q16_supported(int d_a, int d_u, int d_g) { return d_a == 64 && (d_g == 0 || (!(d_u & 1) && d_u <= 8)); }
+int ckv_dma_q16_occupancy(int mode) {
+    return mode == CKV_SOFTMAX ? occupancy<64, 1, 1, CKV_SOFTMAX, 0, true>() : occupancy<64, 1, 1, CKV_SILU_OVER_N, 0, true>();
+}
 
 int ckv_dma_occupancy(int d_a, int nw, int qg, int mode, int d_u) {
     if ((d_u & 1) && !wide_slices(d_a, d_u)) {
@@ -848,6 +1040,8 @@ int ckv_dma_occupancy(int d_a, int nw, int qg, int mode, int d_u) {
 hipError_t ckv_launch_dma(const ckv_cache* c, const ckv_args& a, hipStream_t s) {
     if (c->n_items == 0) return hipSuccess;
     const int d_a = a.d_a, nw = c->nw, qg = c->qg;
+    if (c->q16)
+        return c->shape.mode == CKV_SOFTMAX ? launch<64, 1, 1, CKV_SOFTMAX, 0, true>(c, a, s) : launch<64, 1, 1, CKV_SILU_OVER_N, 0, true>(c, a, s);
     if ((a.d_u & 1) && wide_slices(d_a, a.d_u)) {  // one query group per wavefront only
 #define X(DA, NW)                                                                       \
     if (d_a == DA && nw == NW && qg == 1)                                               \

@@ -101,6 +101,7 @@ struct ckv_cache {
     int nw, tp;          // mfma kernels: waves per workgroup, positions per tile
     int nui;             // dma kernel: user-slice load instructions per wavefront and tile
     int qg;              // dma kernel: groups of 32 queries per wavefront
+    int q16;             // dma kernel: sixteen queries per work item on the 16x16x32 matrix instruction
     int scores_ahead;    // dma kernel: tile loop with the scores one tile ahead (four wavefronts, one query group, 128 columns)
     int QB;              // queries per block
     int n_items, n_merge, n_parts;
@@ -138,6 +139,9 @@ hipError_t ckv_launch_dma(const ckv_cache* c, const ckv_args& a, hipStream_t s);
 int ckv_dma_nui(int d_a, int nw, int d_u);  // -1: shape not served
 int ckv_dma_occupancy(int d_a, int nw, int qg, int mode, int d_u);
 bool ckv_dma_supported(int d_a, int nw, int qg);
+// sixteen queries per work item on the 16x16x32 matrix instruction (64 columns, one wavefront)
+bool ckv_dma_q16_supported(int d_a, int d_u, int d_g);
+int ckv_dma_q16_occupancy(int mode);
 
 // fp32-storage variant of the register-staged mfma kernel (four wavefronts, 128 queries per block).
 hipError_t ckv_launch_mfma32(const ckv_cache* c, const ckv_args& a, hipStream_t s);

@@ -136,8 +136,15 @@ def scores_ahead_supported(DA, NW, QG, UK):
     return DA == 128 and NW == 4 and QG == 1 and UK == 0
 
 
-def run_item(DA, NW, QG, shape, item, buffers, check_rows=True, scores_ahead=False):
+def q16_supported(DA, NW, QG, UK, d_u, d_g):
+    """The instantiation with sixteen queries per work item on the 16x16x32 matrix instruction, and the slices it takes."""
+    return DA == 64 and NW == 1 and QG == 1 and UK == 0 and (d_g == 0 or (d_u % 2 == 0 and d_u <= 8))
+
+
+def run_item(DA, NW, QG, shape, item, buffers, check_rows=True, scores_ahead=False, q16=False):
     """One work item through the kernel's access pattern.
+    q16: sixteen queries per work item (lane = query lane % 16, group of eight positions lane / 16): other operand
+    addresses and another epilogue, the same ring.
     scores_ahead: the tile loop that takes the scores of tile t + 1 in the iteration that finishes tile t (tiles are
     published one iteration earlier, two tiles of gathers in flight instead of three).
 
@@ -186,6 +193,9 @@ def run_item(DA, NW, QG, shape, item, buffers, check_rows=True, scores_ahead=Fal
 
     lane = np.arange(64)
     qn, hh = lane & 31, lane >> 5
+    l16, g4 = lane & 15, lane >> 4
+    need(not q16 or q16_supported(DA, NW, QG, UK, d_u, d_g), "this instantiation or slice width has no sixteen-query organisation")
+    need(not (q16 and scores_ahead), "one tile loop at a time")
     waves = [Wave(lds) for _ in range(NW)]
     any_pool = ksh or vsh
     ilast = n - 1 if any_pool else 7
@@ -211,7 +221,7 @@ def run_item(DA, NW, QG, shape, item, buffers, check_rows=True, scores_ahead=Fal
     QS = DA * 2 + 16
     need(NW * QG * 32 * QS <= G.NS * G.STAGE, "query staging does not fit under the stages")
     qfirst = [item["q0"] + w * QG * 32 for w in range(NW)]
-    qrows = [min(max(Nq - qf, 0), QG * 32) for qf in qfirst]
+    qrows = [min(max(Nq - qf, 0), 16 if q16 else QG * 32) for qf in qfirst]
     qbyte0 = [((item["b"] * H + h) * Nq + qf) * da * 2 for qf in qfirst]
 
     ntiles = (n + TP - 1) // TP
@@ -231,7 +241,17 @@ def run_item(DA, NW, QG, shape, item, buffers, check_rows=True, scores_ahead=Fal
             if ok.any():
                 vals[ok] = g_q.read(qbyte0[w] + row[ok] * da * 2 + c[ok] * 16, 16, "query rows")
             lds.write(qlds + row * QS + c * 16, vals, "query staging")
-        for g in range(QG):
+        for ks in (range(2) if q16 else ()):
+            for j in range(4):
+                ci = 32 * ks + 8 * g4 + 2 * j
+                pc = np.where(ci < dgk, ci + duk, ci - dgk)
+                got = lds.read(qlds + l16 * QS + pc * 2, 4, "query operand")
+                if check_rows:
+                    rows_ok = l16 < qrows[w]
+                    want = g_q.data[(qbyte0[w] + l16 * da * 2 + pc * 2)[rows_ok, None] + np.arange(4)]
+                    need(np.array_equal(got[rows_ok], want), "a query operand is not the query's own columns")
+                    need(not got[~rows_ok].any(), "the operand of a query past the last is not zero")
+        for g in (() if q16 else range(QG)):
             for kk in range(DA // 16):
                 for j in range(4):
                     ci = 16 * kk + 8 * hh + 2 * j
@@ -381,6 +401,34 @@ def run_item(DA, NW, QG, shape, item, buffers, check_rows=True, scores_ahead=Fal
             g16, s16 = lane >> 4, lane & 15
             vrow = G.KV + (4 * hh + (s16 >> 2)) * G.ROWB + (s16 & 1) * 8
             vc, vx = 2 * (g16 & 1) + ((s16 & 3) >> 1), fv(DA, s16 >> 2)
+            if q16:
+                # A operand of score block b: row m = lane % 16 is tile position 8 (m / 4) + 4 b + m % 4, columns
+                # 32 ks + 8 (lane / 16) .. + 8; the lane's four results of block b are then positions 8 (lane / 16) + 4 b + r.
+                # A operand of the output blocks: a group of sixteen lanes fetches positions 8 (lane / 16) + 4 hl .. + 4 by
+                # columns 16 dt .. + 16, four columns a lane, and the transposing read hands lane m column 16 dt + m.
+                ek, ev = expected_rows(tile)
+                for b in range(2):
+                    pk_ = 8 * (l16 >> 2) + 4 * b + (l16 & 3)
+                    for ks in range(2):
+                        got = lds.read(st + pk_ * G.ROWB + (((4 * ks + g4) ^ fk(DA, pk_)) << 4), 16, "K operand").view(np.uint16)
+                        if check_rows:
+                            cols = 32 * ks + 8 * g4[:, None] + np.arange(8)
+                            okp = pk_ < min(n - tile * TP, TP)
+                            need(np.array_equal(got[okp], ek[pk_[:, None], cols][okp]), f"tile {tile}: a K operand is not its position's columns")
+                for hl in range(2):
+                    pv_ = 8 * g4 + (l16 >> 2) + 4 * hl
+                    for dt in range(4):
+                        col = 16 * dt + 4 * (l16 & 3)
+                        ad = st + G.KV + pv_ * G.ROWB + (((col >> 3) ^ fv(DA, pv_)) << 4) + (col & 7) * 2
+                        need(ad.min() >= st + G.KV and (ad + 8).max() <= st + 2 * G.KV, "V operand outside the V rows of its stage")
+                        got = lds.read(ad, 8, "V operand").view(np.uint16)
+                        if check_rows:
+                            cols = col[:, None] + np.arange(4)
+                            okp = pv_ < min(n - tile * TP, TP)
+                            need(np.array_equal(got[okp], ev[pv_[:, None], cols][okp]), f"tile {tile}: a V operand is not its position's columns")
+                            # within a group of sixteen lanes: four positions (lane / 4 within the group) by sixteen columns
+                            need(np.array_equal(np.unique(pv_.reshape(4, 16), axis=1).shape, (4, 4)), "a transposed read does not cover four positions")
+                sides = ()   # (the reads of the 32-query organisation below are not issued)
             if 0 in sides:
                 for kk in range(DA // 16):
                     lds.read(st + qn * G.ROWB + (((2 * kk + hh) ^ kx) << 4), 16, "K operand")
@@ -479,7 +527,50 @@ def run_item(DA, NW, QG, shape, item, buffers, check_rows=True, scores_ahead=Fal
             waves[w].wait(0)
 
     # ---- epilogue
-    for w in range(NW):
+    for w in range(NW if q16 else 0):
+        # lane: query lane % 16, columns 16 dt + 4 (lane / 16) + r of the kernel's order
+        written = np.zeros((16, DA), bool)
+        if item["part"] < 0:
+            for dt in range(4):
+                for r in range(0, 4, 2):
+                    ci = 16 * dt + 4 * g4 + r
+                    pc = np.where(ci < dgv, ci + duv, ci - dgv)
+                    lds.write(l16 * QS + pc * 2, np.zeros((64, 4), np.uint8), "output staging")
+                    written[l16, pc] = True
+                    written[l16, pc + 1] = True
+            need(written.all(), "the staged output rows have columns nobody wrote")
+            for i in range(16 * G.CH // 64):
+                e = i * 64 + lane
+                row, c = e // G.CH, e % G.CH
+                need(row.max() < 16, "copy-out past the sixteen staged rows")
+                v = lds.read(row * QS + c * 16, 16, "output staging")
+                ok = row < qrows[w]
+                if ok.any():
+                    g_out.write(qbyte0[w] + row[ok] * da * 2 + c[ok] * 16, v[ok] + 1, "output rows")
+        else:
+            need(buffers.get("partial") is not None, "a piece of a split history needs the workspace")
+            g_ws = Memory("partial", buffers["partial"])
+            QB = item["QB"]
+            need(QB == 16, "sixteen queries per work item")
+            ws0 = item["part"] * QB * (da + 2) * 4
+            FS = DA * 4 + 16
+            need(16 * FS <= G.NS * G.STAGE, "the staged accumulators must fit in the retired stages")
+            for dt in range(4):
+                for r in range(4):
+                    ci = 16 * dt + 4 * g4 + r
+                    pc = np.where(ci < dgv, ci + duv, ci - dgv)
+                    lds.write(l16 * FS + pc * 4, np.zeros((64, 4), np.uint8), "accumulator staging")
+                    written[l16, pc] = True
+            need(written.all(), "the staged accumulators have columns nobody wrote")
+            first = g4 == 0
+            g_ws.write(ws0 + (QB * da + l16[first]) * 4, np.ones((16, 4), np.uint8), "piece maximum")
+            g_ws.write(ws0 + (QB * da + QB + l16[first]) * 4, np.ones((16, 4), np.uint8), "piece sum")
+            for i in range(16 * (DA // 4) // 64):
+                e = i * 64 + lane
+                row, c = e // (DA // 4), e % (DA // 4)
+                v = lds.read(row * FS + c * 16, 16, "accumulator staging")
+                g_ws.write(ws0 + (row * da + c * 4) * 4, v + 1, "piece accumulators")
+    for w in range(0 if q16 else NW):
         if item["part"] < 0:
             qlds = w * QG * 32 * QS
             for g in range(QG):

@@ -36,16 +36,17 @@ def buffers_for(rng, DA, d_u, share, H, P, pool_ld, T, B, Nq, parts=0, QB=32):
     return shape, buf
 
 
-def run_case(DA, NW, QG, d_u, share=0, lengths=(33, 1, 100), pool_ld=None, Nq=None, seed=0, split=False, d_a=None, scores_ahead=False):
+def run_case(DA, NW, QG, d_u, share=0, lengths=(33, 1, 100), pool_ld=None, Nq=None, seed=0, split=False, d_a=None, scores_ahead=False,
+             q16=False):
     """d_a: the head's own width when it is narrower than the kernel's rows (DA).  scores_ahead: the tile loop that takes the
-    scores of a tile one iteration early."""
+    scores of a tile one iteration early.  q16: the organisation with sixteen queries per work item."""
     rng = np.random.default_rng(seed)
     d_a = DA if d_a is None else d_a
     d_g = d_a - d_u
     H, P, B = 2, 37, len(lengths)
     pool_ld = pool_ld if pool_ld is not None else ((d_g + 7) // 8 * 8 if d_g > 0 else 0)
     T = int(sum(lengths))
-    QB = 32 * NW * QG
+    QB = 16 if q16 else 32 * NW * QG
     Nq = Nq if Nq is not None else QB - 5            # the last wavefront has fewer than 32 query rows
     shape, buf = buffers_for(rng, d_a, d_u, share, H, P, pool_ld, T, B, Nq, parts=4 if split else 0, QB=QB)
     stats = None
@@ -58,7 +59,7 @@ def run_case(DA, NW, QG, d_u, share=0, lengths=(33, 1, 100), pool_ld=None, Nq=No
                 pieces = [(0, n, -1)]
             for lo, nn, part in pieces:
                 item = dict(b=b, h=h, q0=0, n=nn, t0=t0 + lo, part=part, QB=QB)
-                stats = dm.run_item(DA, NW, QG, shape, item, buf, scores_ahead=scores_ahead)
+                stats = dm.run_item(DA, NW, QG, shape, item, buf, scores_ahead=scores_ahead, q16=q16)
         t0 += n
     if not split:       # every byte of every output row was written (the model marks what it writes), nothing beyond
         assert (buf["out"].view(np.uint8) == 1).all()
@@ -126,6 +127,41 @@ def test_tile_loop_with_the_scores_one_tile_ahead(d_u):
         run_case(128, 4, 1, 4, pool_ld=128, Nq=3, seed=26, scores_ahead=True)
     with pytest.raises(dm.ModelError, match="no tile loop with the scores ahead"):
         run_case(128, 2, 1, d_u, scores_ahead=True)
+
+
+@pytest.mark.parametrize("d_u", [0, 2, 4, 6, 8])
+def test_sixteen_queries_per_work_item(d_u):
+    """The 64-column one-wavefront instance on the 16x16x32 matrix instruction: the same ring, other operand addresses (every
+    K operand must be its position's columns, every transposed V read its four positions by sixteen columns) and an epilogue
+    of sixteen rows; ragged ends, split pieces, one side shared, ordinary cache, unpadded pool rows, 1 to 16 queries."""
+    st = run_case(64, 1, 1, d_u, lengths=(33, 1, 100, 32, 64, 65, 0, 257), seed=30, q16=True)
+    assert st["UK"] == 0 and st["NS"] == 2
+    run_case(64, 1, 1, d_u, lengths=(31, 32, 257), seed=31, split=True, q16=True, Nq=16)
+    for Nq in (1, 7, 16):
+        run_case(64, 1, 1, d_u, lengths=(40,), seed=32 + Nq, q16=True, Nq=Nq)
+    if d_u == 4:
+        run_case(64, 1, 1, 4, share=1, lengths=(65, 3), seed=33, q16=True)
+        run_case(64, 1, 1, 4, share=2, lengths=(65, 3), seed=34, q16=True, split=True)
+        run_case(64, 1, 1, 64, lengths=(65, 3), seed=35, q16=True)
+        run_case(64, 1, 1, 8, pool_ld=56, seed=36, q16=True)
+        run_case(64, 1, 1, 4, pool_ld=72, Nq=3, seed=37, q16=True)
+    with pytest.raises(dm.ModelError, match="no sixteen-query organisation"):
+        run_case(64, 2, 1, d_u, q16=True)
+    with pytest.raises(dm.ModelError, match="no sixteen-query organisation"):
+        run_case(128, 1, 1, d_u, q16=True)
+
+
+def test_model_notices_a_wrong_operand_row_of_the_sixteen_query_organisation(monkeypatch):
+    # a swizzle that differs from the one the gathers wrote with: operands come from another chunk of the row
+    real = dm.fk
+    calls = {"n": 0}
+
+    def other(DA, p):
+        calls["n"] += 1
+        return real(DA, p) ^ (1 if calls["n"] % 7 == 0 else 0)
+    monkeypatch.setattr(dm, "fk", other)
+    with pytest.raises(dm.ModelError, match="differ from the final rows|not its position's columns"):
+        run_case(64, 1, 1, 4, lengths=(40,), q16=True)
 
 
 def test_outstanding_loads_of_every_geometry_fit_the_wait_counter():

@@ -243,6 +243,28 @@ def test_tile_loop_with_the_scores_one_tile_ahead(gpu, mode):
         np.testing.assert_array_equal(outs[0], outs[1])
 
 
+@pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
+def test_sixteen_queries_per_work_item(gpu, mode):
+    """64 columns, 3 to 16 queries: the organisation on the 16x16x32 matrix instruction (sixteen queries a work item) against
+    the oracle, and the organisation with 32 queries a work item, which it replaces there, as well: ragged lengths (one tile,
+    tile boundaries, empty), every even slice width, a split history, one side shared, an ordinary cache, unpadded pool rows."""
+    ckv, session = gpu
+    cases = [dict(lengths=MFMA_LENGTHS + (95, 97, 160), d_u=8, Nq=16), dict(lengths=MFMA_LENGTHS, d_u=0, Nq=3),
+             dict(lengths=MFMA_LENGTHS, d_u=2, Nq=9), dict(lengths=RAGGED, d_u=6, Nq=15),
+             dict(lengths=(9000, 70, 2300), d_u=2, Nq=16), dict(lengths=(5000, 1), d_u=8, Nq=5, share=wl.SHARE_V),
+             dict(lengths=MFMA_LENGTHS, d_u=4, Nq=12, share=wl.SHARE_K), dict(lengths=MFMA_LENGTHS, d_u=4, Nq=16, share=wl.SHARE_V),
+             dict(lengths=(65, 1, 640), d_u=64, Nq=16), dict(lengths=MFMA_LENGTHS, d_u=8, Nq=7, pool_ld=56)]
+    for c in cases:
+        kw = {k: c[k] for k in ("share", "pool_ld") if k in c}
+        w = make(c["lengths"], wl.BF16, mode, d_a=64, d_u=c["d_u"], H=2, P=700 if c["d_u"] < 64 else 1, Nq=c["Nq"], **kw)
+        for q16, expect in (("1", "mfma_dma_bf16_d64_w1_q16"), ("0", "mfma_dma_bf16_d64_w1_g1")):
+            ckv.ckv_set_option("dma_q16", q16)
+            try:
+                _run_and_check(ckv, session, w, f"sixteen queries = {q16}, d_u={c['d_u']} Nq={c['Nq']} mode={mode} {kw}", None, expect)
+            finally:
+                ckv.ckv_set_option(None)
+
+
 def test_mfma_unpadded_pool_rows(gpu):
     # pool_ld == d_g (a multiple of 8): the chunk that would be padding does not exist in memory
     w = make(MFMA_LENGTHS, wl.BF16, wl.SOFTMAX, d_a=64, d_u=8, H=2, P=333, Nq=16, pool_ld=56)
@@ -298,7 +320,7 @@ def test_fp32_256_column_heads_full(gpu):
 
 
 def test_config5_full(gpu):
-    run_and_check(gpu, wl.config("cfg5"), "cfg5", expect_variant="mfma_dma_bf16_d64_w1_g1")
+    run_and_check(gpu, wl.config("cfg5"), "cfg5", expect_variant="mfma_dma_bf16_d64_w1_q16")
 
 
 # ---------------------------------------------------------------------------------------------

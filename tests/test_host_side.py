@@ -78,7 +78,7 @@ def test_options_are_validated_and_steer_the_plan():
     from paper_2601_19178_amd import ckv
     for key, value in (("no_such_option", "1"), ("mfma_impl", "fastest"), ("dma_sched", "lazy"), ("dma_shape", "4"),
                        ("dma_shape", "0,1"), ("dma_slow_speed", "fast"), ("dma_slow_speed", "-1"), ("stream_impl", "wide"), ("stream_waves", "3"), ("stream_hot_rows", "33"), ("stream_hot_rows", "many"),
-                       ("dma_scores_ahead", "yes")):
+                       ("dma_scores_ahead", "yes"), ("dma_q16", "2")):
         with pytest.raises(ckv.CkvError) as e:
             ckv.ckv_set_option(key, value)
         assert e.value.code == ckv.CKV_ERR_UNSUPPORTED
@@ -93,6 +93,12 @@ def test_options_are_validated_and_steer_the_plan():
         ckv.ckv_set_option("dma_shape", "4,1")
         assert "_w4_g1" in ckv.ckv_plan(sh, lengths)[2]
         ckv.ckv_set_option("dma_shape", "")
+        few = ckv.make_shape(B=3, H=2, d_g=56, d_u=8, P=100, Nq=12, dtype=ckv.CKV_BF16, mode=0, scale=0.125, pool_ld=64)
+        assert "_w1_q16_" in ckv.ckv_plan(few, lengths)[2]
+        ckv.ckv_set_option("dma_q16", "0")
+        assert "_w1_g1_" in ckv.ckv_plan(few, lengths)[2]
+        ckv.ckv_set_option("dma_q16", None)
+        assert "_w1_q16_" in ckv.ckv_plan(few, lengths)[2]
         rec_static, nwg_static, _ = ckv.ckv_plan(sh, lengths)
         ckv.ckv_set_option("dma_sched", "dynamic")
         rec_dyn, nwg_dyn, _ = ckv.ckv_plan(sh, lengths)

@@ -123,7 +123,7 @@ def test_plan_rejects_bad_arguments():
 
 @pytest.mark.parametrize("d_a,d_u,Nq,dtype,expect", [
     # direct-to-LDS kernel: wavefronts and query groups by width and query count
-    (64, 4, 16, BF16, "mfma_dma_bf16_d64_w1_g1"), (64, 4, 64, BF16, "mfma_dma_bf16_d64_w1_g2"),
+    (64, 4, 16, BF16, "mfma_dma_bf16_d64_w1_q16"), (64, 4, 17, BF16, "mfma_dma_bf16_d64_w1_g1"), (64, 4, 64, BF16, "mfma_dma_bf16_d64_w1_g2"),
     (64, 4, 100, BF16, "mfma_dma_bf16_d64_w4_g1"), (64, 64, 64, BF16, "mfma_dma_bf16_d64_w2_g1"),  # ordinary cache: two wavefronts
     (128, 8, 32, BF16, "mfma_dma_bf16_d128_w1_g1"), (128, 8, 64, BF16, "mfma_dma_bf16_d128_w2_g1"),
     (128, 8, 128, BF16, "mfma_dma_bf16_d128_w4_g1"), (256, 4, 16, BF16, "mfma_dma_bf16_d256_w4_g1"),
