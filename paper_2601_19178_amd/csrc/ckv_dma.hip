@@ -682,6 +682,144 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
             weights_and_output(std::false_type{}, s_cur, ka, va, n - (ntiles - 1) * TP);
             back(ntiles - 1);
         };
+        // The loop with the scores one tile ahead for 256 columns, where a SIMD holds one wavefront and nothing else hides its
+        // vector work: the same schedule of loads, waits and publication as tile_loop_ahead.  Sixteen K operands and sixteen
+        // V^T operands per tile do not fit in registers beside the queries, so the K operands of tile t + 1 come through the
+        // window of eight that tile_loop uses, under the exponentials of tile t, and the V^T operands of tile t in two halves.
+        auto tile_loop_ahead_wide = [&](auto nui_c, auto both_c) {
+            constexpr int NUI = decltype(nui_c)::value;
+            constexpr int NS = G::NS;
+            constexpr int LPI = 2 * G::NI + 1 + NUI;
+            static_assert(QG == 1 && NS == 4, "built for one query group on the four-stage ring");
+            int rk[G::NI], rv[G::NI];
+            gather_rows(both_c, 0, rk, rv);
+            auto front = [&](int t) {
+                issue_idx(t + NS + 2);
+#pragma unroll
+                for (int s = 0; s < 2 * G::NI + NUI; ++s) tile_dma(t + NS - 1, s, rk, rv);
+            };
+            auto back = [&](int t) {
+                __builtin_amdgcn_sched_barrier(0);
+                wait_vm<(NS - 3) * LPI>();
+                if (NUI > 0 && t + 2 >= 0 && t + 2 < ntiles) concat(nui_c, t + 2);
+                gather_rows(both_c, t + NS, rk, rv);
+                lds_barrier();
+            };
+            auto read_k = [&](int tile, int first, int count, bf16x8 (&ka)[NKK]) {
+                const uint32_t st = lds0 + (tile & (NS - 1)) * G::STAGE;
+#pragma unroll
+                for (int kk = first; kk < first + count; ++kk) ka[kk] = *(const lds_bf16x8*)(uintptr_t)(st + krow + (((2 * kk + hh) ^ kx) << 4));
+            };
+            auto scores = [&](int tile, f32x16& sn) {
+                bf16x8 ka[NKK];
+                read_k(tile, 0, NKK, ka);
+#pragma unroll
+                for (int kk = 0; kk < NKK; ++kk) sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk], qreg[0][kk], sn, 0, 0, 0);
+            };
+            auto load_v = [&](int tile, int ks, bf16x8 (&va)[NDT]) {
+                const uint32_t st = lds0 + (tile & (NS - 1)) * G::STAGE;
+#pragma unroll
+                for (int dt = 0; dt < NDT; ++dt) {
+                    const uint32_t ad = st + vrow + (16 * ks) * G::ROWB + (((4 * dt + vc) ^ vx) << 4);
+                    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(uintptr_t)ad);
+                    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(uintptr_t)(ad + 8 * G::ROWB));
+                    va[dt] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                }
+            };
+            // Weights and output of tile t from its scores s; kNext: the sixteen score MFMAs of tile t + 1 go one in front of
+            // each of the sixteen weights of a lane, in program order (a scheduling fence after every pair keeps them there:
+            // a wavefront issues in order, so what is to run under a matrix instruction has to follow it directly).
+            static_assert(NKK == 16, "one score MFMA per weight of a lane");
+            auto step = [&](auto next_c, f32x16& s, int t, int nt) {
+                constexpr bool kNext = decltype(next_c)::value;
+                bf16x8 pb[2], va0[NDT], va1[NDT], ka[NKK];
+                f32x16 sn;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sn[r] = 0.f;
+                load_v(t, 0, va0);
+                if (kNext) read_k(t + 1, 0, 8, ka);
+                __builtin_amdgcn_sched_barrier(0);
+                float psum = 0.f;
+                if (MODE == CKV_SOFTMAX) {
+                    if (!kNext && nt < TP) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) s[r] = mask_tail(s[r], 8 * (r >> 2) + 4 * hh + (r & 3) >= nt, -INFINITY);
+                    }
+                    float tmax = s[0];
+#pragma unroll
+                    for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, s[r]);
+                    tmax = fmaxf(tmax, other_half(tmax)) * sc;
+                    if (__any(tmax > m_ref[0] + kLazy)) {
+                        const float m_new = fmaxf(m_ref[0], tmax);
+                        const float alpha = __builtin_amdgcn_exp2f(m_ref[0] - m_new);
+                        lsum[0] *= alpha;
+#pragma unroll
+                        for (int dt = 0; dt < NDT; ++dt) {
+                            if (kAccInAgprs) asm volatile("" : "+a"(oacc[0][dt]));
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) oacc[0][dt][r] *= alpha;
+                            if (kAccInAgprs) asm volatile("" : "+a"(oacc[0][dt]));
+                        }
+                        m_ref[0] = m_new;
+                    }
+                } else if (!kNext && nt < TP) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) s[r] = mask_tail(s[r], 8 * (r >> 2) + 4 * hh + (r & 3) >= nt, 0.f);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                // (values in flight between two MFMAs are tied to an empty asm statement: the compiler orders pure arithmetic
+                // freely otherwise and had put all sixteen MFMAs in front of all the weights)
+                float pprev = 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    float sr = s[r];
+                    if (kNext) {
+                        // the window of eight K operands is refilled four at a time, four MFMAs ahead of their use
+                        if (r == 4) read_k(t + 1, 8, 4, ka);
+                        if (r == 8) read_k(t + 1, 12, 4, ka);
+                        asm volatile("" : "+v"(sr), "+v"(ka[r]), "+v"(pprev));
+                        sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[r], qreg[0][r], sn, 0, 0, 0);
+                    }
+                    if (r > 0) {
+                        if (MODE == CKV_SOFTMAX) psum += pprev;
+                        pb[(r - 1) >> 3][(r - 1) & 7] = (__bf16)pprev;
+                    }
+                    if (MODE == CKV_SOFTMAX) {
+                        pprev = __builtin_amdgcn_exp2f(fmaf(sr, sc, -m_ref[0]));
+                    } else {
+                        const float e = __builtin_amdgcn_exp2f(sr * nsc);
+                        pprev = (sr * sc) * __builtin_amdgcn_rcpf(1.f + e);
+                    }
+                }
+                if (MODE == CKV_SOFTMAX) psum += pprev;
+                pb[1][7] = (__bf16)pprev;
+                if (MODE == CKV_SOFTMAX) lsum[0] += psum;
+                load_v(t, 1, va1);
+#pragma unroll
+                for (int dt = 0; dt < NDT; ++dt) oacc[0][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va0[dt], pb[0], oacc[0][dt], 0, 0, 0);
+#pragma unroll
+                for (int dt = 0; dt < NDT; ++dt) oacc[0][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va1[dt], pb[1], oacc[0][dt], 0, 0, 0);
+                if (kNext) s = sn;
+            };
+            f32x16 s_cur;
+            front(-(NS - 1));
+            back(-(NS - 1));
+            front(-(NS - 2));
+            back(-(NS - 2));  // publishes tile 0
+            front(-1);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s_cur[r] = 0.f;
+            scores(0, s_cur);
+            back(-1);
+            for (int t = 0; t < ntiles - 1; ++t) {
+                front(t);
+                step(std::true_type{}, s_cur, t, TP);
+                back(t);
+            }
+            front(ntiles - 1);
+            step(std::false_type{}, s_cur, ntiles - 1, n - (ntiles - 1) * TP);
+            back(ntiles - 1);
+        };
         // Sixteen queries: the same ring, waits and publication as tile_loop; a tile is two score blocks of sixteen positions.
         // Row m of score block b is tile position 8 (m / 4) + 4 b + m % 4, so that a lane ends up with the weights of the
         // eight consecutive positions 8 (lane / 16) .. + 8, which is what the B operand of the output instruction wants.
@@ -787,7 +925,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
                 lds_barrier();
             }
         };
-        constexpr bool kScoresAhead = DA == 128 && NW == 4 && QG == 1 && UK == 0;
+        constexpr bool kScoresAhead = (DA == 128 && NW == 4 && QG == 1 && UK == 0) || (DA == 256 && UK == 0);
         auto with_nui = [&](auto nui_c) {
             if constexpr (Q16) {
                 if (ksh && vsh) tile_loop_q16(nui_c, std::true_type{});
@@ -796,8 +934,13 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
             }
             if constexpr (kScoresAhead) {
                 if (a.scores_ahead) {
-                    if (ksh && vsh) tile_loop_ahead(nui_c, std::true_type{});
-                    else tile_loop_ahead(nui_c, std::false_type{});
+                    if constexpr (kWide) {
+                        if (ksh && vsh) tile_loop_ahead_wide(nui_c, std::true_type{});
+                        else tile_loop_ahead_wide(nui_c, std::false_type{});
+                    } else {
+                        if (ksh && vsh) tile_loop_ahead(nui_c, std::true_type{});
+                        else tile_loop_ahead(nui_c, std::false_type{});
+                    }
                     return;
                 }
             }

@@ -133,7 +133,7 @@ class Wave:
 
 def scores_ahead_supported(DA, NW, QG, UK):
     """The instantiations whose tile loop exists with the scores one tile ahead."""
-    return DA == 128 and NW == 4 and QG == 1 and UK == 0
+    return (DA == 128 and NW == 4 and QG == 1 and UK == 0) or (DA == 256 and UK == 0)
 
 
 def q16_supported(DA, NW, QG, UK, d_u, d_g):
@@ -467,7 +467,7 @@ def run_item(DA, NW, QG, shape, item, buffers, check_rows=True, scores_ahead=Fal
         need(not scores_ahead or scores_ahead_supported(DA, NW, QG, UK), "this instantiation has no tile loop with the scores ahead")
         for w in range(NW):
             waves[w].wait(0)                       # wait_vm<0>: the first indices
-        rows = [gather_rows(w, 0) if kAhead else None for w in range(NW)]
+        rows = [gather_rows(w, 0) if (kAhead or scores_ahead) else None for w in range(NW)]   # (the loops with the scores ahead look rows up one iteration early at every width)
         for t in (range(-(NS - 1), ntiles) if scores_ahead else ()):
             # iteration t: this iteration's loads; K operands of tile t + 1 and V operands of tile t; the wait that lets only
             # this iteration's loads stay outstanding; concat and publication of tile t + 2

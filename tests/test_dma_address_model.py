@@ -111,20 +111,26 @@ def test_unpadded_and_overpadded_pool_rows(DA, NW, QG):
     run_case(DA, NW, QG, 4, pool_ld=DA, Nq=3, seed=12)           # three queries: most staging rows are zeros
 
 
+@pytest.mark.parametrize("DA", [128, 256])
 @pytest.mark.parametrize("d_u", [0, 2, 4, 8])
-def test_tile_loop_with_the_scores_one_tile_ahead(d_u):
-    """The loop of the four-wavefront 128-column instance that publishes a tile one iteration earlier (K operands of tile
-    t + 1 are read in the iteration that finishes tile t): histories of one tile, of a few, ragged ends, split pieces,
+def test_tile_loop_with_the_scores_one_tile_ahead(DA, d_u):
+    """The loop of the four-wavefront 128- and 256-column instances that publishes a tile one iteration earlier (K operands of
+    tile t + 1 are read in the iteration that finishes tile t): histories of one tile, of a few, ragged ends, split pieces,
     one side shared, ordinary cache, unpadded pool rows."""
-    st = run_case(128, 4, 1, d_u, lengths=(33, 1, 100, 32, 64, 65, 0, 257), seed=20, scores_ahead=True)
-    assert st["UK"] == 0 and st["peak_outstanding"] <= 2 * (2 * 2 + 1 + 1)     # two iterations of loads at most
-    run_case(128, 4, 1, d_u, lengths=(31, 32, 257), seed=21, split=True, scores_ahead=True)
+    st = run_case(DA, 4, 1, d_u, lengths=(33, 1, 100, 32, 64, 65, 0, 257), seed=20, scores_ahead=True)
+    ni = 32 // (64 // (DA // 8)) // 4
+    assert st["UK"] == 0 and st["peak_outstanding"] <= 2 * (2 * ni + 1 + 1)     # two iterations of loads at most
+    run_case(DA, 4, 1, d_u, lengths=(31, 32, 257), seed=21, split=True, scores_ahead=True)
     if d_u == 4:
-        run_case(128, 4, 1, 4, share=1, lengths=(65, 3), seed=22, scores_ahead=True)
-        run_case(128, 4, 1, 4, share=2, lengths=(65, 3), seed=23, scores_ahead=True)
-        run_case(128, 4, 1, 128, lengths=(65, 3), seed=24, scores_ahead=True)
-        run_case(128, 4, 1, 8, pool_ld=120, seed=25, scores_ahead=True)
-        run_case(128, 4, 1, 4, pool_ld=128, Nq=3, seed=26, scores_ahead=True)
+        run_case(DA, 4, 1, 4, share=1, lengths=(65, 3), seed=22, scores_ahead=True)
+        run_case(DA, 4, 1, 4, share=2, lengths=(65, 3), seed=23, scores_ahead=True)
+        run_case(DA, 4, 1, DA, lengths=(65, 3), seed=24, scores_ahead=True)
+        run_case(DA, 4, 1, 8, pool_ld=DA - 8, seed=25, scores_ahead=True)
+        run_case(DA, 4, 1, 4, pool_ld=DA, Nq=3, seed=26, scores_ahead=True)
+    if DA == 256:
+        for wide in (10, 16, 24, 32):          # slices of up to 32 columns: up to four slice loads per wavefront and tile
+            st = run_case(256, 4, 1, wide, lengths=(33, 100, 257), seed=27, scores_ahead=True)
+            assert st["peak_outstanding"] <= 2 * (2 * ni + 1 + 4)
     with pytest.raises(dm.ModelError, match="no tile loop with the scores ahead"):
         run_case(128, 2, 1, d_u, scores_ahead=True)
 

@@ -220,24 +220,29 @@ def test_mfma_split_history(gpu, impl, mode):
     run_and_check(gpu, w, f"mfma split mode={mode} impl={impl}", expect_variant="mfma", impl=impl)
 
 
+@pytest.mark.parametrize("d_a", [128, 256])
 @pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
-def test_tile_loop_with_the_scores_one_tile_ahead(gpu, mode):
-    """Four wavefronts at 128 columns: the loop that takes the scores of tile t + 1 in the iteration that finishes tile t and
-    the loop that does not must agree bit for bit (the same arithmetic in the same order) and with the oracle: ragged
-    lengths (one tile, tile boundaries, empty), a split history, one side shared, an ordinary cache."""
+def test_tile_loop_with_the_scores_one_tile_ahead(gpu, mode, d_a):
+    """Four wavefronts at 128 and at 256 columns: the loop that takes the scores of tile t + 1 in the iteration that finishes
+    tile t and the loop that does not must agree bit for bit (the same arithmetic in the same order) and with the oracle:
+    ragged lengths (one tile, tile boundaries, empty), a split history, one side shared, an ordinary cache; at 256 columns
+    also few queries (wavefronts without any) and slices of 10 and 32 columns."""
     ckv, session = gpu
     cases = [dict(lengths=MFMA_LENGTHS + (95, 97, 160), d_u=8, Nq=128), dict(lengths=MFMA_LENGTHS, d_u=0, Nq=100),
              dict(lengths=(5000, 70, 2300), d_u=8, Nq=128), dict(lengths=MFMA_LENGTHS, d_u=4, Nq=65, share=wl.SHARE_K),
-             dict(lengths=MFMA_LENGTHS, d_u=4, Nq=128, share=wl.SHARE_V), dict(lengths=(65, 1, 640), d_u=128, Nq=128)]
+             dict(lengths=MFMA_LENGTHS, d_u=4, Nq=128, share=wl.SHARE_V), dict(lengths=(65, 1, 640), d_u=d_a, Nq=128)]
+    if d_a == 256:
+        cases += [dict(lengths=MFMA_LENGTHS, d_u=10, Nq=40), dict(lengths=(3000, 33, 64), d_u=32, Nq=130),
+                  dict(lengths=RAGGED, d_u=2, Nq=3)]
     for c in cases:
-        w = make(c["lengths"], wl.BF16, mode, d_a=128, d_u=c["d_u"], H=2, P=700 if c["d_u"] < 128 else 1, Nq=c["Nq"],
+        w = make(c["lengths"], wl.BF16, mode, d_a=d_a, d_u=c["d_u"], H=2, P=700 if c["d_u"] < d_a else 1, Nq=c["Nq"],
                  share=c.get("share", wl.SHARE_KV))
         outs = []
         for ahead in ("0", "1"):
             ckv.ckv_set_option("dma_scores_ahead", ahead)
             try:
-                outs.append(_run_and_check(ckv, session, w, f"scores ahead = {ahead}, d_u={c['d_u']} Nq={c['Nq']} mode={mode}", None,
-                                           "mfma_dma_bf16_d128_w4_g1"))
+                outs.append(_run_and_check(ckv, session, w, f"scores ahead = {ahead}, d_a={d_a} d_u={c['d_u']} Nq={c['Nq']} mode={mode}", None,
+                                           f"mfma_dma_bf16_d{d_a}_w4_g1"))
             finally:
                 ckv.ckv_set_option(None)
         np.testing.assert_array_equal(outs[0], outs[1])
