@@ -820,9 +820,10 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
             step(std::false_type{}, s_cur, ntiles - 1, n - (ntiles - 1) * TP);
             back(ntiles - 1);
         };
-        // Sixteen queries: the same ring, waits and publication as tile_loop; a tile is two score blocks of sixteen positions.
-        // Row m of score block b is tile position 8 (m / 4) + 4 b + m % 4, so that a lane ends up with the weights of the
-        // eight consecutive positions 8 (lane / 16) .. + 8, which is what the B operand of the output instruction wants.
+        // Sixteen queries: the same ring, waits and publication as tile_loop; a tile is two score blocks of sixteen consecutive
+        // positions (sixteen consecutive rows per K operand read: no LDS bank conflicts).  A lane ends up with the scores of
+        // positions 16 b + 4 (lane / 16) + r (b = 0, 1; r = 0..3); the output instruction, 32 positions deep, takes them as its
+        // k indices 8 (lane / 16) + 4 b + r, and the V^T operand is read in that order of positions.
         auto tile_loop_q16 = [&](auto nui_c, auto both_c) {
             constexpr int NUI = decltype(nui_c)::value;
             constexpr int NS = G::NS;
@@ -833,17 +834,17 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
             uint32_t kad[2][2];
 #pragma unroll
             for (int b = 0; b < 2; ++b) {
-                const int p = 8 * (q16 >> 2) + 4 * b + (q16 & 3);
+                const int p = 16 * b + q16;
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) kad[b][ks] = p * G::ROWB + (((4 * ks + g4) ^ fk<DA>(p)) << 4);
             }
-            const int vp = 8 * g4 + (q16 >> 2);  // position row of the lane's transposed read (and that + 4)
+            const int vp = 4 * g4 + (q16 >> 2);  // position row of the lane's transposed read (and that + 16)
             uint32_t vad[2][4];
 #pragma unroll
             for (int hl = 0; hl < 2; ++hl)
 #pragma unroll
                 for (int dt = 0; dt < 4; ++dt) {
-                    const int p = vp + 4 * hl, col = 16 * dt + 4 * (q16 & 3);
+                    const int p = vp + 16 * hl, col = 16 * dt + 4 * (q16 & 3);
                     vad[hl][dt] = G::KV + p * G::ROWB + (((col >> 3) ^ fv<DA>(p)) << 4) + (col & 7) * 2;
                 }
             for (int t = -(NS - 1); t < ntiles; ++t) {
@@ -872,7 +873,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
 #pragma unroll
                         for (int ks = 0; ks < 2; ++ks) sb[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[b][ks], qreg[0][ks], sb[b], 0, 0, 0);
                     }
-                    // the lane's eight scores, positions 8 (lane / 16) + i of the tile
+                    // the lane's eight scores, positions 16 (i / 4) + 4 (lane / 16) + i % 4 of the tile
                     float sv[8];
 #pragma unroll
                     for (int i = 0; i < 8; ++i) sv[i] = sb[i >> 2][i & 3];
@@ -880,7 +881,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
                     if (MODE == CKV_SOFTMAX) {
                         if (nt < TP) {
 #pragma unroll
-                            for (int i = 0; i < 8; ++i) sv[i] = mask_tail(sv[i], 8 * g4 + i >= nt, -INFINITY);
+                            for (int i = 0; i < 8; ++i) sv[i] = mask_tail(sv[i], 16 * (i >> 2) + 4 * g4 + (i & 3) >= nt, -INFINITY);
                         }
                         float tmax = sv[0];
 #pragma unroll
@@ -908,7 +909,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
                     } else {
                         if (nt < TP) {
 #pragma unroll
-                            for (int i = 0; i < 8; ++i) sv[i] = mask_tail(sv[i], 8 * g4 + i >= nt, 0.f);
+                            for (int i = 0; i < 8; ++i) sv[i] = mask_tail(sv[i], 16 * (i >> 2) + 4 * g4 + (i & 3) >= nt, 0.f);
                         }
 #pragma unroll
                         for (int i = 0; i < 8; ++i) {

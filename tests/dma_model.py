@@ -402,21 +402,24 @@ def run_item(DA, NW, QG, shape, item, buffers, check_rows=True, scores_ahead=Fal
             vrow = G.KV + (4 * hh + (s16 >> 2)) * G.ROWB + (s16 & 1) * 8
             vc, vx = 2 * (g16 & 1) + ((s16 & 3) >> 1), fv(DA, s16 >> 2)
             if q16:
-                # A operand of score block b: row m = lane % 16 is tile position 8 (m / 4) + 4 b + m % 4, columns
-                # 32 ks + 8 (lane / 16) .. + 8; the lane's four results of block b are then positions 8 (lane / 16) + 4 b + r.
-                # A operand of the output blocks: a group of sixteen lanes fetches positions 8 (lane / 16) + 4 hl .. + 4 by
+                # A operand of score block b: row m = lane % 16 is tile position 16 b + m, columns 32 ks + 8 (lane / 16) .. + 8;
+                # the lane's four results of block b are then positions 16 b + 4 (lane / 16) + r.
+                # A operand of the output blocks: a group of sixteen lanes fetches positions 16 hl + 4 (lane / 16) .. + 4 by
                 # columns 16 dt .. + 16, four columns a lane, and the transposing read hands lane m column 16 dt + m.
                 ek, ev = expected_rows(tile)
                 for b in range(2):
-                    pk_ = 8 * (l16 >> 2) + 4 * b + (l16 & 3)
+                    pk_ = 16 * b + l16
                     for ks in range(2):
-                        got = lds.read(st + pk_ * G.ROWB + (((4 * ks + g4) ^ fk(DA, pk_)) << 4), 16, "K operand").view(np.uint16)
+                        kaddr = st + pk_ * G.ROWB + (((4 * ks + g4) ^ fk(DA, pk_)) << 4)
+                        for grp in range(4):        # sixteen lanes are served together: sixteen different 16-byte slots modulo 16
+                            need(len(set(((kaddr[16 * grp:16 * grp + 16] >> 4) & 15).tolist())) == 16, "K operand reads of a lane group share LDS banks")
+                        got = lds.read(kaddr, 16, "K operand").view(np.uint16)
                         if check_rows:
                             cols = 32 * ks + 8 * g4[:, None] + np.arange(8)
                             okp = pk_ < min(n - tile * TP, TP)
                             need(np.array_equal(got[okp], ek[pk_[:, None], cols][okp]), f"tile {tile}: a K operand is not its position's columns")
                 for hl in range(2):
-                    pv_ = 8 * g4 + (l16 >> 2) + 4 * hl
+                    pv_ = 4 * g4 + (l16 >> 2) + 16 * hl
                     for dt in range(4):
                         col = 16 * dt + 4 * (l16 & 3)
                         ad = st + G.KV + pv_ * G.ROWB + (((col >> 3) ^ fv(DA, pv_)) << 4) + (col & 7) * 2
