@@ -31,7 +31,7 @@ def split_workspace_bytes(ckv, s, w):
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     variant = ckv.ckv_variant(s.cache)
     m = re.search(r"_w(\d)_g(\d)", variant)
-    qb = 32 * int(m.group(1)) * int(m.group(2)) if variant.startswith("mfma_dma") else (
+    qb = 16 if "_q16_" in variant else 32 * int(m.group(1)) * int(m.group(2)) if variant.startswith("mfma_dma") else (
         32 * int(re.search(r"_w(\d)", variant).group(1)) if variant.startswith("mfma_bf16") else (128 if variant.startswith("mfma_f32") else w["Nq"]))
     least = None
     for wg in (1, 2, 3, 4, 8):   # the resident workgroups per compute unit are the kernel's; take the smallest plan
@@ -41,7 +41,7 @@ def split_workspace_bytes(ckv, s, w):
     return least * qb * (w["d_g"] + w["d_u"] + 2) * 4
 
 
-@pytest.mark.parametrize("kind", ["dma", "staged", "fp32", "stream", "streamw"])
+@pytest.mark.parametrize("kind", ["dma", "dma16", "staged", "fp32", "stream", "streamw"])
 def test_static_scratch_entry_point_matches_ckv_attend(kind):
     import torch
     assert torch.cuda.is_available(), "these tests need the MI355X"
@@ -49,6 +49,9 @@ def test_static_scratch_entry_point_matches_ckv_attend(kind):
     if kind == "dma":       # direct-to-LDS matrix-core kernel: long histories among short ones are cut and merged
         first = make((5000, 70, 2300, 1024, 1025), wl.BF16, wl.SOFTMAX, d_a=128, d_u=8, H=2, P=5000, Nq=128)
         second = make((3000, 31), wl.BF16, wl.SILU_OVER_N, d_a=64, d_u=4, H=1, P=700, Nq=64)
+    elif kind == "dma16":   # the same kernel's organisation with sixteen queries per work item (pieces of sixteen query rows)
+        first = make((9000, 70, 2300, 1025), wl.BF16, wl.SOFTMAX, d_a=64, d_u=8, H=2, P=5000, Nq=16)
+        second = make((3000, 31), wl.BF16, wl.SILU_OVER_N, d_a=64, d_u=2, H=1, P=700, Nq=5)
     elif kind == "staged":  # register-staged matrix-core kernel
         first = make((5000, 70, 2300), wl.BF16, wl.SOFTMAX, d_a=128, d_u=24, H=2, P=5000, Nq=64)
         second = make((2000, 1), wl.BF16, wl.SOFTMAX, d_a=64, d_u=24, H=1, P=300, Nq=16)
