@@ -705,6 +705,34 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
                 gather_rows(both_c, t + NS, rk, rv);
                 lds_barrier();
             };
+            // The same in two parts around the output MFMAs of a tile, whose matrix time then covers the LDS round trips
+            // (slice staging -> registers, index slots -> registers) that back() waits out: the wait for the wavefront's loads
+            // of tile t + 2, the staged slices and the row lookup in front of the MFMAs, the row tails and the barrier behind.
+            // (measured: softmax weights -3 to -6 %, SiLU weights +1 %, which therefore keep back())
+            constexpr bool kSplitBack = MODE == CKV_SOFTMAX;
+            static_assert(!uodd, "slices in whole dwords");
+            uint32_t cx[G::NUI_MAX];
+            auto back_first = [&](int t) {
+                __builtin_amdgcn_sched_barrier(0);
+                wait_vm<(NS - 3) * LPI>();
+                if (NUI > 0 && t + 2 < ntiles) {
+                    const uint32_t st = lds0 + ((t + 2) & (NS - 1)) * G::STAGE;
+#pragma unroll
+                    for (int u = 0; u < NUI; ++u) cx[u] = *(const lds_u32*)(uintptr_t)(st + 2 * G::KV + (wave * G::NUI_MAX + u) * 256 + lane * 4);
+                }
+                gather_rows(both_c, t + NS, rk, rv);
+                asm volatile("" ::: "memory");  // (the requests stay in front of the MFMAs)
+            };
+            auto back_second = [&](int t) {
+                asm volatile("" ::: "memory");
+                if (NUI > 0 && t + 2 < ntiles) {
+                    const uint32_t st = lds0 + ((t + 2) & (NS - 1)) * G::STAGE;
+#pragma unroll
+                    for (int u = 0; u < NUI; ++u)
+                        if (uok[u]) *(lds_u32*)(uintptr_t)(st + cdst[u]) = cx[u];
+                }
+                lds_barrier();
+            };
             auto read_k = [&](int tile, int first, int count, bf16x8 (&ka)[NKK]) {
                 const uint32_t st = lds0 + (tile & (NS - 1)) * G::STAGE;
 #pragma unroll
@@ -777,8 +805,19 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
                         // the window of eight K operands is refilled four at a time, four MFMAs ahead of their use
                         if (r == 4) read_k(t + 1, 8, 4, ka);
                         if (r == 8) read_k(t + 1, 12, 4, ka);
-                        asm volatile("" : "+v"(sr), "+v"(ka[r]), "+v"(pprev));
+                        // (the operands are tied group by group, as they were requested: one wait for LDS per group, not per MFMA)
+                        if (r == 0) asm volatile("" : "+v"(ka[0]), "+v"(ka[1]), "+v"(ka[2]), "+v"(ka[3]), "+v"(ka[4]), "+v"(ka[5]), "+v"(ka[6]), "+v"(ka[7]));
+                        if (r == 8) asm volatile("" : "+v"(ka[8]), "+v"(ka[9]), "+v"(ka[10]), "+v"(ka[11]));
+                        if (r == 12) asm volatile("" : "+v"(ka[12]), "+v"(ka[13]), "+v"(ka[14]), "+v"(ka[15]));
+                        asm volatile("" : "+v"(sr), "+v"(pprev));
                         sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[r], qreg[0][r], sn, 0, 0, 0);
+                    }
+                    if (r == 12) {
+                        // the second half of the V^T operands, requested here (into the registers the first K operands have
+                        // left) so that they have arrived when the first half's MFMAs are through; the fences keep the requests here
+                        asm volatile("" ::: "memory");
+                        load_v(t, 1, va1);
+                        asm volatile("" ::: "memory");
                     }
                     if (r > 0) {
                         if (MODE == CKV_SOFTMAX) psum += pprev;
@@ -794,12 +833,13 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
                 if (MODE == CKV_SOFTMAX) psum += pprev;
                 pb[1][7] = (__bf16)pprev;
                 if (MODE == CKV_SOFTMAX) lsum[0] += psum;
-                load_v(t, 1, va1);
+                if (kSplitBack) back_first(t);
 #pragma unroll
                 for (int dt = 0; dt < NDT; ++dt) oacc[0][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va0[dt], pb[0], oacc[0][dt], 0, 0, 0);
 #pragma unroll
                 for (int dt = 0; dt < NDT; ++dt) oacc[0][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va1[dt], pb[1], oacc[0][dt], 0, 0, 0);
                 if (kNext) s = sn;
+                if (kSplitBack) back_second(t);
             };
             f32x16 s_cur;
             front(-(NS - 1));
@@ -813,12 +853,12 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
             back(-1);
             for (int t = 0; t < ntiles - 1; ++t) {
                 front(t);
-                step(std::true_type{}, s_cur, t, TP);
-                back(t);
+                step(std::true_type{}, s_cur, t, TP);  // (kSplitBack: with both parts of back(t))
+                if (!kSplitBack) back(t);
             }
             front(ntiles - 1);
             step(std::false_type{}, s_cur, ntiles - 1, n - (ntiles - 1) * TP);
-            back(ntiles - 1);
+            if (!kSplitBack) back(ntiles - 1);
         };
         // Sixteen queries: the same ring, waits and publication as tile_loop; a tile is two score blocks of sixteen consecutive
         // positions (sixteen consecutive rows per K operand read: no LDS bank conflicts).  A lane ends up with the scores of
