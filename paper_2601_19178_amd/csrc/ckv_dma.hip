@@ -836,6 +836,26 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
                 if (kSplitBack) back_first(t);
 #pragma unroll
                 for (int dt = 0; dt < NDT; ++dt) oacc[0][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va0[dt], pb[0], oacc[0][dt], 0, 0, 0);
+                if (kSplitBack && kNext) {
+                    // The barrier, then the loads of the next iteration with the second half of the output MFMAs between
+                    // them, one behind each load (its operand tied to an asm statement there): issuing a tile's loads takes
+                    // a wavefront as long as eight MFMAs take the matrix pipe.
+                    static_assert(2 * G::NI >= NDT, "a load in front of every MFMA of the second half");
+                    __builtin_amdgcn_sched_barrier(0);  // (the first half stays in front of the barrier, over the LDS round trips)
+                    back_second(t);
+                    issue_idx(t + 1 + NS + 2);
+#pragma unroll
+                    for (int i = 0; i < 2 * G::NI + NUI; ++i) {
+                        tile_dma(t + NS, i, rk, rv);
+                        if (i < NDT) {
+                            asm volatile("" : "+v"(va1[i]));
+                            oacc[0][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va1[i], pb[1], oacc[0][i], 0, 0, 0);
+                            __builtin_amdgcn_sched_barrier(0);  // (or the scheduler gathers the MFMAs behind the last load)
+                        }
+                    }
+                    s = sn;
+                    return;
+                }
 #pragma unroll
                 for (int dt = 0; dt < NDT; ++dt) oacc[0][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va1[dt], pb[1], oacc[0][dt], 0, 0, 0);
                 if (kNext) s = sn;
@@ -851,14 +871,21 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
             for (int r = 0; r < 16; ++r) s_cur[r] = 0.f;
             scores(0, s_cur);
             back(-1);
-            for (int t = 0; t < ntiles - 1; ++t) {
-                front(t);
-                step(std::true_type{}, s_cur, t, TP);  // (kSplitBack: with both parts of back(t))
-                if (!kSplitBack) back(t);
+            if (kSplitBack) {
+                // (a step ends with both parts of back(t) and with the loads that front(t + 1) issues)
+                front(0);
+                for (int t = 0; t < ntiles - 1; ++t) step(std::true_type{}, s_cur, t, TP);
+                step(std::false_type{}, s_cur, ntiles - 1, n - (ntiles - 1) * TP);
+            } else {
+                for (int t = 0; t < ntiles - 1; ++t) {
+                    front(t);
+                    step(std::true_type{}, s_cur, t, TP);
+                    back(t);
+                }
+                front(ntiles - 1);
+                step(std::false_type{}, s_cur, ntiles - 1, n - (ntiles - 1) * TP);
+                back(ntiles - 1);
             }
-            front(ntiles - 1);
-            step(std::false_type{}, s_cur, ntiles - 1, n - (ntiles - 1) * TP);
-            if (!kSplitBack) back(ntiles - 1);
         };
         // Sixteen queries: the same ring, waits and publication as tile_loop; a tile is two score blocks of sixteen consecutive
         // positions (sixteen consecutive rows per K operand read: no LDS bank conflicts).  A lane ends up with the scores of
