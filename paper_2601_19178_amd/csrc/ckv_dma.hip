@@ -708,8 +708,9 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
             // The same in two parts around the output MFMAs of a tile, whose matrix time then covers the LDS round trips
             // (slice staging -> registers, index slots -> registers) that back() waits out: the wait for the wavefront's loads
             // of tile t + 2, the staged slices and the row lookup in front of the MFMAs, the row tails and the barrier behind.
-            // (measured: softmax weights -3 to -6 %, SiLU weights +1 %, which therefore keep back())
-            constexpr bool kSplitBack = MODE == CKV_SOFTMAX;
+            // (measured: softmax weights -3 to -6 %; SiLU weights +1 % by itself and -2 % together with the loads that a step
+            // then issues between its last MFMAs)
+            constexpr bool kSplitBack = true;
             static_assert(!uodd, "slices in whole dwords");
             uint32_t cx[G::NUI_MAX];
             auto back_first = [&](int t) {
