@@ -306,7 +306,7 @@ int ckv_remap_hot_rows(ckv_cache* cache, const void* pool_k, const void* pool_v,
  *   "dma_q16"         "0" | "1": up to sixteen queries at 64 columns run sixteen to a work item on the 16x16x32 matrix instruction
  *                     (default "1") or 32 to a work item like larger query counts
  *   "dma_scores_ahead" "0" | "1": tile loop of the direct-to-LDS kernel that takes the scores of a tile one iteration early (exists
- *                     for four wavefronts at 128 columns and for 256 columns; default: on where both sides gather from pools)
+ *                     for four wavefronts at 128 columns and for 256 columns; default: on at 256 columns, at 128 where both sides gather from pools)
  *   "dma_slow_speed"  weight in (0, 4] of a workgroup that shares its SIMDs with an older one (default 0.75 / 1.0)
  *   "debug"           "1": print the chosen split and list statistics to stderr
  * Errors: CKV_ERR_UNSUPPORTED (unknown key, malformed value).

@@ -657,8 +657,10 @@ void choose_variant(ckv_cache* c) {
                 c->nui = nui;
                 // (the loop with the scores one tile ahead exists for four wavefronts of one query group at 128 columns; measured
                 // on the long ragged configuration: 449 -> 444 us where both sides gather from pools, 518 -> 531 us on an
-                // ordinary cache, whose rows all stream from HBM and want the deeper prefetch of the other loop)
-                c->scores_ahead = g_opt.scores_ahead < 0 ? (s.share == CKV_SHARE_KV && s.d_g > 0) : g_opt.scores_ahead;
+                // ordinary cache, whose rows all stream from HBM and want the deeper prefetch of the other loop; at 256 columns,
+                // one wavefront per SIMD, it is the faster loop throughout: 432 -> 391 us, one side shared 490 -> 445 us, an
+                // ordinary cache 517 -> 491 us)
+                c->scores_ahead = g_opt.scores_ahead < 0 ? (dak == 256 || (s.share == CKV_SHARE_KV && s.d_g > 0)) : g_opt.scores_ahead;
                 c->QB = 32 * nw * qg;
                 // (sixteen queries or fewer at 64 columns: the organisation on the 16x16x32 instruction, which they fill)
                 c->q16 = g_opt.q16 != 0 && nw == 1 && qg == 1 && s.Nq <= 16 && ckv_dma_q16_supported(d_a, s.d_u, s.d_g);
