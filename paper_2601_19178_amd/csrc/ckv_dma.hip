@@ -282,7 +282,8 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
         for (int r = 0; r < 4; ++r) o16[dt][r] = 0.f;
     const float sc = MODE == CKV_SOFTMAX ? a.scale * kLog2e : a.scale;
     const float nsc = -kLog2e * a.scale;    // SiLU: exponent of 2 per unit of raw score
-    const bool unit_scale = a.scale == 1.f;  // SiLU(QK^T) taken literally: one multiply less per weight
+    // SiLU: the weights are taken without the factor sc of their numerator (score / (1 + 2^(nsc score))); the output gets it
+    const float osc = MODE == CKV_SOFTMAX ? 1.f : a.scale;
 
     const int ntiles = (n + TP - 1) / TP;
     if (ntiles > 0) {
@@ -508,19 +509,12 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
 #pragma unroll
                             for (int r = 0; r < 16; ++r) sacc[g][r] = mask_tail(sacc[g][r], 8 * (r >> 2) + 4 * hh + (r & 3) >= nt, 0.f);
                         }
-                        // p = x / (1 + 2^(-x log2 e)) with x = sc * score
-                        if (unit_scale) {
+                        // p = x / (1 + 2^(-x log2 e)) with x = sc * score; the factor sc of the numerator is applied once, to the
+                        // output (epilogue), instead of to every weight
 #pragma unroll
-                            for (int r = 0; r < 16; ++r) {
-                                const float e = __builtin_amdgcn_exp2f(sacc[g][r] * -kLog2e);
-                                pb[r >> 3][r & 7] = (__bf16)(sacc[g][r] * __builtin_amdgcn_rcpf(1.f + e));
-                            }
-                        } else {
-#pragma unroll
-                            for (int r = 0; r < 16; ++r) {
-                                const float e = __builtin_amdgcn_exp2f(sacc[g][r] * nsc);
-                                pb[r >> 3][r & 7] = (__bf16)((sacc[g][r] * sc) * __builtin_amdgcn_rcpf(1.f + e));
-                            }
+                        for (int r = 0; r < 16; ++r) {
+                            const float e = __builtin_amdgcn_exp2f(sacc[g][r] * nsc);
+                            pb[r >> 3][r & 7] = (__bf16)(sacc[g][r] * __builtin_amdgcn_rcpf(1.f + e));
                         }
                     }
                     // O^T += V^T P^T
@@ -639,7 +633,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const float e = __builtin_amdgcn_exp2f(s[r] * nsc);
-                        pb[r >> 3][r & 7] = (__bf16)((s[r] * sc) * __builtin_amdgcn_rcpf(1.f + e));
+                        pb[r >> 3][r & 7] = (__bf16)(s[r] * __builtin_amdgcn_rcpf(1.f + e));
                     }
                 }
                 if (kNext) {
@@ -828,7 +822,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
                         pprev = __builtin_amdgcn_exp2f(fmaf(sr, sc, -m_ref[0]));
                     } else {
                         const float e = __builtin_amdgcn_exp2f(sr * nsc);
-                        pprev = (sr * sc) * __builtin_amdgcn_rcpf(1.f + e);
+                        pprev = sr * __builtin_amdgcn_rcpf(1.f + e);
                     }
                 }
                 if (MODE == CKV_SOFTMAX) psum += pprev;
@@ -982,7 +976,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
 #pragma unroll
                         for (int i = 0; i < 8; ++i) {
                             const float e = __builtin_amdgcn_exp2f(sv[i] * nsc);
-                            pb[i] = (__bf16)((sv[i] * sc) * __builtin_amdgcn_rcpf(1.f + e));
+                            pb[i] = (__bf16)(sv[i] * __builtin_amdgcn_rcpf(1.f + e));
                         }
                     }
 #pragma unroll
@@ -1044,7 +1038,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
         if (it.part < 0) {
             float inv;
             if (MODE == CKV_SOFTMAX) inv = l16 > 0.f ? 1.f / l16 : 0.f;
-            else inv = it.n_total > 0 ? 1.f / (float)it.n_total : 0.f;
+            else inv = it.n_total > 0 ? osc / (float)it.n_total : 0.f;
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
@@ -1071,7 +1065,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
                 for (int r = 0; r < 4; ++r) {
                     const int ci = 16 * dt + 4 * g4 + r;
                     const int pc = ci < dgv ? ci + duv : ci - dgv;
-                    *(lds_f32*)(uintptr_t)(lds0 + q16 * FS + pc * 4) = o16[dt][r];
+                    *(lds_f32*)(uintptr_t)(lds0 + q16 * FS + pc * 4) = o16[dt][r] * osc;
                 }
             if (g4 == 0) {
                 ws[(int64_t)a.QB * DA + q16] = m_ref[0] * kLn2;
@@ -1090,7 +1084,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
         for (int g = 0; g < QG; ++g) {
             float inv;
             if (MODE == CKV_SOFTMAX) inv = l_tot[g] > 0.f ? 1.f / l_tot[g] : 0.f;
-            else inv = it.n_total > 0 ? 1.f / (float)it.n_total : 0.f;
+            else inv = it.n_total > 0 ? osc / (float)it.n_total : 0.f;
 #pragma unroll
             for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
@@ -1130,7 +1124,7 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
                 for (int r = 0; r < 16; ++r) {
                     const int ci = 32 * dt + 8 * (r >> 2) + 4 * hh + (r & 3);
                     const int pc = ci < dgv ? ci + duv : ci - dgv;
-                    *(lds_f32*)(uintptr_t)(flds + (g * 32 + qn) * FS + pc * 4) = oacc[g][dt][r];
+                    *(lds_f32*)(uintptr_t)(flds + (g * 32 + qn) * FS + pc * 4) = oacc[g][dt][r] * osc;
                 }
             if (hh == 0) {
                 ws[(int64_t)a.QB * DA + j] = m_ref[g] * kLn2;
