@@ -128,6 +128,8 @@ __global__ __launch_bounds__(256, (DA == 256 ? 1 : 2)) void ckv_mfma32_kernel(ck
         for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
     float m_ref = -INFINITY, lsum = 0.f;
     const float sc = MODE == CKV_SOFTMAX ? a.scale * kLog2e : a.scale;
+    const float nsc = -kLog2e * a.scale;                     // SiLU: exponent of 2 per unit of raw score
+    const float osc = MODE == CKV_SOFTMAX ? 1.f : a.scale;  // SiLU: the scale of the weights' numerator, applied to the output
 
     // ---- gather bookkeeping: this lane owns chunk c of rows p0 + i*RPP
     const int c = tid % CH, p0 = tid / CH;
@@ -325,14 +327,13 @@ __global__ __launch_bounds__(256, (DA == 256 ? 1 : 2)) void ckv_mfma32_kernel(ck
                     // (sixteen independent chains, one kind of instruction at a time: the transcendental unit's
                     // latency is then covered by the other fifteen instead of being waited for sixteen times)
                     float e[16];
+                    // (the weight without the factor scale of its numerator, which the output gets once: a multiplication less)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) p[r] = sacc[r] * sc;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) e[r] = __builtin_amdgcn_exp2f(-kLog2e * p[r]);
+                    for (int r = 0; r < 16; ++r) e[r] = __builtin_amdgcn_exp2f(nsc * sacc[r]);
 #pragma unroll
                     for (int r = 0; r < 16; ++r) e[r] = __builtin_amdgcn_rcpf(1.f + e[r]);
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) p[r] *= e[r];
+                    for (int r = 0; r < 16; ++r) p[r] = sacc[r] * e[r];
                     if (ragged) {
 #pragma unroll
                         for (int r = 0; r < 16; ++r)
@@ -375,7 +376,7 @@ __global__ __launch_bounds__(256, (DA == 256 ? 1 : 2)) void ckv_mfma32_kernel(ck
     if (it.part < 0) {
         float inv;
         if (MODE == CKV_SOFTMAX) inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-        else inv = it.n_total > 0 ? 1.f / (float)it.n_total : 0.f;
+        else inv = it.n_total > 0 ? osc / (float)it.n_total : 0.f;
         if (qok) {
             float* op = (float*)a.out + qo;
 #pragma unroll
@@ -396,7 +397,7 @@ __global__ __launch_bounds__(256, (DA == 256 ? 1 : 2)) void ckv_mfma32_kernel(ck
             for (int r = 0; r < 16; ++r) {
                 const int ci = 32 * (dt0 + dt) + 8 * (r >> 2) + 4 * hh + (r & 3);
                 const int pc = ci < d_gv ? ci + d_uv : ci - d_gv;
-                if (ci < d_a) ws[(int64_t)j * d_a + pc] = oacc[dt][r];
+                if (ci < d_a) ws[(int64_t)j * d_a + pc] = oacc[dt][r] * osc;
             }
         if (hh == 0 && half == 0) {
             ws[(int64_t)a.QB * d_a + j] = m_ref * kLn2;  // natural-log units, as the merge expects
