@@ -565,18 +565,29 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
                 gather_rows(both_c, t + NS, rk, rv);
                 lds_barrier();  // tile t + 2 is published, the stage of tile t is retired
             };
-            auto read_k = [&](int tile, bf16x8 (&ka)[NKK]) {
-                const uint32_t st = lds0 + (tile & (NS - 1)) * G::STAGE;
+            // (operand addresses: a per-lane part that is fixed for the item, tied to an empty asm statement at every use so
+            // that the stage offset added to it stays an immediate of the LDS read instead of becoming a register per stage)
+            uint32_t kb[NKK], vb[NDT];
 #pragma unroll
-                for (int kk = 0; kk < NKK; ++kk) ka[kk] = *(const lds_bf16x8*)(uintptr_t)(st + krow + (((2 * kk + hh) ^ kx) << 4));
+            for (int kk = 0; kk < NKK; ++kk) kb[kk] = lds0 + krow + (((2 * kk + hh) ^ kx) << 4);
+#pragma unroll
+            for (int dt = 0; dt < NDT; ++dt) vb[dt] = lds0 + vrow + (((4 * dt + vc) ^ vx) << 4);
+            auto read_k = [&](int tile, bf16x8 (&ka)[NKK]) {
+                const uint32_t st = (tile & (NS - 1)) * G::STAGE;
+#pragma unroll
+                for (int kk = 0; kk < NKK; ++kk) {
+                    asm volatile("" : "+v"(kb[kk]));
+                    ka[kk] = *(const lds_bf16x8*)(uintptr_t)(kb[kk] + st);
+                }
             };
             auto read_v = [&](int tile, bf16x8 (&va)[2][NDT]) {
-                const uint32_t st = lds0 + (tile & (NS - 1)) * G::STAGE;
+                const uint32_t st = (tile & (NS - 1)) * G::STAGE;
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
                     for (int dt = 0; dt < NDT; ++dt) {
-                        const uint32_t ad = st + vrow + (16 * ks) * G::ROWB + (((4 * dt + vc) ^ vx) << 4);
+                        asm volatile("" : "+v"(vb[dt]));
+                        const uint32_t ad = vb[dt] + st + (16 * ks) * G::ROWB;
                         const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(uintptr_t)ad);
                         const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(uintptr_t)(ad + 8 * G::ROWB));
                         va[ks][dt] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -664,13 +675,23 @@ __attribute__((amdgpu_waves_per_eu(Geo<DA, NW, (UK >= 2)>::WAVES_PER_EU, Geo<DA,
 #pragma unroll
             for (int kk = 0; kk < NKK; ++kk) s_cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk], qreg[0][kk], s_cur, 0, 0, 0);
             back(-1);
-            for (int t = 0; t < ntiles - 1; ++t) {
+            auto steady = [&](int t) {
                 front(t);
                 read_k(t + 1, ka);
                 read_v(t, va);
                 weights_and_output(std::true_type{}, s_cur, ka, va, TP);
                 back(t);
+            };
+            // four tiles per trip, the first a multiple of four: every stage is then a constant of its instruction
+            const int nsteady = ntiles - 1;
+            for (int j = 0; j < (nsteady >> 2); ++j) {
+                const int t4 = j << 2;
+                steady(t4);
+                steady(t4 + 1);
+                steady(t4 + 2);
+                steady(t4 + 3);
             }
+            for (int t = nsteady & ~3; t < nsteady; ++t) steady(t);
             front(ntiles - 1);
             read_v(ntiles - 1, va);
             weights_and_output(std::false_type{}, s_cur, ka, va, n - (ntiles - 1) * TP);
