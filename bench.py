@@ -83,18 +83,19 @@ def parity(w, out, budget_s):
     while True:
         users = np.sort(order[:n])
         t0 = time.time()
-        ref, rss, sss, acs = oracle.attend(w, users=users, with_scales=True)
+        ref, rss, sss, acs, asum = oracle.attend(w, users=users, with_scales=True, with_asum=True)
         dt = time.time() - t0
         if n >= w["B"] or dt >= 0.4 * budget_s:
             break
         n = int(min(w["B"], max(2 * n, n * 0.8 * budget_s / max(dt, 1e-3))))
-    st = compare(out[users], ref[users], rss[users], w["dtype"], sss[users], acs[users])
+    st = compare(out[users], ref[users], rss[users], w["dtype"], sss[users], acs[users], asum[users])
     return {"users_checked": int(n), "of": int(w["B"]), "elements": st["elements"], "tol": st["tol"],
             "max_rel_err_normwise": st["norm_err"], "worst_element_over_bound": st["worst_ratio"],
             "ok": bool(st["finite"] and st["worst_ratio"] <= 1.0),
-            "rule": "|g-r| <= tol*|r| + tol*rss + (d_a+1)*2^-24*sss + 8*2^-24*acs (rss: root-sum-square of the element's summands, "
-                    "sss: the same of the first-order effects of the scores' rounding, acs: sqrt(n) (|r| + root-sum-square of the "
-                    "summands one by one), for the rounding of the additions; all three from the oracle)"}
+            "rule": "|g-r| <= tol*|r| + max(tol*rss, u_w*asum) + (d_a+1)*2^-24*sss + 8*2^-24*acs (rss: root-sum-square of the element's "
+                    "summands, asum: sum of their magnitudes, u_w: unit roundoff of the storage type, sss: root-sum-square of the "
+                    "first-order effects of the scores' rounding, acs: sqrt(n) (|r| + root-sum-square of the summands one by one), "
+                    "for the rounding of the additions; all four from the oracle)"}
 
 
 def measure(name, steps, warmup, traffic_table, steady=0, parity_budget_s=0.0, with_compulsory=True):

@@ -99,7 +99,10 @@ static void final_row(double *row, const void *user, const void *pool, const int
  * not know: sqrt(n) * (|out[c]| + sqrt(sum_i (w_i V_i[c])^2)), the positions taken one by one (a partial sum of
  * k of the n summands in an order unrelated to their values has mean (k/n) out[c] and a spread of at most the
  * root-sum-square of all summands, and there are n - 1 additions).
- * All three are extra outputs for the comparison rule of the tests; out does not depend on them.
+ * asum (same shape, or NULL) receives sum_i |w_i V_i[c]|: whatever the weights are rounded to, with a relative error of at
+ * most u each, out[c] moves by at most u asum[c]; weights that are nearly equal (positions that share their key row up to a
+ * narrow user slice) are rounded the same way, and then the errors add up like that and not like independent ones.
+ * All four are extra outputs for the comparison rule of the tests; out does not depend on them.
  * Returns 0, or -1 on a bad argument (index outside [0,P), negative length, unknown mode).
  */
 struct weighted { double w; int i; };
@@ -114,7 +117,7 @@ static int attend_impl(int B, int H, int d_g, int d_u, int P, int Nq, int dtype,
                        const int32_t *lengths, const int32_t *idx_k, const int32_t *idx_v,
                        const void *user_k, const void *user_v,
                        const void *pool_k, const void *pool_v, const void *q,
-                       double *out, double *rss, double *sss, double *acs, const int32_t *users, int n_users)
+                       double *out, double *rss, double *sss, double *acs, double *asum, const int32_t *users, int n_users)
 {
     const int d_a = d_u + d_g;
     if (B < 0 || H < 1 || d_g < 0 || d_u < 0 || d_a < 1 || Nq < 1 || pool_ld < d_g)
@@ -237,6 +240,13 @@ static int attend_impl(int B, int H, int d_g, int d_u, int P, int Nq, int dtype,
                         acs[qo + c] = sqrt((double)n) * (fabs(out[qo + c]) + sqrt(a2));
                     }
                 }
+                if (asum) {
+                    for (int c = 0; c < d_a; ++c) {
+                        double a1 = 0.0;
+                        for (int i = 0; i < n; ++i) a1 += fabs(w[i] * V[(int64_t)i * d_a + c]);
+                        asum[qo + c] = a1;
+                    }
+                }
             }
             free(K); free(V); free(w); free(sc); free(sa); free(qv);
         }
@@ -253,7 +263,7 @@ int ckv_oracle_attend(int B, int H, int d_g, int d_u, int P, int Nq, int dtype, 
                       double *out, const int32_t *users, int n_users)
 {
     return attend_impl(B, H, d_g, d_u, P, Nq, dtype, mode, share, scale, pool_ld, lengths, idx_k, idx_v, user_k, user_v,
-                       pool_k, pool_v, q, out, NULL, NULL, NULL, users, n_users);
+                       pool_k, pool_v, q, out, NULL, NULL, NULL, NULL, users, n_users);
 }
 
 /* The same, and the root-sum-square of every element's summands in rss (see above). */
@@ -265,19 +275,20 @@ int ckv_oracle_attend_rss(int B, int H, int d_g, int d_u, int P, int Nq, int dty
                           double *out, double *rss, const int32_t *users, int n_users)
 {
     return attend_impl(B, H, d_g, d_u, P, Nq, dtype, mode, share, scale, pool_ld, lengths, idx_k, idx_v, user_k, user_v,
-                       pool_k, pool_v, q, out, rss, NULL, NULL, users, n_users);
+                       pool_k, pool_v, q, out, rss, NULL, NULL, NULL, users, n_users);
 }
 
-/* The same, and the scale of the scores' rounding errors in sss and of the single-precision additions in acs (see above; acs may be NULL). */
+/* The same, and the scale of the scores' rounding errors in sss, of the single-precision additions in acs and the sum of the
+ * summands' magnitudes in asum (see above; acs and asum may be NULL). */
 int ckv_oracle_attend_scales(int B, int H, int d_g, int d_u, int P, int Nq, int dtype, int mode, int share,
                              double scale, int64_t pool_ld,
                              const int32_t *lengths, const int32_t *idx_k, const int32_t *idx_v,
                              const void *user_k, const void *user_v,
                              const void *pool_k, const void *pool_v, const void *q,
-                             double *out, double *rss, double *sss, double *acs, const int32_t *users, int n_users)
+                             double *out, double *rss, double *sss, double *acs, double *asum, const int32_t *users, int n_users)
 {
     return attend_impl(B, H, d_g, d_u, P, Nq, dtype, mode, share, scale, pool_ld, lengths, idx_k, idx_v, user_k, user_v,
-                       pool_k, pool_v, q, out, rss, sss, acs, users, n_users);
+                       pool_k, pool_v, q, out, rss, sss, acs, asum, users, n_users);
 }
 
 /*

@@ -38,7 +38,7 @@ def _load():
         lib.ckv_oracle_attend_rss.restype = ctypes.c_int
         lib.ckv_oracle_attend_rss.argtypes = [i32] * 9 + [dbl, i64] + [vp] * 10 + [vp, i32]
         lib.ckv_oracle_attend_scales.restype = ctypes.c_int
-        lib.ckv_oracle_attend_scales.argtypes = [i32] * 9 + [dbl, i64] + [vp] * 12 + [vp, i32]
+        lib.ckv_oracle_attend_scales.argtypes = [i32] * 9 + [dbl, i64] + [vp] * 13 + [vp, i32]
         lib.ckv_oracle_reconstruct.restype = ctypes.c_int
         lib.ckv_oracle_reconstruct.argtypes = [i32] * 6 + [i64, i64] + [vp] * 8
         lib.ckv_oracle_cache_size.restype = None
@@ -65,7 +65,7 @@ def _check_store(a, dtype, name):
     return a
 
 
-def attend(w, users=None, with_rss=False, with_scales=False):
+def attend(w, users=None, with_rss=False, with_scales=False, with_asum=False):
     """Attention outputs, fp64 [B][H][Nq][d_a].
 
     `w` is a workload dict as made by the seeded generators: keys B, H, d_g, d_u, P, Nq,
@@ -78,6 +78,7 @@ def attend(w, users=None, with_rss=False, with_scales=False):
     k_i = w_i (V_i[c] - out[c]) A_i for softmax and f'(s_i) V_i[c] A_i / n for SiLU/n (first-order effect of an
     error delta_i A_i of score i on the output), and acs the scale of the roundings of out[c]'s own additions when they are
     done in single precision in an unknown order: sqrt(n) * (|out[c]| + sqrt(sum_i (w_i V_i[c])^2)), n the user's length.
+    with_asum (with with_scales): return (out, rss, sss, acs, asum), asum[c] = sum_i |w_i V_i[c]|.
     """
     lib = _load()
     dt = w["dtype"]
@@ -99,7 +100,9 @@ def attend(w, users=None, with_rss=False, with_scales=False):
         rss = np.full(out.shape, np.nan, dtype=np.float64)
         sss = np.full(out.shape, np.nan, dtype=np.float64)
         acs = np.full(out.shape, np.nan, dtype=np.float64)
-        rc = lib.ckv_oracle_attend_scales(*head, _ptr(out), _ptr(rss), _ptr(sss), _ptr(acs), uptr, nu)
+        asum = np.full(out.shape, np.nan, dtype=np.float64) if with_asum else None
+        rc = lib.ckv_oracle_attend_scales(*head, _ptr(out), _ptr(rss), _ptr(sss), _ptr(acs),
+                                          _ptr(asum) if with_asum else ctypes.c_void_p(0), uptr, nu)
     elif with_rss:
         rss = np.full(out.shape, np.nan, dtype=np.float64)
         rc = lib.ckv_oracle_attend_rss(*head, _ptr(out), _ptr(rss), uptr, nu)
@@ -108,7 +111,7 @@ def attend(w, users=None, with_rss=False, with_scales=False):
     if rc != 0:
         raise ValueError("ckv_oracle_attend rejected its arguments")
     if with_scales:
-        return out, rss, sss, acs
+        return (out, rss, sss, acs, asum) if with_asum else (out, rss, sss, acs)
     return (out, rss) if with_rss else out
 
 

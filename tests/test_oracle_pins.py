@@ -598,3 +598,44 @@ def test_addition_scale_does_not_group_equal_weights():
     w = small()
     _, _, _, acs = oracle.attend(w, users=[1], with_scales=True)
     assert np.isnan(acs[0]).all() and np.isfinite(acs[1]).all()
+
+
+# ---------------------------------------------------------------------------------------------
+# the sum of the magnitudes of an element's summands (the bound on what rounding the weights can do to it)
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+@pytest.mark.parametrize("mode", [wl.SOFTMAX, wl.SILU_OVER_N])
+@pytest.mark.parametrize("share", [wl.SHARE_KV, wl.SHARE_K])
+def test_magnitude_sum_matches_explicit_weights(dtype, mode, share):
+    w = small(dtype=dtype, mode=mode, share=share)
+    out, rss, _, acs, asum = oracle.attend(w, with_scales=True, with_asum=True)
+    q = wl.to_f64(w["q"], dtype)
+    for b, h, K, V in dense_kv_shared(w):
+        n = K.shape[0]
+        if n == 0:
+            assert np.all(asum[b, h] == 0)
+            continue
+        s = torch.from_numpy(w["scale"] * q[b, h]) @ K.T
+        wt = torch.softmax(s, dim=-1) if mode == wl.SOFTMAX else torch.nn.functional.silu(s) / n
+        want = (wt[:, :, None] * V[None, :, :]).abs().sum(dim=1).numpy()
+        np.testing.assert_allclose(asum[b, h], want, rtol=1e-11, atol=1e-14)
+    # it bounds the output and the grouped root-sum-square from above, and a planted mistake (signed sum) would not
+    assert (asum >= np.abs(out) * (1 - 1e-12)).all() and (asum >= rss * (1 - 1e-12)).all()
+    assert (asum > np.abs(out) * 1.01).any()
+
+
+def test_magnitude_sum_special_cases():
+    # one position: the magnitude of the one summand
+    w = small(lengths=(1,), Nq=2)
+    out, _, _, _, asum = oracle.attend(w, with_scales=True, with_asum=True)
+    np.testing.assert_allclose(asum, np.abs(out), rtol=1e-14)
+    # q = 0, softmax: every weight is 1/n: the mean of |V_i|
+    w = small(lengths=(40,), H=1, Nq=1)
+    w["q"] = np.zeros_like(w["q"])
+    _, _, _, _, asum = oracle.attend(w, with_scales=True, with_asum=True)
+    for b, h, K, V in dense_kv(w):
+        np.testing.assert_allclose(asum[b, h, 0], np.abs(V.numpy()).mean(axis=0), rtol=1e-12)
+    # users not listed stay NaN, like out; without with_asum the call returns four arrays as before
+    w = small()
+    r = oracle.attend(w, users=[1], with_scales=True, with_asum=True)
+    assert np.isnan(r[4][0]).all() and np.isfinite(r[4][1]).all()
+    assert len(oracle.attend(w, with_scales=True)) == 4

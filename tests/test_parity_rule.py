@@ -74,3 +74,63 @@ def test_fourth_term_is_small_where_weights_differ():
     ref, rss, sss, acs = oracle.attend(w, with_scales=True)
     base = 1e-4 * np.abs(ref) + 1e-4 * rss
     assert np.max(8 * 2.0 ** -24 * acs / base) < 0.2
+
+
+# ---------------------------------------------------------------------------------------------
+# weights that are nearly equal are rounded to bf16 the same way: the bound u_w * asum of the rule
+def two_clusters(n=400):
+    """One user, one head, one query, eight columns of which the first two are the user's; a pool of two key rows (scores +1
+    and -1 up to 1e-4 from the user's columns, no two alike) and two value rows chosen so that the two clusters of SiLU
+    weights nearly cancel in the pool columns.  All stored values are exact in bf16."""
+    w = wl.make(B=1, L=None, H=1, d_a=8, d_u=2, P=2, idx="uniform", Nq=1, mode=wl.SILU_OVER_N, dtype=wl.BF16,
+                sigma_pool=1.0, seed=3, lengths=np.array([n], np.int32), scale=1.0, pool_ld=8)
+    bits = wl.f32_to_bf16_bits
+    rng = np.random.default_rng(12)
+    w["idx_k"][:, 0] = np.arange(n) % 2
+    w["idx_v"][:, 0] = np.arange(n) % 2
+    pk = np.zeros((1, 2, 8), np.float32); pk[0, 0, 0] = 1.0; pk[0, 1, 0] = -1.0          # pool column 0 carries the score
+    pv = np.zeros((1, 2, 8), np.float32); pv[0, 0, :6] = 1.0; pv[0, 1, :6] = 2.71875      # silu(1) : |silu(-1)| = 2.7183
+    qq = np.zeros((1, 1, 1, 8), np.float32); qq[0, 0, 0, :3] = 1.0                        # [user columns | pool columns]
+    uk = np.stack([rng.integers(-127, 128, size=(n, 1)) * 2.0 ** -20,                     # the keys differ a little
+                   rng.integers(-127, 128, size=(n, 1)) * 2.0 ** -27], axis=2).astype(np.float32)
+    uv = np.zeros((n, 1, 2), np.float32)
+    for k, a in (("pool_k", pk), ("pool_v", pv), ("q", qq), ("user_k", uk), ("user_v", uv)):
+        w[k] = bits(a)
+    return w, pk, pv, qq, uk
+
+
+def test_nearly_equal_weights_round_alike_and_the_rule_knows():
+    w, pk, pv, qq, uk = two_clusters()
+    n = int(w["lengths"][0])
+    ref, rss, sss, acs, asum = oracle.attend(w, with_scales=True, with_asum=True)
+    # the decode stage with the weights rounded to bf16 and everything else exact
+    s = uk[:, 0, :].astype(np.float64).sum(axis=1) + pk[0, np.arange(n) % 2, 0].astype(np.float64)
+    wt = s / (1 + np.exp(-s)) / n
+    assert len(np.unique(wt)) > n // 2                                   # not two clusters of *equal* weights: ...
+    wt16 = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(wt.astype(np.float32))).astype(np.float64)
+    assert len(np.unique(wt16)) <= 4                                     # ... but two or three values after rounding
+    V = np.concatenate([np.zeros((n, 2)), pv[0, np.arange(n) % 2, :6].astype(np.float64)], axis=1)   # [user | pool]
+    exact = (wt[:, None] * V).sum(axis=0)
+    np.testing.assert_allclose(ref[0, 0, 0], exact, rtol=1e-9, atol=1e-15)
+    g = (wt16[:, None] * V).sum(axis=0)[None, None, None]
+    assert np.abs(ref[0, 0, 0, 2]) < 0.02 * asum[0, 0, 0, 2]             # the pool columns nearly cancel
+    without = compare(g, ref, rss, wl.BF16, sss, acs)
+    full = compare(g, ref, rss, wl.BF16, sss, acs, asum)
+    assert without["worst_ratio"] > 1.0        # independent roundings would stay far below tol * rss: these add up
+    assert 0.3 < full["worst_ratio"] < 1.0     # the bound that needs no model holds, and not by a wide margin
+    # planted mistakes still fail: positions left out, the weights of one cluster off by two bf16 steps
+    gone = [17, 19, 21]                                                  # three positions of one cluster
+    drop = (np.delete(wt16, gone)[:, None] * np.delete(V, gone, axis=0)).sum(axis=0)[None, None, None]
+    assert compare(drop, ref, rss, wl.BF16, sss, acs, asum)["worst_ratio"] > 2.0
+    off = ((wt16 * np.where(np.arange(n) % 2 == 0, 1 + 2.0 ** -7, 1.0))[:, None] * V).sum(axis=0)[None, None, None]
+    assert compare(off, ref, rss, wl.BF16, sss, acs, asum)["worst_ratio"] > 1.0
+
+
+def test_magnitude_bound_is_the_smaller_one_for_short_histories():
+    # an ordinary bf16 workload: for a history of a hundred positions tol * rss decides, for thousands u_w * asum does,
+    # and that one stays at 2^-9 of what was added up
+    w = wl.make(B=2, L=None, H=1, d_a=64, d_u=8, P=500, idx="uniform", Nq=4, mode=wl.SOFTMAX, dtype=wl.BF16,
+                sigma_pool=0.125, seed=11, lengths=np.array([4096, 100], np.int32))
+    ref, rss, sss, acs, asum = oracle.attend(w, with_scales=True, with_asum=True)
+    ratio = 2.0 ** -9 * asum / (2e-2 * rss)
+    assert np.median(ratio[1]) < 1.0 < np.median(ratio[0]) < 12.0
